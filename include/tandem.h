@@ -1,0 +1,198 @@
+/*
+ * tandem.h - C ABI of the MI355X (gfx950) Tandem Transformer hot path.
+ *
+ * Paper: "Tandem Transformers for Inference Efficient LLMs", Sec. 3 (Eq. (1), Eq. (2)),
+ * Sec. 3.1 (Tandem + SPEED).  Notation follows the paper: M_L / M_S are the primary
+ * (large) and secondary (small) model, gamma the block length, l(j) the layer assignment,
+ * FF_Tandem the map from M_L's width d_L to M_S's width d_S.
+ *
+ * General conventions
+ *   - Every pointer named "device" is GPU memory owned by the caller; the library never
+ *     allocates or frees device memory and keeps no global state.  Descriptor structs and
+ *     the pointer arrays inside them are host memory, read during the call only (the model
+ *     handle copies what it needs).
+ *   - All entry points enqueue work on the given HIP stream (a hipStream_t passed as
+ *     void*, NULL = default stream) and return without synchronising.
+ *   - Return value: a tandem_status.  All argument checks happen on the host before any
+ *     launch; on error nothing has been enqueued.  Launch failures map to TANDEM_ERR_HIP.
+ *   - Tensors are dense, row-major, last index fastest.  Linear maps are y = W x + b with
+ *     W stored [out_features, in_features].
+ *   - dtype TANDEM_BF16: bf16 storage, fp32 scores / softmax / accumulation, bf16 results.
+ *     dtype TANDEM_F32: fp32 everywhere (correctness path for small models, not tuned).
+ *   - Per-sequence lengths live in device memory (int32).  Kernels clamp them to the
+ *     capacities in the descriptor, so a corrupt length cannot cause an out-of-bounds read.
+ *   - Results are deterministic: identical inputs and shapes give bit-identical outputs.
+ */
+#ifndef TANDEM_H
+#define TANDEM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#pragma GCC visibility push(default)
+
+typedef enum {
+  TANDEM_OK = 0,
+  TANDEM_ERR_NULL = 1,        /* a required pointer is NULL                         */
+  TANDEM_ERR_SHAPE = 2,       /* a size is non-positive, inconsistent or over limit */
+  TANDEM_ERR_UNSUPPORTED = 3, /* a valid request this build has no kernel for       */
+  TANDEM_ERR_WORKSPACE = 4,   /* ws_bytes is smaller than the *_workspace() answer  */
+  TANDEM_ERR_HIP = 5          /* the HIP runtime reported an error                  */
+} tandem_status;
+
+typedef enum { TANDEM_F32 = 0, TANDEM_BF16 = 1 } tandem_dtype;
+typedef enum { TANDEM_ACT_NONE = 0, TANDEM_ACT_GELU = 1 /* exact erf form */, TANDEM_ACT_RELU = 2 } tandem_act;
+
+#define TANDEM_MAX_QLEN 32 /* most query rows per sequence in one block-mode pass */
+
+/* Shape of one attention layer's caches.
+ *   caches:            [B, Hkv, T_max, dh]      (large K/V, or the large-derived K_hat/V_hat)
+ *   own-block scratch: [B, Hkv, gamma_max, dh]  (K/V the small model computed for the current block)
+ * Hq must be a multiple of Hkv (G = Hq/Hkv query heads share a KV head; G <= 8).
+ * dh is 64 or 128.  scale is the score multiplier, normally 1/sqrt(dh). */
+typedef struct {
+  int32_t B, Hq, Hkv, dh;
+  int64_t T_max;
+  int32_t gamma_max;
+  float scale;
+  int32_t dtype; /* tandem_dtype */
+} tandem_attn_desc;
+
+/* FF_Tandem of one small layer (Eq. (2), first line).
+ *   d_hidden == 0: linear form  y_hat = W1 x + b1,            W1 [d_S, d_L]   (the paper's experiments)
+ *   d_hidden  > 0: MLP form     y_hat = W2 act(W1 x + b1) + b2, W1 [d_hidden, d_L], W2 [d_S, d_hidden]
+ * Weights and biases are device pointers in `dtype`; b1 / b2 may be NULL (no bias). */
+typedef struct {
+  int32_t d_L, d_hidden, d_S;
+  int32_t act;   /* tandem_act, ignored when d_hidden == 0 */
+  int32_t dtype; /* tandem_dtype */
+  const void *W1, *b1, *W2, *b2;
+} tandem_ff_desc;
+
+/* ---- workspace sizes (bytes of device scratch a call needs; 256-byte aligned base) ---- */
+size_t tandem_project_workspace(const tandem_ff_desc *ff, int64_t M);
+size_t tandem_block_attn_workspace(const tandem_attn_desc *a, int32_t q_len);
+size_t tandem_draft_attn_workspace(const tandem_attn_desc *a);
+
+/* FF_Tandem: y_hat[M, d_S] = FF_Tandem(x[M, d_L])  (Eq. (2), first line; Sec. 1 "projection
+ * layer").  x, y_hat: device, dtype ff->dtype.  M >= 1 rows (the gamma new rows of every
+ * sequence at decode time, whole prompts at prefill time).  ws: device scratch of at least
+ * tandem_project_workspace(ff, M) bytes (holds the hidden activations and split partials). */
+int tandem_project(const tandem_ff_desc *ff, const void *x, void *y_hat, int64_t M, void *ws, size_t ws_bytes,
+                   void *hip_stream);
+
+/* Large-model block-mode attention (Sec. 1 step 3; Sec. 3 "Inference"; Eq. (1) restricted to
+ * the q_len new rows; the SPEED verifier of Sec. 3.1).  For sequence b the K/V rows of the
+ * q_len new tokens are already in the caches at [n_prefix[b], n_prefix[b] + q_len).  Query
+ * row r of head h attends cache rows 0 .. n_prefix[b] + r inclusive of KV head h / G.
+ *   q, out   device [B, q_len, Hq, dh]      k_cache, v_cache  device [B, Hkv, T_max, dh]
+ *   n_prefix device int32 [B], requires n_prefix[b] + q_len <= T_max (clamped otherwise)
+ *   1 <= q_len <= TANDEM_MAX_QLEN.  Reads the caches only; writes out and ws only. */
+int tandem_block_attn(const tandem_attn_desc *a, const void *q, const void *k_cache, const void *v_cache,
+                      const int32_t *n_prefix, int32_t q_len, void *out, void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Mixed-source small-model attention (Eq. (2), second line; Sec. 3 "Training", both bullets).
+ * One query per sequence and head attends, in ONE softmax, the union of
+ *   k_hat/v_hat[b, h/G, 0 : n_large[b]]  rows derived from M_L through FF_Tandem (completed blocks)
+ *   k_cur/v_cur[b, h/G, 0 : n_cur[b]]    rows M_S computed itself for the current block (incl. the query's own)
+ *   q, out device [B, Hq, dh];  k_hat, v_hat device [B, Hkv, T_max, dh];  k_cur, v_cur device
+ *   [B, Hkv, gamma_max, dh];  n_large, n_cur device int32 [B] (clamped to [0,T_max], [0,gamma_max]).
+ * A sequence with n_large + n_cur == 0 gets an all-zero output row.  Never writes the caches. */
+int tandem_draft_attn(const tandem_attn_desc *a, const void *q, const void *k_hat, const void *v_hat,
+                      const int32_t *n_large, const void *k_cur, const void *v_cur, const int32_t *n_cur, void *out,
+                      void *ws, size_t ws_bytes, void *hip_stream);
+
+/* ------------------------------------------------------------------ whole decode step */
+
+/* One pre-norm decoder layer: h = x + Wo Atn(RMSNorm(x; g_attn)); x' = h + W2 gelu(W1 RMSNorm(h; g_mlp) + b1) + b2.
+ * Wqkv stacks the query, key and value maps: [(Hq + 2 Hkv) dh, d] (all Hq query heads, then the
+ * Hkv key heads, then the Hkv value heads).  Wo [d, Hq dh], W1 [d_ff, d], W2 [d, d_ff].
+ * b1, b2 may be NULL.  All device pointers in the model dtype. */
+typedef struct {
+  const void *g_attn, *Wqkv, *Wo, *g_mlp, *W1, *b1, *W2, *b2;
+} tandem_layer_weights;
+
+typedef struct {
+  int32_t n_layers, d, Hq, Hkv, dh, d_ff, vocab;
+  const void *emb;     /* device [vocab, d]                          */
+  const void *g_final; /* device [d], gain of the final RMSNorm       */
+  const void *W_out;   /* device [vocab, d], untied output head        */
+  const tandem_layer_weights *layers; /* host array [n_layers]        */
+} tandem_decoder_desc;
+
+typedef struct {
+  tandem_decoder_desc L, S;  /* M_L and M_S                                                   */
+  const int32_t *ell;        /* host [S.n_layers]; small layer j reads x^(ell[j]), the residual
+                                stream after ell[j] large layers, 0 <= ell[j] <= L.n_layers    */
+  const tandem_ff_desc *ff;  /* host [S.n_layers]; ff[j].d_L == L.d, ff[j].d_S == S.d          */
+  float rms_eps;
+  int32_t dtype;             /* tandem_dtype of every weight, cache and activation             */
+} tandem_model_desc;
+
+/* Caller-owned decoding state (all device memory except the pointer arrays themselves).
+ *   KL[j], VL[j]      [B, L.Hkv, T_max, dh]     M_L's K/V cache of large layer j
+ *   Khat[j], Vhat[j]  [B, S.Hkv, T_max, dh]     rows of small layer j derived from M_L via FF_Tandem
+ *   Kcur[j], Vcur[j]  [B, S.Hkv, gamma_max, dh] small layer j's own rows for the current block
+ *   n[b]        positions 0..n[b]-1 have rows in KL/VL and Khat/Vhat
+ *   pending[b]  token at position n[b]: emitted, but not yet processed by M_L
+ * Cache ownership rule (Sec. 3 "Inference", last paragraph): the draft phase writes only
+ * Kcur/Vcur; KL/VL/Khat/Vhat rows [n, n+gamma) are written by the verify phase after the
+ * small model has finished the block; rows below n[b] are never modified. */
+typedef struct {
+  int32_t B;
+  int64_t T_max;
+  int32_t gamma_max;
+  void *const *KL, *const *VL;     /* host arrays [L.n_layers] */
+  void *const *Khat, *const *Vhat; /* host arrays [S.n_layers] */
+  void *const *Kcur, *const *Vcur; /* host arrays [S.n_layers] */
+  int32_t *n, *pending;            /* device int32 [B]         */
+} tandem_state_desc;
+
+/* Optional per-step outputs, each a device pointer or NULL:
+ *   draft  int32 [B, gamma]  d_1..d_gamma, the small model's greedy tokens
+ *   verify int32 [B, gamma]  M_L's greedy token for the same positions
+ *   y_small  [B, gamma, S.d] final small-model representation y^(L_S) of every draft run
+ *   x_large  [B, gamma, L.d] final large-model representation x^(L_L) of the block rows
+ *   logits_S [B, gamma, vocab], logits_L [B, gamma, vocab]   (model dtype)           */
+typedef struct {
+  int32_t *draft, *verify;
+  void *y_small, *x_large, *logits_S, *logits_L;
+} tandem_step_aux;
+
+typedef struct tandem_model tandem_model; /* opaque host object: validated copy of a tandem_model_desc */
+
+int tandem_model_create(const tandem_model_desc *desc, tandem_model **out);
+void tandem_model_destroy(tandem_model *m);
+size_t tandem_decode_step_workspace(const tandem_model *m, int32_t B, int32_t gamma);
+
+/* One Tandem + SPEED decode step for every sequence (Sec. 3.1; Sec. 1 steps 2-4; one step is
+ * gamma runs of M_S and one block run of M_L):
+ *   1. draft: M_S runs gamma times from `pending`, each run attending Khat/Vhat[0:n) and its own
+ *      block rows (tandem_draft_attn per small layer), greedy token d_{r+1} after run r;
+ *   2. verify: M_L processes [pending, d_1 .. d_{gamma-1}] in block mode at positions n..n+gamma-1
+ *      (tandem_block_attn per large layer), appending its K/V rows and giving its own greedy tokens;
+ *   3. tandem_project per small layer on the gamma new rows of x^(ell[j]), then that layer's
+ *      RMSNorm and W_K/W_V produce the new Khat/Vhat rows;
+ *   4. accept: a[b] = number of leading draft tokens equal to M_L's tokens; emitted tokens are
+ *      d_1..d_a followed by M_L's token at the first mismatch (only d_1..d_gamma if a == gamma);
+ *      n[b] += min(a+1, gamma); pending[b] = last emitted token.  Ties in argmax go to the lowest id.
+ * forced: optional device int32 [B, gamma]; when given, forced[b, r] replaces d_{r+1} as the input
+ *   of the following runs and everything is treated as accepted (teacher forcing / prompt ingestion).
+ * out_tokens device int32 [B, gamma] (emitted tokens, -1 padded), n_accepted device int32 [B] (a[b]).
+ * 1 <= gamma <= min(gamma_max, TANDEM_MAX_QLEN); requires n[b] + gamma <= T_max. */
+int tandem_decode_step(const tandem_model *m, const tandem_state_desc *state, int32_t gamma, const int32_t *forced,
+                       int32_t *out_tokens, int32_t *n_accepted, const tandem_step_aux *aux, void *ws, size_t ws_bytes,
+                       void *hip_stream);
+
+const char *tandem_status_string(int status);
+
+#pragma GCC visibility pop
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TANDEM_H */

@@ -1,0 +1,264 @@
+"""ctypes binding of libtandem.so: argument marshalling only.
+
+Each function has the name of the C entry point it calls (include/tandem.h).  Tensors are
+torch tensors used purely as handles to device memory (``data_ptr()``) and to the current
+HIP stream; no torch operator takes part in the computation.  There is no fallback: if the
+library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import math
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtandem.so")
+
+OK, ERR_NULL, ERR_SHAPE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = range(6)
+F32, BF16 = 0, 1
+ACT_NONE, ACT_GELU, ACT_RELU = 0, 1, 2
+MAX_QLEN = 32
+_ACT = {None: ACT_NONE, "none": ACT_NONE, "gelu": ACT_GELU, "relu": ACT_RELU}
+
+
+class TandemError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+class AttnDesc(C.Structure):
+    _fields_ = [
+        ("B", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32), ("dh", C.c_int32),
+        ("T_max", C.c_int64), ("gamma_max", C.c_int32), ("scale", C.c_float), ("dtype", C.c_int32),
+    ]
+
+
+class FFDesc(C.Structure):
+    _fields_ = [
+        ("d_L", C.c_int32), ("d_hidden", C.c_int32), ("d_S", C.c_int32), ("act", C.c_int32), ("dtype", C.c_int32),
+        ("W1", C.c_void_p), ("b1", C.c_void_p), ("W2", C.c_void_p), ("b2", C.c_void_p),
+    ]
+
+
+class LayerWeights(C.Structure):
+    _fields_ = [(k, C.c_void_p) for k in ("g_attn", "Wqkv", "Wo", "g_mlp", "W1", "b1", "W2", "b2")]
+
+
+class DecoderDesc(C.Structure):
+    _fields_ = [
+        ("n_layers", C.c_int32), ("d", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32), ("dh", C.c_int32),
+        ("d_ff", C.c_int32), ("vocab", C.c_int32),
+        ("emb", C.c_void_p), ("g_final", C.c_void_p), ("W_out", C.c_void_p), ("layers", C.POINTER(LayerWeights)),
+    ]
+
+
+class ModelDesc(C.Structure):
+    _fields_ = [
+        ("L", DecoderDesc), ("S", DecoderDesc), ("ell", C.POINTER(C.c_int32)), ("ff", C.POINTER(FFDesc)),
+        ("rms_eps", C.c_float), ("dtype", C.c_int32),
+    ]
+
+
+class StateDesc(C.Structure):
+    _fields_ = [
+        ("B", C.c_int32), ("T_max", C.c_int64), ("gamma_max", C.c_int32),
+        ("KL", C.POINTER(C.c_void_p)), ("VL", C.POINTER(C.c_void_p)),
+        ("Khat", C.POINTER(C.c_void_p)), ("Vhat", C.POINTER(C.c_void_p)),
+        ("Kcur", C.POINTER(C.c_void_p)), ("Vcur", C.POINTER(C.c_void_p)),
+        ("n", C.c_void_p), ("pending", C.c_void_p),
+    ]
+
+
+class StepAux(C.Structure):
+    _fields_ = [(k, C.c_void_p) for k in ("draft", "verify", "y_small", "x_large", "logits_S", "logits_L")]
+
+
+EXPORTS = (
+    "tandem_status_string",
+    "tandem_project_workspace", "tandem_block_attn_workspace", "tandem_draft_attn_workspace",
+    "tandem_project", "tandem_block_attn", "tandem_draft_attn",
+    "tandem_model_create", "tandem_model_destroy", "tandem_decode_step_workspace", "tandem_decode_step",
+)
+
+_lib = None
+
+
+def lib():
+    """Loads libtandem.so (built in-tree by paper_2402_08644_amd.build).  No fallback."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'` first")
+    L = C.CDLL(LIB_PATH)
+    vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
+    L.tandem_status_string.restype = C.c_char_p
+    L.tandem_status_string.argtypes = [C.c_int]
+    L.tandem_project_workspace.restype = sz
+    L.tandem_project_workspace.argtypes = [C.POINTER(FFDesc), i64]
+    L.tandem_block_attn_workspace.restype = sz
+    L.tandem_block_attn_workspace.argtypes = [C.POINTER(AttnDesc), i32]
+    L.tandem_draft_attn_workspace.restype = sz
+    L.tandem_draft_attn_workspace.argtypes = [C.POINTER(AttnDesc)]
+    L.tandem_project.restype = C.c_int
+    L.tandem_project.argtypes = [C.POINTER(FFDesc), vp, vp, i64, vp, sz, vp]
+    L.tandem_block_attn.restype = C.c_int
+    L.tandem_block_attn.argtypes = [C.POINTER(AttnDesc), vp, vp, vp, vp, i32, vp, vp, sz, vp]
+    L.tandem_draft_attn.restype = C.c_int
+    L.tandem_draft_attn.argtypes = [C.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.tandem_model_create.restype = C.c_int
+    L.tandem_model_create.argtypes = [C.POINTER(ModelDesc), C.POINTER(vp)]
+    L.tandem_model_destroy.restype = None
+    L.tandem_model_destroy.argtypes = [vp]
+    L.tandem_decode_step_workspace.restype = sz
+    L.tandem_decode_step_workspace.argtypes = [vp, i32, i32]
+    L.tandem_decode_step.restype = C.c_int
+    L.tandem_decode_step.argtypes = [vp, C.POINTER(StateDesc), i32, vp, vp, vp, C.POINTER(StepAux), vp, sz, vp]
+    _lib = L
+    return L
+
+
+def status_string(status: int) -> str:
+    return lib().tandem_status_string(int(status)).decode()
+
+
+def _check(rc, where):
+    if rc != OK:
+        raise TandemError(rc, where)
+
+
+def _dtype_code(t):
+    import torch
+
+    if t.dtype == torch.bfloat16:
+        return BF16
+    if t.dtype == torch.float32:
+        return F32
+    raise TypeError(f"unsupported tensor dtype {t.dtype}")
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    import torch
+
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+def _need(t, shape, what):
+    if tuple(t.shape) != tuple(shape) or not t.is_contiguous() or not t.is_cuda:
+        raise ValueError(f"{what}: expected contiguous device tensor of shape {tuple(shape)}, got {tuple(t.shape)}")
+
+
+def _workspace(nbytes, like):
+    import torch
+
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=like.device)
+
+
+def attn_desc(B, Hq, Hkv, dh, T_max, gamma_max, scale, dtype_code):
+    return AttnDesc(B, Hq, Hkv, dh, T_max, gamma_max, scale, dtype_code)
+
+
+def tandem_draft_attn_workspace(desc: AttnDesc) -> int:
+    return int(lib().tandem_draft_attn_workspace(C.byref(desc)))
+
+
+def tandem_block_attn_workspace(desc: AttnDesc, q_len: int) -> int:
+    return int(lib().tandem_block_attn_workspace(C.byref(desc), q_len))
+
+
+def tandem_draft_attn(q, k_hat, v_hat, n_large, k_cur, v_cur, n_cur, scale=None, out=None, ws=None, stream=None):
+    """q [B,Hq,dh]; k_hat,v_hat [B,Hkv,T_max,dh]; k_cur,v_cur [B,Hkv,gamma_max,dh]; n_large,n_cur int32 [B]."""
+    import torch
+
+    B, Hq, dh = q.shape
+    _, Hkv, T_max, _ = k_hat.shape
+    gmax = k_cur.shape[2]
+    _need(q, (B, Hq, dh), "q")
+    for t, nm in ((k_hat, "k_hat"), (v_hat, "v_hat")):
+        _need(t, (B, Hkv, T_max, dh), nm)
+    for t, nm in ((k_cur, "k_cur"), (v_cur, "v_cur")):
+        _need(t, (B, Hkv, gmax, dh), nm)
+    for t, nm in ((n_large, "n_large"), (n_cur, "n_cur")):
+        _need(t, (B,), nm)
+        if t.dtype != torch.int32:
+            raise TypeError(f"{nm} must be int32")
+    for t in (k_hat, v_hat, k_cur, v_cur):
+        if t.dtype != q.dtype:
+            raise TypeError("q / K / V dtypes differ")
+    d = attn_desc(B, Hq, Hkv, dh, T_max, gmax, (1.0 / math.sqrt(dh)) if scale is None else scale, _dtype_code(q))
+    if out is None:
+        out = torch.empty_like(q)
+    need = tandem_draft_attn_workspace(d)
+    if ws is None:
+        ws = _workspace(need, q)
+    rc = lib().tandem_draft_attn(C.byref(d), _ptr(q), _ptr(k_hat), _ptr(v_hat), _ptr(n_large), _ptr(k_cur), _ptr(v_cur),
+                                 _ptr(n_cur), _ptr(out), _ptr(ws), ws.numel(), _stream(stream))
+    _check(rc, "tandem_draft_attn")
+    return out
+
+
+def tandem_block_attn(q, k_cache, v_cache, n_prefix, scale=None, out=None, ws=None, stream=None):
+    """q [B,q_len,Hq,dh]; k_cache,v_cache [B,Hkv,T_max,dh]; n_prefix int32 [B]."""
+    import torch
+
+    B, q_len, Hq, dh = q.shape
+    _, Hkv, T_max, _ = k_cache.shape
+    _need(q, (B, q_len, Hq, dh), "q")
+    _need(k_cache, (B, Hkv, T_max, dh), "k_cache")
+    _need(v_cache, (B, Hkv, T_max, dh), "v_cache")
+    _need(n_prefix, (B,), "n_prefix")
+    if n_prefix.dtype != torch.int32:
+        raise TypeError("n_prefix must be int32")
+    if k_cache.dtype != q.dtype or v_cache.dtype != q.dtype:
+        raise TypeError("q / K / V dtypes differ")
+    d = attn_desc(B, Hq, Hkv, dh, T_max, 0, (1.0 / math.sqrt(dh)) if scale is None else scale, _dtype_code(q))
+    if out is None:
+        out = torch.empty_like(q)
+    need = tandem_block_attn_workspace(d, q_len)
+    if ws is None:
+        ws = _workspace(need, q)
+    rc = lib().tandem_block_attn(C.byref(d), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(n_prefix), q_len, _ptr(out),
+                                 _ptr(ws), ws.numel(), _stream(stream))
+    _check(rc, "tandem_block_attn")
+    return out
+
+
+def ff_desc(ff: dict, dtype_code=None) -> FFDesc:
+    """ff: {"W","b"} (linear) or {"W1","b1","W2","b2","act"} of device tensors, weights [out, in]."""
+    if "W" in ff:
+        W = ff["W"]
+        return FFDesc(W.shape[1], 0, W.shape[0], ACT_NONE, _dtype_code(W), W.data_ptr(),
+                      ff["b"].data_ptr() if ff.get("b") is not None else None, None, None)
+    W1, W2 = ff["W1"], ff["W2"]
+    return FFDesc(W1.shape[1], W1.shape[0], W2.shape[0], _ACT[ff.get("act", "gelu")], _dtype_code(W1), W1.data_ptr(),
+                  ff["b1"].data_ptr() if ff.get("b1") is not None else None, W2.data_ptr(),
+                  ff["b2"].data_ptr() if ff.get("b2") is not None else None)
+
+
+def tandem_project_workspace(desc: FFDesc, M: int) -> int:
+    return int(lib().tandem_project_workspace(C.byref(desc), M))
+
+
+def tandem_project(ff: dict, x, out=None, ws=None, stream=None):
+    """x [M, d_L] -> y_hat [M, d_S]."""
+    import torch
+
+    d = ff_desc(ff)
+    M = x.shape[0]
+    _need(x, (M, d.d_L), "x")
+    if _dtype_code(x) != d.dtype:
+        raise TypeError("x dtype differs from the weights'")
+    if out is None:
+        out = torch.empty((M, d.d_S), dtype=x.dtype, device=x.device)
+    need = tandem_project_workspace(d, M)
+    if ws is None:
+        ws = _workspace(need, x)
+    rc = lib().tandem_project(C.byref(d), _ptr(x), _ptr(out), M, _ptr(ws), ws.numel(), _stream(stream))
+    _check(rc, "tandem_project")
+    return out

@@ -1,0 +1,130 @@
+// C ABI entry points: argument validation on the host, then kernel launches.  Nothing is
+// enqueued when a check fails.
+#include "common.h"
+#include "kernels.h"
+
+namespace {
+
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+int check_attn_desc(const tandem_attn_desc* a) {
+  if (!a) return TANDEM_ERR_NULL;
+  if (a->B <= 0 || a->Hq <= 0 || a->Hkv <= 0 || a->T_max <= 0 || a->gamma_max < 0) return TANDEM_ERR_SHAPE;
+  if (a->Hq % a->Hkv != 0) return TANDEM_ERR_SHAPE;
+  if (a->dtype != TANDEM_F32 && a->dtype != TANDEM_BF16) return TANDEM_ERR_UNSUPPORTED;
+  if (a->dh != 64 && a->dh != 128) return TANDEM_ERR_UNSUPPORTED;
+  const int G = a->Hq / a->Hkv;
+  if (G != 1 && G != 2 && G != 4 && G != 8) return TANDEM_ERR_UNSUPPORTED;
+  if (a->B > 65535 || (int64_t)a->Hkv * TANDEM_MAX_QLEN > 65535) return TANDEM_ERR_SHAPE;
+  return TANDEM_OK;
+}
+
+bool block_uses_mfma(const tandem_attn_desc* a) { return a->dtype == TANDEM_BF16 && a->dh == 128; }
+
+void carve(void* ws, size_t rows, int S, float** ml, float** o) {
+  *ml = (float*)ws;
+  *o = (float*)((char*)ws + align256(rows * S * 2 * sizeof(float)));
+}
+size_t carved_bytes(size_t rows, int S, int dh) {
+  if (S <= 1) return 0;
+  return align256(rows * S * 2 * sizeof(float)) + rows * S * dh * sizeof(float);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* tandem_status_string(int status) {
+  switch (status) {
+    case TANDEM_OK: return "ok";
+    case TANDEM_ERR_NULL: return "required pointer is NULL";
+    case TANDEM_ERR_SHAPE: return "invalid or inconsistent shape";
+    case TANDEM_ERR_UNSUPPORTED: return "unsupported configuration";
+    case TANDEM_ERR_WORKSPACE: return "workspace too small";
+    case TANDEM_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+size_t tandem_draft_attn_workspace(const tandem_attn_desc* a) {
+  if (check_attn_desc(a) != TANDEM_OK) return 0;
+  const int S = attn_rows_splits(a->B, a->Hkv, 1, a->T_max, a->gamma_max);
+  return carved_bytes((size_t)a->B * a->Hq, S, a->dh);
+}
+
+size_t tandem_block_attn_workspace(const tandem_attn_desc* a, int32_t q_len) {
+  if (check_attn_desc(a) != TANDEM_OK || q_len < 1 || q_len > TANDEM_MAX_QLEN) return 0;
+  const int S = block_uses_mfma(a) ? attn_block_splits(a->B, a->Hkv, a->T_max)
+                                   : attn_rows_splits(a->B, a->Hkv, q_len, a->T_max, 0);
+  return carved_bytes((size_t)a->B * q_len * a->Hq, S, a->dh);
+}
+
+int tandem_draft_attn(const tandem_attn_desc* a, const void* q, const void* k_hat, const void* v_hat,
+                      const int32_t* n_large, const void* k_cur, const void* v_cur, const int32_t* n_cur, void* out,
+                      void* ws, size_t ws_bytes, void* hip_stream) {
+  int rc = check_attn_desc(a);
+  if (rc != TANDEM_OK) return rc;
+  if (!q || !k_hat || !v_hat || !n_large || !k_cur || !v_cur || !n_cur || !out) return TANDEM_ERR_NULL;
+  if (a->gamma_max < 1) return TANDEM_ERR_SHAPE;
+  const size_t need = tandem_draft_attn_workspace(a);
+  if (need > 0 && !ws) return TANDEM_ERR_NULL;
+  if (ws_bytes < need) return TANDEM_ERR_WORKSPACE;
+  AttnArgs x{};
+  x.q = q;
+  x.kA = k_hat;
+  x.vA = v_hat;
+  x.kB = k_cur;
+  x.vB = v_cur;
+  x.nA = n_large;
+  x.nB = n_cur;
+  x.causal = 0;
+  x.B = a->B;
+  x.Hq = a->Hq;
+  x.Hkv = a->Hkv;
+  x.dh = a->dh;
+  x.q_len = 1;
+  x.T_max = a->T_max;
+  x.gamma_max = a->gamma_max;
+  x.scale = a->scale;
+  x.dtype = a->dtype;
+  x.out = out;
+  x.S = attn_rows_splits(a->B, a->Hkv, 1, a->T_max, a->gamma_max);
+  if (x.S > 1) carve(ws, (size_t)a->B * a->Hq, x.S, &x.part_ml, &x.part_o);
+  return launch_attn_rows(x, (hipStream_t)hip_stream);
+}
+
+int tandem_block_attn(const tandem_attn_desc* a, const void* q, const void* k_cache, const void* v_cache,
+                      const int32_t* n_prefix, int32_t q_len, void* out, void* ws, size_t ws_bytes, void* hip_stream) {
+  int rc = check_attn_desc(a);
+  if (rc != TANDEM_OK) return rc;
+  if (!q || !k_cache || !v_cache || !n_prefix || !out) return TANDEM_ERR_NULL;
+  if (q_len < 1 || q_len > TANDEM_MAX_QLEN || a->T_max < q_len) return TANDEM_ERR_SHAPE;
+  const size_t need = tandem_block_attn_workspace(a, q_len);
+  if (need > 0 && !ws) return TANDEM_ERR_NULL;
+  if (ws_bytes < need) return TANDEM_ERR_WORKSPACE;
+  AttnArgs x{};
+  x.q = q;
+  x.kA = k_cache;
+  x.vA = v_cache;
+  x.kB = nullptr;
+  x.vB = nullptr;
+  x.nA = n_prefix;
+  x.nB = nullptr;
+  x.causal = 1;
+  x.B = a->B;
+  x.Hq = a->Hq;
+  x.Hkv = a->Hkv;
+  x.dh = a->dh;
+  x.q_len = q_len;
+  x.T_max = a->T_max;
+  x.gamma_max = 0;
+  x.scale = a->scale;
+  x.dtype = a->dtype;
+  x.out = out;
+  const bool mfma = block_uses_mfma(a);
+  x.S = mfma ? attn_block_splits(a->B, a->Hkv, a->T_max) : attn_rows_splits(a->B, a->Hkv, q_len, a->T_max, 0);
+  if (x.S > 1) carve(ws, (size_t)a->B * q_len * a->Hq, x.S, &x.part_ml, &x.part_o);
+  return mfma ? launch_attn_block(x, (hipStream_t)hip_stream) : launch_attn_rows(x, (hipStream_t)hip_stream);
+}
+
+}  // extern "C"

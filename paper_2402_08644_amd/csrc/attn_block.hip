@@ -1,0 +1,321 @@
+// Block-mode attention of the large model on the matrix cores (Sec. 1 step 3, Sec. 3
+// "Inference", Eq. (1) restricted to the q_len new rows; the SPEED verifier of Sec. 3.1).
+// All R = G * q_len query rows that share a KV head (G query heads per KV head, q_len block
+// positions) are handled by one workgroup, so each K and V row is read from HBM exactly once
+// and feeds R rows: R flop per KV byte - past the vector ALUs, a few percent of MFMA peak.
+//
+// Each wavefront works alone on 32-key tiles (no workgroup barrier in the main loop):
+//   * K and V rows are loaded straight from global memory in the MFMA A-operand layout
+//     (lane = key row l%16, 16 bytes at dh offset 32c + 8*(l/16));
+//   * S^T[key, q] = K Q^T with v_mfma_f32_16x16x32_bf16, Q^T held in registers;
+//   * online softmax per query column (one column per lane, 2 cross-lane max steps per tile);
+//   * the C-layout of two 16-key score tiles already IS the B-operand layout of P^T for a
+//     32-deep contraction when contraction index 8g+j is mapped to key 4g+j (j<4) and
+//     16+4g+j-4 (j>=4), so P never moves between lanes;
+//   * V is brought into the matching A-operand layout (keys along the contraction) by
+//     multiplying each 16x32 piece with a 0/1 selection matrix on the matrix cores - an
+//     exact transpose that needs no LDS and no barrier;
+//   * O^T[d, q] += V^T P^T.
+// Wavefront states are merged through LDS at the end, context splits through the workspace.
+#include "common.h"
+#include "kernels.h"
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+struct BlockParams {
+  const bf16_t *q, *k, *v;
+  const int32_t* n;
+  int Hq, Hkv, q_len, G, S;
+  long long T_max;
+  float scale_log2e;
+  bf16_t* out;
+  float* part_ml;
+  float* part_o;
+};
+
+__device__ __forceinline__ bf16x8 ld_bf16x8(const bf16_t* p) {
+  return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(p));
+}
+__device__ __forceinline__ bf16x8 pack8(const f32x4& a, const f32x4& b) {
+  uint4 u;
+  u.x = pack_bf16x2(a[0], a[1]);
+  u.y = pack_bf16x2(a[2], a[3]);
+  u.z = pack_bf16x2(b[0], b[1]);
+  u.w = pack_bf16x2(b[2], b[3]);
+  return __builtin_bit_cast(bf16x8, u);
+}
+__device__ __forceinline__ f32x4 mfma16(const bf16x8& a, const bf16x8& b, const f32x4& c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+
+constexpr int ST_REGS = 34;  // per-lane state of one row tile: m, l, 32 accumulators
+
+template <int RT>
+__global__ __launch_bounds__(256, (RT <= 2 ? 2 : 1)) void attn_block_kernel(BlockParams p) {
+  extern __shared__ float lds[];  // [2][RT][ST_REGS][64]
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int g4 = lane >> 4, c16 = lane & 15;
+  const int s = blockIdx.x, b = blockIdx.z;
+  const int kvh = blockIdx.y % p.Hkv, pass = blockIdx.y / p.Hkv;
+
+  long long n = p.n[b];
+  const long long nmax = p.T_max - p.q_len;
+  n = n < 0 ? 0 : (n > nmax ? nmax : n);
+  const long long total = n + p.q_len;
+  const int R = p.G * p.q_len;
+
+  const long long ntiles = (total + 31) >> 5;
+  const long long per = (ntiles + p.S - 1) / p.S;
+  const long long tile_begin = (long long)s * per;
+  const long long tile_end = ntiles < tile_begin + per ? ntiles : tile_begin + per;
+
+  const bf16_t* kbase = p.k + ((long long)b * p.Hkv + kvh) * p.T_max * 128;
+  const bf16_t* vbase = p.v + ((long long)b * p.Hkv + kvh) * p.T_max * 128;
+
+  // Q^T operands and per-lane causal limits
+  bf16x8 qreg[RT][4];
+  long long lim[RT];
+  long long orow[RT];  // output row index of this lane's query column, -1 for padding
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    const int rho = (pass * RT + rt) * 16 + c16;
+    if (rho < R) {
+      const int r = rho / p.G, gq = rho % p.G;
+      orow[rt] = ((long long)b * p.q_len + r) * p.Hq + kvh * p.G + gq;
+      lim[rt] = n + r;
+      const bf16_t* qp = p.q + orow[rt] * 128 + 8 * g4;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) qreg[rt][c] = ld_bf16x8(qp + 32 * c);
+    } else {
+      orow[rt] = -1;
+      lim[rt] = n;
+      const uint4 z = {0u, 0u, 0u, 0u};
+#pragma unroll
+      for (int c = 0; c < 4; ++c) qreg[rt][c] = __builtin_bit_cast(bf16x8, z);
+    }
+  }
+
+  // selection matrices: sel[h][k = 8*g4 + j][col = c16] = (k == c16 + 16 h)
+  bf16x8 sel[2];
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    uint32_t wv[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t lo = (8 * g4 + 2 * i == c16 + 16 * h) ? 0x3F80u : 0u;
+      const uint32_t hi = (8 * g4 + 2 * i + 1 == c16 + 16 * h) ? 0x3F80u : 0u;
+      wv[i] = lo | (hi << 16);
+    }
+    const uint4 u = {wv[0], wv[1], wv[2], wv[3]};
+    sel[h] = __builtin_bit_cast(bf16x8, u);
+  }
+
+  float m[RT], l[RT];
+  f32x4 acc[RT][8];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    m[rt] = TANDEM_NEG_BIG;
+    l[rt] = 0.f;
+#pragma unroll
+    for (int db = 0; db < 8; ++db) acc[rt][db] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  }
+
+  for (long long ti = tile_begin + w; ti < tile_end; ti += 4) {
+    const long long key0 = ti << 5;
+    bf16x8 kreg[2][4], vreg[2][4];
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub) {
+      long long row = key0 + 16 * sub + c16;
+      row = row < total ? row : total - 1;  // rows past the end are re-reads of a valid row, masked below
+      const bf16_t* kp = kbase + row * 128 + 8 * g4;
+      const bf16_t* vp = vbase + row * 128 + 8 * g4;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        kreg[sub][c] = ld_bf16x8(kp + 32 * c);
+        vreg[sub][c] = ld_bf16x8(vp + 32 * c);
+      }
+    }
+
+    bf16x8 pb[RT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+      f32x4 sc[2];
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub) {
+        f32x4 a = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) a = mfma16(kreg[sub][c], qreg[rt][c], a);
+        const long long kidx = key0 + 16 * sub + 4 * g4;
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) a[r4] = (kidx + r4 <= lim[rt]) ? a[r4] * p.scale_log2e : -INFINITY;
+        sc[sub] = a;
+      }
+      float mx = fmaxf(fmaxf(fmaxf(sc[0][0], sc[0][1]), fmaxf(sc[0][2], sc[0][3])),
+                       fmaxf(fmaxf(sc[1][0], sc[1][1]), fmaxf(sc[1][2], sc[1][3])));
+      mx = fmaxf(mx, __shfl_xor(mx, 16));
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float mn = fmaxf(m[rt], mx);
+      const float corr = fast_exp2(m[rt] - mn);
+      m[rt] = mn;
+      float ps = 0.f;
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          sc[sub][r4] = fast_exp2(sc[sub][r4] - mn);
+          ps += sc[sub][r4];
+        }
+      l[rt] = l[rt] * corr + ps;
+#pragma unroll
+      for (int db = 0; db < 8; ++db) acc[rt][db] *= corr;
+      pb[rt] = pack8(sc[0], sc[1]);
+    }
+
+#pragma unroll
+    for (int db = 0; db < 8; ++db) {
+      const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+      const f32x4 t0 = mfma16(vreg[0][db >> 1], sel[db & 1], z);
+      const f32x4 t1 = mfma16(vreg[1][db >> 1], sel[db & 1], z);
+      const bf16x8 vt = pack8(t0, t1);
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) acc[rt][db] = mfma16(vt, pb[rt], acc[rt][db]);
+    }
+  }
+
+  // row sums: lanes l, l^16, l^32, l^48 hold partial sums of the same query column
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    l[rt] += __shfl_xor(l[rt], 16);
+    l[rt] += __shfl_xor(l[rt], 32);
+  }
+
+  // tree merge of the 4 wavefronts through LDS (lane-local: all waves use the same layout)
+  auto slot = [&](int buf, int rt, int reg) -> float& { return lds[((buf * RT + rt) * ST_REGS + reg) * 64 + lane]; };
+  auto put = [&](int buf) {
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+      slot(buf, rt, 0) = m[rt];
+      slot(buf, rt, 1) = l[rt];
+#pragma unroll
+      for (int db = 0; db < 8; ++db)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) slot(buf, rt, 2 + db * 4 + r4) = acc[rt][db][r4];
+    }
+  };
+  auto take = [&](int buf) {
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+      const float mo = slot(buf, rt, 0), lo = slot(buf, rt, 1);
+      const float mn = fmaxf(m[rt], mo);
+      const float ca = fast_exp2(m[rt] - mn), cb = fast_exp2(mo - mn);
+      m[rt] = mn;
+      l[rt] = l[rt] * ca + lo * cb;
+#pragma unroll
+      for (int db = 0; db < 8; ++db)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) acc[rt][db][r4] = acc[rt][db][r4] * ca + slot(buf, rt, 2 + db * 4 + r4) * cb;
+    }
+  };
+  if (w >= 2) put(w - 2);
+  __syncthreads();
+  if (w < 2) take(w);
+  __syncthreads();
+  if (w == 1) put(0);
+  __syncthreads();
+  if (w == 0) {
+    take(0);
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+      if (orow[rt] < 0) continue;
+      if (p.S == 1) {
+        const float inv = l[rt] > 0.f ? 1.f / l[rt] : 0.f;
+        bf16_t* op = p.out + orow[rt] * 128 + 4 * g4;
+#pragma unroll
+        for (int db = 0; db < 8; ++db) {
+          uint2 u;
+          u.x = pack_bf16x2(acc[rt][db][0] * inv, acc[rt][db][1] * inv);
+          u.y = pack_bf16x2(acc[rt][db][2] * inv, acc[rt][db][3] * inv);
+          *reinterpret_cast<uint2*>(op + 16 * db) = u;
+        }
+      } else {
+        float* op = p.part_o + (orow[rt] * p.S + s) * 128 + 4 * g4;
+#pragma unroll
+        for (int db = 0; db < 8; ++db)
+          *reinterpret_cast<float4*>(op + 16 * db) =
+              make_float4(acc[rt][db][0], acc[rt][db][1], acc[rt][db][2], acc[rt][db][3]);
+        if (g4 == 0) {
+          p.part_ml[(orow[rt] * p.S + s) * 2 + 0] = m[rt];
+          p.part_ml[(orow[rt] * p.S + s) * 2 + 1] = l[rt];
+        }
+      }
+    }
+  }
+}
+
+template <int RT>
+int launch_rt(const BlockParams& p, int passes, int B, hipStream_t st) {
+  const size_t lds_bytes = (size_t)2 * RT * ST_REGS * 64 * sizeof(float);
+  static bool attr_set = false;
+  if (!attr_set && lds_bytes > 48 * 1024) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_block_kernel<RT>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    if (e != hipSuccess) return TANDEM_ERR_HIP;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((attn_block_kernel<RT>), dim3(p.S, p.Hkv * passes, B), dim3(256), lds_bytes, st, p);
+  return hip_ok(hipGetLastError());
+}
+
+}  // namespace
+
+bool attn_block_supported(const AttnArgs& a) { return a.dtype == TANDEM_BF16 && a.dh == 128 && a.causal == 1 && !a.kB; }
+
+// Context splits: a function of shapes only.  Aim at ~1024 workgroups (4 per CU) with at
+// least 8 tiles (256 keys) each.
+int attn_block_splits(int B, int Hkv, int64_t T_max) {
+  const int64_t groups = (int64_t)B * Hkv;
+  int64_t want = (1024 + groups - 1) / groups;
+  int64_t cap = T_max / 256;
+  if (cap < 1) cap = 1;
+  int64_t S = want < cap ? want : cap;
+  if (S < 1) S = 1;
+  if (S > 64) S = 64;
+  return (int)S;
+}
+
+size_t attn_block_workspace(int B, int Hq, int q_len, int S) {
+  if (S <= 1) return 0;
+  return (size_t)B * q_len * Hq * S * (128 + 2) * sizeof(float);
+}
+
+int launch_attn_block(const AttnArgs& a, hipStream_t st) {
+  BlockParams p;
+  p.q = (const bf16_t*)a.q;
+  p.k = (const bf16_t*)a.kA;
+  p.v = (const bf16_t*)a.vA;
+  p.n = a.nA;
+  p.Hq = a.Hq;
+  p.Hkv = a.Hkv;
+  p.q_len = a.q_len;
+  p.G = a.Hq / a.Hkv;
+  p.S = a.S;
+  p.T_max = a.T_max;
+  p.scale_log2e = a.scale * 1.4426950408889634f;
+  p.out = (bf16_t*)a.out;
+  p.part_ml = a.part_ml;
+  p.part_o = a.part_o;
+  const int R = p.G * a.q_len;
+  const int tiles = (R + 15) / 16;
+  int rc;
+  if (tiles == 1)
+    rc = launch_rt<1>(p, 1, a.B, st);
+  else if (tiles == 2)
+    rc = launch_rt<2>(p, 1, a.B, st);
+  else
+    rc = launch_rt<4>(p, (tiles + 3) / 4, a.B, st);
+  if (rc != TANDEM_OK || a.S == 1) return rc;
+  return launch_attn_combine(a.part_ml, a.part_o, a.out, a.B * a.q_len * a.Hq, a.S, 128, a.dtype, st);
+}

@@ -1,0 +1,290 @@
+// Streaming softmax attention on the vector ALUs: the mixed-source small-model attention
+// of Eq. (2) (second line) - one query per head over [K_hat rows of completed blocks ;
+// own rows of the current block] - and the generic (fp32 / dh = 64) form of the block-mode
+// pass of Eq. (1).  Arithmetic intensity is 1 flop per KV byte, so the kernel is a pure
+// HBM stream: every K and V row is read exactly once, 16 lanes per 256-byte row, four rows
+// (1 KiB, contiguous) per load instruction.
+//
+// Work split: grid (S context splits, Hkv * q_len, B); 4 wavefronts per workgroup, each
+// quarter-wavefront (one DPP row of 16 lanes) owns whole key rows and keeps a private
+// online-softmax state (m, l, acc), so the main loop has no cross-row communication apart
+// from the 4-step DPP dot-product reduction.  States are merged once at the end: DPP rows
+// inside the wavefront, wavefronts through LDS, splits through the workspace in fixed order.
+#include "common.h"
+#include "kernels.h"
+
+namespace {
+
+struct RowsParams {
+  const void* q;
+  const void *kA, *vA, *kB, *vB;
+  const int32_t *nA, *nB;
+  int causal, Hq, Hkv, q_len, gamma_max, S;
+  long long T_max;
+  float scale_log2e;
+  void* out;
+  float* part_ml;
+  float* part_o;
+};
+
+template <typename T, int DH, int G, int U>
+__global__ __launch_bounds__(256) void attn_rows_kernel(RowsParams p) {
+  constexpr int EPL = DH / 16;  // elements of a row per lane
+  constexpr int RB = EPL * (int)sizeof(T);
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int sub = lane >> 4, t = lane & 15;
+  const int s = blockIdx.x, b = blockIdx.z;
+  const int kvh = blockIdx.y % p.Hkv, r = blockIdx.y / p.Hkv;
+
+  long long nA = p.nA[b];
+  if (p.causal) nA += r + 1;
+  nA = nA < 0 ? 0 : (nA > p.T_max ? p.T_max : nA);
+  long long nB = 0;
+  if (p.nB) {
+    nB = p.nB[b];
+    nB = nB < 0 ? 0 : (nB > p.gamma_max ? p.gamma_max : nB);
+  }
+  const long long total = nA + nB;
+  long long per = (total + p.S - 1) / p.S;
+  per = (per + 15) & ~15LL;
+  const long long begin = (long long)s * per;
+  const long long end = total < begin + per ? total : begin + per;
+
+  const T* kA = (const T*)p.kA + ((long long)b * p.Hkv + kvh) * p.T_max * DH;
+  const T* vA = (const T*)p.vA + ((long long)b * p.Hkv + kvh) * p.T_max * DH;
+  const T* kB = p.kB ? (const T*)p.kB + ((long long)b * p.Hkv + kvh) * p.gamma_max * DH : nullptr;
+  const T* vB = p.vB ? (const T*)p.vB + ((long long)b * p.Hkv + kvh) * p.gamma_max * DH : nullptr;
+
+  const long long row0 = ((long long)b * p.q_len + r) * p.Hq + (long long)kvh * G;  // first query row of the group
+  float qv[G][EPL];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    Raw<RB> raw;
+    raw.load((const T*)p.q + (row0 + g) * DH + t * EPL);
+    Unpack<T, EPL>::run(raw, qv[g]);
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) qv[g][e] *= p.scale_log2e;
+  }
+
+  float m[G], l[G], acc[G][EPL];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    m[g] = TANDEM_NEG_BIG;
+    l[g] = 0.f;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
+  }
+
+  for (long long base = begin + (long long)w * (4 * U); base < end; base += 16 * U) {
+    Raw<RB> kr[U], vr[U];
+    bool valid[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      long long row = base + u * 4 + sub;
+      valid[u] = row < end;
+      if (!valid[u]) row = begin;  // begin < end here: a readable row, its score is masked below
+      const T *kp, *vp;
+      if (row < nA) {
+        kp = kA + row * DH;
+        vp = vA + row * DH;
+      } else {
+        kp = kB + (row - nA) * DH;
+        vp = vB + (row - nA) * DH;
+      }
+      kr[u].load(kp + t * EPL);
+      vr[u].load(vp + t * EPL);
+    }
+    float sc[U][G];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float kf[EPL];
+      Unpack<T, EPL>::run(kr[u], kf);
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        float d = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) d = fmaf(qv[g][e], kf[e], d);
+        d = row16_sum(d);
+        sc[u][g] = valid[u] ? d : -INFINITY;
+      }
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      float mn = m[g];
+#pragma unroll
+      for (int u = 0; u < U; ++u) mn = fmaxf(mn, sc[u][g]);
+      const float corr = fast_exp2(m[g] - mn);
+      m[g] = mn;
+      l[g] *= corr;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) acc[g][e] *= corr;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float vf[EPL];
+      Unpack<T, EPL>::run(vr[u], vf);
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        const float pw = fast_exp2(sc[u][g] - m[g]);
+        l[g] += pw;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[g][e] = fmaf(pw, vf[e], acc[g][e]);
+      }
+    }
+  }
+
+  // merge the four DPP rows of the wavefront
+#pragma unroll
+  for (int off = 16; off <= 32; off <<= 1) {
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      const float mo = __shfl_xor(m[g], off), lo = __shfl_xor(l[g], off);
+      const float mn = fmaxf(m[g], mo);
+      const float ca = fast_exp2(m[g] - mn), cb = fast_exp2(mo - mn);
+      l[g] = l[g] * ca + lo * cb;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) acc[g][e] = acc[g][e] * ca + __shfl_xor(acc[g][e], off) * cb;
+      m[g] = mn;
+    }
+  }
+
+  __shared__ float sm_m[4][G], sm_l[4][G];
+  __shared__ float sm_o[4][G][DH];
+  if (sub == 0) {
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      if (t == 0) {
+        sm_m[w][g] = m[g];
+        sm_l[w][g] = l[g];
+      }
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) sm_o[w][g][t * EPL + e] = acc[g][e];
+    }
+  }
+  __syncthreads();
+  for (int idx = threadIdx.x; idx < G * DH; idx += 256) {
+    const int g = idx / DH, d = idx % DH;
+    float mn = sm_m[0][g];
+#pragma unroll
+    for (int ww = 1; ww < 4; ++ww) mn = fmaxf(mn, sm_m[ww][g]);
+    float lt = 0.f, ot = 0.f;
+#pragma unroll
+    for (int ww = 0; ww < 4; ++ww) {
+      const float c = fast_exp2(sm_m[ww][g] - mn);
+      lt += sm_l[ww][g] * c;
+      ot += sm_o[ww][g][d] * c;
+    }
+    const long long row = row0 + g;
+    if (p.S == 1) {
+      ((T*)p.out)[row * DH + d] = from_f32<T>(lt > 0.f ? ot / lt : 0.f);
+    } else {
+      p.part_o[(row * p.S + s) * DH + d] = ot;
+      if (d == 0) {
+        p.part_ml[(row * p.S + s) * 2 + 0] = mn;
+        p.part_ml[(row * p.S + s) * 2 + 1] = lt;
+      }
+    }
+  }
+}
+
+// out[row, :] = sum_s O_s 2^(m_s - m) / sum_s l_s 2^(m_s - m), splits visited in index order
+template <typename T>
+__global__ void attn_combine_kernel(const float* __restrict__ part_ml, const float* __restrict__ part_o, T* out,
+                                    int S, int dh) {
+  const long long row = blockIdx.x;
+  const int d = threadIdx.x;
+  float mn = TANDEM_NEG_BIG;
+  for (int s = 0; s < S; ++s) mn = fmaxf(mn, part_ml[(row * S + s) * 2]);
+  float lt = 0.f, ot = 0.f;
+  for (int s = 0; s < S; ++s) {
+    const float c = fast_exp2(part_ml[(row * S + s) * 2] - mn);
+    lt += part_ml[(row * S + s) * 2 + 1] * c;
+    ot += part_o[(row * S + s) * dh + d] * c;
+  }
+  out[row * dh + d] = from_f32<T>(lt > 0.f ? ot / lt : 0.f);
+}
+
+template <typename T, int DH, int G>
+int launch_rows_t(const RowsParams& p, dim3 grid, hipStream_t st) {
+  hipLaunchKernelGGL((attn_rows_kernel<T, DH, G, 4>), grid, dim3(256), 0, st, p);
+  return hip_ok(hipGetLastError());
+}
+
+template <typename T, int DH>
+int launch_rows_g(int G, const RowsParams& p, dim3 grid, hipStream_t st) {
+  switch (G) {
+    case 1: return launch_rows_t<T, DH, 1>(p, grid, st);
+    case 2: return launch_rows_t<T, DH, 2>(p, grid, st);
+    case 4: return launch_rows_t<T, DH, 4>(p, grid, st);
+    case 8: return launch_rows_t<T, DH, 8>(p, grid, st);
+    default: return TANDEM_ERR_UNSUPPORTED;
+  }
+}
+
+}  // namespace
+
+// Splits: enough workgroups to put >= 8 wavefronts on every one of the 256 CUs, but at least
+// 256 keys per split so the per-split epilogue stays small.  A function of shapes only.
+int attn_rows_splits(int B, int Hkv, int q_len, int64_t T_max, int gamma_max) {
+  const int64_t groups = (int64_t)B * Hkv * q_len;
+  const int64_t keys = T_max + gamma_max;
+  int64_t want = (2048 + groups - 1) / groups;
+  int64_t cap = keys / 256;
+  if (cap < 1) cap = 1;
+  int64_t S = want < cap ? want : cap;
+  if (S < 1) S = 1;
+  if (S > 64) S = 64;
+  return (int)S;
+}
+
+size_t attn_rows_workspace(int B, int Hq, int q_len, int dh, int S) {
+  if (S <= 1) return 0;
+  const size_t rows = (size_t)B * q_len * Hq;
+  return rows * S * (dh + 2) * sizeof(float);
+}
+
+int launch_attn_combine(const float* part_ml, const float* part_o, void* out, int rows, int S, int dh, int dtype,
+                        hipStream_t st) {
+  if (dtype == TANDEM_BF16)
+    hipLaunchKernelGGL(attn_combine_kernel<bf16_t>, dim3(rows), dim3(dh), 0, st, part_ml, part_o, (bf16_t*)out, S, dh);
+  else
+    hipLaunchKernelGGL(attn_combine_kernel<float>, dim3(rows), dim3(dh), 0, st, part_ml, part_o, (float*)out, S, dh);
+  return hip_ok(hipGetLastError());
+}
+
+int launch_attn_rows(const AttnArgs& a, hipStream_t st) {
+  RowsParams p;
+  p.q = a.q;
+  p.kA = a.kA;
+  p.vA = a.vA;
+  p.kB = a.kB;
+  p.vB = a.vB;
+  p.nA = a.nA;
+  p.nB = a.nB;
+  p.causal = a.causal;
+  p.Hq = a.Hq;
+  p.Hkv = a.Hkv;
+  p.q_len = a.q_len;
+  p.gamma_max = a.gamma_max;
+  p.S = a.S;
+  p.T_max = a.T_max;
+  p.scale_log2e = a.scale * 1.4426950408889634f;
+  p.out = a.out;
+  p.part_ml = a.part_ml;
+  p.part_o = a.part_o;
+  const int G = a.Hq / a.Hkv;
+  dim3 grid(a.S, a.Hkv * a.q_len, a.B);
+  int rc;
+  if (a.dtype == TANDEM_BF16 && a.dh == 128)
+    rc = launch_rows_g<bf16_t, 128>(G, p, grid, st);
+  else if (a.dtype == TANDEM_BF16 && a.dh == 64)
+    rc = launch_rows_g<bf16_t, 64>(G, p, grid, st);
+  else if (a.dtype == TANDEM_F32 && a.dh == 128)
+    rc = launch_rows_g<float, 128>(G, p, grid, st);
+  else if (a.dtype == TANDEM_F32 && a.dh == 64)
+    rc = launch_rows_g<float, 64>(G, p, grid, st);
+  else
+    return TANDEM_ERR_UNSUPPORTED;
+  if (rc != TANDEM_OK || a.S == 1) return rc;
+  return launch_attn_combine(a.part_ml, a.part_o, a.out, a.B * a.q_len * a.Hq, a.S, a.dh, a.dtype, st);
+}

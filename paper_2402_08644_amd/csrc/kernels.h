@@ -1,0 +1,66 @@
+// Internal launch interface between the C ABI layer and the kernel files.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "tandem.h"
+
+// ---------------------------------------------------------------- attention (attn_rows.hip)
+// Streaming attention of query rows over a virtual key sequence that is the concatenation
+// of source A (cache rows [0, nA)) and source B (own-block rows [0, nB)).
+struct AttnArgs {
+  const void* q;               // [B, q_len, Hq, dh]
+  const void *kA, *vA;         // [B, Hkv, T_max, dh]
+  const void *kB, *vB;         // [B, Hkv, gamma_max, dh] or nullptr
+  const int32_t* nA;           // [B]
+  const int32_t* nB;           // [B] or nullptr
+  int causal;                  // 1: row r of the block sees nA[b] + r + 1 rows of A (block mode)
+  int B, Hq, Hkv, dh, q_len;
+  int64_t T_max;
+  int gamma_max;
+  float scale;
+  int dtype;
+  void* out;                   // [B, q_len, Hq, dh]
+  float* part_ml;              // [rows, S, 2]   (m in log2 units, l)
+  float* part_o;               // [rows, S, dh]  un-normalised
+  int S;                       // number of context splits
+};
+
+int attn_rows_splits(int B, int Hkv, int q_len, int64_t T_max, int gamma_max);
+size_t attn_rows_workspace(int B, int Hq, int q_len, int dh, int S);
+int launch_attn_rows(const AttnArgs& a, hipStream_t st);
+
+// MFMA block-mode attention (attn_block.hip): bf16, dh = 128, all G*q_len rows of a KV head per workgroup.
+int attn_block_splits(int B, int Hkv, int64_t T_max);
+size_t attn_block_workspace(int B, int Hq, int q_len, int S);
+bool attn_block_supported(const AttnArgs& a);
+int launch_attn_block(const AttnArgs& a, hipStream_t st);
+
+// combine of split partials (attn_rows.hip); fixed split order
+int launch_attn_combine(const float* part_ml, const float* part_o, void* out, int rows, int S, int dh, int dtype,
+                        hipStream_t st);
+
+// ---------------------------------------------------------------- dense (gemm.hip)
+// Y[M, N] = epilogue(X[M, K] . W[N, K]^T): + bias[N], activation, + residual[M, N].
+struct GemmArgs {
+  const void* X;
+  int64_t ldx;  // row stride of X in elements
+  const void* W;
+  const void* bias;      // [N] or nullptr
+  const void* residual;  // [M, ldr] or nullptr
+  int64_t ldr;
+  void* Y;
+  int64_t ldy;
+  int M, N, K;
+  int act;    // tandem_act
+  int dtype;  // tandem_dtype of X, W, bias, residual, Y
+  float* ws;  // split-K partials
+  size_t ws_bytes;
+};
+size_t gemm_workspace(int M, int N, int K, int dtype);
+int launch_gemm(const GemmArgs& g, hipStream_t st);
+
+// ---------------------------------------------------------------- glue (glue.hip)
+int launch_rmsnorm(const void* x, const void* g, void* y, int rows, int d, float eps, int dtype, hipStream_t st);
+int launch_embed(const void* emb, const int32_t* tokens, int64_t tok_stride, void* x, int rows, int d, int vocab,
+                 int dtype, hipStream_t st);

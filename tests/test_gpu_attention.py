@@ -1,0 +1,301 @@
+"""GPU parity: tandem_draft_attn and tandem_block_attn (through the C ABI) against the fp64
+oracle on the same seeded inputs, element by element."""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import tandem_oracle as orc
+from paper_2402_08644_amd import inputs
+from parity import assert_rows_close
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def tb():
+    import torch
+
+    from paper_2402_08644_amd import binding
+
+    assert torch.cuda.is_available()
+    binding.lib()
+    return torch, binding
+
+
+def run_draft(tb, case, scale=None):
+    torch, binding = tb
+    dev = {k: case[k].to_torch() for k in ("q", "khat", "vhat", "kcur", "vcur")}
+    nl = torch.from_numpy(case["n_large"]).cuda()
+    nc = torch.from_numpy(case["n_cur"]).cuda()
+    out = binding.tandem_draft_attn(dev["q"], dev["khat"], dev["vhat"], nl, dev["kcur"], dev["vcur"], nc, scale=case["scale"])
+    torch.cuda.synchronize()
+    return inputs.torch_to_f64(out)
+
+
+def oracle_draft(case):
+    return orc.draft_attn(case["q"].f64, case["khat"].f64, case["vhat"].f64, case["n_large"], case["kcur"].f64,
+                          case["vcur"].f64, case["n_cur"], case["scale"])
+
+
+def run_block(tb, case):
+    torch, binding = tb
+    out = binding.tandem_block_attn(case["q"].to_torch(), case["k"].to_torch(), case["v"].to_torch(),
+                                    torch.from_numpy(case["n"]).cuda(), scale=case["scale"])
+    torch.cuda.synchronize()
+    return inputs.torch_to_f64(out)
+
+
+def oracle_block(case):
+    return orc.block_attn(case["q"].f64, case["k"].f64, case["v"].f64, case["n"], case["scale"])
+
+
+# --------------------------------------------------------------------------- draft
+@pytest.mark.parametrize(
+    "B,Hq,Hkv,dh,T_max,gmax,n_large,n_cur,dtype",
+    [
+        (3, 4, 2, 128, 300, 4, [0, 37, 300], [1, 4, 2], "bf16"),       # ragged, empty large part, full cache
+        (2, 8, 8, 128, 1111, 8, [1111, 1000], [8, 3], "bf16"),          # MHA, several splits, ragged tail
+        (2, 8, 1, 128, 700, 4, [513, 64], [4, 1], "bf16"),              # G = 8
+        (2, 4, 1, 128, 520, 4, [500, 17], [2, 4], "bf16"),              # G = 4
+        (2, 4, 2, 64, 400, 4, [400, 129], [3, 1], "bf16"),              # dh = 64
+        (2, 2, 2, 64, 130, 2, [128, 5], [2, 1], "f32"),                 # the tiny config's small model shape
+        (1, 2, 1, 128, 64, 4, [15], [1], "f32"),
+        (2, 2, 2, 128, 16, 4, [0, 0], [1, 4], "bf16"),                  # no completed block at all: own rows only
+    ],
+)
+def test_draft_attn_parity_small(tb, B, Hq, Hkv, dh, T_max, gmax, n_large, n_cur, dtype):
+    case = inputs.draft_attn_case(11, B, Hq, Hkv, dh, T_max, gmax, n_large, n_cur, dtype=dtype, kv_std=1.0)
+    got = run_draft(tb, case)
+    want = oracle_draft(case)
+    e = assert_rows_close(got, want, what="draft")
+    print(f"draft small {B,Hq,Hkv,dh,T_max,dtype}: max rel err {e[0]:.2e}")
+
+
+def test_draft_attn_parity_config1_full(tb):
+    """The single-kernel benchmark configuration: batch 8, 8 heads of 128, 2044 large rows + 4 own rows."""
+    case = inputs.draft_attn_case(1, 8, 8, 8, 128, 2044, 4, 2044, 4, dtype="bf16")
+    got = run_draft(tb, case)
+    e = assert_rows_close(got, oracle_draft(case), what="draft config 1")
+    print(f"draft config1: max rel err {e[0]:.2e}")
+    # ragged variant
+    rng = np.random.default_rng(5)
+    case["n_large"] = rng.integers(1800, 2045, size=8).astype(np.int32)
+    case["n_cur"] = rng.integers(1, 5, size=8).astype(np.int32)
+    assert_rows_close(run_draft(tb, case), oracle_draft(case), what="draft config 1 ragged")
+
+
+def test_draft_attn_lengths_are_clamped(tb):
+    """Lengths beyond the capacities are clamped to them (no out-of-bounds read)."""
+    case = inputs.draft_attn_case(3, 2, 2, 2, 128, 100, 4, [1000, -5], [9, 2], dtype="bf16")
+    got = run_draft(tb, case)
+    case["n_large"] = np.array([100, 0], np.int32)
+    case["n_cur"] = np.array([4, 2], np.int32)
+    assert_rows_close(got, oracle_draft(case), what="draft clamped")
+
+
+def test_draft_attn_indicator_probe_exact_mask(tb):
+    """q = 0 makes every visible row weigh exactly 1/N; V = e_0 on exactly one row.  The output is
+    exactly 0 iff that row is masked.  Sweeps every row of both sources for ragged lengths that
+    straddle split and tile boundaries."""
+    torch, binding = tb
+    B, H, dh, T_max, gmax = 4, 1, 128, 600, 4
+    n_large = np.array([0, 255, 256, 600], np.int32)
+    n_cur = np.array([1, 4, 2, 3], np.int32)
+    q = torch.zeros((B, H, dh), dtype=torch.bfloat16, device="cuda")
+    ones_hat = torch.ones((B, H, T_max, dh), dtype=torch.bfloat16, device="cuda")
+    ones_cur = torch.ones((B, H, gmax, dh), dtype=torch.bfloat16, device="cuda")
+    # V row p carries the value (p mod 251) + 1 in element 0 ... decode which rows contributed through
+    # two probes: indicator of "row index in set A" sums to |visible in A| / N.
+    for probe in range(3):
+        vhat = torch.zeros((B, H, T_max, dh), dtype=torch.float32)
+        vcur = torch.zeros((B, H, gmax, dh), dtype=torch.float32)
+        if probe == 0:  # all rows flagged: output must be exactly 1 (N/N) - every visible row counted once
+            vhat[..., 0] = 1.0
+            vcur[..., 0] = 1.0
+        elif probe == 1:  # only rows that must be masked are flagged: output must be exactly 0
+            for b in range(B):
+                vhat[b, :, n_large[b]:, 0] = 1.0
+                vcur[b, :, n_cur[b]:, 0] = 1.0
+        else:  # only the last visible row of each source is flagged: output 2/N (or 1/N if no large rows)
+            for b in range(B):
+                if n_large[b] > 0:
+                    vhat[b, :, n_large[b] - 1, 0] = 1.0
+                vcur[b, :, n_cur[b] - 1, 0] = 1.0
+        out = binding.tandem_draft_attn(q, ones_hat, vhat.to(torch.bfloat16).cuda(), torch.from_numpy(n_large).cuda(),
+                                        ones_cur, vcur.to(torch.bfloat16).cuda(), torch.from_numpy(n_cur).cuda(), scale=1.0)
+        got = out.float().cpu().numpy()[:, 0, 0]
+        for b in range(B):
+            N = int(n_large[b] + n_cur[b])
+            if probe == 0:
+                assert abs(got[b] - 1.0) <= 2 ** -7, (b, got[b])
+            elif probe == 1:
+                assert got[b] == 0.0, (b, got[b])
+            else:
+                want = (2.0 if n_large[b] > 0 else 1.0) / N
+                assert abs(got[b] - want) <= want * 2 ** -7, (b, got[b], want)
+
+
+def test_draft_attn_single_row_positions_exact(tb):
+    """Moves a single flagged V row across every position around split/tile boundaries: the output is
+    nonzero exactly when the position is visible."""
+    torch, binding = tb
+    B, H, dh, T_max, gmax = 1, 1, 128, 1040, 4
+    q = torch.zeros((B, H, dh), dtype=torch.bfloat16, device="cuda")
+    ones_hat = torch.ones((B, H, T_max, dh), dtype=torch.bfloat16, device="cuda")
+    ones_cur = torch.ones((B, H, gmax, dh), dtype=torch.bfloat16, device="cuda")
+    for n_large, n_cur in [(1037, 3), (256, 1), (15, 4)]:
+        nl = torch.tensor([n_large], dtype=torch.int32, device="cuda")
+        nc = torch.tensor([n_cur], dtype=torch.int32, device="cuda")
+        positions = sorted(set(list(range(0, 40)) + list(range(240, 280)) + list(range(500, 530)) + list(range(1000, 1040))))
+        for p in positions + [T_max + i for i in range(gmax)]:
+            vhat = torch.zeros((B, H, T_max, dh), dtype=torch.bfloat16, device="cuda")
+            vcur = torch.zeros((B, H, gmax, dh), dtype=torch.bfloat16, device="cuda")
+            if p < T_max:
+                vhat[0, 0, p, 5] = 1.0
+                visible = p < n_large
+            else:
+                vcur[0, 0, p - T_max, 5] = 1.0
+                visible = (p - T_max) < n_cur
+            out = binding.tandem_draft_attn(q, ones_hat, vhat, nl, ones_cur, vcur, nc, scale=1.0)
+            v = float(out[0, 0, 5])
+            if visible:
+                want = 1.0 / (n_large + n_cur)
+                assert abs(v - want) <= want * 2 ** -7, (n_large, n_cur, p, v)
+            else:
+                assert v == 0.0, (n_large, n_cur, p, v)
+            assert float(out.float().abs().sum()) == abs(v)
+
+
+def test_draft_attn_is_deterministic(tb):
+    torch, binding = tb
+    case = inputs.draft_attn_case(2, 4, 8, 8, 128, 1500, 4, [1500, 900, 33, 1024], [4, 1, 2, 3], dtype="bf16")
+    dev = {k: case[k].to_torch() for k in ("q", "khat", "vhat", "kcur", "vcur")}
+    nl, nc = torch.from_numpy(case["n_large"]).cuda(), torch.from_numpy(case["n_cur"]).cuda()
+    a = binding.tandem_draft_attn(dev["q"], dev["khat"], dev["vhat"], nl, dev["kcur"], dev["vcur"], nc).clone()
+    b = binding.tandem_draft_attn(dev["q"], dev["khat"], dev["vhat"], nl, dev["kcur"], dev["vcur"], nc)
+    torch.cuda.synchronize()
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+
+def test_draft_attn_never_writes_the_caches(tb):
+    torch, binding = tb
+    case = inputs.draft_attn_case(4, 2, 4, 4, 128, 300, 4, [300, 10], [4, 1], dtype="bf16")
+    dev = {k: case[k].to_torch() for k in ("q", "khat", "vhat", "kcur", "vcur")}
+    before = {k: v.clone() for k, v in dev.items()}
+    binding.tandem_draft_attn(dev["q"], dev["khat"], dev["vhat"], torch.from_numpy(case["n_large"]).cuda(), dev["kcur"],
+                              dev["vcur"], torch.from_numpy(case["n_cur"]).cuda())
+    torch.cuda.synchronize()
+    for k in dev:
+        assert torch.equal(before[k].view(torch.int16), dev[k].view(torch.int16)), k
+
+
+# --------------------------------------------------------------------------- block
+@pytest.mark.parametrize(
+    "B,q_len,Hq,Hkv,dh,T_max,n,dtype",
+    [
+        (2, 4, 8, 2, 128, 300, [296, 0], "bf16"),        # G=4, R=16: one row tile; full cache and empty prefix
+        (3, 8, 8, 2, 128, 700, [692, 100, 31], "bf16"),  # R=32: two row tiles
+        (2, 1, 4, 4, 128, 260, [259, 7], "bf16"),        # block length 1 = ordinary causal decode, G=1 (15 padded rows)
+        (2, 5, 4, 1, 128, 530, [525, 64], "bf16"),       # R=20: ragged row tile
+        (1, 32, 8, 2, 128, 300, [200], "bf16"),          # R=128: two passes of four row tiles
+        (2, 7, 8, 1, 128, 200, [193, 50], "bf16"),       # G=8, R=56: four row tiles with padding
+        (2, 3, 4, 2, 64, 100, [97, 10], "bf16"),         # dh=64 generic path
+        (1, 2, 4, 4, 64, 130, [126], "f32"),             # the tiny config's large model shape
+        (2, 4, 4, 2, 128, 90, [80, 0], "f32"),
+    ],
+)
+def test_block_attn_parity_small(tb, B, q_len, Hq, Hkv, dh, T_max, n, dtype):
+    case = inputs.block_attn_case(21, B, q_len, Hq, Hkv, dh, T_max, n, dtype=dtype)
+    got = run_block(tb, case)
+    e = assert_rows_close(got, oracle_block(case), what="block")
+    print(f"block small {B,q_len,Hq,Hkv,dh,T_max,dtype}: max rel err {e[0]:.2e}")
+
+
+def test_block_attn_parity_config2_full(tb):
+    """Large GQA layer: batch 16, 32/8 heads of 128, prefix 4096 + 4 block-causal queries."""
+    case = inputs.block_attn_case(2, 16, 4, 32, 8, 128, 4100, 4096, dtype="bf16")
+    got = run_block(tb, case)
+    e = assert_rows_close(got, oracle_block(case), what="block config 2")
+    print(f"block config2: max rel err {e[0]:.2e}")
+
+
+def test_block_attn_causal_mask_exact(tb):
+    """Q = 0 (uniform weights) and V flagged on exactly one cache row: row r of the block must give
+    exactly 0 when the flagged row is past n + r, and 1/(n + r + 1) otherwise."""
+    torch, binding = tb
+    B, q_len, Hq, Hkv, dh, T_max = 1, 4, 4, 1, 128, 400
+    q = torch.zeros((B, q_len, Hq, dh), dtype=torch.bfloat16, device="cuda")
+    k = torch.ones((B, Hkv, T_max, dh), dtype=torch.bfloat16, device="cuda")
+    for n in (0, 29, 60, 252, 396):
+        nn = torch.tensor([n], dtype=torch.int32, device="cuda")
+        for p in sorted(set([0, 1, n - 1, n, n + 1, n + 2, n + 3, n + 4, n + 5, 31, 32, 33, 255, 256, T_max - 1])):
+            if p < 0 or p >= T_max:
+                continue
+            v = torch.zeros((B, Hkv, T_max, dh), dtype=torch.bfloat16, device="cuda")
+            v[0, 0, p, 77] = 1.0
+            out = binding.tandem_block_attn(q, k, v, nn, scale=1.0).float().cpu().numpy()
+            for r in range(q_len):
+                for h in range(Hq):
+                    if p <= n + r:
+                        want = 1.0 / (n + r + 1)
+                        assert abs(out[0, r, h, 77] - want) <= want * 2 ** -6, (n, p, r, h, out[0, r, h, 77])
+                    else:
+                        assert out[0, r, h, 77] == 0.0, (n, p, r, h)
+            assert np.count_nonzero(out[..., :77]) == 0 and np.count_nonzero(out[..., 78:]) == 0
+
+
+def test_block_attn_is_deterministic_and_readonly(tb):
+    torch, binding = tb
+    case = inputs.block_attn_case(8, 3, 4, 8, 2, 128, 1000, [996, 500, 3], dtype="bf16")
+    q, k, v = case["q"].to_torch(), case["k"].to_torch(), case["v"].to_torch()
+    k0, v0 = k.clone(), v.clone()
+    n = torch.from_numpy(case["n"]).cuda()
+    a = binding.tandem_block_attn(q, k, v, n).clone()
+    b = binding.tandem_block_attn(q, k, v, n)
+    torch.cuda.synchronize()
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    assert torch.equal(k.view(torch.int16), k0.view(torch.int16)) and torch.equal(v.view(torch.int16), v0.view(torch.int16))
+
+
+def test_block_attn_gamma1_equals_draft_with_own_row(tb):
+    """A block of one token is ordinary causal decoding: the block pass over n+1 cache rows equals the
+    mixed-source kernel fed n large rows plus the (n+1)-th row as its single own row."""
+    torch, binding = tb
+    case = inputs.block_attn_case(9, 2, 1, 8, 8, 128, 400, [399, 100], dtype="bf16")
+    q, k, v = case["q"].to_torch(), case["k"].to_torch(), case["v"].to_torch()
+    n = torch.from_numpy(case["n"]).cuda()
+    blk = binding.tandem_block_attn(q, k, v, n)
+    idx = n.long()
+    kcur = torch.stack([k[b, :, idx[b]] for b in range(2)])[:, :, None, :].contiguous()
+    vcur = torch.stack([v[b, :, idx[b]] for b in range(2)])[:, :, None, :].contiguous()
+    one = torch.ones(2, dtype=torch.int32, device="cuda")
+    drf = binding.tandem_draft_attn(q[:, 0].contiguous(), k, v, n, kcur, vcur, one)
+    assert_rows_close(inputs.torch_to_f64(blk[:, 0]), inputs.torch_to_f64(drf), tol=1e-2, what="gamma=1")
+
+
+# --------------------------------------------------------------------------- error paths
+def test_attention_error_codes(tb):
+    torch, binding = tb
+    import ctypes as C
+
+    L = binding.lib()
+    d = binding.attn_desc(2, 4, 2, 128, 64, 4, 0.1, binding.BF16)
+    t = torch.zeros(2 * 4 * 64 * 128 * 2, dtype=torch.bfloat16, device="cuda")
+    n = torch.zeros(2, dtype=torch.int32, device="cuda")
+    p = C.c_void_p(t.data_ptr())
+    pn = C.c_void_p(n.data_ptr())
+    ws = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda")
+    pw = C.c_void_p(ws.data_ptr())
+    assert L.tandem_draft_attn(C.byref(d), None, p, p, pn, p, p, pn, p, pw, ws.numel(), None) == binding.ERR_NULL
+    assert L.tandem_block_attn(C.byref(d), p, p, p, pn, 0, p, pw, ws.numel(), None) == binding.ERR_SHAPE
+    assert L.tandem_block_attn(C.byref(d), p, p, p, pn, 33, p, pw, ws.numel(), None) == binding.ERR_SHAPE
+    bad = binding.attn_desc(2, 4, 3, 128, 64, 4, 0.1, binding.BF16)
+    assert L.tandem_block_attn(C.byref(bad), p, p, p, pn, 2, p, pw, ws.numel(), None) == binding.ERR_SHAPE
+    bad = binding.attn_desc(2, 4, 2, 96, 64, 4, 0.1, binding.BF16)
+    assert L.tandem_draft_attn(C.byref(bad), p, p, p, pn, p, p, pn, p, pw, ws.numel(), None) == binding.ERR_UNSUPPORTED
+    big = binding.attn_desc(2, 4, 2, 128, 1 << 16, 4, 0.1, binding.BF16)
+    need = binding.tandem_draft_attn_workspace(big)
+    assert need > 0
+    assert L.tandem_draft_attn(C.byref(big), p, p, p, pn, p, p, pn, p, pw, need - 1, None) == binding.ERR_WORKSPACE
+    torch.cuda.synchronize()
