@@ -262,3 +262,137 @@ def tandem_project(ff: dict, x, out=None, ws=None, stream=None):
     rc = lib().tandem_project(C.byref(d), _ptr(x), _ptr(out), M, _ptr(ws), ws.numel(), _stream(stream))
     _check(rc, "tandem_project")
     return out
+
+
+# ------------------------------------------------------------------ decode step
+def _dev(t):
+    """HostTensor (paper_2402_08644_amd.inputs) or torch tensor -> device torch tensor."""
+    return t.to_torch() if hasattr(t, "to_torch") else t
+
+
+class TandemModel:
+    """Owns the device copies of a Tandem pair's weights and the opaque tandem_model handle.
+
+    `weights` has the layout produced by inputs.tandem_weights: {"L": decoder, "S": decoder,
+    "ell": [...], "ff": [...], "eps": float} with per-layer Wq / Wk / Wv stored separately; they are
+    stacked here into the Wqkv operand the C ABI takes."""
+
+    def __init__(self, weights):
+        import torch
+
+        self._keep = []
+        self.eps = float(weights["eps"])
+        self.ell = [int(v) for v in weights["ell"]]
+
+        def hold(t):
+            t = _dev(t).contiguous()
+            self._keep.append(t)
+            return t
+
+        def decoder(M):
+            layers = (LayerWeights * len(M["layers"]))()
+            for i, lay in enumerate(M["layers"]):
+                wqkv = hold(torch.cat([_dev(lay["Wq"]), _dev(lay["Wk"]), _dev(lay["Wv"])], dim=0))
+                vals = dict(g_attn=hold(lay["g_attn"]), Wqkv=wqkv, Wo=hold(lay["Wo"]), g_mlp=hold(lay["g_mlp"]),
+                            W1=hold(lay["W1"]), b1=hold(lay["b1"]) if lay.get("b1") is not None else None,
+                            W2=hold(lay["W2"]), b2=hold(lay["b2"]) if lay.get("b2") is not None else None)
+                for k, v in vals.items():
+                    setattr(layers[i], k, None if v is None else v.data_ptr())
+            self._keep.append(layers)
+            emb, gf, wo = hold(M["emb"]), hold(M["g_final"]), hold(M["W_out"])
+            d = DecoderDesc(len(M["layers"]), emb.shape[1], M["Hq"], M["Hkv"], M["dh"], M["layers"][0]["W1"].shape[0],
+                            emb.shape[0], emb.data_ptr(), gf.data_ptr(), wo.data_ptr(), layers)
+            return d, emb
+
+        L, embL = decoder(weights["L"])
+        S, embS = decoder(weights["S"])
+        self.dtype = embL.dtype
+        self.dtype_code = _dtype_code(embL)
+        self.L, self.S = L, S
+        ffs = (FFDesc * len(weights["ff"]))()
+        for j, ff in enumerate(weights["ff"]):
+            held = {k: (hold(v) if hasattr(v, "shape") else v) for k, v in ff.items()}
+            ffs[j] = ff_desc(held)
+        ell = (C.c_int32 * len(self.ell))(*self.ell)
+        self._keep += [ffs, ell]
+        desc = ModelDesc(L, S, ell, ffs, self.eps, self.dtype_code)
+        handle = C.c_void_p()
+        _check(lib().tandem_model_create(C.byref(desc), C.byref(handle)), "tandem_model_create")
+        self.handle = handle
+
+    def __del__(self):
+        h = getattr(self, "handle", None)
+        if h:
+            lib().tandem_model_destroy(h)
+            self.handle = None
+
+
+class TandemState:
+    """Caller-owned caches and per-sequence state of tandem_decode_step, as torch tensors."""
+
+    def __init__(self, model: TandemModel, B, T_max, gamma_max, device="cuda", fill=None):
+        import torch
+
+        self.B, self.T_max, self.gamma_max = B, T_max, gamma_max
+        L, S = model.L, model.S
+        mk = (lambda *s: torch.zeros(s, dtype=model.dtype, device=device)) if fill is None else fill
+        self.KL = [mk(B, L.Hkv, T_max, L.dh) for _ in range(L.n_layers)]
+        self.VL = [mk(B, L.Hkv, T_max, L.dh) for _ in range(L.n_layers)]
+        self.Khat = [mk(B, S.Hkv, T_max, S.dh) for _ in range(S.n_layers)]
+        self.Vhat = [mk(B, S.Hkv, T_max, S.dh) for _ in range(S.n_layers)]
+        self.Kcur = [torch.zeros((B, S.Hkv, gamma_max, S.dh), dtype=model.dtype, device=device) for _ in range(S.n_layers)]
+        self.Vcur = [torch.zeros((B, S.Hkv, gamma_max, S.dh), dtype=model.dtype, device=device) for _ in range(S.n_layers)]
+        self.n = torch.zeros(B, dtype=torch.int32, device=device)
+        self.pending = torch.zeros(B, dtype=torch.int32, device=device)
+        self._arrays = {}
+        self.desc = self._make_desc()
+
+    def _make_desc(self):
+        def arr(name):
+            ts = getattr(self, name)
+            a = (C.c_void_p * len(ts))(*[t.data_ptr() for t in ts])
+            self._arrays[name] = a
+            return a
+
+        return StateDesc(self.B, self.T_max, self.gamma_max, arr("KL"), arr("VL"), arr("Khat"), arr("Vhat"), arr("Kcur"),
+                         arr("Vcur"), self.n.data_ptr(), self.pending.data_ptr())
+
+
+def tandem_decode_step_workspace(model: TandemModel, B: int, gamma: int) -> int:
+    return int(lib().tandem_decode_step_workspace(model.handle, B, gamma))
+
+
+def tandem_decode_step(model: TandemModel, state: TandemState, gamma: int, forced=None, aux=False, ws=None, out=None,
+                       stream=None):
+    """Runs one step.  Returns a dict with "tokens" [B,gamma] and "n_accepted" [B] (int32 device tensors) and,
+    with aux=True, "draft", "verify", "y_small", "x_large", "logits_S", "logits_L"."""
+    import torch
+
+    B = state.B
+    dev = state.n.device
+    if out is None:
+        out = {"tokens": torch.empty((B, gamma), dtype=torch.int32, device=dev),
+               "n_accepted": torch.empty((B,), dtype=torch.int32, device=dev)}
+        if aux:
+            out.update(
+                draft=torch.empty((B, gamma), dtype=torch.int32, device=dev),
+                verify=torch.empty((B, gamma), dtype=torch.int32, device=dev),
+                y_small=torch.empty((B, gamma, model.S.d), dtype=model.dtype, device=dev),
+                x_large=torch.empty((B, gamma, model.L.d), dtype=model.dtype, device=dev),
+                logits_S=torch.empty((B, gamma, model.S.vocab), dtype=model.dtype, device=dev),
+                logits_L=torch.empty((B, gamma, model.L.vocab), dtype=model.dtype, device=dev),
+            )
+    a = None
+    if "draft" in out:
+        a = StepAux(*[out[k].data_ptr() for k in ("draft", "verify", "y_small", "x_large", "logits_S", "logits_L")])
+    if forced is not None:
+        _need(forced, (B, gamma), "forced")
+        if forced.dtype != torch.int32:
+            raise TypeError("forced must be int32")
+    if ws is None:
+        ws = _workspace(tandem_decode_step_workspace(model, B, gamma), state.n)
+    rc = lib().tandem_decode_step(model.handle, C.byref(state.desc), gamma, _ptr(forced), _ptr(out["tokens"]),
+                                  _ptr(out["n_accepted"]), C.byref(a) if a is not None else None, _ptr(ws), ws.numel(),
+                                  _stream(stream))
+    _check(rc, "tandem_decode_step")
+    return out

@@ -1,0 +1,425 @@
+// tandem_project and tandem_decode_step: host-side orchestration of the kernels for one
+// Tandem + SPEED step (Sec. 3.1; Sec. 1 steps 2-4).  Everything is enqueued on one stream;
+// lengths, tokens and the acceptance decision stay on the device, so the step never
+// synchronises with the host.
+#include <new>
+#include <vector>
+
+#include "common.h"
+#include "glue.h"
+#include "kernels.h"
+
+namespace {
+
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+inline size_t elsize(int dtype) { return dtype == TANDEM_BF16 ? 2 : 4; }
+inline size_t maxz(size_t a, size_t b) { return a > b ? a : b; }
+
+int check_ff(const tandem_ff_desc* ff) {
+  if (!ff) return TANDEM_ERR_NULL;
+  if (ff->d_L <= 0 || ff->d_S <= 0 || ff->d_hidden < 0) return TANDEM_ERR_SHAPE;
+  if (ff->dtype != TANDEM_F32 && ff->dtype != TANDEM_BF16) return TANDEM_ERR_UNSUPPORTED;
+  if (!ff->W1) return TANDEM_ERR_NULL;
+  if (ff->d_hidden > 0) {
+    if (!ff->W2) return TANDEM_ERR_NULL;
+    if (ff->act != TANDEM_ACT_NONE && ff->act != TANDEM_ACT_GELU && ff->act != TANDEM_ACT_RELU)
+      return TANDEM_ERR_UNSUPPORTED;
+  }
+  return TANDEM_OK;
+}
+
+size_t project_ws(const tandem_ff_desc* ff, int64_t M) {
+  if (ff->d_hidden == 0) return align256(gemm_workspace((int)M, ff->d_S, ff->d_L, ff->dtype));
+  const size_t hidden = align256((size_t)M * ff->d_hidden * elsize(ff->dtype));
+  const size_t g = maxz(gemm_workspace((int)M, ff->d_hidden, ff->d_L, ff->dtype),
+                        gemm_workspace((int)M, ff->d_S, ff->d_hidden, ff->dtype));
+  return hidden + align256(g);
+}
+
+int gemm(const void* X, int64_t ldx, const void* W, const void* bias, const void* residual, int64_t ldr, void* Y,
+         int64_t ldy, int M, int N, int K, int act, int dtype, void* ws, size_t ws_bytes, hipStream_t st) {
+  GemmArgs g;
+  g.X = X;
+  g.ldx = ldx;
+  g.W = W;
+  g.bias = bias;
+  g.residual = residual;
+  g.ldr = ldr;
+  g.Y = Y;
+  g.ldy = ldy;
+  g.M = M;
+  g.N = N;
+  g.K = K;
+  g.act = act;
+  g.dtype = dtype;
+  g.ws = (float*)ws;
+  g.ws_bytes = ws_bytes;
+  return launch_gemm(g, st);
+}
+
+// y_hat = FF_Tandem(x)   (Eq. (2), first line)
+int run_project(const tandem_ff_desc* ff, const void* x, void* y, int64_t M, void* ws, size_t ws_bytes, hipStream_t st) {
+  if (ff->d_hidden == 0)
+    return gemm(x, ff->d_L, ff->W1, ff->b1, nullptr, 0, y, ff->d_S, (int)M, ff->d_S, ff->d_L, TANDEM_ACT_NONE, ff->dtype,
+                ws, ws_bytes, st);
+  const size_t hidden = align256((size_t)M * ff->d_hidden * elsize(ff->dtype));
+  void* hbuf = ws;
+  void* gws = (char*)ws + hidden;
+  const size_t gws_bytes = ws_bytes - hidden;
+  int rc = gemm(x, ff->d_L, ff->W1, ff->b1, nullptr, 0, hbuf, ff->d_hidden, (int)M, ff->d_hidden, ff->d_L, ff->act,
+                ff->dtype, gws, gws_bytes, st);
+  if (rc != TANDEM_OK) return rc;
+  return gemm(hbuf, ff->d_hidden, ff->W2, ff->b2, nullptr, 0, y, ff->d_S, (int)M, ff->d_S, ff->d_hidden, TANDEM_ACT_NONE,
+              ff->dtype, gws, gws_bytes, st);
+}
+
+int check_decoder(const tandem_decoder_desc& d) {
+  if (d.n_layers <= 0 || d.d <= 0 || d.Hq <= 0 || d.Hkv <= 0 || d.d_ff <= 0 || d.vocab <= 0) return TANDEM_ERR_SHAPE;
+  if (d.Hq % d.Hkv != 0) return TANDEM_ERR_SHAPE;
+  if (d.dh != 64 && d.dh != 128) return TANDEM_ERR_UNSUPPORTED;
+  const int G = d.Hq / d.Hkv;
+  if (G != 1 && G != 2 && G != 4 && G != 8) return TANDEM_ERR_UNSUPPORTED;
+  if (!d.emb || !d.g_final || !d.W_out || !d.layers) return TANDEM_ERR_NULL;
+  for (int j = 0; j < d.n_layers; ++j) {
+    const tandem_layer_weights& l = d.layers[j];
+    if (!l.g_attn || !l.Wqkv || !l.Wo || !l.g_mlp || !l.W1 || !l.W2) return TANDEM_ERR_NULL;
+  }
+  return TANDEM_OK;
+}
+
+}  // namespace
+
+struct tandem_model {
+  tandem_model_desc d;
+  std::vector<tandem_layer_weights> L_layers, S_layers;
+  std::vector<int32_t> ell;
+  std::vector<tandem_ff_desc> ff;
+};
+
+namespace {
+
+// Workspace layout of one step, a pure function of (model, B, gamma, T_max, gamma_max).
+struct StepPlan {
+  size_t x, xn, qkv, q, att, h, logits, yhat, kv, keep, ints, attn_ws, gemm_ws, total;
+  size_t attn_ws_bytes, gemm_ws_bytes, keep_stride;
+  int32_t n_keep;
+};
+
+StepPlan make_plan(const tandem_model* m, int B, int gamma, int64_t T_max, int gamma_max) {
+  const tandem_decoder_desc &L = m->d.L, &S = m->d.S;
+  const size_t es = elsize(m->d.dtype);
+  const size_t M = (size_t)B * gamma;
+  const size_t dmax = maxz(L.d, S.d);
+  const size_t qkvmax = maxz((size_t)(L.Hq + 2 * L.Hkv) * L.dh, (size_t)(S.Hq + 2 * S.Hkv) * S.dh);
+  const size_t qmax = maxz((size_t)L.Hq * L.dh, (size_t)S.Hq * S.dh);
+  const size_t ffmax = maxz(L.d_ff, S.d_ff);
+  const size_t vmax = maxz(L.vocab, S.vocab);
+  StepPlan p{};
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    const size_t o = off;
+    off += align256(bytes);
+    return o;
+  };
+  p.x = take(M * dmax * es);
+  p.xn = take(M * dmax * es);
+  p.qkv = take(M * qkvmax * es);
+  p.q = take(M * qmax * es);
+  p.att = take(M * qmax * es);
+  p.h = take(M * ffmax * es);
+  p.logits = take(M * vmax * es);
+  p.yhat = take(M * S.d * es);
+  p.kv = take(M * 2 * S.Hkv * S.dh * es);
+  p.n_keep = S.n_layers;
+  p.keep_stride = align256(M * L.d * es);
+  p.keep = take(p.keep_stride * S.n_layers);
+  // ints: ncur[gamma][B], block_tokens[B*gamma], draft[B*gamma], verify[B*gamma]
+  p.ints = take(sizeof(int32_t) * 4 * M);
+  // attention scratch: the larger of the draft and the block call
+  {
+    const int Sd = attn_rows_splits(B, S.Hkv, 1, T_max, gamma_max);
+    size_t a = Sd > 1 ? align256((size_t)B * S.Hq * Sd * 2 * 4) + (size_t)B * S.Hq * Sd * S.dh * 4 : 0;
+    const bool mfma = m->d.dtype == TANDEM_BF16 && L.dh == 128;
+    const int Sb = mfma ? attn_block_splits(B, L.Hkv, T_max) : attn_rows_splits(B, L.Hkv, gamma, T_max, 0);
+    const size_t rows = (size_t)B * gamma * L.Hq;
+    size_t b = Sb > 1 ? align256(rows * Sb * 2 * 4) + rows * Sb * L.dh * 4 : 0;
+    p.attn_ws_bytes = maxz(a, b);
+    p.attn_ws = take(p.attn_ws_bytes);
+  }
+  {
+    const int dt = m->d.dtype;
+    size_t g = 0;
+    auto need = [&](size_t rows, int N, int K) { g = maxz(g, gemm_workspace((int)rows, N, K, dt)); };
+    auto need_decoder = [&](const tandem_decoder_desc& D, size_t rows) {
+      need(rows, (D.Hq + 2 * D.Hkv) * D.dh, D.d);
+      need(rows, D.d, D.Hq * D.dh);
+      need(rows, D.d_ff, D.d);
+      need(rows, D.d, D.d_ff);
+      need(rows, D.vocab, D.d);
+    };
+    need_decoder(S, (size_t)B);
+    need_decoder(L, M);
+    need(M, 2 * S.Hkv * S.dh, S.d);
+    size_t pj = 0;
+    for (int j = 0; j < S.n_layers; ++j) pj = maxz(pj, project_ws(&m->ff[j], (int64_t)M));
+    p.gemm_ws_bytes = maxz(align256(g), pj);
+    p.gemm_ws = take(p.gemm_ws_bytes);
+  }
+  p.total = off;
+  return p;
+}
+
+struct Ctx {
+  const tandem_model* m;
+  const tandem_state_desc* st;
+  StepPlan plan;
+  char* ws;
+  hipStream_t stream;
+  int dtype;
+  float eps;
+  template <typename T = void> T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
+};
+
+#define TRY(expr)                     \
+  do {                                \
+    const int rc_ = (expr);           \
+    if (rc_ != TANDEM_OK) return rc_; \
+  } while (0)
+
+int attn_call(const Ctx& c, const tandem_decoder_desc& D, const void* q, const void* kA, const void* vA, const int32_t* nA,
+              const void* kB, const void* vB, const int32_t* nB, int causal, int q_len, void* out) {
+  AttnArgs a{};
+  a.q = q;
+  a.kA = kA;
+  a.vA = vA;
+  a.kB = kB;
+  a.vB = vB;
+  a.nA = nA;
+  a.nB = nB;
+  a.causal = causal;
+  a.B = c.st->B;
+  a.Hq = D.Hq;
+  a.Hkv = D.Hkv;
+  a.dh = D.dh;
+  a.q_len = q_len;
+  a.T_max = c.st->T_max;
+  a.gamma_max = causal ? 0 : c.st->gamma_max;
+  a.scale = 1.0f / sqrtf((float)D.dh);
+  a.dtype = c.dtype;
+  a.out = out;
+  const bool mfma = causal && attn_block_supported(a);
+  a.S = mfma ? attn_block_splits(a.B, a.Hkv, a.T_max)
+             : attn_rows_splits(a.B, a.Hkv, q_len, a.T_max, causal ? 0 : c.st->gamma_max);
+  if (a.S > 1) {
+    const size_t rows = (size_t)a.B * q_len * a.Hq;
+    a.part_ml = c.at<float>(c.plan.attn_ws);
+    a.part_o = reinterpret_cast<float*>(c.ws + c.plan.attn_ws + align256(rows * a.S * 2 * sizeof(float)));
+  }
+  return mfma ? launch_attn_block(a, c.stream) : launch_attn_rows(a, c.stream);
+}
+
+// One pre-norm decoder layer on `rows` rows of the residual stream c.x (in place).
+// attn: callable doing scatter + attention, reading c.qkv and writing c.att.
+template <typename AttnFn>
+int decoder_layer(const Ctx& c, const tandem_decoder_desc& D, const tandem_layer_weights& w, int rows, AttnFn attn) {
+  void *x = c.at<>(c.plan.x), *xn = c.at<>(c.plan.xn), *qkv = c.at<>(c.plan.qkv), *att = c.at<>(c.plan.att),
+       *h = c.at<>(c.plan.h), *gws = c.at<>(c.plan.gemm_ws);
+  const int nqkv = (D.Hq + 2 * D.Hkv) * D.dh, nq = D.Hq * D.dh;
+  TRY(launch_rmsnorm(x, w.g_attn, xn, rows, D.d, c.eps, c.dtype, c.stream));
+  TRY(gemm(xn, D.d, w.Wqkv, nullptr, nullptr, 0, qkv, nqkv, rows, nqkv, D.d, TANDEM_ACT_NONE, c.dtype, gws,
+           c.plan.gemm_ws_bytes, c.stream));
+  TRY(attn());
+  TRY(gemm(att, nq, w.Wo, nullptr, x, D.d, x, D.d, rows, D.d, nq, TANDEM_ACT_NONE, c.dtype, gws, c.plan.gemm_ws_bytes,
+           c.stream));
+  TRY(launch_rmsnorm(x, w.g_mlp, xn, rows, D.d, c.eps, c.dtype, c.stream));
+  TRY(gemm(xn, D.d, w.W1, w.b1, nullptr, 0, h, D.d_ff, rows, D.d_ff, D.d, TANDEM_ACT_GELU, c.dtype, gws,
+           c.plan.gemm_ws_bytes, c.stream));
+  TRY(gemm(h, D.d_ff, w.W2, w.b2, x, D.d, x, D.d, rows, D.d, D.d_ff, TANDEM_ACT_NONE, c.dtype, gws, c.plan.gemm_ws_bytes,
+           c.stream));
+  return TANDEM_OK;
+}
+
+int head(const Ctx& c, const tandem_decoder_desc& D, int rows, int32_t* tok_out, int64_t tok_stride) {
+  void *x = c.at<>(c.plan.x), *xn = c.at<>(c.plan.xn), *lg = c.at<>(c.plan.logits);
+  TRY(launch_rmsnorm(x, D.g_final, xn, rows, D.d, c.eps, c.dtype, c.stream));
+  TRY(gemm(xn, D.d, D.W_out, nullptr, nullptr, 0, lg, D.vocab, rows, D.vocab, D.d, TANDEM_ACT_NONE, c.dtype,
+           c.at<>(c.plan.gemm_ws), c.plan.gemm_ws_bytes, c.stream));
+  return launch_argmax(lg, rows, D.vocab, tok_out, tok_stride, c.dtype, c.stream);
+}
+
+int copy2d(void* dst, size_t dpitch, const void* src, size_t spitch, size_t width, size_t height, hipStream_t st) {
+  return hip_ok(hipMemcpy2DAsync(dst, dpitch, src, spitch, width, height, hipMemcpyDeviceToDevice, st));
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t tandem_project_workspace(const tandem_ff_desc* ff, int64_t M) {
+  if (check_ff(ff) != TANDEM_OK || M < 1) return 0;
+  return project_ws(ff, M);
+}
+
+int tandem_project(const tandem_ff_desc* ff, const void* x, void* y_hat, int64_t M, void* ws, size_t ws_bytes,
+                   void* hip_stream) {
+  int rc = check_ff(ff);
+  if (rc != TANDEM_OK) return rc;
+  if (!x || !y_hat) return TANDEM_ERR_NULL;
+  if (M < 1 || M > (1 << 24)) return TANDEM_ERR_SHAPE;
+  const size_t need = project_ws(ff, M);
+  if (need > 0 && !ws) return TANDEM_ERR_NULL;
+  if (ws_bytes < need) return TANDEM_ERR_WORKSPACE;
+  return run_project(ff, x, y_hat, M, ws, ws_bytes, (hipStream_t)hip_stream);
+}
+
+int tandem_model_create(const tandem_model_desc* desc, tandem_model** out) {
+  if (!desc || !out) return TANDEM_ERR_NULL;
+  *out = nullptr;
+  if (desc->dtype != TANDEM_F32 && desc->dtype != TANDEM_BF16) return TANDEM_ERR_UNSUPPORTED;
+  int rc = check_decoder(desc->L);
+  if (rc != TANDEM_OK) return rc;
+  rc = check_decoder(desc->S);
+  if (rc != TANDEM_OK) return rc;
+  if (!desc->ell || !desc->ff) return TANDEM_ERR_NULL;
+  if (!(desc->rms_eps >= 0.f)) return TANDEM_ERR_SHAPE;
+  for (int j = 0; j < desc->S.n_layers; ++j) {
+    if (desc->ell[j] < 0 || desc->ell[j] > desc->L.n_layers) return TANDEM_ERR_SHAPE;
+    rc = check_ff(&desc->ff[j]);
+    if (rc != TANDEM_OK) return rc;
+    if (desc->ff[j].d_L != desc->L.d || desc->ff[j].d_S != desc->S.d || desc->ff[j].dtype != desc->dtype)
+      return TANDEM_ERR_SHAPE;
+  }
+  tandem_model* m = new (std::nothrow) tandem_model();
+  if (!m) return TANDEM_ERR_HIP;
+  m->d = *desc;
+  m->L_layers.assign(desc->L.layers, desc->L.layers + desc->L.n_layers);
+  m->S_layers.assign(desc->S.layers, desc->S.layers + desc->S.n_layers);
+  m->ell.assign(desc->ell, desc->ell + desc->S.n_layers);
+  m->ff.assign(desc->ff, desc->ff + desc->S.n_layers);
+  m->d.L.layers = m->L_layers.data();
+  m->d.S.layers = m->S_layers.data();
+  m->d.ell = m->ell.data();
+  m->d.ff = m->ff.data();
+  *out = m;
+  return TANDEM_OK;
+}
+
+void tandem_model_destroy(tandem_model* m) { delete m; }
+
+size_t tandem_decode_step_workspace(const tandem_model* m, int32_t B, int32_t gamma) {
+  if (!m || B < 1 || gamma < 1 || gamma > TANDEM_MAX_QLEN) return 0;
+  // T_max only scales the split-K scratch, which is capped at 64 splits: size for the cap
+  return make_plan(m, B, gamma, (int64_t)1 << 40, gamma).total;
+}
+
+int tandem_decode_step(const tandem_model* m, const tandem_state_desc* state, int32_t gamma, const int32_t* forced,
+                       int32_t* out_tokens, int32_t* n_accepted, const tandem_step_aux* aux, void* ws, size_t ws_bytes,
+                       void* hip_stream) {
+  if (!m || !state || !out_tokens || !n_accepted || !ws) return TANDEM_ERR_NULL;
+  if (!state->KL || !state->VL || !state->Khat || !state->Vhat || !state->Kcur || !state->Vcur || !state->n ||
+      !state->pending)
+    return TANDEM_ERR_NULL;
+  const tandem_decoder_desc &L = m->d.L, &S = m->d.S;
+  const int B = state->B;
+  if (B < 1 || B > 65535 || state->T_max < 1 || state->gamma_max < 1) return TANDEM_ERR_SHAPE;
+  if (gamma < 1 || gamma > TANDEM_MAX_QLEN || gamma > state->gamma_max || gamma > state->T_max) return TANDEM_ERR_SHAPE;
+  for (int j = 0; j < L.n_layers; ++j)
+    if (!state->KL[j] || !state->VL[j]) return TANDEM_ERR_NULL;
+  for (int j = 0; j < S.n_layers; ++j)
+    if (!state->Khat[j] || !state->Vhat[j] || !state->Kcur[j] || !state->Vcur[j]) return TANDEM_ERR_NULL;
+  if (ws_bytes < tandem_decode_step_workspace(m, B, gamma)) return TANDEM_ERR_WORKSPACE;
+
+  Ctx c;
+  c.m = m;
+  c.st = state;
+  c.plan = make_plan(m, B, gamma, state->T_max, state->gamma_max);
+  if (c.plan.total > ws_bytes) return TANDEM_ERR_WORKSPACE;
+  c.ws = (char*)ws;
+  c.stream = (hipStream_t)hip_stream;
+  c.dtype = m->d.dtype;
+  c.eps = m->d.rms_eps;
+  const size_t es = elsize(c.dtype);
+  const int M = B * gamma;
+
+  int32_t* ncur = c.at<int32_t>(c.plan.ints);        // [gamma][B], ncur[r][b] = r + 1
+  int32_t* block_tokens = ncur + M;                  // [B, gamma]
+  int32_t* draft = aux && aux->draft ? aux->draft : block_tokens + M;    // [B, gamma]
+  int32_t* verify = aux && aux->verify ? aux->verify : block_tokens + 2 * M;  // [B, gamma]
+  void *x = c.at<>(c.plan.x), *qkv = c.at<>(c.plan.qkv), *q = c.at<>(c.plan.q), *att = c.at<>(c.plan.att);
+
+  TRY(launch_prepare_step(state->pending, ncur, B, gamma, c.stream));
+
+  // ---- 1. draft: gamma autoregressive runs of M_S --------------------------------------
+  for (int r = 0; r < gamma; ++r) {
+    const int32_t* toks;
+    int64_t stride;
+    if (r == 0) {
+      toks = state->pending;
+      stride = 1;
+    } else {
+      toks = (forced ? forced : draft) + (r - 1);
+      stride = gamma;
+    }
+    TRY(launch_embed(S.emb, toks, stride, x, B, S.d, S.vocab, c.dtype, c.stream));
+    for (int j = 0; j < S.n_layers; ++j) {
+      auto attn = [&]() -> int {
+        TRY(launch_scatter_qkv(qkv, q, state->Kcur[j], state->Vcur[j], nullptr, r, B, 1, S.Hq, S.Hkv, S.dh,
+                               state->gamma_max, 0, S.Hq * S.dh, (S.Hq + 2 * S.Hkv) * S.dh, c.dtype, c.stream));
+        return attn_call(c, S, q, state->Khat[j], state->Vhat[j], state->n, state->Kcur[j], state->Vcur[j],
+                         ncur + (size_t)r * B, 0, 1, att);
+      };
+      TRY(decoder_layer(c, S, S.layers[j], B, attn));
+    }
+    if (aux && aux->y_small)
+      TRY(copy2d((char*)aux->y_small + (size_t)r * S.d * es, (size_t)gamma * S.d * es, x, S.d * es, S.d * es, B, c.stream));
+    TRY(head(c, S, B, draft + r, gamma));
+    if (aux && aux->logits_S)
+      TRY(copy2d((char*)aux->logits_S + (size_t)r * S.vocab * es, (size_t)gamma * S.vocab * es, c.at<>(c.plan.logits),
+                 S.vocab * es, S.vocab * es, B, c.stream));
+  }
+
+  // ---- 2. verify: M_L in block mode on [pending, d_1 .. d_{gamma-1}] -------------------
+  TRY(launch_block_tokens(state->pending, forced ? forced : draft, block_tokens, B, gamma, c.stream));
+  TRY(launch_embed(L.emb, block_tokens, 1, x, M, L.d, L.vocab, c.dtype, c.stream));
+  auto keep = [&](int depth) -> int {  // x^(depth) for every small layer that reads it
+    for (int j = 0; j < S.n_layers; ++j)
+      if (m->ell[j] == depth)
+        TRY(hip_ok(hipMemcpyAsync(c.ws + c.plan.keep + j * c.plan.keep_stride, x, (size_t)M * L.d * es,
+                                  hipMemcpyDeviceToDevice, c.stream)));
+    return TANDEM_OK;
+  };
+  TRY(keep(0));
+  for (int j = 0; j < L.n_layers; ++j) {
+    auto attn = [&]() -> int {
+      TRY(launch_scatter_qkv(qkv, q, state->KL[j], state->VL[j], state->n, 0, M, gamma, L.Hq, L.Hkv, L.dh, state->T_max,
+                             0, L.Hq * L.dh, (L.Hq + 2 * L.Hkv) * L.dh, c.dtype, c.stream));
+      return attn_call(c, L, q, state->KL[j], state->VL[j], state->n, nullptr, nullptr, nullptr, 1, gamma, att);
+    };
+    TRY(decoder_layer(c, L, L.layers[j], M, attn));
+    TRY(keep(j + 1));
+  }
+  if (aux && aux->x_large)
+    TRY(hip_ok(hipMemcpyAsync(aux->x_large, x, (size_t)M * L.d * es, hipMemcpyDeviceToDevice, c.stream)));
+  TRY(head(c, L, M, verify, 1));
+  if (aux && aux->logits_L)
+    TRY(hip_ok(hipMemcpyAsync(aux->logits_L, c.at<>(c.plan.logits), (size_t)M * L.vocab * es, hipMemcpyDeviceToDevice,
+                              c.stream)));
+
+  // ---- 3. FF_Tandem on the new rows, then the small layer's norm and W_K / W_V ---------
+  for (int j = 0; j < S.n_layers; ++j) {
+    void *yhat = c.at<>(c.plan.yhat), *xn = c.at<>(c.plan.xn), *kv = c.at<>(c.plan.kv), *gws = c.at<>(c.plan.gemm_ws);
+    TRY(run_project(&m->ff[j], c.ws + c.plan.keep + j * c.plan.keep_stride, yhat, M, gws, c.plan.gemm_ws_bytes, c.stream));
+    TRY(launch_rmsnorm(yhat, S.layers[j].g_attn, xn, M, S.d, c.eps, c.dtype, c.stream));
+    const void* Wkv = (const char*)S.layers[j].Wqkv + (size_t)S.Hq * S.dh * S.d * es;
+    const int nkv = 2 * S.Hkv * S.dh;
+    TRY(gemm(xn, S.d, Wkv, nullptr, nullptr, 0, kv, nkv, M, nkv, S.d, TANDEM_ACT_NONE, c.dtype, gws, c.plan.gemm_ws_bytes,
+             c.stream));
+    TRY(launch_scatter_qkv(kv, nullptr, state->Khat[j], state->Vhat[j], state->n, 0, M, gamma, S.Hq, S.Hkv, S.dh,
+                           state->T_max, 0, 0, nkv, c.dtype, c.stream));
+  }
+
+  // ---- 4. accept ------------------------------------------------------------------------
+  return launch_accept(draft, verify, forced, out_tokens, n_accepted, state->n, state->pending, B, gamma, c.stream);
+}
+
+}  // extern "C"

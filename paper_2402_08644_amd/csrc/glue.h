@@ -1,0 +1,14 @@
+// Launchers of the small decode-step kernels (glue.hip).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+int launch_scatter_qkv(const void* qkv, void* q, void* kc, void* vc, const int32_t* base, int fixed, int rows, int q_len,
+                       int Hq, int Hkv, int dh, int64_t cap, int q_off_cols, int kv_off_cols, int row_cols, int dtype,
+                       hipStream_t st);
+int launch_argmax(const void* logits, int rows, int vocab, int32_t* out, int64_t out_stride, int dtype, hipStream_t st);
+int launch_prepare_step(const int32_t* pending, int32_t* ncur, int B, int gamma, hipStream_t st);
+int launch_block_tokens(const int32_t* pending, const int32_t* follow, int32_t* block_tokens, int B, int gamma,
+                        hipStream_t st);
+int launch_accept(const int32_t* draft, const int32_t* verify, const int32_t* forced, int32_t* out_tokens,
+                  int32_t* n_accepted, int32_t* n, int32_t* pending, int B, int gamma, hipStream_t st);

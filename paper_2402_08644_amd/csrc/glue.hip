@@ -1,0 +1,205 @@
+// Small kernels between the dense layers and the attention kernels of the decode step:
+// embedding gather, RMSNorm, scattering fresh K/V rows into the caches, greedy argmax and the
+// SPEED acceptance rule (Sec. 3.1).  None of them moves a significant number of bytes.
+#include "common.h"
+#include "kernels.h"
+#include "glue.h"
+
+namespace {
+
+template <typename T>
+__global__ void embed_kernel(const T* __restrict__ emb, const int32_t* __restrict__ tokens, long long tok_stride,
+                             T* __restrict__ x, int d, int vocab) {
+  const int row = blockIdx.x;
+  int t = tokens[(long long)row * tok_stride];
+  t = t < 0 ? 0 : (t >= vocab ? vocab - 1 : t);
+  const T* src = emb + (long long)t * d;
+  T* dst = x + (long long)row * d;
+  for (int i = threadIdx.x; i < d; i += blockDim.x) dst[i] = src[i];
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const T* __restrict__ x, const T* __restrict__ g, T* __restrict__ y,
+                                                      int d, float eps) {
+  __shared__ float red[4];
+  const long long row = blockIdx.x;
+  const T* xr = x + row * d;
+  float ss = 0.f;
+  for (int i = threadIdx.x; i < d; i += 256) {
+    const float v = to_f32<T>(xr[i]);
+    ss += v * v;
+  }
+  for (int off = 32; off >= 1; off >>= 1) ss += __shfl_xor(ss, off);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  const float tot = red[0] + red[1] + red[2] + red[3];
+  const float inv = 1.0f / sqrtf(tot / (float)d + eps);
+  for (int i = threadIdx.x; i < d; i += 256) y[row * d + i] = from_f32<T>(to_f32<T>(xr[i]) * inv * to_f32<T>(g[i]));
+}
+
+// qkv rows [rows, (Hq + 2 Hkv) dh] -> q [rows, Hq dh] (contiguous) and K/V rows into a cache
+// [B, Hkv, cap, dh] at position pos = base[b] (or 0) + fixed + (row % q_len).
+template <typename T>
+__global__ void scatter_qkv_kernel(const T* __restrict__ qkv, T* __restrict__ q, T* __restrict__ kc, T* __restrict__ vc,
+                                   const int32_t* __restrict__ base, int fixed, int q_len, int Hq, int Hkv, int dh,
+                                   long long cap, int q_off_cols, int kv_off_cols, int row_cols) {
+  const int row = blockIdx.x;
+  const int b = row / q_len, r = row % q_len;
+  const T* src = qkv + (long long)row * row_cols;
+  if (q) {
+    T* qd = q + (long long)row * Hq * dh;
+    for (int i = threadIdx.x; i < Hq * dh; i += blockDim.x) qd[i] = src[q_off_cols + i];
+  }
+  long long pos = (base ? base[b] : 0) + fixed + r;
+  if (pos < 0 || pos >= cap) return;  // never write outside the cache
+  for (int i = threadIdx.x; i < Hkv * dh; i += blockDim.x) {
+    const int kvh = i / dh, e = i % dh;
+    const long long dst = (((long long)b * Hkv + kvh) * cap + pos) * dh + e;
+    kc[dst] = src[kv_off_cols + i];
+    vc[dst] = src[kv_off_cols + Hkv * dh + i];
+  }
+}
+
+// greedy token per row; ties go to the lowest id
+template <typename T>
+__global__ __launch_bounds__(256) void argmax_kernel(const T* __restrict__ logits, int vocab, int32_t* __restrict__ out,
+                                                     long long out_stride) {
+  __shared__ float sv[4];
+  __shared__ int si[4];
+  const long long row = blockIdx.x;
+  const T* lr = logits + row * vocab;
+  float best = -INFINITY;
+  int bi = 0x7fffffff;
+  for (int i = threadIdx.x; i < vocab; i += 256) {
+    const float v = to_f32<T>(lr[i]);
+    if (v > best || (v == best && i < bi)) {
+      best = v;
+      bi = i;
+    }
+  }
+  for (int off = 32; off >= 1; off >>= 1) {
+    const float ov = __shfl_xor(best, off);
+    const int oi = __shfl_xor(bi, off);
+    if (ov > best || (ov == best && oi < bi)) {
+      best = ov;
+      bi = oi;
+    }
+  }
+  if ((threadIdx.x & 63) == 0) {
+    sv[threadIdx.x >> 6] = best;
+    si[threadIdx.x >> 6] = bi;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int w = 1; w < 4; ++w)
+      if (sv[w] > best || (sv[w] == best && si[w] < bi)) {
+        best = sv[w];
+        bi = si[w];
+      }
+    out[row * out_stride] = bi == 0x7fffffff ? 0 : bi;
+  }
+}
+
+// block_tokens[b, 0] = pending[b]; block_tokens[b, r] = (forced ? forced : draft)[b, r-1];  ncur[r][b] = r + 1
+__global__ void prepare_step_kernel(const int32_t* pending, int32_t* ncur, int B, int gamma) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < B * gamma) ncur[i] = i / B + 1;
+}
+__global__ void block_tokens_kernel(const int32_t* pending, const int32_t* follow, int32_t* block_tokens, int B,
+                                    int gamma) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= B * gamma) return;
+  const int b = i / gamma, r = i % gamma;
+  block_tokens[i] = r == 0 ? pending[b] : follow[b * gamma + r - 1];
+}
+
+// Sec. 3.1: first location where the draft differs from M_L's token; emit the agreed prefix and
+// M_L's token there; advance n by the rows that stay valid; the last emitted token becomes pending.
+__global__ void accept_kernel(const int32_t* draft, const int32_t* verify, const int32_t* forced, int32_t* out_tokens,
+                              int32_t* n_accepted, int32_t* n, int32_t* pending, int B, int gamma) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B) return;
+  int a = 0;
+  if (forced) {
+    a = gamma;
+    for (int r = 0; r < gamma; ++r) out_tokens[b * gamma + r] = forced[b * gamma + r];
+    pending[b] = forced[b * gamma + gamma - 1];
+  } else {
+    while (a < gamma && draft[b * gamma + a] == verify[b * gamma + a]) ++a;
+    const int emit = a < gamma ? a + 1 : gamma;
+    for (int r = 0; r < gamma; ++r) {
+      int t = -1;
+      if (r < a) t = draft[b * gamma + r];
+      else if (r == a && a < gamma) t = verify[b * gamma + a];
+      out_tokens[b * gamma + r] = t;
+    }
+    pending[b] = out_tokens[b * gamma + emit - 1];
+  }
+  n_accepted[b] = a;
+  n[b] += a < gamma ? a + 1 : gamma;
+}
+
+}  // namespace
+
+int launch_embed(const void* emb, const int32_t* tokens, int64_t tok_stride, void* x, int rows, int d, int vocab,
+                 int dtype, hipStream_t st) {
+  if (dtype == TANDEM_BF16)
+    hipLaunchKernelGGL(embed_kernel<bf16_t>, dim3(rows), dim3(256), 0, st, (const bf16_t*)emb, tokens,
+                       (long long)tok_stride, (bf16_t*)x, d, vocab);
+  else
+    hipLaunchKernelGGL(embed_kernel<float>, dim3(rows), dim3(256), 0, st, (const float*)emb, tokens,
+                       (long long)tok_stride, (float*)x, d, vocab);
+  return hip_ok(hipGetLastError());
+}
+
+int launch_rmsnorm(const void* x, const void* g, void* y, int rows, int d, float eps, int dtype, hipStream_t st) {
+  if (dtype == TANDEM_BF16)
+    hipLaunchKernelGGL(rmsnorm_kernel<bf16_t>, dim3(rows), dim3(256), 0, st, (const bf16_t*)x, (const bf16_t*)g,
+                       (bf16_t*)y, d, eps);
+  else
+    hipLaunchKernelGGL(rmsnorm_kernel<float>, dim3(rows), dim3(256), 0, st, (const float*)x, (const float*)g, (float*)y,
+                       d, eps);
+  return hip_ok(hipGetLastError());
+}
+
+int launch_scatter_qkv(const void* qkv, void* q, void* kc, void* vc, const int32_t* base, int fixed, int rows, int q_len,
+                       int Hq, int Hkv, int dh, int64_t cap, int q_off_cols, int kv_off_cols, int row_cols, int dtype,
+                       hipStream_t st) {
+  if (dtype == TANDEM_BF16)
+    hipLaunchKernelGGL(scatter_qkv_kernel<bf16_t>, dim3(rows), dim3(256), 0, st, (const bf16_t*)qkv, (bf16_t*)q,
+                       (bf16_t*)kc, (bf16_t*)vc, base, fixed, q_len, Hq, Hkv, dh, (long long)cap, q_off_cols,
+                       kv_off_cols, row_cols);
+  else
+    hipLaunchKernelGGL(scatter_qkv_kernel<float>, dim3(rows), dim3(256), 0, st, (const float*)qkv, (float*)q, (float*)kc,
+                       (float*)vc, base, fixed, q_len, Hq, Hkv, dh, (long long)cap, q_off_cols, kv_off_cols, row_cols);
+  return hip_ok(hipGetLastError());
+}
+
+int launch_argmax(const void* logits, int rows, int vocab, int32_t* out, int64_t out_stride, int dtype, hipStream_t st) {
+  if (dtype == TANDEM_BF16)
+    hipLaunchKernelGGL(argmax_kernel<bf16_t>, dim3(rows), dim3(256), 0, st, (const bf16_t*)logits, vocab, out,
+                       (long long)out_stride);
+  else
+    hipLaunchKernelGGL(argmax_kernel<float>, dim3(rows), dim3(256), 0, st, (const float*)logits, vocab, out,
+                       (long long)out_stride);
+  return hip_ok(hipGetLastError());
+}
+
+int launch_prepare_step(const int32_t* pending, int32_t* ncur, int B, int gamma, hipStream_t st) {
+  hipLaunchKernelGGL(prepare_step_kernel, dim3((B * gamma + 255) / 256), dim3(256), 0, st, pending, ncur, B, gamma);
+  return hip_ok(hipGetLastError());
+}
+
+int launch_block_tokens(const int32_t* pending, const int32_t* follow, int32_t* block_tokens, int B, int gamma,
+                        hipStream_t st) {
+  hipLaunchKernelGGL(block_tokens_kernel, dim3((B * gamma + 255) / 256), dim3(256), 0, st, pending, follow, block_tokens,
+                     B, gamma);
+  return hip_ok(hipGetLastError());
+}
+
+int launch_accept(const int32_t* draft, const int32_t* verify, const int32_t* forced, int32_t* out_tokens,
+                  int32_t* n_accepted, int32_t* n, int32_t* pending, int B, int gamma, hipStream_t st) {
+  hipLaunchKernelGGL(accept_kernel, dim3((B + 63) / 64), dim3(64), 0, st, draft, verify, forced, out_tokens, n_accepted,
+                     n, pending, B, gamma);
+  return hip_ok(hipGetLastError());
+}

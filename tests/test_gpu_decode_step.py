@@ -1,0 +1,231 @@
+"""GPU parity: tandem_decode_step through the C ABI against the fp64 oracle.
+
+Floating-point bar for whole-step outputs: bf16 steps accumulate one bf16 rounding of the
+residual stream per dense layer, so the per-row bound is the per-kernel 2e-2 times
+sqrt(number of decoder layers the row passed through), rounded up; fp32 steps use 2e-3.
+Tokens: the GPU's greedy token must lie in the oracle's near-argmax set
+{v : max_logit - logit_v <= 2e-2 * max|logit|} (several results are correct when logits tie
+within the arithmetic's resolution)."""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import tandem_oracle as orc
+from paper_2402_08644_amd import inputs
+from parity import assert_rows_close
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def tb():
+    import torch
+
+    from paper_2402_08644_amd import binding
+
+    assert torch.cuda.is_available()
+    binding.lib()
+    return torch, binding
+
+
+def oracle_state_from(T, B, T_max, seed, n, pending, dtype, std=1.0):
+    """Random caches (seeded, rounded to the storage dtype) as oracle state + HostTensors for upload."""
+    rng = np.random.default_rng(seed)
+    st = orc.empty_state(T, B, T_max)
+    host = {}
+    for key, M in (("KL", T["L"]), ("VL", T["L"]), ("Khat", T["S"]), ("Vhat", T["S"])):
+        host[key] = []
+        for j in range(len(M["layers"])):
+            h = inputs.normal(rng, (B, M["Hkv"], T_max, M["dh"]), std, dtype)
+            host[key].append(h)
+            st[key][j][...] = h.f64
+    st["n"][:] = n
+    st["pending"][:] = pending
+    return st, host
+
+
+def upload_state(tb, model, B, T_max, gamma_max, host, n, pending):
+    torch, binding = tb
+    gst = binding.TandemState(model, B, T_max, gamma_max)
+    for key in ("KL", "VL", "Khat", "Vhat"):
+        for j, h in enumerate(host[key]):
+            getattr(gst, key)[j].copy_(h.to_torch())
+    gst.n.copy_(torch.tensor(n, dtype=torch.int32))
+    gst.pending.copy_(torch.tensor(pending, dtype=torch.int32))
+    return gst
+
+
+def tokens_ok(gpu_tokens, logits, margin=2e-2):
+    """Every GPU token is a near-argmax of the oracle's logits."""
+    logits = np.asarray(logits)
+    flat_t = np.asarray(gpu_tokens).reshape(-1)
+    flat_l = logits.reshape(-1, logits.shape[-1])
+    for t, lg in zip(flat_t, flat_l):
+        if lg.max() - lg[t] > margin * np.abs(lg).max():
+            return False
+    return True
+
+
+def small_bf16_pair(seed, n_layers_L=2, n_layers_S=2, d_hidden=256, w_std=0.05):
+    return inputs.tandem_weights(
+        seed, vocab=512,
+        large=dict(d=512, n_layers=n_layers_L, Hq=8, Hkv=2, dh=128, d_ff=1024),
+        small=dict(d=256, n_layers=n_layers_S, Hq=2, Hkv=2, dh=128, d_ff=512),
+        ell=tuple(min(n_layers_L, j + 1) for j in range(n_layers_S)), d_hidden=d_hidden, dtype="bf16", w_std=w_std)
+
+
+def test_tiny_config_teacher_forced_forward_fp32(tb):
+    """The tiny full-forward configuration: 128 tokens, gamma = 2, fp32 on the GPU.  Sixty-four forced
+    decode steps must reproduce the oracle's teacher-forced forward (Eq. (2)) at every position."""
+    torch, binding = tb
+    W = inputs.tiny_tandem(seed=0, dtype="f32")
+    T = inputs.as_f64(W)
+    toks = inputs.token_ids(0, (129,), 1000)
+    ref = orc.tandem_forward(T, toks[:128], 2)
+    model = binding.TandemModel(W)
+    gst = binding.TandemState(model, 1, 128, 2)
+    gst.pending.copy_(torch.tensor([int(toks[0])], dtype=torch.int32))
+    ys, xs, lgs = [], [], []
+    for pos in range(0, 128, 2):
+        forced = torch.tensor(toks[None, pos + 1: pos + 3], dtype=torch.int32).cuda()
+        out = binding.tandem_decode_step(model, gst, 2, forced=forced, aux=True)
+        ys.append(inputs.torch_to_f64(out["y_small"][0]))
+        xs.append(inputs.torch_to_f64(out["x_large"][0]))
+        lgs.append(inputs.torch_to_f64(out["logits_S"][0]))
+    torch.cuda.synchronize()
+    assert int(gst.n[0]) == 128
+    e = assert_rows_close(np.concatenate(ys), ref["y"], tol=2e-3, what="y^(L_S)")
+    assert_rows_close(np.concatenate(xs), ref["xs"][-1], tol=2e-3, what="x^(L_L)")
+    assert_rows_close(np.concatenate(lgs), ref["logits_S"], tol=2e-3, what="small logits")
+    print(f"tiny config forward: max rel err {e[0]:.2e}")
+
+
+@pytest.mark.parametrize("gamma,B,n", [(4, 3, [40, 7, 0]), (1, 2, [33, 64]), (8, 2, [100, 1])])
+def test_decode_step_bf16_vs_oracle_on_random_caches(tb, gamma, B, n):
+    torch, binding = tb
+    W = small_bf16_pair(40 + gamma)
+    T = inputs.as_f64(W)
+    T_max = 128
+    pending = [3, 500, 77][:B]
+    ost, host = oracle_state_from(T, B, T_max, 50 + gamma, n, pending, "bf16")
+    model = binding.TandemModel(W)
+    gst = upload_state(tb, model, B, T_max, 8, host, n, pending)
+    forced_np = inputs.token_ids(60 + gamma, (B, gamma), 512)
+    forced = torch.tensor(forced_np, dtype=torch.int32).cuda()
+    out = binding.tandem_decode_step(model, gst, gamma, forced=forced, aux=True)
+    torch.cuda.synchronize()
+    want = orc.decode_step(T, ost, gamma, forced=forced_np)
+    tol = 2e-2 * math.ceil(math.sqrt(2 + 1))
+    e1 = assert_rows_close(inputs.torch_to_f64(out["y_small"]), want["y_small"], tol=tol, what="y_small")
+    e2 = assert_rows_close(inputs.torch_to_f64(out["x_large"]), want["x_large"], tol=tol, what="x_large")
+    print(f"decode step gamma={gamma}: y_small err {e1[0]:.2e}, x_large err {e2[0]:.2e}")
+    assert tokens_ok(out["draft"].cpu().numpy(), want["logits_S"])
+    assert tokens_ok(out["verify"].cpu().numpy(), want["logits_L"])
+    # state update (forced: everything accepted)
+    np.testing.assert_array_equal(gst.n.cpu().numpy(), ost["n"])
+    np.testing.assert_array_equal(gst.pending.cpu().numpy(), ost["pending"])
+    np.testing.assert_array_equal(out["tokens"].cpu().numpy(), want["tokens"])
+    np.testing.assert_array_equal(out["n_accepted"].cpu().numpy(), want["n_accepted"])
+    # new cache rows [n, n+gamma) hold the oracle's rows; rows below n are untouched (bit-exact)
+    for b in range(B):
+        lo, hi = n[b], n[b] + gamma
+        for key, tolk in (("KL", tol), ("VL", tol), ("Khat", tol), ("Vhat", tol)):
+            for j in range(len(host[key])):
+                g = getattr(gst, key)[j]
+                assert_rows_close(inputs.torch_to_f64(g[b, :, lo:hi]), ost[key][j][b, :, lo:hi], tol=tolk, what=f"{key}[{j}] new rows")
+                old = host[key][j].to_torch()
+                assert torch.equal(g[b, :, :lo].view(torch.int16), old[b, :, :lo].view(torch.int16)), f"{key}[{j}] rows below n changed"
+                assert torch.equal(g[b, :, hi:].view(torch.int16), old[b, :, hi:].view(torch.int16)), f"{key}[{j}] rows past the block changed"
+
+
+def test_decode_step_acceptance_rule_exact(tb):
+    """Integer part of the step, bit-exact: with the drafter equal to the verifier and identity FF_Tandem every
+    draft token is accepted; corrupting the small model's head makes the first token wrong, so exactly one
+    token (M_L's) is emitted and n advances by one."""
+    torch, binding = tb
+    dec = dict(d=128, n_layers=2, Hq=2, Hkv=2, dh=64, d_ff=256)
+    W = inputs.tandem_weights(5, vocab=64, large=dec, small=dec, ell=(0, 1), d_hidden=0, dtype="f32", w_std=0.5)
+    W["S"] = W["L"]
+    eye = inputs.HostTensor(np.eye(128, dtype=np.float32), "f32")
+    for ff in W["ff"]:
+        ff["W"] = eye
+    T = inputs.as_f64(W)
+    prompt = inputs.token_ids(1, (2, 5), 64)
+    model = binding.TandemModel(W)
+    gst = binding.TandemState(model, 2, 64, 4)
+    ost = orc.empty_state(T, 2, 64)
+    gst.pending.copy_(torch.tensor(prompt[:, 0], dtype=torch.int32))
+    ost["pending"][:] = prompt[:, 0]
+    binding.tandem_decode_step(model, gst, 4, forced=torch.tensor(prompt[:, 1:], dtype=torch.int32).cuda())
+    orc.decode_step(T, ost, 4, forced=prompt[:, 1:])
+    for _ in range(3):
+        out = binding.tandem_decode_step(model, gst, 4, aux=True)
+        want = orc.decode_step(T, ost, 4)
+        np.testing.assert_array_equal(out["n_accepted"].cpu().numpy(), [4, 4])
+        np.testing.assert_array_equal(out["tokens"].cpu().numpy(), want["tokens"])
+        np.testing.assert_array_equal(out["draft"].cpu().numpy(), out["verify"].cpu().numpy())
+        np.testing.assert_array_equal(gst.n.cpu().numpy(), ost["n"])
+        np.testing.assert_array_equal(gst.pending.cpu().numpy(), ost["pending"])
+    # a drafter whose head is the verifier's with its rows rolled by one always proposes (right token + 1)
+    W2 = dict(W)
+    W2["S"] = dict(W["L"])
+    W2["S"]["W_out"] = inputs.HostTensor(np.roll(W["L"]["W_out"].store, 1, axis=0), "f32")
+    T2 = inputs.as_f64(W2)
+    model2 = binding.TandemModel(W2)
+    n_before = gst.n.cpu().numpy().copy()
+    out = binding.tandem_decode_step(model2, gst, 4, aux=True)
+    want = orc.decode_step(T2, ost, 4)
+    np.testing.assert_array_equal(out["n_accepted"].cpu().numpy(), [0, 0])
+    np.testing.assert_array_equal(gst.n.cpu().numpy(), n_before + 1)
+    tok = out["tokens"].cpu().numpy()
+    np.testing.assert_array_equal(tok, want["tokens"])
+    np.testing.assert_array_equal(tok[:, 0], out["verify"].cpu().numpy()[:, 0])
+    np.testing.assert_array_equal(tok[:, 1:], -1)
+    np.testing.assert_array_equal(gst.pending.cpu().numpy(), tok[:, 0])
+
+
+def test_speed_stream_equals_greedy_large_decode_fp32(tb):
+    """Tandem + SPEED on the GPU emits the token stream of greedy decoding with M_L alone (computed by the
+    oracle), whatever the drafter proposes (Sec. 3.1)."""
+    torch, binding = tb
+    W = inputs.tandem_weights(
+        7, vocab=96, large=dict(d=128, n_layers=2, Hq=4, Hkv=2, dh=64, d_ff=256),
+        small=dict(d=64, n_layers=1, Hq=1, Hkv=1, dh=64, d_ff=128), ell=(2,), d_hidden=96, dtype="f32", w_std=0.4)
+    T = inputs.as_f64(W)
+    prompt = inputs.token_ids(2, (6,), 96)
+    n_new = 10
+    want = orc.greedy_decode_large(T["L"], prompt, n_new, T["eps"])
+    model = binding.TandemModel(W)
+    for gamma in (1, 3, 4):
+        gst = binding.TandemState(model, 1, 64, 4)
+        gst.pending.copy_(torch.tensor([int(prompt[0])], dtype=torch.int32))
+        # prompt ingestion in two forced blocks (block length is free at inference time)
+        binding.tandem_decode_step(model, gst, 3, forced=torch.tensor(prompt[None, 1:4], dtype=torch.int32).cuda())
+        binding.tandem_decode_step(model, gst, 2, forced=torch.tensor(prompt[None, 4:6], dtype=torch.int32).cuda())
+        got = []
+        while len(got) < n_new:
+            out = binding.tandem_decode_step(model, gst, gamma)
+            a = int(out["n_accepted"][0])
+            ne = min(a + 1, gamma)
+            got += [int(t) for t in out["tokens"][0, :ne].cpu().numpy()]
+        assert got[:n_new] == want, (gamma, got, want)
+
+
+def test_decode_step_error_codes(tb):
+    torch, binding = tb
+    import ctypes as C
+
+    W = inputs.tiny_tandem(seed=1, dtype="f32")
+    model = binding.TandemModel(W)
+    gst = binding.TandemState(model, 1, 16, 2)
+    with pytest.raises(binding.TandemError) as ei:
+        binding.tandem_decode_step(model, gst, 3)  # gamma above gamma_max
+    assert ei.value.status == binding.ERR_SHAPE
+    with pytest.raises(binding.TandemError) as ei:
+        binding.tandem_decode_step(model, gst, 2, ws=torch.empty(256, dtype=torch.uint8, device="cuda"))
+    assert ei.value.status == binding.ERR_WORKSPACE
+    L = binding.lib()
+    h = C.c_void_p()
+    assert L.tandem_model_create(None, C.byref(h)) == binding.ERR_NULL
+    torch.cuda.synchronize()

@@ -1,0 +1,110 @@
+"""GPU parity: tandem_project (FF_Tandem, Eq. (2) first line) through the C ABI against the fp64 oracle."""
+import numpy as np
+import pytest
+
+from oracle import tandem_oracle as orc
+from paper_2402_08644_amd import inputs
+from parity import assert_rows_close
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def tb():
+    import torch
+
+    from paper_2402_08644_amd import binding
+
+    assert torch.cuda.is_available()
+    binding.lib()
+    return torch, binding
+
+
+def run(tb, case, act="gelu"):
+    torch, binding = tb
+    ff = {k: v.to_torch() for k, v in case.items() if k != "x"}
+    if "W1" in ff:
+        ff["act"] = act
+    out = binding.tandem_project(ff, case["x"].to_torch())
+    torch.cuda.synchronize()
+    return inputs.torch_to_f64(out)
+
+
+def oracle(case, act="gelu"):
+    ff = {k: v.f64 for k, v in case.items() if k != "x"}
+    if "W1" in ff:
+        ff["act"] = act
+    return orc.project(case["x"].f64, ff)
+
+
+@pytest.mark.parametrize(
+    "M,d_L,d_hidden,d_S,dtype,act",
+    [
+        (1, 256, 512, 128, "bf16", "gelu"),
+        (5, 256, 512, 128, "bf16", "gelu"),
+        (32, 512, 1024, 256, "bf16", "gelu"),
+        (33, 512, 1024, 256, "bf16", "relu"),
+        (64, 1024, 2048, 512, "bf16", "gelu"),
+        (100, 512, 1024, 256, "bf16", "gelu"),
+        (128, 1024, 0, 512, "bf16", "gelu"),        # linear form (the paper's experiments)
+        (200, 512, 1024, 256, "bf16", "gelu"),      # more than one pass of 128 rows
+        (7, 100, 36, 52, "bf16", "gelu"),           # shapes off every tile size: generic path
+        (2, 256, 512, 128, "f32", "gelu"),          # the tiny config's FF_Tandem on one block
+        (128, 256, 512, 128, "f32", "gelu"),        # ... and teacher-forced on all 128 positions
+        (9, 64, 0, 48, "f32", "gelu"),
+    ],
+)
+def test_project_parity_small(tb, M, d_L, d_hidden, d_S, dtype, act):
+    case = inputs.project_case(31, M, d_L, d_hidden, d_S, dtype=dtype, w_std=0.05, bias_std=0.1)
+    got = run(tb, case, act)
+    e = assert_rows_close(got, oracle(case, act), what="project")
+    print(f"project {M,d_L,d_hidden,d_S,dtype}: max rel err {e[0]:.2e}")
+
+
+def test_project_parity_config2_full(tb):
+    """The benchmark's projection: 4096 -> 8192 -> 1024 on the 64 new block rows, weights N(0, 0.02)."""
+    case = inputs.project_case(2, 64, 4096, 8192, 1024, dtype="bf16", w_std=0.02)
+    got = run(tb, case)
+    e = assert_rows_close(got, oracle(case), what="project config 2")
+    print(f"project config2: max rel err {e[0]:.2e}")
+
+
+def test_project_decode_step_shape_and_no_bias(tb):
+    """M = 128 rows (batch 32 x gamma 4) with NULL biases."""
+    torch, binding = tb
+    case = inputs.project_case(3, 128, 2048, 4096, 1024, dtype="bf16", w_std=0.02)
+    ff = {"W1": case["W1"].to_torch(), "W2": case["W2"].to_torch(), "b1": None, "b2": None, "act": "gelu"}
+    out = binding.tandem_project(ff, case["x"].to_torch())
+    want = orc.project(case["x"].f64, {"W1": case["W1"].f64, "W2": case["W2"].f64, "act": "gelu"})
+    assert_rows_close(inputs.torch_to_f64(out), want, what="project M=128")
+
+
+def test_project_is_deterministic(tb):
+    torch, binding = tb
+    case = inputs.project_case(4, 64, 1024, 2048, 512, dtype="bf16")
+    ff = {k: v.to_torch() for k, v in case.items() if k != "x"}
+    x = case["x"].to_torch()
+    a = binding.tandem_project(ff, x).clone()
+    b = binding.tandem_project(ff, x)
+    torch.cuda.synchronize()
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+
+def test_project_error_codes(tb):
+    torch, binding = tb
+    import ctypes as C
+
+    L = binding.lib()
+    t = torch.zeros(1 << 16, dtype=torch.bfloat16, device="cuda")
+    p = t.data_ptr()
+    d = binding.FFDesc(64, 128, 32, binding.ACT_GELU, binding.BF16, p, None, p, None)
+    need = binding.tandem_project_workspace(d, 8)
+    assert need >= 8 * 128 * 2
+    assert L.tandem_project(C.byref(d), C.c_void_p(p), C.c_void_p(p), 8, C.c_void_p(p), need - 1, None) == binding.ERR_WORKSPACE
+    assert L.tandem_project(C.byref(d), None, C.c_void_p(p), 8, C.c_void_p(p), need, None) == binding.ERR_NULL
+    assert L.tandem_project(C.byref(d), C.c_void_p(p), C.c_void_p(p), 0, C.c_void_p(p), need, None) == binding.ERR_SHAPE
+    bad = binding.FFDesc(64, 128, 32, binding.ACT_GELU, binding.BF16, p, None, None, None)  # MLP form without W2
+    assert L.tandem_project(C.byref(bad), C.c_void_p(p), C.c_void_p(p), 8, C.c_void_p(p), need, None) == binding.ERR_NULL
+    bad = binding.FFDesc(64, 128, 32, 7, binding.BF16, p, None, p, None)
+    assert L.tandem_project(C.byref(bad), C.c_void_p(p), C.c_void_p(p), 8, C.c_void_p(p), need, None) == binding.ERR_UNSUPPORTED
+    torch.cuda.synchronize()
