@@ -150,6 +150,146 @@ def block_workload(torch, binding, inputs, B, q_len, Hq, Hkv, dh, n_prefix, seed
     return call, R, bytes_alg, oracle_sample
 
 
+# ------------------------------------------------------------------ whole decode step
+C3 = dict(
+    B=32, gamma=4, ctx=8192, vocab=32768,
+    large=dict(d=4096, n_layers=32, Hq=32, Hkv=8, dh=128, d_ff=16384),
+    small=dict(d=1024, n_layers=8, Hq=8, Hkv=8, dh=128, d_ff=4096),
+    d_hidden=8192,
+)
+
+
+def device_tandem_weights(inputs, cfg, seed):
+    """Random-init Tandem pair generated directly in HBM: weights N(0, 0.02), gains 1, biases 0."""
+    import torch
+
+    ctr = [seed * 100000]
+
+    def nrm(*shape):
+        ctr[0] += 1
+        return inputs.device_normal(shape, ctr[0], 0.02)
+
+    def dec(c):
+        def lay():
+            return {"g_attn": torch.ones(c["d"], dtype=torch.bfloat16, device="cuda"),
+                    "Wq": nrm(c["Hq"] * c["dh"], c["d"]), "Wk": nrm(c["Hkv"] * c["dh"], c["d"]),
+                    "Wv": nrm(c["Hkv"] * c["dh"], c["d"]), "Wo": nrm(c["d"], c["Hq"] * c["dh"]),
+                    "g_mlp": torch.ones(c["d"], dtype=torch.bfloat16, device="cuda"),
+                    "W1": nrm(c["d_ff"], c["d"]), "b1": torch.zeros(c["d_ff"], dtype=torch.bfloat16, device="cuda"),
+                    "W2": nrm(c["d"], c["d_ff"]), "b2": torch.zeros(c["d"], dtype=torch.bfloat16, device="cuda")}
+
+        return {"emb": nrm(cfg["vocab"], c["d"]), "layers": [lay() for _ in range(c["n_layers"])],
+                "g_final": torch.ones(c["d"], dtype=torch.bfloat16, device="cuda"), "W_out": nrm(cfg["vocab"], c["d"]),
+                "Hq": c["Hq"], "Hkv": c["Hkv"], "dh": c["dh"]}
+
+    L, S = dec(cfg["large"]), dec(cfg["small"])
+    every = cfg["large"]["n_layers"] // cfg["small"]["n_layers"]
+    ff = [{"W1": nrm(cfg["d_hidden"], cfg["large"]["d"]), "b1": torch.zeros(cfg["d_hidden"], dtype=torch.bfloat16, device="cuda"),
+           "W2": nrm(cfg["small"]["d"], cfg["d_hidden"]), "b2": torch.zeros(cfg["small"]["d"], dtype=torch.bfloat16, device="cuda"),
+           "act": "gelu"} for _ in range(cfg["small"]["n_layers"])]
+    return {"L": L, "S": S, "ell": [every * (j + 1) for j in range(cfg["small"]["n_layers"])], "ff": ff, "eps": 1e-6}
+
+
+def step_bytes(cfg):
+    """Algorithmic HBM bytes of one decode step: every weight once per model run, every visible KV row once."""
+    B, g, ctx = cfg["B"], cfg["gamma"], cfg["ctx"]
+
+    def dec_w(c):
+        per = (c["Hq"] + 2 * c["Hkv"]) * c["dh"] * c["d"] + c["d"] * c["Hq"] * c["dh"] + 2 * c["d"] * c["d_ff"]
+        return 2 * (c["n_layers"] * per + cfg["vocab"] * c["d"])
+
+    def kv(c, rows):
+        return c["n_layers"] * B * c["Hkv"] * rows * c["dh"] * 2 * 2
+
+    L, S = cfg["large"], cfg["small"]
+    n = ctx - g
+    draft = sum(dec_w(S) + kv(S, n + r + 1) for r in range(g))
+    verify = dec_w(L) + kv(L, ctx)
+    ff = S["n_layers"] * 2 * (cfg["d_hidden"] * L["d"] + S["d"] * cfg["d_hidden"] + 2 * S["Hkv"] * S["dh"] * S["d"])
+    return draft + verify + ff
+
+
+def step_workload(torch, binding, inputs, cfg, seed=3):
+    B, g, ctx = cfg["B"], cfg["gamma"], cfg["ctx"]
+    W = device_tandem_weights(inputs, cfg, seed)
+    model = binding.TandemModel(W)
+    del W
+    k = [seed * 7919]
+
+    def fill(*shape):
+        k[0] += 1
+        return inputs.device_normal(shape, k[0], 1.0)
+
+    state = binding.TandemState(model, B, ctx, g, fill=fill)
+    n0 = ctx - g
+    state.n.fill_(n0)
+    state.pending.fill_(1)
+    ws = torch.empty(binding.tandem_decode_step_workspace(model, B, g), dtype=torch.uint8, device="cuda")
+    out = {"tokens": torch.empty((B, g), dtype=torch.int32, device="cuda"),
+           "n_accepted": torch.empty((B,), dtype=torch.int32, device="cuda")}
+
+    def call(_i):
+        state.n.fill_(n0)       # keep the context at ctx: the step itself advances n
+        state.pending.fill_(1)
+        binding.tandem_decode_step(model, state, g, ws=ws, out=out)
+
+    return call, model, state, out
+
+
+def cpu_step_estimate(torch, inputs, cfg, state, model):
+    """Oracle pieces of one step timed on sampled slices (one sequence / one layer each), extrapolated by
+    the layer, run and batch counts.  The full fp64 step is ~2 TFLOP and is not run."""
+    import numpy as np
+
+    from oracle import tandem_oracle as orc
+
+    B, g, ctx = cfg["B"], cfg["gamma"], cfg["ctx"]
+    L, S = cfg["large"], cfg["small"]
+    n = ctx - g
+    rng = np.random.default_rng(0)
+    t = {}
+    f = lambda x: inputs.torch_to_f64(x)
+    # attention: one sequence of one layer each
+    kc, vc = f(state.Khat[0][:1]), f(state.Vhat[0][:1])
+    q = rng.standard_normal((1, S["Hq"], S["dh"]))
+    kcur = rng.standard_normal((1, S["Hkv"], g, S["dh"]))
+    t0 = time.perf_counter()
+    orc.draft_attn(q, kc, vc, [n], kcur, kcur, [g], S["dh"] ** -0.5)
+    t["draft_attn_1seq"] = time.perf_counter() - t0
+    kc, vc = f(state.KL[0][:1]), f(state.VL[0][:1])
+    q = rng.standard_normal((1, g, L["Hq"], L["dh"]))
+    t0 = time.perf_counter()
+    orc.block_attn(q, kc, vc, [n], L["dh"] ** -0.5)
+    t["block_attn_1seq"] = time.perf_counter() - t0
+    del kc, vc
+
+    # dense: products of the right shape on a quarter of the output features, scaled by 4
+    def dense(rows, c):
+        per = (c["Hq"] + 2 * c["Hkv"]) * c["dh"] * c["d"] + c["d"] * c["Hq"] * c["dh"] + 2 * c["d"] * c["d_ff"]
+        nq = per // c["d"] // 4
+        Wq = rng.standard_normal((nq, c["d"]))
+        x = rng.standard_normal((rows, c["d"]))
+        t0 = time.perf_counter()
+        orc.linear(x, Wq)
+        return (time.perf_counter() - t0) * 4
+
+    t["large_layer_dense"] = dense(B * g, L)
+    t["small_layer_dense"] = dense(B, S)
+    ffW = {"W1": rng.standard_normal((cfg["d_hidden"] // 4, L["d"])), "W2": rng.standard_normal((S["d"], cfg["d_hidden"] // 4))}
+    x = rng.standard_normal((B * g, L["d"]))
+    t0 = time.perf_counter()
+    orc.project(x, ffW)
+    t["project"] = (time.perf_counter() - t0) * 4
+    Wh = rng.standard_normal((cfg["vocab"] // 4, L["d"]))
+    t0 = time.perf_counter()
+    orc.linear(x, Wh)
+    t["large_head"] = (time.perf_counter() - t0) * 4
+    est = (L["n_layers"] * (t["large_layer_dense"] + B * t["block_attn_1seq"])
+           + g * S["n_layers"] * (t["small_layer_dense"] + B * t["draft_attn_1seq"])
+           + S["n_layers"] * t["project"] + t["large_head"] * (1 + g * S["d"] / L["d"] * B / (B * g)))
+    return est, t
+
+
 WORKLOADS = {
     # name: (kind, kwargs, oracle sample sequences, description)
     "c1_draft": ("draft", dict(B=8, H=8, Hkv=8, dh=128, n_large=2044, n_cur=4, gmax=4, seed=1), 8,
@@ -167,36 +307,23 @@ WORKLOADS = {
 }
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="c1_draft", choices=sorted(WORKLOADS))
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
-        sys.exit(2)
+def _traffic(name):
+    """HBM traffic per launch measured offline with rocprofv3 counters (see profiles/), or None."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get(name)
+    except Exception:
+        return None
 
-    import torch
 
-    from paper_2402_08644_amd import binding, inputs
-
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(1)
-    binding.lib()  # fails loudly if the HIP library is not built
-    torch.cuda.set_device(0)
-
+def run_kernel_workload(torch, binding, inputs, args):
     kind, kw, n_seq, desc = WORKLOADS[args.workload]
     maker = draft_workload if kind == "draft" else block_workload
     call, n_copies, bytes_alg, oracle_sample = maker(torch, binding, inputs, **kw)
     torch.cuda.synchronize()
     ms = _time_calls(torch, call, n_copies, args.steps, args.warmup, use_graph=not args.no_graph)
     gbs = bytes_alg / (ms * 1e-3) / 1e9
-
     cpu = None
     if not args.no_cpu_baseline:
         sys.path.insert(0, os.path.join(ROOT, "tests"))
@@ -208,25 +335,101 @@ def main():
         cpu = {"value": bytes_alg * frac / dt / 1e9, "unit": "GB/s", "cores": _cpu_threads(), "kind": "oracle",
                "sample": f"{n_seq} of {kw['B']} sequences of the same call, fp64 numpy, {dt:.2f} s",
                "gpu_max_rel_err_on_sample": float(e_inf.max())}
-
-    line = {
+    return {
         "metric": "Tandem attention HBM GB/s (algorithmic KV bytes / time)",
-        "value": gbs,
-        "unit": "GB/s",
-        "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
-        "ms_per_step": ms,
-        "higher_is_better": True,
-        "scaling": "weak",
-        "vs_baseline": None,
-        "dtype": "bf16",
-        "data": "synthetic",
+        "value": gbs, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{args.workload}: {desc}", "rotated_copies": n_copies},
         "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
-                     "traffic": None},
+                     "traffic": _traffic(args.workload)},
         "cpu_baseline": cpu,
     }
+
+
+def run_step_workload(torch, binding, inputs, args):
+    cfg = C3
+    B, g, ctx = cfg["B"], cfg["gamma"], cfg["ctx"]
+    call, model, state, out = step_workload(torch, binding, inputs, cfg)
+    torch.cuda.synchronize()
+    ms = _time_calls(torch, call, 1, args.steps, args.warmup, use_graph=not args.no_graph)
+
+    # dominant kernels, timed alone in the launch configuration the step uses (same caches, one layer
+    # after the other, so every launch streams 1.07 GB that is not in the Infinity Cache)
+    L, S = cfg["large"], cfg["small"]
+    n_dev = torch.full((B,), ctx - g, dtype=torch.int32, device="cuda")
+    qL = inputs.device_normal((B, g, L["Hq"], L["dh"]), 991, 1.0)
+    oL = torch.empty_like(qL)
+    dL = binding.attn_desc(B, L["Hq"], L["Hkv"], L["dh"], ctx, 0, L["dh"] ** -0.5, binding.BF16)
+    wsL = torch.empty(max(256, binding.tandem_block_attn_workspace(dL, g)), dtype=torch.uint8, device="cuda")
+    blk = lambda i: binding.tandem_block_attn(qL, state.KL[i], state.VL[i], n_dev, out=oL, ws=wsL)
+    ms_blk = _time_calls(torch, blk, L["n_layers"], 2 * L["n_layers"], 4, use_graph=not args.no_graph)
+    qS = inputs.device_normal((B, S["Hq"], S["dh"]), 992, 1.0)
+    oS = torch.empty_like(qS)
+    nc = torch.full((B,), g, dtype=torch.int32, device="cuda")
+    dS = binding.attn_desc(B, S["Hq"], S["Hkv"], S["dh"], ctx, g, S["dh"] ** -0.5, binding.BF16)
+    wsS = torch.empty(max(256, binding.tandem_draft_attn_workspace(dS)), dtype=torch.uint8, device="cuda")
+    drf = lambda i: binding.tandem_draft_attn(qS, state.Khat[i], state.Vhat[i], n_dev, state.Kcur[i], state.Vcur[i], nc,
+                                              out=oS, ws=wsS)
+    ms_drf = _time_calls(torch, drf, S["n_layers"], 8 * S["n_layers"], 4, use_graph=not args.no_graph)
+    bytes_blk = B * L["Hkv"] * ctx * L["dh"] * 2 * 2
+    bytes_drf = B * S["Hkv"] * ctx * S["dh"] * 2 * 2
+    gbs_blk = bytes_blk / (ms_blk * 1e-3) / 1e9
+    gbs_drf = bytes_drf / (ms_drf * 1e-3) / 1e9
+    total_bytes = step_bytes(cfg)
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        est, parts = cpu_step_estimate(torch, inputs, cfg, state, model)
+        cpu = {"value": 1.0 / est, "unit": "steps/s", "cores": _cpu_threads(), "kind": "oracle",
+               "sample": "fp64 numpy oracle pieces timed on one sequence of one layer (draft and block attention) and on a "
+                         "quarter of one layer's dense products, extrapolated by layer, run and batch counts: "
+                         + ", ".join(f"{k}={v:.3f}s" for k, v in parts.items())}
+    return {
+        "metric": "Tandem decode steps/sec at gamma=4 (draft/verify attention HBM GB/s in roofline)",
+        "value": 1e3 / ms, "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "c3_step: tandem_decode_step bf16 B=32 ctx=8192 gamma=4, large 32L d=4096 32/8x128, "
+                               "small 8L d=1024 8x128, FF_Tandem 4096->8192->1024, vocab 32768",
+                   "step_algorithmic_GB": total_bytes / 1e9, "step_GBps": total_bytes / (ms * 1e-3) / 1e9,
+                   "step_frac_of_hbm_peak": total_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        "roofline": {"bound": "hbm", "kernel": "attn_block_kernel (tandem_block_attn, one large layer of the step)",
+                     "achieved": gbs_blk, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs_blk / HBM_PEAK_GBS,
+                     "ms_per_launch": ms_blk, "traffic": _traffic("c3_block")},
+        "roofline_draft": {"bound": "hbm", "kernel": "attn_rows_kernel (tandem_draft_attn, one small layer of the step)",
+                           "achieved": gbs_drf, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs_drf / HBM_PEAK_GBS,
+                           "ms_per_launch": ms_drf, "traffic": _traffic("c3_draft")},
+        "cpu_baseline": cpu,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", default="c3_step", choices=sorted(WORKLOADS) + ["c3_step"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    step = args.workload == "c3_step"
+    if args.steps is None:
+        args.steps = 20 if step else 200
+    if args.warmup is None:
+        args.warmup = 3 if step else 20
+
+    import torch
+
+    from paper_2402_08644_amd import binding, inputs
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    binding.lib()  # fails loudly if the HIP library is not built
+    torch.cuda.set_device(0)
+    line = (run_step_workload if step else run_kernel_workload)(torch, binding, inputs, args)
     print(json.dumps(line))
 
 

@@ -98,16 +98,26 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(GemmParams p) {
         acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[j], b[mt][j], acc[mt], 0, 0, 0);
   };
 
-  int c = cb + w;
-  if (c < ce) load(a0, b0, c);
-  while (c < ce) {
-    if (c + NW < ce) load(a1, b1, c + NW);
+  // Wavefront w owns chunks cb + w, cb + w + NW, ...  Workgroups start at different points of that
+  // list (rotation by block index): weight rows are a power-of-two stride apart, so workgroups that
+  // all walk K in the same order would keep hitting the same memory channel at the same time.
+  const int cnt = (ce - cb - w + NW - 1) / NW;  // chunks of this wavefront (<= 0: none)
+  const int rot = cnt > 0 ? (int)((blockIdx.x + 3 * blockIdx.y) % cnt) : 0;
+  auto chunk_of = [&](int i) {
+    int r = i + rot;
+    r = r >= cnt ? r - cnt : r;
+    return cb + w + r * NW;
+  };
+  int i = 0;
+  if (i < cnt) load(a0, b0, chunk_of(0));
+  while (i < cnt) {
+    if (i + 1 < cnt) load(a1, b1, chunk_of(i + 1));
     fma(a0, b0);
-    c += NW;
-    if (c >= ce) break;
-    if (c + NW < ce) load(a0, b0, c + NW);
+    ++i;
+    if (i >= cnt) break;
+    if (i + 1 < cnt) load(a0, b0, chunk_of(i + 1));
     fma(a1, b1);
-    c += NW;
+    ++i;
   }
 
   // tree reduction over the wavefronts (lane-local layout)
