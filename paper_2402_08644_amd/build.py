@@ -20,6 +20,7 @@ FLAGS = [
     "-fvisibility=hidden",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",
+    "-Rpass-analysis=kernel-resource-usage",
     "-I", os.path.join(ROOT, "include"),
     "-I", CSRC,
 ]
@@ -29,12 +30,28 @@ def sources():
     return sorted(f for f in os.listdir(CSRC) if f.endswith(".hip"))
 
 
+def _check_resources(src: str, remarks: str) -> None:
+    """Kernels here must live in registers: private (scratch) memory or register spills turn every
+    loop iteration into extra global-memory traffic, so a build that has them is rejected."""
+    import re
+
+    name = None
+    for line in remarks.splitlines():
+        m = re.search(r"Function Name: (\S+)", line)
+        if m:
+            name = m.group(1)
+        m = re.search(r"(ScratchSize \[bytes/lane\]|VGPRs Spill|SGPRs Spill): (\d+)", line)
+        if m and int(m.group(2)) != 0 and not (m.group(1) == "SGPRs Spill"):
+            raise RuntimeError(f"{src}: kernel {name} uses {m.group(1)} = {m.group(2)}; restructure it")
+
+
 def _compile(src: str) -> str:
     obj = os.path.join(CSRC, src[:-4] + ".o")
     cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed on {src}:\n{r.stdout}\n{r.stderr}")
+    _check_resources(src, r.stderr)
     return obj
 
 

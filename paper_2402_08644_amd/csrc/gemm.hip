@@ -21,6 +21,7 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 struct GemmParams {
   const void* X;
@@ -53,9 +54,19 @@ __device__ __forceinline__ bf16x8 ldg8(const bf16_t* p) {
 
 // ---------------------------------------------------------------- skinny bf16 MFMA kernel
 // grid (N/32, splitK, ceil(M/(32*MT))); block NW*64.  Requires N % 32 == 0, K % 64 == 0.
+//
+// Every wavefront is independent inside the main loop (no workgroup barrier).  Per 64-deep chunk it
+//   - loads its 32 weight rows straight into MFMA A-operands (each lane 64 contiguous bytes),
+//   - loads the X chunk [32*MT rows, 64] with fully coalesced 16-byte loads (8 lanes = one 128-byte
+//     row segment), parks it in a wavefront-private LDS tile (row pitch 144 B) and reads it back in
+//     the B-operand layout with conflict-free ds_read_b128.  Coalesced loads cost the vector cache a
+//     third of what operand-layout loads cost (measured), and X is read 32*MT/32 times per weight byte.
+// The loads of chunk i+1 are in flight while chunk i is multiplied.
+constexpr int XP = 72;  // LDS row pitch in bf16 elements (64 + 8 padding)
+
 template <int MT, int NW>
 __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(GemmParams p) {
-  extern __shared__ float lds[];  // [NW/2][MT][16][64]
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int c32 = lane & 31, h = lane >> 5;
   const int n0 = blockIdx.x * 32;
@@ -64,15 +75,14 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(GemmParams p) {
   const int per = (chunks + p.splitK - 1) / p.splitK;
   const int cb = blockIdx.y * per;
   const int ce = chunks < cb + per ? chunks : cb + per;
+  bf16_t* xs = reinterpret_cast<bf16_t*>(smem) + (size_t)w * (32 * MT) * XP;  // this wavefront's X tile
 
   const bf16_t* wrow = (const bf16_t*)p.W + (long long)(n0 + c32) * p.K + 32 * h;
-  const bf16_t* xrow[MT];
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt) {
-    int m = m0 + mt * 32 + c32;
-    m = m < p.M ? m : p.M - 1;  // rows past M re-read the last row; their results are dropped
-    xrow[mt] = (const bf16_t*)p.X + (long long)m * p.ldx + 32 * h;
-  }
+  // X staging: piece id = lane + 64*i -> row (lane>>3) + 8*i, 16-byte column lane&7
+  constexpr int XL = 4 * MT;  // 16-byte pieces per lane per chunk
+  const int xrow0 = lane >> 3, xcol = lane & 7;
+  const bf16_t* xbase = (const bf16_t*)p.X + xcol * 8;
+  bf16_t* xdst0 = xs + xrow0 * XP + xcol * 8;
 
   f32x16 acc[MT];
 #pragma unroll
@@ -80,48 +90,70 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(GemmParams p) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[mt][r] = 0.f;
 
-  bf16x8 a0[4], b0[MT][4], a1[4], b1[MT][4];
-  auto load = [&](bf16x8* a, bf16x8(*b)[4], int c) {
-    const long long k0 = (long long)c << 6;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) a[j] = ldg8(wrow + k0 + 8 * j);
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-      for (int j = 0; j < 4; ++j) b[mt][j] = ldg8(xrow[mt] + k0 + 8 * j);
-  };
-  auto fma = [&](const bf16x8* a, const bf16x8(*b)[4]) {
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
-        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[j], b[mt][j], acc[mt], 0, 0, 0);
-  };
-
   // Wavefront w owns chunks cb + w, cb + w + NW, ...  Workgroups start at different points of that
   // list (rotation by block index): weight rows are a power-of-two stride apart, so workgroups that
   // all walk K in the same order would keep hitting the same memory channel at the same time.
   const int cnt = (ce - cb - w + NW - 1) / NW;  // chunks of this wavefront (<= 0: none)
   const int rot = cnt > 0 ? (int)((blockIdx.x + 3 * blockIdx.y) % cnt) : 0;
-  auto chunk_of = [&](int i) {
+  auto k_of = [&](int i) __attribute__((always_inline)) -> long long {
     int r = i + rot;
     r = r >= cnt ? r - cnt : r;
-    return cb + w + r * NW;
+    return (long long)(cb + w + r * NW) << 6;
   };
-  int i = 0;
-  if (i < cnt) load(a0, b0, chunk_of(0));
-  while (i < cnt) {
-    if (i + 1 < cnt) load(a1, b1, chunk_of(i + 1));
-    fma(a0, b0);
-    ++i;
-    if (i >= cnt) break;
-    if (i + 1 < cnt) load(a0, b0, chunk_of(i + 1));
-    fma(a1, b1);
-    ++i;
+  bf16x8 a0[4], a1[4];
+  u32x4 xr[XL];
+  auto gload = [&](bf16x8* a, int i) __attribute__((always_inline)) {
+    const long long k0 = k_of(i);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) a[j] = ldg8(wrow + k0 + 8 * j);
+#pragma unroll
+    for (int q = 0; q < XL; ++q) {
+      int m = m0 + xrow0 + 8 * q;
+      m = m < p.M ? m : p.M - 1;  // rows past M re-read the last row; their results are dropped
+      xr[q] = *reinterpret_cast<const u32x4*>(xbase + (long long)m * p.ldx + k0);
+    }
+  };
+  auto xstore = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int q = 0; q < XL; ++q) *reinterpret_cast<u32x4*>(xdst0 + q * 8 * XP) = xr[q];
+  };
+  auto compute = [&](const bf16x8* a) __attribute__((always_inline)) {
+    const bf16_t* xb = xs + c32 * XP + 32 * h;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        const bf16x8 b = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(xb + mt * 32 * XP + 8 * j));
+        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[j], b, acc[mt], 0, 0, 0);
+      }
+  };
+  if (cnt > 0) {
+    gload(a0, 0);
+    int i = 0;
+    for (; i + 2 < cnt; i += 2) {  // steady state: no branch inside, both steps have a successor
+      xstore();
+      gload(a1, i + 1);
+      compute(a0);
+      xstore();
+      gload(a0, i + 2);
+      compute(a1);
+    }
+    if (cnt - i == 2) {
+      xstore();
+      gload(a1, i + 1);
+      compute(a0);
+      xstore();
+      compute(a1);
+    } else {
+      xstore();
+      compute(a0);
+    }
   }
 
-  // tree reduction over the wavefronts (lane-local layout)
-  auto slot = [&](int buf, int mt, int r) -> float& { return lds[((buf * MT + mt) * 16 + r) * 64 + lane]; };
+  // tree reduction over the wavefronts (lane-local layout) through the LDS the X tiles no longer need
+  __syncthreads();
+  float* red = reinterpret_cast<float*>(smem);
+  auto slot = [&](int buf, int mt, int r) __attribute__((always_inline)) -> float& { return red[((buf * MT + mt) * 16 + r) * 64 + lane]; };
 #pragma unroll
   for (int half = NW / 2; half >= 1; half >>= 1) {
     if (w >= half && w < 2 * half) {
@@ -166,6 +198,146 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(GemmParams p) {
   }
 }
 
+// ---------------------------------------------------------------- tile bf16 MFMA kernel (32 < M <= 128 per pass)
+// grid (N/128, splitK, ceil(M/(32*MT))); block 512 = 8 wavefronts = 4 feature groups x 2 contraction
+// groups.  A wavefront owns 32 output features and every second 64-deep chunk of the workgroup's
+// contraction range; it streams its weight rows straight from global memory into MFMA A-operands.
+// The X chunk of a contraction group is fetched once (coalesced), parked in a double-buffered LDS tile
+// and read by the group's four wavefronts in the B-operand layout: a quarter of the X loads and LDS
+// writes per MFMA of the wavefront-private scheme above, which is what the vector cache can sustain
+// when 128 rows share every weight byte.  One barrier per chunk; the loads of chunk i+1 fly while
+// chunk i is multiplied.  Requires N % 128 == 0, K % 128 == 0 and an even chunk count per split.
+template <int MT>
+__global__ __launch_bounds__(512) void gemm_tile_kernel(GemmParams p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int ng = w & 3, kg = w >> 2;
+  const int c32 = lane & 31, h = lane >> 5;
+  const int tg = threadIdx.x & 255;  // thread index inside the contraction group
+  const int n0 = blockIdx.x * 128 + ng * 32;
+  const int m0 = blockIdx.z * (32 * MT);
+  const int chunks = p.K >> 6;
+  const int per = chunks / p.splitK;  // even (launcher)
+  const int cb = blockIdx.y * per;
+  const int T = per >> 1;  // iterations: one chunk per contraction group each
+  const int rot = (int)((blockIdx.x * 5 + blockIdx.y * 3) % T);
+
+  constexpr int TILE = (32 * MT) * XP;  // elements of one X tile
+  bf16_t* xs = reinterpret_cast<bf16_t*>(smem) + (size_t)kg * 2 * TILE;  // [2][32*MT][XP]
+  const bf16_t* wrow = (const bf16_t*)p.W + (long long)(n0 + c32) * p.K + 32 * h;
+  // X staging: piece id = tg + 256*q -> row (tg>>3) + 32*q, 16-byte column tg&7
+  const int xrow0 = tg >> 3, xcol = tg & 7;
+  const bf16_t* xbase = (const bf16_t*)p.X + xcol * 8;
+  bf16_t* xdst0 = xs + xrow0 * XP + xcol * 8;
+  const bf16_t* xb0 = xs + c32 * XP + 32 * h;
+
+  f32x16 acc[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[mt][r] = 0.f;
+
+  bf16x8 a0[4], a1[4];
+  u32x4 xr[MT];
+#define TG_K_OF(i, k0)                          \
+  long long k0;                                 \
+  {                                             \
+    int r_ = (i) + rot;                         \
+    r_ = r_ >= T ? r_ - T : r_;                 \
+    k0 = (long long)(cb + 2 * r_ + kg) << 6;    \
+  }
+#define TG_GLOAD(a, i)                                                                        \
+  {                                                                                           \
+    TG_K_OF(i, k0_)                                                                           \
+    _Pragma("unroll") for (int j = 0; j < 4; ++j) a[j] = ldg8(wrow + k0_ + 8 * j);            \
+    _Pragma("unroll") for (int q = 0; q < MT; ++q) {                                          \
+      int m_ = m0 + xrow0 + 32 * q;                                                           \
+      m_ = m_ < p.M ? m_ : p.M - 1;                                                           \
+      xr[q] = *reinterpret_cast<const u32x4*>(xbase + (long long)m_ * p.ldx + k0_);           \
+    }                                                                                         \
+  }
+#define TG_XSTORE(buf)                                                                                         \
+  {                                                                                                            \
+    _Pragma("unroll") for (int q = 0; q < MT; ++q)                                                             \
+        *reinterpret_cast<u32x4*>(xdst0 + (buf) * TILE + q * 32 * XP) = xr[q];                                 \
+  }
+#define TG_COMPUTE(a, buf)                                                                                     \
+  {                                                                                                            \
+    _Pragma("unroll") for (int j = 0; j < 4; ++j) _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) {           \
+      const bf16x8 b_ =                                                                                        \
+          __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(xb0 + (buf) * TILE + mt * 32 * XP + 8 * j)); \
+      acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[j], b_, acc[mt], 0, 0, 0);                           \
+    }                                                                                                          \
+  }
+
+  TG_GLOAD(a0, 0)
+  TG_XSTORE(0)
+  __syncthreads();
+  int i = 0;
+  for (; i + 2 < T; i += 2) {  // T is even or odd; steady state has no branch inside
+    TG_GLOAD(a1, i + 1)
+    TG_COMPUTE(a0, 0)
+    TG_XSTORE(1)
+    __syncthreads();
+    TG_GLOAD(a0, i + 2)
+    TG_COMPUTE(a1, 1)
+    TG_XSTORE(0)
+    __syncthreads();
+  }
+  if (T - i == 2) {
+    TG_GLOAD(a1, i + 1)
+    TG_COMPUTE(a0, 0)
+    TG_XSTORE(1)
+    __syncthreads();
+    TG_COMPUTE(a1, 1)
+  } else {
+    TG_COMPUTE(a0, 0)
+  }
+#undef TG_K_OF
+#undef TG_GLOAD
+#undef TG_XSTORE
+#undef TG_COMPUTE
+
+  // contraction group 1 hands its sums to group 0 through LDS (lane-local layout)
+  __syncthreads();
+  float* red = reinterpret_cast<float*>(smem);
+  if (kg == 1) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) red[((ng * MT + mt) * 16 + r) * 64 + lane] = acc[mt][r];
+  }
+  __syncthreads();
+  if (kg == 1) return;
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[mt][r] += red[((ng * MT + mt) * 16 + r) * 64 + lane];
+
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+    const int m = m0 + mt * 32 + c32;
+    if (m >= p.M) continue;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int n = n0 + 8 * q + 4 * h;
+      if (p.splitK > 1) {
+        float* dst = p.part + ((long long)blockIdx.y * p.M + m) * p.N + n;
+        *reinterpret_cast<float4*>(dst) =
+            make_float4(acc[mt][4 * q], acc[mt][4 * q + 1], acc[mt][4 * q + 2], acc[mt][4 * q + 3]);
+      } else {
+        float v[4];
+#pragma unroll
+        for (int ii = 0; ii < 4; ++ii) v[ii] = epilogue<bf16_t>(acc[mt][4 * q + ii], m, n + ii, p);
+        uint2 u;
+        u.x = pack_bf16x2(v[0], v[1]);
+        u.y = pack_bf16x2(v[2], v[3]);
+        *reinterpret_cast<uint2*>((bf16_t*)p.Y + (long long)m * p.ldy + n) = u;
+      }
+    }
+  }
+}
+
 // sums the split partials in split order, then the epilogue
 template <typename T>
 __global__ void gemm_splitk_epilogue_kernel(GemmParams p) {
@@ -198,7 +370,9 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(GemmParams p) {
 
 template <int MT, int NW>
 int launch_skinny(const GemmParams& p, int mpasses, hipStream_t st) {
-  const size_t lds_bytes = (size_t)(NW / 2) * MT * 16 * 64 * sizeof(float);
+  const size_t xbytes = (size_t)NW * (32 * MT) * XP * sizeof(bf16_t);
+  const size_t rbytes = (size_t)(NW / 2) * MT * 16 * 64 * sizeof(float);
+  const size_t lds_bytes = xbytes > rbytes ? xbytes : rbytes;
   static bool attr_set = false;
   if (!attr_set && lds_bytes > 48 * 1024) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_skinny_kernel<MT, NW>),
@@ -210,16 +384,40 @@ int launch_skinny(const GemmParams& p, int mpasses, hipStream_t st) {
   return hip_ok(hipGetLastError());
 }
 
+template <int MT>
+int launch_tile(const GemmParams& p, int mpasses, hipStream_t st) {
+  const size_t xbytes = (size_t)2 * 2 * (32 * MT) * XP * sizeof(bf16_t);
+  const size_t rbytes = (size_t)4 * MT * 16 * 64 * sizeof(float);
+  const size_t lds_bytes = xbytes > rbytes ? xbytes : rbytes;
+  static bool attr_set = false;
+  if (!attr_set && lds_bytes > 48 * 1024) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_tile_kernel<MT>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
+      return TANDEM_ERR_HIP;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((gemm_tile_kernel<MT>), dim3(p.N / 128, p.splitK, mpasses), dim3(512), lds_bytes, st, p);
+  return hip_ok(hipGetLastError());
+}
+
 bool skinny_ok(int M, int N, int K, int dtype, long long ldx) {
   return dtype == TANDEM_BF16 && N % 32 == 0 && K % 64 == 0 && ldx % 8 == 0 && M >= 1;
 }
+bool tile_ok(int M, int N, int K) { return M > 32 && N % 128 == 0 && K % 128 == 0; }
 
-// split of the contraction across workgroups: only when the N tiles alone cannot fill the chip
-int skinny_splitk(int M, int N, int K) {
-  const int tiles = (N / 32) * ((M + 127) / 128);
+// Split of the contraction across workgroups (a function of the shape only): used when the feature
+// tiles alone cannot occupy the 256 CUs.
+int gemm_splitk(int M, int N, int K) {
+  const int mpasses = (M + 127) / 128;
   const int chunks = K / 64;
   int s = 1;
-  while (tiles * s < 256 && s * 2 * 8 <= chunks && s < 16) s *= 2;  // keep >= 1 chunk per wavefront
+  if (tile_ok(M, N, K)) {
+    const int tiles = (N / 128) * mpasses;
+    while (tiles * s < 200 && s < 16 && chunks % (4 * s) == 0 && chunks / (2 * s) >= 8) s *= 2;
+  } else {
+    const int tiles = (N / 32) * mpasses;
+    while (tiles * s < 200 && s * 2 * 8 <= chunks && s < 16) s *= 2;
+  }
   return s;
 }
 
@@ -227,7 +425,7 @@ int skinny_splitk(int M, int N, int K) {
 
 size_t gemm_workspace(int M, int N, int K, int dtype) {
   if (!skinny_ok(M, N, K, dtype, 8)) return 0;
-  const int s = skinny_splitk(M, N, K);
+  const int s = gemm_splitk(M, N, K);
   return s > 1 ? (size_t)s * M * N * sizeof(float) : 0;
 }
 
@@ -250,12 +448,14 @@ int launch_gemm(const GemmArgs& g, hipStream_t st) {
   p.m_base = 0;
   if (skinny_ok(g.M, g.N, g.K, g.dtype, g.ldx) && (reinterpret_cast<uintptr_t>(g.X) % 16 == 0) &&
       (reinterpret_cast<uintptr_t>(g.W) % 16 == 0) && (reinterpret_cast<uintptr_t>(g.Y) % 8 == 0) && g.ldy % 4 == 0) {
-    p.splitK = skinny_splitk(g.M, g.N, g.K);
+    p.splitK = gemm_splitk(g.M, g.N, g.K);
     if (p.splitK > 1 && (size_t)p.splitK * g.M * g.N * sizeof(float) > g.ws_bytes) return TANDEM_ERR_WORKSPACE;
     const int mt = g.M <= 32 ? 1 : (g.M <= 64 ? 2 : 4);
     const int mpasses = (g.M + 32 * mt - 1) / (32 * mt);
     int rc;
-    if (mt == 1)
+    if (tile_ok(g.M, g.N, g.K))
+      rc = mt == 2 ? launch_tile<2>(p, mpasses, st) : launch_tile<4>(p, mpasses, st);
+    else if (mt == 1)
       rc = launch_skinny<1, 8>(p, mpasses, st);
     else if (mt == 2)
       rc = launch_skinny<2, 8>(p, mpasses, st);
