@@ -200,13 +200,18 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(GemmParams p) {
 
 // ---------------------------------------------------------------- tile bf16 MFMA kernel (32 < M <= 128 per pass)
 // grid (N/128, splitK, ceil(M/(32*MT))); block 512 = 8 wavefronts = 4 feature groups x 2 contraction
-// groups.  A wavefront owns 32 output features and every second 64-deep chunk of the workgroup's
-// contraction range; it streams its weight rows straight from global memory into MFMA A-operands.
-// The X chunk of a contraction group is fetched once (coalesced), parked in a double-buffered LDS tile
-// and read by the group's four wavefronts in the B-operand layout: a quarter of the X loads and LDS
-// writes per MFMA of the wavefront-private scheme above, which is what the vector cache can sustain
-// when 128 rows share every weight byte.  One barrier per chunk; the loads of chunk i+1 fly while
-// chunk i is multiplied.  Requires N % 128 == 0, K % 128 == 0 and an even chunk count per split.
+// groups.  A wavefront owns 32 output features and every second 128-deep chunk of the workgroup's
+// contraction range; it streams its weight rows straight from global memory into MFMA A-operands
+// (each lane 128 contiguous bytes, a weight row 256 contiguous bytes per chunk: shorter runs per row
+// cap the HBM stream well below what longer ones reach).  The X chunk of a contraction group is
+// fetched once (coalesced), parked in a double-buffered LDS tile (row pitch 272 B, conflict-free
+// 16-byte reads) and read by the group's four wavefronts in the B-operand layout: a quarter of the X
+// loads and LDS writes per MFMA of the wavefront-private scheme above.  One barrier per chunk; the
+// loads of chunk i+1 fly while chunk i is multiplied.
+// Requires N % 128 == 0, K % 256 == 0 and an even chunk count per split.
+constexpr int KC = 128;      // contraction depth of a chunk
+constexpr int XPT = KC + 8;  // LDS row pitch in bf16 elements
+
 template <int MT>
 __global__ __launch_bounds__(512) void gemm_tile_kernel(GemmParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -216,20 +221,21 @@ __global__ __launch_bounds__(512) void gemm_tile_kernel(GemmParams p) {
   const int tg = threadIdx.x & 255;  // thread index inside the contraction group
   const int n0 = blockIdx.x * 128 + ng * 32;
   const int m0 = blockIdx.z * (32 * MT);
-  const int chunks = p.K >> 6;
+  const int chunks = p.K / KC;
   const int per = chunks / p.splitK;  // even (launcher)
   const int cb = blockIdx.y * per;
   const int T = per >> 1;  // iterations: one chunk per contraction group each
   const int rot = (int)((blockIdx.x * 5 + blockIdx.y * 3) % T);
 
-  constexpr int TILE = (32 * MT) * XP;  // elements of one X tile
-  bf16_t* xs = reinterpret_cast<bf16_t*>(smem) + (size_t)kg * 2 * TILE;  // [2][32*MT][XP]
-  const bf16_t* wrow = (const bf16_t*)p.W + (long long)(n0 + c32) * p.K + 32 * h;
-  // X staging: piece id = tg + 256*q -> row (tg>>3) + 32*q, 16-byte column tg&7
-  const int xrow0 = tg >> 3, xcol = tg & 7;
+  constexpr int TILE = (32 * MT) * XPT;  // elements of one X tile
+  constexpr int XL = 2 * MT;             // 16-byte pieces per thread per chunk
+  bf16_t* xs = reinterpret_cast<bf16_t*>(smem) + (size_t)kg * 2 * TILE;  // [2][32*MT][XPT]
+  const bf16_t* wrow = (const bf16_t*)p.W + (long long)(n0 + c32) * p.K + (KC / 2) * h;
+  // X staging: piece id = tg + 256*q -> row (tg>>4) + 16*q, 16-byte column tg&15
+  const int xrow0 = tg >> 4, xcol = tg & 15;
   const bf16_t* xbase = (const bf16_t*)p.X + xcol * 8;
-  bf16_t* xdst0 = xs + xrow0 * XP + xcol * 8;
-  const bf16_t* xb0 = xs + c32 * XP + 32 * h;
+  bf16_t* xdst0 = xs + xrow0 * XPT + xcol * 8;
+  const bf16_t* xb0 = xs + c32 * XPT + (KC / 2) * h;
 
   f32x16 acc[MT];
 #pragma unroll
@@ -237,64 +243,71 @@ __global__ __launch_bounds__(512) void gemm_tile_kernel(GemmParams p) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[mt][r] = 0.f;
 
-  bf16x8 a0[4], a1[4];
-  u32x4 xr[MT];
-#define TG_K_OF(i, k0)                          \
-  long long k0;                                 \
-  {                                             \
-    int r_ = (i) + rot;                         \
-    r_ = r_ >= T ? r_ - T : r_;                 \
-    k0 = (long long)(cb + 2 * r_ + kg) << 6;    \
+  bf16x8 a0[8], a1[8];
+  u32x4 xr[XL];
+#define TG_K0(i, k0_)                                             \
+  long long k0_;                                                  \
+  {                                                               \
+    int r_ = (i) < T ? (i) : T - 1; /* past the end: re-read */   \
+    r_ += rot;                                                    \
+    r_ = r_ >= T ? r_ - T : r_;                                   \
+    k0_ = (long long)(cb + 2 * r_ + kg) * KC;                     \
   }
-#define TG_GLOAD(a, i)                                                                        \
+#define TG_XLOAD(i)                                                                           \
   {                                                                                           \
-    TG_K_OF(i, k0_)                                                                           \
-    _Pragma("unroll") for (int j = 0; j < 4; ++j) a[j] = ldg8(wrow + k0_ + 8 * j);            \
-    _Pragma("unroll") for (int q = 0; q < MT; ++q) {                                          \
-      int m_ = m0 + xrow0 + 32 * q;                                                           \
+    TG_K0(i, k0_)                                                                             \
+    _Pragma("unroll") for (int q = 0; q < XL; ++q) {                                          \
+      int m_ = m0 + xrow0 + 16 * q;                                                           \
       m_ = m_ < p.M ? m_ : p.M - 1;                                                           \
       xr[q] = *reinterpret_cast<const u32x4*>(xbase + (long long)m_ * p.ldx + k0_);           \
     }                                                                                         \
+    __builtin_amdgcn_sched_barrier(0); /* keep the issue order: loads complete in order */    \
+  }
+#define TG_WLOAD(a, i)                                                                        \
+  {                                                                                           \
+    TG_K0(i, k0_)                                                                             \
+    __builtin_amdgcn_sched_barrier(0);                                                        \
+    _Pragma("unroll") for (int j = 0; j < 8; ++j) a[j] = ldg8(wrow + k0_ + 8 * j);            \
+    __builtin_amdgcn_sched_barrier(0);                                                        \
   }
 #define TG_XSTORE(buf)                                                                                         \
   {                                                                                                            \
-    _Pragma("unroll") for (int q = 0; q < MT; ++q)                                                             \
-        *reinterpret_cast<u32x4*>(xdst0 + (buf) * TILE + q * 32 * XP) = xr[q];                                 \
+    _Pragma("unroll") for (int q = 0; q < XL; ++q)                                                             \
+        *reinterpret_cast<u32x4*>(xdst0 + (buf) * TILE + q * 16 * XPT) = xr[q];                                \
   }
 #define TG_COMPUTE(a, buf)                                                                                     \
   {                                                                                                            \
-    _Pragma("unroll") for (int j = 0; j < 4; ++j) _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) {           \
-      const bf16x8 b_ =                                                                                        \
-          __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(xb0 + (buf) * TILE + mt * 32 * XP + 8 * j)); \
+    _Pragma("unroll") for (int j = 0; j < 8; ++j) _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) {           \
+      const bf16x8 b_ = __builtin_bit_cast(                                                                    \
+          bf16x8, *reinterpret_cast<const u32x4*>(xb0 + (buf) * TILE + mt * 32 * XPT + 8 * j));                \
       acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[j], b_, acc[mt], 0, 0, 0);                           \
     }                                                                                                          \
   }
 
-  TG_GLOAD(a0, 0)
+  // Software pipeline, one chunk ahead.  X is requested before the weights: loads complete in issue
+  // order, X comes from cache and is needed first (LDS store before the barrier), so the weight loads
+  // stay in flight across the barrier.
+  TG_XLOAD(0)
+  TG_WLOAD(a0, 0)
   TG_XSTORE(0)
   __syncthreads();
   int i = 0;
-  for (; i + 2 < T; i += 2) {  // T is even or odd; steady state has no branch inside
-    TG_GLOAD(a1, i + 1)
+  for (; i + 1 < T; i += 2) {  // no branch inside
+    TG_XLOAD(i + 1)
+    TG_WLOAD(a1, i + 1)
     TG_COMPUTE(a0, 0)
     TG_XSTORE(1)
     __syncthreads();
-    TG_GLOAD(a0, i + 2)
+    TG_XLOAD(i + 2)
+    TG_WLOAD(a0, i + 2)
     TG_COMPUTE(a1, 1)
     TG_XSTORE(0)
     __syncthreads();
   }
-  if (T - i == 2) {
-    TG_GLOAD(a1, i + 1)
-    TG_COMPUTE(a0, 0)
-    TG_XSTORE(1)
-    __syncthreads();
-    TG_COMPUTE(a1, 1)
-  } else {
-    TG_COMPUTE(a0, 0)
-  }
-#undef TG_K_OF
-#undef TG_GLOAD
+  if (i < T) TG_COMPUTE(a0, 0)
+#undef TG_K0
+#undef TG_XLOAD
+#undef TG_WLOAD
 #undef TG_XSTORE
 #undef TG_COMPUTE
 
@@ -386,7 +399,7 @@ int launch_skinny(const GemmParams& p, int mpasses, hipStream_t st) {
 
 template <int MT>
 int launch_tile(const GemmParams& p, int mpasses, hipStream_t st) {
-  const size_t xbytes = (size_t)2 * 2 * (32 * MT) * XP * sizeof(bf16_t);
+  const size_t xbytes = (size_t)2 * 2 * (32 * MT) * XPT * sizeof(bf16_t);
   const size_t rbytes = (size_t)4 * MT * 16 * 64 * sizeof(float);
   const size_t lds_bytes = xbytes > rbytes ? xbytes : rbytes;
   static bool attr_set = false;
@@ -403,7 +416,7 @@ int launch_tile(const GemmParams& p, int mpasses, hipStream_t st) {
 bool skinny_ok(int M, int N, int K, int dtype, long long ldx) {
   return dtype == TANDEM_BF16 && N % 32 == 0 && K % 64 == 0 && ldx % 8 == 0 && M >= 1;
 }
-bool tile_ok(int M, int N, int K) { return M > 32 && N % 128 == 0 && K % 128 == 0; }
+bool tile_ok(int M, int N, int K) { return M > 32 && N % 128 == 0 && K % (2 * KC) == 0; }
 
 // Split of the contraction across workgroups (a function of the shape only): used when the feature
 // tiles alone cannot occupy the 256 CUs.
@@ -412,8 +425,8 @@ int gemm_splitk(int M, int N, int K) {
   const int chunks = K / 64;
   int s = 1;
   if (tile_ok(M, N, K)) {
-    const int tiles = (N / 128) * mpasses;
-    while (tiles * s < 200 && s < 16 && chunks % (4 * s) == 0 && chunks / (2 * s) >= 8) s *= 2;
+    const int tiles = (N / 128) * mpasses, kc = K / KC;  // every split keeps an even number (>= 4) of chunks
+    while (tiles * s < 200 && s < 16 && kc % (4 * s) == 0 && kc / (2 * s) >= 4) s *= 2;
   } else {
     const int tiles = (N / 32) * mpasses;
     while (tiles * s < 200 && s * 2 * 8 <= chunks && s < 16) s *= 2;
