@@ -410,6 +410,9 @@ def main():
     ap.add_argument("--workload", default="c3_step", choices=sorted(WORKLOADS) + ["c3_step"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="first run three plain 1 GiB device copies (known traffic) so that rocprofv3 --pmc "
+                         "FETCH_SIZE / WRITE_SIZE readings of the same run can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -429,6 +432,13 @@ def main():
         sys.exit(1)
     binding.lib()  # fails loudly if the HIP library is not built
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")  # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     line = (run_step_workload if step else run_kernel_workload)(torch, binding, inputs, args)
     print(json.dumps(line))
 

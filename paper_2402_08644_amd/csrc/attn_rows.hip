@@ -223,12 +223,12 @@ int launch_rows_g(int G, const RowsParams& p, dim3 grid, hipStream_t st) {
 
 }  // namespace
 
-// Splits: enough workgroups to put >= 8 wavefronts on every one of the 256 CUs, but at least
-// 256 keys per split so the per-split epilogue stays small.  A function of shapes only.
+// Context splits: a function of shapes only.  Measured on MI355X: about 512 workgroups in total (two
+// per CU) stream best; more splits only add partials and tail effects.  At least 256 keys per split.
 int attn_rows_splits(int B, int Hkv, int q_len, int64_t T_max, int gamma_max) {
   const int64_t groups = (int64_t)B * Hkv * q_len;
   const int64_t keys = T_max + gamma_max;
-  int64_t want = (2048 + groups - 1) / groups;
+  int64_t want = (512 + groups - 1) / groups;
   int64_t cap = keys / 256;
   if (cap < 1) cap = 1;
   int64_t S = want < cap ? want : cap;
