@@ -54,6 +54,25 @@ int gemm(const void* X, int64_t ldx, const void* W, const void* bias, const void
   g.dtype = dtype;
   g.ws = (float*)ws;
   g.ws_bytes = ws_bytes;
+  g.defer = 0;
+  return launch_gemm(g, st);
+}
+
+// X . W^T left as fp32 partial sums in ws (see GemmArgs::defer)
+int gemm_deferred(const void* X, int64_t ldx, const void* W, int M, int N, int K, int dtype, void* ws, size_t ws_bytes,
+                  hipStream_t st) {
+  GemmArgs g{};
+  g.X = X;
+  g.ldx = ldx;
+  g.W = W;
+  g.M = M;
+  g.N = N;
+  g.K = K;
+  g.act = TANDEM_ACT_NONE;
+  g.dtype = dtype;
+  g.ws = (float*)ws;
+  g.ws_bytes = ws_bytes;
+  g.defer = 1;
   return launch_gemm(g, st);
 }
 
@@ -103,6 +122,7 @@ struct StepPlan {
   size_t x, xn, qkv, q, att, h, logits, yhat, kv, keep, ints, attn_ws, gemm_ws, total;
   size_t attn_ws_bytes, gemm_ws_bytes, keep_stride;
   int32_t n_keep;
+  bool fused;  // bf16 path with deferred GEMM epilogues finished by fused row kernels
 };
 
 StepPlan make_plan(const tandem_model* m, int B, int gamma, int64_t T_max, int gamma_max) {
@@ -112,7 +132,8 @@ StepPlan make_plan(const tandem_model* m, int B, int gamma, int64_t T_max, int g
   const size_t dmax = maxz(L.d, S.d);
   const size_t qkvmax = maxz((size_t)(L.Hq + 2 * L.Hkv) * L.dh, (size_t)(S.Hq + 2 * S.Hkv) * S.dh);
   const size_t qmax = maxz((size_t)L.Hq * L.dh, (size_t)S.Hq * S.dh);
-  const size_t ffmax = maxz(L.d_ff, S.d_ff);
+  size_t ffmax = maxz(L.d_ff, S.d_ff);
+  for (int j = 0; j < S.n_layers; ++j) ffmax = maxz(ffmax, (size_t)m->ff[j].d_hidden);
   const size_t vmax = maxz(L.vocab, S.vocab);
   StepPlan p{};
   size_t off = 0;
@@ -160,6 +181,25 @@ StepPlan make_plan(const tandem_model* m, int B, int gamma, int64_t T_max, int g
     need_decoder(S, (size_t)B);
     need_decoder(L, M);
     need(M, 2 * S.Hkv * S.dh, S.d);
+    // deferred epilogues: every product of the step must be able to leave partials
+    p.fused = dt == TANDEM_BF16 && L.d % 4 == 0 && S.d % 4 == 0 && L.dh % 4 == 0 && S.dh % 4 == 0;
+    auto dneed = [&](size_t rows, int N, int K) {
+      if (!gemm_can_defer((int)rows, N, K, dt, K)) p.fused = false;
+      else g = maxz(g, gemm_deferred_workspace((int)rows, N, K));
+    };
+    auto dneed_decoder = [&](const tandem_decoder_desc& D, size_t rows) {
+      dneed(rows, (D.Hq + 2 * D.Hkv) * D.dh, D.d);
+      dneed(rows, D.d, D.Hq * D.dh);
+      dneed(rows, D.d, D.d_ff);
+    };
+    dneed_decoder(S, (size_t)B);
+    dneed_decoder(L, M);
+    dneed(M, 2 * S.Hkv * S.dh, S.d);
+    for (int j = 0; j < S.n_layers; ++j) {
+      const tandem_ff_desc& f = m->ff[j];
+      if (f.d_hidden > 0) dneed(M, f.d_S, f.d_hidden);
+      else dneed(M, f.d_S, f.d_L);
+    }
     size_t pj = 0;
     for (int j = 0; j < S.n_layers; ++j) pj = maxz(pj, project_ws(&m->ff[j], (int64_t)M));
     p.gemm_ws_bytes = maxz(align256(g), pj);
@@ -237,6 +277,37 @@ int decoder_layer(const Ctx& c, const tandem_decoder_desc& D, const tandem_layer
   TRY(gemm(h, D.d_ff, w.W2, w.b2, x, D.d, x, D.d, rows, D.d, D.d_ff, TANDEM_ACT_NONE, c.dtype, gws, c.plan.gemm_ws_bytes,
            c.stream));
   return TANDEM_OK;
+}
+
+// Fused form of one decoder layer (bf16): the QKV, O and second MLP products leave fp32 partials that row
+// kernels finish together with what follows them (cache scatter; residual + next RMSNorm), so a layer is
+// 10 launches instead of 13.  On entry c.xn holds RMSNorm(x; w.g_attn); on exit RMSNorm(x'; g_next).
+template <typename ScatterFn, typename AttnFn>
+int decoder_layer_fused(const Ctx& c, const tandem_decoder_desc& D, const tandem_layer_weights& w, int rows,
+                        const void* g_next, ScatterFn finish_qkv, AttnFn attn) {
+  void *x = c.at<>(c.plan.x), *xn = c.at<>(c.plan.xn), *att = c.at<>(c.plan.att), *h = c.at<>(c.plan.h);
+  float* gws = c.at<float>(c.plan.gemm_ws);
+  const size_t gwb = c.plan.gemm_ws_bytes;
+  const int nqkv = (D.Hq + 2 * D.Hkv) * D.dh, nq = D.Hq * D.dh;
+  TRY(gemm_deferred(xn, D.d, w.Wqkv, rows, nqkv, D.d, c.dtype, gws, gwb, c.stream));
+  TRY(finish_qkv(gws, gemm_splits(rows, nqkv, D.d)));
+  TRY(attn());
+  TRY(gemm_deferred(att, nq, w.Wo, rows, D.d, nq, c.dtype, gws, gwb, c.stream));
+  TRY(launch_finish_norm(gws, gemm_splits(rows, D.d, nq), nullptr, x, x, w.g_mlp, xn, rows, D.d, c.eps, c.dtype,
+                         c.stream));
+  TRY(gemm(xn, D.d, w.W1, w.b1, nullptr, 0, h, D.d_ff, rows, D.d_ff, D.d, TANDEM_ACT_GELU, c.dtype, gws, gwb, c.stream));
+  TRY(gemm_deferred(h, D.d_ff, w.W2, rows, D.d, D.d_ff, c.dtype, gws, gwb, c.stream));
+  TRY(launch_finish_norm(gws, gemm_splits(rows, D.d, D.d_ff), w.b2, x, x, g_next, xn, rows, D.d, c.eps, c.dtype,
+                         c.stream));
+  return TANDEM_OK;
+}
+
+// logits and greedy token when c.xn already holds RMSNorm(x; g_final)
+int head_normed(const Ctx& c, const tandem_decoder_desc& D, int rows, int32_t* tok_out, int64_t tok_stride) {
+  void *xn = c.at<>(c.plan.xn), *lg = c.at<>(c.plan.logits);
+  TRY(gemm(xn, D.d, D.W_out, nullptr, nullptr, 0, lg, D.vocab, rows, D.vocab, D.d, TANDEM_ACT_NONE, c.dtype,
+           c.at<>(c.plan.gemm_ws), c.plan.gemm_ws_bytes, c.stream));
+  return launch_argmax(lg, rows, D.vocab, tok_out, tok_stride, c.dtype, c.stream);
 }
 
 int head(const Ctx& c, const tandem_decoder_desc& D, int rows, int32_t* tok_out, int64_t tok_stride) {
@@ -361,18 +432,31 @@ int tandem_decode_step(const tandem_model* m, const tandem_state_desc* state, in
       stride = gamma;
     }
     TRY(launch_embed(S.emb, toks, stride, x, B, S.d, S.vocab, c.dtype, c.stream));
+    if (c.plan.fused) TRY(launch_rmsnorm(x, S.layers[0].g_attn, c.at<>(c.plan.xn), B, S.d, c.eps, c.dtype, c.stream));
     for (int j = 0; j < S.n_layers; ++j) {
-      auto attn = [&]() -> int {
-        TRY(launch_scatter_qkv(qkv, q, state->Kcur[j], state->Vcur[j], nullptr, r, B, 1, S.Hq, S.Hkv, S.dh,
-                               state->gamma_max, 0, S.Hq * S.dh, (S.Hq + 2 * S.Hkv) * S.dh, c.dtype, c.stream));
+      auto attn_only = [&]() -> int {
         return attn_call(c, S, q, state->Khat[j], state->Vhat[j], state->n, state->Kcur[j], state->Vcur[j],
                          ncur + (size_t)r * B, 0, 1, att);
       };
-      TRY(decoder_layer(c, S, S.layers[j], B, attn));
+      if (c.plan.fused) {
+        auto finish_qkv = [&](const float* part, int splits) -> int {
+          return launch_finish_scatter(part, splits, q, state->Kcur[j], state->Vcur[j], nullptr, r, B, 1, S.Hq, S.Hkv,
+                                       S.dh, state->gamma_max, S.Hq * S.dh, (S.Hq + 2 * S.Hkv) * S.dh, c.dtype, c.stream);
+        };
+        const void* g_next = j + 1 < S.n_layers ? S.layers[j + 1].g_attn : S.g_final;
+        TRY(decoder_layer_fused(c, S, S.layers[j], B, g_next, finish_qkv, attn_only));
+      } else {
+        auto attn = [&]() -> int {
+          TRY(launch_scatter_qkv(qkv, q, state->Kcur[j], state->Vcur[j], nullptr, r, B, 1, S.Hq, S.Hkv, S.dh,
+                                 state->gamma_max, 0, S.Hq * S.dh, (S.Hq + 2 * S.Hkv) * S.dh, c.dtype, c.stream));
+          return attn_only();
+        };
+        TRY(decoder_layer(c, S, S.layers[j], B, attn));
+      }
     }
     if (aux && aux->y_small)
       TRY(copy2d((char*)aux->y_small + (size_t)r * S.d * es, (size_t)gamma * S.d * es, x, S.d * es, S.d * es, B, c.stream));
-    TRY(head(c, S, B, draft + r, gamma));
+    TRY(c.plan.fused ? head_normed(c, S, B, draft + r, gamma) : head(c, S, B, draft + r, gamma));
     if (aux && aux->logits_S)
       TRY(copy2d((char*)aux->logits_S + (size_t)r * S.vocab * es, (size_t)gamma * S.vocab * es, c.at<>(c.plan.logits),
                  S.vocab * es, S.vocab * es, B, c.stream));
@@ -389,18 +473,31 @@ int tandem_decode_step(const tandem_model* m, const tandem_state_desc* state, in
     return TANDEM_OK;
   };
   TRY(keep(0));
+  if (c.plan.fused) TRY(launch_rmsnorm(x, L.layers[0].g_attn, c.at<>(c.plan.xn), M, L.d, c.eps, c.dtype, c.stream));
   for (int j = 0; j < L.n_layers; ++j) {
-    auto attn = [&]() -> int {
-      TRY(launch_scatter_qkv(qkv, q, state->KL[j], state->VL[j], state->n, 0, M, gamma, L.Hq, L.Hkv, L.dh, state->T_max,
-                             0, L.Hq * L.dh, (L.Hq + 2 * L.Hkv) * L.dh, c.dtype, c.stream));
+    auto attn_only = [&]() -> int {
       return attn_call(c, L, q, state->KL[j], state->VL[j], state->n, nullptr, nullptr, nullptr, 1, gamma, att);
     };
-    TRY(decoder_layer(c, L, L.layers[j], M, attn));
+    if (c.plan.fused) {
+      auto finish_qkv = [&](const float* part, int splits) -> int {
+        return launch_finish_scatter(part, splits, q, state->KL[j], state->VL[j], state->n, 0, M, gamma, L.Hq, L.Hkv,
+                                     L.dh, state->T_max, L.Hq * L.dh, (L.Hq + 2 * L.Hkv) * L.dh, c.dtype, c.stream);
+      };
+      const void* g_next = j + 1 < L.n_layers ? L.layers[j + 1].g_attn : L.g_final;
+      TRY(decoder_layer_fused(c, L, L.layers[j], M, g_next, finish_qkv, attn_only));
+    } else {
+      auto attn = [&]() -> int {
+        TRY(launch_scatter_qkv(qkv, q, state->KL[j], state->VL[j], state->n, 0, M, gamma, L.Hq, L.Hkv, L.dh,
+                               state->T_max, 0, L.Hq * L.dh, (L.Hq + 2 * L.Hkv) * L.dh, c.dtype, c.stream));
+        return attn_only();
+      };
+      TRY(decoder_layer(c, L, L.layers[j], M, attn));
+    }
     TRY(keep(j + 1));
   }
   if (aux && aux->x_large)
     TRY(hip_ok(hipMemcpyAsync(aux->x_large, x, (size_t)M * L.d * es, hipMemcpyDeviceToDevice, c.stream)));
-  TRY(head(c, L, M, verify, 1));
+  TRY(c.plan.fused ? head_normed(c, L, M, verify, 1) : head(c, L, M, verify, 1));
   if (aux && aux->logits_L)
     TRY(hip_ok(hipMemcpyAsync(aux->logits_L, c.at<>(c.plan.logits), (size_t)M * L.vocab * es, hipMemcpyDeviceToDevice,
                               c.stream)));
@@ -408,14 +505,35 @@ int tandem_decode_step(const tandem_model* m, const tandem_state_desc* state, in
   // ---- 3. FF_Tandem on the new rows, then the small layer's norm and W_K / W_V ---------
   for (int j = 0; j < S.n_layers; ++j) {
     void *yhat = c.at<>(c.plan.yhat), *xn = c.at<>(c.plan.xn), *kv = c.at<>(c.plan.kv), *gws = c.at<>(c.plan.gemm_ws);
-    TRY(run_project(&m->ff[j], c.ws + c.plan.keep + j * c.plan.keep_stride, yhat, M, gws, c.plan.gemm_ws_bytes, c.stream));
-    TRY(launch_rmsnorm(yhat, S.layers[j].g_attn, xn, M, S.d, c.eps, c.dtype, c.stream));
+    const void* xk = c.ws + c.plan.keep + j * c.plan.keep_stride;
     const void* Wkv = (const char*)S.layers[j].Wqkv + (size_t)S.Hq * S.dh * S.d * es;
     const int nkv = 2 * S.Hkv * S.dh;
-    TRY(gemm(xn, S.d, Wkv, nullptr, nullptr, 0, kv, nkv, M, nkv, S.d, TANDEM_ACT_NONE, c.dtype, gws, c.plan.gemm_ws_bytes,
-             c.stream));
-    TRY(launch_scatter_qkv(kv, nullptr, state->Khat[j], state->Vhat[j], state->n, 0, M, gamma, S.Hq, S.Hkv, S.dh,
-                           state->T_max, 0, 0, nkv, c.dtype, c.stream));
+    if (c.plan.fused) {
+      const tandem_ff_desc& f = m->ff[j];
+      float* part = (float*)gws;
+      if (f.d_hidden > 0) {
+        void* hb = c.at<>(c.plan.h);
+        TRY(gemm(xk, f.d_L, f.W1, f.b1, nullptr, 0, hb, f.d_hidden, M, f.d_hidden, f.d_L, f.act, c.dtype, gws,
+                 c.plan.gemm_ws_bytes, c.stream));
+        TRY(gemm_deferred(hb, f.d_hidden, f.W2, M, f.d_S, f.d_hidden, c.dtype, gws, c.plan.gemm_ws_bytes, c.stream));
+        TRY(launch_finish_norm(part, gemm_splits(M, f.d_S, f.d_hidden), f.b2, nullptr, yhat, S.layers[j].g_attn, xn, M,
+                               S.d, c.eps, c.dtype, c.stream));
+      } else {
+        TRY(gemm_deferred(xk, f.d_L, f.W1, M, f.d_S, f.d_L, c.dtype, gws, c.plan.gemm_ws_bytes, c.stream));
+        TRY(launch_finish_norm(part, gemm_splits(M, f.d_S, f.d_L), f.b1, nullptr, yhat, S.layers[j].g_attn, xn, M, S.d,
+                               c.eps, c.dtype, c.stream));
+      }
+      TRY(gemm_deferred(xn, S.d, Wkv, M, nkv, S.d, c.dtype, gws, c.plan.gemm_ws_bytes, c.stream));
+      TRY(launch_finish_scatter(part, gemm_splits(M, nkv, S.d), nullptr, state->Khat[j], state->Vhat[j], state->n, 0, M,
+                                gamma, S.Hq, S.Hkv, S.dh, state->T_max, 0, nkv, c.dtype, c.stream));
+    } else {
+      TRY(run_project(&m->ff[j], xk, yhat, M, gws, c.plan.gemm_ws_bytes, c.stream));
+      TRY(launch_rmsnorm(yhat, S.layers[j].g_attn, xn, M, S.d, c.eps, c.dtype, c.stream));
+      TRY(gemm(xn, S.d, Wkv, nullptr, nullptr, 0, kv, nkv, M, nkv, S.d, TANDEM_ACT_NONE, c.dtype, gws,
+               c.plan.gemm_ws_bytes, c.stream));
+      TRY(launch_scatter_qkv(kv, nullptr, state->Khat[j], state->Vhat[j], state->n, 0, M, gamma, S.Hq, S.Hkv, S.dh,
+                             state->T_max, 0, 0, nkv, c.dtype, c.stream));
+    }
   }
 
   // ---- 4. accept ------------------------------------------------------------------------

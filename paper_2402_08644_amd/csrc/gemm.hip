@@ -31,7 +31,7 @@ struct GemmParams {
   void* Y;
   float* part;  // [splitK, M, N] fp32 partial sums
   long long ldx, ldr, ldy;
-  int M, N, K, act, splitK, m_base;
+  int M, N, K, act, splitK, m_base, defer;
 };
 
 __device__ __forceinline__ float apply_act(float v, int act) {
@@ -181,7 +181,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(GemmParams p) {
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       const int n = n0 + 8 * q + 4 * h;
-      if (p.splitK > 1) {
+      if (p.splitK > 1 || p.defer) {
         float* dst = p.part + ((long long)blockIdx.y * p.M + m) * p.N + n;
         *reinterpret_cast<float4*>(dst) =
             make_float4(acc[mt][4 * q], acc[mt][4 * q + 1], acc[mt][4 * q + 2], acc[mt][4 * q + 3]);
@@ -334,7 +334,7 @@ __global__ __launch_bounds__(512) void gemm_tile_kernel(GemmParams p) {
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       const int n = n0 + 8 * q + 4 * h;
-      if (p.splitK > 1) {
+      if (p.splitK > 1 || p.defer) {
         float* dst = p.part + ((long long)blockIdx.y * p.M + m) * p.N + n;
         *reinterpret_cast<float4*>(dst) =
             make_float4(acc[mt][4 * q], acc[mt][4 * q + 1], acc[mt][4 * q + 2], acc[mt][4 * q + 3]);
@@ -436,6 +436,10 @@ int gemm_splitk(int M, int N, int K) {
 
 }  // namespace
 
+bool gemm_can_defer(int M, int N, int K, int dtype, int64_t ldx) { return skinny_ok(M, N, K, dtype, ldx); }
+int gemm_splits(int M, int N, int K) { return gemm_splitk(M, N, K); }
+size_t gemm_deferred_workspace(int M, int N, int K) { return (size_t)gemm_splitk(M, N, K) * M * N * sizeof(float); }
+
 size_t gemm_workspace(int M, int N, int K, int dtype) {
   if (!skinny_ok(M, N, K, dtype, 8)) return 0;
   const int s = gemm_splitk(M, N, K);
@@ -459,10 +463,11 @@ int launch_gemm(const GemmArgs& g, hipStream_t st) {
   p.act = g.act;
   p.splitK = 1;
   p.m_base = 0;
+  p.defer = g.defer;
   if (skinny_ok(g.M, g.N, g.K, g.dtype, g.ldx) && (reinterpret_cast<uintptr_t>(g.X) % 16 == 0) &&
       (reinterpret_cast<uintptr_t>(g.W) % 16 == 0) && (reinterpret_cast<uintptr_t>(g.Y) % 8 == 0) && g.ldy % 4 == 0) {
     p.splitK = gemm_splitk(g.M, g.N, g.K);
-    if (p.splitK > 1 && (size_t)p.splitK * g.M * g.N * sizeof(float) > g.ws_bytes) return TANDEM_ERR_WORKSPACE;
+    if ((p.splitK > 1 || g.defer) && (size_t)p.splitK * g.M * g.N * sizeof(float) > g.ws_bytes) return TANDEM_ERR_WORKSPACE;
     const int mt = g.M <= 32 ? 1 : (g.M <= 64 ? 2 : 4);
     const int mpasses = (g.M + 32 * mt - 1) / (32 * mt);
     int rc;
@@ -474,11 +479,12 @@ int launch_gemm(const GemmArgs& g, hipStream_t st) {
       rc = launch_skinny<2, 8>(p, mpasses, st);
     else
       rc = launch_skinny<4, 8>(p, mpasses, st);
-    if (rc != TANDEM_OK || p.splitK == 1) return rc;
+    if (rc != TANDEM_OK || p.splitK == 1 || g.defer) return rc;
     const long long total = (long long)g.M * g.N;
     hipLaunchKernelGGL(gemm_splitk_epilogue_kernel<bf16_t>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, p);
     return hip_ok(hipGetLastError());
   }
+  if (g.defer) return TANDEM_ERR_UNSUPPORTED;
   dim3 grid((g.N + 15) / 16, (g.M + 15) / 16);
   if (g.dtype == TANDEM_BF16)
     hipLaunchKernelGGL(gemm_generic_kernel<bf16_t>, grid, dim3(256), 0, st, p);

@@ -6,6 +6,9 @@
 int launch_scatter_qkv(const void* qkv, void* q, void* kc, void* vc, const int32_t* base, int fixed, int rows, int q_len,
                        int Hq, int Hkv, int dh, int64_t cap, int q_off_cols, int kv_off_cols, int row_cols, int dtype,
                        hipStream_t st);
+int launch_finish_scatter(const float* part, int splits, void* q, void* kc, void* vc, const int32_t* base, int fixed,
+                          int rows, int q_len, int Hq, int Hkv, int dh, int64_t cap, int q_cols, int row_cols, int dtype,
+                          hipStream_t st);
 int launch_argmax(const void* logits, int rows, int vocab, int32_t* out, int64_t out_stride, int dtype, hipStream_t st);
 int launch_prepare_step(const int32_t* pending, int32_t* ncur, int B, int gamma, hipStream_t st);
 int launch_block_tokens(const int32_t* pending, const int32_t* follow, int32_t* block_tokens, int B, int gamma,

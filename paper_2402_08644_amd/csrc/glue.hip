@@ -100,6 +100,115 @@ __global__ __launch_bounds__(256) void argmax_kernel(const T* __restrict__ logit
   }
 }
 
+// Finishes a deferred GEMM for one row per workgroup: v = sum_s part[s][row][:] (+ bias) (+ residual);
+// x_out = v (storage dtype); if g: xn_out = v / sqrt(mean(v^2) + eps) * g.  Partials are summed in split
+// order.  Two passes over the (cache-resident) partials instead of a register copy of the row.
+template <typename T>
+__global__ __launch_bounds__(256) void finish_norm_kernel(const float* __restrict__ part, int splits, long long MN,
+                                                          const T* __restrict__ bias, const T* residual, T* x_out,
+                                                          const T* __restrict__ g, T* __restrict__ xn_out, int d,
+                                                          float eps) {
+  __shared__ float red[4];
+  const long long row = blockIdx.x;
+  const float* pr = part + row * d;
+  auto value4 = [&](int c) __attribute__((always_inline)) {
+    float4 v = *reinterpret_cast<const float4*>(pr + c);
+    for (int s = 1; s < splits; ++s) {
+      const float4 t = *reinterpret_cast<const float4*>(pr + s * MN + c);
+      v.x += t.x;
+      v.y += t.y;
+      v.z += t.z;
+      v.w += t.w;
+    }
+    if (bias) {
+      v.x += to_f32<T>(bias[c]);
+      v.y += to_f32<T>(bias[c + 1]);
+      v.z += to_f32<T>(bias[c + 2]);
+      v.w += to_f32<T>(bias[c + 3]);
+    }
+    if (residual) {
+      const T* rr = residual + row * d + c;
+      v.x += to_f32<T>(rr[0]);
+      v.y += to_f32<T>(rr[1]);
+      v.z += to_f32<T>(rr[2]);
+      v.w += to_f32<T>(rr[3]);
+    }
+    return v;
+  };
+  float inv = 0.f;
+  if (g) {
+    float ss = 0.f;
+    for (int c = threadIdx.x * 4; c < d; c += 1024) {
+      const float4 v = value4(c);
+      ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+    }
+    for (int off = 32; off >= 1; off >>= 1) ss += __shfl_xor(ss, off);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    inv = 1.0f / sqrtf((red[0] + red[1] + red[2] + red[3]) / (float)d + eps);
+  }
+  // the residual row is read again below before x_out (which may alias it) is written: each thread only
+  // rewrites the four elements it has just read
+  for (int c = threadIdx.x * 4; c < d; c += 1024) {
+    const float4 v = value4(c);
+    T* xo = x_out + row * d + c;
+    xo[0] = from_f32<T>(v.x);
+    xo[1] = from_f32<T>(v.y);
+    xo[2] = from_f32<T>(v.z);
+    xo[3] = from_f32<T>(v.w);
+    if (g) {
+      T* xn = xn_out + row * d + c;
+      xn[0] = from_f32<T>(v.x * inv * to_f32<T>(g[c]));
+      xn[1] = from_f32<T>(v.y * inv * to_f32<T>(g[c + 1]));
+      xn[2] = from_f32<T>(v.z * inv * to_f32<T>(g[c + 2]));
+      xn[3] = from_f32<T>(v.w * inv * to_f32<T>(g[c + 3]));
+    }
+  }
+}
+
+// Finishes a deferred QKV (or KV) GEMM: sums the partials of one row and writes the query part to the
+// contiguous q buffer and the key / value parts into the cache rows (same addressing as scatter_qkv_kernel).
+template <typename T>
+__global__ __launch_bounds__(256) void finish_scatter_kernel(const float* __restrict__ part, int splits, long long MN,
+                                                             T* __restrict__ q, T* __restrict__ kc, T* __restrict__ vc,
+                                                             const int32_t* __restrict__ base, int fixed, int q_len,
+                                                             int Hq, int Hkv, int dh, long long cap, int q_cols,
+                                                             int row_cols) {
+  const int row = blockIdx.x;
+  const int b = row / q_len, r = row % q_len;
+  const float* pr = part + (long long)row * row_cols;
+  const long long pos = (base ? base[b] : 0) + fixed + r;
+  const bool pos_ok = pos >= 0 && pos < cap;  // never write outside the cache
+  for (int c = threadIdx.x * 4; c < row_cols; c += 1024) {
+    float4 v = *reinterpret_cast<const float4*>(pr + c);
+    for (int s = 1; s < splits; ++s) {
+      const float4 t = *reinterpret_cast<const float4*>(pr + s * MN + c);
+      v.x += t.x;
+      v.y += t.y;
+      v.z += t.z;
+      v.w += t.w;
+    }
+    T* dst;
+    if (c < q_cols) {
+      dst = q + (long long)row * q_cols + c;
+    } else {
+      if (!pos_ok) continue;
+      int i = c - q_cols;
+      T* cache = kc;
+      if (i >= Hkv * dh) {
+        i -= Hkv * dh;
+        cache = vc;
+      }
+      const int kvh = i / dh, e = i % dh;
+      dst = cache + (((long long)b * Hkv + kvh) * cap + pos) * dh + e;
+    }
+    dst[0] = from_f32<T>(v.x);
+    dst[1] = from_f32<T>(v.y);
+    dst[2] = from_f32<T>(v.z);
+    dst[3] = from_f32<T>(v.w);
+  }
+}
+
 // block_tokens[b, 0] = pending[b]; block_tokens[b, r] = (forced ? forced : draft)[b, r-1];  ncur[r][b] = r + 1
 __global__ void prepare_step_kernel(const int32_t* pending, int32_t* ncur, int B, int gamma) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -159,6 +268,33 @@ int launch_rmsnorm(const void* x, const void* g, void* y, int rows, int d, float
   else
     hipLaunchKernelGGL(rmsnorm_kernel<float>, dim3(rows), dim3(256), 0, st, (const float*)x, (const float*)g, (float*)y,
                        d, eps);
+  return hip_ok(hipGetLastError());
+}
+
+int launch_finish_norm(const float* part, int splits, const void* bias, const void* residual, void* x_out,
+                       const void* g, void* xn_out, int rows, int d, float eps, int dtype, hipStream_t st) {
+  if (d % 4 != 0) return TANDEM_ERR_UNSUPPORTED;
+  const long long MN = (long long)rows * d;
+  if (dtype == TANDEM_BF16)
+    hipLaunchKernelGGL(finish_norm_kernel<bf16_t>, dim3(rows), dim3(256), 0, st, part, splits, MN, (const bf16_t*)bias,
+                       (const bf16_t*)residual, (bf16_t*)x_out, (const bf16_t*)g, (bf16_t*)xn_out, d, eps);
+  else
+    hipLaunchKernelGGL(finish_norm_kernel<float>, dim3(rows), dim3(256), 0, st, part, splits, MN, (const float*)bias,
+                       (const float*)residual, (float*)x_out, (const float*)g, (float*)xn_out, d, eps);
+  return hip_ok(hipGetLastError());
+}
+
+int launch_finish_scatter(const float* part, int splits, void* q, void* kc, void* vc, const int32_t* base, int fixed,
+                          int rows, int q_len, int Hq, int Hkv, int dh, int64_t cap, int q_cols, int row_cols, int dtype,
+                          hipStream_t st) {
+  if (row_cols % 4 != 0 || q_cols % 4 != 0 || dh % 4 != 0) return TANDEM_ERR_UNSUPPORTED;
+  const long long MN = (long long)rows * row_cols;
+  if (dtype == TANDEM_BF16)
+    hipLaunchKernelGGL(finish_scatter_kernel<bf16_t>, dim3(rows), dim3(256), 0, st, part, splits, MN, (bf16_t*)q,
+                       (bf16_t*)kc, (bf16_t*)vc, base, fixed, q_len, Hq, Hkv, dh, (long long)cap, q_cols, row_cols);
+  else
+    hipLaunchKernelGGL(finish_scatter_kernel<float>, dim3(rows), dim3(256), 0, st, part, splits, MN, (float*)q,
+                       (float*)kc, (float*)vc, base, fixed, q_len, Hq, Hkv, dh, (long long)cap, q_cols, row_cols);
   return hip_ok(hipGetLastError());
 }
 

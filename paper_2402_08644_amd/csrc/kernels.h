@@ -56,11 +56,20 @@ struct GemmArgs {
   int dtype;  // tandem_dtype of X, W, bias, residual, Y
   float* ws;  // split-K partials
   size_t ws_bytes;
+  int defer;  // 1: leave fp32 partial sums [splits, M, N] in ws and skip the epilogue (bf16 MFMA path only);
+              //    a fused consumer kernel finishes the layer.  bias / act / residual / Y are then ignored.
 };
 size_t gemm_workspace(int M, int N, int K, int dtype);
+bool gemm_can_defer(int M, int N, int K, int dtype, int64_t ldx);  // deferred epilogue available for this shape
+size_t gemm_deferred_workspace(int M, int N, int K);
+int gemm_splits(int M, int N, int K);  // number of partials a deferred launch leaves
 int launch_gemm(const GemmArgs& g, hipStream_t st);
 
 // ---------------------------------------------------------------- glue (glue.hip)
 int launch_rmsnorm(const void* x, const void* g, void* y, int rows, int d, float eps, int dtype, hipStream_t st);
+// finishes a deferred GEMM row by row: v = sum of partials (+ bias) (+ residual); x_out = v; and, when g is
+// given, xn_out = RMSNorm(v; g).  residual may alias x_out.
+int launch_finish_norm(const float* part, int splits, const void* bias, const void* residual, void* x_out,
+                       const void* g, void* xn_out, int rows, int d, float eps, int dtype, hipStream_t st);
 int launch_embed(const void* emb, const int32_t* tokens, int64_t tok_stride, void* x, int rows, int d, int vocab,
                  int dtype, hipStream_t st);
