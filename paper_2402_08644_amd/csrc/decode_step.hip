@@ -182,7 +182,7 @@ StepPlan make_plan(const tandem_model* m, int B, int gamma, int64_t T_max, int g
     need_decoder(L, M);
     need(M, 2 * S.Hkv * S.dh, S.d);
     // deferred epilogues: every product of the step must be able to leave partials
-    p.fused = dt == TANDEM_BF16 && L.d % 4 == 0 && S.d % 4 == 0 && L.dh % 4 == 0 && S.dh % 4 == 0;
+    p.fused = dt == TANDEM_BF16 && L.d % 4 == 0 && S.d % 4 == 0 && L.d <= 16384 && S.d <= 16384;
     auto dneed = [&](size_t rows, int N, int K) {
       if (!gemm_can_defer((int)rows, N, K, dt, K)) p.fused = false;
       else g = maxz(g, gemm_deferred_workspace((int)rows, N, K));

@@ -7,6 +7,19 @@
 
 namespace {
 
+__device__ __forceinline__ void store4(float* p, const float4& v) { *reinterpret_cast<float4*>(p) = v; }
+__device__ __forceinline__ void store4(bf16_t* p, const float4& v) {
+  uint2 u;
+  u.x = pack_bf16x2(v.x, v.y);
+  u.y = pack_bf16x2(v.z, v.w);
+  *reinterpret_cast<uint2*>(p) = u;
+}
+__device__ __forceinline__ float4 load4(const float* p) { return *reinterpret_cast<const float4*>(p); }
+__device__ __forceinline__ float4 load4(const bf16_t* p) {
+  const uint2 u = *reinterpret_cast<const uint2*>(p);
+  return make_float4(bf16lo_to_f32(u.x), bf16hi_to_f32(u.x), bf16lo_to_f32(u.y), bf16hi_to_f32(u.y));
+}
+
 template <typename T>
 __global__ void embed_kernel(const T* __restrict__ emb, const int32_t* __restrict__ tokens, long long tok_stride,
                              T* __restrict__ x, int d, int vocab) {
@@ -25,16 +38,31 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const T* __restrict__ x, c
   const long long row = blockIdx.x;
   const T* xr = x + row * d;
   float ss = 0.f;
-  for (int i = threadIdx.x; i < d; i += 256) {
-    const float v = to_f32<T>(xr[i]);
-    ss += v * v;
+  const bool vec = (d & 3) == 0;
+  if (vec) {
+    for (int i = threadIdx.x * 4; i < d; i += 1024) {
+      const float4 v = load4(xr + i);
+      ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+    }
+  } else {
+    for (int i = threadIdx.x; i < d; i += 256) {
+      const float v = to_f32<T>(xr[i]);
+      ss += v * v;
+    }
   }
   for (int off = 32; off >= 1; off >>= 1) ss += __shfl_xor(ss, off);
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
   __syncthreads();
   const float tot = red[0] + red[1] + red[2] + red[3];
   const float inv = 1.0f / sqrtf(tot / (float)d + eps);
-  for (int i = threadIdx.x; i < d; i += 256) y[row * d + i] = from_f32<T>(to_f32<T>(xr[i]) * inv * to_f32<T>(g[i]));
+  if (vec) {
+    for (int i = threadIdx.x * 4; i < d; i += 1024) {
+      const float4 v = load4(xr + i), gg = load4(g + i);
+      store4(y + row * d + i, make_float4(v.x * inv * gg.x, v.y * inv * gg.y, v.z * inv * gg.z, v.w * inv * gg.w));
+    }
+  } else {
+    for (int i = threadIdx.x; i < d; i += 256) y[row * d + i] = from_f32<T>(to_f32<T>(xr[i]) * inv * to_f32<T>(g[i]));
+  }
 }
 
 // qkv rows [rows, (Hq + 2 Hkv) dh] -> q [rows, Hq dh] (contiguous) and K/V rows into a cache
@@ -70,12 +98,22 @@ __global__ __launch_bounds__(256) void argmax_kernel(const T* __restrict__ logit
   const T* lr = logits + row * vocab;
   float best = -INFINITY;
   int bi = 0x7fffffff;
-  for (int i = threadIdx.x; i < vocab; i += 256) {
-    const float v = to_f32<T>(lr[i]);
+  auto consider = [&](float v, int i) __attribute__((always_inline)) {
     if (v > best || (v == best && i < bi)) {
       best = v;
       bi = i;
     }
+  };
+  if ((vocab & 3) == 0) {
+    for (int i = threadIdx.x * 4; i < vocab; i += 1024) {
+      const float4 v = load4(lr + i);
+      consider(v.x, i);
+      consider(v.y, i + 1);
+      consider(v.z, i + 2);
+      consider(v.w, i + 3);
+    }
+  } else {
+    for (int i = threadIdx.x; i < vocab; i += 256) consider(to_f32<T>(lr[i]), i);
   }
   for (int off = 32; off >= 1; off >>= 1) {
     const float ov = __shfl_xor(best, off);
@@ -102,66 +140,69 @@ __global__ __launch_bounds__(256) void argmax_kernel(const T* __restrict__ logit
 
 // Finishes a deferred GEMM for one row per workgroup: v = sum_s part[s][row][:] (+ bias) (+ residual);
 // x_out = v (storage dtype); if g: xn_out = v / sqrt(mean(v^2) + eps) * g.  Partials are summed in split
-// order.  Two passes over the (cache-resident) partials instead of a register copy of the row.
+// order.  Up to 1024 threads per row, each owning NV groups of four consecutive columns held in registers,
+// so the row is read once.
+constexpr int FIN_NV = 4;  // column groups per thread: rows up to 1024 * 4 * FIN_NV = 16384 wide
+
 template <typename T>
-__global__ __launch_bounds__(256) void finish_norm_kernel(const float* __restrict__ part, int splits, long long MN,
-                                                          const T* __restrict__ bias, const T* residual, T* x_out,
-                                                          const T* __restrict__ g, T* __restrict__ xn_out, int d,
-                                                          float eps) {
-  __shared__ float red[4];
+__global__ __launch_bounds__(1024) void finish_norm_kernel(const float* __restrict__ part, int splits, long long MN,
+                                                           const T* __restrict__ bias, const T* residual, T* x_out,
+                                                           const T* __restrict__ g, T* __restrict__ xn_out, int d,
+                                                           float eps) {
+  __shared__ float red[16];
   const long long row = blockIdx.x;
   const float* pr = part + row * d;
-  auto value4 = [&](int c) __attribute__((always_inline)) {
-    float4 v = *reinterpret_cast<const float4*>(pr + c);
-    for (int s = 1; s < splits; ++s) {
-      const float4 t = *reinterpret_cast<const float4*>(pr + s * MN + c);
-      v.x += t.x;
-      v.y += t.y;
-      v.z += t.z;
-      v.w += t.w;
+  const int stride = blockDim.x * 4;
+  float4 v[FIN_NV];
+  float ss = 0.f;
+#pragma unroll
+  for (int i = 0; i < FIN_NV; ++i) {
+    const int c = threadIdx.x * 4 + i * stride;
+    v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (c < d) {
+      for (int s = 0; s < splits; ++s) {
+        const float4 t = load4(pr + s * MN + c);
+        v[i].x += t.x;
+        v[i].y += t.y;
+        v[i].z += t.z;
+        v[i].w += t.w;
+      }
+      if (bias) {
+        const float4 t = load4(bias + c);
+        v[i].x += t.x;
+        v[i].y += t.y;
+        v[i].z += t.z;
+        v[i].w += t.w;
+      }
+      if (residual) {
+        const float4 t = load4(residual + row * d + c);
+        v[i].x += t.x;
+        v[i].y += t.y;
+        v[i].z += t.z;
+        v[i].w += t.w;
+      }
+      ss += v[i].x * v[i].x + v[i].y * v[i].y + v[i].z * v[i].z + v[i].w * v[i].w;
     }
-    if (bias) {
-      v.x += to_f32<T>(bias[c]);
-      v.y += to_f32<T>(bias[c + 1]);
-      v.z += to_f32<T>(bias[c + 2]);
-      v.w += to_f32<T>(bias[c + 3]);
-    }
-    if (residual) {
-      const T* rr = residual + row * d + c;
-      v.x += to_f32<T>(rr[0]);
-      v.y += to_f32<T>(rr[1]);
-      v.z += to_f32<T>(rr[2]);
-      v.w += to_f32<T>(rr[3]);
-    }
-    return v;
-  };
+  }
   float inv = 0.f;
   if (g) {
-    float ss = 0.f;
-    for (int c = threadIdx.x * 4; c < d; c += 1024) {
-      const float4 v = value4(c);
-      ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
-    }
     for (int off = 32; off >= 1; off >>= 1) ss += __shfl_xor(ss, off);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
     __syncthreads();
-    inv = 1.0f / sqrtf((red[0] + red[1] + red[2] + red[3]) / (float)d + eps);
+    float tot = 0.f;
+    for (int w = 0; w < (int)(blockDim.x >> 6); ++w) tot += red[w];
+    inv = 1.0f / sqrtf(tot / (float)d + eps);
   }
-  // the residual row is read again below before x_out (which may alias it) is written: each thread only
-  // rewrites the four elements it has just read
-  for (int c = threadIdx.x * 4; c < d; c += 1024) {
-    const float4 v = value4(c);
-    T* xo = x_out + row * d + c;
-    xo[0] = from_f32<T>(v.x);
-    xo[1] = from_f32<T>(v.y);
-    xo[2] = from_f32<T>(v.z);
-    xo[3] = from_f32<T>(v.w);
-    if (g) {
-      T* xn = xn_out + row * d + c;
-      xn[0] = from_f32<T>(v.x * inv * to_f32<T>(g[c]));
-      xn[1] = from_f32<T>(v.y * inv * to_f32<T>(g[c + 1]));
-      xn[2] = from_f32<T>(v.z * inv * to_f32<T>(g[c + 2]));
-      xn[3] = from_f32<T>(v.w * inv * to_f32<T>(g[c + 3]));
+#pragma unroll
+  for (int i = 0; i < FIN_NV; ++i) {
+    const int c = threadIdx.x * 4 + i * stride;
+    if (c < d) {
+      store4(x_out + row * d + c, v[i]);
+      if (g) {
+        const float4 gg = load4(g + c);
+        store4(xn_out + row * d + c,
+               make_float4(v[i].x * inv * gg.x, v[i].y * inv * gg.y, v[i].z * inv * gg.z, v[i].w * inv * gg.w));
+      }
     }
   }
 }
@@ -169,7 +210,7 @@ __global__ __launch_bounds__(256) void finish_norm_kernel(const float* __restric
 // Finishes a deferred QKV (or KV) GEMM: sums the partials of one row and writes the query part to the
 // contiguous q buffer and the key / value parts into the cache rows (same addressing as scatter_qkv_kernel).
 template <typename T>
-__global__ __launch_bounds__(256) void finish_scatter_kernel(const float* __restrict__ part, int splits, long long MN,
+__global__ __launch_bounds__(1024) void finish_scatter_kernel(const float* __restrict__ part, int splits, long long MN,
                                                              T* __restrict__ q, T* __restrict__ kc, T* __restrict__ vc,
                                                              const int32_t* __restrict__ base, int fixed, int q_len,
                                                              int Hq, int Hkv, int dh, long long cap, int q_cols,
@@ -179,7 +220,7 @@ __global__ __launch_bounds__(256) void finish_scatter_kernel(const float* __rest
   const float* pr = part + (long long)row * row_cols;
   const long long pos = (base ? base[b] : 0) + fixed + r;
   const bool pos_ok = pos >= 0 && pos < cap;  // never write outside the cache
-  for (int c = threadIdx.x * 4; c < row_cols; c += 1024) {
+  for (int c = threadIdx.x * 4; c < row_cols; c += blockDim.x * 4) {
     float4 v = *reinterpret_cast<const float4*>(pr + c);
     for (int s = 1; s < splits; ++s) {
       const float4 t = *reinterpret_cast<const float4*>(pr + s * MN + c);
@@ -202,10 +243,7 @@ __global__ __launch_bounds__(256) void finish_scatter_kernel(const float* __rest
       const int kvh = i / dh, e = i % dh;
       dst = cache + (((long long)b * Hkv + kvh) * cap + pos) * dh + e;
     }
-    dst[0] = from_f32<T>(v.x);
-    dst[1] = from_f32<T>(v.y);
-    dst[2] = from_f32<T>(v.z);
-    dst[3] = from_f32<T>(v.w);
+    store4(dst, v);
   }
 }
 
@@ -273,13 +311,15 @@ int launch_rmsnorm(const void* x, const void* g, void* y, int rows, int d, float
 
 int launch_finish_norm(const float* part, int splits, const void* bias, const void* residual, void* x_out,
                        const void* g, void* xn_out, int rows, int d, float eps, int dtype, hipStream_t st) {
-  if (d % 4 != 0) return TANDEM_ERR_UNSUPPORTED;
+  if (d % 4 != 0 || d > 1024 * 4 * FIN_NV) return TANDEM_ERR_UNSUPPORTED;
   const long long MN = (long long)rows * d;
+  int threads = (d / 4 + 63) / 64 * 64;
+  threads = threads > 1024 ? 1024 : threads;
   if (dtype == TANDEM_BF16)
-    hipLaunchKernelGGL(finish_norm_kernel<bf16_t>, dim3(rows), dim3(256), 0, st, part, splits, MN, (const bf16_t*)bias,
+    hipLaunchKernelGGL(finish_norm_kernel<bf16_t>, dim3(rows), dim3(threads), 0, st, part, splits, MN, (const bf16_t*)bias,
                        (const bf16_t*)residual, (bf16_t*)x_out, (const bf16_t*)g, (bf16_t*)xn_out, d, eps);
   else
-    hipLaunchKernelGGL(finish_norm_kernel<float>, dim3(rows), dim3(256), 0, st, part, splits, MN, (const float*)bias,
+    hipLaunchKernelGGL(finish_norm_kernel<float>, dim3(rows), dim3(threads), 0, st, part, splits, MN, (const float*)bias,
                        (const float*)residual, (float*)x_out, (const float*)g, (float*)xn_out, d, eps);
   return hip_ok(hipGetLastError());
 }
@@ -289,11 +329,13 @@ int launch_finish_scatter(const float* part, int splits, void* q, void* kc, void
                           hipStream_t st) {
   if (row_cols % 4 != 0 || q_cols % 4 != 0 || dh % 4 != 0) return TANDEM_ERR_UNSUPPORTED;
   const long long MN = (long long)rows * row_cols;
+  int threads = (row_cols / 4 + 63) / 64 * 64;
+  threads = threads > 1024 ? 1024 : threads;
   if (dtype == TANDEM_BF16)
-    hipLaunchKernelGGL(finish_scatter_kernel<bf16_t>, dim3(rows), dim3(256), 0, st, part, splits, MN, (bf16_t*)q,
+    hipLaunchKernelGGL(finish_scatter_kernel<bf16_t>, dim3(rows), dim3(threads), 0, st, part, splits, MN, (bf16_t*)q,
                        (bf16_t*)kc, (bf16_t*)vc, base, fixed, q_len, Hq, Hkv, dh, (long long)cap, q_cols, row_cols);
   else
-    hipLaunchKernelGGL(finish_scatter_kernel<float>, dim3(rows), dim3(256), 0, st, part, splits, MN, (float*)q,
+    hipLaunchKernelGGL(finish_scatter_kernel<float>, dim3(rows), dim3(threads), 0, st, part, splits, MN, (float*)q,
                        (float*)kc, (float*)vc, base, fixed, q_len, Hq, Hkv, dh, (long long)cap, q_cols, row_cols);
   return hip_ok(hipGetLastError());
 }
