@@ -351,6 +351,147 @@ __global__ __launch_bounds__(512) void gemm_tile_kernel(GemmParams p) {
   }
 }
 
+// ---------------------------------------------------------------- big-tile bf16 MFMA kernel (M >= 256)
+// The compute-bound regime (prompt-time FF_Tandem over whole prompts, large verify batches): 256 x 256
+// output tile per workgroup, 4 wavefronts in a 2 x 2 arrangement, 128 x 128 per wavefront = 16 MFMA
+// tiles of 32x32 (256 accumulator registers) so that one operand fetched from LDS feeds four MFMAs and
+// LDS read traffic stays at half its bandwidth.  Both operands are staged through LDS with coalesced
+// global loads (64-deep stages, double-buffered, row pitch 144 B for conflict-free 16-byte operand
+// reads).  Workgroup ids are remapped so that the workgroups an XCD receives (round-robin by id) cover
+// neighbouring tiles that share a weight tile in that XCD's L2.
+// Requires N % 256 == 0, K % 128 == 0; M ragged (rows past M are clamped on load, skipped on store).
+constexpr int BK = 64;
+constexpr int BP = BK + 8;  // LDS row pitch in elements
+
+__global__ __launch_bounds__(256, 1) void gemm_big_kernel(GemmParams p, int tiles_m, int tiles_n) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  bf16_t* As = reinterpret_cast<bf16_t*>(smem);  // [2][256][BP]
+  bf16_t* Bs = As + 2 * 256 * BP;                // [2][256][BP]
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int wm = w >> 1, wn = w & 1;
+  const int c32 = lane & 31, h = lane >> 5;
+
+  // XCD-aware tile order
+  const int total = tiles_m * tiles_n;
+  int id = blockIdx.x;
+  if ((total & 7) == 0) id = (id & 7) * (total >> 3) + (id >> 3);
+  int tn = id / tiles_m, tm = id % tiles_m;
+  if ((total & 7) == 0 && (tiles_m & 7) == 0 && (tiles_n & 3) == 0) {
+    // the 32 tiles an XCD works on at a time form an 8 x 4 block: 12 operand tiles feed 32 output tiles
+    const int block = id >> 5, within = id & 31, blocks_m = tiles_m >> 3;
+    tm = (block % blocks_m) * 8 + (within & 7);
+    tn = (block / blocks_m) * 4 + (within >> 3);
+  }
+  const int m0 = tm * 256, n0 = tn * 256;
+
+  // staging: thread t covers rows (t>>3) + 32*q, 16-byte column t&7, for q = 0..7 of each operand
+  const int srow = threadIdx.x >> 3, scol = threadIdx.x & 7;
+  const bf16_t* wg = (const bf16_t*)p.W + (long long)(n0 + srow) * p.K + scol * 8;
+  const bf16_t* xg = (const bf16_t*)p.X + scol * 8;
+  const int sdst = srow * BP + scol * 8;
+
+  f32x16 acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  u32x4 sa0[8], sb0[8], sa1[8], sb1[8];
+#define BG_GLOAD(sa, sb, k0)                                                                                \
+  {                                                                                                         \
+    _Pragma("unroll") for (int q = 0; q < 8; ++q) {                                                         \
+      int m_ = m0 + srow + 32 * q;                                                                          \
+      m_ = m_ < p.M ? m_ : p.M - 1;                                                                         \
+      sa[q] = *reinterpret_cast<const u32x4*>(xg + (long long)m_ * p.ldx + (k0));                           \
+    }                                                                                                       \
+    _Pragma("unroll") for (int q = 0; q < 8; ++q)                                                           \
+        sb[q] = *reinterpret_cast<const u32x4*>(wg + (long long)(32 * q) * p.K + (k0));                     \
+    __builtin_amdgcn_sched_barrier(0);                                                                      \
+  }
+#define BG_STORE(sa, sb, buf)                                                                               \
+  {                                                                                                         \
+    _Pragma("unroll") for (int q = 0; q < 8; ++q) {                                                         \
+      *reinterpret_cast<u32x4*>(As + (buf) * 256 * BP + sdst + q * 32 * BP) = sa[q];                        \
+      *reinterpret_cast<u32x4*>(Bs + (buf) * 256 * BP + sdst + q * 32 * BP) = sb[q];                        \
+    }                                                                                                       \
+  }
+  const bf16_t* a_rd = As + (wm * 128 + c32) * BP + 8 * h;
+  const bf16_t* b_rd = Bs + (wn * 128 + c32) * BP + 8 * h;
+  bf16x8 av0[4], bv0[4], av1[4], bv1[4];
+#define BG_OPS(av, bv, buf, ks)                                                                             \
+  {                                                                                                         \
+    _Pragma("unroll") for (int t = 0; t < 4; ++t) {                                                         \
+      av[t] = __builtin_bit_cast(                                                                           \
+          bf16x8, *reinterpret_cast<const u32x4*>(a_rd + (buf) * 256 * BP + t * 32 * BP + (ks) * 16));      \
+      bv[t] = __builtin_bit_cast(                                                                           \
+          bf16x8, *reinterpret_cast<const u32x4*>(b_rd + (buf) * 256 * BP + t * 32 * BP + (ks) * 16));      \
+    }                                                                                                       \
+  }
+#define BG_MFMA(av, bv)                                                                                     \
+  {                                                                                                         \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i) _Pragma("unroll") for (int j = 0; j < 4; ++j)              \
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], bv[j], acc[i][j], 0, 0, 0);              \
+  }
+  // operands of contraction step ks+1 are fetched from LDS while the 16 MFMAs of step ks run
+#define BG_COMPUTE(buf)        \
+  {                            \
+    BG_OPS(av0, bv0, buf, 0)   \
+    BG_OPS(av1, bv1, buf, 1)   \
+    BG_MFMA(av0, bv0)          \
+    BG_OPS(av0, bv0, buf, 2)   \
+    BG_MFMA(av1, bv1)          \
+    BG_OPS(av1, bv1, buf, 3)   \
+    BG_MFMA(av0, bv0)          \
+    BG_MFMA(av1, bv1)          \
+  }
+
+  // Global loads run two stages ahead of the MFMAs (two staging register sets), the LDS tiles one.
+  const int stages = p.K / BK;  // even (launcher): the loop below retires two stages per trip
+  BG_GLOAD(sa0, sb0, 0)
+  BG_GLOAD(sa1, sb1, BK)
+  BG_STORE(sa0, sb0, 0)
+  __syncthreads();
+  for (int st = 0; st < stages; st += 2) {
+    const int s2 = st + 2 < stages ? st + 2 : stages - 1;  // past the end: harmless re-reads
+    const int s3 = st + 3 < stages ? st + 3 : stages - 1;
+    BG_GLOAD(sa0, sb0, (long long)s2 * BK)
+    BG_COMPUTE(0)
+    BG_STORE(sa1, sb1, 1)
+    __syncthreads();
+    BG_GLOAD(sa1, sb1, (long long)s3 * BK)
+    BG_COMPUTE(1)
+    BG_STORE(sa0, sb0, 0)
+    __syncthreads();
+  }
+#undef BG_GLOAD
+#undef BG_STORE
+#undef BG_COMPUTE
+#undef BG_OPS
+#undef BG_MFMA
+
+  // C layout: lane holds column j = lane%32 (feature n), rows i = 8*(r/4) + 4*(lane/32) + r%4 (row m)
+#define BG_OUT(i, j)                                                                                      \
+  {                                                                                                       \
+    const int n_ = n0 + wn * 128 + (j) * 32 + c32;                                                        \
+    _Pragma("clang loop unroll(full)") for (int r = 0; r < 16; ++r) {                                     \
+      const int m_ = m0 + wm * 128 + (i) * 32 + 8 * (r >> 2) + 4 * h + (r & 3);                           \
+      if (m_ < p.M)                                                                                       \
+        ((bf16_t*)p.Y)[(long long)m_ * p.ldy + n_] = f32_to_bf16(epilogue<bf16_t>(acc[i][j][r], m_, n_, p)); \
+    }                                                                                                     \
+  }
+#define BG_OUT_ROW(i)                                                       \
+  BG_OUT(i, 0) __builtin_amdgcn_sched_barrier(0); BG_OUT(i, 1) __builtin_amdgcn_sched_barrier(0); \
+  BG_OUT(i, 2) __builtin_amdgcn_sched_barrier(0); BG_OUT(i, 3) __builtin_amdgcn_sched_barrier(0);
+  BG_OUT_ROW(0)
+  BG_OUT_ROW(1)
+  BG_OUT_ROW(2)
+  BG_OUT_ROW(3)
+#undef BG_OUT_ROW
+#undef BG_OUT
+}
+
 // sums the split partials in split order, then the epilogue
 template <typename T>
 __global__ void gemm_splitk_epilogue_kernel(GemmParams p) {
@@ -413,6 +554,24 @@ int launch_tile(const GemmParams& p, int mpasses, hipStream_t st) {
   return hip_ok(hipGetLastError());
 }
 
+int launch_big(const GemmParams& p, hipStream_t st) {
+  const size_t lds_bytes = (size_t)2 * 2 * 256 * BP * sizeof(bf16_t);
+  static bool attr_set = false;
+  if (!attr_set) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_big_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)lds_bytes) != hipSuccess)
+      return TANDEM_ERR_HIP;
+    attr_set = true;
+  }
+  const int tiles_m = (p.M + 255) / 256, tiles_n = p.N / 256;
+  hipLaunchKernelGGL(gemm_big_kernel, dim3(tiles_m * tiles_n), dim3(256), lds_bytes, st, p, tiles_m, tiles_n);
+  return hip_ok(hipGetLastError());
+}
+// enough 256 x 256 tiles to occupy most of the 256 CUs, otherwise the tile kernel in row passes does better
+bool big_ok(int M, int N, int K) {
+  return N % 256 == 0 && K % (2 * BK) == 0 && (long long)((M + 255) / 256) * (N / 256) >= 192;
+}
+
 bool skinny_ok(int M, int N, int K, int dtype, long long ldx) {
   return dtype == TANDEM_BF16 && N % 32 == 0 && K % 64 == 0 && ldx % 8 == 0 && M >= 1;
 }
@@ -442,6 +601,7 @@ size_t gemm_deferred_workspace(int M, int N, int K) { return (size_t)gemm_splitk
 
 size_t gemm_workspace(int M, int N, int K, int dtype) {
   if (!skinny_ok(M, N, K, dtype, 8)) return 0;
+  if (big_ok(M, N, K)) return 0;
   const int s = gemm_splitk(M, N, K);
   return s > 1 ? (size_t)s * M * N * sizeof(float) : 0;
 }
@@ -466,6 +626,7 @@ int launch_gemm(const GemmArgs& g, hipStream_t st) {
   p.defer = g.defer;
   if (skinny_ok(g.M, g.N, g.K, g.dtype, g.ldx) && (reinterpret_cast<uintptr_t>(g.X) % 16 == 0) &&
       (reinterpret_cast<uintptr_t>(g.W) % 16 == 0) && (reinterpret_cast<uintptr_t>(g.Y) % 8 == 0) && g.ldy % 4 == 0) {
+    if (big_ok(g.M, g.N, g.K) && !g.defer) return launch_big(p, st);
     p.splitK = gemm_splitk(g.M, g.N, g.K);
     if ((p.splitK > 1 || g.defer) && (size_t)p.splitK * g.M * g.N * sizeof(float) > g.ws_bytes) return TANDEM_ERR_WORKSPACE;
     const int mt = g.M <= 32 ? 1 : (g.M <= 64 ? 2 : 4);

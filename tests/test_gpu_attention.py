@@ -72,6 +72,14 @@ def test_draft_attn_parity_small(tb, B, Hq, Hkv, dh, T_max, gmax, n_large, n_cur
     print(f"draft small {B,Hq,Hkv,dh,T_max,dtype}: max rel err {e[0]:.2e}")
 
 
+def test_attention_parity_long_context_many_splits(tb):
+    """One sequence, one KV head, long context: the largest split count (64) with a ragged last split."""
+    case = inputs.draft_attn_case(12, 1, 1, 1, 128, 17001, 4, [16999], [3], dtype="bf16", kv_std=1.0)
+    assert_rows_close(run_draft(tb, case), oracle_draft(case), what="draft long context")
+    blk = inputs.block_attn_case(13, 1, 4, 4, 1, 128, 17001, [16990], dtype="bf16")
+    assert_rows_close(run_block(tb, blk), oracle_block(blk), what="block long context")
+
+
 def test_draft_attn_parity_config1_full(tb):
     """The single-kernel benchmark configuration: batch 8, 8 heads of 128, 2044 large rows + 4 own rows."""
     case = inputs.draft_attn_case(1, 8, 8, 8, 128, 2044, 4, 2044, 4, dtype="bf16")

@@ -61,6 +61,15 @@ def test_project_parity_small(tb, M, d_L, d_hidden, d_S, dtype, act):
     print(f"project {M,d_L,d_hidden,d_S,dtype}: max rel err {e[0]:.2e}")
 
 
+@pytest.mark.parametrize("M,d_L,d_hidden,d_S", [(3000, 256, 0, 4096), (3072, 384, 0, 4096), (2100, 128, 4096, 512)])
+def test_project_parity_prompt_sized(tb, M, d_L, d_hidden, d_S):
+    """Prompt-time FF_Tandem (thousands of rows): the compute-bound 256 x 256 tile kernel, ragged last row tile."""
+    case = inputs.project_case(41, M, d_L, d_hidden, d_S, dtype="bf16", w_std=0.05, bias_std=0.1)
+    got = run(tb, case)
+    e = assert_rows_close(got, oracle(case), what="project prompt-sized")
+    print(f"project prompt-sized {M,d_L,d_hidden,d_S}: max rel err {e[0]:.2e}")
+
+
 def test_project_parity_config2_full(tb):
     """The benchmark's projection: 4096 -> 8192 -> 1024 on the 64 new block rows, weights N(0, 0.02)."""
     case = inputs.project_case(2, 64, 4096, 8192, 1024, dtype="bf16", w_std=0.02)
