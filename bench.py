@@ -307,6 +307,68 @@ WORKLOADS = {
 }
 
 
+# ------------------------------------------------------------------ FF_Tandem projection
+MFMA_PEAK_TFLOPS = 2500.0
+PROJECT_WORKLOADS = {
+    # the benchmark's projection 4096 -> 8192 -> 1024 (GELU) on M rows
+    "c2_project": (64, "tandem_project bf16 M=64 (batch 16 x gamma 4) 4096->8192->1024"),
+    "c3_project": (128, "tandem_project bf16 M=128 (batch 32 x gamma 4) 4096->8192->1024"),
+    "project_m512": (512, "tandem_project bf16 M=512 (batch 64 x gamma 8) 4096->8192->1024"),
+    "project_m4096": (4096, "tandem_project bf16 M=4096 (prompt-time, one 4096-token prompt) 4096->8192->1024"),
+    "project_m65536": (65536, "tandem_project bf16 M=65536 (prompt-time, 16 prompts of 4096 tokens) 4096->8192->1024"),
+}
+
+
+def run_project_workload(torch, binding, inputs, args):
+    M, desc = PROJECT_WORKLOADS[args.workload]
+    d_L, d_h, d_S = 4096, 8192, 1024
+    wbytes = 2 * (d_h * d_L + d_S * d_h)
+    R = _rotations(wbytes)
+    ffs = [{"W1": inputs.device_normal((d_h, d_L), 700 + 2 * i, 0.02), "b1": torch.zeros(d_h, dtype=torch.bfloat16, device="cuda"),
+            "W2": inputs.device_normal((d_S, d_h), 701 + 2 * i, 0.02), "b2": torch.zeros(d_S, dtype=torch.bfloat16, device="cuda"),
+            "act": "gelu"} for i in range(R)]
+    x = inputs.device_normal((M, d_L), 699, 1.0)
+    y = torch.empty((M, d_S), dtype=torch.bfloat16, device="cuda")
+    ws = binding.workspace(binding.tandem_project_workspace(binding.ff_desc(ffs[0]), M))
+    call = lambda i: binding.tandem_project(ffs[i], x, out=y, ws=ws)
+    torch.cuda.synchronize()
+    ms = _time_calls(torch, call, R, args.steps, args.warmup, use_graph=not args.no_graph)
+    flops = 2.0 * M * (d_L * d_h + d_h * d_S)
+    bytes_alg = wbytes + 2 * M * (d_L + 2 * d_h + d_S)  # weights once; x read, hidden written and read, y written
+    tflops = flops / (ms * 1e-3) / 1e12
+    gbs = bytes_alg / (ms * 1e-3) / 1e9
+    hbm_bound = flops / bytes_alg < MFMA_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)
+    cpu = None
+    if not args.no_cpu_baseline:
+        sys.path.insert(0, os.path.join(ROOT, "tests"))
+        from oracle import tandem_oracle as orc
+        from parity import row_errors
+
+        rows = min(M, 64)
+        ff64 = {k: (inputs.torch_to_f64(v) if hasattr(v, "shape") else v) for k, v in ffs[0].items()}
+        xs = inputs.torch_to_f64(x[:rows])
+        t0 = time.perf_counter()
+        want = orc.project(xs, ff64)
+        dt = time.perf_counter() - t0
+        call(0)
+        torch.cuda.synchronize()
+        e_inf, _ = row_errors(inputs.torch_to_f64(y[:rows]), want)
+        cpu = {"value": flops * rows / M / dt / 1e12, "unit": "TFLOP/s", "cores": _cpu_threads(), "kind": "oracle",
+               "sample": f"first {rows} of {M} rows, fp64 numpy, {dt:.2f} s", "gpu_max_rel_err_on_sample": float(e_inf.max())}
+    roof = ({"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS}
+            if hbm_bound else
+            {"bound": "mfma", "achieved": tflops, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": tflops / MFMA_PEAK_TFLOPS})
+    roof["traffic"] = _traffic(args.workload)
+    return {
+        "metric": "FF_Tandem projection TFLOP/s (bf16 MFMA)", "value": tflops, "unit": "TFLOP/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {desc}", "rotated_weight_sets": R, "frac_of_mfma_peak": tflops / MFMA_PEAK_TFLOPS,
+                   "weight_stream_GBps": wbytes / (ms * 1e-3) / 1e9},
+        "roofline": roof, "cpu_baseline": cpu,
+    }
+
+
 def _traffic(name):
     """HBM traffic per launch measured offline with rocprofv3 counters (see profiles/), or None."""
     path = os.path.join(ROOT, "profiles", "traffic.json")
@@ -407,7 +469,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="c3_step", choices=sorted(WORKLOADS) + ["c3_step"])
+    ap.add_argument("--workload", default="c3_step", choices=sorted(WORKLOADS) + sorted(PROJECT_WORKLOADS) + ["c3_step"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -439,7 +501,10 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    line = (run_step_workload if step else run_kernel_workload)(torch, binding, inputs, args)
+    runner = run_step_workload if step else (run_project_workload if args.workload in PROJECT_WORKLOADS else run_kernel_workload)
+    if args.workload in ("project_m4096", "project_m65536"):
+        args.steps = min(args.steps, 20)
+    line = runner(torch, binding, inputs, args)
     print(json.dumps(line))
 
 

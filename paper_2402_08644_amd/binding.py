@@ -160,6 +160,13 @@ def _workspace(nbytes, like):
     return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=like.device)
 
 
+def workspace(nbytes, device="cuda"):
+    """Device scratch of at least nbytes for the *_workspace() sizes (at least 256 bytes)."""
+    import torch
+
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
 def attn_desc(B, Hq, Hkv, dh, T_max, gamma_max, scale, dtype_code):
     return AttnDesc(B, Hq, Hkv, dh, T_max, gamma_max, scale, dtype_code)
 
