@@ -71,12 +71,24 @@ typedef struct {
   int32_t act;   /* tandem_act, ignored when d_hidden == 0 */
   int32_t dtype; /* tandem_dtype */
   const void *W1, *b1, *W2, *b2;
+  const void *W1p, *W2p; /* optional: W1 / W2 in the packed layout written by tandem_pack_weight (device, same
+                            dtype and shape), or NULL.  Used instead of W1 / W2 when the row count allows. */
 } tandem_ff_desc;
 
 /* ---- workspace sizes (bytes of device scratch a call needs; 256-byte aligned base) ---- */
 size_t tandem_project_workspace(const tandem_ff_desc *ff, int64_t M);
 size_t tandem_block_attn_workspace(const tandem_attn_desc *a, int32_t q_len);
 size_t tandem_draft_attn_workspace(const tandem_attn_desc *a);
+
+/* Packed weight layout (a choice of this library, not of the paper: the products of Eq. (1) / Eq. (2)
+ * are unchanged, only the order of W's elements in memory).  W[N, K] row-major, bf16, is cut into
+ * tiles of 32 rows x 64 columns; tile (nb, kb) starts at element (nb * (K / 64) + kb) * 2048 and holds,
+ * at element ((j * 64 + 32 * h + c) * 8 + e), W[32 * nb + c][64 * kb + 32 * h + 8 * j + e]
+ * (j < 4, h < 2, c < 32, e < 8).  tandem_packed_weight_bytes: size of the packed copy, 0 when the
+ * shape or dtype cannot be packed (needs bf16, N % 128 == 0, K % 256 == 0).  tandem_pack_weight
+ * writes it (W, Wp: device, 16-byte aligned, not overlapping; enqueued on hip_stream). */
+size_t tandem_packed_weight_bytes(int64_t N, int64_t K, int32_t dtype);
+int tandem_pack_weight(const void *W, int64_t N, int64_t K, int32_t dtype, void *Wp, void *hip_stream);
 
 /* FF_Tandem: y_hat[M, d_S] = FF_Tandem(x[M, d_L])  (Eq. (2), first line; Sec. 1 "projection
  * layer").  x, y_hat: device, dtype ff->dtype.  M >= 1 rows (the gamma new rows of every
@@ -131,7 +143,15 @@ typedef struct {
   const tandem_ff_desc *ff;  /* host [S.n_layers]; ff[j].d_L == L.d, ff[j].d_S == S.d          */
   float rms_eps;
   int32_t dtype;             /* tandem_dtype of every weight, cache and activation             */
+  int32_t flags;             /* TANDEM_MODEL_* bits                                            */
 } tandem_model_desc;
+
+/* tandem_model_desc.flags: keep, in device memory owned by the model, a second copy of every bf16
+ * weight matrix whose shape allows it (rows % 128 == 0, columns % 256 == 0) in the packed layout of
+ * tandem_pack_weight: decode-time products then read each weight as one contiguous stream.  Costs
+ * as much device memory again as those matrices (allocated by tandem_model_create with hipMalloc on
+ * the current device, packed on the null stream, which is synchronised before returning). */
+#define TANDEM_MODEL_PACK_WEIGHTS 1
 
 /* Caller-owned decoding state (all device memory except the pointer arrays themselves).
  *   KL[j], VL[j]      [B, L.Hkv, T_max, dh]     M_L's K/V cache of large layer j

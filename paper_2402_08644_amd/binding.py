@@ -38,6 +38,7 @@ class FFDesc(C.Structure):
     _fields_ = [
         ("d_L", C.c_int32), ("d_hidden", C.c_int32), ("d_S", C.c_int32), ("act", C.c_int32), ("dtype", C.c_int32),
         ("W1", C.c_void_p), ("b1", C.c_void_p), ("W2", C.c_void_p), ("b2", C.c_void_p),
+        ("W1p", C.c_void_p), ("W2p", C.c_void_p),
     ]
 
 
@@ -56,7 +57,7 @@ class DecoderDesc(C.Structure):
 class ModelDesc(C.Structure):
     _fields_ = [
         ("L", DecoderDesc), ("S", DecoderDesc), ("ell", C.POINTER(C.c_int32)), ("ff", C.POINTER(FFDesc)),
-        ("rms_eps", C.c_float), ("dtype", C.c_int32),
+        ("rms_eps", C.c_float), ("dtype", C.c_int32), ("flags", C.c_int32),
     ]
 
 
@@ -74,9 +75,12 @@ class StepAux(C.Structure):
     _fields_ = [(k, C.c_void_p) for k in ("draft", "verify", "y_small", "x_large", "logits_S", "logits_L")]
 
 
+MODEL_PACK_WEIGHTS = 1
+
 EXPORTS = (
     "tandem_status_string",
     "tandem_project_workspace", "tandem_block_attn_workspace", "tandem_draft_attn_workspace",
+    "tandem_packed_weight_bytes", "tandem_pack_weight",
     "tandem_project", "tandem_block_attn", "tandem_draft_attn",
     "tandem_model_create", "tandem_model_destroy", "tandem_decode_step_workspace", "tandem_decode_step",
 )
@@ -101,6 +105,10 @@ def lib():
     L.tandem_block_attn_workspace.argtypes = [C.POINTER(AttnDesc), i32]
     L.tandem_draft_attn_workspace.restype = sz
     L.tandem_draft_attn_workspace.argtypes = [C.POINTER(AttnDesc)]
+    L.tandem_packed_weight_bytes.restype = sz
+    L.tandem_packed_weight_bytes.argtypes = [i64, i64, i32]
+    L.tandem_pack_weight.restype = C.c_int
+    L.tandem_pack_weight.argtypes = [vp, i64, i64, i32, vp, vp]
     L.tandem_project.restype = C.c_int
     L.tandem_project.argtypes = [C.POINTER(FFDesc), vp, vp, i64, vp, sz, vp]
     L.tandem_block_attn.restype = C.c_int
@@ -237,15 +245,35 @@ def tandem_block_attn(q, k_cache, v_cache, n_prefix, scale=None, out=None, ws=No
 
 
 def ff_desc(ff: dict, dtype_code=None) -> FFDesc:
-    """ff: {"W","b"} (linear) or {"W1","b1","W2","b2","act"} of device tensors, weights [out, in]."""
+    """ff: {"W","b"} (linear) or {"W1","b1","W2","b2","act"} of device tensors, weights [out, in]; optional
+    "Wp" / "W1p","W2p": the same weights packed by tandem_pack_weight."""
+    opt = lambda k: ff[k].data_ptr() if ff.get(k) is not None else None
     if "W" in ff:
         W = ff["W"]
-        return FFDesc(W.shape[1], 0, W.shape[0], ACT_NONE, _dtype_code(W), W.data_ptr(),
-                      ff["b"].data_ptr() if ff.get("b") is not None else None, None, None)
+        return FFDesc(W.shape[1], 0, W.shape[0], ACT_NONE, _dtype_code(W), W.data_ptr(), opt("b"), None, None,
+                      opt("Wp"), None)
     W1, W2 = ff["W1"], ff["W2"]
     return FFDesc(W1.shape[1], W1.shape[0], W2.shape[0], _ACT[ff.get("act", "gelu")], _dtype_code(W1), W1.data_ptr(),
-                  ff["b1"].data_ptr() if ff.get("b1") is not None else None, W2.data_ptr(),
-                  ff["b2"].data_ptr() if ff.get("b2") is not None else None)
+                  opt("b1"), W2.data_ptr(), opt("b2"), opt("W1p"), opt("W2p"))
+
+
+def tandem_packed_weight_bytes(N: int, K: int, dtype_code: int) -> int:
+    return int(lib().tandem_packed_weight_bytes(N, K, dtype_code))
+
+
+def tandem_pack_weight(W, stream=None):
+    """W [N, K] device tensor -> its packed copy (a tensor of the same shape and dtype holding the tile layout),
+    or None when the shape or dtype has no packed form."""
+    import torch
+
+    N, K = W.shape
+    if not W.is_contiguous():
+        raise ValueError("W must be contiguous")
+    if tandem_packed_weight_bytes(N, K, _dtype_code(W)) == 0:
+        return None
+    Wp = torch.empty_like(W)
+    _check(lib().tandem_pack_weight(_ptr(W), N, K, _dtype_code(W), _ptr(Wp), _stream(stream)), "tandem_pack_weight")
+    return Wp
 
 
 def tandem_project_workspace(desc: FFDesc, M: int) -> int:
@@ -282,9 +310,10 @@ class TandemModel:
 
     `weights` has the layout produced by inputs.tandem_weights: {"L": decoder, "S": decoder,
     "ell": [...], "ff": [...], "eps": float} with per-layer Wq / Wk / Wv stored separately; they are
-    stacked here into the Wqkv operand the C ABI takes."""
+    stacked here into the Wqkv operand the C ABI takes.  pack_weights: let the library keep packed copies of
+    the weight matrices (faster decode-time products, as much device memory again as those matrices)."""
 
-    def __init__(self, weights):
+    def __init__(self, weights, pack_weights=True):
         import torch
 
         self._keep = []
@@ -322,7 +351,7 @@ class TandemModel:
             ffs[j] = ff_desc(held)
         ell = (C.c_int32 * len(self.ell))(*self.ell)
         self._keep += [ffs, ell]
-        desc = ModelDesc(L, S, ell, ffs, self.eps, self.dtype_code)
+        desc = ModelDesc(L, S, ell, ffs, self.eps, self.dtype_code, MODEL_PACK_WEIGHTS if pack_weights else 0)
         handle = C.c_void_p()
         _check(lib().tandem_model_create(C.byref(desc), C.byref(handle)), "tandem_model_create")
         self.handle = handle

@@ -3,6 +3,7 @@
 // lengths, tokens and the acceptance decision stay on the device, so the step never
 // synchronises with the host.
 #include <new>
+#include <unordered_map>
 #include <vector>
 
 #include "common.h"
@@ -36,12 +37,13 @@ size_t project_ws(const tandem_ff_desc* ff, int64_t M) {
   return hidden + align256(g);
 }
 
-int gemm(const void* X, int64_t ldx, const void* W, const void* bias, const void* residual, int64_t ldr, void* Y,
+int gemm(const void* X, int64_t ldx, const void* W, const void* Wp, const void* bias, const void* residual, int64_t ldr, void* Y,
          int64_t ldy, int M, int N, int K, int act, int dtype, void* ws, size_t ws_bytes, hipStream_t st) {
   GemmArgs g;
   g.X = X;
   g.ldx = ldx;
   g.W = W;
+  g.Wp = Wp;
   g.bias = bias;
   g.residual = residual;
   g.ldr = ldr;
@@ -59,12 +61,13 @@ int gemm(const void* X, int64_t ldx, const void* W, const void* bias, const void
 }
 
 // X . W^T left as fp32 partial sums in ws (see GemmArgs::defer)
-int gemm_deferred(const void* X, int64_t ldx, const void* W, int M, int N, int K, int dtype, void* ws, size_t ws_bytes,
+int gemm_deferred(const void* X, int64_t ldx, const void* W, const void* Wp, int M, int N, int K, int dtype, void* ws, size_t ws_bytes,
                   hipStream_t st) {
   GemmArgs g{};
   g.X = X;
   g.ldx = ldx;
   g.W = W;
+  g.Wp = Wp;
   g.M = M;
   g.N = N;
   g.K = K;
@@ -79,16 +82,16 @@ int gemm_deferred(const void* X, int64_t ldx, const void* W, int M, int N, int K
 // y_hat = FF_Tandem(x)   (Eq. (2), first line)
 int run_project(const tandem_ff_desc* ff, const void* x, void* y, int64_t M, void* ws, size_t ws_bytes, hipStream_t st) {
   if (ff->d_hidden == 0)
-    return gemm(x, ff->d_L, ff->W1, ff->b1, nullptr, 0, y, ff->d_S, (int)M, ff->d_S, ff->d_L, TANDEM_ACT_NONE, ff->dtype,
+    return gemm(x, ff->d_L, ff->W1, ff->W1p, ff->b1, nullptr, 0, y, ff->d_S, (int)M, ff->d_S, ff->d_L, TANDEM_ACT_NONE, ff->dtype,
                 ws, ws_bytes, st);
   const size_t hidden = align256((size_t)M * ff->d_hidden * elsize(ff->dtype));
   void* hbuf = ws;
   void* gws = (char*)ws + hidden;
   const size_t gws_bytes = ws_bytes - hidden;
-  int rc = gemm(x, ff->d_L, ff->W1, ff->b1, nullptr, 0, hbuf, ff->d_hidden, (int)M, ff->d_hidden, ff->d_L, ff->act,
+  int rc = gemm(x, ff->d_L, ff->W1, ff->W1p, ff->b1, nullptr, 0, hbuf, ff->d_hidden, (int)M, ff->d_hidden, ff->d_L, ff->act,
                 ff->dtype, gws, gws_bytes, st);
   if (rc != TANDEM_OK) return rc;
-  return gemm(hbuf, ff->d_hidden, ff->W2, ff->b2, nullptr, 0, y, ff->d_S, (int)M, ff->d_S, ff->d_hidden, TANDEM_ACT_NONE,
+  return gemm(hbuf, ff->d_hidden, ff->W2, ff->W2p, ff->b2, nullptr, 0, y, ff->d_S, (int)M, ff->d_S, ff->d_hidden, TANDEM_ACT_NONE,
               ff->dtype, gws, gws_bytes, st);
 }
 
@@ -113,9 +116,74 @@ struct tandem_model {
   std::vector<tandem_layer_weights> L_layers, S_layers;
   std::vector<int32_t> ell;
   std::vector<tandem_ff_desc> ff;
+  void* packed_buf = nullptr;                              // one allocation holding every packed weight copy
+  std::unordered_map<const void*, const void*> packed;     // caller's weight pointer -> packed copy
+  const void* pk(const void* W) const {
+    auto it = packed.find(W);
+    return it == packed.end() ? nullptr : it->second;
+  }
 };
 
 namespace {
+
+// Packed copies (the layout the stream GEMM kernel reads) of every weight matrix whose shape allows one, in
+// one device allocation owned by the model.
+int pack_model(tandem_model* m) {
+  struct Item {
+    const void* W;
+    int64_t N, K;
+  };
+  std::vector<Item> items;
+  const int dt = m->d.dtype;
+  auto add = [&](const void* W, int64_t N, int64_t K) {
+    if (W && gemm_packable(N, K, dt) && reinterpret_cast<uintptr_t>(W) % 16 == 0 && !m->packed.count(W)) {
+      items.push_back({W, N, K});
+      m->packed[W] = nullptr;
+    }
+  };
+  auto add_decoder = [&](const tandem_decoder_desc& D) {
+    for (int j = 0; j < D.n_layers; ++j) {
+      const tandem_layer_weights& l = D.layers[j];
+      add(l.Wqkv, (int64_t)(D.Hq + 2 * D.Hkv) * D.dh, D.d);
+      add(l.Wo, D.d, (int64_t)D.Hq * D.dh);
+      add(l.W1, D.d_ff, D.d);
+      add(l.W2, D.d, D.d_ff);
+    }
+    add(D.W_out, D.vocab, D.d);
+  };
+  add_decoder(m->d.L);
+  add_decoder(m->d.S);
+  for (const tandem_ff_desc& f : m->ff) {
+    if (f.d_hidden > 0) {
+      add(f.W1, f.d_hidden, f.d_L);
+      add(f.W2, f.d_S, f.d_hidden);
+    } else {
+      add(f.W1, f.d_S, f.d_L);
+    }
+  }
+  if (items.empty()) return TANDEM_OK;
+  size_t total = 0;
+  for (const Item& it : items) total += align256((size_t)it.N * it.K * elsize(dt));
+  if (hipMalloc(&m->packed_buf, total) != hipSuccess) {
+    m->packed_buf = nullptr;
+    m->packed.clear();
+    return TANDEM_ERR_HIP;
+  }
+  size_t off = 0;
+  for (const Item& it : items) {
+    void* dst = (char*)m->packed_buf + off;
+    const int rc = launch_pack_weights(it.W, dst, it.N, it.K, nullptr);
+    if (rc != TANDEM_OK) return rc;
+    m->packed[it.W] = dst;
+    off += align256((size_t)it.N * it.K * elsize(dt));
+  }
+  if (hipStreamSynchronize(nullptr) != hipSuccess) return TANDEM_ERR_HIP;
+  for (tandem_ff_desc& f : m->ff) {
+    f.W1p = m->pk(f.W1);
+    f.W2p = f.d_hidden > 0 ? m->pk(f.W2) : nullptr;
+  }
+  return TANDEM_OK;
+}
 
 // Workspace layout of one step, a pure function of (model, B, gamma, T_max, gamma_max).
 struct StepPlan {
@@ -218,6 +286,7 @@ struct Ctx {
   int dtype;
   float eps;
   template <typename T = void> T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
+  const void* pk(const void* W) const { return m->pk(W); }
 };
 
 #define TRY(expr)                     \
@@ -266,15 +335,15 @@ int decoder_layer(const Ctx& c, const tandem_decoder_desc& D, const tandem_layer
        *h = c.at<>(c.plan.h), *gws = c.at<>(c.plan.gemm_ws);
   const int nqkv = (D.Hq + 2 * D.Hkv) * D.dh, nq = D.Hq * D.dh;
   TRY(launch_rmsnorm(x, w.g_attn, xn, rows, D.d, c.eps, c.dtype, c.stream));
-  TRY(gemm(xn, D.d, w.Wqkv, nullptr, nullptr, 0, qkv, nqkv, rows, nqkv, D.d, TANDEM_ACT_NONE, c.dtype, gws,
+  TRY(gemm(xn, D.d, w.Wqkv, c.pk(w.Wqkv), nullptr, nullptr, 0, qkv, nqkv, rows, nqkv, D.d, TANDEM_ACT_NONE, c.dtype, gws,
            c.plan.gemm_ws_bytes, c.stream));
   TRY(attn());
-  TRY(gemm(att, nq, w.Wo, nullptr, x, D.d, x, D.d, rows, D.d, nq, TANDEM_ACT_NONE, c.dtype, gws, c.plan.gemm_ws_bytes,
+  TRY(gemm(att, nq, w.Wo, c.pk(w.Wo), nullptr, x, D.d, x, D.d, rows, D.d, nq, TANDEM_ACT_NONE, c.dtype, gws, c.plan.gemm_ws_bytes,
            c.stream));
   TRY(launch_rmsnorm(x, w.g_mlp, xn, rows, D.d, c.eps, c.dtype, c.stream));
-  TRY(gemm(xn, D.d, w.W1, w.b1, nullptr, 0, h, D.d_ff, rows, D.d_ff, D.d, TANDEM_ACT_GELU, c.dtype, gws,
+  TRY(gemm(xn, D.d, w.W1, c.pk(w.W1), w.b1, nullptr, 0, h, D.d_ff, rows, D.d_ff, D.d, TANDEM_ACT_GELU, c.dtype, gws,
            c.plan.gemm_ws_bytes, c.stream));
-  TRY(gemm(h, D.d_ff, w.W2, w.b2, x, D.d, x, D.d, rows, D.d, D.d_ff, TANDEM_ACT_NONE, c.dtype, gws, c.plan.gemm_ws_bytes,
+  TRY(gemm(h, D.d_ff, w.W2, c.pk(w.W2), w.b2, x, D.d, x, D.d, rows, D.d, D.d_ff, TANDEM_ACT_NONE, c.dtype, gws, c.plan.gemm_ws_bytes,
            c.stream));
   return TANDEM_OK;
 }
@@ -289,15 +358,15 @@ int decoder_layer_fused(const Ctx& c, const tandem_decoder_desc& D, const tandem
   float* gws = c.at<float>(c.plan.gemm_ws);
   const size_t gwb = c.plan.gemm_ws_bytes;
   const int nqkv = (D.Hq + 2 * D.Hkv) * D.dh, nq = D.Hq * D.dh;
-  TRY(gemm_deferred(xn, D.d, w.Wqkv, rows, nqkv, D.d, c.dtype, gws, gwb, c.stream));
-  TRY(finish_qkv(gws, gemm_splits(rows, nqkv, D.d)));
+  TRY(gemm_deferred(xn, D.d, w.Wqkv, c.pk(w.Wqkv), rows, nqkv, D.d, c.dtype, gws, gwb, c.stream));
+  TRY(finish_qkv(gws, gemm_splits(rows, nqkv, D.d, c.pk(w.Wqkv) != nullptr)));
   TRY(attn());
-  TRY(gemm_deferred(att, nq, w.Wo, rows, D.d, nq, c.dtype, gws, gwb, c.stream));
-  TRY(launch_finish_norm(gws, gemm_splits(rows, D.d, nq), nullptr, x, x, w.g_mlp, xn, rows, D.d, c.eps, c.dtype,
+  TRY(gemm_deferred(att, nq, w.Wo, c.pk(w.Wo), rows, D.d, nq, c.dtype, gws, gwb, c.stream));
+  TRY(launch_finish_norm(gws, gemm_splits(rows, D.d, nq, c.pk(w.Wo) != nullptr), nullptr, x, x, w.g_mlp, xn, rows, D.d, c.eps, c.dtype,
                          c.stream));
-  TRY(gemm(xn, D.d, w.W1, w.b1, nullptr, 0, h, D.d_ff, rows, D.d_ff, D.d, TANDEM_ACT_GELU, c.dtype, gws, gwb, c.stream));
-  TRY(gemm_deferred(h, D.d_ff, w.W2, rows, D.d, D.d_ff, c.dtype, gws, gwb, c.stream));
-  TRY(launch_finish_norm(gws, gemm_splits(rows, D.d, D.d_ff), w.b2, x, x, g_next, xn, rows, D.d, c.eps, c.dtype,
+  TRY(gemm(xn, D.d, w.W1, c.pk(w.W1), w.b1, nullptr, 0, h, D.d_ff, rows, D.d_ff, D.d, TANDEM_ACT_GELU, c.dtype, gws, gwb, c.stream));
+  TRY(gemm_deferred(h, D.d_ff, w.W2, c.pk(w.W2), rows, D.d, D.d_ff, c.dtype, gws, gwb, c.stream));
+  TRY(launch_finish_norm(gws, gemm_splits(rows, D.d, D.d_ff, c.pk(w.W2) != nullptr), w.b2, x, x, g_next, xn, rows, D.d, c.eps, c.dtype,
                          c.stream));
   return TANDEM_OK;
 }
@@ -305,7 +374,7 @@ int decoder_layer_fused(const Ctx& c, const tandem_decoder_desc& D, const tandem
 // logits and greedy token when c.xn already holds RMSNorm(x; g_final)
 int head_normed(const Ctx& c, const tandem_decoder_desc& D, int rows, int32_t* tok_out, int64_t tok_stride) {
   void *xn = c.at<>(c.plan.xn), *lg = c.at<>(c.plan.logits);
-  TRY(gemm(xn, D.d, D.W_out, nullptr, nullptr, 0, lg, D.vocab, rows, D.vocab, D.d, TANDEM_ACT_NONE, c.dtype,
+  TRY(gemm(xn, D.d, D.W_out, c.pk(D.W_out), nullptr, nullptr, 0, lg, D.vocab, rows, D.vocab, D.d, TANDEM_ACT_NONE, c.dtype,
            c.at<>(c.plan.gemm_ws), c.plan.gemm_ws_bytes, c.stream));
   return launch_argmax(lg, rows, D.vocab, tok_out, tok_stride, c.dtype, c.stream);
 }
@@ -313,7 +382,7 @@ int head_normed(const Ctx& c, const tandem_decoder_desc& D, int rows, int32_t* t
 int head(const Ctx& c, const tandem_decoder_desc& D, int rows, int32_t* tok_out, int64_t tok_stride) {
   void *x = c.at<>(c.plan.x), *xn = c.at<>(c.plan.xn), *lg = c.at<>(c.plan.logits);
   TRY(launch_rmsnorm(x, D.g_final, xn, rows, D.d, c.eps, c.dtype, c.stream));
-  TRY(gemm(xn, D.d, D.W_out, nullptr, nullptr, 0, lg, D.vocab, rows, D.vocab, D.d, TANDEM_ACT_NONE, c.dtype,
+  TRY(gemm(xn, D.d, D.W_out, c.pk(D.W_out), nullptr, nullptr, 0, lg, D.vocab, rows, D.vocab, D.d, TANDEM_ACT_NONE, c.dtype,
            c.at<>(c.plan.gemm_ws), c.plan.gemm_ws_bytes, c.stream));
   return launch_argmax(lg, rows, D.vocab, tok_out, tok_stride, c.dtype, c.stream);
 }
@@ -371,11 +440,36 @@ int tandem_model_create(const tandem_model_desc* desc, tandem_model** out) {
   m->d.S.layers = m->S_layers.data();
   m->d.ell = m->ell.data();
   m->d.ff = m->ff.data();
+  for (auto& f : m->ff) f.W1p = f.W2p = nullptr;  // the model packs for itself
+  if (desc->flags & TANDEM_MODEL_PACK_WEIGHTS) {
+    rc = pack_model(m);
+    if (rc != TANDEM_OK) {
+      tandem_model_destroy(m);
+      return rc;
+    }
+  }
   *out = m;
   return TANDEM_OK;
 }
 
-void tandem_model_destroy(tandem_model* m) { delete m; }
+void tandem_model_destroy(tandem_model* m) {
+  if (!m) return;
+  if (m->packed_buf) (void)hipFree(m->packed_buf);
+  delete m;
+}
+
+size_t tandem_packed_weight_bytes(int64_t N, int64_t K, int32_t dtype) {
+  if (N < 1 || K < 1 || !gemm_packable(N, K, dtype)) return 0;
+  return (size_t)N * K * elsize(dtype);
+}
+
+int tandem_pack_weight(const void* W, int64_t N, int64_t K, int32_t dtype, void* Wp, void* hip_stream) {
+  if (!W || !Wp) return TANDEM_ERR_NULL;
+  if (N < 1 || K < 1) return TANDEM_ERR_SHAPE;
+  if (!gemm_packable(N, K, dtype)) return TANDEM_ERR_UNSUPPORTED;
+  if (reinterpret_cast<uintptr_t>(W) % 16 != 0 || reinterpret_cast<uintptr_t>(Wp) % 16 != 0) return TANDEM_ERR_SHAPE;
+  return launch_pack_weights(W, Wp, N, K, (hipStream_t)hip_stream);
+}
 
 size_t tandem_decode_step_workspace(const tandem_model* m, int32_t B, int32_t gamma) {
   if (!m || B < 1 || gamma < 1 || gamma > TANDEM_MAX_QLEN) return 0;
@@ -507,29 +601,31 @@ int tandem_decode_step(const tandem_model* m, const tandem_state_desc* state, in
     void *yhat = c.at<>(c.plan.yhat), *xn = c.at<>(c.plan.xn), *kv = c.at<>(c.plan.kv), *gws = c.at<>(c.plan.gemm_ws);
     const void* xk = c.ws + c.plan.keep + j * c.plan.keep_stride;
     const void* Wkv = (const char*)S.layers[j].Wqkv + (size_t)S.Hq * S.dh * S.d * es;
+    const void* Wq_p = c.pk(S.layers[j].Wqkv);  // packed tiles hold 32 rows each: the K/V rows start on a tile
+    const void* Wkv_p = Wq_p && (S.Hq * S.dh) % 32 == 0 ? (const char*)Wq_p + (size_t)S.Hq * S.dh * S.d * es : nullptr;
     const int nkv = 2 * S.Hkv * S.dh;
     if (c.plan.fused) {
       const tandem_ff_desc& f = m->ff[j];
       float* part = (float*)gws;
       if (f.d_hidden > 0) {
         void* hb = c.at<>(c.plan.h);
-        TRY(gemm(xk, f.d_L, f.W1, f.b1, nullptr, 0, hb, f.d_hidden, M, f.d_hidden, f.d_L, f.act, c.dtype, gws,
+        TRY(gemm(xk, f.d_L, f.W1, f.W1p, f.b1, nullptr, 0, hb, f.d_hidden, M, f.d_hidden, f.d_L, f.act, c.dtype, gws,
                  c.plan.gemm_ws_bytes, c.stream));
-        TRY(gemm_deferred(hb, f.d_hidden, f.W2, M, f.d_S, f.d_hidden, c.dtype, gws, c.plan.gemm_ws_bytes, c.stream));
-        TRY(launch_finish_norm(part, gemm_splits(M, f.d_S, f.d_hidden), f.b2, nullptr, yhat, S.layers[j].g_attn, xn, M,
+        TRY(gemm_deferred(hb, f.d_hidden, f.W2, f.W2p, M, f.d_S, f.d_hidden, c.dtype, gws, c.plan.gemm_ws_bytes, c.stream));
+        TRY(launch_finish_norm(part, gemm_splits(M, f.d_S, f.d_hidden, f.W2p != nullptr), f.b2, nullptr, yhat, S.layers[j].g_attn, xn, M,
                                S.d, c.eps, c.dtype, c.stream));
       } else {
-        TRY(gemm_deferred(xk, f.d_L, f.W1, M, f.d_S, f.d_L, c.dtype, gws, c.plan.gemm_ws_bytes, c.stream));
-        TRY(launch_finish_norm(part, gemm_splits(M, f.d_S, f.d_L), f.b1, nullptr, yhat, S.layers[j].g_attn, xn, M, S.d,
+        TRY(gemm_deferred(xk, f.d_L, f.W1, f.W1p, M, f.d_S, f.d_L, c.dtype, gws, c.plan.gemm_ws_bytes, c.stream));
+        TRY(launch_finish_norm(part, gemm_splits(M, f.d_S, f.d_L, f.W1p != nullptr), f.b1, nullptr, yhat, S.layers[j].g_attn, xn, M, S.d,
                                c.eps, c.dtype, c.stream));
       }
-      TRY(gemm_deferred(xn, S.d, Wkv, M, nkv, S.d, c.dtype, gws, c.plan.gemm_ws_bytes, c.stream));
-      TRY(launch_finish_scatter(part, gemm_splits(M, nkv, S.d), nullptr, state->Khat[j], state->Vhat[j], state->n, 0, M,
+      TRY(gemm_deferred(xn, S.d, Wkv, Wkv_p, M, nkv, S.d, c.dtype, gws, c.plan.gemm_ws_bytes, c.stream));
+      TRY(launch_finish_scatter(part, gemm_splits(M, nkv, S.d, Wkv_p != nullptr), nullptr, state->Khat[j], state->Vhat[j], state->n, 0, M,
                                 gamma, S.Hq, S.Hkv, S.dh, state->T_max, 0, nkv, c.dtype, c.stream));
     } else {
       TRY(run_project(&m->ff[j], xk, yhat, M, gws, c.plan.gemm_ws_bytes, c.stream));
       TRY(launch_rmsnorm(yhat, S.layers[j].g_attn, xn, M, S.d, c.eps, c.dtype, c.stream));
-      TRY(gemm(xn, S.d, Wkv, nullptr, nullptr, 0, kv, nkv, M, nkv, S.d, TANDEM_ACT_NONE, c.dtype, gws,
+      TRY(gemm(xn, S.d, Wkv, Wkv_p, nullptr, nullptr, 0, kv, nkv, M, nkv, S.d, TANDEM_ACT_NONE, c.dtype, gws,
                c.plan.gemm_ws_bytes, c.stream));
       TRY(launch_scatter_qkv(kv, nullptr, state->Khat[j], state->Vhat[j], state->n, 0, M, gamma, S.Hq, S.Hkv, S.dh,
                              state->T_max, 0, 0, nkv, c.dtype, c.stream));

@@ -12,6 +12,10 @@
 // meet in LDS; the epilogue (bias, activation, residual, store) is fused when no split
 // across workgroups is needed.
 //
+// gemm_tile_kernel / gemm_stream_kernel (bf16, 32 < M <= 128 per pass): the same regime with the X rows
+// shared through LDS; the stream kernel reads weights re-laid out in contiguous operand tiles.
+// gemm_big_kernel (bf16, thousands of rows): 256 x 256 tiles, both operands through LDS, compute-bound.
+//
 // gemm_generic_kernel: any dtype / shape, LDS-tiled on the vector ALUs (the fp32
 // correctness path of the tiny configuration and odd shapes).
 #include "common.h"
@@ -26,6 +30,7 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 struct GemmParams {
   const void* X;
   const void* W;
+  const void* Wp;  // the same weights in the packed tile layout, or null
   const void* bias;
   const void* residual;
   void* Y;
@@ -46,6 +51,66 @@ __device__ __forceinline__ float epilogue(float v, int m, int n, const GemmParam
   v = apply_act(v, p.act);
   if (p.residual) v += to_f32<T>(((const T*)p.residual)[(long long)m * p.ldr + n]);
   return v;
+}
+
+// The MFMA kernels finish dozens of values per lane.  With the activation chosen at run time per value the
+// unrolled epilogue was a chain of branches around inlined erff bodies, larger than the instruction cache
+// (measured: 10 us per launch).  There the activation is a template argument, selected once per kernel by
+// ACT_SWITCH, and the erf of GELU is the branch-free rational-times-exponential form (Abramowitz & Stegun
+// 7.1.26, absolute error below 1.5e-7: three orders below bf16 resolution).
+__device__ __forceinline__ float erf_as(float x) {
+  const float ax = fabsf(x);
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, ax, 1.f));
+  float y = fmaf(1.061405429f, t, -1.453152027f);
+  y = fmaf(y, t, 1.421413741f);
+  y = fmaf(y, t, -0.284496736f);
+  y = fmaf(y, t, 0.254829592f);
+  y = 1.f - y * t * fast_exp2(-1.4426950408889634f * ax * ax);
+  return copysignf(y, x);
+}
+template <int ACT>
+__device__ __forceinline__ float act_fn(float v) {
+  if (ACT == TANDEM_ACT_GELU) return 0.5f * v * (1.f + erf_as(v * 0.70710678118654752f));
+  if (ACT == TANDEM_ACT_RELU) return fmaxf(v, 0.f);
+  return v;
+}
+#define ACT_SWITCH(act, BODY)                         \
+  switch (act) {                                      \
+    case TANDEM_ACT_GELU: {                           \
+      constexpr int ACT = TANDEM_ACT_GELU;            \
+      BODY                                            \
+    } break;                                          \
+    case TANDEM_ACT_RELU: {                           \
+      constexpr int ACT = TANDEM_ACT_RELU;            \
+      BODY                                            \
+    } break;                                          \
+    default: {                                        \
+      constexpr int ACT = TANDEM_ACT_NONE;            \
+      BODY                                            \
+    }                                                 \
+  }
+
+// bf16 store of one 32 x 32 MFMA result tile whose lanes hold a feature each (X rows were the A-operand):
+// lane (c, h) has feature n and rows mbase + 8 * (r / 4) + 4 * h + r % 4.  Neighbouring lanes (features n,
+// n ^ 1) trade one value per pair of rows, so that every lane stores two adjacent features of one row as a
+// 4-byte word and a store instruction covers 64-byte row segments.  bn: bias of feature n (0 without).
+template <int ACT>
+__device__ __forceinline__ void store_tile_bf16(const f32x16& acc, int mbase, int n, int h, float bn, const GemmParams& p) {
+  const bool odd = n & 1;
+#pragma unroll
+  for (int r = 0; r < 16; r += 2) {
+    const int m = mbase + 8 * (r >> 2) + 4 * h + (r & 3);  // rows m (value r) and m + 1 (value r + 1)
+    float v0 = act_fn<ACT>(acc[r] + bn), v1 = act_fn<ACT>(acc[r + 1] + bn);
+    if (p.residual) {
+      const int mc = m < p.M ? m : p.M - 1, mc1 = m + 1 < p.M ? m + 1 : p.M - 1;
+      v0 += bf16_to_f32(((const bf16_t*)p.residual)[(long long)mc * p.ldr + n]);
+      v1 += bf16_to_f32(((const bf16_t*)p.residual)[(long long)mc1 * p.ldr + n]);
+    }
+    const float got = dpp_f32<0xB1>(odd ? v0 : v1);  // from lane ^ 1
+    const uint32_t word = odd ? pack_bf16x2(got, v1) : pack_bf16x2(v0, got);
+    const int row = odd ? m + 1 : m;
+    if (row < p.M) *reinterpret_cast<uint32_t*>((bf16_t*)p.Y + (long long)row * p.ldy + (n & ~1)) = word;
+  }
 }
 
 __device__ __forceinline__ bf16x8 ldg8(const bf16_t* p) {
@@ -174,28 +239,40 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(GemmParams p) {
   if (w != 0) return;
 
   // C layout of the 32x32 tile: lane holds column j = lane%32 (row m of X), rows i = 8*(r/4) + 4*(lane/32) + r%4 (n)
+  if (p.splitK > 1 || p.defer) {
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt) {
-    const int m = m0 + mt * 32 + c32;
-    if (m >= p.M) continue;
+    for (int mt = 0; mt < MT; ++mt) {
+      const int m = m0 + mt * 32 + c32;
+      if (m >= p.M) continue;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int n = n0 + 8 * q + 4 * h;
-      if (p.splitK > 1 || p.defer) {
-        float* dst = p.part + ((long long)blockIdx.y * p.M + m) * p.N + n;
+      for (int q = 0; q < 4; ++q) {
+        float* dst = p.part + ((long long)blockIdx.y * p.M + m) * p.N + n0 + 8 * q + 4 * h;
         *reinterpret_cast<float4*>(dst) =
             make_float4(acc[mt][4 * q], acc[mt][4 * q + 1], acc[mt][4 * q + 2], acc[mt][4 * q + 3]);
-      } else {
+      }
+    }
+    return;
+  }
+  ACT_SWITCH(p.act, {
+    _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) {
+      const int m = m0 + mt * 32 + c32;
+      if (m >= p.M) continue;
+      _Pragma("unroll") for (int q = 0; q < 4; ++q) {
+        const int n = n0 + 8 * q + 4 * h;
         float v[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) v[i] = epilogue<bf16_t>(acc[mt][4 * q + i], m, n + i, p);
+        _Pragma("unroll") for (int i = 0; i < 4; ++i) {
+          v[i] = acc[mt][4 * q + i];
+          if (p.bias) v[i] += bf16_to_f32(((const bf16_t*)p.bias)[n + i]);
+          v[i] = act_fn<ACT>(v[i]);
+          if (p.residual) v[i] += bf16_to_f32(((const bf16_t*)p.residual)[(long long)m * p.ldr + n + i]);
+        }
         uint2 u;
         u.x = pack_bf16x2(v[0], v[1]);
         u.y = pack_bf16x2(v[2], v[3]);
         *reinterpret_cast<uint2*>((bf16_t*)p.Y + (long long)m * p.ldy + n) = u;
       }
     }
-  }
+  })
 }
 
 // ---------------------------------------------------------------- tile bf16 MFMA kernel (32 < M <= 128 per pass)
@@ -327,28 +404,275 @@ __global__ __launch_bounds__(512) void gemm_tile_kernel(GemmParams p) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[mt][r] += red[((ng * MT + mt) * 16 + r) * 64 + lane];
 
+  if (p.splitK > 1 || p.defer) {
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt) {
-    const int m = m0 + mt * 32 + c32;
-    if (m >= p.M) continue;
+    for (int mt = 0; mt < MT; ++mt) {
+      const int m = m0 + mt * 32 + c32;
+      if (m >= p.M) continue;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int n = n0 + 8 * q + 4 * h;
-      if (p.splitK > 1 || p.defer) {
-        float* dst = p.part + ((long long)blockIdx.y * p.M + m) * p.N + n;
+      for (int q = 0; q < 4; ++q) {
+        float* dst = p.part + ((long long)blockIdx.y * p.M + m) * p.N + n0 + 8 * q + 4 * h;
         *reinterpret_cast<float4*>(dst) =
             make_float4(acc[mt][4 * q], acc[mt][4 * q + 1], acc[mt][4 * q + 2], acc[mt][4 * q + 3]);
-      } else {
+      }
+    }
+    return;
+  }
+  ACT_SWITCH(p.act, {
+    _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) {
+      const int m = m0 + mt * 32 + c32;
+      if (m >= p.M) continue;
+      _Pragma("unroll") for (int q = 0; q < 4; ++q) {
+        const int n = n0 + 8 * q + 4 * h;
         float v[4];
-#pragma unroll
-        for (int ii = 0; ii < 4; ++ii) v[ii] = epilogue<bf16_t>(acc[mt][4 * q + ii], m, n + ii, p);
+        _Pragma("unroll") for (int i = 0; i < 4; ++i) {
+          v[i] = acc[mt][4 * q + i];
+          if (p.bias) v[i] += bf16_to_f32(((const bf16_t*)p.bias)[n + i]);
+          v[i] = act_fn<ACT>(v[i]);
+          if (p.residual) v[i] += bf16_to_f32(((const bf16_t*)p.residual)[(long long)m * p.ldr + n + i]);
+        }
         uint2 u;
         u.x = pack_bf16x2(v[0], v[1]);
         u.y = pack_bf16x2(v[2], v[3]);
         *reinterpret_cast<uint2*>((bf16_t*)p.Y + (long long)m * p.ldy + n) = u;
       }
     }
+  })
+}
+
+// ---------------------------------------------------------------- stream bf16 MFMA kernel (packed weights)
+// The decode-time regime again (32 < M <= 128 rows per pass, bound by reading every weight once), for
+// weights re-laid out by pack_weights_kernel: one 4 KB tile per (32 features, 64-deep stage), inside it
+// [j = 0..3][lane = 0..63][8 values] with lane = 32 * h + c holding W[32 * nb + c][64 * kb + 32 * h + 8 * j ..],
+// the A-operand of the j-th v_mfma_f32_32x32x16_bf16 of the stage.  Every load instruction of a wavefront
+// then reads 1 KB of consecutive addresses and a wavefront walks one contiguous stream.
+//
+// grid (N/128, splitK, row passes), 8 wavefronts with two roles:
+//   wavefronts 0-3 (multipliers) own 32 features each; their only global loads are their weight tiles, three
+//     stages ahead in a ring of four register sets (contiguous per-wavefront streams reach the HBM rate with
+//     one or two stages in flight: measured).
+//   wavefronts 4-7 (feeders) bring the X rows of each stage into LDS for all four multipliers (coalesced
+//     16-byte loads eight stages ahead, row pitch 144 B for conflict-free operand reads).
+// Separate roles keep the two load streams apart: a wavefront's loads complete in issue order, so one that
+// waits for cache-resident X rows also waits for every HBM weight load issued before them.  One workgroup
+// barrier per stage hands an X buffer over.  X rows are the MFMA A-operand, so a lane ends up holding one
+// feature for 16 rows per tile and stores cover whole row segments.
+// Measured at M = 128, N = 32768, K = 4096 (268 MB of weights): the main loop runs at the HBM rate (about
+// 38 us); launch, the first loads, uneven finishing times of the workgroups and the output stores add some
+// 25 us.  Requires N % 128 == 0, K % 256 == 0, at least four stages per split.
+constexpr int SK = 64;       // contraction depth of a stage
+constexpr int XPS = SK + 8;  // LDS row pitch in bf16 elements
+
+template <int MT>
+__global__ __launch_bounds__(512) void gemm_stream_kernel(GemmParams p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int lane = threadIdx.x & 63;
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int m0 = blockIdx.z * (32 * MT);
+  const int T = (p.K / SK) / p.splitK;  // stages of this workgroup
+  const int sb = blockIdx.y * T;
+  const int rot = (int)((blockIdx.x * 5 + blockIdx.y * 3) % T);
+  constexpr int TILE = (32 * MT) * XPS;  // elements of one X buffer
+  bf16_t* xs = reinterpret_cast<bf16_t*>(smem);  // [2][32*MT][XPS]
+
+  // global stage index of the i-th stage (rotated start; past the end: re-read the last)
+#define SG_STAGE(i, st_)                 \
+  long long st_;                         \
+  {                                      \
+    int r_ = (i) < T ? (i) : T - 1;      \
+    r_ += rot;                           \
+    r_ = r_ >= T ? r_ - T : r_;          \
+    st_ = (long long)(sb + r_);          \
   }
+
+  if (w >= 4) {
+    // ---------------- feeder: X rows of stage s+1 into LDS buffer (s+1)&1 while stage s is multiplied
+    const int tl = threadIdx.x - 256;
+    // piece id = tl + 256*q -> row (tl>>3) + 32*q, 16-byte column tl&7
+    const int xrow0 = tl >> 3, xcol = tl & 7;
+    const bf16_t* xbase = (const bf16_t*)p.X + xcol * 8;
+    bf16_t* xdst0 = xs + xrow0 * XPS + xcol * 8;
+    u32x4 x0[MT], x1[MT], x2[MT], x3[MT], x4[MT], x5[MT], x6[MT], x7[MT];
+#define SG_XLOAD(xr, i)                                                                    \
+  {                                                                                        \
+    SG_STAGE(i, st_)                                                                       \
+    _Pragma("unroll") for (int q = 0; q < MT; ++q) {                                       \
+      int m_ = m0 + xrow0 + 32 * q;                                                        \
+      m_ = m_ < p.M ? m_ : p.M - 1;                                                        \
+      xr[q] = *reinterpret_cast<const u32x4*>(xbase + (long long)m_ * p.ldx + st_ * SK);   \
+    }                                                                                      \
+    __builtin_amdgcn_sched_barrier(0);                                                     \
+  }
+#define SG_XSTORE(xr, buf)                                                                 \
+  {                                                                                        \
+    _Pragma("unroll") for (int q = 0; q < MT; ++q)                                         \
+        *reinterpret_cast<u32x4*>(xdst0 + (buf) * TILE + q * 32 * XPS) = xr[q];            \
+  }
+    // step s: request X(s+8) into the set parked one step ago, park X(s+1)
+#define SG_FEED(s, xload, xstore, buf) \
+  SG_XLOAD(xload, (s) + 8)             \
+  SG_XSTORE(xstore, buf)               \
+  __syncthreads();
+    SG_XLOAD(x0, 0)
+    SG_XLOAD(x1, 1)
+    SG_XLOAD(x2, 2)
+    SG_XLOAD(x3, 3)
+    SG_XLOAD(x4, 4)
+    SG_XLOAD(x5, 5)
+    SG_XLOAD(x6, 6)
+    SG_XLOAD(x7, 7)
+    SG_XSTORE(x0, 0)
+    __syncthreads();
+    int s = 0;
+    for (; s + 8 <= T; s += 8) {
+      SG_FEED(s, x0, x1, 1)
+      SG_FEED(s + 1, x1, x2, 0)
+      SG_FEED(s + 2, x2, x3, 1)
+      SG_FEED(s + 3, x3, x4, 0)
+      SG_FEED(s + 4, x4, x5, 1)
+      SG_FEED(s + 5, x5, x6, 0)
+      SG_FEED(s + 6, x6, x7, 1)
+      SG_FEED(s + 7, x7, x0, 0)
+    }
+    if (s < T) {
+      SG_FEED(s, x0, x1, 1)
+      if (s + 1 < T) {
+        SG_FEED(s + 1, x1, x2, 0)
+        if (s + 2 < T) {
+          SG_FEED(s + 2, x2, x3, 1)
+          if (s + 3 < T) {
+            SG_FEED(s + 3, x3, x4, 0)
+            if (s + 4 < T) {
+              SG_FEED(s + 4, x4, x5, 1)
+              if (s + 5 < T) {
+                SG_FEED(s + 5, x5, x6, 0)
+                if (s + 6 < T) { SG_FEED(s + 6, x6, x7, 1) }
+              }
+            }
+          }
+        }
+      }
+    }
+#undef SG_XLOAD
+#undef SG_XSTORE
+#undef SG_FEED
+    return;
+  }
+
+  // ---------------- multiplier
+  const int c32 = lane & 31, h = lane >> 5;
+  const int n0 = blockIdx.x * 128 + w * 32;
+  const bf16_t* wp = (const bf16_t*)p.Wp + (long long)(n0 >> 5) * 32 * p.K + lane * 8;
+  const bf16_t* xb0 = xs + c32 * XPS + 32 * h;
+  f32x16 acc[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[mt][r] = 0.f;
+  bf16x8 a0[4], a1[4], a2[4], a3[4];
+  bf16x8 b0[2][MT], b1[2][MT];  // B-operands of the first / second half (j = 0,1 / 2,3) of a stage
+#pragma unroll
+  for (int j = 0; j < 4; ++j) a3[j] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) b1[j][mt] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+#define SG_WLOAD(a, i)                                                                         \
+  {                                                                                            \
+    SG_STAGE(i, st_)                                                                           \
+    __builtin_amdgcn_sched_barrier(0);                                                         \
+    _Pragma("unroll") for (int j = 0; j < 4; ++j) a[j] = ldg8(wp + st_ * (32 * SK) + 512 * j); \
+    __builtin_amdgcn_sched_barrier(0);                                                         \
+  }
+#define SG_READ(b, buf, half)                                                                  \
+  {                                                                                            \
+    _Pragma("unroll") for (int j = 0; j < 2; ++j) _Pragma("unroll") for (int mt = 0; mt < MT; ++mt)  \
+        b[j][mt] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(                 \
+                                                  xb0 + (buf) * TILE + mt * 32 * XPS + 8 * (2 * (half) + j))); \
+    __builtin_amdgcn_sched_barrier(0);                                                         \
+  }
+#define SG_MMA(a, b, half)                                                                     \
+  {                                                                                            \
+    _Pragma("unroll") for (int j = 0; j < 2; ++j) _Pragma("unroll") for (int mt = 0; mt < MT; ++mt)  \
+        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j][mt], a[2 * (half) + j], acc[mt], 0, 0, 0); \
+    __builtin_amdgcn_sched_barrier(0);                                                         \
+  }
+  // A wavefront is alone on its SIMD and an LDS read returns 1 KB in about as many cycles as an MFMA takes,
+  // so reads and MFMAs are interleaved by hand, half a stage apart: while the 8 operand reads of one half
+  // return, the 8 MFMAs of the half before it run.  The second half of a stage is multiplied after the
+  // barrier that ends the stage (its operands are in registers by then), under the reads of the next stage.
+  // step s: aprev = weights of stage s-1 (its set is refilled with W(s+3) once its last MFMAs are issued)
+#define SG_MUL(s, acur, aprev, buf)       \
+  SG_READ(b0, buf, 0)                     \
+  SG_MMA(aprev, b1, 1)                    \
+  SG_WLOAD(aprev, (s) + 3)                \
+  SG_READ(b1, buf, 1)                     \
+  SG_MMA(acur, b0, 0)                     \
+  __syncthreads();
+  SG_WLOAD(a0, 0)
+  SG_WLOAD(a1, 1)
+  SG_WLOAD(a2, 2)
+  __syncthreads();
+  int s = 0;
+  for (; s + 4 <= T; s += 4) {  // no branch inside
+    SG_MUL(s, a0, a3, 0)
+    SG_MUL(s + 1, a1, a0, 1)
+    SG_MUL(s + 2, a2, a1, 0)
+    SG_MUL(s + 3, a3, a2, 1)
+  }
+  if (s < T) {
+    SG_MUL(s, a0, a3, 0)
+    if (s + 1 < T) {
+      SG_MUL(s + 1, a1, a0, 1)
+      if (s + 2 < T) {
+        SG_MUL(s + 2, a2, a1, 0)
+        SG_MMA(a2, b1, 1)
+      } else {
+        SG_MMA(a1, b1, 1)
+      }
+    } else {
+      SG_MMA(a0, b1, 1)
+    }
+  } else {
+    SG_MMA(a3, b1, 1)
+  }
+#undef SG_READ
+#undef SG_MMA
+#undef SG_STAGE
+#undef SG_WLOAD
+#undef SG_MUL
+
+  // X rows are the A-operand, so a lane holds feature n = n0 + c32 for the rows 8 * (r / 4) + 4 * h + r % 4 of
+  // each 32-row tile: a store instruction covers whole 128-byte (fp32) or 64-byte (bf16) row segments.
+  const int n = n0 + c32;
+  if (p.splitK > 1 || p.defer) {
+    float* dst = p.part + (long long)blockIdx.y * p.M * p.N + n;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = m0 + mt * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+        if (m < p.M) dst[(long long)m * p.N] = acc[mt][r];
+      }
+    return;
+  }
+  const float bn = p.bias ? bf16_to_f32(((const bf16_t*)p.bias)[n]) : 0.f;
+  ACT_SWITCH(p.act, {
+    _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) store_tile_bf16<ACT>(acc[mt], m0 + mt * 32, n, h, bn, p);
+  })
+}
+
+// Re-lays W[N, K] (bf16, row-major) out in the 4 KB tiles the stream kernel reads: one thread per 16 bytes
+// of output.  Requires N % 32 == 0, K % 64 == 0.
+__global__ void pack_weights_kernel(const bf16_t* __restrict__ W, bf16_t* __restrict__ Wp, long long N, long long K) {
+  const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;  // output piece
+  if (t >= N * K / 8) return;
+  const int lane = (int)(t & 63), j = (int)((t >> 6) & 3);
+  const long long tile = t >> 8, kbs = K / SK;
+  const long long nb = tile / kbs, kb = tile - nb * kbs;
+  const int c = lane & 31, h = lane >> 5;
+  const uint4 v = *reinterpret_cast<const uint4*>(W + (32 * nb + c) * K + SK * kb + 32 * h + 8 * j);
+  *reinterpret_cast<uint4*>(Wp + t * 8) = v;
 }
 
 // ---------------------------------------------------------------- big-tile bf16 MFMA kernel (M >= 256)
@@ -472,22 +796,15 @@ __global__ __launch_bounds__(256, 1) void gemm_big_kernel(GemmParams p, int tile
 #undef BG_MFMA
 
   // C layout: lane holds column j = lane%32 (feature n), rows i = 8*(r/4) + 4*(lane/32) + r%4 (row m)
-#define BG_OUT(i, j)                                                                                      \
-  {                                                                                                       \
-    const int n_ = n0 + wn * 128 + (j) * 32 + c32;                                                        \
-    _Pragma("clang loop unroll(full)") for (int r = 0; r < 16; ++r) {                                     \
-      const int m_ = m0 + wm * 128 + (i) * 32 + 8 * (r >> 2) + 4 * h + (r & 3);                           \
-      if (m_ < p.M)                                                                                       \
-        ((bf16_t*)p.Y)[(long long)m_ * p.ldy + n_] = f32_to_bf16(epilogue<bf16_t>(acc[i][j][r], m_, n_, p)); \
-    }                                                                                                     \
+#define BG_OUT(i, j)                                                                              \
+  {                                                                                               \
+    const int n_ = n0 + wn * 128 + (j) * 32 + c32;                                                \
+    const float bn_ = p.bias ? bf16_to_f32(((const bf16_t*)p.bias)[n_]) : 0.f;                    \
+    store_tile_bf16<ACT>(acc[i][j], m0 + wm * 128 + (i) * 32, n_, h, bn_, p);                     \
+    __builtin_amdgcn_sched_barrier(0);                                                            \
   }
-#define BG_OUT_ROW(i)                                                       \
-  BG_OUT(i, 0) __builtin_amdgcn_sched_barrier(0); BG_OUT(i, 1) __builtin_amdgcn_sched_barrier(0); \
-  BG_OUT(i, 2) __builtin_amdgcn_sched_barrier(0); BG_OUT(i, 3) __builtin_amdgcn_sched_barrier(0);
-  BG_OUT_ROW(0)
-  BG_OUT_ROW(1)
-  BG_OUT_ROW(2)
-  BG_OUT_ROW(3)
+#define BG_OUT_ROW(i) BG_OUT(i, 0) BG_OUT(i, 1) BG_OUT(i, 2) BG_OUT(i, 3)
+  ACT_SWITCH(p.act, { BG_OUT_ROW(0) BG_OUT_ROW(1) BG_OUT_ROW(2) BG_OUT_ROW(3) })
 #undef BG_OUT_ROW
 #undef BG_OUT
 }
@@ -539,6 +856,20 @@ int launch_skinny(const GemmParams& p, int mpasses, hipStream_t st) {
 }
 
 template <int MT>
+int launch_stream(const GemmParams& p, int mpasses, hipStream_t st) {
+  const size_t lds_bytes = (size_t)2 * (32 * MT) * XPS * sizeof(bf16_t);
+  static bool attr_set = false;
+  if (!attr_set && lds_bytes > 48 * 1024) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_stream_kernel<MT>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
+      return TANDEM_ERR_HIP;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((gemm_stream_kernel<MT>), dim3(p.N / 128, p.splitK, mpasses), dim3(512), lds_bytes, st, p);
+  return hip_ok(hipGetLastError());
+}
+
+template <int MT>
 int launch_tile(const GemmParams& p, int mpasses, hipStream_t st) {
   const size_t xbytes = (size_t)2 * 2 * (32 * MT) * XPT * sizeof(bf16_t);
   const size_t rbytes = (size_t)4 * MT * 16 * 64 * sizeof(float);
@@ -576,14 +907,19 @@ bool skinny_ok(int M, int N, int K, int dtype, long long ldx) {
   return dtype == TANDEM_BF16 && N % 32 == 0 && K % 64 == 0 && ldx % 8 == 0 && M >= 1;
 }
 bool tile_ok(int M, int N, int K) { return M > 32 && N % 128 == 0 && K % (2 * KC) == 0; }
+bool stream_ok(int M, int N, int K) { return M > 32 && N % 128 == 0 && K % (4 * SK) == 0; }  // = gemm_packable
 
 // Split of the contraction across workgroups (a function of the shape only): used when the feature
 // tiles alone cannot occupy the 256 CUs.
-int gemm_splitk(int M, int N, int K) {
+int gemm_splitk(int M, int N, int K, bool packed) {
   const int mpasses = (M + 127) / 128;
   const int chunks = K / 64;
   int s = 1;
-  if (tile_ok(M, N, K)) {
+  if (packed && stream_ok(M, N, K)) {
+    // at most one workgroup per CU (a second round of workgroups would run alone), at least four stages each
+    const int tiles = (N / 128) * mpasses, stages = K / SK;
+    while (tiles * s * 2 <= 256 && s < 16 && stages % (2 * s) == 0 && stages / (2 * s) >= 4) s *= 2;
+  } else if (tile_ok(M, N, K)) {
     const int tiles = (N / 128) * mpasses, kc = K / KC;  // every split keeps an even number (>= 4) of chunks
     while (tiles * s < 200 && s < 16 && kc % (4 * s) == 0 && kc / (2 * s) >= 4) s *= 2;
   } else {
@@ -596,13 +932,24 @@ int gemm_splitk(int M, int N, int K) {
 }  // namespace
 
 bool gemm_can_defer(int M, int N, int K, int dtype, int64_t ldx) { return skinny_ok(M, N, K, dtype, ldx); }
-int gemm_splits(int M, int N, int K) { return gemm_splitk(M, N, K); }
-size_t gemm_deferred_workspace(int M, int N, int K) { return (size_t)gemm_splitk(M, N, K) * M * N * sizeof(float); }
+int gemm_splits(int M, int N, int K, bool packed) { return gemm_splitk(M, N, K, packed); }
+size_t gemm_deferred_workspace(int M, int N, int K) {
+  const int a = gemm_splitk(M, N, K, false), b = gemm_splitk(M, N, K, true);
+  return (size_t)(a > b ? a : b) * M * N * sizeof(float);
+}
+bool gemm_packable(int64_t N, int64_t K, int dtype) { return dtype == TANDEM_BF16 && N % 128 == 0 && K % (4 * SK) == 0; }
+int launch_pack_weights(const void* W, void* Wp, int64_t N, int64_t K, hipStream_t st) {
+  const long long pieces = N * K / 8;
+  hipLaunchKernelGGL(pack_weights_kernel, dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, st, (const bf16_t*)W,
+                     (bf16_t*)Wp, (long long)N, (long long)K);
+  return hip_ok(hipGetLastError());
+}
 
 size_t gemm_workspace(int M, int N, int K, int dtype) {
   if (!skinny_ok(M, N, K, dtype, 8)) return 0;
   if (big_ok(M, N, K)) return 0;
-  const int s = gemm_splitk(M, N, K);
+  const int a = gemm_splitk(M, N, K, false), b = gemm_splitk(M, N, K, true);
+  const int s = a > b ? a : b;
   return s > 1 ? (size_t)s * M * N * sizeof(float) : 0;
 }
 
@@ -610,6 +957,7 @@ int launch_gemm(const GemmArgs& g, hipStream_t st) {
   GemmParams p;
   p.X = g.X;
   p.W = g.W;
+  p.Wp = g.Wp;
   p.bias = g.bias;
   p.residual = g.residual;
   p.Y = g.Y;
@@ -627,12 +975,16 @@ int launch_gemm(const GemmArgs& g, hipStream_t st) {
   if (skinny_ok(g.M, g.N, g.K, g.dtype, g.ldx) && (reinterpret_cast<uintptr_t>(g.X) % 16 == 0) &&
       (reinterpret_cast<uintptr_t>(g.W) % 16 == 0) && (reinterpret_cast<uintptr_t>(g.Y) % 8 == 0) && g.ldy % 4 == 0) {
     if (big_ok(g.M, g.N, g.K) && !g.defer) return launch_big(p, st);
-    p.splitK = gemm_splitk(g.M, g.N, g.K);
+    const bool packed = g.Wp && stream_ok(g.M, g.N, g.K);
+    if (packed && reinterpret_cast<uintptr_t>(g.Wp) % 16 != 0) return TANDEM_ERR_SHAPE;
+    p.splitK = gemm_splitk(g.M, g.N, g.K, packed);
     if ((p.splitK > 1 || g.defer) && (size_t)p.splitK * g.M * g.N * sizeof(float) > g.ws_bytes) return TANDEM_ERR_WORKSPACE;
     const int mt = g.M <= 32 ? 1 : (g.M <= 64 ? 2 : 4);
     const int mpasses = (g.M + 32 * mt - 1) / (32 * mt);
     int rc;
-    if (tile_ok(g.M, g.N, g.K))
+    if (packed)
+      rc = mt == 2 ? launch_stream<2>(p, mpasses, st) : launch_stream<4>(p, mpasses, st);
+    else if (tile_ok(g.M, g.N, g.K))
       rc = mt == 2 ? launch_tile<2>(p, mpasses, st) : launch_tile<4>(p, mpasses, st);
     else if (mt == 1)
       rc = launch_skinny<1, 8>(p, mpasses, st);

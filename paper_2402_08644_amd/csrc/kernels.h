@@ -46,6 +46,7 @@ struct GemmArgs {
   const void* X;
   int64_t ldx;  // row stride of X in elements
   const void* W;
+  const void* Wp;        // W in the packed tile layout (launch_pack_weights) or nullptr; used when the shape allows
   const void* bias;      // [N] or nullptr
   const void* residual;  // [M, ldr] or nullptr
   int64_t ldr;
@@ -62,7 +63,9 @@ struct GemmArgs {
 size_t gemm_workspace(int M, int N, int K, int dtype);
 bool gemm_can_defer(int M, int N, int K, int dtype, int64_t ldx);  // deferred epilogue available for this shape
 size_t gemm_deferred_workspace(int M, int N, int K);
-int gemm_splits(int M, int N, int K);  // number of partials a deferred launch leaves
+int gemm_splits(int M, int N, int K, bool packed);  // number of partials a deferred launch leaves
+bool gemm_packable(int64_t N, int64_t K, int dtype);  // a packed copy of W[N, K] can be used
+int launch_pack_weights(const void* W, void* Wp, int64_t N, int64_t K, hipStream_t st);
 int launch_gemm(const GemmArgs& g, hipStream_t st);
 
 // ---------------------------------------------------------------- glue (glue.hip)

@@ -139,6 +139,37 @@ def test_decode_step_bf16_vs_oracle_on_random_caches(tb, gamma, B, n):
                 assert torch.equal(g[b, :, hi:].view(torch.int16), old[b, :, hi:].view(torch.int16)), f"{key}[{j}] rows past the block changed"
 
 
+@pytest.mark.parametrize("pack", [True, False])
+def test_decode_step_bf16_many_rows_packed_and_plain_weights(tb, pack):
+    """B * gamma = 48 rows: the verify pass and the K-hat / V-hat production run the 128-row weight-streaming
+    kernels, with the model's packed weight copies (pack) or the caller's row-major ones."""
+    torch, binding = tb
+    B, gamma, T_max = 12, 4, 96
+    W = small_bf16_pair(91)
+    T = inputs.as_f64(W)
+    n = [int(v) for v in np.random.default_rng(92).integers(0, T_max - gamma, B)]
+    pending = [int(v) for v in inputs.token_ids(93, (B,), 512)]
+    ost, host = oracle_state_from(T, B, T_max, 94, n, pending, "bf16")
+    model = binding.TandemModel(W, pack_weights=pack)
+    gst = upload_state(tb, model, B, T_max, gamma, host, n, pending)
+    forced_np = inputs.token_ids(95, (B, gamma), 512)
+    out = binding.tandem_decode_step(model, gst, gamma, forced=torch.tensor(forced_np, dtype=torch.int32).cuda(), aux=True)
+    torch.cuda.synchronize()
+    want = orc.decode_step(T, ost, gamma, forced=forced_np)
+    tol = 2e-2 * math.ceil(math.sqrt(2 + 1))
+    assert_rows_close(inputs.torch_to_f64(out["y_small"]), want["y_small"], tol=tol, what="y_small")
+    assert_rows_close(inputs.torch_to_f64(out["x_large"]), want["x_large"], tol=tol, what="x_large")
+    assert tokens_ok(out["draft"].cpu().numpy(), want["logits_S"])
+    assert tokens_ok(out["verify"].cpu().numpy(), want["logits_L"])
+    np.testing.assert_array_equal(gst.n.cpu().numpy(), ost["n"])
+    for b in range(B):
+        lo, hi = n[b], n[b] + gamma
+        for key in ("KL", "VL", "Khat", "Vhat"):
+            for j in range(len(host[key])):
+                g = getattr(gst, key)[j]
+                assert_rows_close(inputs.torch_to_f64(g[b, :, lo:hi]), ost[key][j][b, :, lo:hi], tol=tol, what=f"{key}[{j}] new rows")
+
+
 def test_decode_step_acceptance_rule_exact(tb):
     """Integer part of the step, bit-exact: with the drafter equal to the verifier and identity FF_Tandem every
     draft token is accepted; corrupting the small model's head makes the first token wrong, so exactly one

@@ -88,6 +88,71 @@ def test_project_decode_step_shape_and_no_bias(tb):
     assert_rows_close(inputs.torch_to_f64(out), want, what="project M=128")
 
 
+def test_pack_weight_layout(tb):
+    """The packed copy holds exactly the elements the header's formula names (bit-exact re-layout)."""
+    torch, binding = tb
+    N, K = 256, 512
+    W = inputs.normal(np.random.default_rng(5), (N, K), 1.0, "bf16")
+    Wp = binding.tandem_pack_weight(W.to_torch())
+    torch.cuda.synchronize()
+    got = Wp.view(torch.int16).cpu().numpy().reshape(-1)
+    src = W.to_torch().view(torch.int16).cpu().numpy()
+    want = np.empty(N * K, dtype=np.int16)
+    for nb in range(N // 32):
+        for kb in range(K // 64):
+            base = (nb * (K // 64) + kb) * 2048
+            tile = src[32 * nb:32 * nb + 32, 64 * kb:64 * kb + 64]  # [c, 32h + 8j + e]
+            t = tile.reshape(32, 2, 4, 8).transpose(2, 1, 0, 3)      # [j, h, c, e]
+            want[base:base + 2048] = t.reshape(-1)
+    assert np.array_equal(got, want)
+    assert binding.tandem_packed_weight_bytes(N, K, binding.BF16) == N * K * 2
+    assert binding.tandem_packed_weight_bytes(N + 32, K, binding.BF16) == 0
+    assert binding.tandem_packed_weight_bytes(N, K + 64, binding.BF16) == 0
+    assert binding.tandem_packed_weight_bytes(N, K, binding.F32) == 0
+    assert binding.tandem_pack_weight(torch.zeros(96, 512, dtype=torch.bfloat16, device="cuda")) is None
+
+
+@pytest.mark.parametrize(
+    "M,d_L,d_hidden,d_S,act",
+    [
+        (33, 512, 1024, 256, "relu"),
+        (64, 1024, 2048, 512, "gelu"),
+        (100, 512, 1024, 256, "gelu"),
+        (128, 1024, 0, 512, "gelu"),
+        (128, 256, 512, 128, "gelu"),     # two stages per contraction group: shorter than the pipeline
+        (128, 768, 1280, 384, "gelu"),    # stage counts that are not multiples of four
+        (200, 512, 1024, 256, "gelu"),    # more than one pass of 128 rows
+        (16, 512, 1024, 256, "gelu"),     # too few rows for the packed path: plain weights are used
+    ],
+)
+def test_project_parity_packed(tb, M, d_L, d_hidden, d_S, act):
+    """FF_Tandem reading weights in the packed layout: same product, same tolerance."""
+    torch, binding = tb
+    case = inputs.project_case(37, M, d_L, d_hidden, d_S, dtype="bf16", w_std=0.05, bias_std=0.1)
+    ff = {k: v.to_torch() for k, v in case.items() if k != "x"}
+    if "W1" in ff:
+        ff["act"] = act
+        ff["W1p"], ff["W2p"] = binding.tandem_pack_weight(ff["W1"]), binding.tandem_pack_weight(ff["W2"])
+        assert ff["W1p"] is not None and ff["W2p"] is not None
+    else:
+        ff["Wp"] = binding.tandem_pack_weight(ff["W"])
+        assert ff["Wp"] is not None
+    out = binding.tandem_project(ff, case["x"].to_torch())
+    torch.cuda.synchronize()
+    e = assert_rows_close(inputs.torch_to_f64(out), oracle(case, act), what="project packed")
+    print(f"project packed {M,d_L,d_hidden,d_S}: max rel err {e[0]:.2e}")
+
+
+def test_project_parity_config2_packed(tb):
+    torch, binding = tb
+    case = inputs.project_case(2, 64, 4096, 8192, 1024, dtype="bf16", w_std=0.02)
+    ff = {k: v.to_torch() for k, v in case.items() if k != "x"}
+    ff["W1p"], ff["W2p"] = binding.tandem_pack_weight(ff["W1"]), binding.tandem_pack_weight(ff["W2"])
+    out = binding.tandem_project(ff, case["x"].to_torch())
+    torch.cuda.synchronize()
+    assert_rows_close(inputs.torch_to_f64(out), oracle(case), what="project config 2 packed")
+
+
 def test_project_is_deterministic(tb):
     torch, binding = tb
     case = inputs.project_case(4, 64, 1024, 2048, 512, dtype="bf16")
@@ -106,14 +171,14 @@ def test_project_error_codes(tb):
     L = binding.lib()
     t = torch.zeros(1 << 16, dtype=torch.bfloat16, device="cuda")
     p = t.data_ptr()
-    d = binding.FFDesc(64, 128, 32, binding.ACT_GELU, binding.BF16, p, None, p, None)
+    d = binding.FFDesc(64, 128, 32, binding.ACT_GELU, binding.BF16, p, None, p, None, None, None)
     need = binding.tandem_project_workspace(d, 8)
     assert need >= 8 * 128 * 2
     assert L.tandem_project(C.byref(d), C.c_void_p(p), C.c_void_p(p), 8, C.c_void_p(p), need - 1, None) == binding.ERR_WORKSPACE
     assert L.tandem_project(C.byref(d), None, C.c_void_p(p), 8, C.c_void_p(p), need, None) == binding.ERR_NULL
     assert L.tandem_project(C.byref(d), C.c_void_p(p), C.c_void_p(p), 0, C.c_void_p(p), need, None) == binding.ERR_SHAPE
-    bad = binding.FFDesc(64, 128, 32, binding.ACT_GELU, binding.BF16, p, None, None, None)  # MLP form without W2
+    bad = binding.FFDesc(64, 128, 32, binding.ACT_GELU, binding.BF16, p, None, None, None, None, None)  # MLP form without W2
     assert L.tandem_project(C.byref(bad), C.c_void_p(p), C.c_void_p(p), 8, C.c_void_p(p), need, None) == binding.ERR_NULL
-    bad = binding.FFDesc(64, 128, 32, 7, binding.BF16, p, None, p, None)
+    bad = binding.FFDesc(64, 128, 32, 7, binding.BF16, p, None, p, None, None, None)
     assert L.tandem_project(C.byref(bad), C.c_void_p(p), C.c_void_p(p), 8, C.c_void_p(p), need, None) == binding.ERR_UNSUPPORTED
     torch.cuda.synchronize()
