@@ -209,10 +209,10 @@ def step_bytes(cfg):
     return draft + verify + ff
 
 
-def step_workload(torch, binding, inputs, cfg, seed=3):
+def step_workload(torch, binding, inputs, cfg, seed=3, pack_weights=True):
     B, g, ctx = cfg["B"], cfg["gamma"], cfg["ctx"]
     W = device_tandem_weights(inputs, cfg, seed)
-    model = binding.TandemModel(W)
+    model = binding.TandemModel(W, pack_weights=pack_weights)
     del W
     k = [seed * 7919]
 
@@ -327,6 +327,9 @@ def run_project_workload(torch, binding, inputs, args):
     ffs = [{"W1": inputs.device_normal((d_h, d_L), 700 + 2 * i, 0.02), "b1": torch.zeros(d_h, dtype=torch.bfloat16, device="cuda"),
             "W2": inputs.device_normal((d_S, d_h), 701 + 2 * i, 0.02), "b2": torch.zeros(d_S, dtype=torch.bfloat16, device="cuda"),
             "act": "gelu"} for i in range(R)]
+    if not args.plain_weights:  # weights are static: packed once, outside the timed region, as a deployed model holds them
+        for ff in ffs:
+            ff["W1p"], ff["W2p"] = binding.tandem_pack_weight(ff["W1"]), binding.tandem_pack_weight(ff["W2"])
     x = inputs.device_normal((M, d_L), 699, 1.0)
     y = torch.empty((M, d_S), dtype=torch.bfloat16, device="cuda")
     ws = binding.workspace(binding.tandem_project_workspace(binding.ff_desc(ffs[0]), M))
@@ -345,7 +348,7 @@ def run_project_workload(torch, binding, inputs, args):
         from parity import row_errors
 
         rows = min(M, 64)
-        ff64 = {k: (inputs.torch_to_f64(v) if hasattr(v, "shape") else v) for k, v in ffs[0].items()}
+        ff64 = {k: (inputs.torch_to_f64(v) if hasattr(v, "shape") else v) for k, v in ffs[0].items() if not k.endswith("p")}
         xs = inputs.torch_to_f64(x[:rows])
         t0 = time.perf_counter()
         want = orc.project(xs, ff64)
@@ -363,7 +366,7 @@ def run_project_workload(torch, binding, inputs, args):
         "metric": "FF_Tandem projection TFLOP/s (bf16 MFMA)", "value": tflops, "unit": "TFLOP/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{args.workload}: {desc}", "rotated_weight_sets": R, "frac_of_mfma_peak": tflops / MFMA_PEAK_TFLOPS,
+        "config": {"workload": f"{args.workload}: {desc}", "rotated_weight_sets": R, "packed_weights": not args.plain_weights, "frac_of_mfma_peak": tflops / MFMA_PEAK_TFLOPS,
                    "weight_stream_GBps": wbytes / (ms * 1e-3) / 1e9},
         "roofline": roof, "cpu_baseline": cpu,
     }
@@ -411,7 +414,7 @@ def run_kernel_workload(torch, binding, inputs, args):
 def run_step_workload(torch, binding, inputs, args):
     cfg = C3
     B, g, ctx = cfg["B"], cfg["gamma"], cfg["ctx"]
-    call, model, state, out = step_workload(torch, binding, inputs, cfg)
+    call, model, state, out = step_workload(torch, binding, inputs, cfg, pack_weights=not args.plain_weights)
     torch.cuda.synchronize()
     ms = _time_calls(torch, call, 1, args.steps, args.warmup, use_graph=not args.no_graph)
 
@@ -472,6 +475,8 @@ def main():
     ap.add_argument("--workload", default="c3_step", choices=sorted(WORKLOADS) + sorted(PROJECT_WORKLOADS) + ["c3_step"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
+    ap.add_argument("--plain-weights", action="store_true",
+                    help="read weights in the caller's row-major layout only (no packed copies)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run three plain 1 GiB device copies (known traffic) so that rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE readings of the same run can be scaled")
