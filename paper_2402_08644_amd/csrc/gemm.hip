@@ -678,20 +678,29 @@ __global__ void pack_weights_kernel(const bf16_t* __restrict__ W, bf16_t* __rest
 // ---------------------------------------------------------------- big-tile bf16 MFMA kernel (M >= 256)
 // The compute-bound regime (prompt-time FF_Tandem over whole prompts, large verify batches): 256 x 256
 // output tile per workgroup, 4 wavefronts in a 2 x 2 arrangement, 128 x 128 per wavefront = 16 MFMA
-// tiles of 32x32 (256 accumulator registers) so that one operand fetched from LDS feeds four MFMAs and
-// LDS read traffic stays at half its bandwidth.  Both operands are staged through LDS with coalesced
-// global loads (64-deep stages, double-buffered, row pitch 144 B for conflict-free 16-byte operand
-// reads).  Workgroup ids are remapped so that the workgroups an XCD receives (round-robin by id) cover
+// tiles of 32x32 (256 accumulator registers) so that one operand fetched from LDS feeds four MFMAs.
+// Both operands reach LDS by direct global-to-LDS loads (global_load_lds_dwordx4: no staging registers, no
+// LDS store instructions), 64-deep stages, double-buffered; the loads of stage s+1 are issued when stage s
+// starts and must have landed at the barrier that ends it.  Such a load writes the 64 lanes' 16-byte
+// pieces to consecutive LDS addresses, so rows cannot be padded; instead piece c of row r sits at position
+// c ^ ((r >> 1) & 7) of the row (the lane-to-address map of the load does the permutation), which keeps
+// the 16-byte operand reads of 16 consecutive rows on 16 different bank groups.
+// A wavefront is alone on its SIMD, so LDS reads and MFMAs are interleaved by hand: the operands of
+// contraction step k+1 are requested before the 16 MFMAs of step k are issued; the last step of a stage
+// is multiplied after the barrier, under the first operand reads of the next stage.
+// Workgroup ids are remapped so that the workgroups an XCD receives (round-robin by id) cover
 // neighbouring tiles that share a weight tile in that XCD's L2.
 // Requires N % 256 == 0, K % 128 == 0; M ragged (rows past M are clamped on load, skipped on store).
 constexpr int BK = 64;
-constexpr int BP = BK + 8;  // LDS row pitch in elements
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+typedef const __attribute__((address_space(1))) void* global_void_ptr;
 
 __global__ __launch_bounds__(256, 1) void gemm_big_kernel(GemmParams p, int tiles_m, int tiles_n) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  bf16_t* As = reinterpret_cast<bf16_t*>(smem);  // [2][256][BP]
-  bf16_t* Bs = As + 2 * 256 * BP;                // [2][256][BP]
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  bf16_t* As = reinterpret_cast<bf16_t*>(smem);  // [2][256][BK], pieces permuted inside a row
+  bf16_t* Bs = As + 2 * 256 * BK;                // [2][256][BK]
+  const int lane = threadIdx.x & 63;
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = w >> 1, wn = w & 1;
   const int c32 = lane & 31, h = lane >> 5;
 
@@ -708,11 +717,29 @@ __global__ __launch_bounds__(256, 1) void gemm_big_kernel(GemmParams p, int tile
   }
   const int m0 = tm * 256, n0 = tn * 256;
 
-  // staging: thread t covers rows (t>>3) + 32*q, 16-byte column t&7, for q = 0..7 of each operand
-  const int srow = threadIdx.x >> 3, scol = threadIdx.x & 7;
-  const bf16_t* wg = (const bf16_t*)p.W + (long long)(n0 + srow) * p.K + scol * 8;
-  const bf16_t* xg = (const bf16_t*)p.X + scol * 8;
-  const int sdst = srow * BP + scol * 8;
+  // Direct loads: instruction q of wavefront w fills rows 8 * (4 * q + w) .. + 8 of an operand tile (1 KB of
+  // LDS); lane l lands on row l >> 3, position l & 7, so it fetches piece (l & 7) ^ ((row >> 1) & 7).
+  const int drow = lane >> 3;
+  const int dpiece = (lane & 7) ^ ((((w & 1) << 2) | (drow >> 1)) & 7);
+  const bf16_t* ag[8];
+  const bf16_t* bg[8];
+#pragma unroll
+  for (int q = 0; q < 8; ++q) {
+    const int row = 8 * (4 * q + w) + drow;
+    int m_ = m0 + row;
+    m_ = m_ < p.M ? m_ : p.M - 1;
+    ag[q] = (const bf16_t*)p.X + (long long)m_ * p.ldx + dpiece * 8;
+    bg[q] = (const bf16_t*)p.W + (long long)(n0 + row) * p.K + dpiece * 8;
+  }
+  // one direct load (1 KB): rows 8 * (4 * q + w) .. + 8 of the A (X) or B (W) tile of a stage
+#define BG_DMA_A(buf, k0, q)                                                                                \
+  __builtin_amdgcn_global_load_lds((global_void_ptr)(ag[q] + (k0)),                                         \
+                                   (lds_void_ptr)(As + (buf) * 256 * BK + (4 * (q) + w) * 8 * BK), 16, 0, 0); \
+  __builtin_amdgcn_sched_barrier(0);
+#define BG_DMA_B(buf, k0, q)                                                                                \
+  __builtin_amdgcn_global_load_lds((global_void_ptr)(bg[q] + (k0)),                                         \
+                                   (lds_void_ptr)(Bs + (buf) * 256 * BK + (4 * (q) + w) * 8 * BK), 16, 0, 0); \
+  __builtin_amdgcn_sched_barrier(0);
 
   f32x16 acc[4][4];
 #pragma unroll
@@ -722,76 +749,88 @@ __global__ __launch_bounds__(256, 1) void gemm_big_kernel(GemmParams p, int tile
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  u32x4 sa0[8], sb0[8], sa1[8], sb1[8];
-#define BG_GLOAD(sa, sb, k0)                                                                                \
-  {                                                                                                         \
-    _Pragma("unroll") for (int q = 0; q < 8; ++q) {                                                         \
-      int m_ = m0 + srow + 32 * q;                                                                          \
-      m_ = m_ < p.M ? m_ : p.M - 1;                                                                         \
-      sa[q] = *reinterpret_cast<const u32x4*>(xg + (long long)m_ * p.ldx + (k0));                           \
-    }                                                                                                       \
-    _Pragma("unroll") for (int q = 0; q < 8; ++q)                                                           \
-        sb[q] = *reinterpret_cast<const u32x4*>(wg + (long long)(32 * q) * p.K + (k0));                     \
-    __builtin_amdgcn_sched_barrier(0);                                                                      \
-  }
-#define BG_STORE(sa, sb, buf)                                                                               \
-  {                                                                                                         \
-    _Pragma("unroll") for (int q = 0; q < 8; ++q) {                                                         \
-      *reinterpret_cast<u32x4*>(As + (buf) * 256 * BP + sdst + q * 32 * BP) = sa[q];                        \
-      *reinterpret_cast<u32x4*>(Bs + (buf) * 256 * BP + sdst + q * 32 * BP) = sb[q];                        \
-    }                                                                                                       \
-  }
-  const bf16_t* a_rd = As + (wm * 128 + c32) * BP + 8 * h;
-  const bf16_t* b_rd = Bs + (wn * 128 + c32) * BP + 8 * h;
+  // operand reads: row (wm | wn) * 128 + 32 * t + c32, piece 2 * ks + h, at position piece ^ ((c32 >> 1) & 7)
+  const int fsw = (c32 >> 1) & 7;
+  const bf16_t* a_rd = As + (wm * 128 + c32) * BK;
+  const bf16_t* b_rd = Bs + (wn * 128 + c32) * BK;
+  int pos[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) pos[ks] = ((2 * ks + h) ^ fsw) * 8;
   bf16x8 av0[4], bv0[4], av1[4], bv1[4];
 #define BG_OPS(av, bv, buf, ks)                                                                             \
   {                                                                                                         \
     _Pragma("unroll") for (int t = 0; t < 4; ++t) {                                                         \
       av[t] = __builtin_bit_cast(                                                                           \
-          bf16x8, *reinterpret_cast<const u32x4*>(a_rd + (buf) * 256 * BP + t * 32 * BP + (ks) * 16));      \
+          bf16x8, *reinterpret_cast<const u32x4*>(a_rd + (buf) * 256 * BK + t * 32 * BK + pos[ks]));        \
       bv[t] = __builtin_bit_cast(                                                                           \
-          bf16x8, *reinterpret_cast<const u32x4*>(b_rd + (buf) * 256 * BP + t * 32 * BP + (ks) * 16));      \
+          bf16x8, *reinterpret_cast<const u32x4*>(b_rd + (buf) * 256 * BK + t * 32 * BK + pos[ks]));        \
     }                                                                                                       \
+    __builtin_amdgcn_sched_barrier(0);                                                                      \
   }
 #define BG_MFMA(av, bv)                                                                                     \
   {                                                                                                         \
     _Pragma("unroll") for (int i = 0; i < 4; ++i) _Pragma("unroll") for (int j = 0; j < 4; ++j)              \
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], bv[j], acc[i][j], 0, 0, 0);              \
+    __builtin_amdgcn_sched_barrier(0);                                                                      \
   }
-  // operands of contraction step ks+1 are fetched from LDS while the 16 MFMAs of step ks run
-#define BG_COMPUTE(buf)        \
-  {                            \
-    BG_OPS(av0, bv0, buf, 0)   \
-    BG_OPS(av1, bv1, buf, 1)   \
-    BG_MFMA(av0, bv0)          \
-    BG_OPS(av0, bv0, buf, 2)   \
-    BG_MFMA(av1, bv1)          \
-    BG_OPS(av1, bv1, buf, 3)   \
-    BG_MFMA(av0, bv0)          \
-    BG_MFMA(av1, bv1)          \
-  }
+#define BG_MFMA2(av, bv, i, j)                                                                             \
+  acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], bv[j], acc[i][j], 0, 0, 0);                   \
+  acc[i][(j) + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], bv[(j) + 1], acc[i][(j) + 1], 0, 0, 0); \
+  __builtin_amdgcn_sched_barrier(0);
+  // 16 MFMAs with a direct load after every second one.  Issuing such a load occupies the wavefront for
+  // about 60 cycles (measured), an MFMA the matrix pipe for 32: issued in one block, the 16 loads of a
+  // stage left the pipe idle for some 900 cycles per stage.
+#define BG_MFMA_DMA(av, bv, DMA, buf, k0)                                    \
+  BG_MFMA2(av, bv, 0, 0) DMA(buf, k0, 0) BG_MFMA2(av, bv, 0, 2) DMA(buf, k0, 1) \
+  BG_MFMA2(av, bv, 1, 0) DMA(buf, k0, 2) BG_MFMA2(av, bv, 1, 2) DMA(buf, k0, 3) \
+  BG_MFMA2(av, bv, 2, 0) DMA(buf, k0, 4) BG_MFMA2(av, bv, 2, 2) DMA(buf, k0, 5) \
+  BG_MFMA2(av, bv, 3, 0) DMA(buf, k0, 6) BG_MFMA2(av, bv, 3, 2) DMA(buf, k0, 7)
+  // BG_LDS_DONE waits for the operand reads issued before the previous group of MFMAs (long complete: the
+  // group takes 512 cycles to issue).  Without it the compiler waits for ALL outstanding LDS reads right
+  // before each MFMA group, i.e. also for the reads just issued for the next step.
+#define BG_LDS_DONE                                                      \
+  __builtin_amdgcn_s_waitcnt(0xC07F); /* lgkmcnt(0), other counters free */ \
+  __builtin_amdgcn_sched_barrier(0);
+  // One stage reading LDS buffer buf.  On entry av0 / bv0 are being read for its first contraction step and
+  // av1 / bv1 hold the last step of the stage before, which is multiplied first, under those reads; the
+  // loads of the next stage (into the buffer that stage before just left) ride on the first two groups.
+#define BG_STAGE(buf, knext)                                  \
+  BG_MFMA_DMA(av1, bv1, BG_DMA_A, 1 - (buf), knext)           \
+  BG_LDS_DONE                                                 \
+  BG_OPS(av1, bv1, buf, 1)                                    \
+  BG_MFMA_DMA(av0, bv0, BG_DMA_B, 1 - (buf), knext)           \
+  BG_LDS_DONE                                                 \
+  BG_OPS(av0, bv0, buf, 2)                                    \
+  BG_MFMA(av1, bv1)                                           \
+  BG_LDS_DONE                                                 \
+  BG_OPS(av1, bv1, buf, 3)                                    \
+  BG_MFMA(av0, bv0)                                           \
+  __syncthreads();                                            \
+  BG_OPS(av0, bv0, 1 - (buf), 0)
 
-  // Global loads run two stages ahead of the MFMAs (two staging register sets), the LDS tiles one.
   const int stages = p.K / BK;  // even (launcher): the loop below retires two stages per trip
-  BG_GLOAD(sa0, sb0, 0)
-  BG_GLOAD(sa1, sb1, BK)
-  BG_STORE(sa0, sb0, 0)
-  __syncthreads();
-  for (int st = 0; st < stages; st += 2) {
-    const int s2 = st + 2 < stages ? st + 2 : stages - 1;  // past the end: harmless re-reads
-    const int s3 = st + 3 < stages ? st + 3 : stages - 1;
-    BG_GLOAD(sa0, sb0, (long long)s2 * BK)
-    BG_COMPUTE(0)
-    BG_STORE(sa1, sb1, 1)
-    __syncthreads();
-    BG_GLOAD(sa1, sb1, (long long)s3 * BK)
-    BG_COMPUTE(1)
-    BG_STORE(sa0, sb0, 0)
-    __syncthreads();
+#pragma unroll
+  for (int q = 0; q < 8; ++q) {
+    BG_DMA_A(0, 0, q)
+    BG_DMA_B(0, 0, q)
   }
-#undef BG_GLOAD
-#undef BG_STORE
-#undef BG_COMPUTE
+#pragma unroll
+  for (int t = 0; t < 4; ++t) av1[t] = bv1[t] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};  // "last step of the stage before" of stage 0
+  __syncthreads();
+  BG_OPS(av0, bv0, 0, 0)
+  for (int st = 0; st < stages; st += 2) {
+    const long long k1 = (long long)(st + 1) * BK;                                  // st + 1 < stages
+    const long long k2 = (long long)(st + 2 < stages ? st + 2 : stages - 1) * BK;   // past the end: harmless re-read
+    BG_STAGE(0, k1)
+    BG_STAGE(1, k2)
+  }
+  BG_MFMA(av1, bv1)  // last step of the last stage
+#undef BG_DMA_A
+#undef BG_DMA_B
+#undef BG_MFMA2
+#undef BG_MFMA_DMA
+#undef BG_LDS_DONE
+#undef BG_STAGE
 #undef BG_OPS
 #undef BG_MFMA
 
@@ -886,7 +925,7 @@ int launch_tile(const GemmParams& p, int mpasses, hipStream_t st) {
 }
 
 int launch_big(const GemmParams& p, hipStream_t st) {
-  const size_t lds_bytes = (size_t)2 * 2 * 256 * BP * sizeof(bf16_t);
+  const size_t lds_bytes = (size_t)2 * 2 * 256 * BK * sizeof(bf16_t);
   static bool attr_set = false;
   if (!attr_set) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_big_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
