@@ -39,12 +39,14 @@ struct BlockParams {
 __device__ __forceinline__ bf16x8 ld_bf16x8(const bf16_t* p) {
   return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(p));
 }
+// probabilities -> bf16 in the hot loop: the integer-arithmetic rounding measured 5 % faster for the whole
+// kernel than the hardware conversion instruction here (same results)
 __device__ __forceinline__ bf16x8 pack8(const f32x4& a, const f32x4& b) {
   uint4 u;
-  u.x = pack_bf16x2(a[0], a[1]);
-  u.y = pack_bf16x2(a[2], a[3]);
-  u.z = pack_bf16x2(b[0], b[1]);
-  u.w = pack_bf16x2(b[2], b[3]);
+  u.x = pack_bf16x2_alu(a[0], a[1]);
+  u.y = pack_bf16x2_alu(a[2], a[3]);
+  u.z = pack_bf16x2_alu(b[0], b[1]);
+  u.w = pack_bf16x2_alu(b[2], b[3]);
   return __builtin_bit_cast(bf16x8, u);
 }
 __device__ __forceinline__ f32x4 mfma16(const bf16x8& a, const bf16x8& b, const f32x4& c) {
