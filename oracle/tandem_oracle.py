@@ -256,21 +256,24 @@ def attended_sets(i, gamma):
 # d_1..d_gamma as the *inputs* of the following small runs and that are all
 # treated as accepted (teacher forcing).  The state is updated in place.
 # ----------------------------------------------------------------------------
-def decode_step(T, state, gamma, forced=None):
+def decode_step(T, state, gamma, forced=None, free_token=False):
     eps = T["eps"]
     ML, MS = T["L"], T["S"]
     B = len(state["n"])
     LS, LL = len(MS["layers"]), len(ML["layers"])
+    # rows M_L processes: the block [pending, d_1 .. d_{gamma-1}], plus d_gamma when the bonus ("free")
+    # token of Sec. 3.1 / Fig. 2 is wanted
+    nq = gamma + 1 if free_token else gamma
     out = {
         "draft": np.zeros((B, gamma), np.int64),
-        "verify": np.zeros((B, gamma), np.int64),
+        "verify": np.zeros((B, nq), np.int64),
         "n_accepted": np.zeros(B, np.int64),
-        "tokens": -np.ones((B, gamma), np.int64),
+        "tokens": -np.ones((B, nq), np.int64),
         "n_emitted": np.zeros(B, np.int64),
         "y_small": np.zeros((B, gamma, MS["emb"].shape[1]), F64),
-        "x_large": np.zeros((B, gamma, ML["emb"].shape[1]), F64),
+        "x_large": np.zeros((B, nq, ML["emb"].shape[1]), F64),
         "logits_S": np.zeros((B, gamma, MS["W_out"].shape[0]), F64),
-        "logits_L": np.zeros((B, gamma, ML["W_out"].shape[0]), F64),
+        "logits_L": np.zeros((B, nq, ML["W_out"].shape[0]), F64),
     }
     for b in range(B):
         n = int(state["n"][b])
@@ -304,33 +307,33 @@ def decode_step(T, state, gamma, forced=None):
             d = argmax_lowest(lg)
             out["draft"][b, r] = d
             inputs.append(int(forced[b][r]) if forced is not None else d)
-        # ---- verify: M_L in block mode on [pending, d_1 .. d_{gamma-1}] ----
+        # ---- verify: M_L in block mode on the first nq tokens of [pending, d_1 .. d_gamma] ----
         Hq, Hkv, dh = ML["Hq"], ML["Hkv"], ML["dh"]
         G = Hq // Hkv
         scale = 1.0 / math.sqrt(dh)
-        x = np.asarray(ML["emb"], F64)[np.asarray(inputs[:gamma])]
+        x = np.asarray(ML["emb"], F64)[np.asarray(inputs[:nq])]
         xs = [x]
         for j, lay in enumerate(ML["layers"]):
             hn = rmsnorm(x, lay["g_attn"], eps)
-            q = _heads(linear(hn, lay["Wq"]), Hq, dh)
+            qh = _heads(linear(hn, lay["Wq"]), Hq, dh)
             k = _heads(linear(hn, lay["Wk"]), Hkv, dh)
             v = _heads(linear(hn, lay["Wv"]), Hkv, dh)
-            state["KL"][j][b, :, n : n + gamma] = k.transpose(1, 0, 2)
-            state["VL"][j][b, :, n : n + gamma] = v.transpose(1, 0, 2)
-            a = np.zeros((gamma, Hq, dh), F64)
-            for r in range(gamma):
+            state["KL"][j][b, :, n : n + nq] = k.transpose(1, 0, 2)
+            state["VL"][j][b, :, n : n + nq] = v.transpose(1, 0, 2)
+            a = np.zeros((nq, Hq, dh), F64)
+            for r in range(nq):
                 for h in range(Hq):
                     kv = h // G
                     a[r, h] = attention_one(
-                        q[r, h], state["KL"][j][b, kv, : n + r + 1], state["VL"][j][b, kv, : n + r + 1], scale
+                        qh[r, h], state["KL"][j][b, kv, : n + r + 1], state["VL"][j][b, kv, : n + r + 1], scale
                     )
-            x = x + linear(a.reshape(gamma, Hq * dh), lay["Wo"])
+            x = x + linear(a.reshape(nq, Hq * dh), lay["Wo"])
             x = x + mlp(rmsnorm(x, lay["g_mlp"], eps), lay)
             xs.append(x)
         out["x_large"][b] = x
         lgL = logits_of(ML, x, eps)
         out["logits_L"][b] = lgL
-        tL = [argmax_lowest(lgL[r]) for r in range(gamma)]
+        tL = [argmax_lowest(lgL[r]) for r in range(nq)]
         out["verify"][b] = tL
         # ---- FF_Tandem on the new rows, then the small layer's own norm and
         #      W_K / W_V turn y_hat into cached K_hat / V_hat (Eq. (2) line 1,
@@ -340,26 +343,33 @@ def decode_step(T, state, gamma, forced=None):
             hh = rmsnorm(yh, lay["g_attn"], eps)
             kh = _heads(linear(hh, lay["Wk"]), MS["Hkv"], MS["dh"])
             vh = _heads(linear(hh, lay["Wv"]), MS["Hkv"], MS["dh"])
-            state["Khat"][j][b, :, n : n + gamma] = kh.transpose(1, 0, 2)
-            state["Vhat"][j][b, :, n : n + gamma] = vh.transpose(1, 0, 2)
+            state["Khat"][j][b, :, n : n + nq] = kh.transpose(1, 0, 2)
+            state["Vhat"][j][b, :, n : n + nq] = vh.transpose(1, 0, 2)
         # ---- accept (Sec. 3.1: first location where the draft is wrong) ----
+        # Without the free token M_L has not seen d_gamma, so a fully accepted block emits gamma tokens and
+        # d_gamma stays pending.  With it, M_L's token after the accepted prefix is always emitted: a + 1
+        # tokens, the last of them the bonus token when all gamma drafts were right (Fig. 2).
         if forced is not None:
             a_cnt = gamma
             emitted = [int(t) for t in forced[b][:gamma]]
+            if free_token:
+                emitted.append(tL[gamma])
             new_pending = emitted[-1]
+            n_new = n + nq
         else:
             a_cnt = 0
             while a_cnt < gamma and out["draft"][b, a_cnt] == tL[a_cnt]:
                 a_cnt += 1
-            if a_cnt < gamma:
+            if a_cnt < gamma or free_token:
                 emitted = [int(t) for t in out["draft"][b, :a_cnt]] + [tL[a_cnt]]
             else:
                 emitted = [int(t) for t in out["draft"][b]]
             new_pending = emitted[-1]
+            n_new = n + (a_cnt + 1 if free_token else min(a_cnt + 1, gamma))
         out["n_accepted"][b] = a_cnt
         out["n_emitted"][b] = len(emitted)
         out["tokens"][b, : len(emitted)] = emitted
-        state["n"][b] = n + min(a_cnt + 1, gamma)
+        state["n"][b] = n_new
         state["pending"][b] = new_pending
     return out
 

@@ -262,6 +262,86 @@ def test_speed_stream_equals_greedy_large_decode(gamma, seed):
     assert got[:n_new] == want
 
 
+@pytest.mark.parametrize("gamma,seed", [(1, 0), (2, 1), (3, 2), (4, 3)])
+def test_speed_stream_with_free_token_equals_greedy_large_decode(gamma, seed):
+    """The same invariant with the bonus token (Fig. 2): M_L verifies gamma + 1 rows, every step emits
+    n_accepted + 1 tokens and advances n by as many, and the stream is still M_L's greedy stream."""
+    T = small_pair(seed=20 + seed, w_std=0.5)
+    P, n_new = 5, 9
+    prompt = inputs.token_ids(seed, (P,), 40)
+    want = orc.greedy_decode_large(T["L"], prompt, n_new, T["eps"])
+    st = orc.empty_state(T, 1, 64)
+    st["pending"][0] = prompt[0]
+    orc.decode_step(T, st, P - 1, forced=prompt[None, 1:])
+    got = []
+    while len(got) < n_new:
+        n0 = int(st["n"][0])
+        out = orc.decode_step(T, st, gamma, free_token=True)
+        a = int(out["n_accepted"][0])
+        assert int(out["n_emitted"][0]) == a + 1 and int(st["n"][0]) == n0 + a + 1
+        assert out["tokens"].shape == (1, gamma + 1) and out["verify"].shape == (1, gamma + 1)
+        assert int(st["pending"][0]) == int(out["verify"][0, a]) == int(out["tokens"][0, a])
+        assert (out["tokens"][0, a + 1:] == -1).all()
+        got += [int(t) for t in out["tokens"][0, : a + 1]]
+    assert got[:n_new] == want
+
+
+def test_free_token_step_is_a_longer_block_for_the_large_model():
+    """With forced tokens, a free-token step of gamma is M_L's block pass over gamma + 1 positions: it leaves
+    the caches of a plain step of gamma + 1 over the same tokens (M_S's drafts do not enter the caches), and
+    its bonus token is M_L's greedy token after them."""
+    T = small_pair(seed=31, w_std=0.5)
+    toks = inputs.token_ids(7, (1, 8), 40)
+    a, b = orc.empty_state(T, 1, 32), orc.empty_state(T, 1, 32)
+    a["pending"][0] = b["pending"][0] = toks[0, 0]
+    oa = orc.decode_step(T, a, 3, forced=toks[:, 1:4], free_token=True)           # rows 0..3
+    ob = orc.decode_step(T, b, 4, forced=toks[:, 1:5])                             # rows 0..3, token 4 pending
+    assert int(a["n"][0]) == int(b["n"][0]) == 4
+    for key in ("KL", "VL", "Khat", "Vhat"):
+        for j in range(len(a[key])):
+            np.testing.assert_allclose(a[key][j][:, :, :4], b[key][j][:, :, :4], rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(oa["x_large"], ob["x_large"], rtol=1e-12, atol=1e-12)
+    assert int(a["pending"][0]) == int(oa["verify"][0, 3]) == int(ob["verify"][0, 3])
+    assert [int(t) for t in oa["tokens"][0]] == [int(t) for t in toks[0, 1:4]] + [int(oa["verify"][0, 3])]
+
+
+def test_free_token_bonus_when_drafter_is_the_verifier():
+    """Drafter = verifier: all gamma drafts accepted and a bonus token follows, gamma + 1 tokens per step."""
+    W = inputs.tandem_weights(
+        5, vocab=30, large=dict(d=16, n_layers=2, Hq=2, Hkv=2, dh=8, d_ff=32),
+        small=dict(d=16, n_layers=2, Hq=2, Hkv=2, dh=8, d_ff=32), ell=(0, 1), d_hidden=0, dtype="f32", w_std=0.5)
+    T = inputs.as_f64(W)
+    T["S"] = T["L"]
+    for ff in T["ff"]:
+        ff["W"] = np.eye(16)
+    prompt = inputs.token_ids(1, (4,), 30)
+    st = orc.empty_state(T, 1, 64)
+    st["pending"][0] = prompt[0]
+    orc.decode_step(T, st, 3, forced=prompt[None, 1:])
+    for _ in range(3):
+        n0 = int(st["n"][0])
+        out = orc.decode_step(T, st, 3, free_token=True)
+        assert int(out["n_accepted"][0]) == 3 and int(out["n_emitted"][0]) == 4 and int(st["n"][0]) == n0 + 4
+        np.testing.assert_array_equal(out["draft"][0], out["verify"][0, :3])
+
+
+def test_decode_step_state_follows_free_token_schedule():
+    """Positions M_L processes per block under the free-token scheme (Fig. 2): gamma + 1 per block."""
+    T = small_pair()
+    P, gamma = 7, 2
+    st = orc.empty_state(T, 1, 32)
+    toks = inputs.token_ids(3, (P + 9,), 40)
+    st["pending"][0] = toks[0]
+    # under this scheme M_L processes the whole prompt and emits the first new token itself
+    orc.decode_step(T, st, P - 1, forced=toks[None, 1:P], free_token=True)
+    assert st["n"][0] == P
+    sched = [e for e in orc.inference_schedule(P, gamma, 2, free_token=True) if e[0] == "L"][1:]
+    for e in sched:
+        n0 = int(st["n"][0])
+        orc.decode_step(T, st, gamma, forced=toks[None, n0 + 1 : n0 + 1 + gamma], free_token=True)
+        assert list(range(n0, int(st["n"][0]))) == e[1]
+
+
 def test_speed_accepts_everything_when_drafter_is_the_verifier():
     """If M_S is M_L itself and the large-derived rows equal M_L's own K/V (identity
     FF_Tandem on the layer input), every draft token must be accepted."""
