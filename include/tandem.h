@@ -160,7 +160,7 @@ typedef struct {
  *   n[b]        positions 0..n[b]-1 have rows in KL/VL and Khat/Vhat
  *   pending[b]  token at position n[b]: emitted, but not yet processed by M_L
  * Cache ownership rule (Sec. 3 "Inference", last paragraph): the draft phase writes only
- * Kcur/Vcur; KL/VL/Khat/Vhat rows [n, n+gamma) are written by the verify phase after the
+ * Kcur/Vcur; KL/VL/Khat/Vhat rows [n, n+q) are written by the verify phase after the
  * small model has finished the block; rows below n[b] are never modified. */
 typedef struct {
   int32_t B;
@@ -172,12 +172,13 @@ typedef struct {
   int32_t *n, *pending;            /* device int32 [B]         */
 } tandem_state_desc;
 
-/* Optional per-step outputs, each a device pointer or NULL:
+/* Optional per-step outputs, each a device pointer or NULL (q = rows M_L verifies per sequence: gamma,
+ * or gamma + 1 with TANDEM_STEP_FREE_TOKEN):
  *   draft  int32 [B, gamma]  d_1..d_gamma, the small model's greedy tokens
- *   verify int32 [B, gamma]  M_L's greedy token for the same positions
+ *   verify int32 [B, q]      M_L's greedy token after each verified row
  *   y_small  [B, gamma, S.d] final small-model representation y^(L_S) of every draft run
- *   x_large  [B, gamma, L.d] final large-model representation x^(L_L) of the block rows
- *   logits_S [B, gamma, vocab], logits_L [B, gamma, vocab]   (model dtype)           */
+ *   x_large  [B, q, L.d]     final large-model representation x^(L_L) of the block rows
+ *   logits_S [B, gamma, vocab], logits_L [B, q, vocab]   (model dtype)           */
 typedef struct {
   int32_t *draft, *verify;
   void *y_small, *x_large, *logits_S, *logits_L;
@@ -189,22 +190,31 @@ int tandem_model_create(const tandem_model_desc *desc, tandem_model **out);
 void tandem_model_destroy(tandem_model *m);
 size_t tandem_decode_step_workspace(const tandem_model *m, int32_t B, int32_t gamma);
 
+/* tandem_decode_step flags.  TANDEM_STEP_FREE_TOKEN (Sec. 3.1, Fig. 2): M_L also processes the last
+ * draft token, q = gamma + 1 rows, so its own token after the accepted prefix is always available: every
+ * step emits a + 1 tokens, the last one a bonus token when all gamma drafts were right. */
+#define TANDEM_STEP_FREE_TOKEN 1
+
 /* One Tandem + SPEED decode step for every sequence (Sec. 3.1; Sec. 1 steps 2-4; one step is
- * gamma runs of M_S and one block run of M_L):
+ * gamma runs of M_S and one block run of M_L over q = gamma (+ 1 with the free token) rows):
  *   1. draft: M_S runs gamma times from `pending`, each run attending Khat/Vhat[0:n) and its own
  *      block rows (tandem_draft_attn per small layer), greedy token d_{r+1} after run r;
- *   2. verify: M_L processes [pending, d_1 .. d_{gamma-1}] in block mode at positions n..n+gamma-1
- *      (tandem_block_attn per large layer), appending its K/V rows and giving its own greedy tokens;
- *   3. tandem_project per small layer on the gamma new rows of x^(ell[j]), then that layer's
+ *   2. verify: M_L processes the first q of [pending, d_1 .. d_gamma] in block mode at positions
+ *      n..n+q-1 (tandem_block_attn per large layer), appending its K/V rows and giving its own greedy tokens;
+ *   3. tandem_project per small layer on the q new rows of x^(ell[j]), then that layer's
  *      RMSNorm and W_K/W_V produce the new Khat/Vhat rows;
  *   4. accept: a[b] = number of leading draft tokens equal to M_L's tokens; emitted tokens are
- *      d_1..d_a followed by M_L's token at the first mismatch (only d_1..d_gamma if a == gamma);
- *      n[b] += min(a+1, gamma); pending[b] = last emitted token.  Ties in argmax go to the lowest id.
+ *      d_1..d_a followed by M_L's token after them - except that without the free token a fully accepted
+ *      block (a == gamma) emits d_1..d_gamma only, M_L not having seen d_gamma;
+ *      n[b] += number of emitted tokens; pending[b] = last emitted token.  Ties in argmax go to the lowest id.
  * forced: optional device int32 [B, gamma]; when given, forced[b, r] replaces d_{r+1} as the input
- *   of the following runs and everything is treated as accepted (teacher forcing / prompt ingestion).
- * out_tokens device int32 [B, gamma] (emitted tokens, -1 padded), n_accepted device int32 [B] (a[b]).
- * 1 <= gamma <= min(gamma_max, TANDEM_MAX_QLEN); requires n[b] + gamma <= T_max. */
-int tandem_decode_step(const tandem_model *m, const tandem_state_desc *state, int32_t gamma, const int32_t *forced,
+ *   of the following runs and everything is treated as accepted (teacher forcing / prompt ingestion):
+ *   n[b] += q, emitted = forced[b, :] (+ M_L's token after them with the free token).
+ * out_tokens device int32 [B, q] (emitted tokens, -1 padded), n_accepted device int32 [B] (a[b]).
+ * 1 <= gamma <= gamma_max, q <= TANDEM_MAX_QLEN; requires n[b] + q <= T_max.
+ * ws: at least tandem_decode_step_workspace(m, B, gamma) bytes (sized for either mode). */
+int tandem_decode_step(const tandem_model *m, const tandem_state_desc *state, int32_t gamma, int32_t flags,
+                       const int32_t *forced,
                        int32_t *out_tokens, int32_t *n_accepted, const tandem_step_aux *aux, void *ws, size_t ws_bytes,
                        void *hip_stream);
 

@@ -76,6 +76,7 @@ class StepAux(C.Structure):
 
 
 MODEL_PACK_WEIGHTS = 1
+STEP_FREE_TOKEN = 1
 
 EXPORTS = (
     "tandem_status_string",
@@ -122,7 +123,7 @@ def lib():
     L.tandem_decode_step_workspace.restype = sz
     L.tandem_decode_step_workspace.argtypes = [vp, i32, i32]
     L.tandem_decode_step.restype = C.c_int
-    L.tandem_decode_step.argtypes = [vp, C.POINTER(StateDesc), i32, vp, vp, vp, C.POINTER(StepAux), vp, sz, vp]
+    L.tandem_decode_step.argtypes = [vp, C.POINTER(StateDesc), i32, i32, vp, vp, vp, C.POINTER(StepAux), vp, sz, vp]
     _lib = L
     return L
 
@@ -399,25 +400,29 @@ def tandem_decode_step_workspace(model: TandemModel, B: int, gamma: int) -> int:
 
 
 def tandem_decode_step(model: TandemModel, state: TandemState, gamma: int, forced=None, aux=False, ws=None, out=None,
-                       stream=None):
-    """Runs one step.  Returns a dict with "tokens" [B,gamma] and "n_accepted" [B] (int32 device tensors) and,
-    with aux=True, "draft", "verify", "y_small", "x_large", "logits_S", "logits_L"."""
+                       stream=None, free_token=False):
+    """Runs one step.  q = gamma, or gamma + 1 with free_token (M_L also verifies the last draft and always
+    emits its own token after the accepted prefix).  Returns a dict with "tokens" [B,q] and "n_accepted" [B]
+    (int32 device tensors) and, with aux=True, "draft" [B,gamma], "verify" [B,q], "y_small", "x_large",
+    "logits_S", "logits_L"."""
     import torch
 
     B = state.B
     dev = state.n.device
+    q = gamma + 1 if free_token else gamma
     if out is None:
-        out = {"tokens": torch.empty((B, gamma), dtype=torch.int32, device=dev),
+        out = {"tokens": torch.empty((B, q), dtype=torch.int32, device=dev),
                "n_accepted": torch.empty((B,), dtype=torch.int32, device=dev)}
         if aux:
             out.update(
                 draft=torch.empty((B, gamma), dtype=torch.int32, device=dev),
-                verify=torch.empty((B, gamma), dtype=torch.int32, device=dev),
+                verify=torch.empty((B, q), dtype=torch.int32, device=dev),
                 y_small=torch.empty((B, gamma, model.S.d), dtype=model.dtype, device=dev),
-                x_large=torch.empty((B, gamma, model.L.d), dtype=model.dtype, device=dev),
+                x_large=torch.empty((B, q, model.L.d), dtype=model.dtype, device=dev),
                 logits_S=torch.empty((B, gamma, model.S.vocab), dtype=model.dtype, device=dev),
-                logits_L=torch.empty((B, gamma, model.L.vocab), dtype=model.dtype, device=dev),
+                logits_L=torch.empty((B, q, model.L.vocab), dtype=model.dtype, device=dev),
             )
+    _need(out["tokens"], (B, q), "out tokens")
     a = None
     if "draft" in out:
         a = StepAux(*[out[k].data_ptr() for k in ("draft", "verify", "y_small", "x_large", "logits_S", "logits_L")])
@@ -427,7 +432,8 @@ def tandem_decode_step(model: TandemModel, state: TandemState, gamma: int, force
             raise TypeError("forced must be int32")
     if ws is None:
         ws = _workspace(tandem_decode_step_workspace(model, B, gamma), state.n)
-    rc = lib().tandem_decode_step(model.handle, C.byref(state.desc), gamma, _ptr(forced), _ptr(out["tokens"]),
+    rc = lib().tandem_decode_step(model.handle, C.byref(state.desc), gamma, STEP_FREE_TOKEN if free_token else 0,
+                                  _ptr(forced), _ptr(out["tokens"]),
                                   _ptr(out["n_accepted"]), C.byref(a) if a is not None else None, _ptr(ws), ws.numel(),
                                   _stream(stream))
     _check(rc, "tandem_decode_step")

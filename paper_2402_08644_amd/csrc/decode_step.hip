@@ -473,13 +473,15 @@ int tandem_pack_weight(const void* W, int64_t N, int64_t K, int32_t dtype, void*
 
 size_t tandem_decode_step_workspace(const tandem_model* m, int32_t B, int32_t gamma) {
   if (!m || B < 1 || gamma < 1 || gamma > TANDEM_MAX_QLEN) return 0;
-  // T_max only scales the split-K scratch, which is capped at 64 splits: size for the cap
-  return make_plan(m, B, gamma, (int64_t)1 << 40, gamma).total;
+  // T_max only scales the split-K scratch, which is capped at 64 splits: size for the cap.  Sized for the
+  // free-token mode (gamma + 1 verified rows), which also covers the plain one.
+  const int nq = gamma < TANDEM_MAX_QLEN ? gamma + 1 : gamma;
+  return make_plan(m, B, nq, (int64_t)1 << 40, gamma).total;
 }
 
-int tandem_decode_step(const tandem_model* m, const tandem_state_desc* state, int32_t gamma, const int32_t* forced,
-                       int32_t* out_tokens, int32_t* n_accepted, const tandem_step_aux* aux, void* ws, size_t ws_bytes,
-                       void* hip_stream) {
+int tandem_decode_step(const tandem_model* m, const tandem_state_desc* state, int32_t gamma, int32_t flags,
+                       const int32_t* forced, int32_t* out_tokens, int32_t* n_accepted, const tandem_step_aux* aux,
+                       void* ws, size_t ws_bytes, void* hip_stream) {
   if (!m || !state || !out_tokens || !n_accepted || !ws) return TANDEM_ERR_NULL;
   if (!state->KL || !state->VL || !state->Khat || !state->Vhat || !state->Kcur || !state->Vcur || !state->n ||
       !state->pending)
@@ -487,7 +489,10 @@ int tandem_decode_step(const tandem_model* m, const tandem_state_desc* state, in
   const tandem_decoder_desc &L = m->d.L, &S = m->d.S;
   const int B = state->B;
   if (B < 1 || B > 65535 || state->T_max < 1 || state->gamma_max < 1) return TANDEM_ERR_SHAPE;
-  if (gamma < 1 || gamma > TANDEM_MAX_QLEN || gamma > state->gamma_max || gamma > state->T_max) return TANDEM_ERR_SHAPE;
+  if (flags & ~TANDEM_STEP_FREE_TOKEN) return TANDEM_ERR_UNSUPPORTED;
+  // rows M_L verifies per sequence: the block [pending, d_1 .. d_{gamma-1}], plus d_gamma for the free token
+  const int nq = gamma + ((flags & TANDEM_STEP_FREE_TOKEN) ? 1 : 0);
+  if (gamma < 1 || nq > TANDEM_MAX_QLEN || gamma > state->gamma_max || nq > state->T_max) return TANDEM_ERR_SHAPE;
   for (int j = 0; j < L.n_layers; ++j)
     if (!state->KL[j] || !state->VL[j]) return TANDEM_ERR_NULL;
   for (int j = 0; j < S.n_layers; ++j)
@@ -497,19 +502,19 @@ int tandem_decode_step(const tandem_model* m, const tandem_state_desc* state, in
   Ctx c;
   c.m = m;
   c.st = state;
-  c.plan = make_plan(m, B, gamma, state->T_max, state->gamma_max);
+  c.plan = make_plan(m, B, nq, state->T_max, state->gamma_max);
   if (c.plan.total > ws_bytes) return TANDEM_ERR_WORKSPACE;
   c.ws = (char*)ws;
   c.stream = (hipStream_t)hip_stream;
   c.dtype = m->d.dtype;
   c.eps = m->d.rms_eps;
   const size_t es = elsize(c.dtype);
-  const int M = B * gamma;
+  const int M = B * nq;  // rows of the verify pass and of everything derived from it
 
   int32_t* ncur = c.at<int32_t>(c.plan.ints);        // [gamma][B], ncur[r][b] = r + 1
-  int32_t* block_tokens = ncur + M;                  // [B, gamma]
+  int32_t* block_tokens = ncur + M;                  // [B, nq]
   int32_t* draft = aux && aux->draft ? aux->draft : block_tokens + M;    // [B, gamma]
-  int32_t* verify = aux && aux->verify ? aux->verify : block_tokens + 2 * M;  // [B, gamma]
+  int32_t* verify = aux && aux->verify ? aux->verify : block_tokens + 2 * M;  // [B, nq]
   void *x = c.at<>(c.plan.x), *qkv = c.at<>(c.plan.qkv), *q = c.at<>(c.plan.q), *att = c.at<>(c.plan.att);
 
   TRY(launch_prepare_step(state->pending, ncur, B, gamma, c.stream));
@@ -556,8 +561,8 @@ int tandem_decode_step(const tandem_model* m, const tandem_state_desc* state, in
                  S.vocab * es, S.vocab * es, B, c.stream));
   }
 
-  // ---- 2. verify: M_L in block mode on [pending, d_1 .. d_{gamma-1}] -------------------
-  TRY(launch_block_tokens(state->pending, forced ? forced : draft, block_tokens, B, gamma, c.stream));
+  // ---- 2. verify: M_L in block mode on the first nq of [pending, d_1 .. d_gamma] ---------
+  TRY(launch_block_tokens(state->pending, forced ? forced : draft, block_tokens, B, gamma, nq, c.stream));
   TRY(launch_embed(L.emb, block_tokens, 1, x, M, L.d, L.vocab, c.dtype, c.stream));
   auto keep = [&](int depth) -> int {  // x^(depth) for every small layer that reads it
     for (int j = 0; j < S.n_layers; ++j)
@@ -570,18 +575,18 @@ int tandem_decode_step(const tandem_model* m, const tandem_state_desc* state, in
   if (c.plan.fused) TRY(launch_rmsnorm(x, L.layers[0].g_attn, c.at<>(c.plan.xn), M, L.d, c.eps, c.dtype, c.stream));
   for (int j = 0; j < L.n_layers; ++j) {
     auto attn_only = [&]() -> int {
-      return attn_call(c, L, q, state->KL[j], state->VL[j], state->n, nullptr, nullptr, nullptr, 1, gamma, att);
+      return attn_call(c, L, q, state->KL[j], state->VL[j], state->n, nullptr, nullptr, nullptr, 1, nq, att);
     };
     if (c.plan.fused) {
       auto finish_qkv = [&](const float* part, int splits) -> int {
-        return launch_finish_scatter(part, splits, q, state->KL[j], state->VL[j], state->n, 0, M, gamma, L.Hq, L.Hkv,
+        return launch_finish_scatter(part, splits, q, state->KL[j], state->VL[j], state->n, 0, M, nq, L.Hq, L.Hkv,
                                      L.dh, state->T_max, L.Hq * L.dh, (L.Hq + 2 * L.Hkv) * L.dh, c.dtype, c.stream);
       };
       const void* g_next = j + 1 < L.n_layers ? L.layers[j + 1].g_attn : L.g_final;
       TRY(decoder_layer_fused(c, L, L.layers[j], M, g_next, finish_qkv, attn_only));
     } else {
       auto attn = [&]() -> int {
-        TRY(launch_scatter_qkv(qkv, q, state->KL[j], state->VL[j], state->n, 0, M, gamma, L.Hq, L.Hkv, L.dh,
+        TRY(launch_scatter_qkv(qkv, q, state->KL[j], state->VL[j], state->n, 0, M, nq, L.Hq, L.Hkv, L.dh,
                                state->T_max, 0, L.Hq * L.dh, (L.Hq + 2 * L.Hkv) * L.dh, c.dtype, c.stream));
         return attn_only();
       };
@@ -621,19 +626,19 @@ int tandem_decode_step(const tandem_model* m, const tandem_state_desc* state, in
       }
       TRY(gemm_deferred(xn, S.d, Wkv, Wkv_p, M, nkv, S.d, c.dtype, gws, c.plan.gemm_ws_bytes, c.stream));
       TRY(launch_finish_scatter(part, gemm_splits(M, nkv, S.d, Wkv_p != nullptr), nullptr, state->Khat[j], state->Vhat[j], state->n, 0, M,
-                                gamma, S.Hq, S.Hkv, S.dh, state->T_max, 0, nkv, c.dtype, c.stream));
+                                nq, S.Hq, S.Hkv, S.dh, state->T_max, 0, nkv, c.dtype, c.stream));
     } else {
       TRY(run_project(&m->ff[j], xk, yhat, M, gws, c.plan.gemm_ws_bytes, c.stream));
       TRY(launch_rmsnorm(yhat, S.layers[j].g_attn, xn, M, S.d, c.eps, c.dtype, c.stream));
       TRY(gemm(xn, S.d, Wkv, Wkv_p, nullptr, nullptr, 0, kv, nkv, M, nkv, S.d, TANDEM_ACT_NONE, c.dtype, gws,
                c.plan.gemm_ws_bytes, c.stream));
-      TRY(launch_scatter_qkv(kv, nullptr, state->Khat[j], state->Vhat[j], state->n, 0, M, gamma, S.Hq, S.Hkv, S.dh,
+      TRY(launch_scatter_qkv(kv, nullptr, state->Khat[j], state->Vhat[j], state->n, 0, M, nq, S.Hq, S.Hkv, S.dh,
                              state->T_max, 0, 0, nkv, c.dtype, c.stream));
     }
   }
 
   // ---- 4. accept ------------------------------------------------------------------------
-  return launch_accept(draft, verify, forced, out_tokens, n_accepted, state->n, state->pending, B, gamma, c.stream);
+  return launch_accept(draft, verify, forced, out_tokens, n_accepted, state->n, state->pending, B, gamma, nq, c.stream);
 }
 
 }  // extern "C"

@@ -11,7 +11,8 @@ int launch_finish_scatter(const float* part, int splits, void* q, void* kc, void
                           hipStream_t st);
 int launch_argmax(const void* logits, int rows, int vocab, int32_t* out, int64_t out_stride, int dtype, hipStream_t st);
 int launch_prepare_step(const int32_t* pending, int32_t* ncur, int B, int gamma, hipStream_t st);
-int launch_block_tokens(const int32_t* pending, const int32_t* follow, int32_t* block_tokens, int B, int gamma,
+// q: rows M_L verifies per sequence, gamma or gamma + 1 (free token)
+int launch_block_tokens(const int32_t* pending, const int32_t* follow, int32_t* block_tokens, int B, int gamma, int q,
                         hipStream_t st);
 int launch_accept(const int32_t* draft, const int32_t* verify, const int32_t* forced, int32_t* out_tokens,
-                  int32_t* n_accepted, int32_t* n, int32_t* pending, int B, int gamma, hipStream_t st);
+                  int32_t* n_accepted, int32_t* n, int32_t* pending, int B, int gamma, int q, hipStream_t st);

@@ -252,38 +252,44 @@ __global__ void prepare_step_kernel(const int32_t* pending, int32_t* ncur, int B
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < B * gamma) ncur[i] = i / B + 1;
 }
+// block_tokens[b, r] (r < q): the tokens M_L processes, pending[b] then the first q - 1 of follow[b, :gamma]
 __global__ void block_tokens_kernel(const int32_t* pending, const int32_t* follow, int32_t* block_tokens, int B,
-                                    int gamma) {
+                                    int gamma, int q) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= B * gamma) return;
-  const int b = i / gamma, r = i % gamma;
+  if (i >= B * q) return;
+  const int b = i / q, r = i % q;
   block_tokens[i] = r == 0 ? pending[b] : follow[b * gamma + r - 1];
 }
 
 // Sec. 3.1: first location where the draft differs from M_L's token; emit the agreed prefix and
 // M_L's token there; advance n by the rows that stay valid; the last emitted token becomes pending.
+// draft, forced: [B, gamma]; verify, out_tokens: [B, q] with q = gamma (M_L has not seen the last draft:
+// a fully accepted block emits gamma tokens) or gamma + 1 (free token, Fig. 2: always a + 1 tokens).
 __global__ void accept_kernel(const int32_t* draft, const int32_t* verify, const int32_t* forced, int32_t* out_tokens,
-                              int32_t* n_accepted, int32_t* n, int32_t* pending, int B, int gamma) {
+                              int32_t* n_accepted, int32_t* n, int32_t* pending, int B, int gamma, int q) {
   const int b = blockIdx.x * blockDim.x + threadIdx.x;
   if (b >= B) return;
+  const bool free_token = q > gamma;
   int a = 0;
   if (forced) {
     a = gamma;
-    for (int r = 0; r < gamma; ++r) out_tokens[b * gamma + r] = forced[b * gamma + r];
-    pending[b] = forced[b * gamma + gamma - 1];
+    for (int r = 0; r < gamma; ++r) out_tokens[b * q + r] = forced[b * gamma + r];
+    if (free_token) out_tokens[b * q + gamma] = verify[b * q + gamma];
+    pending[b] = out_tokens[b * q + q - 1];
+    n[b] += q;
   } else {
-    while (a < gamma && draft[b * gamma + a] == verify[b * gamma + a]) ++a;
-    const int emit = a < gamma ? a + 1 : gamma;
-    for (int r = 0; r < gamma; ++r) {
+    while (a < gamma && draft[b * gamma + a] == verify[b * q + a]) ++a;
+    const int emit = (a < gamma || free_token) ? a + 1 : gamma;
+    for (int r = 0; r < q; ++r) {
       int t = -1;
       if (r < a) t = draft[b * gamma + r];
-      else if (r == a && a < gamma) t = verify[b * gamma + a];
-      out_tokens[b * gamma + r] = t;
+      else if (r == a && r < emit) t = verify[b * q + a];
+      out_tokens[b * q + r] = t;
     }
-    pending[b] = out_tokens[b * gamma + emit - 1];
+    pending[b] = out_tokens[b * q + emit - 1];
+    n[b] += emit;
   }
   n_accepted[b] = a;
-  n[b] += a < gamma ? a + 1 : gamma;
 }
 
 }  // namespace
@@ -368,16 +374,16 @@ int launch_prepare_step(const int32_t* pending, int32_t* ncur, int B, int gamma,
   return hip_ok(hipGetLastError());
 }
 
-int launch_block_tokens(const int32_t* pending, const int32_t* follow, int32_t* block_tokens, int B, int gamma,
+int launch_block_tokens(const int32_t* pending, const int32_t* follow, int32_t* block_tokens, int B, int gamma, int q,
                         hipStream_t st) {
-  hipLaunchKernelGGL(block_tokens_kernel, dim3((B * gamma + 255) / 256), dim3(256), 0, st, pending, follow, block_tokens,
-                     B, gamma);
+  hipLaunchKernelGGL(block_tokens_kernel, dim3((B * q + 255) / 256), dim3(256), 0, st, pending, follow, block_tokens,
+                     B, gamma, q);
   return hip_ok(hipGetLastError());
 }
 
 int launch_accept(const int32_t* draft, const int32_t* verify, const int32_t* forced, int32_t* out_tokens,
-                  int32_t* n_accepted, int32_t* n, int32_t* pending, int B, int gamma, hipStream_t st) {
+                  int32_t* n_accepted, int32_t* n, int32_t* pending, int B, int gamma, int q, hipStream_t st) {
   hipLaunchKernelGGL(accept_kernel, dim3((B + 63) / 64), dim3(64), 0, st, draft, verify, forced, out_tokens, n_accepted,
-                     n, pending, B, gamma);
+                     n, pending, B, gamma, q);
   return hip_ok(hipGetLastError());
 }

@@ -243,6 +243,74 @@ def test_speed_stream_equals_greedy_large_decode_fp32(tb):
         assert got[:n_new] == want, (gamma, got, want)
 
 
+@pytest.mark.parametrize("gamma,B,n", [(4, 3, [40, 7, 0]), (1, 2, [33, 64]), (7, 9, [100, 1, 5, 17, 60, 2, 99, 31, 8])])
+def test_decode_step_free_token_bf16_vs_oracle(tb, gamma, B, n):
+    """Free-token mode (Sec. 3.1, Fig. 2): gamma + 1 verified rows; every step emits n_accepted + 1 tokens."""
+    torch, binding = tb
+    W = small_bf16_pair(70 + gamma)
+    T = inputs.as_f64(W)
+    T_max, q = 128, gamma + 1
+    pending = [int(v) for v in inputs.token_ids(71 + gamma, (B,), 512)]
+    ost, host = oracle_state_from(T, B, T_max, 72 + gamma, n, pending, "bf16")
+    model = binding.TandemModel(W)
+    gst = upload_state(tb, model, B, T_max, 8, host, n, pending)
+    forced_np = inputs.token_ids(73 + gamma, (B, gamma), 512)
+    forced = torch.tensor(forced_np, dtype=torch.int32).cuda()
+    out = binding.tandem_decode_step(model, gst, gamma, forced=forced, aux=True, free_token=True)
+    torch.cuda.synchronize()
+    want = orc.decode_step(T, ost, gamma, forced=forced_np, free_token=True)
+    tol = 2e-2 * math.ceil(math.sqrt(2 + 1))
+    assert out["tokens"].shape == (B, q) and out["x_large"].shape[1] == q
+    assert_rows_close(inputs.torch_to_f64(out["y_small"]), want["y_small"], tol=tol, what="y_small")
+    assert_rows_close(inputs.torch_to_f64(out["x_large"]), want["x_large"], tol=tol, what="x_large")
+    assert tokens_ok(out["draft"].cpu().numpy(), want["logits_S"])
+    assert tokens_ok(out["verify"].cpu().numpy(), want["logits_L"])
+    # integer part: forced tokens, then M_L's own token; n advances by gamma + 1
+    tok = out["tokens"].cpu().numpy()
+    np.testing.assert_array_equal(tok[:, :gamma], forced_np)
+    np.testing.assert_array_equal(tok[:, gamma], out["verify"].cpu().numpy()[:, gamma])
+    np.testing.assert_array_equal(gst.pending.cpu().numpy(), tok[:, gamma])
+    np.testing.assert_array_equal(gst.n.cpu().numpy(), np.asarray(n) + q)
+    np.testing.assert_array_equal(out["n_accepted"].cpu().numpy(), gamma)
+    for b in range(B):
+        lo, hi = n[b], n[b] + q
+        for key in ("KL", "VL", "Khat", "Vhat"):
+            for j in range(len(host[key])):
+                g = getattr(gst, key)[j]
+                assert_rows_close(inputs.torch_to_f64(g[b, :, lo:hi]), ost[key][j][b, :, lo:hi], tol=tol, what=f"{key}[{j}] new rows")
+                old = host[key][j].to_torch()
+                assert torch.equal(g[b, :, :lo].view(torch.int16), old[b, :, :lo].view(torch.int16))
+                assert torch.equal(g[b, :, hi:].view(torch.int16), old[b, :, hi:].view(torch.int16))
+
+
+def test_free_token_stream_equals_greedy_large_decode_fp32(tb):
+    """Tandem + SPEED with the bonus token on the GPU: the stream is still greedy M_L's (oracle), a step emits
+    n_accepted + 1 tokens and n advances by as many (exact integer behaviour, fp32)."""
+    torch, binding = tb
+    W = inputs.tandem_weights(
+        7, vocab=96, large=dict(d=128, n_layers=2, Hq=4, Hkv=2, dh=64, d_ff=256),
+        small=dict(d=64, n_layers=1, Hq=1, Hkv=1, dh=64, d_ff=128), ell=(2,), d_hidden=96, dtype="f32", w_std=0.4)
+    T = inputs.as_f64(W)
+    prompt = inputs.token_ids(2, (6,), 96)
+    n_new = 12
+    want = orc.greedy_decode_large(T["L"], prompt, n_new, T["eps"])
+    model = binding.TandemModel(W)
+    for gamma in (1, 3, 4):
+        gst = binding.TandemState(model, 1, 64, 4)
+        gst.pending.copy_(torch.tensor([int(prompt[0])], dtype=torch.int32))
+        binding.tandem_decode_step(model, gst, 3, forced=torch.tensor(prompt[None, 1:4], dtype=torch.int32).cuda())
+        binding.tandem_decode_step(model, gst, 2, forced=torch.tensor(prompt[None, 4:6], dtype=torch.int32).cuda())
+        got = []
+        while len(got) < n_new:
+            n0 = int(gst.n[0])
+            out = binding.tandem_decode_step(model, gst, gamma, free_token=True)
+            a = int(out["n_accepted"][0])
+            tok = out["tokens"][0].cpu().numpy()
+            assert int(gst.n[0]) == n0 + a + 1 and (tok[a + 1:] == -1).all() and int(gst.pending[0]) == tok[a]
+            got += [int(t) for t in tok[: a + 1]]
+        assert got[:n_new] == want, (gamma, got, want)
+
+
 def test_decode_step_error_codes(tb):
     torch, binding = tb
     import ctypes as C
@@ -252,6 +320,10 @@ def test_decode_step_error_codes(tb):
     gst = binding.TandemState(model, 1, 16, 2)
     with pytest.raises(binding.TandemError) as ei:
         binding.tandem_decode_step(model, gst, 3)  # gamma above gamma_max
+    assert ei.value.status == binding.ERR_SHAPE
+    big = binding.TandemState(model, 1, 64, 32)
+    with pytest.raises(binding.TandemError) as ei:
+        binding.tandem_decode_step(model, big, 32, free_token=True)  # 33 verified rows exceed TANDEM_MAX_QLEN
     assert ei.value.status == binding.ERR_SHAPE
     with pytest.raises(binding.TandemError) as ei:
         binding.tandem_decode_step(model, gst, 2, ws=torch.empty(256, dtype=torch.uint8, device="cuda"))

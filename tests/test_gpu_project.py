@@ -153,6 +153,23 @@ def test_project_parity_config2_packed(tb):
     assert_rows_close(inputs.torch_to_f64(out), oracle(case), what="project config 2 packed")
 
 
+def test_pack_weight_error_codes(tb):
+    torch, binding = tb
+    import ctypes as C
+
+    L = binding.lib()
+    t = torch.zeros(256 * 512 + 8, dtype=torch.bfloat16, device="cuda")
+    p = t.data_ptr()
+    vp = C.c_void_p
+    assert L.tandem_pack_weight(None, 256, 512, binding.BF16, vp(p), None) == binding.ERR_NULL
+    assert L.tandem_pack_weight(vp(p), 256, 512, binding.BF16, None, None) == binding.ERR_NULL
+    assert L.tandem_pack_weight(vp(p), 0, 512, binding.BF16, vp(p), None) == binding.ERR_SHAPE
+    assert L.tandem_pack_weight(vp(p), 200, 512, binding.BF16, vp(p), None) == binding.ERR_UNSUPPORTED
+    assert L.tandem_pack_weight(vp(p), 256, 512, binding.F32, vp(p), None) == binding.ERR_UNSUPPORTED
+    assert L.tandem_pack_weight(vp(p + 2), 256, 512, binding.BF16, vp(p), None) == binding.ERR_SHAPE  # misaligned
+    torch.cuda.synchronize()
+
+
 def test_project_is_deterministic(tb):
     torch, binding = tb
     case = inputs.project_case(4, 64, 1024, 2048, 512, dtype="bf16")
