@@ -374,6 +374,60 @@ def decode_step(T, state, gamma, forced=None, free_token=False):
     return out
 
 
+def prefill_block(T, state, tokens, emit=False):
+    """Prompt ingestion (Sec. 1 steps 1 and 3 for tokens that are already known; Sec. 3 "Inference"):
+    for every sequence b, M_L processes tokens[b, 0:q] at positions n[b] .. n[b]+q-1 in block mode
+    (Eq. (1): row r attends cache rows 0 .. n+r), which appends its K/V rows; FF_Tandem of x^(l(j))
+    followed by small layer j's own norm and W_K / W_V appends the K_hat / V_hat rows (Eq. (2) line 1,
+    Training paragraph second bullet).  M_S itself does not run: of its own rows only those of the block
+    being drafted are ever attended (Eq. (2) line 2).  n[b] += q.  With emit, pending[b] becomes M_L's
+    greedy token after the last row (the first generated token); otherwise pending is left alone.
+    Returns x^(L_L) of the q rows and, with emit, the emitted tokens."""
+    eps = T["eps"]
+    ML, MS = T["L"], T["S"]
+    tokens = np.asarray(tokens)
+    B, nq = tokens.shape
+    Hq, Hkv, dh = ML["Hq"], ML["Hkv"], ML["dh"]
+    G = Hq // Hkv
+    scale = 1.0 / math.sqrt(dh)
+    out = {"x_large": np.zeros((B, nq, ML["emb"].shape[1]), F64), "next": -np.ones(B, np.int64)}
+    for b in range(B):
+        n = int(state["n"][b])
+        x = np.asarray(ML["emb"], F64)[tokens[b]]
+        xs = [x]
+        for j, lay in enumerate(ML["layers"]):
+            hn = rmsnorm(x, lay["g_attn"], eps)
+            qh = _heads(linear(hn, lay["Wq"]), Hq, dh)
+            k = _heads(linear(hn, lay["Wk"]), Hkv, dh)
+            v = _heads(linear(hn, lay["Wv"]), Hkv, dh)
+            state["KL"][j][b, :, n : n + nq] = k.transpose(1, 0, 2)
+            state["VL"][j][b, :, n : n + nq] = v.transpose(1, 0, 2)
+            a = np.zeros((nq, Hq, dh), F64)
+            for r in range(nq):
+                for h in range(Hq):
+                    kv = h // G
+                    a[r, h] = attention_one(
+                        qh[r, h], state["KL"][j][b, kv, : n + r + 1], state["VL"][j][b, kv, : n + r + 1], scale
+                    )
+            x = x + linear(a.reshape(nq, Hq * dh), lay["Wo"])
+            x = x + mlp(rmsnorm(x, lay["g_mlp"], eps), lay)
+            xs.append(x)
+        out["x_large"][b] = x
+        for j, lay in enumerate(MS["layers"]):
+            yh = project(xs[T["ell"][j]], T["ff"][j])
+            hh = rmsnorm(yh, lay["g_attn"], eps)
+            kh = _heads(linear(hh, lay["Wk"]), MS["Hkv"], MS["dh"])
+            vh = _heads(linear(hh, lay["Wv"]), MS["Hkv"], MS["dh"])
+            state["Khat"][j][b, :, n : n + nq] = kh.transpose(1, 0, 2)
+            state["Vhat"][j][b, :, n : n + nq] = vh.transpose(1, 0, 2)
+        if emit:
+            t = argmax_lowest(logits_of(ML, x[-1], eps))
+            out["next"][b] = t
+            state["pending"][b] = t
+        state["n"][b] = n + nq
+    return out
+
+
 def empty_state(T, B, T_max):
     ML, MS = T["L"], T["S"]
     z = lambda M: np.zeros((B, M["Hkv"], T_max, M["dh"]), F64)

@@ -377,3 +377,70 @@ def test_decode_step_batch_rows_are_independent_and_ragged():
     np.testing.assert_array_equal(both["y_small"][1], single["y_small"][0])
     np.testing.assert_array_equal(both["tokens"][1], single["tokens"][0])
     assert st["n"][1] == one["n"][0]
+
+
+# ------------------------------------------------------------------ prompt ingestion
+def test_prefill_in_chunks_equals_the_teacher_forced_forward():
+    """Ingesting a prompt chunk by chunk leaves exactly the rows the teacher-forced forward defines: M_L's K/V
+    rows are those of its causal forward, K_hat / V_hat those of FF_Tandem(x^(l(j))) through the small layer's
+    norm and W_K / W_V (Eq. (2)); checked through the whole-sequence formulation of tandem_forward, and
+    through the torch mask formulation of it."""
+    T = small_pair(seed=41, w_std=0.4)
+    S_len = 11
+    toks = inputs.token_ids(41, (S_len,), 40)
+    st = orc.empty_state(T, 1, 16)
+    x_rows = []
+    for lo, hi in ((0, 4), (4, 5), (5, 11)):  # chunk sizes 4, 1, 6
+        x_rows.append(orc.prefill_block(T, st, toks[None, lo:hi])["x_large"][0])
+    assert int(st["n"][0]) == S_len
+    ref = orc.tandem_forward(T, toks, 3)  # the large side and y_hat do not depend on gamma
+    np.testing.assert_allclose(np.concatenate(x_rows), ref["xs"][-1], rtol=1e-10, atol=1e-12)
+    tref = torch_tandem_forward(T, toks, 3)
+    np.testing.assert_allclose(np.concatenate(x_rows), tref[1], rtol=1e-9, atol=1e-11)
+    eps = T["eps"]
+    for j, lay in enumerate(T["S"]["layers"]):
+        yh = orc.project(ref["xs"][T["ell"][j]], T["ff"][j])
+        hh = orc.rmsnorm(yh, lay["g_attn"], eps)
+        kh = orc.linear(hh, lay["Wk"]).reshape(S_len, T["S"]["Hkv"], T["S"]["dh"]).transpose(1, 0, 2)
+        np.testing.assert_allclose(st["Khat"][j][0, :, :S_len], kh, rtol=1e-10, atol=1e-12)
+
+
+def test_prefill_then_decode_equals_forced_steps_then_decode():
+    """State after prefill == state after forced decode steps over the same tokens (the draft phase of a forced
+    step leaves nothing behind), so the generated stream is the same; with emit, the first generated token is
+    M_L's greedy token after the prompt."""
+    T = small_pair(seed=42, w_std=0.5)
+    prompt = inputs.token_ids(42, (7,), 40)
+    a, b = orc.empty_state(T, 1, 48), orc.empty_state(T, 1, 48)
+    a["pending"][0] = b["pending"][0] = prompt[0]
+    orc.decode_step(T, a, 3, forced=prompt[None, 1:4])
+    orc.decode_step(T, a, 3, forced=prompt[None, 4:7])          # rows 0..5, prompt[6] pending
+    orc.prefill_block(T, b, prompt[None, 0:6])
+    b["pending"][0] = prompt[6]
+    assert int(a["n"][0]) == int(b["n"][0]) == 6 and int(a["pending"][0]) == int(b["pending"][0])
+    for key in ("KL", "VL", "Khat", "Vhat"):
+        for j in range(len(a[key])):
+            np.testing.assert_allclose(a[key][j][:, :, :6], b[key][j][:, :, :6], rtol=1e-12, atol=1e-12)
+    for _ in range(3):
+        oa, ob = orc.decode_step(T, a, 2), orc.decode_step(T, b, 2)
+        np.testing.assert_array_equal(oa["tokens"], ob["tokens"])
+    c = orc.empty_state(T, 1, 48)
+    out = orc.prefill_block(T, c, prompt[None, :], emit=True)
+    want = orc.greedy_decode_large(T["L"], prompt, 1, T["eps"])
+    assert int(out["next"][0]) == int(c["pending"][0]) == want[0] and int(c["n"][0]) == 7
+
+
+def test_prefill_rows_are_ragged_and_independent():
+    T = small_pair(seed=43)
+    toks = inputs.token_ids(43, (2, 3), 40)
+    st = orc.empty_state(T, 2, 16)
+    st["n"][:] = [0, 5]
+    rng = np.random.default_rng(5)
+    for key in ("KL", "VL", "Khat", "Vhat"):
+        for j in range(len(st[key])):
+            st[key][j][1, :, :5] = rng.standard_normal(st[key][j][1, :, :5].shape)
+    solo = orc.empty_state(T, 1, 16)
+    both = orc.prefill_block(T, st, toks)
+    one = orc.prefill_block(T, solo, toks[:1])
+    np.testing.assert_allclose(both["x_large"][0], one["x_large"][0], rtol=1e-12, atol=1e-12)
+    assert list(st["n"]) == [3, 8]
