@@ -218,6 +218,20 @@ int tandem_decode_step(const tandem_model *m, const tandem_state_desc *state, in
                        int32_t *out_tokens, int32_t *n_accepted, const tandem_step_aux *aux, void *ws, size_t ws_bytes,
                        void *hip_stream);
 
+/* Prompt ingestion (Sec. 1 steps 1 and 3 for tokens that are already known; Sec. 3 "Inference"): for every
+ * sequence, M_L processes tokens[b, 0:q_len) at positions n[b] .. n[b]+q_len-1 in block mode, appending its
+ * K/V rows, and FF_Tandem with the small layers' norm and W_K / W_V appends the Khat/Vhat rows.  M_S does not
+ * run: of its own rows only those of the block being drafted are ever attended (Eq. (2) line 2).
+ * n[b] += q_len.  With TANDEM_PREFILL_EMIT, pending[b] becomes M_L's greedy token after the last row (the first
+ * generated token); otherwise pending is left alone (the caller keeps the last prompt token pending).
+ *   tokens   device int32 [B, q_len];  1 <= q_len <= TANDEM_MAX_QLEN: longer prompts take several calls
+ *   x_large  optional device [B, q_len, L.d]: x^(L_L) of the rows
+ *   requires n[b] + q_len <= T_max;  ws: at least tandem_prefill_workspace(m, B, q_len) bytes. */
+#define TANDEM_PREFILL_EMIT 1
+size_t tandem_prefill_workspace(const tandem_model *m, int32_t B, int32_t q_len);
+int tandem_prefill(const tandem_model *m, const tandem_state_desc *state, const int32_t *tokens, int32_t q_len,
+                   int32_t flags, void *x_large, void *ws, size_t ws_bytes, void *hip_stream);
+
 const char *tandem_status_string(int status);
 
 #pragma GCC visibility pop

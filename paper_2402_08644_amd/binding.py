@@ -77,6 +77,7 @@ class StepAux(C.Structure):
 
 MODEL_PACK_WEIGHTS = 1
 STEP_FREE_TOKEN = 1
+PREFILL_EMIT = 1
 
 EXPORTS = (
     "tandem_status_string",
@@ -84,6 +85,7 @@ EXPORTS = (
     "tandem_packed_weight_bytes", "tandem_pack_weight",
     "tandem_project", "tandem_block_attn", "tandem_draft_attn",
     "tandem_model_create", "tandem_model_destroy", "tandem_decode_step_workspace", "tandem_decode_step",
+    "tandem_prefill_workspace", "tandem_prefill",
 )
 
 _lib = None
@@ -124,6 +126,10 @@ def lib():
     L.tandem_decode_step_workspace.argtypes = [vp, i32, i32]
     L.tandem_decode_step.restype = C.c_int
     L.tandem_decode_step.argtypes = [vp, C.POINTER(StateDesc), i32, i32, vp, vp, vp, C.POINTER(StepAux), vp, sz, vp]
+    L.tandem_prefill_workspace.restype = sz
+    L.tandem_prefill_workspace.argtypes = [vp, i32, i32]
+    L.tandem_prefill.restype = C.c_int
+    L.tandem_prefill.argtypes = [vp, C.POINTER(StateDesc), vp, i32, i32, vp, vp, sz, vp]
     _lib = L
     return L
 
@@ -438,3 +444,23 @@ def tandem_decode_step(model: TandemModel, state: TandemState, gamma: int, force
                                   _stream(stream))
     _check(rc, "tandem_decode_step")
     return out
+
+
+def tandem_prefill_workspace(model: TandemModel, B: int, q_len: int) -> int:
+    return int(lib().tandem_prefill_workspace(model.handle, B, q_len))
+
+
+def tandem_prefill(model: TandemModel, state: TandemState, tokens, emit=False, x_large=None, ws=None, stream=None):
+    """Ingests tokens [B, q_len] (int32 device tensor, q_len <= 32) for every sequence: M_L's block pass plus the
+    Khat / Vhat rows; n += q_len; with emit, pending = M_L's greedy token after the last row."""
+    import torch
+
+    B, q_len = tokens.shape
+    _need(tokens, (state.B, q_len), "tokens")
+    if tokens.dtype != torch.int32:
+        raise TypeError("tokens must be int32")
+    if ws is None:
+        ws = _workspace(tandem_prefill_workspace(model, B, q_len), state.n)
+    rc = lib().tandem_prefill(model.handle, C.byref(state.desc), _ptr(tokens), q_len, PREFILL_EMIT if emit else 0,
+                              _ptr(x_large), _ptr(ws), ws.numel(), _stream(stream))
+    _check(rc, "tandem_prefill")

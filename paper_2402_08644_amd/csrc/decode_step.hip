@@ -391,6 +391,96 @@ int copy2d(void* dst, size_t dpitch, const void* src, size_t spitch, size_t widt
   return hip_ok(hipMemcpy2DAsync(dst, dpitch, src, spitch, width, height, hipMemcpyDeviceToDevice, st));
 }
 
+// M_L in block mode on block_tokens[B, nq] at positions n .. n+nq-1 (Eq. (1) on the new rows: appends its K/V
+// rows, tandem_block_attn per layer), then, per small layer, FF_Tandem on x^(ell[j]) of those rows and that
+// layer's RMSNorm and W_K / W_V, which append the K_hat / V_hat rows (Eq. (2) line 1).  verify (optional):
+// M_L's greedy token after every row.  Reads state->n, does not change it.
+int large_block_pass(const Ctx& c, const int32_t* block_tokens, int nq, const tandem_step_aux* aux, int32_t* verify) {
+  const tandem_model* m = c.m;
+  const tandem_state_desc* state = c.st;
+  const tandem_decoder_desc &L = m->d.L, &S = m->d.S;
+  const int B = state->B, M = B * nq;
+  const size_t es = elsize(c.dtype);
+  void *x = c.at<>(c.plan.x), *qkv = c.at<>(c.plan.qkv), *q = c.at<>(c.plan.q), *att = c.at<>(c.plan.att);
+  TRY(launch_embed(L.emb, block_tokens, 1, x, M, L.d, L.vocab, c.dtype, c.stream));
+  auto keep = [&](int depth) -> int {  // x^(depth) for every small layer that reads it
+    for (int j = 0; j < S.n_layers; ++j)
+      if (m->ell[j] == depth)
+        TRY(hip_ok(hipMemcpyAsync(c.ws + c.plan.keep + j * c.plan.keep_stride, x, (size_t)M * L.d * es,
+                                  hipMemcpyDeviceToDevice, c.stream)));
+    return TANDEM_OK;
+  };
+  TRY(keep(0));
+  if (c.plan.fused) TRY(launch_rmsnorm(x, L.layers[0].g_attn, c.at<>(c.plan.xn), M, L.d, c.eps, c.dtype, c.stream));
+  for (int j = 0; j < L.n_layers; ++j) {
+    auto attn_only = [&]() -> int {
+      return attn_call(c, L, q, state->KL[j], state->VL[j], state->n, nullptr, nullptr, nullptr, 1, nq, att);
+    };
+    if (c.plan.fused) {
+      auto finish_qkv = [&](const float* part, int splits) -> int {
+        return launch_finish_scatter(part, splits, q, state->KL[j], state->VL[j], state->n, 0, M, nq, L.Hq, L.Hkv,
+                                     L.dh, state->T_max, L.Hq * L.dh, (L.Hq + 2 * L.Hkv) * L.dh, c.dtype, c.stream);
+      };
+      const void* g_next = j + 1 < L.n_layers ? L.layers[j + 1].g_attn : L.g_final;
+      TRY(decoder_layer_fused(c, L, L.layers[j], M, g_next, finish_qkv, attn_only));
+    } else {
+      auto attn = [&]() -> int {
+        TRY(launch_scatter_qkv(qkv, q, state->KL[j], state->VL[j], state->n, 0, M, nq, L.Hq, L.Hkv, L.dh,
+                               state->T_max, 0, L.Hq * L.dh, (L.Hq + 2 * L.Hkv) * L.dh, c.dtype, c.stream));
+        return attn_only();
+      };
+      TRY(decoder_layer(c, L, L.layers[j], M, attn));
+    }
+    TRY(keep(j + 1));
+  }
+  if (aux && aux->x_large)
+    TRY(hip_ok(hipMemcpyAsync(aux->x_large, x, (size_t)M * L.d * es, hipMemcpyDeviceToDevice, c.stream)));
+  if (verify) {
+    TRY(c.plan.fused ? head_normed(c, L, M, verify, 1) : head(c, L, M, verify, 1));
+    if (aux && aux->logits_L)
+      TRY(hip_ok(hipMemcpyAsync(aux->logits_L, c.at<>(c.plan.logits), (size_t)M * L.vocab * es, hipMemcpyDeviceToDevice,
+                                c.stream)));
+  }
+
+  // ---- 3. FF_Tandem on the new rows, then the small layer's norm and W_K / W_V ---------
+  for (int j = 0; j < S.n_layers; ++j) {
+    void *yhat = c.at<>(c.plan.yhat), *xn = c.at<>(c.plan.xn), *kv = c.at<>(c.plan.kv), *gws = c.at<>(c.plan.gemm_ws);
+    const void* xk = c.ws + c.plan.keep + j * c.plan.keep_stride;
+    const void* Wkv = (const char*)S.layers[j].Wqkv + (size_t)S.Hq * S.dh * S.d * es;
+    const void* Wq_p = c.pk(S.layers[j].Wqkv);  // packed tiles hold 32 rows each: the K/V rows start on a tile
+    const void* Wkv_p = Wq_p && (S.Hq * S.dh) % 32 == 0 ? (const char*)Wq_p + (size_t)S.Hq * S.dh * S.d * es : nullptr;
+    const int nkv = 2 * S.Hkv * S.dh;
+    if (c.plan.fused) {
+      const tandem_ff_desc& f = m->ff[j];
+      float* part = (float*)gws;
+      if (f.d_hidden > 0) {
+        void* hb = c.at<>(c.plan.h);
+        TRY(gemm(xk, f.d_L, f.W1, f.W1p, f.b1, nullptr, 0, hb, f.d_hidden, M, f.d_hidden, f.d_L, f.act, c.dtype, gws,
+                 c.plan.gemm_ws_bytes, c.stream));
+        TRY(gemm_deferred(hb, f.d_hidden, f.W2, f.W2p, M, f.d_S, f.d_hidden, c.dtype, gws, c.plan.gemm_ws_bytes, c.stream));
+        TRY(launch_finish_norm(part, gemm_splits(M, f.d_S, f.d_hidden, f.W2p != nullptr), f.b2, nullptr, yhat, S.layers[j].g_attn, xn, M,
+                               S.d, c.eps, c.dtype, c.stream));
+      } else {
+        TRY(gemm_deferred(xk, f.d_L, f.W1, f.W1p, M, f.d_S, f.d_L, c.dtype, gws, c.plan.gemm_ws_bytes, c.stream));
+        TRY(launch_finish_norm(part, gemm_splits(M, f.d_S, f.d_L, f.W1p != nullptr), f.b1, nullptr, yhat, S.layers[j].g_attn, xn, M, S.d,
+                               c.eps, c.dtype, c.stream));
+      }
+      TRY(gemm_deferred(xn, S.d, Wkv, Wkv_p, M, nkv, S.d, c.dtype, gws, c.plan.gemm_ws_bytes, c.stream));
+      TRY(launch_finish_scatter(part, gemm_splits(M, nkv, S.d, Wkv_p != nullptr), nullptr, state->Khat[j], state->Vhat[j], state->n, 0, M,
+                                nq, S.Hq, S.Hkv, S.dh, state->T_max, 0, nkv, c.dtype, c.stream));
+    } else {
+      TRY(run_project(&m->ff[j], xk, yhat, M, gws, c.plan.gemm_ws_bytes, c.stream));
+      TRY(launch_rmsnorm(yhat, S.layers[j].g_attn, xn, M, S.d, c.eps, c.dtype, c.stream));
+      TRY(gemm(xn, S.d, Wkv, Wkv_p, nullptr, nullptr, 0, kv, nkv, M, nkv, S.d, TANDEM_ACT_NONE, c.dtype, gws,
+               c.plan.gemm_ws_bytes, c.stream));
+      TRY(launch_scatter_qkv(kv, nullptr, state->Khat[j], state->Vhat[j], state->n, 0, M, nq, S.Hq, S.Hkv, S.dh,
+                             state->T_max, 0, 0, nkv, c.dtype, c.stream));
+    }
+  }
+
+  return TANDEM_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -561,84 +651,58 @@ int tandem_decode_step(const tandem_model* m, const tandem_state_desc* state, in
                  S.vocab * es, S.vocab * es, B, c.stream));
   }
 
-  // ---- 2. verify: M_L in block mode on the first nq of [pending, d_1 .. d_gamma] ---------
+  // ---- 2. verify: M_L in block mode on the first nq of [pending, d_1 .. d_gamma]; 3. new K_hat / V_hat rows
   TRY(launch_block_tokens(state->pending, forced ? forced : draft, block_tokens, B, gamma, nq, c.stream));
-  TRY(launch_embed(L.emb, block_tokens, 1, x, M, L.d, L.vocab, c.dtype, c.stream));
-  auto keep = [&](int depth) -> int {  // x^(depth) for every small layer that reads it
-    for (int j = 0; j < S.n_layers; ++j)
-      if (m->ell[j] == depth)
-        TRY(hip_ok(hipMemcpyAsync(c.ws + c.plan.keep + j * c.plan.keep_stride, x, (size_t)M * L.d * es,
-                                  hipMemcpyDeviceToDevice, c.stream)));
-    return TANDEM_OK;
-  };
-  TRY(keep(0));
-  if (c.plan.fused) TRY(launch_rmsnorm(x, L.layers[0].g_attn, c.at<>(c.plan.xn), M, L.d, c.eps, c.dtype, c.stream));
-  for (int j = 0; j < L.n_layers; ++j) {
-    auto attn_only = [&]() -> int {
-      return attn_call(c, L, q, state->KL[j], state->VL[j], state->n, nullptr, nullptr, nullptr, 1, nq, att);
-    };
-    if (c.plan.fused) {
-      auto finish_qkv = [&](const float* part, int splits) -> int {
-        return launch_finish_scatter(part, splits, q, state->KL[j], state->VL[j], state->n, 0, M, nq, L.Hq, L.Hkv,
-                                     L.dh, state->T_max, L.Hq * L.dh, (L.Hq + 2 * L.Hkv) * L.dh, c.dtype, c.stream);
-      };
-      const void* g_next = j + 1 < L.n_layers ? L.layers[j + 1].g_attn : L.g_final;
-      TRY(decoder_layer_fused(c, L, L.layers[j], M, g_next, finish_qkv, attn_only));
-    } else {
-      auto attn = [&]() -> int {
-        TRY(launch_scatter_qkv(qkv, q, state->KL[j], state->VL[j], state->n, 0, M, nq, L.Hq, L.Hkv, L.dh,
-                               state->T_max, 0, L.Hq * L.dh, (L.Hq + 2 * L.Hkv) * L.dh, c.dtype, c.stream));
-        return attn_only();
-      };
-      TRY(decoder_layer(c, L, L.layers[j], M, attn));
-    }
-    TRY(keep(j + 1));
-  }
-  if (aux && aux->x_large)
-    TRY(hip_ok(hipMemcpyAsync(aux->x_large, x, (size_t)M * L.d * es, hipMemcpyDeviceToDevice, c.stream)));
-  TRY(c.plan.fused ? head_normed(c, L, M, verify, 1) : head(c, L, M, verify, 1));
-  if (aux && aux->logits_L)
-    TRY(hip_ok(hipMemcpyAsync(aux->logits_L, c.at<>(c.plan.logits), (size_t)M * L.vocab * es, hipMemcpyDeviceToDevice,
-                              c.stream)));
-
-  // ---- 3. FF_Tandem on the new rows, then the small layer's norm and W_K / W_V ---------
-  for (int j = 0; j < S.n_layers; ++j) {
-    void *yhat = c.at<>(c.plan.yhat), *xn = c.at<>(c.plan.xn), *kv = c.at<>(c.plan.kv), *gws = c.at<>(c.plan.gemm_ws);
-    const void* xk = c.ws + c.plan.keep + j * c.plan.keep_stride;
-    const void* Wkv = (const char*)S.layers[j].Wqkv + (size_t)S.Hq * S.dh * S.d * es;
-    const void* Wq_p = c.pk(S.layers[j].Wqkv);  // packed tiles hold 32 rows each: the K/V rows start on a tile
-    const void* Wkv_p = Wq_p && (S.Hq * S.dh) % 32 == 0 ? (const char*)Wq_p + (size_t)S.Hq * S.dh * S.d * es : nullptr;
-    const int nkv = 2 * S.Hkv * S.dh;
-    if (c.plan.fused) {
-      const tandem_ff_desc& f = m->ff[j];
-      float* part = (float*)gws;
-      if (f.d_hidden > 0) {
-        void* hb = c.at<>(c.plan.h);
-        TRY(gemm(xk, f.d_L, f.W1, f.W1p, f.b1, nullptr, 0, hb, f.d_hidden, M, f.d_hidden, f.d_L, f.act, c.dtype, gws,
-                 c.plan.gemm_ws_bytes, c.stream));
-        TRY(gemm_deferred(hb, f.d_hidden, f.W2, f.W2p, M, f.d_S, f.d_hidden, c.dtype, gws, c.plan.gemm_ws_bytes, c.stream));
-        TRY(launch_finish_norm(part, gemm_splits(M, f.d_S, f.d_hidden, f.W2p != nullptr), f.b2, nullptr, yhat, S.layers[j].g_attn, xn, M,
-                               S.d, c.eps, c.dtype, c.stream));
-      } else {
-        TRY(gemm_deferred(xk, f.d_L, f.W1, f.W1p, M, f.d_S, f.d_L, c.dtype, gws, c.plan.gemm_ws_bytes, c.stream));
-        TRY(launch_finish_norm(part, gemm_splits(M, f.d_S, f.d_L, f.W1p != nullptr), f.b1, nullptr, yhat, S.layers[j].g_attn, xn, M, S.d,
-                               c.eps, c.dtype, c.stream));
-      }
-      TRY(gemm_deferred(xn, S.d, Wkv, Wkv_p, M, nkv, S.d, c.dtype, gws, c.plan.gemm_ws_bytes, c.stream));
-      TRY(launch_finish_scatter(part, gemm_splits(M, nkv, S.d, Wkv_p != nullptr), nullptr, state->Khat[j], state->Vhat[j], state->n, 0, M,
-                                nq, S.Hq, S.Hkv, S.dh, state->T_max, 0, nkv, c.dtype, c.stream));
-    } else {
-      TRY(run_project(&m->ff[j], xk, yhat, M, gws, c.plan.gemm_ws_bytes, c.stream));
-      TRY(launch_rmsnorm(yhat, S.layers[j].g_attn, xn, M, S.d, c.eps, c.dtype, c.stream));
-      TRY(gemm(xn, S.d, Wkv, Wkv_p, nullptr, nullptr, 0, kv, nkv, M, nkv, S.d, TANDEM_ACT_NONE, c.dtype, gws,
-               c.plan.gemm_ws_bytes, c.stream));
-      TRY(launch_scatter_qkv(kv, nullptr, state->Khat[j], state->Vhat[j], state->n, 0, M, nq, S.Hq, S.Hkv, S.dh,
-                             state->T_max, 0, 0, nkv, c.dtype, c.stream));
-    }
-  }
+  TRY(large_block_pass(c, block_tokens, nq, aux, verify));
 
   // ---- 4. accept ------------------------------------------------------------------------
   return launch_accept(draft, verify, forced, out_tokens, n_accepted, state->n, state->pending, B, gamma, nq, c.stream);
+}
+
+size_t tandem_prefill_workspace(const tandem_model* m, int32_t B, int32_t q_len) {
+  if (!m || B < 1 || q_len < 1 || q_len > TANDEM_MAX_QLEN) return 0;
+  return make_plan(m, B, q_len, (int64_t)1 << 40, 1).total;
+}
+
+int tandem_prefill(const tandem_model* m, const tandem_state_desc* state, const int32_t* tokens, int32_t q_len,
+                   int32_t flags, void* x_large, void* ws, size_t ws_bytes, void* hip_stream) {
+  if (!m || !state || !tokens || !ws) return TANDEM_ERR_NULL;
+  if (!state->KL || !state->VL || !state->Khat || !state->Vhat || !state->n || !state->pending) return TANDEM_ERR_NULL;
+  if (flags & ~TANDEM_PREFILL_EMIT) return TANDEM_ERR_UNSUPPORTED;
+  const tandem_decoder_desc &L = m->d.L, &S = m->d.S;
+  const int B = state->B;
+  if (B < 1 || B > 65535 || state->T_max < 1) return TANDEM_ERR_SHAPE;
+  if (q_len < 1 || q_len > TANDEM_MAX_QLEN || q_len > state->T_max) return TANDEM_ERR_SHAPE;
+  for (int j = 0; j < L.n_layers; ++j)
+    if (!state->KL[j] || !state->VL[j]) return TANDEM_ERR_NULL;
+  for (int j = 0; j < S.n_layers; ++j)
+    if (!state->Khat[j] || !state->Vhat[j]) return TANDEM_ERR_NULL;
+  Ctx c;
+  c.m = m;
+  c.st = state;
+  c.plan = make_plan(m, B, q_len, state->T_max, state->gamma_max > 0 ? state->gamma_max : 1);
+  if (c.plan.total > ws_bytes) return TANDEM_ERR_WORKSPACE;
+  c.ws = (char*)ws;
+  c.stream = (hipStream_t)hip_stream;
+  c.dtype = m->d.dtype;
+  c.eps = m->d.rms_eps;
+  const size_t es = elsize(c.dtype);
+  tandem_step_aux aux{};
+  aux.x_large = x_large;
+  TRY(large_block_pass(c, tokens, q_len, x_large ? &aux : nullptr, nullptr));
+  if (flags & TANDEM_PREFILL_EMIT) {
+    // M_L's greedy token after the last row of every sequence: gather those rows of the residual stream to
+    // the front of x (through a buffer that step 3 no longer needs) and run the head on B rows
+    void* x = c.at<>(c.plan.x);
+    if (q_len > 1) {
+      void* tmp = c.ws + c.plan.keep;
+      TRY(copy2d(tmp, (size_t)L.d * es, (const char*)x + (size_t)(q_len - 1) * L.d * es, (size_t)q_len * L.d * es,
+                 (size_t)L.d * es, B, c.stream));
+      TRY(hip_ok(hipMemcpyAsync(x, tmp, (size_t)B * L.d * es, hipMemcpyDeviceToDevice, c.stream)));
+    }
+    TRY(head(c, L, B, state->pending, 1));
+  }
+  return launch_advance(state->n, B, q_len, c.stream);
 }
 
 }  // extern "C"

@@ -16,3 +16,4 @@ int launch_block_tokens(const int32_t* pending, const int32_t* follow, int32_t* 
                         hipStream_t st);
 int launch_accept(const int32_t* draft, const int32_t* verify, const int32_t* forced, int32_t* out_tokens,
                   int32_t* n_accepted, int32_t* n, int32_t* pending, int B, int gamma, int q, hipStream_t st);
+int launch_advance(int32_t* n, int B, int by, hipStream_t st);  // n[b] += by

@@ -292,7 +292,17 @@ __global__ void accept_kernel(const int32_t* draft, const int32_t* verify, const
   n_accepted[b] = a;
 }
 
+__global__ void advance_kernel(int32_t* n, int B, int by) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b < B) n[b] += by;
+}
+
 }  // namespace
+
+int launch_advance(int32_t* n, int B, int by, hipStream_t st) {
+  hipLaunchKernelGGL(advance_kernel, dim3((B + 63) / 64), dim3(64), 0, st, n, B, by);
+  return hip_ok(hipGetLastError());
+}
 
 int launch_embed(const void* emb, const int32_t* tokens, int64_t tok_stride, void* x, int rows, int d, int vocab,
                  int dtype, hipStream_t st) {

@@ -311,6 +311,85 @@ def test_free_token_stream_equals_greedy_large_decode_fp32(tb):
         assert got[:n_new] == want, (gamma, got, want)
 
 
+@pytest.mark.parametrize("chunks,B", [((4, 1, 6), 3), ((32, 9), 2), ((16,), 5)])
+def test_prefill_bf16_vs_oracle(tb, chunks, B):
+    """tandem_prefill chunk by chunk (ragged starting lengths): new cache rows, x^(L_L) and n against the oracle;
+    rows outside the written range stay bit-identical."""
+    torch, binding = tb
+    W = small_bf16_pair(80 + len(chunks))
+    T = inputs.as_f64(W)
+    T_max = 96
+    n = [int(v) for v in np.random.default_rng(81).integers(0, 20, B)]
+    pending = [1] * B
+    ost, host = oracle_state_from(T, B, T_max, 82, n, pending, "bf16")
+    model = binding.TandemModel(W)
+    gst = upload_state(tb, model, B, T_max, 4, host, n, pending)
+    tol = 2e-2 * math.ceil(math.sqrt(2 + 1))
+    for ci, q in enumerate(chunks):
+        toks = inputs.token_ids(83 + ci, (B, q), 512)
+        n0 = [int(v) for v in ost["n"]]
+        before = {key: [g.clone() for g in getattr(gst, key)] for key in ("KL", "VL", "Khat", "Vhat")}
+        xl = torch.empty((B, q, model.L.d), dtype=model.dtype, device="cuda")
+        binding.tandem_prefill(model, gst, torch.tensor(toks, dtype=torch.int32).cuda(), x_large=xl)
+        torch.cuda.synchronize()
+        want = orc.prefill_block(T, ost, toks)
+        assert_rows_close(inputs.torch_to_f64(xl), want["x_large"], tol=tol, what="x_large")
+        np.testing.assert_array_equal(gst.n.cpu().numpy(), ost["n"])
+        np.testing.assert_array_equal(gst.pending.cpu().numpy(), pending)
+        for b in range(B):
+            lo, hi = n0[b], n0[b] + q
+            for key in ("KL", "VL", "Khat", "Vhat"):
+                for j in range(len(host[key])):
+                    g = getattr(gst, key)[j]
+                    assert_rows_close(inputs.torch_to_f64(g[b, :, lo:hi]), ost[key][j][b, :, lo:hi], tol=tol, what=f"{key}[{j}] new rows")
+                    old = before[key][j]
+                    assert torch.equal(g[b, :, :lo].view(torch.int16), old[b, :, :lo].view(torch.int16))
+                    assert torch.equal(g[b, :, hi:].view(torch.int16), old[b, :, hi:].view(torch.int16))
+        # the oracle continues from the GPU's rounded rows, as a real decode would
+        for key in ("KL", "VL", "Khat", "Vhat"):
+            for j in range(len(host[key])):
+                ost[key][j][...] = inputs.torch_to_f64(getattr(gst, key)[j])
+
+
+def test_prefill_emit_then_decode_fp32_equals_greedy_large(tb):
+    """Prompt through tandem_prefill (two chunks, the last with emit), then Tandem + SPEED steps: the first
+    generated token and the whole stream are greedy M_L's (exact integers, fp32)."""
+    torch, binding = tb
+    W = inputs.tandem_weights(
+        7, vocab=96, large=dict(d=128, n_layers=2, Hq=4, Hkv=2, dh=64, d_ff=256),
+        small=dict(d=64, n_layers=1, Hq=1, Hkv=1, dh=64, d_ff=128), ell=(2,), d_hidden=96, dtype="f32", w_std=0.4)
+    T = inputs.as_f64(W)
+    prompt = inputs.token_ids(2, (6,), 96)
+    n_new = 10
+    want = orc.greedy_decode_large(T["L"], prompt, n_new, T["eps"])
+    model = binding.TandemModel(W)
+    gst = binding.TandemState(model, 1, 64, 4)
+    binding.tandem_prefill(model, gst, torch.tensor(prompt[None, :4], dtype=torch.int32).cuda())
+    binding.tandem_prefill(model, gst, torch.tensor(prompt[None, 4:], dtype=torch.int32).cuda(), emit=True)
+    assert int(gst.n[0]) == 6
+    got = [int(gst.pending[0])]
+    while len(got) < n_new:
+        out = binding.tandem_decode_step(model, gst, 3)
+        ne = min(int(out["n_accepted"][0]) + 1, 3)
+        got += [int(t) for t in out["tokens"][0, :ne].cpu().numpy()]
+    assert got[:n_new] == want, (got, want)
+
+
+def test_prefill_error_codes(tb):
+    torch, binding = tb
+    W = inputs.tiny_tandem(seed=1, dtype="f32")
+    model = binding.TandemModel(W)
+    gst = binding.TandemState(model, 1, 16, 2)
+    toks = torch.zeros((1, 33), dtype=torch.int32, device="cuda")
+    with pytest.raises(binding.TandemError) as ei:
+        binding.tandem_prefill(model, gst, toks)  # more rows than one call takes
+    assert ei.value.status == binding.ERR_SHAPE
+    with pytest.raises(binding.TandemError) as ei:
+        binding.tandem_prefill(model, gst, toks[:, :4].contiguous(), ws=torch.empty(256, dtype=torch.uint8, device="cuda"))
+    assert ei.value.status == binding.ERR_WORKSPACE
+    torch.cuda.synchronize()
+
+
 def test_decode_step_error_codes(tb):
     torch, binding = tb
     import ctypes as C
