@@ -236,6 +236,50 @@ def step_workload(torch, binding, inputs, cfg, seed=3, pack_weights=True):
     return call, model, state, out
 
 
+def run_prefill_workload(torch, binding, inputs, args):
+    """One tandem_prefill call: 32 prompt tokens of each of 32 sequences appended at context 4096 (C3 pair)."""
+    cfg = dict(C3)
+    B, q, n0 = cfg["B"], 32, 4096
+    W = device_tandem_weights(inputs, cfg, 3)
+    model = binding.TandemModel(W, pack_weights=not args.plain_weights)
+    del W
+    k = [5]
+
+    def fill(*shape):
+        k[0] += 1
+        return inputs.device_normal(shape, k[0], 1.0)
+
+    state = binding.TandemState(model, B, cfg["ctx"], 4, fill=fill)
+    toks = torch.randint(0, cfg["vocab"], (B, q), dtype=torch.int32, device="cuda", generator=torch.Generator("cuda").manual_seed(9))
+    ws = torch.empty(binding.tandem_prefill_workspace(model, B, q), dtype=torch.uint8, device="cuda")
+
+    def call(_i):
+        state.n.fill_(n0)
+        binding.tandem_prefill(model, state, toks, ws=ws)
+
+    torch.cuda.synchronize()
+    ms = _time_calls(torch, call, 1, args.steps, args.warmup, use_graph=not args.no_graph)
+    L, S = cfg["large"], cfg["small"]
+    M = B * q
+    per_layer = (L["Hq"] + 2 * L["Hkv"]) * L["dh"] * L["d"] + L["d"] * L["Hq"] * L["dh"] + 2 * L["d"] * L["d_ff"]
+    ff = S["n_layers"] * (cfg["d_hidden"] * L["d"] + S["d"] * cfg["d_hidden"] + 2 * S["Hkv"] * S["dh"] * S["d"])
+    flops_dense = 2.0 * M * (L["n_layers"] * per_layer + ff)
+    flops_attn = 4.0 * B * q * L["Hq"] * L["dh"] * (n0 + q / 2) * L["n_layers"]
+    tflops = (flops_dense + flops_attn) / (ms * 1e-3) / 1e12
+    return {
+        "metric": "Tandem prompt ingestion tokens/sec (tandem_prefill, 32 tokens x 32 sequences per call)",
+        "value": M / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "c3_prefill: tandem_prefill bf16 B=32, 32 rows per sequence at context 4096, C3 model pair "
+                               "(M_L block pass + FF_Tandem + K_hat/V_hat rows; M_S does not run)",
+                   "dense_TFLOP": flops_dense / 1e12, "attention_TFLOP": flops_attn / 1e12},
+        "roofline": {"bound": "mfma", "achieved": tflops, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": tflops / MFMA_PEAK_TFLOPS, "traffic": None},
+        "cpu_baseline": None,
+    }
+
+
 def cpu_step_estimate(torch, inputs, cfg, state, model):
     """Oracle pieces of one step timed on sampled slices (one sequence / one layer each), extrapolated by
     the layer, run and batch counts.  The full fp64 step is ~2 TFLOP and is not run."""
@@ -472,7 +516,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="c3_step", choices=sorted(WORKLOADS) + sorted(PROJECT_WORKLOADS) + ["c3_step"])
+    ap.add_argument("--workload", default="c3_step", choices=sorted(WORKLOADS) + sorted(PROJECT_WORKLOADS) + ["c3_step", "c3_prefill"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--plain-weights", action="store_true",
@@ -507,6 +551,9 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     runner = run_step_workload if step else (run_project_workload if args.workload in PROJECT_WORKLOADS else run_kernel_workload)
+    if args.workload == "c3_prefill":
+        runner = run_prefill_workload
+        args.steps = min(args.steps, 10)
     if args.workload in ("project_m4096", "project_m65536"):
         args.steps = min(args.steps, 20)
     line = runner(torch, binding, inputs, args)

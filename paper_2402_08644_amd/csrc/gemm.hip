@@ -716,6 +716,8 @@ __global__ __launch_bounds__(256, 1) void gemm_big_kernel(GemmParams p, int tile
     tn = (block / blocks_m) * 4 + (within >> 3);
   }
   const int m0 = tm * 256, n0 = tn * 256;
+  const int stages = (p.K / BK) / p.splitK;  // of this workgroup; even (launcher)
+  const long long kbase = (long long)blockIdx.y * stages * BK;
 
   // Direct loads: instruction q of wavefront w fills rows 8 * (4 * q + w) .. + 8 of an operand tile (1 KB of
   // LDS); lane l lands on row l >> 3, position l & 7, so it fetches piece (l & 7) ^ ((row >> 1) & 7).
@@ -728,8 +730,8 @@ __global__ __launch_bounds__(256, 1) void gemm_big_kernel(GemmParams p, int tile
     const int row = 8 * (4 * q + w) + drow;
     int m_ = m0 + row;
     m_ = m_ < p.M ? m_ : p.M - 1;
-    ag[q] = (const bf16_t*)p.X + (long long)m_ * p.ldx + dpiece * 8;
-    bg[q] = (const bf16_t*)p.W + (long long)(n0 + row) * p.K + dpiece * 8;
+    ag[q] = (const bf16_t*)p.X + (long long)m_ * p.ldx + kbase + dpiece * 8;
+    bg[q] = (const bf16_t*)p.W + (long long)(n0 + row) * p.K + kbase + dpiece * 8;
   }
   // one direct load (1 KB): rows 8 * (4 * q + w) .. + 8 of the A (X) or B (W) tile of a stage
 #define BG_DMA_A(buf, k0, q)                                                                                \
@@ -808,7 +810,6 @@ __global__ __launch_bounds__(256, 1) void gemm_big_kernel(GemmParams p, int tile
   __syncthreads();                                            \
   BG_OPS(av0, bv0, 1 - (buf), 0)
 
-  const int stages = p.K / BK;  // even (launcher): the loop below retires two stages per trip
 #pragma unroll
   for (int q = 0; q < 8; ++q) {
     BG_DMA_A(0, 0, q)
@@ -843,6 +844,24 @@ __global__ __launch_bounds__(256, 1) void gemm_big_kernel(GemmParams p, int tile
     __builtin_amdgcn_sched_barrier(0);                                                            \
   }
 #define BG_OUT_ROW(i) BG_OUT(i, 0) BG_OUT(i, 1) BG_OUT(i, 2) BG_OUT(i, 3)
+  if (p.splitK > 1 || p.defer) {
+    // fp32 partial sums [split, M, N]: 32 lanes = 128 contiguous bytes of a row per store
+    const int mrow = m0 + wm * 128 + 4 * h;
+    float* part = p.part + ((long long)blockIdx.y * p.M + mrow) * p.N + n0 + wn * 128 + c32;
+#define BG_PART(i, j)                                                                             \
+  {                                                                                               \
+    _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                              \
+      const int dm = (i) * 32 + 8 * (r >> 2) + (r & 3);                                           \
+      if (mrow + dm < p.M) part[dm * p.N + (j) * 32] = acc[i][j][r];                              \
+    }                                                                                             \
+    __builtin_amdgcn_sched_barrier(0);                                                            \
+  }
+#define BG_PART_ROW(i) BG_PART(i, 0) BG_PART(i, 1) BG_PART(i, 2) BG_PART(i, 3)
+    BG_PART_ROW(0) BG_PART_ROW(1) BG_PART_ROW(2) BG_PART_ROW(3)
+#undef BG_PART_ROW
+#undef BG_PART
+    return;
+  }
   ACT_SWITCH(p.act, { BG_OUT_ROW(0) BG_OUT_ROW(1) BG_OUT_ROW(2) BG_OUT_ROW(3) })
 #undef BG_OUT_ROW
 #undef BG_OUT
@@ -934,13 +953,25 @@ int launch_big(const GemmParams& p, hipStream_t st) {
     attr_set = true;
   }
   const int tiles_m = (p.M + 255) / 256, tiles_n = p.N / 256;
-  hipLaunchKernelGGL(gemm_big_kernel, dim3(tiles_m * tiles_n), dim3(256), lds_bytes, st, p, tiles_m, tiles_n);
+  hipLaunchKernelGGL(gemm_big_kernel, dim3(tiles_m * tiles_n, p.splitK), dim3(256), lds_bytes, st, p, tiles_m, tiles_n);
   return hip_ok(hipGetLastError());
 }
-// enough 256 x 256 tiles to occupy most of the 256 CUs, otherwise the tile kernel in row passes does better
-bool big_ok(int M, int N, int K) {
-  return N % 256 == 0 && K % (2 * BK) == 0 && (long long)((M + 255) / 256) * (N / 256) >= 192;
+// The big-tile kernel takes a product when its 256 x 256 tiles occupy at least half the CUs, or, from 1024
+// rows on, when splitting the contraction across workgroups gets them there (each split keeps at least 16
+// stages, an even number): below that the weight-streaming kernels in passes of 128 rows are as fast
+// (measured at 512 rows) and leave no fp32 partials.  Returns the split count, 0 when the kernel does not
+// apply.
+int big_splits(int M, int N, int K) {
+  if (M < 256 || N % 256 != 0 || N > (1 << 22) || K % (2 * BK) != 0) return 0;
+  const long long tiles = (long long)((M + 255) / 256) * (N / 256);
+  if (tiles >= 128) return 1;
+  if (M < 1024) return 0;
+  const int stages = K / BK;
+  int s = 1;
+  while (tiles * s < 200 && s < 8 && stages % (4 * s) == 0 && stages / (2 * s) >= 16) s *= 2;
+  return tiles * s >= 128 ? s : 0;
 }
+bool big_ok(int M, int N, int K) { return big_splits(M, N, K) > 0; }
 
 bool skinny_ok(int M, int N, int K, int dtype, long long ldx) {
   return dtype == TANDEM_BF16 && N % 32 == 0 && K % 64 == 0 && ldx % 8 == 0 && M >= 1;
@@ -953,7 +984,9 @@ bool stream_ok(int M, int N, int K) { return M > 32 && N % 128 == 0 && K % (4 * 
 int gemm_splitk(int M, int N, int K, bool packed) {
   const int mpasses = (M + 127) / 128;
   const int chunks = K / 64;
-  int s = 1;
+  int s = big_splits(M, N, K);
+  if (s > 0) return s;
+  s = 1;
   if (packed && stream_ok(M, N, K)) {
     // at most one workgroup per CU (a second round of workgroups would run alone), at least four stages each
     const int tiles = (N / 128) * mpasses, stages = K / SK;
@@ -986,7 +1019,6 @@ int launch_pack_weights(const void* W, void* Wp, int64_t N, int64_t K, hipStream
 
 size_t gemm_workspace(int M, int N, int K, int dtype) {
   if (!skinny_ok(M, N, K, dtype, 8)) return 0;
-  if (big_ok(M, N, K)) return 0;
   const int a = gemm_splitk(M, N, K, false), b = gemm_splitk(M, N, K, true);
   const int s = a > b ? a : b;
   return s > 1 ? (size_t)s * M * N * sizeof(float) : 0;
@@ -1013,11 +1045,18 @@ int launch_gemm(const GemmArgs& g, hipStream_t st) {
   p.defer = g.defer;
   if (skinny_ok(g.M, g.N, g.K, g.dtype, g.ldx) && (reinterpret_cast<uintptr_t>(g.X) % 16 == 0) &&
       (reinterpret_cast<uintptr_t>(g.W) % 16 == 0) && (reinterpret_cast<uintptr_t>(g.Y) % 8 == 0) && g.ldy % 4 == 0) {
-    if (big_ok(g.M, g.N, g.K) && !g.defer) return launch_big(p, st);
-    const bool packed = g.Wp && stream_ok(g.M, g.N, g.K);
+    const bool big = big_ok(g.M, g.N, g.K);
+    const bool packed = !big && g.Wp && stream_ok(g.M, g.N, g.K);
     if (packed && reinterpret_cast<uintptr_t>(g.Wp) % 16 != 0) return TANDEM_ERR_SHAPE;
     p.splitK = gemm_splitk(g.M, g.N, g.K, packed);
     if ((p.splitK > 1 || g.defer) && (size_t)p.splitK * g.M * g.N * sizeof(float) > g.ws_bytes) return TANDEM_ERR_WORKSPACE;
+    if (big) {
+      const int rc = launch_big(p, st);
+      if (rc != TANDEM_OK || p.splitK == 1 || g.defer) return rc;
+      const long long total = (long long)g.M * g.N;
+      hipLaunchKernelGGL(gemm_splitk_epilogue_kernel<bf16_t>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, p);
+      return hip_ok(hipGetLastError());
+    }
     const int mt = g.M <= 32 ? 1 : (g.M <= 64 ? 2 : 4);
     const int mpasses = (g.M + 32 * mt - 1) / (32 * mt);
     int rc;

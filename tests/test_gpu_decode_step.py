@@ -311,7 +311,7 @@ def test_free_token_stream_equals_greedy_large_decode_fp32(tb):
         assert got[:n_new] == want, (gamma, got, want)
 
 
-@pytest.mark.parametrize("chunks,B", [((4, 1, 6), 3), ((32, 9), 2), ((16,), 5)])
+@pytest.mark.parametrize("chunks,B", [((4, 1, 6), 3), ((32, 9), 2), ((16,), 5), ((32,), 9)])  # last: 288 rows, big tiles
 def test_prefill_bf16_vs_oracle(tb, chunks, B):
     """tandem_prefill chunk by chunk (ragged starting lengths): new cache rows, x^(L_L) and n against the oracle;
     rows outside the written range stay bit-identical."""

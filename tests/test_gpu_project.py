@@ -61,7 +61,10 @@ def test_project_parity_small(tb, M, d_L, d_hidden, d_S, dtype, act):
     print(f"project {M,d_L,d_hidden,d_S,dtype}: max rel err {e[0]:.2e}")
 
 
-@pytest.mark.parametrize("M,d_L,d_hidden,d_S", [(3000, 256, 0, 4096), (3072, 384, 0, 4096), (2100, 128, 4096, 512)])
+@pytest.mark.parametrize("M,d_L,d_hidden,d_S", [(3000, 256, 0, 4096), (3072, 384, 0, 4096), (2100, 128, 4096, 512),
+                                                 (1024, 8192, 0, 4096),    # 64 big tiles: contraction split 4 ways
+                                                 (1100, 4096, 0, 6144),    # 120 big tiles, split 2 ways, ragged rows
+                                                 (300, 1024, 4096, 256)])  # few rows: row passes
 def test_project_parity_prompt_sized(tb, M, d_L, d_hidden, d_S):
     """Prompt-time FF_Tandem (thousands of rows): the compute-bound 256 x 256 tile kernel, ragged last row tile."""
     case = inputs.project_case(41, M, d_L, d_hidden, d_S, dtype="bf16", w_std=0.05, bias_std=0.1)
