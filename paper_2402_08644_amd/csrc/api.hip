@@ -48,14 +48,14 @@ const char* tandem_status_string(int status) {
 
 size_t tandem_draft_attn_workspace(const tandem_attn_desc* a) {
   if (check_attn_desc(a) != TANDEM_OK) return 0;
-  const int S = attn_rows_splits(a->B, a->Hkv, 1, a->T_max, a->gamma_max);
+  const int S = attn_rows_splits(a->B, a->Hkv, 1, a->Hq / a->Hkv, a->T_max, a->gamma_max, nullptr);
   return carved_bytes((size_t)a->B * a->Hq, S, a->dh);
 }
 
 size_t tandem_block_attn_workspace(const tandem_attn_desc* a, int32_t q_len) {
   if (check_attn_desc(a) != TANDEM_OK || q_len < 1 || q_len > TANDEM_MAX_QLEN) return 0;
-  const int S = block_uses_mfma(a) ? attn_block_splits(a->B, a->Hkv, a->T_max)
-                                   : attn_rows_splits(a->B, a->Hkv, q_len, a->T_max, 0);
+  const int S = block_uses_mfma(a) ? attn_block_splits(a->B, a->Hkv, q_len, a->Hq / a->Hkv, a->T_max, nullptr)
+                                   : attn_rows_splits(a->B, a->Hkv, q_len, a->Hq / a->Hkv, a->T_max, 0, nullptr);
   return carved_bytes((size_t)a->B * q_len * a->Hq, S, a->dh);
 }
 
@@ -88,7 +88,7 @@ int tandem_draft_attn(const tandem_attn_desc* a, const void* q, const void* k_ha
   x.scale = a->scale;
   x.dtype = a->dtype;
   x.out = out;
-  x.S = attn_rows_splits(a->B, a->Hkv, 1, a->T_max, a->gamma_max);
+  x.S = attn_rows_splits(a->B, a->Hkv, 1, a->Hq / a->Hkv, a->T_max, a->gamma_max, &x.wide);
   if (x.S > 1) carve(ws, (size_t)a->B * a->Hq, x.S, &x.part_ml, &x.part_o);
   return launch_attn_rows(x, (hipStream_t)hip_stream);
 }
@@ -122,7 +122,9 @@ int tandem_block_attn(const tandem_attn_desc* a, const void* q, const void* k_ca
   x.dtype = a->dtype;
   x.out = out;
   const bool mfma = block_uses_mfma(a);
-  x.S = mfma ? attn_block_splits(a->B, a->Hkv, a->T_max) : attn_rows_splits(a->B, a->Hkv, q_len, a->T_max, 0);
+  x.wide = 0;
+  x.S = mfma ? attn_block_splits(a->B, a->Hkv, q_len, a->Hq / a->Hkv, a->T_max, &x.wide)
+             : attn_rows_splits(a->B, a->Hkv, q_len, a->Hq / a->Hkv, a->T_max, 0, &x.wide);
   if (x.S > 1) carve(ws, (size_t)a->B * q_len * a->Hq, x.S, &x.part_ml, &x.part_o);
   return mfma ? launch_attn_block(x, (hipStream_t)hip_stream) : launch_attn_rows(x, (hipStream_t)hip_stream);
 }

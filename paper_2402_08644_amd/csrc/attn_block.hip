@@ -55,9 +55,11 @@ __device__ __forceinline__ f32x4 mfma16(const bf16x8& a, const bf16x8& b, const 
 
 constexpr int ST_REGS = 34;  // per-lane state of one row tile: m, l, 32 accumulators
 
-template <int RT>
-__global__ __launch_bounds__(256, (RT <= 2 ? 2 : 1)) void attn_block_kernel(BlockParams p) {
-  extern __shared__ float lds[];  // [2][RT][ST_REGS][64]
+// NW wavefronts per workgroup (4 or 8): eight put the work of two context splits into one workgroup, whose
+// wavefronts merge through LDS, so that no partials leave the workgroup and no combine kernel follows.
+template <int RT, int NW>
+__global__ __launch_bounds__(64 * NW, (RT <= 2 && NW == 4 ? 2 : 1)) void attn_block_kernel(BlockParams p) {
+  extern __shared__ float lds[];  // [NW / 2][RT][ST_REGS][64]
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int g4 = lane >> 4, c16 = lane & 15;
   const int s = blockIdx.x, b = blockIdx.z;
@@ -125,7 +127,7 @@ __global__ __launch_bounds__(256, (RT <= 2 ? 2 : 1)) void attn_block_kernel(Bloc
     for (int db = 0; db < 8; ++db) acc[rt][db] = (f32x4){0.f, 0.f, 0.f, 0.f};
   }
 
-  for (long long ti = tile_begin + w; ti < tile_end; ti += 4) {
+  for (long long ti = tile_begin + w; ti < tile_end; ti += NW) {
     const long long key0 = ti << 5;
     bf16x8 kreg[2][4], vreg[2][4];
 #pragma unroll
@@ -194,7 +196,7 @@ __global__ __launch_bounds__(256, (RT <= 2 ? 2 : 1)) void attn_block_kernel(Bloc
     l[rt] += __shfl_xor(l[rt], 32);
   }
 
-  // tree merge of the 4 wavefronts through LDS (lane-local: all waves use the same layout)
+  // tree merge of the wavefronts through LDS (lane-local: all waves use the same layout)
   auto slot = [&](int buf, int rt, int reg) -> float& { return lds[((buf * RT + rt) * ST_REGS + reg) * 64 + lane]; };
   auto put = [&](int buf) {
 #pragma unroll
@@ -221,7 +223,13 @@ __global__ __launch_bounds__(256, (RT <= 2 ? 2 : 1)) void attn_block_kernel(Bloc
         for (int r4 = 0; r4 < 4; ++r4) acc[rt][db][r4] = acc[rt][db][r4] * ca + slot(buf, rt, 2 + db * 4 + r4) * cb;
     }
   };
-  if (w >= 2) put(w - 2);
+  if (NW == 8) {
+    if (w >= 4) put(w - 4);
+    __syncthreads();
+    if (w < 4) take(w);
+    __syncthreads();
+  }
+  if (w >= 2 && w < 4) put(w - 2);
   __syncthreads();
   if (w < 2) take(w);
   __syncthreads();
@@ -257,17 +265,17 @@ __global__ __launch_bounds__(256, (RT <= 2 ? 2 : 1)) void attn_block_kernel(Bloc
   }
 }
 
-template <int RT>
+template <int RT, int NW>
 int launch_rt(const BlockParams& p, int passes, int B, hipStream_t st) {
-  const size_t lds_bytes = (size_t)2 * RT * ST_REGS * 64 * sizeof(float);
+  const size_t lds_bytes = (size_t)(NW / 2) * RT * ST_REGS * 64 * sizeof(float);
   static bool attr_set = false;
   if (!attr_set && lds_bytes > 48 * 1024) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_block_kernel<RT>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_block_kernel<RT, NW>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
     if (e != hipSuccess) return TANDEM_ERR_HIP;
     attr_set = true;
   }
-  hipLaunchKernelGGL((attn_block_kernel<RT>), dim3(p.S, p.Hkv * passes, B), dim3(256), lds_bytes, st, p);
+  hipLaunchKernelGGL((attn_block_kernel<RT, NW>), dim3(p.S, p.Hkv * passes, B), dim3(64 * NW), lds_bytes, st, p);
   return hip_ok(hipGetLastError());
 }
 
@@ -277,7 +285,7 @@ bool attn_block_supported(const AttnArgs& a) { return a.dtype == TANDEM_BF16 && 
 
 // Context splits: a function of shapes only.  Measured on MI355X: about 512 workgroups in total (two
 // per CU) stream best; more splits only add partials and tail effects.  At least 8 tiles (256 keys) each.
-int attn_block_splits(int B, int Hkv, int64_t T_max) {
+int attn_block_splits(int B, int Hkv, int q_len, int G, int64_t T_max, int* wide) {
   const int64_t groups = (int64_t)B * Hkv;
   int64_t want = (512 + groups - 1) / groups;
   int64_t cap = T_max / 256;
@@ -285,7 +293,10 @@ int attn_block_splits(int B, int Hkv, int64_t T_max) {
   int64_t S = want < cap ? want : cap;
   if (S < 1) S = 1;
   if (S > 64) S = 64;
-  return (int)S;
+  // an even number of splits becomes half as many workgroups of eight wavefronts (up to 32 query rows)
+  const bool w8 = S % 2 == 0 && G * q_len <= 32;
+  if (wide) *wide = w8 ? 1 : 0;
+  return (int)(w8 ? S / 2 : S);
 }
 
 size_t attn_block_workspace(int B, int Hq, int q_len, int S) {
@@ -313,11 +324,11 @@ int launch_attn_block(const AttnArgs& a, hipStream_t st) {
   const int tiles = (R + 15) / 16;
   int rc;
   if (tiles == 1)
-    rc = launch_rt<1>(p, 1, a.B, st);
+    rc = a.wide ? launch_rt<1, 8>(p, 1, a.B, st) : launch_rt<1, 4>(p, 1, a.B, st);
   else if (tiles == 2)
-    rc = launch_rt<2>(p, 1, a.B, st);
+    rc = a.wide ? launch_rt<2, 8>(p, 1, a.B, st) : launch_rt<2, 4>(p, 1, a.B, st);
   else
-    rc = launch_rt<4>(p, (tiles + 3) / 4, a.B, st);
+    rc = launch_rt<4, 4>(p, (tiles + 3) / 4, a.B, st);
   if (rc != TANDEM_OK || a.S == 1) return rc;
   return launch_attn_combine(a.part_ml, a.part_o, a.out, a.B * a.q_len * a.Hq, a.S, 128, a.dtype, st);
 }

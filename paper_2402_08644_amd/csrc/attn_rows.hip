@@ -27,8 +27,10 @@ struct RowsParams {
   float* part_o;
 };
 
-template <typename T, int DH, int G, int U>
-__global__ __launch_bounds__(256) void attn_rows_kernel(RowsParams p) {
+// NW wavefronts per workgroup (4 or 8): eight put the work of two context splits into one workgroup, whose
+// wavefronts merge through LDS, so that no partials leave the workgroup and no combine kernel follows.
+template <typename T, int DH, int G, int U, int NW>
+__global__ __launch_bounds__(64 * NW) void attn_rows_kernel(RowsParams p) {
   constexpr int EPL = DH / 16;  // elements of a row per lane
   constexpr int RB = EPL * (int)sizeof(T);
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -75,7 +77,7 @@ __global__ __launch_bounds__(256) void attn_rows_kernel(RowsParams p) {
     for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
   }
 
-  for (long long base = begin + (long long)w * (4 * U); base < end; base += 16 * U) {
+  for (long long base = begin + (long long)w * (4 * U); base < end; base += 4 * NW * U) {
     Raw<RB> kr[U], vr[U];
     bool valid[U];
 #pragma unroll
@@ -148,8 +150,8 @@ __global__ __launch_bounds__(256) void attn_rows_kernel(RowsParams p) {
     }
   }
 
-  __shared__ float sm_m[4][G], sm_l[4][G];
-  __shared__ float sm_o[4][G][DH];
+  __shared__ float sm_m[NW][G], sm_l[NW][G];
+  __shared__ float sm_o[NW][G][DH];
   if (sub == 0) {
 #pragma unroll
     for (int g = 0; g < G; ++g) {
@@ -162,14 +164,14 @@ __global__ __launch_bounds__(256) void attn_rows_kernel(RowsParams p) {
     }
   }
   __syncthreads();
-  for (int idx = threadIdx.x; idx < G * DH; idx += 256) {
+  for (int idx = threadIdx.x; idx < G * DH; idx += 64 * NW) {
     const int g = idx / DH, d = idx % DH;
     float mn = sm_m[0][g];
 #pragma unroll
-    for (int ww = 1; ww < 4; ++ww) mn = fmaxf(mn, sm_m[ww][g]);
+    for (int ww = 1; ww < NW; ++ww) mn = fmaxf(mn, sm_m[ww][g]);
     float lt = 0.f, ot = 0.f;
 #pragma unroll
-    for (int ww = 0; ww < 4; ++ww) {
+    for (int ww = 0; ww < NW; ++ww) {
       const float c = fast_exp2(sm_m[ww][g] - mn);
       lt += sm_l[ww][g] * c;
       ot += sm_o[ww][g][d] * c;
@@ -204,19 +206,19 @@ __global__ void attn_combine_kernel(const float* __restrict__ part_ml, const flo
   out[row * dh + d] = from_f32<T>(lt > 0.f ? ot / lt : 0.f);
 }
 
-template <typename T, int DH, int G>
+template <typename T, int DH, int G, int NW>
 int launch_rows_t(const RowsParams& p, dim3 grid, hipStream_t st) {
-  hipLaunchKernelGGL((attn_rows_kernel<T, DH, G, 4>), grid, dim3(256), 0, st, p);
+  hipLaunchKernelGGL((attn_rows_kernel<T, DH, G, 4, NW>), grid, dim3(64 * NW), 0, st, p);
   return hip_ok(hipGetLastError());
 }
 
 template <typename T, int DH>
-int launch_rows_g(int G, const RowsParams& p, dim3 grid, hipStream_t st) {
+int launch_rows_g(int G, bool wide, const RowsParams& p, dim3 grid, hipStream_t st) {
   switch (G) {
-    case 1: return launch_rows_t<T, DH, 1>(p, grid, st);
-    case 2: return launch_rows_t<T, DH, 2>(p, grid, st);
-    case 4: return launch_rows_t<T, DH, 4>(p, grid, st);
-    case 8: return launch_rows_t<T, DH, 8>(p, grid, st);
+    case 1: return wide ? launch_rows_t<T, DH, 1, 8>(p, grid, st) : launch_rows_t<T, DH, 1, 4>(p, grid, st);
+    case 2: return wide ? launch_rows_t<T, DH, 2, 8>(p, grid, st) : launch_rows_t<T, DH, 2, 4>(p, grid, st);
+    case 4: return launch_rows_t<T, DH, 4, 4>(p, grid, st);
+    case 8: return launch_rows_t<T, DH, 8, 4>(p, grid, st);
     default: return TANDEM_ERR_UNSUPPORTED;
   }
 }
@@ -225,7 +227,7 @@ int launch_rows_g(int G, const RowsParams& p, dim3 grid, hipStream_t st) {
 
 // Context splits: a function of shapes only.  Measured on MI355X: about 512 workgroups in total (two
 // per CU) stream best; more splits only add partials and tail effects.  At least 256 keys per split.
-int attn_rows_splits(int B, int Hkv, int q_len, int64_t T_max, int gamma_max) {
+int attn_rows_splits(int B, int Hkv, int q_len, int G, int64_t T_max, int gamma_max, int* wide) {
   const int64_t groups = (int64_t)B * Hkv * q_len;
   const int64_t keys = T_max + gamma_max;
   int64_t want = (512 + groups - 1) / groups;
@@ -234,7 +236,10 @@ int attn_rows_splits(int B, int Hkv, int q_len, int64_t T_max, int gamma_max) {
   int64_t S = want < cap ? want : cap;
   if (S < 1) S = 1;
   if (S > 64) S = 64;
-  return (int)S;
+  // an even number of splits becomes half as many workgroups of eight wavefronts (query groups of 1 or 2 heads)
+  const bool w8 = S % 2 == 0 && G <= 2;
+  if (wide) *wide = w8 ? 1 : 0;
+  return (int)(w8 ? S / 2 : S);
 }
 
 size_t attn_rows_workspace(int B, int Hq, int q_len, int dh, int S) {
@@ -276,13 +281,13 @@ int launch_attn_rows(const AttnArgs& a, hipStream_t st) {
   dim3 grid(a.S, a.Hkv * a.q_len, a.B);
   int rc;
   if (a.dtype == TANDEM_BF16 && a.dh == 128)
-    rc = launch_rows_g<bf16_t, 128>(G, p, grid, st);
+    rc = launch_rows_g<bf16_t, 128>(G, a.wide != 0, p, grid, st);
   else if (a.dtype == TANDEM_BF16 && a.dh == 64)
-    rc = launch_rows_g<bf16_t, 64>(G, p, grid, st);
+    rc = launch_rows_g<bf16_t, 64>(G, a.wide != 0, p, grid, st);
   else if (a.dtype == TANDEM_F32 && a.dh == 128)
-    rc = launch_rows_g<float, 128>(G, p, grid, st);
+    rc = launch_rows_g<float, 128>(G, a.wide != 0, p, grid, st);
   else if (a.dtype == TANDEM_F32 && a.dh == 64)
-    rc = launch_rows_g<float, 64>(G, p, grid, st);
+    rc = launch_rows_g<float, 64>(G, a.wide != 0, p, grid, st);
   else
     return TANDEM_ERR_UNSUPPORTED;
   if (rc != TANDEM_OK || a.S == 1) return rc;

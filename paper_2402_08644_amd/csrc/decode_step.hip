@@ -226,10 +226,10 @@ StepPlan make_plan(const tandem_model* m, int B, int gamma, int64_t T_max, int g
   p.ints = take(sizeof(int32_t) * 4 * M);
   // attention scratch: the larger of the draft and the block call
   {
-    const int Sd = attn_rows_splits(B, S.Hkv, 1, T_max, gamma_max);
+    const int Sd = attn_rows_splits(B, S.Hkv, 1, S.Hq / S.Hkv, T_max, gamma_max, nullptr);
     size_t a = Sd > 1 ? align256((size_t)B * S.Hq * Sd * 2 * 4) + (size_t)B * S.Hq * Sd * S.dh * 4 : 0;
     const bool mfma = m->d.dtype == TANDEM_BF16 && L.dh == 128;
-    const int Sb = mfma ? attn_block_splits(B, L.Hkv, T_max) : attn_rows_splits(B, L.Hkv, gamma, T_max, 0);
+    const int Sb = mfma ? attn_block_splits(B, L.Hkv, gamma, L.Hq / L.Hkv, T_max, nullptr) : attn_rows_splits(B, L.Hkv, gamma, L.Hq / L.Hkv, T_max, 0, nullptr);
     const size_t rows = (size_t)B * gamma * L.Hq;
     size_t b = Sb > 1 ? align256(rows * Sb * 2 * 4) + rows * Sb * L.dh * 4 : 0;
     p.attn_ws_bytes = maxz(a, b);
@@ -317,8 +317,8 @@ int attn_call(const Ctx& c, const tandem_decoder_desc& D, const void* q, const v
   a.dtype = c.dtype;
   a.out = out;
   const bool mfma = causal && attn_block_supported(a);
-  a.S = mfma ? attn_block_splits(a.B, a.Hkv, a.T_max)
-             : attn_rows_splits(a.B, a.Hkv, q_len, a.T_max, causal ? 0 : c.st->gamma_max);
+  a.S = mfma ? attn_block_splits(a.B, a.Hkv, q_len, a.Hq / a.Hkv, a.T_max, &a.wide)
+             : attn_rows_splits(a.B, a.Hkv, q_len, a.Hq / a.Hkv, a.T_max, causal ? 0 : c.st->gamma_max, &a.wide);
   if (a.S > 1) {
     const size_t rows = (size_t)a.B * q_len * a.Hq;
     a.part_ml = c.at<float>(c.plan.attn_ws);

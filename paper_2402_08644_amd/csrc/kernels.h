@@ -24,14 +24,17 @@ struct AttnArgs {
   float* part_ml;              // [rows, S, 2]   (m in log2 units, l)
   float* part_o;               // [rows, S, dh]  un-normalised
   int S;                       // number of context splits
+  int wide;                    // 1 = workgroups of eight wavefronts (see attn_*_splits)
 };
 
-int attn_rows_splits(int B, int Hkv, int q_len, int64_t T_max, int gamma_max);
+// number of context splits; *wide (optional) = 1 when the workgroups should have eight wavefronts (AttnArgs::wide)
+int attn_rows_splits(int B, int Hkv, int q_len, int G, int64_t T_max, int gamma_max, int* wide);
 size_t attn_rows_workspace(int B, int Hq, int q_len, int dh, int S);
 int launch_attn_rows(const AttnArgs& a, hipStream_t st);
 
 // MFMA block-mode attention (attn_block.hip): bf16, dh = 128, all G*q_len rows of a KV head per workgroup.
-int attn_block_splits(int B, int Hkv, int64_t T_max);
+// number of context splits; *wide (optional) = 1 when the workgroups should have eight wavefronts (AttnArgs::wide)
+int attn_block_splits(int B, int Hkv, int q_len, int G, int64_t T_max, int* wide);
 size_t attn_block_workspace(int B, int Hq, int q_len, int S);
 bool attn_block_supported(const AttnArgs& a);
 int launch_attn_block(const AttnArgs& a, hipStream_t st);
