@@ -563,10 +563,12 @@ int tandem_pack_weight(const void* W, int64_t N, int64_t K, int32_t dtype, void*
 
 size_t tandem_decode_step_workspace(const tandem_model* m, int32_t B, int32_t gamma) {
   if (!m || B < 1 || gamma < 1 || gamma > TANDEM_MAX_QLEN) return 0;
-  // T_max only scales the split-K scratch, which is capped at 64 splits: size for the cap.  Sized for the
-  // free-token mode (gamma + 1 verified rows), which also covers the plain one.
-  const int nq = gamma < TANDEM_MAX_QLEN ? gamma + 1 : gamma;
-  return make_plan(m, B, nq, (int64_t)1 << 40, gamma).total;
+  // T_max only scales the split-K scratch, which is capped at 64 splits: size for the cap.  The larger of the
+  // plain mode and the free-token mode (gamma + 1 verified rows): more rows can mean fewer contraction splits
+  // and hence less scratch, so neither covers the other.
+  size_t total = make_plan(m, B, gamma, (int64_t)1 << 40, gamma).total;
+  if (gamma < TANDEM_MAX_QLEN) total = maxz(total, make_plan(m, B, gamma + 1, (int64_t)1 << 40, gamma).total);
+  return total;
 }
 
 int tandem_decode_step(const tandem_model* m, const tandem_state_desc* state, int32_t gamma, int32_t flags,

@@ -390,6 +390,22 @@ def test_prefill_error_codes(tb):
     torch.cuda.synchronize()
 
 
+@pytest.mark.parametrize("B,gamma", [(32, 4), (40, 3), (8, 31)])
+def test_decode_step_workspace_covers_both_modes(tb, B, gamma):
+    """tandem_decode_step_workspace(m, B, gamma) bytes are enough with and without the free token (the two modes
+    run different row counts, hence different contraction splits and scratch sizes)."""
+    torch, binding = tb
+    W = small_bf16_pair(99)
+    model = binding.TandemModel(W)
+    gst = binding.TandemState(model, B, 96, gamma)
+    gst.pending.fill_(3)
+    ws = torch.empty(binding.tandem_decode_step_workspace(model, B, gamma), dtype=torch.uint8, device="cuda")
+    binding.tandem_decode_step(model, gst, gamma, ws=ws)
+    binding.tandem_decode_step(model, gst, gamma, ws=ws, free_token=True)
+    torch.cuda.synchronize()
+    assert int(gst.n.min()) >= 2
+
+
 def test_decode_step_error_codes(tb):
     torch, binding = tb
     import ctypes as C
