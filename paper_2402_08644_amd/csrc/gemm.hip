@@ -995,8 +995,10 @@ int gemm_splitk(int M, int N, int K, bool packed) {
     const int tiles = (N / 128) * mpasses, kc = K / KC;  // every split keeps an even number (>= 4) of chunks
     while (tiles * s < 200 && s < 16 && kc % (4 * s) == 0 && kc / (2 * s) >= 4) s *= 2;
   } else {
+    // (from 128 workgroups on a split buys nothing: these products are launch-bound, and a split of a
+    // product with an epilogue costs a second kernel)
     const int tiles = (N / 32) * mpasses;
-    while (tiles * s < 200 && s * 2 * 8 <= chunks && s < 16) s *= 2;
+    while (tiles * s < 128 && s * 2 * 8 <= chunks && s < 16) s *= 2;
   }
   return s;
 }
