@@ -37,6 +37,7 @@ struct GemmParams {
   float* part;  // [splitK, M, N] fp32 partial sums
   long long ldx, ldr, ldy;
   int M, N, K, act, splitK, m_base, defer;
+  int xcd_map;  // stream kernel: 1 = workgroup ids are mapped to (tile, split) so that a split stays on one XCD
 };
 
 __device__ __forceinline__ float apply_act(float v, int act) {
@@ -469,9 +470,26 @@ __global__ __launch_bounds__(512) void gemm_stream_kernel(GemmParams p) {
   const int lane = threadIdx.x & 63;
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int m0 = blockIdx.z * (32 * MT);
+  // (feature tile bx, contraction split by) of this workgroup.  Workgroups go to the 8 XCDs round-robin by id;
+  // the split index follows the XCD, so that the workgroups sharing an XCD's L2 read the same slice of X
+  // (with the plain order an XCD saw every slice, and X competed with the weight stream for its L2).
+  int bx, by;
+  {
+    const int id = blockIdx.x, S = p.splitK, xcd = id & 7;
+    if (p.xcd_map && S >= 8) {
+      by = xcd + 8 * ((id >> 3) % (S >> 3));
+      bx = id / S;
+    } else if (p.xcd_map) {
+      by = xcd % S;
+      bx = (id >> 3) * (8 / S) + xcd / S;
+    } else {
+      bx = id % (p.N / 128);
+      by = id / (p.N / 128);
+    }
+  }
   const int T = (p.K / SK) / p.splitK;  // stages of this workgroup
-  const int sb = blockIdx.y * T;
-  const int rot = (int)((blockIdx.x * 5 + blockIdx.y * 3) % T);
+  const int sb = by * T;
+  const int rot = (int)((bx * 5 + by * 3) % T);
   constexpr int TILE = (32 * MT) * XPS;  // elements of one X buffer
   bf16_t* xs = reinterpret_cast<bf16_t*>(smem);  // [2][32*MT][XPS]
 
@@ -561,7 +579,7 @@ __global__ __launch_bounds__(512) void gemm_stream_kernel(GemmParams p) {
 
   // ---------------- multiplier
   const int c32 = lane & 31, h = lane >> 5;
-  const int n0 = blockIdx.x * 128 + w * 32;
+  const int n0 = bx * 128 + w * 32;
   const bf16_t* wp = (const bf16_t*)p.Wp + (long long)(n0 >> 5) * 32 * p.K + lane * 8;
   const bf16_t* xb0 = xs + c32 * XPS + 32 * h;
   f32x16 acc[MT];
@@ -646,7 +664,7 @@ __global__ __launch_bounds__(512) void gemm_stream_kernel(GemmParams p) {
   // each 32-row tile: a store instruction covers whole 128-byte (fp32) or 64-byte (bf16) row segments.
   const int n = n0 + c32;
   if (p.splitK > 1 || p.defer) {
-    float* dst = p.part + (long long)blockIdx.y * p.M * p.N + n;
+    float* dst = p.part + (long long)by * p.M * p.N + n;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -923,7 +941,10 @@ int launch_stream(const GemmParams& p, int mpasses, hipStream_t st) {
       return TANDEM_ERR_HIP;
     attr_set = true;
   }
-  hipLaunchKernelGGL((gemm_stream_kernel<MT>), dim3(p.N / 128, p.splitK, mpasses), dim3(512), lds_bytes, st, p);
+  GemmParams q = p;
+  const int tiles = p.N / 128, S = p.splitK;
+  q.xcd_map = (S >= 8 ? S % 8 == 0 : (8 % S == 0 && tiles % (8 / S) == 0)) ? 1 : 0;
+  hipLaunchKernelGGL((gemm_stream_kernel<MT>), dim3(tiles * S, 1, mpasses), dim3(512), lds_bytes, st, q);
   return hip_ok(hipGetLastError());
 }
 
@@ -1044,6 +1065,7 @@ int launch_gemm(const GemmArgs& g, hipStream_t st) {
   p.act = g.act;
   p.splitK = 1;
   p.m_base = 0;
+  p.xcd_map = 0;
   p.defer = g.defer;
   if (skinny_ok(g.M, g.N, g.K, g.dtype, g.ldx) && (reinterpret_cast<uintptr_t>(g.X) % 16 == 0) &&
       (reinterpret_cast<uintptr_t>(g.W) % 16 == 0) && (reinterpret_cast<uintptr_t>(g.Y) % 8 == 0) && g.ldy % 4 == 0) {
