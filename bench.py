@@ -209,7 +209,7 @@ def step_bytes(cfg):
     return draft + verify + ff
 
 
-def step_workload(torch, binding, inputs, cfg, seed=3, pack_weights=True):
+def step_workload(torch, binding, inputs, cfg, seed=3, pack_weights=True, free_token=False):
     B, g, ctx = cfg["B"], cfg["gamma"], cfg["ctx"]
     W = device_tandem_weights(inputs, cfg, seed)
     model = binding.TandemModel(W, pack_weights=pack_weights)
@@ -221,17 +221,18 @@ def step_workload(torch, binding, inputs, cfg, seed=3, pack_weights=True):
         return inputs.device_normal(shape, k[0], 1.0)
 
     state = binding.TandemState(model, B, ctx, g, fill=fill)
-    n0 = ctx - g
+    q = g + 1 if free_token else g
+    n0 = ctx - q
     state.n.fill_(n0)
     state.pending.fill_(1)
     ws = torch.empty(binding.tandem_decode_step_workspace(model, B, g), dtype=torch.uint8, device="cuda")
-    out = {"tokens": torch.empty((B, g), dtype=torch.int32, device="cuda"),
+    out = {"tokens": torch.empty((B, q), dtype=torch.int32, device="cuda"),
            "n_accepted": torch.empty((B,), dtype=torch.int32, device="cuda")}
 
     def call(_i):
         state.n.fill_(n0)       # keep the context at ctx: the step itself advances n
         state.pending.fill_(1)
-        binding.tandem_decode_step(model, state, g, ws=ws, out=out)
+        binding.tandem_decode_step(model, state, g, ws=ws, out=out, free_token=free_token)
 
     return call, model, state, out
 
@@ -458,7 +459,8 @@ def run_kernel_workload(torch, binding, inputs, args):
 def run_step_workload(torch, binding, inputs, args):
     cfg = C3
     B, g, ctx = cfg["B"], cfg["gamma"], cfg["ctx"]
-    call, model, state, out = step_workload(torch, binding, inputs, cfg, pack_weights=not args.plain_weights)
+    call, model, state, out = step_workload(torch, binding, inputs, cfg, pack_weights=not args.plain_weights,
+                                            free_token=args.free_token)
     torch.cuda.synchronize()
     ms = _time_calls(torch, call, 1, args.steps, args.warmup, use_graph=not args.no_graph)
 
@@ -498,7 +500,8 @@ def run_step_workload(torch, binding, inputs, args):
         "value": 1e3 / ms, "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "c3_step: tandem_decode_step bf16 B=32 ctx=8192 gamma=4, large 32L d=4096 32/8x128, "
-                               "small 8L d=1024 8x128, FF_Tandem 4096->8192->1024, vocab 32768",
+                               "small 8L d=1024 8x128, FF_Tandem 4096->8192->1024, vocab 32768"
+                               + (", free token (5 verified rows)" if args.free_token else ""),
                    "step_algorithmic_GB": total_bytes / 1e9, "step_GBps": total_bytes / (ms * 1e-3) / 1e9,
                    "step_frac_of_hbm_peak": total_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
         "roofline": {"bound": "hbm", "kernel": "attn_block_kernel (tandem_block_attn, one large layer of the step)",
@@ -521,6 +524,8 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--plain-weights", action="store_true",
                     help="read weights in the caller's row-major layout only (no packed copies)")
+    ap.add_argument("--free-token", action="store_true",
+                    help="c3_step only: verify gamma + 1 rows and emit the bonus token (Fig. 2)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run three plain 1 GiB device copies (known traffic) so that rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE readings of the same run can be scaled")
