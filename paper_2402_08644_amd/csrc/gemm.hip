@@ -1000,6 +1000,27 @@ bool skinny_ok(int M, int N, int K, int dtype, long long ldx) {
 bool tile_ok(int M, int N, int K) { return M > 32 && N % 128 == 0 && K % (2 * KC) == 0; }
 bool stream_ok(int M, int N, int K) { return M > 32 && N % 128 == 0 && K % (4 * SK) == 0; }  // = gemm_packable
 
+// Stream kernel: contraction splits when every pass covers 128 rows: at most one workgroup per CU (a second
+// round of workgroups would run alone), at least four stages each.
+int stream_base_splits(int M, int N, int K) {
+  const int tiles = (N / 128) * ((M + 127) / 128), stages = K / SK;
+  int s = 1;
+  while (tiles * s * 2 <= 256 && s < 16 && stages % (2 * s) == 0 && stages / (2 * s) >= 4) s *= 2;
+  return s;
+}
+
+// Stream kernel, 64 < M <= 128: instead of s contraction splits of 128 rows, two row halves of s / 2 splits
+// each (same number of workgroups).  The halves of a tile run on the same XCD at the same time and share
+// the weight tile through its L2, so every weight still comes from HBM once but crosses L2 -> CU twice;
+// in return half the fp32 partials are written and read back (none at all, and no epilogue kernel, when
+// s was 2).  Measured: a gain unless the weights are much larger than the partials saved (a quarter of
+// the weight bytes is the break-even).
+bool stream_row_halves(int M, int N, int K, int s) {
+  if (M <= 64 || M > 128 || s < 2) return false;
+  const double saved = (double)(s / 2) * M * N * 8.0, extra = 0.25 * 2.0 * N * (double)K;
+  return s == 2 || saved >= extra;
+}
+
 // Split of the contraction across workgroups (a function of the shape only): used when the feature
 // tiles alone cannot occupy the 256 CUs.
 int gemm_splitk(int M, int N, int K, bool packed) {
@@ -1009,9 +1030,8 @@ int gemm_splitk(int M, int N, int K, bool packed) {
   if (s > 0) return s;
   s = 1;
   if (packed && stream_ok(M, N, K)) {
-    // at most one workgroup per CU (a second round of workgroups would run alone), at least four stages each
-    const int tiles = (N / 128) * mpasses, stages = K / SK;
-    while (tiles * s * 2 <= 256 && s < 16 && stages % (2 * s) == 0 && stages / (2 * s) >= 4) s *= 2;
+    s = stream_base_splits(M, N, K);
+    if (stream_row_halves(M, N, K, s)) s /= 2;
   } else if (tile_ok(M, N, K)) {
     const int tiles = (N / 128) * mpasses, kc = K / KC;  // every split keeps an even number (>= 4) of chunks
     while (tiles * s < 200 && s < 16 && kc % (4 * s) == 0 && kc / (2 * s) >= 4) s *= 2;
@@ -1081,7 +1101,8 @@ int launch_gemm(const GemmArgs& g, hipStream_t st) {
       hipLaunchKernelGGL(gemm_splitk_epilogue_kernel<bf16_t>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, p);
       return hip_ok(hipGetLastError());
     }
-    const int mt = g.M <= 32 ? 1 : (g.M <= 64 ? 2 : 4);
+    int mt = g.M <= 32 ? 1 : (g.M <= 64 ? 2 : 4);
+    if (packed && stream_row_halves(g.M, g.N, g.K, stream_base_splits(g.M, g.N, g.K))) mt = 2;  // two passes of 64 rows
     const int mpasses = (g.M + 32 * mt - 1) / (32 * mt);
     int rc;
     if (packed)
