@@ -451,6 +451,33 @@ def greedy_decode_large(ML, prompt, n_new, eps):
 
 
 # ----------------------------------------------------------------------------
+# Several samples per prompt (Sec. 4 "num-samples"; footnote of Table 2): the
+# samples of one prompt share the prompt's K/V rows; each has its own rows
+# for what it generated.  Block-mode attention (Eq. (1) on the new rows) of
+# sample s over [shared rows of its prompt ; its own rows], one softmax.
+# ----------------------------------------------------------------------------
+def block_attn_shared(Q, Ks, Vs, n_shared, Ko, Vo, n_own, scale):
+    """Q [B, ns, q_len, Hq, dh]; Ks, Vs [B, Hkv, Ts, dh] with n_shared[b] valid rows, visible to every
+    row of every sample of prompt b; Ko, Vo [B*ns, Hkv, To, dh], sample (b, s) = sequence b*ns + s, whose
+    query row r sees own rows 0 .. n_own[b*ns+s] + r (its block's rows are already in place)."""
+    Q = np.asarray(Q, F64)
+    B, ns, q_len, Hq, dh = Q.shape
+    Hkv = np.asarray(Ks).shape[1]
+    G = Hq // Hkv
+    out = np.zeros_like(Q)
+    for b in range(B):
+        for s in range(ns):
+            i = b * ns + s
+            for r in range(q_len):
+                for h in range(Hq):
+                    kv = h // G
+                    K = np.concatenate([np.asarray(Ks, F64)[b, kv, : n_shared[b]], np.asarray(Ko, F64)[i, kv, : n_own[i] + r + 1]])
+                    V = np.concatenate([np.asarray(Vs, F64)[b, kv, : n_shared[b]], np.asarray(Vo, F64)[i, kv, : n_own[i] + r + 1]])
+                    out[b, s, r, h] = attention_one(Q[b, s, r, h], K, V, scale)
+    return out
+
+
+# ----------------------------------------------------------------------------
 # a5  split-K re-association of the softmax (exact in real arithmetic):
 #     per split (m_s, l_s, O_s) with O_s un-normalised; merged in split order.
 # ----------------------------------------------------------------------------

@@ -240,3 +240,29 @@ def test_rmsnorm_hand_and_library():
     g = rng.standard_normal(16)
     want = F.rms_norm(torch.from_numpy(x), (16,), torch.from_numpy(g), eps=1e-6).numpy()
     np.testing.assert_allclose(orc.rmsnorm(x, g, 1e-6), want, rtol=1e-12)
+
+
+def test_block_attn_shared_equals_block_attn_on_materialised_caches():
+    """Shared-prompt attention == ordinary block attention on per-sample caches that hold a copy of the prompt
+    rows followed by the sample's own rows (the pinned block_attn, and torch's SDPA through it)."""
+    rng = np.random.default_rng(11)
+    B, ns, q_len, Hq, Hkv, dh, Ts, To = 2, 3, 2, 4, 2, 8, 9, 6
+    Q = rng.standard_normal((B, ns, q_len, Hq, dh))
+    Ks, Vs = rng.standard_normal((B, Hkv, Ts, dh)), rng.standard_normal((B, Hkv, Ts, dh))
+    Ko, Vo = rng.standard_normal((B * ns, Hkv, To, dh)), rng.standard_normal((B * ns, Hkv, To, dh))
+    n_shared = np.array([9, 0])
+    n_own = np.array([0, 3, 4, 1, 0, 2])
+    scale = dh ** -0.5
+    got = orc.block_attn_shared(Q, Ks, Vs, n_shared, Ko, Vo, n_own, scale)
+    Kc = np.zeros((B * ns, Hkv, Ts + To, dh))
+    Vc = np.zeros_like(Kc)
+    n = np.zeros(B * ns, dtype=np.int64)
+    for b in range(B):
+        for s_ in range(ns):
+            i = b * ns + s_
+            m = n_shared[b]
+            Kc[i, :, :m], Vc[i, :, :m] = Ks[b, :, :m], Vs[b, :, :m]
+            Kc[i, :, m : m + To], Vc[i, :, m : m + To] = Ko[i], Vo[i]
+            n[i] = m + n_own[i]
+    want = orc.block_attn(Q.reshape(B * ns, q_len, Hq, dh), Kc, Vc, n, scale).reshape(Q.shape)
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-13)
