@@ -150,6 +150,70 @@ def block_workload(torch, binding, inputs, B, q_len, Hq, Hkv, dh, n_prefix, seed
     return call, R, bytes_alg, oracle_sample
 
 
+def shared_workload(torch, binding, inputs, B, samples, q_len, Hq, Hkv, dh, n_shared, n_own, seed, copied=False):
+    """Block-mode attention with `samples` continuations per prompt.  copied=False: the prompt rows stored and
+    read once per prompt (tandem_block_attn_shared).  copied=True: the form it replaces - every sample holds a
+    copy of the prompt rows in its own cache (tandem_block_attn) - on the same values."""
+    T_own = n_own + q_len
+    nseq = B * samples
+    if copied:
+        bytes_alg = nseq * Hkv * (n_shared + T_own) * dh * 2 * 2
+    else:
+        bytes_alg = (B * n_shared + nseq * T_own) * Hkv * dh * 2 * 2
+    R = _rotations(bytes_alg)
+    sets = []
+    for i in range(R):
+        c = dict(
+            q=inputs.device_normal((B, samples, q_len, Hq, dh), seed * 100 + 5 * i, 1.0),
+            ks=inputs.device_normal((B, Hkv, n_shared, dh), seed * 100 + 5 * i + 1, 1.0),
+            vs=inputs.device_normal((B, Hkv, n_shared, dh), seed * 100 + 5 * i + 2, 1.0),
+            ko=inputs.device_normal((nseq, Hkv, T_own, dh), seed * 100 + 5 * i + 3, 1.0),
+            vo=inputs.device_normal((nseq, Hkv, T_own, dh), seed * 100 + 5 * i + 4, 1.0),
+        )
+        if copied:
+            rep = lambda t: t.repeat_interleave(samples, dim=0)
+            c["k"] = torch.cat([rep(c["ks"]), c["ko"]], dim=2).contiguous()
+            c["v"] = torch.cat([rep(c["vs"]), c["vo"]], dim=2).contiguous()
+            if i > 0:
+                del c["ks"], c["vs"], c["ko"], c["vo"]
+        sets.append(c)
+    ns_t = torch.full((B,), n_shared, dtype=torch.int32, device="cuda")
+    no_t = torch.full((nseq,), n_own, dtype=torch.int32, device="cuda")
+    n_t = torch.full((nseq,), n_shared + n_own, dtype=torch.int32, device="cuda")
+    out = torch.empty((B, samples, q_len, Hq, dh), dtype=torch.bfloat16, device="cuda")
+    if copied:
+        d = binding.attn_desc(nseq, Hq, Hkv, dh, n_shared + T_own, 0, 1.0 / math.sqrt(dh), binding.BF16)
+        ws = binding.workspace(binding.tandem_block_attn_workspace(d, q_len))
+    else:
+        d = binding.attn_desc(B, Hq, Hkv, dh, n_shared, 0, 1.0 / math.sqrt(dh), binding.BF16)
+        ws = binding.workspace(binding.tandem_block_attn_shared_workspace(d, samples, T_own, q_len))
+
+    def call(i):
+        s = sets[i]
+        if copied:
+            binding.tandem_block_attn(s["q"].view(nseq, q_len, Hq, dh), s["k"], s["v"], n_t,
+                                      out=out.view(nseq, q_len, Hq, dh), ws=ws)
+        else:
+            binding.tandem_block_attn_shared(s["q"], s["ks"], s["vs"], ns_t, s["ko"], s["vo"], no_t, out=out, ws=ws)
+
+    def oracle_sample(n_prompts):
+        from oracle import tandem_oracle as orc
+
+        s = sets[0]
+        f = inputs.torch_to_f64
+        args = (f(s["q"][:n_prompts]), f(s["ks"][:n_prompts]), f(s["vs"][:n_prompts]), ns_t[:n_prompts].cpu().numpy(),
+                f(s["ko"][:n_prompts * samples]), f(s["vo"][:n_prompts * samples]),
+                no_t[:n_prompts * samples].cpu().numpy(), 1.0 / math.sqrt(dh))
+        t0 = time.perf_counter()
+        want = orc.block_attn_shared(*args)
+        dt = time.perf_counter() - t0
+        call(0)
+        torch.cuda.synchronize()
+        return dt, want.reshape(-1, Hq, dh), inputs.torch_to_f64(out[:n_prompts]).reshape(-1, Hq, dh)
+
+    return call, R, bytes_alg, oracle_sample
+
+
 # ------------------------------------------------------------------ whole decode step
 C3 = dict(
     B=32, gamma=4, ctx=8192, vocab=32768,
@@ -349,6 +413,15 @@ WORKLOADS = {
                  "tandem_draft_attn bf16 B=32 H=8 dh=128 ctx=8188+4 (one small layer of the decode step)"),
     "c3_block": ("block", dict(B=32, q_len=4, Hq=32, Hkv=8, dh=128, n_prefix=8188, seed=3), 2,
                  "tandem_block_attn bf16 B=32 Hq/Hkv=32/8 dh=128 prefix=8188 gamma=4 (one large layer of the decode step)"),
+    # the latency evaluation's 4 samples per prompt at the C3 layer shape: 8 prompts of 7936 rows, each sample
+    # 251 rows past the prompt, a block of gamma + 1 = 5 rows
+    "s4_shared": ("shared", dict(B=8, samples=4, q_len=5, Hq=32, Hkv=8, dh=128, n_shared=7936, n_own=251, seed=5), 1,
+                  "tandem_block_attn_shared bf16 8 prompts x 4 samples, Hq/Hkv=32/8 dh=128, prompt 7936 rows read once "
+                  "per prompt + 256 own rows per sample, 5 query rows"),
+    "s4_copied": ("shared", dict(B=8, samples=4, q_len=5, Hq=32, Hkv=8, dh=128, n_shared=7936, n_own=251, seed=5,
+                                 copied=True), 1,
+                  "tandem_block_attn bf16 on 32 per-sample caches that each hold a copy of the 7936 prompt rows "
+                  "(the form tandem_block_attn_shared replaces; same values)"),
 }
 
 
@@ -429,7 +502,7 @@ def _traffic(name):
 
 def run_kernel_workload(torch, binding, inputs, args):
     kind, kw, n_seq, desc = WORKLOADS[args.workload]
-    maker = draft_workload if kind == "draft" else block_workload
+    maker = {"draft": draft_workload, "block": block_workload, "shared": shared_workload}[kind]
     call, n_copies, bytes_alg, oracle_sample = maker(torch, binding, inputs, **kw)
     torch.cuda.synchronize()
     ms = _time_calls(torch, call, n_copies, args.steps, args.warmup, use_graph=not args.no_graph)

@@ -48,6 +48,7 @@ typedef enum { TANDEM_F32 = 0, TANDEM_BF16 = 1 } tandem_dtype;
 typedef enum { TANDEM_ACT_NONE = 0, TANDEM_ACT_GELU = 1 /* exact erf form */, TANDEM_ACT_RELU = 2 } tandem_act;
 
 #define TANDEM_MAX_QLEN 32 /* most query rows per sequence in one block-mode pass */
+#define TANDEM_MAX_SHARED_ROWS 256 /* most samples * q_len per prompt in tandem_block_attn_shared */
 
 /* Shape of one attention layer's caches.
  *   caches:            [B, Hkv, T_max, dh]      (large K/V, or the large-derived K_hat/V_hat)
@@ -106,6 +107,28 @@ int tandem_project(const tandem_ff_desc *ff, const void *x, void *y_hat, int64_t
  *   1 <= q_len <= TANDEM_MAX_QLEN.  Reads the caches only; writes out and ws only. */
 int tandem_block_attn(const tandem_attn_desc *a, const void *q, const void *k_cache, const void *v_cache,
                       const int32_t *n_prefix, int32_t q_len, void *out, void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Block-mode attention when several samples continue one prompt (the num-samples > 1 setting of Sec. 3.1,
+ * measured with 4 samples in the latency evaluation of Sec. 4; the footnote of Sec. 3.1 notes that more samples
+ * per prompt raise the efficiency of the attention layer too - this is where that comes from).  The prompt's
+ * K/V rows are stored once per prompt and read once per prompt for all samples' query rows; each sample keeps
+ * only the rows generated after the prompt.  The result equals tandem_block_attn on per-sample caches that
+ * hold a copy of the prompt rows followed by the sample's own rows.  Sample s of prompt b is sequence
+ * i = b * samples + s.  Query row r of sequence i attends, in ONE softmax,
+ *   k_shared/v_shared[b, h/G, 0 : n_shared[b]]  and  k_own/v_own[i, h/G, 0 : n_own[i] + r + 1]
+ * (the q_len new rows of sequence i are already in place at [n_own[i], n_own[i] + q_len)).
+ *   q, out    device [B, samples, q_len, Hq, dh]     (B = a->B prompts)
+ *   k_shared, v_shared device [B, Hkv, a->T_max, dh];  n_shared device int32 [B], clamped to [0, a->T_max]
+ *   k_own, v_own       device [B * samples, Hkv, T_own, dh];  n_own device int32 [B * samples], clamped to
+ *                      [0, T_own - q_len]
+ *   1 <= q_len <= TANDEM_MAX_QLEN, samples * q_len <= TANDEM_MAX_SHARED_ROWS, B * samples <= 65535.
+ * ws: device scratch of at least tandem_block_attn_shared_workspace(...) bytes, always needed (the two key
+ * segments are merged through it).  Reads the caches only; writes out and ws only. */
+size_t tandem_block_attn_shared_workspace(const tandem_attn_desc *a, int32_t samples, int64_t T_own, int32_t q_len);
+int tandem_block_attn_shared(const tandem_attn_desc *a, int32_t samples, int64_t T_own, const void *q,
+                             const void *k_shared, const void *v_shared, const int32_t *n_shared, const void *k_own,
+                             const void *v_own, const int32_t *n_own, int32_t q_len, void *out, void *ws,
+                             size_t ws_bytes, void *hip_stream);
 
 /* Mixed-source small-model attention (Eq. (2), second line; Sec. 3 "Training", both bullets).
  * One query per sequence and head attends, in ONE softmax, the union of

@@ -84,6 +84,7 @@ EXPORTS = (
     "tandem_project_workspace", "tandem_block_attn_workspace", "tandem_draft_attn_workspace",
     "tandem_packed_weight_bytes", "tandem_pack_weight",
     "tandem_project", "tandem_block_attn", "tandem_draft_attn",
+    "tandem_block_attn_shared_workspace", "tandem_block_attn_shared",
     "tandem_model_create", "tandem_model_destroy", "tandem_decode_step_workspace", "tandem_decode_step",
     "tandem_prefill_workspace", "tandem_prefill",
 )
@@ -104,6 +105,10 @@ def lib():
     L.tandem_status_string.argtypes = [C.c_int]
     L.tandem_project_workspace.restype = sz
     L.tandem_project_workspace.argtypes = [C.POINTER(FFDesc), i64]
+    L.tandem_block_attn_shared_workspace.restype = sz
+    L.tandem_block_attn_shared_workspace.argtypes = [C.POINTER(AttnDesc), i32, i64, i32]
+    L.tandem_block_attn_shared.restype = C.c_int
+    L.tandem_block_attn_shared.argtypes = [C.POINTER(AttnDesc), i32, i64, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
     L.tandem_block_attn_workspace.restype = sz
     L.tandem_block_attn_workspace.argtypes = [C.POINTER(AttnDesc), i32]
     L.tandem_draft_attn_workspace.restype = sz
@@ -248,6 +253,45 @@ def tandem_block_attn(q, k_cache, v_cache, n_prefix, scale=None, out=None, ws=No
     rc = lib().tandem_block_attn(C.byref(d), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(n_prefix), q_len, _ptr(out),
                                  _ptr(ws), ws.numel(), _stream(stream))
     _check(rc, "tandem_block_attn")
+    return out
+
+
+def tandem_block_attn_shared_workspace(desc: AttnDesc, samples: int, T_own: int, q_len: int) -> int:
+    return int(lib().tandem_block_attn_shared_workspace(C.byref(desc), samples, T_own, q_len))
+
+
+def tandem_block_attn_shared(q, k_shared, v_shared, n_shared, k_own, v_own, n_own, scale=None, out=None, ws=None,
+                             stream=None):
+    """q [B,samples,q_len,Hq,dh]; k_shared,v_shared [B,Hkv,T_max,dh], n_shared int32 [B]; k_own,v_own
+    [B*samples,Hkv,T_own,dh], n_own int32 [B*samples]."""
+    import torch
+
+    B, ns, q_len, Hq, dh = q.shape
+    _, Hkv, T_max, _ = k_shared.shape
+    T_own = k_own.shape[2]
+    _need(q, (B, ns, q_len, Hq, dh), "q")
+    for t, nm in ((k_shared, "k_shared"), (v_shared, "v_shared")):
+        _need(t, (B, Hkv, T_max, dh), nm)
+    for t, nm in ((k_own, "k_own"), (v_own, "v_own")):
+        _need(t, (B * ns, Hkv, T_own, dh), nm)
+    _need(n_shared, (B,), "n_shared")
+    _need(n_own, (B * ns,), "n_own")
+    for t, nm in ((n_shared, "n_shared"), (n_own, "n_own")):
+        if t.dtype != torch.int32:
+            raise TypeError(f"{nm} must be int32")
+    for t in (k_shared, v_shared, k_own, v_own):
+        if t.dtype != q.dtype:
+            raise TypeError("q / K / V dtypes differ")
+    d = attn_desc(B, Hq, Hkv, dh, T_max, 0, (1.0 / math.sqrt(dh)) if scale is None else scale, _dtype_code(q))
+    if out is None:
+        out = torch.empty_like(q)
+    need = tandem_block_attn_shared_workspace(d, ns, T_own, q_len)
+    if ws is None:
+        ws = _workspace(max(need, 256), q)
+    rc = lib().tandem_block_attn_shared(C.byref(d), ns, T_own, _ptr(q), _ptr(k_shared), _ptr(v_shared), _ptr(n_shared),
+                                        _ptr(k_own), _ptr(v_own), _ptr(n_own), q_len, _ptr(out), _ptr(ws), ws.numel(),
+                                        _stream(stream))
+    _check(rc, "tandem_block_attn_shared")
     return out
 
 

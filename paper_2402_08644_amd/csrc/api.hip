@@ -30,6 +30,31 @@ size_t carved_bytes(size_t rows, int S, int dh) {
   return align256(rows * S * 2 * sizeof(float)) + rows * S * dh * sizeof(float);
 }
 
+// Splits of the two key segments of shared-prompt attention: the prompt rows (one workgroup set per prompt, all
+// samples' rows together) and each sample's own rows.
+struct SharedPlan {
+  int S1, wide1, S2, wide2;
+};
+int plan_shared(const tandem_attn_desc* a, int32_t samples, int64_t T_own, int32_t q_len, SharedPlan* pl) {
+  int rc = check_attn_desc(a);
+  if (rc != TANDEM_OK) return rc;
+  if (samples < 1 || q_len < 1 || q_len > TANDEM_MAX_QLEN || (int64_t)samples * q_len > TANDEM_MAX_SHARED_ROWS)
+    return TANDEM_ERR_SHAPE;
+  if (T_own < q_len || (int64_t)a->B * samples > 65535) return TANDEM_ERR_SHAPE;
+  if ((int64_t)a->Hkv * samples * q_len > 65535) return TANDEM_ERR_SHAPE;
+  const int G = a->Hq / a->Hkv;
+  const int rows1 = samples * q_len;
+  pl->wide1 = pl->wide2 = 0;
+  if (block_uses_mfma(a)) {
+    pl->S1 = attn_block_splits(a->B, a->Hkv, rows1, G, a->T_max, &pl->wide1);
+    pl->S2 = attn_block_splits(a->B * samples, a->Hkv, q_len, G, T_own, &pl->wide2);
+  } else {
+    pl->S1 = attn_rows_splits(a->B, a->Hkv, rows1, G, a->T_max, 0, &pl->wide1);
+    pl->S2 = attn_rows_splits(a->B * samples, a->Hkv, q_len, G, T_own, 0, &pl->wide2);
+  }
+  return TANDEM_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -127,6 +152,64 @@ int tandem_block_attn(const tandem_attn_desc* a, const void* q, const void* k_ca
              : attn_rows_splits(a->B, a->Hkv, q_len, a->Hq / a->Hkv, a->T_max, 0, &x.wide);
   if (x.S > 1) carve(ws, (size_t)a->B * q_len * a->Hq, x.S, &x.part_ml, &x.part_o);
   return mfma ? launch_attn_block(x, (hipStream_t)hip_stream) : launch_attn_rows(x, (hipStream_t)hip_stream);
+}
+
+size_t tandem_block_attn_shared_workspace(const tandem_attn_desc* a, int32_t samples, int64_t T_own, int32_t q_len) {
+  SharedPlan pl;
+  if (plan_shared(a, samples, T_own, q_len, &pl) != TANDEM_OK) return 0;
+  return carved_bytes((size_t)a->B * samples * q_len * a->Hq, pl.S1 + pl.S2, a->dh);
+}
+
+int tandem_block_attn_shared(const tandem_attn_desc* a, int32_t samples, int64_t T_own, const void* q,
+                             const void* k_shared, const void* v_shared, const int32_t* n_shared, const void* k_own,
+                             const void* v_own, const int32_t* n_own, int32_t q_len, void* out, void* ws,
+                             size_t ws_bytes, void* hip_stream) {
+  SharedPlan pl;
+  int rc = plan_shared(a, samples, T_own, q_len, &pl);
+  if (rc != TANDEM_OK) return rc;
+  if (!q || !k_shared || !v_shared || !n_shared || !k_own || !v_own || !n_own || !out || !ws) return TANDEM_ERR_NULL;
+  const size_t rows = (size_t)a->B * samples * q_len * a->Hq;
+  const int S = pl.S1 + pl.S2;
+  if (ws_bytes < carved_bytes(rows, S, a->dh)) return TANDEM_ERR_WORKSPACE;
+  const bool mfma = block_uses_mfma(a);
+  hipStream_t st = (hipStream_t)hip_stream;
+  AttnArgs x{};
+  x.q = q;
+  x.Hq = a->Hq;
+  x.Hkv = a->Hkv;
+  x.dh = a->dh;
+  x.scale = a->scale;
+  x.dtype = a->dtype;
+  x.out = out;
+  x.S_total = S;
+  carve(ws, rows, S, &x.part_ml, &x.part_o);
+  // prompt rows: per prompt, the samples * q_len query rows form one block that sees all n_shared[b] keys
+  x.kA = k_shared;
+  x.vA = v_shared;
+  x.nA = n_shared;
+  x.causal = 0;
+  x.B = a->B;
+  x.q_len = samples * q_len;
+  x.T_max = a->T_max;
+  x.S = pl.S1;
+  x.wide = pl.wide1;
+  x.s_off = 0;
+  rc = mfma ? launch_attn_block(x, st) : launch_attn_rows(x, st);
+  if (rc != TANDEM_OK) return rc;
+  // own rows: every sample is a sequence of its own, causal inside the block
+  x.kA = k_own;
+  x.vA = v_own;
+  x.nA = n_own;
+  x.causal = 1;
+  x.B = a->B * samples;
+  x.q_len = q_len;
+  x.T_max = T_own;
+  x.S = pl.S2;
+  x.wide = pl.wide2;
+  x.s_off = pl.S1;
+  rc = mfma ? launch_attn_block(x, st) : launch_attn_rows(x, st);
+  if (rc != TANDEM_OK) return rc;
+  return launch_attn_combine(x.part_ml, x.part_o, out, (int)rows, S, a->dh, a->dtype, st);
 }
 
 }  // extern "C"

@@ -29,6 +29,8 @@ struct BlockParams {
   const bf16_t *q, *k, *v;
   const int32_t* n;
   int Hq, Hkv, q_len, G, S;
+  int causal;         // 1: the q_len rows are the last rows of the cache (row r sees n + r + 1 keys); 0: all see n keys
+  int S_total, s_off;  // partial slots per row and this launch's first slot
   long long T_max;
   float scale_log2e;
   bf16_t* out;
@@ -49,6 +51,14 @@ __device__ __forceinline__ bf16x8 pack8(const f32x4& a, const f32x4& b) {
   u.w = pack_bf16x2_alu(b[2], b[3]);
   return __builtin_bit_cast(bf16x8, u);
 }
+__device__ __forceinline__ bf16x8 pack8_hw(const f32x4& a, const f32x4& b) {
+  uint4 u;
+  u.x = pack_bf16x2(a[0], a[1]);
+  u.y = pack_bf16x2(a[2], a[3]);
+  u.z = pack_bf16x2(b[0], b[1]);
+  u.w = pack_bf16x2(b[2], b[3]);
+  return __builtin_bit_cast(bf16x8, u);
+}
 __device__ __forceinline__ f32x4 mfma16(const bf16x8& a, const bf16x8& b, const f32x4& c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
@@ -66,9 +76,10 @@ __global__ __launch_bounds__(64 * NW, (RT <= 2 && NW == 4 ? 2 : 1)) void attn_bl
   const int kvh = blockIdx.y % p.Hkv, pass = blockIdx.y / p.Hkv;
 
   long long n = p.n[b];
-  const long long nmax = p.T_max - p.q_len;
+  const int ext = p.causal ? p.q_len : 0;
+  const long long nmax = p.T_max - ext;
   n = n < 0 ? 0 : (n > nmax ? nmax : n);
-  const long long total = n + p.q_len;
+  const long long total = n + ext;
   const int R = p.G * p.q_len;
 
   const long long ntiles = (total + 31) >> 5;
@@ -89,7 +100,7 @@ __global__ __launch_bounds__(64 * NW, (RT <= 2 && NW == 4 ? 2 : 1)) void attn_bl
     if (rho < R) {
       const int r = rho / p.G, gq = rho % p.G;
       orow[rt] = ((long long)b * p.q_len + r) * p.Hq + kvh * p.G + gq;
-      lim[rt] = n + r;
+      lim[rt] = p.causal ? n + r : n - 1;
       const bf16_t* qp = p.q + orow[rt] * 128 + 8 * g4;
 #pragma unroll
       for (int c = 0; c < 4; ++c) qreg[rt][c] = ld_bf16x8(qp + 32 * c);
@@ -240,7 +251,7 @@ __global__ __launch_bounds__(64 * NW, (RT <= 2 && NW == 4 ? 2 : 1)) void attn_bl
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
       if (orow[rt] < 0) continue;
-      if (p.S == 1) {
+      if (p.S_total == 1) {
         const float inv = l[rt] > 0.f ? 1.f / l[rt] : 0.f;
         bf16_t* op = p.out + orow[rt] * 128 + 4 * g4;
 #pragma unroll
@@ -251,18 +262,240 @@ __global__ __launch_bounds__(64 * NW, (RT <= 2 && NW == 4 ? 2 : 1)) void attn_bl
           *reinterpret_cast<uint2*>(op + 16 * db) = u;
         }
       } else {
-        float* op = p.part_o + (orow[rt] * p.S + s) * 128 + 4 * g4;
+        const long long ps = orow[rt] * p.S_total + p.s_off + s;
+        float* op = p.part_o + ps * 128 + 4 * g4;
 #pragma unroll
         for (int db = 0; db < 8; ++db)
           *reinterpret_cast<float4*>(op + 16 * db) =
               make_float4(acc[rt][db][0], acc[rt][db][1], acc[rt][db][2], acc[rt][db][3]);
         if (g4 == 0) {
-          p.part_ml[(orow[rt] * p.S + s) * 2 + 0] = m[rt];
-          p.part_ml[(orow[rt] * p.S + s) * 2 + 1] = l[rt];
+          p.part_ml[ps * 2 + 0] = m[rt];
+          p.part_ml[ps * 2 + 1] = l[rt];
         }
       }
     }
   }
+}
+
+// Many query rows per KV head (G * q_len > 32: long prompt blocks, several samples per prompt).  Splitting the
+// keys over the wavefronts, as above, would need one pass over K and V per 32 rows; here the wavefronts split
+// the ROWS instead - wavefront w owns row tile w (16 query columns) for the whole key range of the workgroup,
+// so no merge between wavefronts is needed - and every 32-key tile is fetched from HBM once per workgroup and
+// handed to all wavefronts through LDS, already in the operand layouts of the two products:
+//   * chunks 0..7:  K operand pieces (sub, c), a plain copy of what each lane would have loaded itself;
+//   * chunks 8..15: V^T operand pieces db, transposed once per workgroup on the matrix cores (selection
+//     matrices, as above).
+// The eight staging units of a tile (4 of K, 4 of V) are dealt round-robin to the wavefronts; their global loads
+// for tile t + 1 are in flight while tile t is multiplied.  One barrier per tile, two LDS buffers.
+template <int NW, int D>
+__global__ __launch_bounds__(64 * NW) void attn_mrows_kernel(BlockParams p) {
+  __shared__ uint4 buf[2][16][64];
+  constexpr int NU = (8 + NW - 1) / NW;  // staging units per wavefront
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int g4 = lane >> 4, c16 = lane & 15;
+  const int s = blockIdx.x, b = blockIdx.z;
+  const int kvh = blockIdx.y % p.Hkv, pass = blockIdx.y / p.Hkv;
+
+  long long n = p.n[b];
+  const int ext = p.causal ? p.q_len : 0;
+  const long long nmax = p.T_max - ext;
+  n = n < 0 ? 0 : (n > nmax ? nmax : n);
+  const long long total = n + ext;
+  const int R = p.G * p.q_len;
+
+  const long long ntiles = (total + 31) >> 5;
+  const long long per = (ntiles + p.S - 1) / p.S;
+  const long long tile_begin = (long long)s * per;
+  const long long tile_end = ntiles < tile_begin + per ? ntiles : tile_begin + per;
+
+  const bf16_t* kbase = p.k + ((long long)b * p.Hkv + kvh) * p.T_max * 128;
+  const bf16_t* vbase = p.v + ((long long)b * p.Hkv + kvh) * p.T_max * 128;
+
+  // scores are taken as (+-Q K) * |scale|: a negative scale is moved into Q's sign bits (exact)
+  const float absl = fabsf(p.scale_log2e);
+  const uint32_t flip = p.scale_log2e < 0.f ? 0x80008000u : 0u;
+  bf16x8 qreg[4];
+  long long lim, orow;
+  {
+    const int rho = (pass * NW + w) * 16 + c16;
+    if (rho < R) {
+      const int r = rho / p.G, gq = rho % p.G;
+      orow = ((long long)b * p.q_len + r) * p.Hq + kvh * p.G + gq;
+      lim = p.causal ? n + r : n - 1;
+      const bf16_t* qp = p.q + orow * 128 + 8 * g4;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        uint4 u = *reinterpret_cast<const uint4*>(qp + 32 * c);
+        u.x ^= flip, u.y ^= flip, u.z ^= flip, u.w ^= flip;
+        qreg[c] = __builtin_bit_cast(bf16x8, u);
+      }
+    } else {
+      orow = -1;
+      lim = n;
+      const uint4 z = {0u, 0u, 0u, 0u};
+#pragma unroll
+      for (int c = 0; c < 4; ++c) qreg[c] = __builtin_bit_cast(bf16x8, z);
+    }
+  }
+  long long lim_min = lim;  // smallest limit among the wavefront's rows
+#pragma unroll
+  for (int off = 1; off < 16; off <<= 1) {
+    const long long o = __shfl_xor(lim_min, off);
+    lim_min = o < lim_min ? o : lim_min;
+  }
+
+  bf16x8 sel[2];
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    uint32_t wv[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t lo = (8 * g4 + 2 * i == c16 + 16 * h) ? 0x3F80u : 0u;
+      const uint32_t hi = (8 * g4 + 2 * i + 1 == c16 + 16 * h) ? 0x3F80u : 0u;
+      wv[i] = lo | (hi << 16);
+    }
+    const uint4 u = {wv[0], wv[1], wv[2], wv[3]};
+    sel[h] = __builtin_bit_cast(bf16x8, u);
+  }
+
+  float m = TANDEM_NEG_BIG, l = 0.f;
+  f32x4 acc[8];
+#pragma unroll
+  for (int db = 0; db < 8; ++db) acc[db] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+  // staging unit u of a tile: u < 4 - V columns [32u, 32u + 32) of its 32 rows; u >= 4 - the same of K
+  // D tiles ahead are in flight in registers
+  uint4 raw[D][NU][2];
+  auto issue = [&](int j, long long ti) {
+#pragma unroll
+    for (int i = 0; i < NU; ++i) {
+      const int u = w + i * NW;
+      if (u < 8) {
+        const bf16_t* base = (u >= 4 ? kbase : vbase) + 32 * (u & 3) + 8 * g4;
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+          long long row = (ti << 5) + 16 * sub + c16;
+          row = row < total ? row : total - 1;  // rows past the end are re-reads of a valid row, masked below
+          raw[j][i][sub] = *reinterpret_cast<const uint4*>(base + row * 128);
+        }
+      }
+    }
+  };
+  auto stage = [&](int j, int bi) {
+#pragma unroll
+    for (int i = 0; i < NU; ++i) {
+      const int u = w + i * NW;
+      if (u >= 8) continue;
+      const int c = u & 3;
+      if (u >= 4) {
+        buf[bi][c][lane] = raw[j][i][0];
+        buf[bi][4 + c][lane] = raw[j][i][1];
+      } else {
+        const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+        const bf16x8 v0 = __builtin_bit_cast(bf16x8, raw[j][i][0]), v1 = __builtin_bit_cast(bf16x8, raw[j][i][1]);
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          const f32x4 t0 = mfma16(v0, sel[h], z);
+          const f32x4 t1 = mfma16(v1, sel[h], z);
+          buf[bi][8 + 2 * c + h][lane] = __builtin_bit_cast(uint4, pack8_hw(t0, t1));
+        }
+      }
+    }
+  };
+
+#pragma unroll
+  for (int j = 0; j < D; ++j)
+    if (tile_begin + j < tile_end) issue(j, tile_begin + j);
+  for (long long t0 = tile_begin; t0 < tile_end; t0 += D) {
+#pragma unroll
+  for (int j = 0; j < D; ++j) {
+    const long long ti = t0 + j;
+    if (ti >= tile_end) break;
+    const int bi = (int)(ti - tile_begin) & 1;
+    stage(j, bi);
+    if (ti + D < tile_end) issue(j, ti + D);
+    __syncthreads();  // tile ti is complete in buf[bi]; buf[1 - bi] is free again (everyone finished tile ti - 1)
+
+    const long long key0 = ti << 5;
+    f32x4 sc[2];
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub) {
+      f32x4 a = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int c = 0; c < 4; ++c) a = mfma16(__builtin_bit_cast(bf16x8, buf[bi][4 * sub + c][lane]), qreg[c], a);
+      sc[sub] = a;
+    }
+    const bool edge = key0 + 31 > lim_min;  // wave-uniform: some key of this tile is hidden from some row
+    if (edge) {
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub) {
+        const long long kidx = key0 + 16 * sub + 4 * g4;
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) sc[sub][r4] = (kidx + r4 <= lim) ? sc[sub][r4] : -INFINITY;
+      }
+    }
+    float mx = fmaxf(fmaxf(fmaxf(sc[0][0], sc[0][1]), fmaxf(sc[0][2], sc[0][3])),
+                     fmaxf(fmaxf(sc[1][0], sc[1][1]), fmaxf(sc[1][2], sc[1][3])));
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    mx *= absl;
+    // The running maximum m is only raised when some row's scores pass it by more than 2^8 (weights stay
+    // below 256, exact in the fp32 sums; the result does not depend on which m is subtracted), so the
+    // rescaling of the 32 accumulators is skipped for almost every tile.
+    if (__builtin_amdgcn_ballot_w64(mx > m + 8.f) != 0) {
+      const float mn = fmaxf(m, mx);
+      const float corr = fast_exp2(m - mn);
+      m = mn;
+      l *= corr;
+#pragma unroll
+      for (int db = 0; db < 8; ++db) acc[db] *= corr;
+    }
+    float ps = 0.f;
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        sc[sub][r4] = fast_exp2(fmaf(sc[sub][r4], absl, -m));
+        ps += sc[sub][r4];
+      }
+    l += ps;
+    const bf16x8 pb = pack8_hw(sc[0], sc[1]);
+#pragma unroll
+    for (int db = 0; db < 8; ++db)
+      acc[db] = mfma16(__builtin_bit_cast(bf16x8, buf[bi][8 + db][lane]), pb, acc[db]);
+  }
+  }
+
+  l += __shfl_xor(l, 16);
+  l += __shfl_xor(l, 32);
+  if (orow < 0) return;
+  if (p.S_total == 1) {
+    const float inv = l > 0.f ? 1.f / l : 0.f;
+    bf16_t* op = p.out + orow * 128 + 4 * g4;
+#pragma unroll
+    for (int db = 0; db < 8; ++db) {
+      uint2 u;
+      u.x = pack_bf16x2(acc[db][0] * inv, acc[db][1] * inv);
+      u.y = pack_bf16x2(acc[db][2] * inv, acc[db][3] * inv);
+      *reinterpret_cast<uint2*>(op + 16 * db) = u;
+    }
+  } else {
+    const long long ps = orow * p.S_total + p.s_off + s;
+    float* op = p.part_o + ps * 128 + 4 * g4;
+#pragma unroll
+    for (int db = 0; db < 8; ++db)
+      *reinterpret_cast<float4*>(op + 16 * db) = make_float4(acc[db][0], acc[db][1], acc[db][2], acc[db][3]);
+    if (g4 == 0) {
+      p.part_ml[ps * 2 + 0] = m;
+      p.part_ml[ps * 2 + 1] = l;
+    }
+  }
+}
+
+template <int NW>
+int launch_mrows(const BlockParams& p, int passes, int B, hipStream_t st) {
+  hipLaunchKernelGGL((attn_mrows_kernel<NW, 1>), dim3(p.S, p.Hkv * passes, B), dim3(64 * NW), 0, st, p);
+  return hip_ok(hipGetLastError());
 }
 
 template <int RT, int NW>
@@ -281,7 +514,7 @@ int launch_rt(const BlockParams& p, int passes, int B, hipStream_t st) {
 
 }  // namespace
 
-bool attn_block_supported(const AttnArgs& a) { return a.dtype == TANDEM_BF16 && a.dh == 128 && a.causal == 1 && !a.kB; }
+bool attn_block_supported(const AttnArgs& a) { return a.dtype == TANDEM_BF16 && a.dh == 128 && !a.kB; }
 
 // Context splits: a function of shapes only.  Measured on MI355X: about 512 workgroups in total (two
 // per CU) stream best; more splits only add partials and tail effects.  At least 8 tiles (256 keys) each.
@@ -315,6 +548,9 @@ int launch_attn_block(const AttnArgs& a, hipStream_t st) {
   p.q_len = a.q_len;
   p.G = a.Hq / a.Hkv;
   p.S = a.S;
+  p.causal = a.causal;
+  p.S_total = a.S_total > 0 ? a.S_total : a.S;
+  p.s_off = a.S_total > 0 ? a.s_off : 0;
   p.T_max = a.T_max;
   p.scale_log2e = a.scale * 1.4426950408889634f;
   p.out = (bf16_t*)a.out;
@@ -327,8 +563,19 @@ int launch_attn_block(const AttnArgs& a, hipStream_t st) {
     rc = a.wide ? launch_rt<1, 8>(p, 1, a.B, st) : launch_rt<1, 4>(p, 1, a.B, st);
   else if (tiles == 2)
     rc = a.wide ? launch_rt<2, 8>(p, 1, a.B, st) : launch_rt<2, 4>(p, 1, a.B, st);
-  else
-    rc = launch_rt<4, 4>(p, (tiles + 3) / 4, a.B, st);
-  if (rc != TANDEM_OK || a.S == 1) return rc;
+  else {
+    // more than 32 rows: the wavefronts split the rows, up to 128 rows per pass over K and V
+    const int passes = (tiles + 7) / 8;
+    const int nw = (tiles + passes - 1) / passes;
+    switch (nw) {
+      case 3: rc = launch_mrows<3>(p, passes, a.B, st); break;
+      case 4: rc = launch_mrows<4>(p, passes, a.B, st); break;
+      case 5: rc = launch_mrows<5>(p, passes, a.B, st); break;
+      case 6: rc = launch_mrows<6>(p, passes, a.B, st); break;
+      case 7: rc = launch_mrows<7>(p, passes, a.B, st); break;
+      default: rc = launch_mrows<8>(p, passes, a.B, st); break;
+    }
+  }
+  if (rc != TANDEM_OK || a.S_total > 0 || a.S == 1) return rc;
   return launch_attn_combine(a.part_ml, a.part_o, a.out, a.B * a.q_len * a.Hq, a.S, 128, a.dtype, st);
 }

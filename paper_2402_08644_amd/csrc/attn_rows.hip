@@ -20,6 +20,7 @@ struct RowsParams {
   const void *kA, *vA, *kB, *vB;
   const int32_t *nA, *nB;
   int causal, Hq, Hkv, q_len, gamma_max, S;
+  int S_total, s_off;  // partial slots per row and this launch's first slot
   long long T_max;
   float scale_log2e;
   void* out;
@@ -177,13 +178,14 @@ __global__ __launch_bounds__(64 * NW) void attn_rows_kernel(RowsParams p) {
       ot += sm_o[ww][g][d] * c;
     }
     const long long row = row0 + g;
-    if (p.S == 1) {
+    if (p.S_total == 1) {
       ((T*)p.out)[row * DH + d] = from_f32<T>(lt > 0.f ? ot / lt : 0.f);
     } else {
-      p.part_o[(row * p.S + s) * DH + d] = ot;
+      const long long ps = row * p.S_total + p.s_off + s;
+      p.part_o[ps * DH + d] = ot;
       if (d == 0) {
-        p.part_ml[(row * p.S + s) * 2 + 0] = mn;
-        p.part_ml[(row * p.S + s) * 2 + 1] = lt;
+        p.part_ml[ps * 2 + 0] = mn;
+        p.part_ml[ps * 2 + 1] = lt;
       }
     }
   }
@@ -272,6 +274,8 @@ int launch_attn_rows(const AttnArgs& a, hipStream_t st) {
   p.q_len = a.q_len;
   p.gamma_max = a.gamma_max;
   p.S = a.S;
+  p.S_total = a.S_total > 0 ? a.S_total : a.S;
+  p.s_off = a.S_total > 0 ? a.s_off : 0;
   p.T_max = a.T_max;
   p.scale_log2e = a.scale * 1.4426950408889634f;
   p.out = a.out;
@@ -290,6 +294,6 @@ int launch_attn_rows(const AttnArgs& a, hipStream_t st) {
     rc = launch_rows_g<float, 64>(G, a.wide != 0, p, grid, st);
   else
     return TANDEM_ERR_UNSUPPORTED;
-  if (rc != TANDEM_OK || a.S == 1) return rc;
+  if (rc != TANDEM_OK || a.S_total > 0 || a.S == 1) return rc;
   return launch_attn_combine(a.part_ml, a.part_o, a.out, a.B * a.q_len * a.Hq, a.S, a.dh, a.dtype, st);
 }

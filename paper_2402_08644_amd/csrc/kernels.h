@@ -14,7 +14,8 @@ struct AttnArgs {
   const void *kB, *vB;         // [B, Hkv, gamma_max, dh] or nullptr
   const int32_t* nA;           // [B]
   const int32_t* nB;           // [B] or nullptr
-  int causal;                  // 1: row r of the block sees nA[b] + r + 1 rows of A (block mode)
+  int causal;                  // 1: row r of the block sees nA[b] + r + 1 rows of A (block mode);
+                               // 0: every row sees nA[b] rows of A (and nB[b] rows of B)
   int B, Hq, Hkv, dh, q_len;
   int64_t T_max;
   int gamma_max;
@@ -25,6 +26,10 @@ struct AttnArgs {
   float* part_o;               // [rows, S, dh]  un-normalised
   int S;                       // number of context splits
   int wide;                    // 1 = workgroups of eight wavefronts (see attn_*_splits)
+  // Several launches over different key segments can fill one table of partials: the launch writes slots
+  // [s_off, s_off + S) of S_total per row and leaves the combine to the caller.  S_total = 0 means S_total = S,
+  // s_off = 0, and the launch combines its own splits.
+  int S_total, s_off;
 };
 
 // number of context splits; *wide (optional) = 1 when the workgroups should have eight wavefronts (AttnArgs::wide)

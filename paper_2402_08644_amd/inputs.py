@@ -110,6 +110,22 @@ def block_attn_case(seed, B, q_len, Hq, Hkv, dh, T_max, n_prefix, dtype="bf16", 
     }
 
 
+def shared_attn_case(seed, B, samples, q_len, Hq, Hkv, dh, T_shared, T_own, n_shared, n_own, dtype="bf16", std=1.0):
+    """Inputs of one block-mode attention call in which `samples` sequences continue each of B prompts: the
+    prompt rows once per prompt, each sample's later rows in a cache of its own (Q/K/V ~ N(0, std))."""
+    rng = np.random.default_rng(seed)
+    return {
+        "q": normal(rng, (B, samples, q_len, Hq, dh), std, dtype),
+        "ks": normal(rng, (B, Hkv, T_shared, dh), std, dtype),
+        "vs": normal(rng, (B, Hkv, T_shared, dh), std, dtype),
+        "ko": normal(rng, (B * samples, Hkv, T_own, dh), std, dtype),
+        "vo": normal(rng, (B * samples, Hkv, T_own, dh), std, dtype),
+        "n_shared": np.broadcast_to(np.asarray(n_shared, np.int32), (B,)).copy(),
+        "n_own": np.broadcast_to(np.asarray(n_own, np.int32), (B * samples,)).copy(),
+        "scale": 1.0 / math.sqrt(dh),
+    }
+
+
 def project_case(seed, M, d_L, d_hidden, d_S, dtype="bf16", x_std=1.0, w_std=0.02, bias_std=0.0):
     """Inputs of one FF_Tandem call.  d_hidden == 0 gives the linear form.
     Weights are stored [out, in]."""

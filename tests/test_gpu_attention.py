@@ -208,6 +208,10 @@ def test_draft_attn_never_writes_the_caches(tb):
         (2, 5, 4, 1, 128, 530, [525, 64], "bf16"),       # R=20: ragged row tile
         (1, 32, 8, 2, 128, 300, [200], "bf16"),          # R=128: two passes of four row tiles
         (2, 7, 8, 1, 128, 200, [193, 50], "bf16"),       # G=8, R=56: four row tiles with padding
+        (2, 12, 4, 1, 128, 333, [321, 0], "bf16"),       # R=48: three wavefronts, one row tile each
+        (1, 24, 8, 2, 128, 777, [753], "bf16"),          # R=96: six
+        (2, 28, 4, 1, 128, 150, [122, 31], "bf16"),      # R=112: seven
+        (1, 18, 8, 1, 128, 1100, [1082], "bf16"),        # G=8, R=144: two passes of five row tiles, ragged
         (2, 3, 4, 2, 64, 100, [97, 10], "bf16"),         # dh=64 generic path
         (1, 2, 4, 4, 64, 130, [126], "f32"),             # the tiny config's large model shape
         (2, 4, 4, 2, 128, 90, [80, 0], "f32"),
@@ -280,6 +284,106 @@ def test_block_attn_gamma1_equals_draft_with_own_row(tb):
     one = torch.ones(2, dtype=torch.int32, device="cuda")
     drf = binding.tandem_draft_attn(q[:, 0].contiguous(), k, v, n, kcur, vcur, one)
     assert_rows_close(inputs.torch_to_f64(blk[:, 0]), inputs.torch_to_f64(drf), tol=1e-2, what="gamma=1")
+
+
+# --------------------------------------------------------------------------- several samples per prompt
+def run_shared(tb, case):
+    torch, binding = tb
+    out = binding.tandem_block_attn_shared(case["q"].to_torch(), case["ks"].to_torch(), case["vs"].to_torch(),
+                                           torch.from_numpy(case["n_shared"]).cuda(), case["ko"].to_torch(),
+                                           case["vo"].to_torch(), torch.from_numpy(case["n_own"]).cuda(),
+                                           scale=case["scale"])
+    torch.cuda.synchronize()
+    return inputs.torch_to_f64(out)
+
+
+def oracle_shared(case):
+    return orc.block_attn_shared(case["q"].f64, case["ks"].f64, case["vs"].f64, case["n_shared"], case["ko"].f64,
+                                 case["vo"].f64, case["n_own"], case["scale"])
+
+
+@pytest.mark.parametrize(
+    "B,ns,q_len,Hq,Hkv,dh,Ts,To,n_shared,n_own,dtype",
+    [
+        (2, 4, 4, 8, 2, 128, 300, 40, [300, 37], [0, 36, 7, 20, 1, 2, 3, 30], "bf16"),   # R=64 shared rows: 4 row tiles
+        (1, 4, 5, 4, 1, 128, 700, 64, [650], [59, 0, 13, 31], "bf16"),                   # R=80: two passes, ragged
+        (2, 2, 1, 4, 4, 128, 260, 20, [0, 259], [19, 0, 5, 7], "bf16"),                  # an empty prompt; G=1, q_len=1
+        (3, 1, 3, 8, 2, 128, 100, 300, [100, 5, 64], [297, 0, 100], "bf16"),             # one sample: prompt + own = a plain split
+        (1, 8, 4, 8, 1, 128, 1200, 33, [1111], [29, 0, 1, 2, 3, 4, 5, 6], "bf16"),       # G=8, 256 rows on the prompt
+        (2, 3, 2, 4, 2, 64, 90, 12, [90, 10], [10, 0, 3, 4, 5, 6], "bf16"),              # dh=64 generic path
+        (2, 2, 3, 4, 4, 64, 50, 16, [17, 50], [0, 13, 7, 2], "f32"),
+        (1, 4, 2, 4, 2, 128, 600, 70, [555], [68, 1, 30, 0], "f32"),
+    ],
+)
+def test_block_attn_shared_parity_small(tb, B, ns, q_len, Hq, Hkv, dh, Ts, To, n_shared, n_own, dtype):
+    case = inputs.shared_attn_case(31, B, ns, q_len, Hq, Hkv, dh, Ts, To, n_shared, n_own, dtype=dtype)
+    got = run_shared(tb, case)
+    e = assert_rows_close(got.reshape(-1, Hq, dh), oracle_shared(case).reshape(-1, Hq, dh), what="shared")
+    print(f"shared small {B,ns,q_len,Hq,Hkv,dh,Ts,To,dtype}: max rel err {e[0]:.2e}")
+
+
+def test_block_attn_shared_equals_block_attn_on_copied_prompts(tb):
+    """At the latency evaluation's shape (4 samples per prompt, long prompt, short continuations) the shared
+    form agrees with tandem_block_attn on per-sample caches holding a copy of the prompt rows, and with the
+    oracle on sampled output rows."""
+    torch, binding = tb
+    B, ns, q_len, Hq, Hkv, dh, Ts, To = 4, 4, 5, 32, 8, 128, 4096, 256
+    rng = np.random.default_rng(5)
+    n_shared = np.array([4096, 3000, 17, 2049], np.int32)
+    n_own = rng.integers(0, To - q_len + 1, size=B * ns).astype(np.int32)
+    case = inputs.shared_attn_case(32, B, ns, q_len, Hq, Hkv, dh, Ts, To, n_shared, n_own, dtype="bf16")
+    got = run_shared(tb, case)
+    ks, vs, ko, vo = (case[k].to_torch() for k in ("ks", "vs", "ko", "vo"))
+    kc = torch.zeros(B * ns, Hkv, Ts + To, dh, dtype=torch.bfloat16, device="cuda")
+    vc = torch.zeros_like(kc)
+    n = np.zeros(B * ns, np.int32)
+    for b in range(B):
+        for s_ in range(ns):
+            i, m = b * ns + s_, int(n_shared[b])
+            kc[i, :, :m], vc[i, :, :m] = ks[b, :, :m], vs[b, :, :m]
+            kc[i, :, m:m + To], vc[i, :, m:m + To] = ko[i], vo[i]
+            n[i] = m + n_own[i]
+    ref = binding.tandem_block_attn(case["q"].to_torch().view(B * ns, q_len, Hq, dh), kc, vc,
+                                    torch.from_numpy(n).cuda(), scale=case["scale"])
+    torch.cuda.synchronize()
+    assert_rows_close(got.reshape(-1, Hq, dh), inputs.torch_to_f64(ref).reshape(-1, Hq, dh), what="shared vs copied")
+    q64, ks64, vs64, ko64, vo64 = (case[k].f64 for k in ("q", "ks", "vs", "ko", "vo"))
+    G = Hq // Hkv
+    for _ in range(24):
+        b, s_, r, h = (int(rng.integers(0, x)) for x in (B, ns, q_len, Hq))
+        i, kv = b * ns + s_, h // G
+        K = np.concatenate([ks64[b, kv, : n_shared[b]], ko64[i, kv, : n_own[i] + r + 1]])
+        V = np.concatenate([vs64[b, kv, : n_shared[b]], vo64[i, kv, : n_own[i] + r + 1]])
+        want = orc.attention_one(q64[b, s_, r, h], K, V, case["scale"])
+        assert_rows_close(got[b, s_, r, h][None], want[None], what=f"shared sampled row {b,s_,r,h}")
+
+
+def test_block_attn_shared_error_codes(tb):
+    torch, binding = tb
+    import ctypes as C
+
+    L = binding.lib()
+    d = binding.attn_desc(2, 4, 2, 128, 64, 0, 0.1, binding.BF16)
+    t = torch.zeros(2 * 4 * 4 * 64 * 128, dtype=torch.bfloat16, device="cuda")
+    n = torch.zeros(8, dtype=torch.int32, device="cuda")
+    p, pn = C.c_void_p(t.data_ptr()), C.c_void_p(n.data_ptr())
+    ws = torch.zeros(1 << 22, dtype=torch.uint8, device="cuda")
+    pw = C.c_void_p(ws.data_ptr())
+    call = lambda desc, ns, To, ql, q=p, w=pw, wb=ws.numel(): L.tandem_block_attn_shared(
+        C.byref(desc), ns, To, q, p, p, pn, p, p, pn, ql, p, w, wb, None)
+    assert call(d, 0, 16, 2) == binding.ERR_SHAPE
+    assert call(d, 4, 16, 0) == binding.ERR_SHAPE
+    assert call(d, 4, 16, 33) == binding.ERR_SHAPE
+    assert call(d, 16, 64, 32) == binding.ERR_SHAPE          # samples * q_len above the limit
+    assert call(d, 4, 1, 2) == binding.ERR_SHAPE             # own cache shorter than the block
+    assert call(d, 4, 16, 2, q=None) == binding.ERR_NULL
+    assert call(d, 4, 16, 2, w=None) == binding.ERR_NULL
+    need = binding.tandem_block_attn_shared_workspace(d, 4, 16, 2)
+    assert need > 0
+    assert call(d, 4, 16, 2, wb=need - 1) == binding.ERR_WORKSPACE
+    assert call(d, 4, 16, 2, wb=need) == binding.OK
+    assert binding.tandem_block_attn_shared_workspace(d, 0, 16, 2) == 0
+    torch.cuda.synchronize()
 
 
 # --------------------------------------------------------------------------- error paths
