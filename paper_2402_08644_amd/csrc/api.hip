@@ -207,8 +207,11 @@ int tandem_block_attn_shared(const tandem_attn_desc* a, int32_t samples, int64_t
   x.S = pl.S2;
   x.wide = pl.wide2;
   x.s_off = pl.S1;
+  // an unsplit last segment merges the prompt segment's partials itself (matrix-core kernels)
+  const bool merge = mfma && pl.S2 == 1;
+  x.merge_prev = merge ? pl.S1 : 0;
   rc = mfma ? launch_attn_block(x, st) : launch_attn_rows(x, st);
-  if (rc != TANDEM_OK) return rc;
+  if (rc != TANDEM_OK || merge) return rc;
   return launch_attn_combine(x.part_ml, x.part_o, out, (int)rows, S, a->dh, a->dtype, st);
 }
 

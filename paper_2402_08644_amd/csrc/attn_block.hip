@@ -31,6 +31,7 @@ struct BlockParams {
   int Hq, Hkv, q_len, G, S;
   int causal;         // 1: the q_len rows are the last rows of the cache (row r sees n + r + 1 keys); 0: all see n keys
   int S_total, s_off;  // partial slots per row and this launch's first slot
+  int merge_prev;      // > 0 (needs S == 1): merge slots [0, merge_prev) into this launch's result and write out
   long long T_max;
   float scale_log2e;
   bf16_t* out;
@@ -61,6 +62,53 @@ __device__ __forceinline__ bf16x8 pack8_hw(const f32x4& a, const f32x4& b) {
 }
 __device__ __forceinline__ f32x4 mfma16(const bf16x8& a, const bf16x8& b, const f32x4& c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+
+// Result of one query column (lane group c16; this lane holds output elements 16 db + 4 g4 + r4): the finished
+// row when this launch sees all keys, its partial (m, l, O) otherwise.  With merge_prev the partials that earlier
+// launches left for this row are folded in first, in slot order, and the row is finished here.
+__device__ __forceinline__ void write_row(const BlockParams& p, long long orow, int s, int g4, float m, float l,
+                                          f32x4 (&acc)[8]) {
+  if (p.merge_prev > 0) {
+    for (int t = 0; t < p.merge_prev; ++t) {
+      const long long ps = orow * p.S_total + t;
+      const float mo = p.part_ml[ps * 2], lo = p.part_ml[ps * 2 + 1];
+      const float mn = fmaxf(m, mo);
+      const float ca = fast_exp2(m - mn), cb = fast_exp2(mo - mn);
+      m = mn;
+      l = l * ca + lo * cb;
+      const float* op = p.part_o + ps * 128 + 4 * g4;
+#pragma unroll
+      for (int db = 0; db < 8; ++db) {
+        const float4 o = *reinterpret_cast<const float4*>(op + 16 * db);
+        acc[db][0] = acc[db][0] * ca + o.x * cb;
+        acc[db][1] = acc[db][1] * ca + o.y * cb;
+        acc[db][2] = acc[db][2] * ca + o.z * cb;
+        acc[db][3] = acc[db][3] * ca + o.w * cb;
+      }
+    }
+  }
+  if (p.S_total == 1 || p.merge_prev > 0) {
+    const float inv = l > 0.f ? 1.f / l : 0.f;
+    bf16_t* op = p.out + orow * 128 + 4 * g4;
+#pragma unroll
+    for (int db = 0; db < 8; ++db) {
+      uint2 u;
+      u.x = pack_bf16x2(acc[db][0] * inv, acc[db][1] * inv);
+      u.y = pack_bf16x2(acc[db][2] * inv, acc[db][3] * inv);
+      *reinterpret_cast<uint2*>(op + 16 * db) = u;
+    }
+  } else {
+    const long long ps = orow * p.S_total + p.s_off + s;
+    float* op = p.part_o + ps * 128 + 4 * g4;
+#pragma unroll
+    for (int db = 0; db < 8; ++db)
+      *reinterpret_cast<float4*>(op + 16 * db) = make_float4(acc[db][0], acc[db][1], acc[db][2], acc[db][3]);
+    if (g4 == 0) {
+      p.part_ml[ps * 2 + 0] = m;
+      p.part_ml[ps * 2 + 1] = l;
+    }
+  }
 }
 
 constexpr int ST_REGS = 34;  // per-lane state of one row tile: m, l, 32 accumulators
@@ -249,31 +297,8 @@ __global__ __launch_bounds__(64 * NW, (RT <= 2 && NW == 4 ? 2 : 1)) void attn_bl
   if (w == 0) {
     take(0);
 #pragma unroll
-    for (int rt = 0; rt < RT; ++rt) {
-      if (orow[rt] < 0) continue;
-      if (p.S_total == 1) {
-        const float inv = l[rt] > 0.f ? 1.f / l[rt] : 0.f;
-        bf16_t* op = p.out + orow[rt] * 128 + 4 * g4;
-#pragma unroll
-        for (int db = 0; db < 8; ++db) {
-          uint2 u;
-          u.x = pack_bf16x2(acc[rt][db][0] * inv, acc[rt][db][1] * inv);
-          u.y = pack_bf16x2(acc[rt][db][2] * inv, acc[rt][db][3] * inv);
-          *reinterpret_cast<uint2*>(op + 16 * db) = u;
-        }
-      } else {
-        const long long ps = orow[rt] * p.S_total + p.s_off + s;
-        float* op = p.part_o + ps * 128 + 4 * g4;
-#pragma unroll
-        for (int db = 0; db < 8; ++db)
-          *reinterpret_cast<float4*>(op + 16 * db) =
-              make_float4(acc[rt][db][0], acc[rt][db][1], acc[rt][db][2], acc[rt][db][3]);
-        if (g4 == 0) {
-          p.part_ml[ps * 2 + 0] = m[rt];
-          p.part_ml[ps * 2 + 1] = l[rt];
-        }
-      }
-    }
+    for (int rt = 0; rt < RT; ++rt)
+      if (orow[rt] >= 0) write_row(p, orow[rt], s, g4, m[rt], l[rt], acc[rt]);
   }
 }
 
@@ -468,28 +493,7 @@ __global__ __launch_bounds__(64 * NW) void attn_mrows_kernel(BlockParams p) {
 
   l += __shfl_xor(l, 16);
   l += __shfl_xor(l, 32);
-  if (orow < 0) return;
-  if (p.S_total == 1) {
-    const float inv = l > 0.f ? 1.f / l : 0.f;
-    bf16_t* op = p.out + orow * 128 + 4 * g4;
-#pragma unroll
-    for (int db = 0; db < 8; ++db) {
-      uint2 u;
-      u.x = pack_bf16x2(acc[db][0] * inv, acc[db][1] * inv);
-      u.y = pack_bf16x2(acc[db][2] * inv, acc[db][3] * inv);
-      *reinterpret_cast<uint2*>(op + 16 * db) = u;
-    }
-  } else {
-    const long long ps = orow * p.S_total + p.s_off + s;
-    float* op = p.part_o + ps * 128 + 4 * g4;
-#pragma unroll
-    for (int db = 0; db < 8; ++db)
-      *reinterpret_cast<float4*>(op + 16 * db) = make_float4(acc[db][0], acc[db][1], acc[db][2], acc[db][3]);
-    if (g4 == 0) {
-      p.part_ml[ps * 2 + 0] = m;
-      p.part_ml[ps * 2 + 1] = l;
-    }
-  }
+  if (orow >= 0) write_row(p, orow, s, g4, m, l, acc);
 }
 
 template <int NW>
@@ -551,6 +555,7 @@ int launch_attn_block(const AttnArgs& a, hipStream_t st) {
   p.causal = a.causal;
   p.S_total = a.S_total > 0 ? a.S_total : a.S;
   p.s_off = a.S_total > 0 ? a.s_off : 0;
+  p.merge_prev = a.S_total > 0 && a.S == 1 ? a.merge_prev : 0;
   p.T_max = a.T_max;
   p.scale_log2e = a.scale * 1.4426950408889634f;
   p.out = (bf16_t*)a.out;

@@ -30,6 +30,9 @@ struct AttnArgs {
   // [s_off, s_off + S) of S_total per row and leaves the combine to the caller.  S_total = 0 means S_total = S,
   // s_off = 0, and the launch combines its own splits.
   int S_total, s_off;
+  // MFMA block kernels only, S == 1: fold slots [0, merge_prev) (written by earlier launches on the stream)
+  // into this launch's rows and write the finished rows to out - the last segment needs no combine launch.
+  int merge_prev;
 };
 
 // number of context splits; *wide (optional) = 1 when the workgroups should have eight wavefronts (AttnArgs::wide)
