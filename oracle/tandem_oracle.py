@@ -478,6 +478,33 @@ def block_attn_shared(Q, Ks, Vs, n_shared, Ko, Vo, n_own, scale):
 
 
 # ----------------------------------------------------------------------------
+# a4'  the small model's attention at EVERY position of a known sequence (Eq. (2), second line, with the
+#      block boundary k = floor(i / gamma) * gamma of the query's own position i, 0-indexed; Sec. 3
+#      "Training": this is the form used for training and for teacher-forced scoring).  One call handles
+#      q_len consecutive positions n[b] .. n[b] + q_len - 1 of every sequence.
+# ----------------------------------------------------------------------------
+def mixed_attn(Q, Khat, Vhat, Kown, Vown, n, gamma, scale):
+    """Q [B, q_len, Hq, dh]; Khat, Vhat (rows derived from M_L through FF_Tandem) and Kown, Vown (rows M_S
+    computed itself) [B, Hkv, T, dh], all indexed by absolute position.  The query at position
+    i = n[b] + r attends Khat/Vhat[0 : k) and Kown/Vown[k : i + 1) in one softmax, k = (i // gamma) * gamma."""
+    Q = np.asarray(Q, F64)
+    B, q_len, Hq, dh = Q.shape
+    Hkv = np.asarray(Khat).shape[1]
+    G = Hq // Hkv
+    out = np.zeros_like(Q)
+    for b in range(B):
+        for r in range(q_len):
+            i = int(n[b]) + r
+            large, own = attended_sets(i, gamma)
+            for h in range(Hq):
+                kv = h // G
+                K = np.concatenate([np.asarray(Khat, F64)[b, kv, large], np.asarray(Kown, F64)[b, kv, own]])
+                V = np.concatenate([np.asarray(Vhat, F64)[b, kv, large], np.asarray(Vown, F64)[b, kv, own]])
+                out[b, r, h] = attention_one(Q[b, r, h], K, V, scale)
+    return out
+
+
+# ----------------------------------------------------------------------------
 # a5  split-K re-association of the softmax (exact in real arithmetic):
 #     per split (m_s, l_s, O_s) with O_s un-normalised; merged in split order.
 # ----------------------------------------------------------------------------
