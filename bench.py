@@ -214,6 +214,43 @@ def shared_workload(torch, binding, inputs, B, samples, q_len, Hq, Hkv, dh, n_sh
     return call, R, bytes_alg, oracle_sample
 
 
+def mixed_workload(torch, binding, inputs, B, q_len, H, Hkv, dh, n_prefix, gamma, seed):
+    """All-positions small-model attention on q_len consecutive positions at the end of a context: the keys are the
+    rows derived from the large model up to each query's block boundary plus a few own rows."""
+    T_max = n_prefix + q_len
+    bytes_alg = B * Hkv * T_max * dh * 2 * 2  # every visible position's K and V row once, from one cache or the other
+    R = _rotations(bytes_alg)
+    sets = []
+    for i in range(R):
+        sets.append({k: inputs.device_normal(sh, seed * 100 + 5 * i + j, 1.0) for j, (k, sh) in enumerate((
+            ("q", (B, q_len, H, dh)), ("khat", (B, Hkv, T_max, dh)), ("vhat", (B, Hkv, T_max, dh)),
+            ("kown", (B, Hkv, T_max, dh)), ("vown", (B, Hkv, T_max, dh))))})
+    n = torch.full((B,), n_prefix, dtype=torch.int32, device="cuda")
+    out = torch.empty((B, q_len, H, dh), dtype=torch.bfloat16, device="cuda")
+    d = binding.attn_desc(B, H, Hkv, dh, T_max, 0, 1.0 / math.sqrt(dh), binding.BF16)
+    ws = binding.workspace(binding.tandem_mixed_attn_workspace(d, q_len))
+
+    def call(i):
+        s = sets[i]
+        binding.tandem_mixed_attn(s["q"], s["khat"], s["vhat"], s["kown"], s["vown"], n, gamma, out=out, ws=ws)
+
+    def oracle_sample(n_seq):
+        from oracle import tandem_oracle as orc
+
+        s = sets[0]
+        f = lambda t: inputs.torch_to_f64(t[:n_seq])
+        args = (f(s["q"]), f(s["khat"]), f(s["vhat"]), f(s["kown"]), f(s["vown"]), n[:n_seq].cpu().numpy(), gamma,
+                1.0 / math.sqrt(dh))
+        t0 = time.perf_counter()
+        want = orc.mixed_attn(*args)
+        dt = time.perf_counter() - t0
+        call(0)
+        torch.cuda.synchronize()
+        return dt, want.reshape(-1, H, dh), inputs.torch_to_f64(out[:n_seq]).reshape(-1, H, dh)
+
+    return call, R, bytes_alg, oracle_sample
+
+
 # ------------------------------------------------------------------ whole decode step
 C3 = dict(
     B=32, gamma=4, ctx=8192, vocab=32768,
@@ -418,6 +455,10 @@ WORKLOADS = {
     "s4_shared": ("shared", dict(B=8, samples=4, q_len=5, Hq=32, Hkv=8, dh=128, n_shared=7936, n_own=251, seed=5), 1,
                   "tandem_block_attn_shared bf16 8 prompts x 4 samples, Hq/Hkv=32/8 dh=128, prompt 7936 rows read once "
                   "per prompt + 256 own rows per sample, 5 query rows"),
+    # teacher-forced scoring with the small model: 32 consecutive positions of every sequence at the end of an 8192
+    # context, C3's small-layer shape, block length 4
+    "c3_mixed": ("mixed", dict(B=32, q_len=32, H=8, Hkv=8, dh=128, n_prefix=8160, gamma=4, seed=6), 1,
+                 "tandem_mixed_attn bf16 B=32 H=8 dh=128, 32 query positions at context 8160+32, gamma=4"),
     "s4_copied": ("shared", dict(B=8, samples=4, q_len=5, Hq=32, Hkv=8, dh=128, n_shared=7936, n_own=251, seed=5,
                                  copied=True), 1,
                   "tandem_block_attn bf16 on 32 per-sample caches that each hold a copy of the 7936 prompt rows "
@@ -502,7 +543,7 @@ def _traffic(name):
 
 def run_kernel_workload(torch, binding, inputs, args):
     kind, kw, n_seq, desc = WORKLOADS[args.workload]
-    maker = {"draft": draft_workload, "block": block_workload, "shared": shared_workload}[kind]
+    maker = {"draft": draft_workload, "block": block_workload, "shared": shared_workload, "mixed": mixed_workload}[kind]
     call, n_copies, bytes_alg, oracle_sample = maker(torch, binding, inputs, **kw)
     torch.cuda.synchronize()
     ms = _time_calls(torch, call, n_copies, args.steps, args.warmup, use_graph=not args.no_graph)

@@ -130,6 +130,23 @@ int tandem_block_attn_shared(const tandem_attn_desc *a, int32_t samples, int64_t
                              const void *v_own, const int32_t *n_own, int32_t q_len, void *out, void *ws,
                              size_t ws_bytes, void *hip_stream);
 
+/* The small model's attention at every position of a known sequence (Eq. (2), second line, with the block
+ * boundary of each query's own position; Sec. 3 "Training": the form used in training and in teacher-forced
+ * scoring, where M_S processes all tokens and, inside a block, sees its own rows instead of M_L's).  One call
+ * handles the q_len consecutive positions n_prefix[b] .. n_prefix[b] + q_len - 1 of every sequence.  The query
+ * at position i (0-indexed), head h, attends in ONE softmax, with k = floor(i / gamma) * gamma,
+ *   k_hat/v_hat[b, h/G, 0 : k)       rows derived from M_L through FF_Tandem (completed blocks)
+ *   k_own/v_own[b, h/G, k : i + 1)   rows M_S computed itself (the query's own block, incl. its own row)
+ *   q, out  device [B, q_len, Hq, dh]     all four caches device [B, Hkv, T_max, dh], indexed by position
+ *   n_prefix device int32 [B], requires n_prefix[b] + q_len <= T_max (clamped otherwise);  gamma >= 1
+ *   1 <= q_len <= TANDEM_MAX_QLEN.  ws: at least tandem_mixed_attn_workspace(a, q_len) bytes.
+ * gamma = 1 is tandem_draft_attn with one own row per query; gamma > T_max is tandem_block_attn on the own
+ * caches.  Reads the caches only; writes out and ws only. */
+size_t tandem_mixed_attn_workspace(const tandem_attn_desc *a, int32_t q_len);
+int tandem_mixed_attn(const tandem_attn_desc *a, const void *q, const void *k_hat, const void *v_hat,
+                      const void *k_own, const void *v_own, const int32_t *n_prefix, int32_t q_len, int32_t gamma,
+                      void *out, void *ws, size_t ws_bytes, void *hip_stream);
+
 /* Mixed-source small-model attention (Eq. (2), second line; Sec. 3 "Training", both bullets).
  * One query per sequence and head attends, in ONE softmax, the union of
  *   k_hat/v_hat[b, h/G, 0 : n_large[b]]  rows derived from M_L through FF_Tandem (completed blocks)

@@ -85,6 +85,7 @@ EXPORTS = (
     "tandem_packed_weight_bytes", "tandem_pack_weight",
     "tandem_project", "tandem_block_attn", "tandem_draft_attn",
     "tandem_block_attn_shared_workspace", "tandem_block_attn_shared",
+    "tandem_mixed_attn_workspace", "tandem_mixed_attn",
     "tandem_model_create", "tandem_model_destroy", "tandem_decode_step_workspace", "tandem_decode_step",
     "tandem_prefill_workspace", "tandem_prefill",
 )
@@ -105,6 +106,10 @@ def lib():
     L.tandem_status_string.argtypes = [C.c_int]
     L.tandem_project_workspace.restype = sz
     L.tandem_project_workspace.argtypes = [C.POINTER(FFDesc), i64]
+    L.tandem_mixed_attn_workspace.restype = sz
+    L.tandem_mixed_attn_workspace.argtypes = [C.POINTER(AttnDesc), i32]
+    L.tandem_mixed_attn.restype = C.c_int
+    L.tandem_mixed_attn.argtypes = [C.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, sz, vp]
     L.tandem_block_attn_shared_workspace.restype = sz
     L.tandem_block_attn_shared_workspace.argtypes = [C.POINTER(AttnDesc), i32, i64, i32]
     L.tandem_block_attn_shared.restype = C.c_int
@@ -292,6 +297,36 @@ def tandem_block_attn_shared(q, k_shared, v_shared, n_shared, k_own, v_own, n_ow
                                         _ptr(k_own), _ptr(v_own), _ptr(n_own), q_len, _ptr(out), _ptr(ws), ws.numel(),
                                         _stream(stream))
     _check(rc, "tandem_block_attn_shared")
+    return out
+
+
+def tandem_mixed_attn_workspace(desc: AttnDesc, q_len: int) -> int:
+    return int(lib().tandem_mixed_attn_workspace(C.byref(desc), q_len))
+
+
+def tandem_mixed_attn(q, k_hat, v_hat, k_own, v_own, n_prefix, gamma, scale=None, out=None, ws=None, stream=None):
+    """q [B,q_len,Hq,dh]; k_hat,v_hat,k_own,v_own [B,Hkv,T_max,dh] indexed by position; n_prefix int32 [B]."""
+    import torch
+
+    B, q_len, Hq, dh = q.shape
+    _, Hkv, T_max, _ = k_hat.shape
+    _need(q, (B, q_len, Hq, dh), "q")
+    for t, nm in ((k_hat, "k_hat"), (v_hat, "v_hat"), (k_own, "k_own"), (v_own, "v_own")):
+        _need(t, (B, Hkv, T_max, dh), nm)
+        if t.dtype != q.dtype:
+            raise TypeError("q / K / V dtypes differ")
+    _need(n_prefix, (B,), "n_prefix")
+    if n_prefix.dtype != torch.int32:
+        raise TypeError("n_prefix must be int32")
+    d = attn_desc(B, Hq, Hkv, dh, T_max, 0, (1.0 / math.sqrt(dh)) if scale is None else scale, _dtype_code(q))
+    if out is None:
+        out = torch.empty_like(q)
+    need = tandem_mixed_attn_workspace(d, q_len)
+    if ws is None:
+        ws = _workspace(need, q)
+    rc = lib().tandem_mixed_attn(C.byref(d), _ptr(q), _ptr(k_hat), _ptr(v_hat), _ptr(k_own), _ptr(v_own),
+                                 _ptr(n_prefix), q_len, int(gamma), _ptr(out), _ptr(ws), ws.numel(), _stream(stream))
+    _check(rc, "tandem_mixed_attn")
     return out
 
 

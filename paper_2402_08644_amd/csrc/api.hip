@@ -215,4 +215,71 @@ int tandem_block_attn_shared(const tandem_attn_desc* a, int32_t samples, int64_t
   return launch_attn_combine(x.part_ml, x.part_o, out, (int)rows, S, a->dh, a->dtype, st);
 }
 
+size_t tandem_mixed_attn_workspace(const tandem_attn_desc* a, int32_t q_len) {
+  if (check_attn_desc(a) != TANDEM_OK || q_len < 1 || q_len > TANDEM_MAX_QLEN) return 0;
+  const size_t rows = (size_t)a->B * q_len * a->Hq;
+  if (block_uses_mfma(a))
+    return carved_bytes(rows, attn_block_splits(a->B, a->Hkv, q_len, a->Hq / a->Hkv, a->T_max, nullptr) + 1, a->dh);
+  return carved_bytes(rows, attn_rows_splits(a->B, a->Hkv, q_len, a->Hq / a->Hkv, a->T_max, 0, nullptr), a->dh);
+}
+
+int tandem_mixed_attn(const tandem_attn_desc* a, const void* q, const void* k_hat, const void* v_hat,
+                      const void* k_own, const void* v_own, const int32_t* n_prefix, int32_t q_len, int32_t gamma,
+                      void* out, void* ws, size_t ws_bytes, void* hip_stream) {
+  int rc = check_attn_desc(a);
+  if (rc != TANDEM_OK) return rc;
+  if (!q || !k_hat || !v_hat || !k_own || !v_own || !n_prefix || !out) return TANDEM_ERR_NULL;
+  if (q_len < 1 || q_len > TANDEM_MAX_QLEN || a->T_max < q_len || gamma < 1) return TANDEM_ERR_SHAPE;
+  const size_t need = tandem_mixed_attn_workspace(a, q_len);
+  if (need > 0 && !ws) return TANDEM_ERR_NULL;
+  if (ws_bytes < need) return TANDEM_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const size_t rows = (size_t)a->B * q_len * a->Hq;
+  AttnArgs x{};
+  x.q = q;
+  x.nA = n_prefix;
+  x.B = a->B;
+  x.Hq = a->Hq;
+  x.Hkv = a->Hkv;
+  x.dh = a->dh;
+  x.q_len = q_len;
+  x.T_max = a->T_max;
+  x.scale = a->scale;
+  x.dtype = a->dtype;
+  x.out = out;
+  x.gamma = gamma;
+  if (!block_uses_mfma(a)) {
+    // generic kernel: both sources in one launch, one workgroup per query row and KV head
+    x.kA = k_hat;
+    x.vA = v_hat;
+    x.kB = k_own;
+    x.vB = v_own;
+    x.mixed = 3;
+    x.wide = 0;
+    x.S = attn_rows_splits(a->B, a->Hkv, q_len, a->Hq / a->Hkv, a->T_max, 0, &x.wide);
+    if (x.S > 1) carve(ws, rows, x.S, &x.part_ml, &x.part_o);
+    return launch_attn_rows(x, st);
+  }
+  // matrix-core kernels: the rows derived from the large model first (split over the context), then the few own
+  // rows of the blocks in flight, whose launch folds the first segment's partials in and finishes the rows
+  const int S1 = attn_block_splits(a->B, a->Hkv, q_len, a->Hq / a->Hkv, a->T_max, &x.wide);
+  x.S_total = S1 + 1;
+  carve(ws, rows, x.S_total, &x.part_ml, &x.part_o);
+  x.kA = k_hat;
+  x.vA = v_hat;
+  x.mixed = 1;
+  x.S = S1;
+  x.s_off = 0;
+  rc = launch_attn_block(x, st);
+  if (rc != TANDEM_OK) return rc;
+  x.kA = k_own;
+  x.vA = v_own;
+  x.mixed = 2;
+  x.wide = 0;
+  x.S = 1;
+  x.s_off = S1;
+  x.merge_prev = S1;
+  return launch_attn_block(x, st);
+}
+
 }  // extern "C"

@@ -31,6 +31,7 @@ struct BlockParams {
   int Hq, Hkv, q_len, G, S;
   int causal;         // 1: the q_len rows are the last rows of the cache (row r sees n + r + 1 keys); 0: all see n keys
   int S_total, s_off;  // partial slots per row and this launch's first slot
+  int mixed, gamma;    // attn_mrows_kernel only: 1 / 2 = first / second key segment of the all-positions small-model attention
   int merge_prev;      // > 0 (needs S == 1): merge slots [0, merge_prev) into this launch's result and write out
   long long T_max;
   float scale_log2e;
@@ -124,10 +125,12 @@ __global__ __launch_bounds__(64 * NW, (RT <= 2 && NW == 4 ? 2 : 1)) void attn_bl
   const int kvh = blockIdx.y % p.Hkv, pass = blockIdx.y / p.Hkv;
 
   long long n = p.n[b];
-  const int ext = p.causal ? p.q_len : 0;
+  // mixed == 1: first key segment of the all-positions small-model attention (see attn_mrows_kernel): row r sees
+  // the keys below its block boundary kb(n + r), no lower limit - the only segment form this kernel takes
+  const int ext = (p.causal || p.mixed) ? p.q_len : 0;
   const long long nmax = p.T_max - ext;
   n = n < 0 ? 0 : (n > nmax ? nmax : n);
-  const long long total = n + ext;
+  const long long total = p.mixed ? (n + p.q_len - 1) / p.gamma * p.gamma : n + ext;
   const int R = p.G * p.q_len;
 
   const long long ntiles = (total + 31) >> 5;
@@ -148,7 +151,7 @@ __global__ __launch_bounds__(64 * NW, (RT <= 2 && NW == 4 ? 2 : 1)) void attn_bl
     if (rho < R) {
       const int r = rho / p.G, gq = rho % p.G;
       orow[rt] = ((long long)b * p.q_len + r) * p.Hq + kvh * p.G + gq;
-      lim[rt] = p.causal ? n + r : n - 1;
+      lim[rt] = p.mixed ? (n + r) / p.gamma * p.gamma - 1 : (p.causal ? n + r : n - 1);
       const bf16_t* qp = p.q + orow[rt] * 128 + 8 * g4;
 #pragma unroll
       for (int c = 0; c < 4; ++c) qreg[rt][c] = ld_bf16x8(qp + 32 * c);
@@ -312,7 +315,9 @@ __global__ __launch_bounds__(64 * NW, (RT <= 2 && NW == 4 ? 2 : 1)) void attn_bl
 //     matrices, as above).
 // The eight staging units of a tile (4 of K, 4 of V) are dealt round-robin to the wavefronts; their global loads
 // for tile t + 1 are in flight while tile t is multiplied.  One barrier per tile, two LDS buffers.
-template <int NW, int D>
+// MIXED = false compiles the per-row lower key limit and the segment logic out (they cost registers: 121 -> 134 at
+// five wavefronts, one wavefront per SIMD less).
+template <int NW, int D, bool MIXED>
 __global__ __launch_bounds__(64 * NW) void attn_mrows_kernel(BlockParams p) {
   __shared__ uint4 buf[2][16][64];
   constexpr int NU = (8 + NW - 1) / NW;  // staging units per wavefront
@@ -321,17 +326,24 @@ __global__ __launch_bounds__(64 * NW) void attn_mrows_kernel(BlockParams p) {
   const int s = blockIdx.x, b = blockIdx.z;
   const int kvh = blockIdx.y % p.Hkv, pass = blockIdx.y / p.Hkv;
 
+  // Key range and per-row visibility.  Ordinary block (mixed == 0): keys [0, total), row r sees keys <= lim.
+  // All-positions small-model attention (Eq. (2) with the query's own block boundary kb(i) = floor(i / gamma)
+  // * gamma, i = n + r): segment 1 reads the rows derived from the large model, keys [0, kb(i)); segment 2 the
+  // model's own rows, keys [kb(i), i].
   long long n = p.n[b];
-  const int ext = p.causal ? p.q_len : 0;
+  const int mixed = MIXED ? p.mixed : 0;
+  const int ext = (p.causal || mixed) ? p.q_len : 0;
   const long long nmax = p.T_max - ext;
   n = n < 0 ? 0 : (n > nmax ? nmax : n);
-  const long long total = n + ext;
+  auto kb = [&](long long i) { return i / p.gamma * p.gamma; };
+  const long long total = mixed == 1 ? kb(n + p.q_len - 1) : n + ext;
+  const long long first = mixed == 2 ? kb(n) >> 5 : 0;  // first tile that any row can see
   const int R = p.G * p.q_len;
 
-  const long long ntiles = (total + 31) >> 5;
+  const long long ntiles = ((total + 31) >> 5) - first;
   const long long per = (ntiles + p.S - 1) / p.S;
-  const long long tile_begin = (long long)s * per;
-  const long long tile_end = ntiles < tile_begin + per ? ntiles : tile_begin + per;
+  const long long tile_begin = first + (long long)s * per;
+  const long long tile_end = first + (ntiles < (s + 1) * per ? ntiles : (s + 1) * per);
 
   const bf16_t* kbase = p.k + ((long long)b * p.Hkv + kvh) * p.T_max * 128;
   const bf16_t* vbase = p.v + ((long long)b * p.Hkv + kvh) * p.T_max * 128;
@@ -340,13 +352,20 @@ __global__ __launch_bounds__(64 * NW) void attn_mrows_kernel(BlockParams p) {
   const float absl = fabsf(p.scale_log2e);
   const uint32_t flip = p.scale_log2e < 0.f ? 0x80008000u : 0u;
   bf16x8 qreg[4];
-  long long lim, orow;
+  long long lim, lo = 0, orow;  // this lane's query column sees keys lo .. lim
   {
     const int rho = (pass * NW + w) * 16 + c16;
     if (rho < R) {
       const int r = rho / p.G, gq = rho % p.G;
       orow = ((long long)b * p.q_len + r) * p.Hq + kvh * p.G + gq;
-      lim = p.causal ? n + r : n - 1;
+      if (mixed == 1) {
+        lim = kb(n + r) - 1;
+      } else if (mixed == 2) {
+        lim = n + r;
+        lo = kb(n + r);
+      } else {
+        lim = p.causal ? n + r : n - 1;
+      }
       const bf16_t* qp = p.q + orow * 128 + 8 * g4;
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
@@ -356,17 +375,18 @@ __global__ __launch_bounds__(64 * NW) void attn_mrows_kernel(BlockParams p) {
       }
     } else {
       orow = -1;
-      lim = n;
+      lim = total;  // padding columns: Q = 0, everything visible, never written
       const uint4 z = {0u, 0u, 0u, 0u};
 #pragma unroll
       for (int c = 0; c < 4; ++c) qreg[c] = __builtin_bit_cast(bf16x8, z);
     }
   }
-  long long lim_min = lim;  // smallest limit among the wavefront's rows
+  long long lim_min = lim, lo_max = lo;  // tightest limits among the wavefront's rows
 #pragma unroll
   for (int off = 1; off < 16; off <<= 1) {
-    const long long o = __shfl_xor(lim_min, off);
+    const long long o = __shfl_xor(lim_min, off), u = __shfl_xor(lo_max, off);
     lim_min = o < lim_min ? o : lim_min;
+    lo_max = u > lo_max ? u : lo_max;
   }
 
   bf16x8 sel[2];
@@ -450,13 +470,20 @@ __global__ __launch_bounds__(64 * NW) void attn_mrows_kernel(BlockParams p) {
       for (int c = 0; c < 4; ++c) a = mfma16(__builtin_bit_cast(bf16x8, buf[bi][4 * sub + c][lane]), qreg[c], a);
       sc[sub] = a;
     }
-    const bool edge = key0 + 31 > lim_min;  // wave-uniform: some key of this tile is hidden from some row
+    // wave-uniform: some key of this tile is hidden from some row
+    const bool edge = key0 + 31 > lim_min || (MIXED && key0 < lo_max);
+    uint32_t seen = 0xffu;  // bit 4 sub + r4: this lane's score is of a visible key
     if (edge) {
+      seen = 0;
 #pragma unroll
       for (int sub = 0; sub < 2; ++sub) {
         const long long kidx = key0 + 16 * sub + 4 * g4;
 #pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) sc[sub][r4] = (kidx + r4 <= lim) ? sc[sub][r4] : -INFINITY;
+        for (int r4 = 0; r4 < 4; ++r4) {
+          const bool ok = kidx + r4 <= lim && (!MIXED || kidx + r4 >= lo);
+          seen |= ok ? 1u << (4 * sub + r4) : 0u;
+          sc[sub][r4] = ok ? sc[sub][r4] : -INFINITY;
+        }
       }
     }
     float mx = fmaxf(fmaxf(fmaxf(sc[0][0], sc[0][1]), fmaxf(sc[0][2], sc[0][3])),
@@ -480,7 +507,8 @@ __global__ __launch_bounds__(64 * NW) void attn_mrows_kernel(BlockParams p) {
     for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
       for (int r4 = 0; r4 < 4; ++r4) {
-        sc[sub][r4] = fast_exp2(fmaf(sc[sub][r4], absl, -m));
+        const float e = fast_exp2(fmaf(sc[sub][r4], absl, -m));
+        sc[sub][r4] = (seen >> (4 * sub + r4)) & 1u ? e : 0.f;  // (-inf * 0 is not a number when the scale is 0)
         ps += sc[sub][r4];
       }
     l += ps;
@@ -498,7 +526,10 @@ __global__ __launch_bounds__(64 * NW) void attn_mrows_kernel(BlockParams p) {
 
 template <int NW>
 int launch_mrows(const BlockParams& p, int passes, int B, hipStream_t st) {
-  hipLaunchKernelGGL((attn_mrows_kernel<NW, 1>), dim3(p.S, p.Hkv * passes, B), dim3(64 * NW), 0, st, p);
+  if (p.mixed)
+    hipLaunchKernelGGL((attn_mrows_kernel<NW, 1, true>), dim3(p.S, p.Hkv * passes, B), dim3(64 * NW), 0, st, p);
+  else
+    hipLaunchKernelGGL((attn_mrows_kernel<NW, 1, false>), dim3(p.S, p.Hkv * passes, B), dim3(64 * NW), 0, st, p);
   return hip_ok(hipGetLastError());
 }
 
@@ -556,6 +587,8 @@ int launch_attn_block(const AttnArgs& a, hipStream_t st) {
   p.S_total = a.S_total > 0 ? a.S_total : a.S;
   p.s_off = a.S_total > 0 ? a.s_off : 0;
   p.merge_prev = a.S_total > 0 && a.S == 1 ? a.merge_prev : 0;
+  p.mixed = a.mixed;
+  p.gamma = a.gamma > 0 ? a.gamma : 1;
   p.T_max = a.T_max;
   p.scale_log2e = a.scale * 1.4426950408889634f;
   p.out = (bf16_t*)a.out;
@@ -564,7 +597,20 @@ int launch_attn_block(const AttnArgs& a, hipStream_t st) {
   const int R = p.G * a.q_len;
   const int tiles = (R + 15) / 16;
   int rc;
-  if (tiles == 1)
+  if (a.mixed == 2 || (a.mixed == 1 && tiles > 2)) {
+    // per-row key ranges with a lower end exist in the row-split kernel only
+    const int passes = (tiles + 7) / 8;
+    switch ((tiles + passes - 1) / passes) {
+      case 1: rc = launch_mrows<1>(p, passes, a.B, st); break;
+      case 2: rc = launch_mrows<2>(p, passes, a.B, st); break;
+      case 3: rc = launch_mrows<3>(p, passes, a.B, st); break;
+      case 4: rc = launch_mrows<4>(p, passes, a.B, st); break;
+      case 5: rc = launch_mrows<5>(p, passes, a.B, st); break;
+      case 6: rc = launch_mrows<6>(p, passes, a.B, st); break;
+      case 7: rc = launch_mrows<7>(p, passes, a.B, st); break;
+      default: rc = launch_mrows<8>(p, passes, a.B, st); break;
+    }
+  } else if (tiles == 1)
     rc = a.wide ? launch_rt<1, 8>(p, 1, a.B, st) : launch_rt<1, 4>(p, 1, a.B, st);
   else if (tiles == 2)
     rc = a.wide ? launch_rt<2, 8>(p, 1, a.B, st) : launch_rt<2, 4>(p, 1, a.B, st);

@@ -21,6 +21,7 @@ struct RowsParams {
   const int32_t *nA, *nB;
   int causal, Hq, Hkv, q_len, gamma_max, S;
   int S_total, s_off;  // partial slots per row and this launch's first slot
+  int mixed_gamma;     // > 0: all-positions small-model attention with this block length (see below)
   long long T_max;
   float scale_log2e;
   void* out;
@@ -40,12 +41,24 @@ __global__ __launch_bounds__(64 * NW) void attn_rows_kernel(RowsParams p) {
   const int kvh = blockIdx.y % p.Hkv, r = blockIdx.y / p.Hkv;
 
   long long nA = p.nA[b];
-  if (p.causal) nA += r + 1;
-  nA = nA < 0 ? 0 : (nA > p.T_max ? p.T_max : nA);
   long long nB = 0;
-  if (p.nB) {
-    nB = p.nB[b];
-    nB = nB < 0 ? 0 : (nB > p.gamma_max ? p.gamma_max : nB);
+  long long strideB = p.gamma_max;  // rows per (sequence, head) of source B
+  if (p.mixed_gamma > 0) {
+    // Eq. (2) at position i = n + r: rows [0, kb) of A (derived from the large model), rows [kb, i] of B (own rows,
+    // a cache indexed by position), kb = floor(i / gamma) * gamma
+    const long long nmax = p.T_max - p.q_len;
+    nA = nA < 0 ? 0 : (nA > nmax ? nmax : nA);
+    const long long i = nA + r;
+    nA = i / p.mixed_gamma * p.mixed_gamma;
+    nB = i + 1 - nA;
+    strideB = p.T_max;
+  } else {
+    if (p.causal) nA += r + 1;
+    nA = nA < 0 ? 0 : (nA > p.T_max ? p.T_max : nA);
+    if (p.nB) {
+      nB = p.nB[b];
+      nB = nB < 0 ? 0 : (nB > p.gamma_max ? p.gamma_max : nB);
+    }
   }
   const long long total = nA + nB;
   long long per = (total + p.S - 1) / p.S;
@@ -55,8 +68,10 @@ __global__ __launch_bounds__(64 * NW) void attn_rows_kernel(RowsParams p) {
 
   const T* kA = (const T*)p.kA + ((long long)b * p.Hkv + kvh) * p.T_max * DH;
   const T* vA = (const T*)p.vA + ((long long)b * p.Hkv + kvh) * p.T_max * DH;
-  const T* kB = p.kB ? (const T*)p.kB + ((long long)b * p.Hkv + kvh) * p.gamma_max * DH : nullptr;
-  const T* vB = p.vB ? (const T*)p.vB + ((long long)b * p.Hkv + kvh) * p.gamma_max * DH : nullptr;
+  // in the all-positions form row (row - nA) of B is cache row `row`: shift the base by nA rows
+  const long long offB = ((long long)b * p.Hkv + kvh) * strideB * DH + (p.mixed_gamma > 0 ? nA * DH : 0);
+  const T* kB = p.kB ? (const T*)p.kB + offB : nullptr;
+  const T* vB = p.vB ? (const T*)p.vB + offB : nullptr;
 
   const long long row0 = ((long long)b * p.q_len + r) * p.Hq + (long long)kvh * G;  // first query row of the group
   float qv[G][EPL];
@@ -276,6 +291,7 @@ int launch_attn_rows(const AttnArgs& a, hipStream_t st) {
   p.S = a.S;
   p.S_total = a.S_total > 0 ? a.S_total : a.S;
   p.s_off = a.S_total > 0 ? a.s_off : 0;
+  p.mixed_gamma = a.mixed == 3 ? (a.gamma > 0 ? a.gamma : 1) : 0;
   p.T_max = a.T_max;
   p.scale_log2e = a.scale * 1.4426950408889634f;
   p.out = a.out;

@@ -33,6 +33,11 @@ struct AttnArgs {
   // MFMA block kernels only, S == 1: fold slots [0, merge_prev) (written by earlier launches on the stream)
   // into this launch's rows and write the finished rows to out - the last segment needs no combine launch.
   int merge_prev;
+  // All-positions small-model attention (Eq. (2) with the query's own block boundary kb = floor(i / gamma) * gamma,
+  // i = nA[b] + r).  MFMA kernels: mixed = 1 - kA/vA hold the rows derived from the large model, row r sees keys
+  // [0, kb); mixed = 2 - kA/vA hold the model's own rows, row r sees [kb, i].  attn_rows kernels: mixed = 3 - kA/vA
+  // as in 1, kB/vB own rows in a cache of T_max rows indexed by position, both in one launch.
+  int mixed, gamma;
 };
 
 // number of context splits; *wide (optional) = 1 when the workgroups should have eight wavefronts (AttnArgs::wide)

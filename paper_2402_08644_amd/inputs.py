@@ -126,6 +126,21 @@ def shared_attn_case(seed, B, samples, q_len, Hq, Hkv, dh, T_shared, T_own, n_sh
     }
 
 
+def mixed_attn_case(seed, B, q_len, Hq, Hkv, dh, T_max, n_prefix, dtype="bf16", std=1.0):
+    """Inputs of one all-positions small-model attention call: queries for q_len consecutive positions and the
+    two caches (rows derived from the large model; the small model's own rows), Q/K/V ~ N(0, std)."""
+    rng = np.random.default_rng(seed)
+    return {
+        "q": normal(rng, (B, q_len, Hq, dh), std, dtype),
+        "khat": normal(rng, (B, Hkv, T_max, dh), std, dtype),
+        "vhat": normal(rng, (B, Hkv, T_max, dh), std, dtype),
+        "kown": normal(rng, (B, Hkv, T_max, dh), std, dtype),
+        "vown": normal(rng, (B, Hkv, T_max, dh), std, dtype),
+        "n": np.broadcast_to(np.asarray(n_prefix, np.int32), (B,)).copy(),
+        "scale": 1.0 / math.sqrt(dh),
+    }
+
+
 def project_case(seed, M, d_L, d_hidden, d_S, dtype="bf16", x_std=1.0, w_std=0.02, bias_std=0.0):
     """Inputs of one FF_Tandem call.  d_hidden == 0 gives the linear form.
     Weights are stored [out, in]."""

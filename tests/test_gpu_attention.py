@@ -386,6 +386,111 @@ def test_block_attn_shared_error_codes(tb):
     torch.cuda.synchronize()
 
 
+# --------------------------------------------------------------------------- all positions of the small model
+def run_mixed(tb, case, gamma):
+    torch, binding = tb
+    dev = {k: case[k].to_torch() for k in ("q", "khat", "vhat", "kown", "vown")}
+    out = binding.tandem_mixed_attn(dev["q"], dev["khat"], dev["vhat"], dev["kown"], dev["vown"],
+                                    torch.from_numpy(case["n"]).cuda(), gamma, scale=case["scale"])
+    torch.cuda.synchronize()
+    return inputs.torch_to_f64(out)
+
+
+def oracle_mixed(case, gamma):
+    return orc.mixed_attn(case["q"].f64, case["khat"].f64, case["vhat"].f64, case["kown"].f64, case["vown"].f64,
+                          case["n"], gamma, case["scale"])
+
+
+@pytest.mark.parametrize(
+    "B,q_len,Hq,Hkv,dh,T_max,n,gamma,dtype",
+    [
+        (2, 32, 8, 8, 128, 700, [668, 0], 4, "bf16"),     # the small model's shape (G=1): 32 rows, two wavefronts
+        (3, 8, 8, 2, 128, 300, [292, 100, 3], 4, "bf16"),  # G=4: 32 rows; block boundaries inside the chunk
+        (2, 5, 4, 4, 128, 530, [525, 64], 3, "bf16"),      # chunk not aligned with the blocks, one wavefront
+        (1, 32, 8, 2, 128, 1300, [1200], 8, "bf16"),       # 128 rows: eight wavefronts, several context splits
+        (2, 18, 8, 1, 128, 400, [382, 5], 5, "bf16"),      # G=8, 144 rows: two passes
+        (2, 6, 4, 2, 128, 200, [194, 0], 1, "bf16"),       # block length 1: only the query's own row is its own
+        (2, 6, 4, 2, 128, 200, [194, 0], 1000, "bf16"),    # no block ever completes: causal over the own rows
+        (2, 7, 4, 2, 64, 150, [143, 10], 4, "bf16"),       # dh=64 generic path
+        (2, 4, 2, 2, 64, 130, [126, 0], 2, "f32"),         # the tiny config's small model shape
+        (1, 9, 4, 1, 128, 600, [555], 4, "f32"),
+    ],
+)
+def test_mixed_attn_parity_small(tb, B, q_len, Hq, Hkv, dh, T_max, n, gamma, dtype):
+    case = inputs.mixed_attn_case(41, B, q_len, Hq, Hkv, dh, T_max, n, dtype=dtype)
+    got = run_mixed(tb, case, gamma)
+    e = assert_rows_close(got.reshape(-1, Hq, dh), oracle_mixed(case, gamma).reshape(-1, Hq, dh), what="mixed")
+    print(f"mixed small {B,q_len,Hq,Hkv,dh,T_max,gamma,dtype}: max rel err {e[0]:.2e}")
+
+
+def test_mixed_attn_reads_the_right_cache_exactly(tb):
+    """Q = 0 (uniform weights); V of the hat cache is 1 everywhere, V of the own cache 2: the query at position i
+    must give exactly (k + 2 (i + 1 - k)) / (i + 1) with k = floor(i / gamma) * gamma - any key taken from the
+    wrong cache, hidden or counted twice changes the value."""
+    torch, binding = tb
+    B, q_len, Hq, Hkv, dh, T_max, gamma = 1, 32, 8, 8, 128, 400, 4
+    q = torch.zeros(B, q_len, Hq, dh, dtype=torch.bfloat16, device="cuda")
+    k = torch.randn(B, Hkv, T_max, dh, device="cuda").to(torch.bfloat16)
+    vh = torch.ones(B, Hkv, T_max, dh, dtype=torch.bfloat16, device="cuda")
+    vo = 2 * vh
+    for n0 in (0, 37, 368):
+        n = torch.tensor([n0], dtype=torch.int32, device="cuda")
+        out = binding.tandem_mixed_attn(q, k, vh, k, vo, n, gamma, scale=1.0).float().cpu().numpy()
+        for r in range(q_len):
+            i = n0 + r
+            kb = i // gamma * gamma
+            want = (kb + 2.0 * (i + 1 - kb)) / (i + 1)
+            assert np.allclose(out[0, r], want, rtol=4e-3), (n0, r, out[0, r, 0, 0], want)
+
+
+def test_mixed_attn_full_size_sampled(tb):
+    """C3's small-model layer shape at context 8192 (the bench configuration): sampled output rows against the
+    oracle's single-row definition."""
+    torch, binding = tb
+    B, q_len, Hq, Hkv, dh, T_max, gamma = 32, 32, 8, 8, 128, 8192, 4
+    g = torch.Generator(device="cuda").manual_seed(7)
+    mk = lambda *sh: torch.randn(*sh, device="cuda", generator=g).to(torch.bfloat16)
+    q, kh, vh, ko, vo = mk(B, q_len, Hq, dh), mk(B, Hkv, T_max, dh), mk(B, Hkv, T_max, dh), mk(B, Hkv, T_max, dh), mk(B, Hkv, T_max, dh)
+    n_host = np.full(B, T_max - q_len, np.int32)
+    n_host[1], n_host[2] = 1000, 0
+    out = binding.tandem_mixed_attn(q, kh, vh, ko, vo, torch.from_numpy(n_host).cuda(), gamma)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(3)
+    f = inputs.torch_to_f64
+    for _ in range(24):
+        b, r, h = int(rng.integers(0, B)), int(rng.integers(0, q_len)), int(rng.integers(0, Hq))
+        i = int(n_host[b]) + r
+        kb = i // gamma * gamma
+        K = np.concatenate([f(kh[b, h, :kb]), f(ko[b, h, kb:i + 1])])
+        V = np.concatenate([f(vh[b, h, :kb]), f(vo[b, h, kb:i + 1])])
+        want = orc.attention_one(f(q[b, r, h]), K, V, 1.0 / math.sqrt(dh))
+        assert_rows_close(f(out[b, r, h])[None], want[None], what=f"mixed sampled row {b,r,h}")
+
+
+def test_mixed_attn_error_codes(tb):
+    torch, binding = tb
+    import ctypes as C
+
+    L = binding.lib()
+    d = binding.attn_desc(2, 4, 2, 128, 64, 0, 0.1, binding.BF16)
+    t = torch.zeros(2 * 4 * 64 * 128, dtype=torch.bfloat16, device="cuda")
+    n = torch.zeros(2, dtype=torch.int32, device="cuda")
+    p, pn = C.c_void_p(t.data_ptr()), C.c_void_p(n.data_ptr())
+    ws = torch.zeros(1 << 22, dtype=torch.uint8, device="cuda")
+    pw = C.c_void_p(ws.data_ptr())
+    call = lambda ql, g, q=p, w=pw, wb=ws.numel(): L.tandem_mixed_attn(C.byref(d), q, p, p, p, p, pn, ql, g, p, w, wb, None)
+    assert call(0, 4) == binding.ERR_SHAPE
+    assert call(33, 4) == binding.ERR_SHAPE
+    assert call(4, 0) == binding.ERR_SHAPE
+    assert call(4, 4, q=None) == binding.ERR_NULL
+    need = binding.tandem_mixed_attn_workspace(d, 4)
+    assert need > 0
+    assert call(4, 4, w=None) == binding.ERR_NULL
+    assert call(4, 4, wb=need - 1) == binding.ERR_WORKSPACE
+    assert call(4, 4, wb=need) == binding.OK
+    torch.cuda.synchronize()
+
+
 # --------------------------------------------------------------------------- error paths
 def test_attention_error_codes(tb):
     torch, binding = tb
