@@ -243,6 +243,43 @@ def attended_sets(i, gamma):
 
 
 # ----------------------------------------------------------------------------
+# O6a  adaptive block length (Sec. 3.1 "Adaptive Block Length"; Sec. 4: tau = 0.8).  After every draft token a
+#      2-layer router MLP looks at M_S's output distribution and decides whether M_S may go on drafting.
+#      Features, in this order: the entropy of the distribution over the vocabulary (nats), the k largest
+#      probabilities in descending order (equal values: lowest id first), and M_S's embedding rows of those k
+#      tokens.  Readings (the paper fixes neither): hidden activation ReLU, output sigmoid = predicted
+#      probability that M_L accepts the current draft token; drafting continues iff it is >= tau.
+#      R = {"k": int, "W1": [H, 1 + k + k*d], "b1": [H], "w2": [H], "b2": scalar}
+# ----------------------------------------------------------------------------
+def router_features(logits, emb, k):
+    lg = np.asarray(logits, F64)
+    z = lg - lg.max()
+    e = np.exp(z)
+    Z = e.sum()
+    prob = e / Z
+    nz = prob > 0.0
+    entropy = -(prob[nz] * np.log(prob[nz])).sum()
+    ids = []
+    for _ in range(k):
+        best = -1
+        for t in range(len(lg)):  # lowest id wins among equal logits
+            if t in ids:
+                continue
+            if best < 0 or lg[t] > lg[best]:
+                best = t
+        ids.append(best)
+    feats = [np.array([entropy]), prob[ids]] + [np.asarray(emb, F64)[t] for t in ids]
+    return np.concatenate(feats), ids
+
+
+def router_prob(R, logits, emb):
+    f, _ = router_features(logits, emb, R["k"])
+    h = relu(np.asarray(R["W1"], F64) @ f + np.asarray(R["b1"], F64))
+    z = float(np.asarray(R["w2"], F64) @ h + float(np.asarray(R["b2"], F64).reshape(-1)[0]))
+    return 1.0 / (1.0 + math.exp(-z))
+
+
+# ----------------------------------------------------------------------------
 # O6  one Tandem + SPEED decode step on caller-provided caches (Sec. 3.1,
 #     Sec. 1 steps 2-4, Table 6: one step = gamma small runs + one large run).
 #
@@ -256,7 +293,11 @@ def attended_sets(i, gamma):
 # d_1..d_gamma as the *inputs* of the following small runs and that are all
 # treated as accepted (teacher forcing).  The state is updated in place.
 # ----------------------------------------------------------------------------
-def decode_step(T, state, gamma, forced=None, free_token=False):
+def decode_step(T, state, gamma, forced=None, free_token=False, router=None, tau=0.8):
+    """router: with it, gamma is the largest block length; sequence b stops drafting after the first draft token
+    whose router probability is below tau (n_drafted[b] tokens, at least one) and M_L verifies that many (+ 1 with
+    the free token); rows of the outputs beyond a sequence's own block length stay at their initial values."""
+    assert router is None or forced is None
     eps = T["eps"]
     ML, MS = T["L"], T["S"]
     B = len(state["n"])
@@ -274,8 +315,12 @@ def decode_step(T, state, gamma, forced=None, free_token=False):
         "x_large": np.zeros((B, nq, ML["emb"].shape[1]), F64),
         "logits_S": np.zeros((B, gamma, MS["W_out"].shape[0]), F64),
         "logits_L": np.zeros((B, nq, ML["W_out"].shape[0]), F64),
+        "n_drafted": np.full(B, gamma, np.int64),
+        "router_p": np.full((B, gamma), np.nan, F64),
     }
+    gamma_max, nq_max = gamma, nq
     for b in range(B):
+        gamma, nq = gamma_max, nq_max
         n = int(state["n"][b])
         # ---- draft: gamma autoregressive runs of M_S (Sec. 3.1) ------------
         Hq, Hkv, dh = MS["Hq"], MS["Hkv"], MS["dh"]
@@ -307,6 +352,14 @@ def decode_step(T, state, gamma, forced=None, free_token=False):
             d = argmax_lowest(lg)
             out["draft"][b, r] = d
             inputs.append(int(forced[b][r]) if forced is not None else d)
+            if router is not None:
+                pr = router_prob(router, lg, MS["emb"])
+                out["router_p"][b, r] = pr
+                if pr < tau:  # M_L is unlikely to accept this token: verify now
+                    gamma = r + 1
+                    break
+        nq = gamma + 1 if free_token else gamma
+        out["n_drafted"][b] = gamma
         # ---- verify: M_L in block mode on the first nq tokens of [pending, d_1 .. d_gamma] ----
         Hq, Hkv, dh = ML["Hq"], ML["Hkv"], ML["dh"]
         G = Hq // Hkv
@@ -330,11 +383,11 @@ def decode_step(T, state, gamma, forced=None, free_token=False):
             x = x + linear(a.reshape(nq, Hq * dh), lay["Wo"])
             x = x + mlp(rmsnorm(x, lay["g_mlp"], eps), lay)
             xs.append(x)
-        out["x_large"][b] = x
+        out["x_large"][b, :nq] = x
         lgL = logits_of(ML, x, eps)
-        out["logits_L"][b] = lgL
+        out["logits_L"][b, :nq] = lgL
         tL = [argmax_lowest(lgL[r]) for r in range(nq)]
-        out["verify"][b] = tL
+        out["verify"][b, :nq] = tL
         # ---- FF_Tandem on the new rows, then the small layer's own norm and
         #      W_K / W_V turn y_hat into cached K_hat / V_hat (Eq. (2) line 1,
         #      Training paragraph second bullet) --------------------------
@@ -363,7 +416,7 @@ def decode_step(T, state, gamma, forced=None, free_token=False):
             if a_cnt < gamma or free_token:
                 emitted = [int(t) for t in out["draft"][b, :a_cnt]] + [tL[a_cnt]]
             else:
-                emitted = [int(t) for t in out["draft"][b]]
+                emitted = [int(t) for t in out["draft"][b, :gamma]]
             new_pending = emitted[-1]
             n_new = n + (a_cnt + 1 if free_token else min(a_cnt + 1, gamma))
         out["n_accepted"][b] = a_cnt

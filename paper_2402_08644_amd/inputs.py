@@ -226,6 +226,19 @@ def tiny_tandem(seed=0, dtype="f32"):
     )
 
 
+def router_weights(seed, k, d, hidden, dtype="f32", w_std=0.05):
+    """Random-init router MLP of the adaptive block length: input 1 + k + k*d features, `hidden` units, one output
+    (weights N(0, w_std); the trained router of the paper is not available)."""
+    rng = np.random.default_rng(seed)
+    return {
+        "k": k,
+        "W1": normal(rng, (hidden, 1 + k + k * d), w_std, dtype),
+        "b1": normal(rng, (hidden,), w_std, dtype),
+        "w2": normal(rng, (hidden,), 10 * w_std, dtype),
+        "b2": normal(rng, (1,), w_std, dtype),
+    }
+
+
 def as_f64(tree):
     """Map a weight tree of HostTensors to the float64 tree the oracle takes."""
     if isinstance(tree, HostTensor):

@@ -444,3 +444,132 @@ def test_prefill_rows_are_ragged_and_independent():
     one = orc.prefill_block(T, solo, toks[:1])
     np.testing.assert_allclose(both["x_large"][0], one["x_large"][0], rtol=1e-12, atol=1e-12)
     assert list(st["n"]) == [3, 8]
+
+
+# ------------------------------------------------------------------ adaptive block length
+def test_router_features_against_scipy_and_sorting():
+    """Entropy and probabilities against scipy's softmax / entropy, the top-k order against a stable sort."""
+    from scipy.special import softmax
+    from scipy.stats import entropy
+
+    rng = np.random.default_rng(0)
+    V, d, k = 50, 6, 4
+    lg = 3.0 * rng.standard_normal(V)
+    lg[7] = lg[31] = lg.max() + 1.0  # a tie at the top: the lower id comes first
+    emb = rng.standard_normal((V, d))
+    f, ids = orc.router_features(lg, emb, k)
+    order = np.argsort(-lg, kind="stable")[:k]
+    assert ids == [int(t) for t in order] and ids[:2] == [7, 31]
+    pr = softmax(lg)
+    assert f.shape == (1 + k + k * d,)
+    np.testing.assert_allclose(f[0], entropy(pr), rtol=1e-12)
+    np.testing.assert_allclose(f[1:1 + k], pr[order], rtol=1e-12)
+    np.testing.assert_array_equal(f[1 + k:].reshape(k, d), emb[order])
+
+
+def test_router_closed_forms():
+    V, d, k, H = 16, 3, 2, 5
+    emb = np.arange(V * d, dtype=np.float64).reshape(V, d)
+    f, ids = orc.router_features(np.zeros(V), emb, k)  # uniform distribution
+    assert ids == [0, 1]
+    np.testing.assert_allclose(f[0], np.log(V), rtol=1e-14)
+    np.testing.assert_allclose(f[1:3], 1.0 / V, rtol=1e-14)
+    lg = np.full(V, -800.0)
+    lg[5] = 0.0  # all mass on one token: entropy 0, exp underflow must not produce NaN
+    f, ids = orc.router_features(lg, emb, k)
+    assert ids[0] == 5 and f[0] == 0.0 and f[1] == 1.0 and f[2] == 0.0
+    R = {"k": k, "W1": np.zeros((H, 1 + k + k * d)), "b1": np.array([1.0, -2.0, 0.5, 0.0, 3.0]),
+         "w2": np.array([1.0, 100.0, -2.0, 7.0, 0.5]), "b2": np.array([0.25])}
+    # h = relu(b1) = [1, 0, .5, 0, 3]; z = 1 - 1 + 1.5 + .25 = 1.75
+    np.testing.assert_allclose(orc.router_prob(R, np.zeros(V), emb), 1.0 / (1.0 + np.exp(-1.75)), rtol=1e-14)
+    R["w2"] = np.zeros(H)
+    R["b2"] = np.array([0.0])
+    assert orc.router_prob(R, lg, emb) == 0.5
+
+
+def test_router_mlp_against_torch():
+    rng = np.random.default_rng(1)
+    V, d, k, H = 30, 8, 3, 12
+    R = inputs.as_f64(inputs.router_weights(3, k, d, H, w_std=0.5))
+    emb, lg = rng.standard_normal((V, d)), 2.0 * rng.standard_normal(V)
+    f, _ = orc.router_features(lg, emb, k)
+    t = lambda a: torch.from_numpy(np.asarray(a, np.float64))
+    h = F.relu(F.linear(t(f), t(R["W1"]), t(R["b1"])))
+    want = torch.sigmoid(F.linear(h, t(R["w2"])[None], t(R["b2"])))[0].item()
+    np.testing.assert_allclose(orc.router_prob(R, lg, emb), want, rtol=1e-12)
+
+
+def _random_state(T, B, T_max, seed, n, pending):
+    st = orc.empty_state(T, B, T_max)
+    rng = np.random.default_rng(seed)
+    for key in ("KL", "VL", "Khat", "Vhat"):
+        for a in st[key]:
+            a[...] = rng.standard_normal(a.shape)
+    st["n"][:] = n
+    st["pending"][:] = pending
+    return st
+
+
+@pytest.mark.parametrize("free", [False, True])
+def test_adaptive_block_length_limits_and_per_sequence_equivalence(free):
+    """tau = 0: the router never stops M_S, the step is the fixed-gamma step.  tau > 1: it always stops after one
+    draft token, the step is the gamma = 1 step.  In between: every sequence's outcome and cache rows are those
+    of a fixed-gamma step with gamma = its own number of drafted tokens."""
+    T = small_pair(seed=40)
+    d_S = T["S"]["emb"].shape[1]
+    R = inputs.as_f64(inputs.router_weights(9, 3, d_S, 10, w_std=0.6))
+    B, gmax = 4, 4
+    mk = lambda: _random_state(T, B, 40, 5, [5, 11, 0, 20], [3, 17, 8, 30])
+    for tau, g_fixed in ((0.0, gmax), (1.5, 1)):
+        sa, sf = mk(), mk()
+        a = orc.decode_step(T, sa, gmax, free_token=free, router=R, tau=tau)
+        f = orc.decode_step(T, sf, g_fixed, free_token=free)
+        assert list(a["n_drafted"]) == [g_fixed] * B
+        q = g_fixed + (1 if free else 0)
+        np.testing.assert_array_equal(a["tokens"][:, :q], f["tokens"])
+        np.testing.assert_array_equal(a["n_accepted"], f["n_accepted"])
+        np.testing.assert_array_equal(sa["n"], sf["n"])
+        np.testing.assert_array_equal(sa["pending"], sf["pending"])
+        for key in ("KL", "VL", "Khat", "Vhat"):
+            for x, y in zip(sa[key], sf[key]):
+                np.testing.assert_array_equal(x, y)
+    # a threshold inside the spread of this router's probabilities: mixed block lengths
+    probe = orc.decode_step(T, mk(), gmax, free_token=free, router=R, tau=0.0)["router_p"]
+    tau = float(np.median(probe))
+    sa = mk()
+    a = orc.decode_step(T, sa, gmax, free_token=free, router=R, tau=tau)
+    assert len(set(a["n_drafted"])) > 1, a["n_drafted"]
+    for b in range(B):
+        g = int(a["n_drafted"][b])
+        first_low = [r for r in range(gmax) if probe[b, r] < tau]
+        assert g == (first_low[0] + 1 if first_low else gmax)
+        full = mk()
+        one = {k: ([x[b:b + 1].copy() for x in v] if isinstance(v, list) else v[b:b + 1].copy()) for k, v in full.items()}
+        f = orc.decode_step(T, one, g, free_token=free)
+        q = g + (1 if free else 0)
+        np.testing.assert_array_equal(a["tokens"][b, :q], f["tokens"][0])
+        assert (a["tokens"][b, q:] == -1).all()
+        assert a["n_accepted"][b] == f["n_accepted"][0] and sa["n"][b] == one["n"][0] and sa["pending"][b] == one["pending"][0]
+        for key in ("KL", "VL", "Khat", "Vhat"):
+            for x, y in zip(sa[key], one[key]):
+                np.testing.assert_array_equal(x[b], y[0])
+
+
+def test_adaptive_speed_stream_equals_greedy_large_decode():
+    """Whatever the router decides, Tandem + SPEED emits what greedy decoding with M_L alone emits (Sec. 3.1)."""
+    T = small_pair(seed=23, w_std=0.5)
+    R = inputs.as_f64(inputs.router_weights(4, 2, T["S"]["emb"].shape[1], 8, w_std=0.8))
+    P, n_new = 5, 10
+    prompt = inputs.token_ids(2, (P,), 40)
+    want = orc.greedy_decode_large(T["L"], prompt, n_new, T["eps"])
+    for free in (False, True):
+        st = orc.empty_state(T, 1, 64)
+        st["pending"][0] = prompt[0]
+        orc.decode_step(T, st, P - 1, forced=prompt[None, 1:])
+        got, drafted = [], []
+        while len(got) < n_new:
+            out = orc.decode_step(T, st, 4, free_token=free, router=R, tau=0.5)
+            got += [int(t) for t in out["tokens"][0, : int(out["n_emitted"][0])]]
+            drafted.append(int(out["n_drafted"][0]))
+        assert got[:n_new] == want
+        assert min(drafted) >= 1 and max(drafted) <= 4
