@@ -310,7 +310,7 @@ def step_bytes(cfg):
     return draft + verify + ff
 
 
-def step_workload(torch, binding, inputs, cfg, seed=3, pack_weights=True, free_token=False):
+def step_workload(torch, binding, inputs, cfg, seed=3, pack_weights=True, free_token=False, adaptive=False):
     B, g, ctx = cfg["B"], cfg["gamma"], cfg["ctx"]
     W = device_tandem_weights(inputs, cfg, seed)
     model = binding.TandemModel(W, pack_weights=pack_weights)
@@ -329,11 +329,22 @@ def step_workload(torch, binding, inputs, cfg, seed=3, pack_weights=True, free_t
     ws = torch.empty(binding.tandem_decode_step_workspace(model, B, g), dtype=torch.uint8, device="cuda")
     out = {"tokens": torch.empty((B, q), dtype=torch.int32, device="cuda"),
            "n_accepted": torch.empty((B,), dtype=torch.int32, device="cuda")}
+    router = None
+    if adaptive:
+        # random-init router of the adaptive block length (k = 4, 256 hidden units); the threshold 0.5 sits in
+        # the middle of what such a router puts out, so the sequences stop at different block lengths
+        S = cfg["small"]
+        router = {"k": 4, "W1": inputs.device_normal((256, 1 + 4 * (S["d"] + 1)), seed * 31 + 1, 0.05),
+                  "b1": inputs.device_normal((256,), seed * 31 + 2, 0.05),
+                  "w2": inputs.device_normal((256,), seed * 31 + 3, 0.5),
+                  "b2": inputs.device_normal((1,), seed * 31 + 4, 0.05)}
+        out["n_drafted"] = torch.empty((B,), dtype=torch.int32, device="cuda")
+        out["router_p"] = torch.empty((B, g), dtype=torch.float32, device="cuda")
 
     def call(_i):
         state.n.fill_(n0)       # keep the context at ctx: the step itself advances n
         state.pending.fill_(1)
-        binding.tandem_decode_step(model, state, g, ws=ws, out=out, free_token=free_token)
+        binding.tandem_decode_step(model, state, g, ws=ws, out=out, free_token=free_token, router=router, tau=0.5)
 
     return call, model, state, out
 
@@ -574,7 +585,7 @@ def run_step_workload(torch, binding, inputs, args):
     cfg = C3
     B, g, ctx = cfg["B"], cfg["gamma"], cfg["ctx"]
     call, model, state, out = step_workload(torch, binding, inputs, cfg, pack_weights=not args.plain_weights,
-                                            free_token=args.free_token)
+                                            free_token=args.free_token, adaptive=args.adaptive)
     torch.cuda.synchronize()
     ms = _time_calls(torch, call, 1, args.steps, args.warmup, use_graph=not args.no_graph)
 
@@ -615,7 +626,9 @@ def run_step_workload(torch, binding, inputs, args):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "c3_step: tandem_decode_step bf16 B=32 ctx=8192 gamma=4, large 32L d=4096 32/8x128, "
                                "small 8L d=1024 8x128, FF_Tandem 4096->8192->1024, vocab 32768"
-                               + (", free token (5 verified rows)" if args.free_token else ""),
+                               + (", free token (5 verified rows)" if args.free_token else "")
+                               + (", adaptive block length (random-init router, k=4, 256 units, tau=0.5; block lengths "
+                                  f"drafted in the last step: {sorted(out['n_drafted'].cpu().tolist())})" if args.adaptive else ""),
                    "step_algorithmic_GB": total_bytes / 1e9, "step_GBps": total_bytes / (ms * 1e-3) / 1e9,
                    "step_frac_of_hbm_peak": total_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
         "roofline": {"bound": "hbm", "kernel": "attn_block_kernel (tandem_block_attn, one large layer of the step)",
@@ -638,6 +651,8 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--plain-weights", action="store_true",
                     help="read weights in the caller's row-major layout only (no packed copies)")
+    ap.add_argument("--adaptive", action="store_true",
+                    help="c3_step: run the step with the adaptive block length (tandem_decode_step_adaptive)")
     ap.add_argument("--free-token", action="store_true",
                     help="c3_step only: verify gamma + 1 rows and emit the bonus token (Fig. 2)")
     ap.add_argument("--copy-calibration", action="store_true",

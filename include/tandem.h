@@ -258,6 +258,42 @@ int tandem_decode_step(const tandem_model *m, const tandem_state_desc *state, in
                        int32_t *out_tokens, int32_t *n_accepted, const tandem_step_aux *aux, void *ws, size_t ws_bytes,
                        void *hip_stream);
 
+/* ---- adaptive block length (Sec. 3.1 "Adaptive Block Length"; Sec. 4: threshold 0.8) ----
+ * A 2-layer router MLP decides after every draft token whether M_S goes on drafting or M_L verifies now.  Its
+ * input, in this order: the entropy (nats) of M_S's distribution over the vocabulary for the current token, the k
+ * largest probabilities in descending order (equal logits: lowest id first), and M_S's input-embedding rows of those
+ * k tokens - 1 + k + k * d numbers.  The paper fixes neither the hidden activation nor the meaning of the output;
+ * here: p = sigmoid(w2 . relu(W1 f + b1) + b2) is the predicted probability that M_L accepts the current draft
+ * token, and drafting continues iff p >= tau.  All device pointers in `dtype`; b1, b2 may be NULL (zero).
+ *   W1 [d_hidden, 1 + k + k * d]   b1 [d_hidden]   w2 [d_hidden]   b2 [1]
+ * 1 <= k <= TANDEM_ROUTER_MAX_K, (1 + k + k * d) * 4 bytes + 64 <= 64 KB (the feature vector lives in LDS). */
+#define TANDEM_ROUTER_MAX_K 8
+typedef struct {
+  int32_t k, d_hidden;
+  int32_t dtype; /* tandem_dtype; for tandem_decode_step_adaptive the model's */
+  float tau;
+  const void *W1, *b1, *w2, *b2;
+} tandem_router_desc;
+
+/* The router alone: p_out[i] (device fp32 [rows]) for the logits rows logits[i, :] (device [rows, vocab]) with the
+ * embedding table emb (device [vocab, d]), both in r->dtype.  tau is not used. */
+int tandem_router_eval(const tandem_router_desc *r, const void *logits, const void *emb, int32_t rows, int32_t vocab,
+                       int32_t d, float *p_out, void *hip_stream);
+
+/* tandem_decode_step with the adaptive block length: gamma_max is the largest block.  Sequence b stops drafting
+ * after the first draft token whose router probability is below tau: g[b] tokens, 1 <= g[b] <= gamma_max.  The
+ * batch still runs gamma_max draft runs and verifies q = gamma_max (+ 1) rows per sequence - a stopped sequence
+ * keeps its place, its later rows are computed and ignored, and the cache rows they write lie beyond the new n[b]
+ * and are overwritten by the following steps - but acceptance, emitted tokens, n[b] and pending[b] are those of
+ * a step with gamma = g[b] (the free token, if asked for, is M_L's token after d_g[b]).
+ *   n_drafted  optional device int32 [B]: g[b]
+ *   router_p   optional device fp32 [B, gamma_max]: the router's p after every draft run (also past g[b])
+ * No forced tokens.  Everything else as in tandem_decode_step, including the workspace size. */
+int tandem_decode_step_adaptive(const tandem_model *m, const tandem_state_desc *state,
+                                const tandem_router_desc *router, int32_t gamma_max, int32_t flags,
+                                int32_t *out_tokens, int32_t *n_accepted, int32_t *n_drafted, float *router_p,
+                                const tandem_step_aux *aux, void *ws, size_t ws_bytes, void *hip_stream);
+
 /* Prompt ingestion (Sec. 1 steps 1 and 3 for tokens that are already known; Sec. 3 "Inference"): for every
  * sequence, M_L processes tokens[b, 0:q_len) at positions n[b] .. n[b]+q_len-1 in block mode, appending its
  * K/V rows, and FF_Tandem with the small layers' norm and W_K / W_V appends the Khat/Vhat rows.  M_S does not

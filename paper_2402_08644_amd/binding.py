@@ -75,6 +75,12 @@ class StepAux(C.Structure):
     _fields_ = [(k, C.c_void_p) for k in ("draft", "verify", "y_small", "x_large", "logits_S", "logits_L")]
 
 
+class RouterDesc(C.Structure):
+    _fields_ = [("k", C.c_int32), ("d_hidden", C.c_int32), ("dtype", C.c_int32), ("tau", C.c_float),
+                ("W1", C.c_void_p), ("b1", C.c_void_p), ("w2", C.c_void_p), ("b2", C.c_void_p)]
+
+
+ROUTER_MAX_K = 8
 MODEL_PACK_WEIGHTS = 1
 STEP_FREE_TOKEN = 1
 PREFILL_EMIT = 1
@@ -88,6 +94,7 @@ EXPORTS = (
     "tandem_mixed_attn_workspace", "tandem_mixed_attn",
     "tandem_model_create", "tandem_model_destroy", "tandem_decode_step_workspace", "tandem_decode_step",
     "tandem_prefill_workspace", "tandem_prefill",
+    "tandem_router_eval", "tandem_decode_step_adaptive",
 )
 
 _lib = None
@@ -106,6 +113,11 @@ def lib():
     L.tandem_status_string.argtypes = [C.c_int]
     L.tandem_project_workspace.restype = sz
     L.tandem_project_workspace.argtypes = [C.POINTER(FFDesc), i64]
+    L.tandem_router_eval.restype = C.c_int
+    L.tandem_router_eval.argtypes = [C.POINTER(RouterDesc), vp, vp, i32, i32, i32, vp, vp]
+    L.tandem_decode_step_adaptive.restype = C.c_int
+    L.tandem_decode_step_adaptive.argtypes = [vp, C.POINTER(StateDesc), C.POINTER(RouterDesc), i32, i32, vp, vp, vp, vp,
+                                              C.POINTER(StepAux), vp, sz, vp]
     L.tandem_mixed_attn_workspace.restype = sz
     L.tandem_mixed_attn_workspace.argtypes = [C.POINTER(AttnDesc), i32]
     L.tandem_mixed_attn.restype = C.c_int
@@ -484,12 +496,47 @@ def tandem_decode_step_workspace(model: TandemModel, B: int, gamma: int) -> int:
     return int(lib().tandem_decode_step_workspace(model.handle, B, gamma))
 
 
+def router_desc(router: dict, tau: float = 0.8) -> RouterDesc:
+    """router: {"k", "W1" [H, 1+k+k*d], "w2" [H], optional "b1" [H], "b2" [1]} of device tensors of one dtype."""
+    W1 = router["W1"]
+    opt = lambda k: router[k].data_ptr() if router.get(k) is not None else None
+    for k in ("W1", "b1", "w2", "b2"):
+        t = router.get(k)
+        if t is not None and (not t.is_cuda or not t.is_contiguous() or t.dtype != W1.dtype):
+            raise ValueError(f"router {k}: expected a contiguous device tensor of the dtype of W1")
+    if router["w2"].numel() != W1.shape[0] or (router.get("b1") is not None and router["b1"].numel() != W1.shape[0]):
+        raise ValueError("router: b1 / w2 do not match the rows of W1")
+    return RouterDesc(int(router["k"]), W1.shape[0], _dtype_code(W1), float(tau), W1.data_ptr(), opt("b1"),
+                      router["w2"].data_ptr(), opt("b2"))
+
+
+def tandem_router_eval(router: dict, logits, emb, out=None, stream=None):
+    """The router's probability for every logits row: logits [rows, vocab], emb [vocab, d] -> fp32 [rows]."""
+    import torch
+
+    rows, vocab = logits.shape
+    d = emb.shape[1]
+    _need(logits, (rows, vocab), "logits")
+    _need(emb, (vocab, d), "emb")
+    rd = router_desc(router)
+    if router["W1"].shape[1] != 1 + rd.k * (d + 1):
+        raise ValueError("router W1: expected 1 + k + k*d columns")
+    if logits.dtype != router["W1"].dtype or emb.dtype != router["W1"].dtype:
+        raise TypeError("logits / emb / router dtypes differ")
+    if out is None:
+        out = torch.empty((rows,), dtype=torch.float32, device=logits.device)
+    rc = lib().tandem_router_eval(C.byref(rd), _ptr(logits), _ptr(emb), rows, vocab, d, _ptr(out), _stream(stream))
+    _check(rc, "tandem_router_eval")
+    return out
+
+
 def tandem_decode_step(model: TandemModel, state: TandemState, gamma: int, forced=None, aux=False, ws=None, out=None,
-                       stream=None, free_token=False):
+                       stream=None, free_token=False, router=None, tau=0.8):
     """Runs one step.  q = gamma, or gamma + 1 with free_token (M_L also verifies the last draft and always
     emits its own token after the accepted prefix).  Returns a dict with "tokens" [B,q] and "n_accepted" [B]
     (int32 device tensors) and, with aux=True, "draft" [B,gamma], "verify" [B,q], "y_small", "x_large",
-    "logits_S", "logits_L"."""
+    "logits_S", "logits_L".  With router (see router_desc) the block length adapts per sequence up to gamma:
+    the dict then also holds "n_drafted" [B] (int32) and "router_p" [B,gamma] (fp32)."""
     import torch
 
     B = state.B
@@ -517,6 +564,21 @@ def tandem_decode_step(model: TandemModel, state: TandemState, gamma: int, force
             raise TypeError("forced must be int32")
     if ws is None:
         ws = _workspace(tandem_decode_step_workspace(model, B, gamma), state.n)
+    if router is not None:
+        if forced is not None:
+            raise ValueError("forced tokens and the adaptive block length exclude each other")
+        rd = router_desc(router, tau)
+        if router["W1"].shape[1] != 1 + rd.k * (model.S.d + 1):
+            raise ValueError("router W1: expected 1 + k + k*d columns")
+        out.setdefault("n_drafted", torch.empty((B,), dtype=torch.int32, device=dev))
+        out.setdefault("router_p", torch.empty((B, gamma), dtype=torch.float32, device=dev))
+        rc = lib().tandem_decode_step_adaptive(model.handle, C.byref(state.desc), C.byref(rd), gamma,
+                                               STEP_FREE_TOKEN if free_token else 0, _ptr(out["tokens"]),
+                                               _ptr(out["n_accepted"]), _ptr(out["n_drafted"]), _ptr(out["router_p"]),
+                                               C.byref(a) if a is not None else None, _ptr(ws), ws.numel(),
+                                               _stream(stream))
+        _check(rc, "tandem_decode_step_adaptive")
+        return out
     rc = lib().tandem_decode_step(model.handle, C.byref(state.desc), gamma, STEP_FREE_TOKEN if free_token else 0,
                                   _ptr(forced), _ptr(out["tokens"]),
                                   _ptr(out["n_accepted"]), C.byref(a) if a is not None else None, _ptr(ws), ws.numel(),

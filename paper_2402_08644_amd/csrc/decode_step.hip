@@ -222,8 +222,8 @@ StepPlan make_plan(const tandem_model* m, int B, int gamma, int64_t T_max, int g
   p.n_keep = S.n_layers;
   p.keep_stride = align256(M * L.d * es);
   p.keep = take(p.keep_stride * S.n_layers);
-  // ints: ncur[gamma][B], block_tokens[B*gamma], draft[B*gamma], verify[B*gamma]
-  p.ints = take(sizeof(int32_t) * 4 * M);
+  // ints: ncur[gamma][B], block_tokens[B*gamma], draft[B*gamma], verify[B*gamma], stop[B]
+  p.ints = take(sizeof(int32_t) * (4 * M + B));  // + stop[B] of the adaptive block length
   // attention scratch: the larger of the draft and the block call
   {
     const int Sd = attn_rows_splits(B, S.Hkv, 1, S.Hq / S.Hkv, T_max, gamma_max, nullptr);
@@ -571,9 +571,11 @@ size_t tandem_decode_step_workspace(const tandem_model* m, int32_t B, int32_t ga
   return total;
 }
 
-int tandem_decode_step(const tandem_model* m, const tandem_state_desc* state, int32_t gamma, int32_t flags,
-                       const int32_t* forced, int32_t* out_tokens, int32_t* n_accepted, const tandem_step_aux* aux,
-                       void* ws, size_t ws_bytes, void* hip_stream) {
+namespace {
+int decode_step_impl(const tandem_model* m, const tandem_state_desc* state, const tandem_router_desc* router,
+                     int32_t gamma, int32_t flags, const int32_t* forced, int32_t* out_tokens, int32_t* n_accepted,
+                     int32_t* n_drafted, float* router_p, const tandem_step_aux* aux, void* ws, size_t ws_bytes,
+                     void* hip_stream) {
   if (!m || !state || !out_tokens || !n_accepted || !ws) return TANDEM_ERR_NULL;
   if (!state->KL || !state->VL || !state->Khat || !state->Vhat || !state->Kcur || !state->Vcur || !state->n ||
       !state->pending)
@@ -607,9 +609,10 @@ int tandem_decode_step(const tandem_model* m, const tandem_state_desc* state, in
   int32_t* block_tokens = ncur + M;                  // [B, nq]
   int32_t* draft = aux && aux->draft ? aux->draft : block_tokens + M;    // [B, gamma]
   int32_t* verify = aux && aux->verify ? aux->verify : block_tokens + 2 * M;  // [B, nq]
+  int32_t* stop = router ? ncur + 4 * (size_t)M : nullptr;                    // [B], see accept_kernel
   void *x = c.at<>(c.plan.x), *qkv = c.at<>(c.plan.qkv), *q = c.at<>(c.plan.q), *att = c.at<>(c.plan.att);
 
-  TRY(launch_prepare_step(state->pending, ncur, B, gamma, c.stream));
+  TRY(launch_prepare_step(state->pending, ncur, stop, B, gamma, c.stream));
 
   // ---- 1. draft: gamma autoregressive runs of M_S --------------------------------------
   for (int r = 0; r < gamma; ++r) {
@@ -651,6 +654,11 @@ int tandem_decode_step(const tandem_model* m, const tandem_state_desc* state, in
     if (aux && aux->logits_S)
       TRY(copy2d((char*)aux->logits_S + (size_t)r * S.vocab * es, (size_t)gamma * S.vocab * es, c.at<>(c.plan.logits),
                  S.vocab * es, S.vocab * es, B, c.stream));
+    // adaptive block length (Sec. 3.1): the router sees this run's distribution; a sequence it stops keeps its
+    // place in the batch (the later runs compute rows that nobody reads) and is verified on its shorter block
+    if (router)
+      TRY(launch_router(router, c.at<>(c.plan.logits), S.emb, B, S.vocab, S.d, r, stop, router_p ? router_p + r : nullptr,
+                        gamma, c.stream));
   }
 
   // ---- 2. verify: M_L in block mode on the first nq of [pending, d_1 .. d_gamma]; 3. new K_hat / V_hat rows
@@ -658,7 +666,28 @@ int tandem_decode_step(const tandem_model* m, const tandem_state_desc* state, in
   TRY(large_block_pass(c, block_tokens, nq, aux, verify));
 
   // ---- 4. accept ------------------------------------------------------------------------
-  return launch_accept(draft, verify, forced, out_tokens, n_accepted, state->n, state->pending, B, gamma, nq, c.stream);
+  return launch_accept(draft, verify, forced, stop, out_tokens, n_accepted, n_drafted, state->n, state->pending, B, gamma,
+                       nq, c.stream);
+}
+}  // namespace
+
+int tandem_decode_step(const tandem_model* m, const tandem_state_desc* state, int32_t gamma, int32_t flags,
+                       const int32_t* forced, int32_t* out_tokens, int32_t* n_accepted, const tandem_step_aux* aux,
+                       void* ws, size_t ws_bytes, void* hip_stream) {
+  return decode_step_impl(m, state, nullptr, gamma, flags, forced, out_tokens, n_accepted, nullptr, nullptr, aux, ws,
+                          ws_bytes, hip_stream);
+}
+
+int tandem_decode_step_adaptive(const tandem_model* m, const tandem_state_desc* state, const tandem_router_desc* router,
+                                int32_t gamma_max, int32_t flags, int32_t* out_tokens, int32_t* n_accepted,
+                                int32_t* n_drafted, float* router_p, const tandem_step_aux* aux, void* ws,
+                                size_t ws_bytes, void* hip_stream) {
+  if (!m || !router) return TANDEM_ERR_NULL;
+  int rc = check_router(router, m->d.S.d);
+  if (rc != TANDEM_OK) return rc;
+  if (router->dtype != m->d.dtype || m->d.S.vocab < router->k) return TANDEM_ERR_UNSUPPORTED;
+  return decode_step_impl(m, state, router, gamma_max, flags, nullptr, out_tokens, n_accepted, n_drafted, router_p, aux,
+                          ws, ws_bytes, hip_stream);
 }
 
 size_t tandem_prefill_workspace(const tandem_model* m, int32_t B, int32_t q_len) {

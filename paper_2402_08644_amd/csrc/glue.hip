@@ -248,9 +248,10 @@ __global__ __launch_bounds__(1024) void finish_scatter_kernel(const float* __res
 }
 
 // block_tokens[b, 0] = pending[b]; block_tokens[b, r] = (forced ? forced : draft)[b, r-1];  ncur[r][b] = r + 1
-__global__ void prepare_step_kernel(const int32_t* pending, int32_t* ncur, int B, int gamma) {
+__global__ void prepare_step_kernel(const int32_t* pending, int32_t* ncur, int32_t* stop, int B, int gamma) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < B * gamma) ncur[i] = i / B + 1;
+  if (stop && i < B) stop[i] = 0;
 }
 // block_tokens[b, r] (r < q): the tokens M_L processes, pending[b] then the first q - 1 of follow[b, :gamma]
 __global__ void block_tokens_kernel(const int32_t* pending, const int32_t* follow, int32_t* block_tokens, int B,
@@ -265,11 +266,16 @@ __global__ void block_tokens_kernel(const int32_t* pending, const int32_t* follo
 // M_L's token there; advance n by the rows that stay valid; the last emitted token becomes pending.
 // draft, forced: [B, gamma]; verify, out_tokens: [B, q] with q = gamma (M_L has not seen the last draft:
 // a fully accepted block emits gamma tokens) or gamma + 1 (free token, Fig. 2: always a + 1 tokens).
-__global__ void accept_kernel(const int32_t* draft, const int32_t* verify, const int32_t* forced, int32_t* out_tokens,
-                              int32_t* n_accepted, int32_t* n, int32_t* pending, int B, int gamma, int q) {
+// With the adaptive block length (Sec. 3.1) sequence b drafted only gb = stop[b] tokens (0 = all gamma): M_L's rows
+// beyond them are ignored, and gb takes gamma's place in the rule above.
+__global__ void accept_kernel(const int32_t* draft, const int32_t* verify, const int32_t* forced, const int32_t* stop,
+                              int32_t* out_tokens, int32_t* n_accepted, int32_t* n_drafted, int32_t* n,
+                              int32_t* pending, int B, int gamma, int q) {
   const int b = blockIdx.x * blockDim.x + threadIdx.x;
   if (b >= B) return;
   const bool free_token = q > gamma;
+  const int gb = stop && stop[b] > 0 && stop[b] < gamma ? stop[b] : gamma;
+  if (n_drafted) n_drafted[b] = gb;
   int a = 0;
   if (forced) {
     a = gamma;
@@ -278,8 +284,8 @@ __global__ void accept_kernel(const int32_t* draft, const int32_t* verify, const
     pending[b] = out_tokens[b * q + q - 1];
     n[b] += q;
   } else {
-    while (a < gamma && draft[b * gamma + a] == verify[b * q + a]) ++a;
-    const int emit = (a < gamma || free_token) ? a + 1 : gamma;
+    while (a < gb && draft[b * gamma + a] == verify[b * q + a]) ++a;
+    const int emit = (a < gb || free_token) ? a + 1 : gb;
     for (int r = 0; r < q; ++r) {
       int t = -1;
       if (r < a) t = draft[b * gamma + r];
@@ -379,8 +385,8 @@ int launch_argmax(const void* logits, int rows, int vocab, int32_t* out, int64_t
   return hip_ok(hipGetLastError());
 }
 
-int launch_prepare_step(const int32_t* pending, int32_t* ncur, int B, int gamma, hipStream_t st) {
-  hipLaunchKernelGGL(prepare_step_kernel, dim3((B * gamma + 255) / 256), dim3(256), 0, st, pending, ncur, B, gamma);
+int launch_prepare_step(const int32_t* pending, int32_t* ncur, int32_t* stop, int B, int gamma, hipStream_t st) {
+  hipLaunchKernelGGL(prepare_step_kernel, dim3((B * gamma + 255) / 256), dim3(256), 0, st, pending, ncur, stop, B, gamma);
   return hip_ok(hipGetLastError());
 }
 
@@ -391,9 +397,10 @@ int launch_block_tokens(const int32_t* pending, const int32_t* follow, int32_t* 
   return hip_ok(hipGetLastError());
 }
 
-int launch_accept(const int32_t* draft, const int32_t* verify, const int32_t* forced, int32_t* out_tokens,
-                  int32_t* n_accepted, int32_t* n, int32_t* pending, int B, int gamma, int q, hipStream_t st) {
-  hipLaunchKernelGGL(accept_kernel, dim3((B + 63) / 64), dim3(64), 0, st, draft, verify, forced, out_tokens, n_accepted,
-                     n, pending, B, gamma, q);
+int launch_accept(const int32_t* draft, const int32_t* verify, const int32_t* forced, const int32_t* stop,
+                  int32_t* out_tokens, int32_t* n_accepted, int32_t* n_drafted, int32_t* n, int32_t* pending, int B,
+                  int gamma, int q, hipStream_t st) {
+  hipLaunchKernelGGL(accept_kernel, dim3((B + 63) / 64), dim3(64), 0, st, draft, verify, forced, stop, out_tokens,
+                     n_accepted, n_drafted, n, pending, B, gamma, q);
   return hip_ok(hipGetLastError());
 }

@@ -226,15 +226,17 @@ def tiny_tandem(seed=0, dtype="f32"):
     )
 
 
-def router_weights(seed, k, d, hidden, dtype="f32", w_std=0.05):
+def router_weights(seed, k, d, hidden, dtype="f32", w_std=0.05, out_std=None):
     """Random-init router MLP of the adaptive block length: input 1 + k + k*d features, `hidden` units, one output
-    (weights N(0, w_std); the trained router of the paper is not available)."""
+    (first layer N(0, w_std), output layer N(0, out_std), default 10 w_std; the trained router of the paper is
+    not available)."""
     rng = np.random.default_rng(seed)
+    out_std = 10 * w_std if out_std is None else out_std
     return {
         "k": k,
         "W1": normal(rng, (hidden, 1 + k + k * d), w_std, dtype),
         "b1": normal(rng, (hidden,), w_std, dtype),
-        "w2": normal(rng, (hidden,), 10 * w_std, dtype),
+        "w2": normal(rng, (hidden,), out_std, dtype),
         "b2": normal(rng, (1,), w_std, dtype),
     }
 
