@@ -393,6 +393,53 @@ def run_prefill_workload(torch, binding, inputs, args):
     }
 
 
+def run_score_workload(torch, binding, inputs, args):
+    """One tandem_score call: the small model teacher-forced on 32 tokens of each of 32 sequences at context 4096 (C3
+    pair; the large model's K_hat / V_hat rows are already in the state)."""
+    cfg = dict(C3)
+    B, q, n0, gamma = cfg["B"], 32, 4096, cfg["gamma"]
+    W = device_tandem_weights(inputs, cfg, 3)
+    model = binding.TandemModel(W, pack_weights=not args.plain_weights)
+    del W
+    k = [5]
+
+    def fill(*shape):
+        k[0] += 1
+        return inputs.device_normal(shape, k[0], 1.0)
+
+    state = binding.TandemState(model, B, cfg["ctx"], 4, fill=fill)
+    S = cfg["small"]
+    ko = [fill(B, S["Hkv"], cfg["ctx"], S["dh"]) for _ in range(S["n_layers"])]
+    vo = [fill(B, S["Hkv"], cfg["ctx"], S["dh"]) for _ in range(S["n_layers"])]
+    toks = torch.randint(0, cfg["vocab"], (B, q), dtype=torch.int32, device="cuda", generator=torch.Generator("cuda").manual_seed(9))
+    pos = torch.full((B,), n0, dtype=torch.int32, device="cuda")
+    ws = torch.empty(binding.tandem_score_workspace(model, B, q), dtype=torch.uint8, device="cuda")
+
+    def call(_i):
+        binding.tandem_score(model, state, ko, vo, pos, toks, gamma, ws=ws)
+
+    torch.cuda.synchronize()
+    ms = _time_calls(torch, call, 1, args.steps, args.warmup, use_graph=not args.no_graph)
+    M = B * q
+    # per layer the visible K_hat / V_hat and own rows cross HBM once; the weights are small (25 MB per layer)
+    kv_bytes = S["n_layers"] * B * S["Hkv"] * (n0 + q) * S["dh"] * 2 * 2
+    w_bytes = 2 * (S["n_layers"] * ((S["Hq"] + 2 * S["Hkv"]) * S["dh"] * S["d"] + S["d"] * S["Hq"] * S["dh"] + 2 * S["d"] * S["d_ff"])
+                   + 2 * cfg["vocab"] * S["d"])
+    gbs = (kv_bytes + w_bytes) / (ms * 1e-3) / 1e9
+    return {
+        "metric": "Tandem teacher-forced small-model scoring tokens/sec (tandem_score, 32 tokens x 32 sequences per call)",
+        "value": M / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "c3_score: tandem_score bf16 B=32, 32 positions per sequence at context 4096, gamma=4, C3 small "
+                               "model (8 layers, all-positions mixed attention, head over 32768 tokens)",
+                   "kv_GB": kv_bytes / 1e9, "weight_GB": w_bytes / 1e9},
+        "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
+                     "traffic": None},
+        "cpu_baseline": None,
+    }
+
+
 def cpu_step_estimate(torch, inputs, cfg, state, model):
     """Oracle pieces of one step timed on sampled slices (one sequence / one layer each), extrapolated by
     the layer, run and batch counts.  The full fp64 step is ~2 TFLOP and is not run."""
@@ -646,7 +693,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="c3_step", choices=sorted(WORKLOADS) + sorted(PROJECT_WORKLOADS) + ["c3_step", "c3_prefill"])
+    ap.add_argument("--workload", default="c3_step", choices=sorted(WORKLOADS) + sorted(PROJECT_WORKLOADS) + ["c3_step", "c3_prefill", "c3_score"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--plain-weights", action="store_true",
@@ -688,6 +735,9 @@ def main():
     if args.workload == "c3_prefill":
         runner = run_prefill_workload
         args.steps = min(args.steps, 10)
+    if args.workload == "c3_score":
+        runner = run_score_workload
+        args.steps = min(args.steps, 20)
     if args.workload in ("project_m4096", "project_m65536"):
         args.steps = min(args.steps, 20)
     line = runner(torch, binding, inputs, args)

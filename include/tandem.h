@@ -308,6 +308,24 @@ size_t tandem_prefill_workspace(const tandem_model *m, int32_t B, int32_t q_len)
 int tandem_prefill(const tandem_model *m, const tandem_state_desc *state, const int32_t *tokens, int32_t q_len,
                    int32_t flags, void *x_large, void *ws, size_t ws_bytes, void *hip_stream);
 
+/* Teacher-forced pass of the small model over known tokens (Eq. (2) at every position; Sec. 3 "Training": the form
+ * that training and the evaluation of the Tandem model's own predictions use).  For every sequence, M_S processes
+ * tokens[b, 0:q_len) at positions pos[b] .. pos[b] + q_len - 1: every layer appends its own K/V rows to
+ * k_own[j] / v_own[j] at those positions and attends with tandem_mixed_attn (Khat/Vhat rows below the query's block
+ * boundary floor(i / gamma) * gamma, own rows from there to i).  The Khat/Vhat rows of all completed blocks below
+ * pos[b] + q_len must already be in the state (tandem_prefill over the same tokens), and the own rows of the current
+ * block below pos[b] in k_own / v_own (earlier calls).  The state is only read.
+ *   k_own, v_own  host arrays [S.n_layers] of device [B, S.Hkv, T_max, S.dh] (caller-owned, indexed by position)
+ *   pos           device int32 [B], requires pos[b] + q_len <= T_max
+ *   tokens        device int32 [B, q_len];  1 <= q_len <= TANDEM_MAX_QLEN, gamma >= 1
+ *   greedy        optional device int32 [B, q_len]: M_S's greedy prediction of the token after each position
+ *   logits        optional device [B, q_len, vocab];  y_small optional device [B, q_len, S.d]: y^(L_S)
+ * ws: at least tandem_score_workspace(m, B, q_len) bytes. */
+size_t tandem_score_workspace(const tandem_model *m, int32_t B, int32_t q_len);
+int tandem_score(const tandem_model *m, const tandem_state_desc *state, void *const *k_own, void *const *v_own,
+                 const int32_t *pos, const int32_t *tokens, int32_t q_len, int32_t gamma, int32_t *greedy, void *logits,
+                 void *y_small, void *ws, size_t ws_bytes, void *hip_stream);
+
 const char *tandem_status_string(int status);
 
 #pragma GCC visibility pop

@@ -95,6 +95,7 @@ EXPORTS = (
     "tandem_model_create", "tandem_model_destroy", "tandem_decode_step_workspace", "tandem_decode_step",
     "tandem_prefill_workspace", "tandem_prefill",
     "tandem_router_eval", "tandem_decode_step_adaptive",
+    "tandem_score_workspace", "tandem_score",
 )
 
 _lib = None
@@ -113,6 +114,11 @@ def lib():
     L.tandem_status_string.argtypes = [C.c_int]
     L.tandem_project_workspace.restype = sz
     L.tandem_project_workspace.argtypes = [C.POINTER(FFDesc), i64]
+    L.tandem_score_workspace.restype = sz
+    L.tandem_score_workspace.argtypes = [vp, i32, i32]
+    L.tandem_score.restype = C.c_int
+    L.tandem_score.argtypes = [vp, C.POINTER(StateDesc), C.POINTER(vp), C.POINTER(vp), vp, vp, i32, i32, vp, vp, vp, vp,
+                               sz, vp]
     L.tandem_router_eval.restype = C.c_int
     L.tandem_router_eval.argtypes = [C.POINTER(RouterDesc), vp, vp, i32, i32, i32, vp, vp]
     L.tandem_decode_step_adaptive.restype = C.c_int
@@ -584,6 +590,56 @@ def tandem_decode_step(model: TandemModel, state: TandemState, gamma: int, force
                                   _ptr(out["n_accepted"]), C.byref(a) if a is not None else None, _ptr(ws), ws.numel(),
                                   _stream(stream))
     _check(rc, "tandem_decode_step")
+    return out
+
+
+def tandem_score_workspace(model: TandemModel, B: int, q_len: int) -> int:
+    return int(lib().tandem_score_workspace(model.handle, B, q_len))
+
+
+def own_caches(model: TandemModel, state: TandemState):
+    """Zeroed position-indexed caches for the small model's own K/V rows (tandem_score): two lists over its layers."""
+    import torch
+
+    S = model.S
+    mk = lambda: [torch.zeros((state.B, S.Hkv, state.T_max, S.dh), dtype=model.dtype, device=state.n.device)
+                  for _ in range(S.n_layers)]
+    return mk(), mk()
+
+
+def tandem_score(model: TandemModel, state: TandemState, k_own, v_own, pos, tokens, gamma, logits=False, y_small=False,
+                 ws=None, stream=None):
+    """Teacher-forced small-model pass over tokens [B, q_len] (int32) at positions pos[b].. (int32 [B]); k_own, v_own
+    from own_caches().  Returns {"greedy" [B,q_len] int32, optionally "logits" [B,q_len,vocab], "y_small" [B,q_len,d]}."""
+    import torch
+
+    B, q_len = tokens.shape
+    _need(tokens, (state.B, q_len), "tokens")
+    _need(pos, (state.B,), "pos")
+    if tokens.dtype != torch.int32 or pos.dtype != torch.int32:
+        raise TypeError("tokens and pos must be int32")
+    S = model.S
+    for ts, nm in ((k_own, "k_own"), (v_own, "v_own")):
+        if len(ts) != S.n_layers:
+            raise ValueError(f"{nm}: one tensor per small layer")
+        for t in ts:
+            _need(t, (B, S.Hkv, state.T_max, S.dh), nm)
+            if t.dtype != model.dtype:
+                raise TypeError(f"{nm}: model dtype expected")
+    dev = state.n.device
+    out = {"greedy": torch.empty((B, q_len), dtype=torch.int32, device=dev)}
+    if logits:
+        out["logits"] = torch.empty((B, q_len, S.vocab), dtype=model.dtype, device=dev)
+    if y_small:
+        out["y_small"] = torch.empty((B, q_len, S.d), dtype=model.dtype, device=dev)
+    if ws is None:
+        ws = _workspace(tandem_score_workspace(model, B, q_len), state.n)
+    ka = (C.c_void_p * S.n_layers)(*[t.data_ptr() for t in k_own])
+    va = (C.c_void_p * S.n_layers)(*[t.data_ptr() for t in v_own])
+    rc = lib().tandem_score(model.handle, C.byref(state.desc), ka, va, _ptr(pos), _ptr(tokens), q_len, int(gamma),
+                            _ptr(out["greedy"]), _ptr(out.get("logits")), _ptr(out.get("y_small")), _ptr(ws), ws.numel(),
+                            _stream(stream))
+    _check(rc, "tandem_score")
     return out
 
 

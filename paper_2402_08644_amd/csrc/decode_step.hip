@@ -193,7 +193,8 @@ struct StepPlan {
   bool fused;  // bf16 path with deferred GEMM epilogues finished by fused row kernels
 };
 
-StepPlan make_plan(const tandem_model* m, int B, int gamma, int64_t T_max, int gamma_max) {
+// score: the small model also runs on all B * gamma rows (teacher-forced pass), with the all-positions attention
+StepPlan make_plan(const tandem_model* m, int B, int gamma, int64_t T_max, int gamma_max, bool score = false) {
   const tandem_decoder_desc &L = m->d.L, &S = m->d.S;
   const size_t es = elsize(m->d.dtype);
   const size_t M = (size_t)B * gamma;
@@ -233,6 +234,10 @@ StepPlan make_plan(const tandem_model* m, int B, int gamma, int64_t T_max, int g
     const size_t rows = (size_t)B * gamma * L.Hq;
     size_t b = Sb > 1 ? align256(rows * Sb * 2 * 4) + rows * Sb * L.dh * 4 : 0;
     p.attn_ws_bytes = maxz(a, b);
+    if (score) {
+      tandem_attn_desc sd{B, S.Hq, S.Hkv, S.dh, T_max, 0, 1.f, m->d.dtype};
+      p.attn_ws_bytes = maxz(p.attn_ws_bytes, tandem_mixed_attn_workspace(&sd, gamma));
+    }
     p.attn_ws = take(p.attn_ws_bytes);
   }
   {
@@ -246,7 +251,7 @@ StepPlan make_plan(const tandem_model* m, int B, int gamma, int64_t T_max, int g
       need(rows, D.d, D.d_ff);
       need(rows, D.vocab, D.d);
     };
-    need_decoder(S, (size_t)B);
+    need_decoder(S, score ? M : (size_t)B);
     need_decoder(L, M);
     need(M, 2 * S.Hkv * S.dh, S.d);
     // deferred epilogues: every product of the step must be able to leave partials
@@ -260,7 +265,7 @@ StepPlan make_plan(const tandem_model* m, int B, int gamma, int64_t T_max, int g
       dneed(rows, D.d, D.Hq * D.dh);
       dneed(rows, D.d, D.d_ff);
     };
-    dneed_decoder(S, (size_t)B);
+    dneed_decoder(S, score ? M : (size_t)B);
     dneed_decoder(L, M);
     dneed(M, 2 * S.Hkv * S.dh, S.d);
     for (int j = 0; j < S.n_layers; ++j) {
@@ -734,6 +739,68 @@ int tandem_prefill(const tandem_model* m, const tandem_state_desc* state, const 
     TRY(head(c, L, B, state->pending, 1));
   }
   return launch_advance(state->n, B, q_len, c.stream);
+}
+
+size_t tandem_score_workspace(const tandem_model* m, int32_t B, int32_t q_len) {
+  if (!m || B < 1 || q_len < 1 || q_len > TANDEM_MAX_QLEN) return 0;
+  return make_plan(m, B, q_len, (int64_t)1 << 40, 1, true).total;
+}
+
+int tandem_score(const tandem_model* m, const tandem_state_desc* state, void* const* k_own, void* const* v_own,
+                 const int32_t* pos, const int32_t* tokens, int32_t q_len, int32_t gamma, int32_t* greedy, void* logits,
+                 void* y_small, void* ws, size_t ws_bytes, void* hip_stream) {
+  if (!m || !state || !k_own || !v_own || !pos || !tokens || !ws) return TANDEM_ERR_NULL;
+  if (!state->Khat || !state->Vhat) return TANDEM_ERR_NULL;
+  const tandem_decoder_desc& S = m->d.S;
+  const int B = state->B;
+  if (B < 1 || B > 65535 || state->T_max < 1) return TANDEM_ERR_SHAPE;
+  if (q_len < 1 || q_len > TANDEM_MAX_QLEN || q_len > state->T_max || gamma < 1) return TANDEM_ERR_SHAPE;
+  for (int j = 0; j < S.n_layers; ++j)
+    if (!state->Khat[j] || !state->Vhat[j] || !k_own[j] || !v_own[j]) return TANDEM_ERR_NULL;
+  Ctx c;
+  c.m = m;
+  c.st = state;
+  c.plan = make_plan(m, B, q_len, state->T_max, state->gamma_max > 0 ? state->gamma_max : 1, true);
+  if (c.plan.total > ws_bytes) return TANDEM_ERR_WORKSPACE;
+  c.ws = (char*)ws;
+  c.stream = (hipStream_t)hip_stream;
+  c.dtype = m->d.dtype;
+  c.eps = m->d.rms_eps;
+  const size_t es = elsize(c.dtype);
+  const int M = B * q_len;
+  void *x = c.at<>(c.plan.x), *qkv = c.at<>(c.plan.qkv), *q = c.at<>(c.plan.q), *att = c.at<>(c.plan.att);
+  int32_t* tok_scratch = c.at<int32_t>(c.plan.ints);  // greedy tokens when the caller does not want them
+  tandem_attn_desc ad{B, S.Hq, S.Hkv, S.dh, state->T_max, 0, 1.0f / sqrtf((float)S.dh), c.dtype};
+
+  TRY(launch_embed(S.emb, tokens, 1, x, M, S.d, S.vocab, c.dtype, c.stream));
+  if (c.plan.fused) TRY(launch_rmsnorm(x, S.layers[0].g_attn, c.at<>(c.plan.xn), M, S.d, c.eps, c.dtype, c.stream));
+  for (int j = 0; j < S.n_layers; ++j) {
+    auto attn_only = [&]() -> int {
+      return tandem_mixed_attn(&ad, q, state->Khat[j], state->Vhat[j], k_own[j], v_own[j], pos, q_len, gamma, att,
+                               c.at<>(c.plan.attn_ws), c.plan.attn_ws_bytes, c.stream);
+    };
+    if (c.plan.fused) {
+      auto finish_qkv = [&](const float* part, int splits) -> int {
+        return launch_finish_scatter(part, splits, q, k_own[j], v_own[j], pos, 0, M, q_len, S.Hq, S.Hkv, S.dh,
+                                     state->T_max, S.Hq * S.dh, (S.Hq + 2 * S.Hkv) * S.dh, c.dtype, c.stream);
+      };
+      const void* g_next = j + 1 < S.n_layers ? S.layers[j + 1].g_attn : S.g_final;
+      TRY(decoder_layer_fused(c, S, S.layers[j], M, g_next, finish_qkv, attn_only));
+    } else {
+      auto attn = [&]() -> int {
+        TRY(launch_scatter_qkv(qkv, q, k_own[j], v_own[j], pos, 0, M, q_len, S.Hq, S.Hkv, S.dh, state->T_max, 0,
+                               S.Hq * S.dh, (S.Hq + 2 * S.Hkv) * S.dh, c.dtype, c.stream));
+        return attn_only();
+      };
+      TRY(decoder_layer(c, S, S.layers[j], M, attn));
+    }
+  }
+  if (y_small) TRY(hip_ok(hipMemcpyAsync(y_small, x, (size_t)M * S.d * es, hipMemcpyDeviceToDevice, c.stream)));
+  int32_t* tok = greedy ? greedy : tok_scratch;
+  TRY(c.plan.fused ? head_normed(c, S, M, tok, 1) : head(c, S, M, tok, 1));
+  if (logits)
+    TRY(hip_ok(hipMemcpyAsync(logits, c.at<>(c.plan.logits), (size_t)M * S.vocab * es, hipMemcpyDeviceToDevice, c.stream)));
+  return TANDEM_OK;
 }
 
 }  // extern "C"
