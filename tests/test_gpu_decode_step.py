@@ -427,3 +427,58 @@ def test_decode_step_error_codes(tb):
     h = C.c_void_p()
     assert L.tandem_model_create(None, C.byref(h)) == binding.ERR_NULL
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("adaptive", [False, True])
+def test_decode_step_graph_replays_equal_eager(tb, adaptive):
+    """bench.py times a captured HIP graph of the step: every replay (with the program's own eager work - state
+    resets, copies, synchronisation - between the replays) must give exactly what the eager call gives."""
+    torch, binding = tb
+    B, gamma, T_max = 5, 4, 96
+    W = small_bf16_pair(97)
+    T = inputs.as_f64(W)
+    n = [int(v) for v in np.random.default_rng(98).integers(0, T_max - gamma - 1, B)]
+    pending = [int(v) for v in inputs.token_ids(99, (B,), 512)]
+    _, host = oracle_state_from(T, B, T_max, 100, n, pending, "bf16")
+    model = binding.TandemModel(W)
+    gst = upload_state(tb, model, B, T_max, gamma, host, n, pending)
+    n_dev, p_dev = gst.n.clone(), gst.pending.clone()
+    router = None
+    if adaptive:
+        R = inputs.router_weights(5, 2, 256, 16, dtype="bf16", w_std=0.1, out_std=0.5)
+        router = {k: (v if k == "k" else v.to_torch()) for k, v in R.items()}
+    ws = binding.workspace(binding.tandem_decode_step_workspace(model, B, gamma))
+    out = binding.tandem_decode_step(model, gst, gamma, aux=True, ws=ws, free_token=True, router=router, tau=0.5)
+    torch.cuda.synchronize()
+    eager = {k: v.clone() for k, v in out.items()}
+    eager_n, eager_p = gst.n.clone(), gst.pending.clone()
+    eager_k = gst.Khat[1].clone()
+
+    def reset():
+        gst.n.copy_(n_dev)
+        gst.pending.copy_(p_dev)
+        for v in out.values():
+            v.zero_()
+
+    reset()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        binding.tandem_decode_step(model, gst, gamma, ws=ws, out=out, free_token=True, router=router, tau=0.5)  # warm-up
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    reset()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        binding.tandem_decode_step(model, gst, gamma, ws=ws, out=out, free_token=True, router=router, tau=0.5)
+    for replay in range(4):
+        reset()
+        ws.zero_()  # nothing may depend on what an earlier replay left in the workspace
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for k in eager:
+            assert torch.equal(out[k].view(torch.int16) if out[k].dtype == torch.bfloat16 else out[k], eager[k].view(torch.int16) if eager[k].dtype == torch.bfloat16 else eager[k]), (replay, k)
+        assert torch.equal(gst.n, eager_n) and torch.equal(gst.pending, eager_p), replay
+        assert torch.equal(gst.Khat[1].view(torch.int16), eager_k.view(torch.int16)), replay
