@@ -130,6 +130,15 @@ int tandem_block_attn_shared(const tandem_attn_desc *a, int32_t samples, int64_t
                              const void *v_own, const int32_t *n_own, int32_t q_len, void *out, void *ws,
                              size_t ws_bytes, void *hip_stream);
 
+/* Deep Tandem's large-model attention (Eq. (3)): the query at position i = n_prefix[b] + r (0-indexed) attends only
+ * the rows of the blocks completed before its own block, cache rows 0 .. floor(i / gamma) * gamma - 1 (the paper's
+ * keys x_{<= k gamma}, k = ceil((i - gamma) / gamma), in 1-indexed positions); queries of the first block see no key
+ * and give zeros (the paper does not say).  Shapes, limits and workspace as tandem_block_attn; gamma >= 1. */
+size_t tandem_block_prefix_attn_workspace(const tandem_attn_desc *a, int32_t q_len);
+int tandem_block_prefix_attn(const tandem_attn_desc *a, const void *q, const void *k_cache, const void *v_cache,
+                             const int32_t *n_prefix, int32_t q_len, int32_t gamma, void *out, void *ws, size_t ws_bytes,
+                             void *hip_stream);
+
 /* The small model's attention at every position of a known sequence (Eq. (2), second line, with the block
  * boundary of each query's own position; Sec. 3 "Training": the form used in training and in teacher-forced
  * scoring, where M_S processes all tokens and, inside a block, sees its own rows instead of M_L's).  One call

@@ -558,6 +558,33 @@ def mixed_attn(Q, Khat, Vhat, Kown, Vown, n, gamma, scale):
 
 
 # ----------------------------------------------------------------------------
+# a3'  Deep Tandem's large-model attention (Eq. (3)): the query at position i attends only the positions of the
+#      blocks completed before its own block, keys x_{<= k gamma} with k = ceil((i - gamma) / gamma) in the
+#      paper's 1-indexed positions - 0-indexed: keys j < floor(i / gamma) * gamma.  Queries of the first block see
+#      no key at all; their output is defined as zero here (the paper does not say).
+# ----------------------------------------------------------------------------
+def block_prefix_attn(Q, Kc, Vc, n, gamma, scale):
+    """Q [B, q_len, Hq, dh] for positions n[b] .. n[b] + q_len - 1; Kc, Vc [B, Hkv, T, dh] indexed by position."""
+    Q = np.asarray(Q, F64)
+    B, q_len, Hq, dh = Q.shape
+    Hkv = np.asarray(Kc).shape[1]
+    G = Hq // Hkv
+    out = np.zeros_like(Q)
+    for b in range(B):
+        for r in range(q_len):
+            i1 = int(n[b]) + r + 1                     # the paper's 1-indexed position
+            k = -((-(i1 - gamma)) // gamma)            # ceil((i - gamma) / gamma)
+            visible = max(k, 0) * gamma                # keys x_1 .. x_{k gamma}
+            if visible == 0:
+                continue
+            for h in range(Hq):
+                kv = h // G
+                out[b, r, h] = attention_one(Q[b, r, h], np.asarray(Kc, F64)[b, kv, :visible],
+                                             np.asarray(Vc, F64)[b, kv, :visible], scale)
+    return out
+
+
+# ----------------------------------------------------------------------------
 # a5  split-K re-association of the softmax (exact in real arithmetic):
 #     per split (m_s, l_s, O_s) with O_s un-normalised; merged in split order.
 # ----------------------------------------------------------------------------

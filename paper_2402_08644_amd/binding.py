@@ -92,6 +92,7 @@ EXPORTS = (
     "tandem_project", "tandem_block_attn", "tandem_draft_attn",
     "tandem_block_attn_shared_workspace", "tandem_block_attn_shared",
     "tandem_mixed_attn_workspace", "tandem_mixed_attn",
+    "tandem_block_prefix_attn_workspace", "tandem_block_prefix_attn",
     "tandem_model_create", "tandem_model_destroy", "tandem_decode_step_workspace", "tandem_decode_step",
     "tandem_prefill_workspace", "tandem_prefill",
     "tandem_router_eval", "tandem_decode_step_adaptive",
@@ -124,6 +125,10 @@ def lib():
     L.tandem_decode_step_adaptive.restype = C.c_int
     L.tandem_decode_step_adaptive.argtypes = [vp, C.POINTER(StateDesc), C.POINTER(RouterDesc), i32, i32, vp, vp, vp, vp,
                                               C.POINTER(StepAux), vp, sz, vp]
+    L.tandem_block_prefix_attn_workspace.restype = sz
+    L.tandem_block_prefix_attn_workspace.argtypes = [C.POINTER(AttnDesc), i32]
+    L.tandem_block_prefix_attn.restype = C.c_int
+    L.tandem_block_prefix_attn.argtypes = [C.POINTER(AttnDesc), vp, vp, vp, vp, i32, i32, vp, vp, sz, vp]
     L.tandem_mixed_attn_workspace.restype = sz
     L.tandem_mixed_attn_workspace.argtypes = [C.POINTER(AttnDesc), i32]
     L.tandem_mixed_attn.restype = C.c_int
@@ -315,6 +320,31 @@ def tandem_block_attn_shared(q, k_shared, v_shared, n_shared, k_own, v_own, n_ow
                                         _ptr(k_own), _ptr(v_own), _ptr(n_own), q_len, _ptr(out), _ptr(ws), ws.numel(),
                                         _stream(stream))
     _check(rc, "tandem_block_attn_shared")
+    return out
+
+
+def tandem_block_prefix_attn(q, k_cache, v_cache, n_prefix, gamma, scale=None, out=None, ws=None, stream=None):
+    """Deep Tandem's large-model attention: q [B,q_len,Hq,dh]; k_cache,v_cache [B,Hkv,T_max,dh]; n_prefix int32 [B]."""
+    import torch
+
+    B, q_len, Hq, dh = q.shape
+    _, Hkv, T_max, _ = k_cache.shape
+    _need(q, (B, q_len, Hq, dh), "q")
+    _need(k_cache, (B, Hkv, T_max, dh), "k_cache")
+    _need(v_cache, (B, Hkv, T_max, dh), "v_cache")
+    _need(n_prefix, (B,), "n_prefix")
+    if n_prefix.dtype != torch.int32:
+        raise TypeError("n_prefix must be int32")
+    if k_cache.dtype != q.dtype or v_cache.dtype != q.dtype:
+        raise TypeError("q / K / V dtypes differ")
+    d = attn_desc(B, Hq, Hkv, dh, T_max, 0, (1.0 / math.sqrt(dh)) if scale is None else scale, _dtype_code(q))
+    if out is None:
+        out = torch.empty_like(q)
+    if ws is None:
+        ws = _workspace(int(lib().tandem_block_prefix_attn_workspace(C.byref(d), q_len)), q)
+    rc = lib().tandem_block_prefix_attn(C.byref(d), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(n_prefix), q_len,
+                                        int(gamma), _ptr(out), _ptr(ws), ws.numel(), _stream(stream))
+    _check(rc, "tandem_block_prefix_attn")
     return out
 
 

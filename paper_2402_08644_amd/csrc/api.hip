@@ -215,6 +215,43 @@ int tandem_block_attn_shared(const tandem_attn_desc* a, int32_t samples, int64_t
   return launch_attn_combine(x.part_ml, x.part_o, out, (int)rows, S, a->dh, a->dtype, st);
 }
 
+size_t tandem_block_prefix_attn_workspace(const tandem_attn_desc* a, int32_t q_len) {
+  return tandem_block_attn_workspace(a, q_len);
+}
+
+int tandem_block_prefix_attn(const tandem_attn_desc* a, const void* q, const void* k_cache, const void* v_cache,
+                             const int32_t* n_prefix, int32_t q_len, int32_t gamma, void* out, void* ws, size_t ws_bytes,
+                             void* hip_stream) {
+  int rc = check_attn_desc(a);
+  if (rc != TANDEM_OK) return rc;
+  if (!q || !k_cache || !v_cache || !n_prefix || !out) return TANDEM_ERR_NULL;
+  if (q_len < 1 || q_len > TANDEM_MAX_QLEN || a->T_max < q_len || gamma < 1) return TANDEM_ERR_SHAPE;
+  const size_t need = tandem_block_prefix_attn_workspace(a, q_len);
+  if (need > 0 && !ws) return TANDEM_ERR_NULL;
+  if (ws_bytes < need) return TANDEM_ERR_WORKSPACE;
+  AttnArgs x{};
+  x.q = q;
+  x.kA = k_cache;
+  x.vA = v_cache;
+  x.nA = n_prefix;
+  x.B = a->B;
+  x.Hq = a->Hq;
+  x.Hkv = a->Hkv;
+  x.dh = a->dh;
+  x.q_len = q_len;
+  x.T_max = a->T_max;
+  x.scale = a->scale;
+  x.dtype = a->dtype;
+  x.out = out;
+  x.gamma = gamma;
+  const bool mfma = block_uses_mfma(a);
+  x.mixed = mfma ? 1 : 3;  // the first key segment of the all-positions attention, alone
+  x.S = mfma ? attn_block_splits(a->B, a->Hkv, q_len, a->Hq / a->Hkv, a->T_max, &x.wide)
+             : attn_rows_splits(a->B, a->Hkv, q_len, a->Hq / a->Hkv, a->T_max, 0, &x.wide);
+  if (x.S > 1) carve(ws, (size_t)a->B * q_len * a->Hq, x.S, &x.part_ml, &x.part_o);
+  return mfma ? launch_attn_block(x, (hipStream_t)hip_stream) : launch_attn_rows(x, (hipStream_t)hip_stream);
+}
+
 size_t tandem_mixed_attn_workspace(const tandem_attn_desc* a, int32_t q_len) {
   if (check_attn_desc(a) != TANDEM_OK || q_len < 1 || q_len > TANDEM_MAX_QLEN) return 0;
   const size_t rows = (size_t)a->B * q_len * a->Hq;

@@ -50,7 +50,7 @@ __global__ __launch_bounds__(64 * NW) void attn_rows_kernel(RowsParams p) {
     nA = nA < 0 ? 0 : (nA > nmax ? nmax : nA);
     const long long i = nA + r;
     nA = i / p.mixed_gamma * p.mixed_gamma;
-    nB = i + 1 - nA;
+    nB = p.kB ? i + 1 - nA : 0;  // without source B: only the rows below the block boundary (Eq. (3))
     strideB = p.T_max;
   } else {
     if (p.causal) nA += r + 1;

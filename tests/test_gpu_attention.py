@@ -467,6 +467,33 @@ def test_mixed_attn_full_size_sampled(tb):
         assert_rows_close(f(out[b, r, h])[None], want[None], what=f"mixed sampled row {b,r,h}")
 
 
+@pytest.mark.parametrize(
+    "B,q_len,Hq,Hkv,dh,T_max,n,gamma,dtype",
+    [
+        (3, 8, 8, 2, 128, 300, [292, 100, 0], 4, "bf16"),   # 32 rows; the third sequence's first block sees nothing
+        (1, 32, 8, 2, 128, 1300, [1200], 8, "bf16"),        # 128 rows: the row-split kernel
+        (2, 5, 4, 4, 128, 530, [525, 2], 3, "bf16"),
+        (2, 7, 4, 2, 64, 150, [143, 1], 4, "bf16"),         # generic path
+        (2, 6, 4, 4, 64, 130, [124, 0], 2, "f32"),
+    ],
+)
+def test_block_prefix_attn_parity_small(tb, B, q_len, Hq, Hkv, dh, T_max, n, gamma, dtype):
+    torch, binding = tb
+    case = inputs.block_attn_case(51, B, q_len, Hq, Hkv, dh, T_max, n, dtype=dtype)
+    out = binding.tandem_block_prefix_attn(case["q"].to_torch(), case["k"].to_torch(), case["v"].to_torch(),
+                                           torch.from_numpy(case["n"]).cuda(), gamma, scale=case["scale"])
+    torch.cuda.synchronize()
+    want = orc.block_prefix_attn(case["q"].f64, case["k"].f64, case["v"].f64, case["n"], gamma, case["scale"])
+    got = inputs.torch_to_f64(out)
+    for b in range(B):
+        for r in range(q_len):
+            if (case["n"][b] + r) // gamma == 0:
+                assert (got[b, r] == 0).all()   # no visible key: exactly zero
+    seen = np.abs(want).reshape(B * q_len, -1).max(1) > 0
+    e = assert_rows_close(got.reshape(B * q_len, Hq, dh)[seen], want.reshape(B * q_len, Hq, dh)[seen], what="prefix")
+    print(f"prefix small {B,q_len,Hq,Hkv,dh,T_max,gamma,dtype}: max rel err {e[0]:.2e}")
+
+
 def test_mixed_attn_error_codes(tb):
     torch, binding = tb
     import ctypes as C

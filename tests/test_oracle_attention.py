@@ -348,3 +348,33 @@ def test_mixed_attn_is_the_attention_inside_tandem_forward():
         T1["S"] = dict(MS, layers=[lay])
         T1["ff"], T1["ell"] = T_["ff"][:1], T_["ell"][:1]
         np.testing.assert_allclose(y1, orc.tandem_forward(T1, toks, gamma)["y"], rtol=1e-10, atol=1e-12)
+
+
+def test_block_prefix_attn_mask():
+    """Deep Tandem's mask (Eq. (3)): against torch SDPA with the mask 'key j visible iff j < floor(i / gamma) gamma'
+    written from the 0-indexed form (rows of the first block: zero), and against the paper's 1-indexed formula
+    spelled out for gamma = 3 with uniform weights."""
+    B, q_len, Hq, Hkv, dh, T, gamma = 2, 6, 4, 2, 8, 20, 3
+    Q, K, V, _, _ = _mixed_case(8, B, q_len, Hq, Hkv, dh, T)
+    n = np.array([11, 0])
+    scale = dh ** -0.5
+    got = orc.block_prefix_attn(Q, K, V, n, gamma, scale)
+    G = Hq // Hkv
+    for b in range(B):
+        pos = n[b] + np.arange(q_len)
+        kb = (pos // gamma) * gamma
+        for r in range(q_len):
+            if kb[r] == 0:
+                assert (got[b, r] == 0).all()
+                continue
+            mask = (np.arange(T) < kb[r])[None, None, :]
+            want = torch.nn.functional.scaled_dot_product_attention(
+                torch.from_numpy(Q[b, r][:, None, :]), torch.from_numpy(np.repeat(K[b], G, axis=0)),
+                torch.from_numpy(np.repeat(V[b], G, axis=0)), attn_mask=torch.from_numpy(mask), scale=scale).numpy()[:, 0]
+            np.testing.assert_allclose(got[b, r], want, rtol=1e-11, atol=1e-12)
+    # paper's 1-indexed formula, spelled out for gamma = 3: positions 1..3 see nothing, 4..6 see x_1..x_3, 7..9 x_1..x_6
+    one = orc.block_prefix_attn(np.ones((1, 9, 1, 2)), np.zeros((1, 1, 9, 2)), np.arange(18.0).reshape(1, 1, 9, 2), [0], 3, 1.0)
+    want_rows = [None] * 3 + [3] * 3 + [6] * 3
+    V1 = np.arange(18.0).reshape(9, 2)
+    for i, m in enumerate(want_rows):
+        np.testing.assert_allclose(one[0, i, 0], 0.0 if m is None else V1[:m].mean(0), rtol=1e-13)
