@@ -985,11 +985,13 @@ int launch_big(const GemmParams& p, hipStream_t st) {
 int big_splits(int M, int N, int K) {
   if (M < 256 || N % 256 != 0 || N > (1 << 22) || K % (2 * BK) != 0) return 0;
   const long long tiles = (long long)((M + 255) / 256) * (N / 256);
-  if (tiles >= 128) return 1;
-  if (M < 1024) return 0;
+  if (M < 1024) return tiles >= 128 ? 1 : 0;
+  // From 1024 rows on, contraction splits while all workgroups still run at once (one per CU): a second round of
+  // quarter-length workgroups and twice the fp32 partials cost more than they save (measured at 1024 x 6144 x 4096:
+  // 4 splits of 96 tiles 104 us, 2 splits 75 us), and 128 tiles alone leave half of the chip idle.
   const int stages = K / BK;
   int s = 1;
-  while (tiles * s < 200 && s < 8 && stages % (4 * s) == 0 && stages / (2 * s) >= 16) s *= 2;
+  while (tiles * s * 2 <= 256 && s < 8 && stages % (4 * s) == 0 && stages / (2 * s) >= 16) s *= 2;
   return tiles * s >= 128 ? s : 0;
 }
 bool big_ok(int M, int N, int K) { return big_splits(M, N, K) > 0; }
