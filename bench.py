@@ -350,9 +350,9 @@ def step_workload(torch, binding, inputs, cfg, seed=3, pack_weights=True, free_t
 
 
 def run_prefill_workload(torch, binding, inputs, args):
-    """One tandem_prefill call: 32 prompt tokens of each of 32 sequences appended at context 4096 (C3 pair)."""
+    """One tandem_prefill call: 128 prompt tokens of each of 32 sequences appended at context 4096 (C3 pair)."""
     cfg = dict(C3)
-    B, q, n0 = cfg["B"], 32, 4096
+    B, q, n0 = cfg["B"], 128, 4096
     W = device_tandem_weights(inputs, cfg, 3)
     model = binding.TandemModel(W, pack_weights=not args.plain_weights)
     del W
@@ -380,11 +380,11 @@ def run_prefill_workload(torch, binding, inputs, args):
     flops_attn = 4.0 * B * q * L["Hq"] * L["dh"] * (n0 + q / 2) * L["n_layers"]
     tflops = (flops_dense + flops_attn) / (ms * 1e-3) / 1e12
     return {
-        "metric": "Tandem prompt ingestion tokens/sec (tandem_prefill, 32 tokens x 32 sequences per call)",
+        "metric": "Tandem prompt ingestion tokens/sec (tandem_prefill, 128 tokens x 32 sequences per call)",
         "value": M / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": "c3_prefill: tandem_prefill bf16 B=32, 32 rows per sequence at context 4096, C3 model pair "
+        "config": {"workload": "c3_prefill: tandem_prefill bf16 B=32, 128 rows per sequence at context 4096, C3 model pair "
                                "(M_L block pass + FF_Tandem + K_hat/V_hat rows; M_S does not run)",
                    "dense_TFLOP": flops_dense / 1e12, "attention_TFLOP": flops_attn / 1e12},
         "roofline": {"bound": "mfma", "achieved": tflops, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",

@@ -48,6 +48,7 @@ typedef enum { TANDEM_F32 = 0, TANDEM_BF16 = 1 } tandem_dtype;
 typedef enum { TANDEM_ACT_NONE = 0, TANDEM_ACT_GELU = 1 /* exact erf form */, TANDEM_ACT_RELU = 2 } tandem_act;
 
 #define TANDEM_MAX_QLEN 32 /* most query rows per sequence in one block-mode pass */
+#define TANDEM_MAX_PREFILL 128 /* most prompt tokens per sequence in one tandem_prefill call */
 #define TANDEM_MAX_SHARED_ROWS 256 /* most samples * q_len per prompt in tandem_block_attn_shared */
 
 /* Shape of one attention layer's caches.
@@ -309,7 +310,8 @@ int tandem_decode_step_adaptive(const tandem_model *m, const tandem_state_desc *
  * run: of its own rows only those of the block being drafted are ever attended (Eq. (2) line 2).
  * n[b] += q_len.  With TANDEM_PREFILL_EMIT, pending[b] becomes M_L's greedy token after the last row (the first
  * generated token); otherwise pending is left alone (the caller keeps the last prompt token pending).
- *   tokens   device int32 [B, q_len];  1 <= q_len <= TANDEM_MAX_QLEN: longer prompts take several calls
+ *   tokens   device int32 [B, q_len];  1 <= q_len <= TANDEM_MAX_PREFILL: longer prompts take several calls (the
+ *            dense layers run on all B * q_len rows at once, the attention on sub-blocks of TANDEM_MAX_QLEN rows)
  *   x_large  optional device [B, q_len, L.d]: x^(L_L) of the rows
  *   requires n[b] + q_len <= T_max;  ws: at least tandem_prefill_workspace(m, B, q_len) bytes. */
 #define TANDEM_PREFILL_EMIT 1

@@ -18,6 +18,7 @@ OK, ERR_NULL, ERR_SHAPE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = range(6)
 F32, BF16 = 0, 1
 ACT_NONE, ACT_GELU, ACT_RELU = 0, 1, 2
 MAX_QLEN = 32
+MAX_PREFILL = 128
 _ACT = {None: ACT_NONE, "none": ACT_NONE, "gelu": ACT_GELU, "relu": ACT_RELU}
 
 
@@ -678,7 +679,7 @@ def tandem_prefill_workspace(model: TandemModel, B: int, q_len: int) -> int:
 
 
 def tandem_prefill(model: TandemModel, state: TandemState, tokens, emit=False, x_large=None, ws=None, stream=None):
-    """Ingests tokens [B, q_len] (int32 device tensor, q_len <= 32) for every sequence: M_L's block pass plus the
+    """Ingests tokens [B, q_len] (int32 device tensor, q_len <= 128) for every sequence: M_L's block pass plus the
     Khat / Vhat rows; n += q_len; with emit, pending = M_L's greedy token after the last row."""
     import torch
 

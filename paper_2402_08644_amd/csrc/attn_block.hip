@@ -32,6 +32,8 @@ struct BlockParams {
   int causal;         // 1: the q_len rows are the last rows of the cache (row r sees n + r + 1 keys); 0: all see n keys
   int S_total, s_off;  // partial slots per row and this launch's first slot
   int mixed, gamma;    // attn_mrows_kernel only: 1 / 2 = first / second key segment of the all-positions small-model attention
+  long long row_skip;  // q / out hold (q_len * Hq + row_skip) rows per sequence (a call on part of the rows)
+  int n_off;           // added to n[b]
   int merge_prev;      // > 0 (needs S == 1): merge slots [0, merge_prev) into this launch's result and write out
   long long T_max;
   float scale_log2e;
@@ -68,7 +70,7 @@ __device__ __forceinline__ f32x4 mfma16(const bf16x8& a, const bf16x8& b, const 
 // Result of one query column (lane group c16; this lane holds output elements 16 db + 4 g4 + r4): the finished
 // row when this launch sees all keys, its partial (m, l, O) otherwise.  With merge_prev the partials that earlier
 // launches left for this row are folded in first, in slot order, and the row is finished here.
-__device__ __forceinline__ void write_row(const BlockParams& p, long long orow, int s, int g4, float m, float l,
+__device__ __forceinline__ void write_row(const BlockParams& p, long long orow, int b, int s, int g4, float m, float l,
                                           f32x4 (&acc)[8]) {
   if (p.merge_prev > 0) {
     for (int t = 0; t < p.merge_prev; ++t) {
@@ -91,7 +93,7 @@ __device__ __forceinline__ void write_row(const BlockParams& p, long long orow, 
   }
   if (p.S_total == 1 || p.merge_prev > 0) {
     const float inv = l > 0.f ? 1.f / l : 0.f;
-    bf16_t* op = p.out + orow * 128 + 4 * g4;
+    bf16_t* op = p.out + (orow + b * p.row_skip) * 128 + 4 * g4;
 #pragma unroll
     for (int db = 0; db < 8; ++db) {
       uint2 u;
@@ -124,7 +126,7 @@ __global__ __launch_bounds__(64 * NW, (RT <= 2 && NW == 4 ? 2 : 1)) void attn_bl
   const int s = blockIdx.x, b = blockIdx.z;
   const int kvh = blockIdx.y % p.Hkv, pass = blockIdx.y / p.Hkv;
 
-  long long n = p.n[b];
+  long long n = (long long)p.n[b] + p.n_off;
   // mixed == 1: first key segment of the all-positions small-model attention (see attn_mrows_kernel): row r sees
   // the keys below its block boundary kb(n + r), no lower limit - the only segment form this kernel takes
   const int ext = (p.causal || p.mixed) ? p.q_len : 0;
@@ -152,7 +154,7 @@ __global__ __launch_bounds__(64 * NW, (RT <= 2 && NW == 4 ? 2 : 1)) void attn_bl
       const int r = rho / p.G, gq = rho % p.G;
       orow[rt] = ((long long)b * p.q_len + r) * p.Hq + kvh * p.G + gq;
       lim[rt] = p.mixed ? (n + r) / p.gamma * p.gamma - 1 : (p.causal ? n + r : n - 1);
-      const bf16_t* qp = p.q + orow[rt] * 128 + 8 * g4;
+      const bf16_t* qp = p.q + (orow[rt] + b * p.row_skip) * 128 + 8 * g4;
 #pragma unroll
       for (int c = 0; c < 4; ++c) qreg[rt][c] = ld_bf16x8(qp + 32 * c);
     } else {
@@ -301,7 +303,7 @@ __global__ __launch_bounds__(64 * NW, (RT <= 2 && NW == 4 ? 2 : 1)) void attn_bl
     take(0);
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt)
-      if (orow[rt] >= 0) write_row(p, orow[rt], s, g4, m[rt], l[rt], acc[rt]);
+      if (orow[rt] >= 0) write_row(p, orow[rt], b, s, g4, m[rt], l[rt], acc[rt]);
   }
 }
 
@@ -330,7 +332,7 @@ __global__ __launch_bounds__(64 * NW) void attn_mrows_kernel(BlockParams p) {
   // All-positions small-model attention (Eq. (2) with the query's own block boundary kb(i) = floor(i / gamma)
   // * gamma, i = n + r): segment 1 reads the rows derived from the large model, keys [0, kb(i)); segment 2 the
   // model's own rows, keys [kb(i), i].
-  long long n = p.n[b];
+  long long n = (long long)p.n[b] + p.n_off;
   const int mixed = MIXED ? p.mixed : 0;
   const int ext = (p.causal || mixed) ? p.q_len : 0;
   const long long nmax = p.T_max - ext;
@@ -366,7 +368,7 @@ __global__ __launch_bounds__(64 * NW) void attn_mrows_kernel(BlockParams p) {
       } else {
         lim = p.causal ? n + r : n - 1;
       }
-      const bf16_t* qp = p.q + orow * 128 + 8 * g4;
+      const bf16_t* qp = p.q + (orow + b * p.row_skip) * 128 + 8 * g4;
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
         uint4 u = *reinterpret_cast<const uint4*>(qp + 32 * c);
@@ -521,7 +523,7 @@ __global__ __launch_bounds__(64 * NW) void attn_mrows_kernel(BlockParams p) {
 
   l += __shfl_xor(l, 16);
   l += __shfl_xor(l, 32);
-  if (orow >= 0) write_row(p, orow, s, g4, m, l, acc);
+  if (orow >= 0) write_row(p, orow, b, s, g4, m, l, acc);
 }
 
 template <int NW>
@@ -588,6 +590,8 @@ int launch_attn_block(const AttnArgs& a, hipStream_t st) {
   p.s_off = a.S_total > 0 ? a.s_off : 0;
   p.merge_prev = a.S_total > 0 && a.S == 1 ? a.merge_prev : 0;
   p.mixed = a.mixed;
+  p.row_skip = a.q_rows > a.q_len ? (long long)(a.q_rows - a.q_len) * a.Hq : 0;
+  p.n_off = a.n_off;
   p.gamma = a.gamma > 0 ? a.gamma : 1;
   p.T_max = a.T_max;
   p.scale_log2e = a.scale * 1.4426950408889634f;
@@ -628,5 +632,6 @@ int launch_attn_block(const AttnArgs& a, hipStream_t st) {
     }
   }
   if (rc != TANDEM_OK || a.S_total > 0 || a.S == 1) return rc;
-  return launch_attn_combine(a.part_ml, a.part_o, a.out, a.B * a.q_len * a.Hq, a.S, 128, a.dtype, st);
+  return launch_attn_combine(a.part_ml, a.part_o, a.out, a.B * a.q_len * a.Hq, a.S, 128, a.dtype, st, a.q_len * a.Hq,
+                             p.row_skip);
 }

@@ -21,6 +21,8 @@ struct RowsParams {
   const int32_t *nA, *nB;
   int causal, Hq, Hkv, q_len, gamma_max, S;
   int S_total, s_off;  // partial slots per row and this launch's first slot
+  long long row_skip;  // q / out hold (q_len * Hq + row_skip) rows per sequence
+  int n_off;           // added to nA[b]
   int mixed_gamma;     // > 0: all-positions small-model attention with this block length (see below)
   long long T_max;
   float scale_log2e;
@@ -40,7 +42,7 @@ __global__ __launch_bounds__(64 * NW) void attn_rows_kernel(RowsParams p) {
   const int s = blockIdx.x, b = blockIdx.z;
   const int kvh = blockIdx.y % p.Hkv, r = blockIdx.y / p.Hkv;
 
-  long long nA = p.nA[b];
+  long long nA = (long long)p.nA[b] + p.n_off;
   long long nB = 0;
   long long strideB = p.gamma_max;  // rows per (sequence, head) of source B
   if (p.mixed_gamma > 0) {
@@ -78,7 +80,7 @@ __global__ __launch_bounds__(64 * NW) void attn_rows_kernel(RowsParams p) {
 #pragma unroll
   for (int g = 0; g < G; ++g) {
     Raw<RB> raw;
-    raw.load((const T*)p.q + (row0 + g) * DH + t * EPL);
+    raw.load((const T*)p.q + (row0 + b * p.row_skip + g) * DH + t * EPL);
     Unpack<T, EPL>::run(raw, qv[g]);
 #pragma unroll
     for (int e = 0; e < EPL; ++e) qv[g][e] *= p.scale_log2e;
@@ -194,7 +196,7 @@ __global__ __launch_bounds__(64 * NW) void attn_rows_kernel(RowsParams p) {
     }
     const long long row = row0 + g;
     if (p.S_total == 1) {
-      ((T*)p.out)[row * DH + d] = from_f32<T>(lt > 0.f ? ot / lt : 0.f);
+      ((T*)p.out)[(row + b * p.row_skip) * DH + d] = from_f32<T>(lt > 0.f ? ot / lt : 0.f);
     } else {
       const long long ps = row * p.S_total + p.s_off + s;
       p.part_o[ps * DH + d] = ot;
@@ -209,7 +211,7 @@ __global__ __launch_bounds__(64 * NW) void attn_rows_kernel(RowsParams p) {
 // out[row, :] = sum_s O_s 2^(m_s - m) / sum_s l_s 2^(m_s - m), splits visited in index order
 template <typename T>
 __global__ void attn_combine_kernel(const float* __restrict__ part_ml, const float* __restrict__ part_o, T* out,
-                                    int S, int dh) {
+                                    int S, int dh, int rows_per_seq, long long row_skip) {
   const long long row = blockIdx.x;
   const int d = threadIdx.x;
   float mn = TANDEM_NEG_BIG;
@@ -220,7 +222,8 @@ __global__ void attn_combine_kernel(const float* __restrict__ part_ml, const flo
     lt += part_ml[(row * S + s) * 2 + 1] * c;
     ot += part_o[(row * S + s) * dh + d] * c;
   }
-  out[row * dh + d] = from_f32<T>(lt > 0.f ? ot / lt : 0.f);
+  const long long orow = rows_per_seq > 0 ? row + row / rows_per_seq * row_skip : row;
+  out[orow * dh + d] = from_f32<T>(lt > 0.f ? ot / lt : 0.f);
 }
 
 template <typename T, int DH, int G, int NW>
@@ -266,11 +269,13 @@ size_t attn_rows_workspace(int B, int Hq, int q_len, int dh, int S) {
 }
 
 int launch_attn_combine(const float* part_ml, const float* part_o, void* out, int rows, int S, int dh, int dtype,
-                        hipStream_t st) {
+                        hipStream_t st, int rows_per_seq, long long row_skip) {
   if (dtype == TANDEM_BF16)
-    hipLaunchKernelGGL(attn_combine_kernel<bf16_t>, dim3(rows), dim3(dh), 0, st, part_ml, part_o, (bf16_t*)out, S, dh);
+    hipLaunchKernelGGL(attn_combine_kernel<bf16_t>, dim3(rows), dim3(dh), 0, st, part_ml, part_o, (bf16_t*)out, S, dh,
+                       rows_per_seq, row_skip);
   else
-    hipLaunchKernelGGL(attn_combine_kernel<float>, dim3(rows), dim3(dh), 0, st, part_ml, part_o, (float*)out, S, dh);
+    hipLaunchKernelGGL(attn_combine_kernel<float>, dim3(rows), dim3(dh), 0, st, part_ml, part_o, (float*)out, S, dh,
+                       rows_per_seq, row_skip);
   return hip_ok(hipGetLastError());
 }
 
@@ -291,6 +296,8 @@ int launch_attn_rows(const AttnArgs& a, hipStream_t st) {
   p.S = a.S;
   p.S_total = a.S_total > 0 ? a.S_total : a.S;
   p.s_off = a.S_total > 0 ? a.s_off : 0;
+  p.row_skip = a.q_rows > a.q_len ? (long long)(a.q_rows - a.q_len) * a.Hq : 0;
+  p.n_off = a.n_off;
   p.mixed_gamma = a.mixed == 3 ? (a.gamma > 0 ? a.gamma : 1) : 0;
   p.T_max = a.T_max;
   p.scale_log2e = a.scale * 1.4426950408889634f;
@@ -311,5 +318,6 @@ int launch_attn_rows(const AttnArgs& a, hipStream_t st) {
   else
     return TANDEM_ERR_UNSUPPORTED;
   if (rc != TANDEM_OK || a.S_total > 0 || a.S == 1) return rc;
-  return launch_attn_combine(a.part_ml, a.part_o, a.out, a.B * a.q_len * a.Hq, a.S, a.dh, a.dtype, st);
+  return launch_attn_combine(a.part_ml, a.part_o, a.out, a.B * a.q_len * a.Hq, a.S, a.dh, a.dtype, st, a.q_len * a.Hq,
+                             p.row_skip);
 }

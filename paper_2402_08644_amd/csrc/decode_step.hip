@@ -230,9 +230,15 @@ StepPlan make_plan(const tandem_model* m, int B, int gamma, int64_t T_max, int g
     const int Sd = attn_rows_splits(B, S.Hkv, 1, S.Hq / S.Hkv, T_max, gamma_max, nullptr);
     size_t a = Sd > 1 ? align256((size_t)B * S.Hq * Sd * 2 * 4) + (size_t)B * S.Hq * Sd * S.dh * 4 : 0;
     const bool mfma = m->d.dtype == TANDEM_BF16 && L.dh == 128;
-    const int Sb = mfma ? attn_block_splits(B, L.Hkv, gamma, L.Hq / L.Hkv, T_max, nullptr) : attn_rows_splits(B, L.Hkv, gamma, L.Hq / L.Hkv, T_max, 0, nullptr);
-    const size_t rows = (size_t)B * gamma * L.Hq;
-    size_t b = Sb > 1 ? align256(rows * Sb * 2 * 4) + rows * Sb * L.dh * 4 : 0;
+    // block calls cover at most TANDEM_MAX_QLEN rows per sequence (longer prompt chunks run in sub-blocks)
+    auto blk_ws = [&](int q) -> size_t {
+      const int Sb = mfma ? attn_block_splits(B, L.Hkv, q, L.Hq / L.Hkv, T_max, nullptr)
+                          : attn_rows_splits(B, L.Hkv, q, L.Hq / L.Hkv, T_max, 0, nullptr);
+      const size_t rows = (size_t)B * q * L.Hq;
+      return Sb > 1 ? align256(rows * Sb * 2 * 4) + rows * Sb * L.dh * 4 : 0;
+    };
+    size_t b = blk_ws(gamma < TANDEM_MAX_QLEN ? gamma : TANDEM_MAX_QLEN);
+    if (gamma > TANDEM_MAX_QLEN && gamma % TANDEM_MAX_QLEN) b = maxz(b, blk_ws(gamma % TANDEM_MAX_QLEN));
     p.attn_ws_bytes = maxz(a, b);
     if (score) {
       tandem_attn_desc sd{B, S.Hq, S.Hkv, S.dh, T_max, 0, 1.f, m->d.dtype};
@@ -300,9 +306,17 @@ struct Ctx {
     if (rc_ != TANDEM_OK) return rc_; \
   } while (0)
 
+// row0 / q_rows: the call covers rows row0 .. row0 + q_len - 1 of the q_rows rows that q and out hold per sequence
+// (block mode: those rows sit at positions nA[b] + row0 ..)
 int attn_call(const Ctx& c, const tandem_decoder_desc& D, const void* q, const void* kA, const void* vA, const int32_t* nA,
-              const void* kB, const void* vB, const int32_t* nB, int causal, int q_len, void* out) {
+              const void* kB, const void* vB, const int32_t* nB, int causal, int q_len, void* out, int row0 = 0,
+              int q_rows = 0) {
   AttnArgs a{};
+  const size_t skip = (size_t)row0 * D.Hq * D.dh * elsize(c.dtype);
+  q = (const char*)q + skip;
+  out = (char*)out + skip;
+  a.q_rows = q_rows;
+  a.n_off = row0;
   a.q = q;
   a.kA = kA;
   a.vA = vA;
@@ -419,7 +433,13 @@ int large_block_pass(const Ctx& c, const int32_t* block_tokens, int nq, const ta
   if (c.plan.fused) TRY(launch_rmsnorm(x, L.layers[0].g_attn, c.at<>(c.plan.xn), M, L.d, c.eps, c.dtype, c.stream));
   for (int j = 0; j < L.n_layers; ++j) {
     auto attn_only = [&]() -> int {
-      return attn_call(c, L, q, state->KL[j], state->VL[j], state->n, nullptr, nullptr, nullptr, 1, nq, att);
+      // more than TANDEM_MAX_QLEN rows per sequence (long prompt chunks): the attention runs on sub-blocks of rows,
+      // all of whose K/V rows are already in the cache
+      for (int r0 = 0; r0 < nq; r0 += TANDEM_MAX_QLEN) {
+        const int rows = nq - r0 < TANDEM_MAX_QLEN ? nq - r0 : TANDEM_MAX_QLEN;
+        TRY(attn_call(c, L, q, state->KL[j], state->VL[j], state->n, nullptr, nullptr, nullptr, 1, rows, att, r0, nq));
+      }
+      return TANDEM_OK;
     };
     if (c.plan.fused) {
       auto finish_qkv = [&](const float* part, int splits) -> int {
@@ -696,7 +716,7 @@ int tandem_decode_step_adaptive(const tandem_model* m, const tandem_state_desc* 
 }
 
 size_t tandem_prefill_workspace(const tandem_model* m, int32_t B, int32_t q_len) {
-  if (!m || B < 1 || q_len < 1 || q_len > TANDEM_MAX_QLEN) return 0;
+  if (!m || B < 1 || q_len < 1 || q_len > TANDEM_MAX_PREFILL) return 0;
   return make_plan(m, B, q_len, (int64_t)1 << 40, 1).total;
 }
 
@@ -708,7 +728,7 @@ int tandem_prefill(const tandem_model* m, const tandem_state_desc* state, const 
   const tandem_decoder_desc &L = m->d.L, &S = m->d.S;
   const int B = state->B;
   if (B < 1 || B > 65535 || state->T_max < 1) return TANDEM_ERR_SHAPE;
-  if (q_len < 1 || q_len > TANDEM_MAX_QLEN || q_len > state->T_max) return TANDEM_ERR_SHAPE;
+  if (q_len < 1 || q_len > TANDEM_MAX_PREFILL || q_len > state->T_max) return TANDEM_ERR_SHAPE;
   for (int j = 0; j < L.n_layers; ++j)
     if (!state->KL[j] || !state->VL[j]) return TANDEM_ERR_NULL;
   for (int j = 0; j < S.n_layers; ++j)

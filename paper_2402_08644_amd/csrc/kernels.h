@@ -38,6 +38,9 @@ struct AttnArgs {
   // [0, kb); mixed = 2 - kA/vA hold the model's own rows, row r sees [kb, i].  attn_rows kernels: mixed = 3 - kA/vA
   // as in 1, kB/vB own rows in a cache of T_max rows indexed by position, both in one launch.
   int mixed, gamma;
+  // A call may cover q_len of the q_rows rows that q and out hold per sequence (q / out then point at the first
+  // covered row of sequence 0): q_rows = 0 means q_len.  n_off is added to every nA[b].
+  int q_rows, n_off;
 };
 
 // number of context splits; *wide (optional) = 1 when the workgroups should have eight wavefronts (AttnArgs::wide)
@@ -53,8 +56,9 @@ bool attn_block_supported(const AttnArgs& a);
 int launch_attn_block(const AttnArgs& a, hipStream_t st);
 
 // combine of split partials (attn_rows.hip); fixed split order
+// rows_per_seq / row_skip: output row (row + (row / rows_per_seq) * row_skip); 0 / 0 for a dense output
 int launch_attn_combine(const float* part_ml, const float* part_o, void* out, int rows, int S, int dh, int dtype,
-                        hipStream_t st);
+                        hipStream_t st, int rows_per_seq = 0, long long row_skip = 0);
 
 // ---------------------------------------------------------------- dense (gemm.hip)
 // Y[M, N] = epilogue(X[M, K] . W[N, K]^T): + bias[N], activation, + residual[M, N].

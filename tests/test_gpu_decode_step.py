@@ -311,14 +311,15 @@ def test_free_token_stream_equals_greedy_large_decode_fp32(tb):
         assert got[:n_new] == want, (gamma, got, want)
 
 
-@pytest.mark.parametrize("chunks,B", [((4, 1, 6), 3), ((32, 9), 2), ((16,), 5), ((32,), 9)])  # last: 288 rows, big tiles
+# (32,) x 9: 288 rows, big tiles; (70, 33): more than 32 rows per sequence - attention in sub-blocks of 32 + a tail
+@pytest.mark.parametrize("chunks,B", [((4, 1, 6), 3), ((32, 9), 2), ((16,), 5), ((32,), 9), ((70, 33), 2), ((128,), 1)])
 def test_prefill_bf16_vs_oracle(tb, chunks, B):
     """tandem_prefill chunk by chunk (ragged starting lengths): new cache rows, x^(L_L) and n against the oracle;
     rows outside the written range stay bit-identical."""
     torch, binding = tb
     W = small_bf16_pair(80 + len(chunks))
     T = inputs.as_f64(W)
-    T_max = 96
+    T_max = 160
     n = [int(v) for v in np.random.default_rng(81).integers(0, 20, B)]
     pending = [1] * B
     ost, host = oracle_state_from(T, B, T_max, 82, n, pending, "bf16")
@@ -380,7 +381,8 @@ def test_prefill_error_codes(tb):
     W = inputs.tiny_tandem(seed=1, dtype="f32")
     model = binding.TandemModel(W)
     gst = binding.TandemState(model, 1, 16, 2)
-    toks = torch.zeros((1, 33), dtype=torch.int32, device="cuda")
+    gst = binding.TandemState(model, 1, 256, 2)
+    toks = torch.zeros((1, 129), dtype=torch.int32, device="cuda")
     with pytest.raises(binding.TandemError) as ei:
         binding.tandem_prefill(model, gst, toks)  # more rows than one call takes
     assert ei.value.status == binding.ERR_SHAPE
@@ -482,3 +484,29 @@ def test_decode_step_graph_replays_equal_eager(tb, adaptive):
             assert torch.equal(out[k].view(torch.int16) if out[k].dtype == torch.bfloat16 else out[k], eager[k].view(torch.int16) if eager[k].dtype == torch.bfloat16 else eager[k]), (replay, k)
         assert torch.equal(gst.n, eager_n) and torch.equal(gst.pending, eager_p), replay
         assert torch.equal(gst.Khat[1].view(torch.int16), eager_k.view(torch.int16)), replay
+
+
+def test_prefill_long_chunk_fp32_vs_oracle(tb):
+    """70 prompt tokens in one call on the generic (fp32, d_h = 64) kernels: the attention runs in sub-blocks of 32,
+    32 and 6 rows of a 70-row q tensor."""
+    torch, binding = tb
+    W = inputs.tiny_tandem(seed=3, dtype="f32")
+    T = inputs.as_f64(W)
+    B, T_max, q = 2, 96, 70
+    n, pending = [9, 0], [1, 1]
+    ost, host = oracle_state_from(T, B, T_max, 7, n, pending, "f32")
+    model = binding.TandemModel(W)
+    gst = upload_state(tb, model, B, T_max, 2, host, n, pending)
+    toks = inputs.token_ids(8, (B, q), 1000)
+    xl = torch.empty((B, q, model.L.d), dtype=model.dtype, device="cuda")
+    binding.tandem_prefill(model, gst, torch.tensor(toks, dtype=torch.int32).cuda(), x_large=xl)
+    torch.cuda.synchronize()
+    want = orc.prefill_block(T, ost, toks)
+    assert_rows_close(inputs.torch_to_f64(xl), want["x_large"], tol=2e-3, what="x_large")
+    np.testing.assert_array_equal(gst.n.cpu().numpy(), ost["n"])
+    for b in range(B):
+        for key in ("KL", "Khat", "Vhat"):
+            for j in range(len(host[key])):
+                g = getattr(gst, key)[j]
+                assert_rows_close(inputs.torch_to_f64(g[b, :, n[b]:n[b] + q]), ost[key][j][b, :, n[b]:n[b] + q], tol=2e-3,
+                                  what=f"{key}[{j}] new rows")
