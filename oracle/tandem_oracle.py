@@ -530,6 +530,30 @@ def block_attn_shared(Q, Ks, Vs, n_shared, Ko, Vo, n_own, scale):
     return out
 
 
+def draft_attn_shared(q, Khs, Vhs, n_shared, Kho, Vho, n_own, kcur, vcur, n_cur, scale):
+    """The small model's draft attention (Eq. (2), second line) when `ns` samples continue one prompt: q
+    [B, ns, Hq, dh]; Khs, Vhs [B, Hkv, Ts, dh] hold the K_hat / V_hat rows of the prompt, once per prompt; Kho, Vho
+    [B*ns, Hkv, To, dh] those of each sample's completed blocks after the prompt; kcur, vcur [B*ns, Hkv, gmax, dh] the
+    sample's own rows of the block being drafted.  Sample (b, s) = sequence i = b*ns + s attends, in one softmax,
+    Khs[b, :, :n_shared[b]], Kho[i, :, :n_own[i]] and kcur[i, :, :n_cur[i]]."""
+    q = np.asarray(q, F64)
+    B, ns, Hq, dh = q.shape
+    Hkv = np.asarray(Khs).shape[1]
+    G = Hq // Hkv
+    out = np.zeros_like(q)
+    for b in range(B):
+        for s in range(ns):
+            i = b * ns + s
+            for h in range(Hq):
+                kv = h // G
+                K = np.concatenate([np.asarray(Khs, F64)[b, kv, : n_shared[b]], np.asarray(Kho, F64)[i, kv, : n_own[i]],
+                                    np.asarray(kcur, F64)[i, kv, : n_cur[i]]])
+                V = np.concatenate([np.asarray(Vhs, F64)[b, kv, : n_shared[b]], np.asarray(Vho, F64)[i, kv, : n_own[i]],
+                                    np.asarray(vcur, F64)[i, kv, : n_cur[i]]])
+                out[b, s, h] = attention_one(q[b, s, h], K, V, scale)
+    return out
+
+
 # ----------------------------------------------------------------------------
 # a4'  the small model's attention at EVERY position of a known sequence (Eq. (2), second line, with the
 #      block boundary k = floor(i / gamma) * gamma of the query's own position i, 0-indexed; Sec. 3

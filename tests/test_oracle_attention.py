@@ -378,3 +378,27 @@ def test_block_prefix_attn_mask():
     V1 = np.arange(18.0).reshape(9, 2)
     for i, m in enumerate(want_rows):
         np.testing.assert_allclose(one[0, i, 0], 0.0 if m is None else V1[:m].mean(0), rtol=1e-13)
+
+
+def test_draft_attn_shared_equals_draft_attn_on_materialised_caches():
+    """Shared-prompt draft attention == the pinned draft_attn on per-sample K_hat caches that hold a copy of the
+    prompt's rows followed by the sample's own completed rows."""
+    rng = np.random.default_rng(12)
+    B, ns, Hq, Hkv, dh, Ts, To, gmax = 2, 3, 4, 2, 8, 9, 6, 4
+    mk = lambda *sh: rng.standard_normal(sh)
+    q = mk(B, ns, Hq, dh)
+    Khs, Vhs, Kho, Vho = mk(B, Hkv, Ts, dh), mk(B, Hkv, Ts, dh), mk(B * ns, Hkv, To, dh), mk(B * ns, Hkv, To, dh)
+    kc, vc = mk(B * ns, Hkv, gmax, dh), mk(B * ns, Hkv, gmax, dh)
+    n_shared, n_own, n_cur = np.array([9, 0]), np.array([0, 3, 6, 1, 0, 2]), np.array([1, 4, 2, 3, 1, 4])
+    scale = dh ** -0.5
+    got = orc.draft_attn_shared(q, Khs, Vhs, n_shared, Kho, Vho, n_own, kc, vc, n_cur, scale)
+    Kc, Vc = np.zeros((B * ns, Hkv, Ts + To, dh)), np.zeros((B * ns, Hkv, Ts + To, dh))
+    n = np.zeros(B * ns, dtype=np.int64)
+    for b in range(B):
+        for s_ in range(ns):
+            i, m = b * ns + s_, n_shared[b]
+            Kc[i, :, :m], Vc[i, :, :m] = Khs[b, :, :m], Vhs[b, :, :m]
+            Kc[i, :, m:m + To], Vc[i, :, m:m + To] = Kho[i], Vho[i]
+            n[i] = m + n_own[i]
+    want = orc.draft_attn(q.reshape(B * ns, Hq, dh), Kc, Vc, n, kc, vc, n_cur, scale).reshape(q.shape)
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-13)
