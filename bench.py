@@ -214,6 +214,59 @@ def shared_workload(torch, binding, inputs, B, samples, q_len, Hq, Hkv, dh, n_sh
     return call, R, bytes_alg, oracle_sample
 
 
+def shared_draft_workload(torch, binding, inputs, B, samples, H, Hkv, dh, n_shared, n_own, n_cur, gmax, seed, copied=False):
+    """Draft attention with `samples` continuations per prompt: the prompt's K_hat / V_hat rows stored and read once per
+    prompt (tandem_draft_attn_shared), or - copied - tandem_draft_attn on per-sample caches that each hold a copy."""
+    nseq = B * samples
+    rows_own = n_own + n_cur
+    bytes_alg = ((nseq * (n_shared + rows_own)) if copied else (B * n_shared + nseq * rows_own)) * Hkv * dh * 2 * 2
+    R = _rotations(bytes_alg)
+    sets = []
+    for i in range(R):
+        mk = lambda j, *sh: inputs.device_normal(sh, seed * 100 + 7 * i + j, 1.0)
+        c = dict(q=mk(0, B, samples, H, dh), khs=mk(1, B, Hkv, n_shared, dh), vhs=mk(2, B, Hkv, n_shared, dh),
+                 kho=mk(3, nseq, Hkv, n_own, dh), vho=mk(4, nseq, Hkv, n_own, dh),
+                 kc=mk(5, nseq, Hkv, gmax, dh), vc=mk(6, nseq, Hkv, gmax, dh))
+        if copied:
+            rep = lambda t: t.repeat_interleave(samples, dim=0)
+            c["k"] = torch.cat([rep(c["khs"]), c["kho"]], dim=2).contiguous()
+            c["v"] = torch.cat([rep(c["vhs"]), c["vho"]], dim=2).contiguous()
+            if i > 0:
+                del c["khs"], c["vhs"], c["kho"], c["vho"]
+        sets.append(c)
+    i32 = lambda n, v: torch.full((n,), v, dtype=torch.int32, device="cuda")
+    ns_t, no_t, nc_t, n_t = i32(B, n_shared), i32(nseq, n_own), i32(nseq, n_cur), i32(nseq, n_shared + n_own)
+    out = torch.empty((B, samples, H, dh), dtype=torch.bfloat16, device="cuda")
+    ws = binding.workspace(1 << 26)
+
+    def call(i):
+        s = sets[i]
+        if copied:
+            binding.tandem_draft_attn(s["q"].view(nseq, H, dh), s["k"], s["v"], n_t, s["kc"], s["vc"], nc_t,
+                                      out=out.view(nseq, H, dh), ws=ws)
+        else:
+            binding.tandem_draft_attn_shared(s["q"], s["khs"], s["vhs"], ns_t, s["kho"], s["vho"], no_t, s["kc"], s["vc"],
+                                             nc_t, out=out, ws=ws)
+
+    def oracle_sample(n_prompts):
+        from oracle import tandem_oracle as orc
+
+        s = sets[0]
+        f = inputs.torch_to_f64
+        m = n_prompts * samples
+        args = (f(s["q"][:n_prompts]), f(s["khs"][:n_prompts]), f(s["vhs"][:n_prompts]), ns_t[:n_prompts].cpu().numpy(),
+                f(s["kho"][:m]), f(s["vho"][:m]), no_t[:m].cpu().numpy(), f(s["kc"][:m]), f(s["vc"][:m]),
+                nc_t[:m].cpu().numpy(), 1.0 / math.sqrt(dh))
+        t0 = time.perf_counter()
+        want = orc.draft_attn_shared(*args)
+        dt = time.perf_counter() - t0
+        call(0)
+        torch.cuda.synchronize()
+        return dt, want.reshape(-1, H, dh), inputs.torch_to_f64(out[:n_prompts]).reshape(-1, H, dh)
+
+    return call, R, bytes_alg, oracle_sample
+
+
 def mixed_workload(torch, binding, inputs, B, q_len, H, Hkv, dh, n_prefix, gamma, seed):
     """All-positions small-model attention on q_len consecutive positions at the end of a context: the keys are the
     rows derived from the large model up to each query's block boundary plus a few own rows."""
@@ -513,6 +566,14 @@ WORKLOADS = {
     "s4_shared": ("shared", dict(B=8, samples=4, q_len=5, Hq=32, Hkv=8, dh=128, n_shared=7936, n_own=251, seed=5), 1,
                   "tandem_block_attn_shared bf16 8 prompts x 4 samples, Hq/Hkv=32/8 dh=128, prompt 7936 rows read once "
                   "per prompt + 256 own rows per sample, 5 query rows"),
+    "s4_draft_shared": ("shared_draft", dict(B=8, samples=4, H=8, Hkv=8, dh=128, n_shared=7936, n_own=248, n_cur=4, gmax=4,
+                                             seed=7), 1,
+                        "tandem_draft_attn_shared bf16 8 prompts x 4 samples, H=8 dh=128, prompt 7936 K_hat rows read once per "
+                        "prompt + 248 own + 4 current rows per sample"),
+    "s4_draft_copied": ("shared_draft", dict(B=8, samples=4, H=8, Hkv=8, dh=128, n_shared=7936, n_own=248, n_cur=4, gmax=4,
+                                             seed=7, copied=True), 1,
+                        "tandem_draft_attn bf16 on 32 per-sample caches that each hold a copy of the 7936 prompt rows (the "
+                        "form tandem_draft_attn_shared replaces; same values)"),
     # teacher-forced scoring with the small model: 32 consecutive positions of every sequence at the end of an 8192
     # context, C3's small-layer shape, block length 4
     "c3_mixed": ("mixed", dict(B=32, q_len=32, H=8, Hkv=8, dh=128, n_prefix=8160, gamma=4, seed=6), 1,
@@ -601,7 +662,8 @@ def _traffic(name):
 
 def run_kernel_workload(torch, binding, inputs, args):
     kind, kw, n_seq, desc = WORKLOADS[args.workload]
-    maker = {"draft": draft_workload, "block": block_workload, "shared": shared_workload, "mixed": mixed_workload}[kind]
+    maker = {"draft": draft_workload, "block": block_workload, "shared": shared_workload, "mixed": mixed_workload,
+             "shared_draft": shared_draft_workload}[kind]
     call, n_copies, bytes_alg, oracle_sample = maker(torch, binding, inputs, **kw)
     torch.cuda.synchronize()
     ms = _time_calls(torch, call, n_copies, args.steps, args.warmup, use_graph=not args.no_graph)

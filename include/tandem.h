@@ -131,6 +131,24 @@ int tandem_block_attn_shared(const tandem_attn_desc *a, int32_t samples, int64_t
                              const void *v_own, const int32_t *n_own, int32_t q_len, void *out, void *ws,
                              size_t ws_bytes, void *hip_stream);
 
+/* tandem_draft_attn when several samples continue one prompt (Sec. 3.1, num-samples): the prompt's Khat/Vhat rows
+ * are stored and read once per prompt for the queries of all its samples.  Sample s of prompt b is sequence
+ * i = b * samples + s; its query attends, in ONE softmax,
+ *   k_hat_shared/v_hat_shared[b, h/G, 0 : n_shared[b])   the prompt's rows (derived from M_L)
+ *   k_hat_own/v_hat_own[i, h/G, 0 : n_own[i])            rows of the sample's completed blocks after the prompt
+ *   k_cur/v_cur[i, h/G, 0 : n_cur[i])                    the sample's own rows of the block being drafted
+ *   q, out  device [B, samples, Hq, dh]  (B = a->B prompts);  k_hat_shared, v_hat_shared device [B, Hkv, a->T_max, dh]
+ *   k_hat_own, v_hat_own device [B * samples, Hkv, T_own, dh];  k_cur, v_cur device [B * samples, Hkv, a->gamma_max, dh]
+ *   n_shared int32 [B]; n_own, n_cur int32 [B * samples]; all clamped to their caches
+ *   samples <= TANDEM_MAX_SHARED_ROWS, B * samples <= 65535.
+ * ws: at least tandem_draft_attn_shared_workspace(...) bytes, always needed.  Reads the caches only. */
+size_t tandem_draft_attn_shared_workspace(const tandem_attn_desc *a, int32_t samples, int64_t T_own);
+int tandem_draft_attn_shared(const tandem_attn_desc *a, int32_t samples, int64_t T_own, const void *q,
+                             const void *k_hat_shared, const void *v_hat_shared, const int32_t *n_shared,
+                             const void *k_hat_own, const void *v_hat_own, const int32_t *n_own, const void *k_cur,
+                             const void *v_cur, const int32_t *n_cur, void *out, void *ws, size_t ws_bytes,
+                             void *hip_stream);
+
 /* Deep Tandem's large-model attention (Eq. (3)): the query at position i = n_prefix[b] + r (0-indexed) attends only
  * the rows of the blocks completed before its own block, cache rows 0 .. floor(i / gamma) * gamma - 1 (the paper's
  * keys x_{<= k gamma}, k = ceil((i - gamma) / gamma), in 1-indexed positions); queries of the first block see no key

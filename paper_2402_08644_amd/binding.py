@@ -92,6 +92,7 @@ EXPORTS = (
     "tandem_packed_weight_bytes", "tandem_pack_weight",
     "tandem_project", "tandem_block_attn", "tandem_draft_attn",
     "tandem_block_attn_shared_workspace", "tandem_block_attn_shared",
+    "tandem_draft_attn_shared_workspace", "tandem_draft_attn_shared",
     "tandem_mixed_attn_workspace", "tandem_mixed_attn",
     "tandem_block_prefix_attn_workspace", "tandem_block_prefix_attn",
     "tandem_model_create", "tandem_model_destroy", "tandem_decode_step_workspace", "tandem_decode_step",
@@ -134,6 +135,10 @@ def lib():
     L.tandem_mixed_attn_workspace.argtypes = [C.POINTER(AttnDesc), i32]
     L.tandem_mixed_attn.restype = C.c_int
     L.tandem_mixed_attn.argtypes = [C.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, sz, vp]
+    L.tandem_draft_attn_shared_workspace.restype = sz
+    L.tandem_draft_attn_shared_workspace.argtypes = [C.POINTER(AttnDesc), i32, i64]
+    L.tandem_draft_attn_shared.restype = C.c_int
+    L.tandem_draft_attn_shared.argtypes = [C.POINTER(AttnDesc), i32, i64] + [vp] * 11 + [vp, sz, vp]
     L.tandem_block_attn_shared_workspace.restype = sz
     L.tandem_block_attn_shared_workspace.argtypes = [C.POINTER(AttnDesc), i32, i64, i32]
     L.tandem_block_attn_shared.restype = C.c_int
@@ -282,6 +287,43 @@ def tandem_block_attn(q, k_cache, v_cache, n_prefix, scale=None, out=None, ws=No
     rc = lib().tandem_block_attn(C.byref(d), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(n_prefix), q_len, _ptr(out),
                                  _ptr(ws), ws.numel(), _stream(stream))
     _check(rc, "tandem_block_attn")
+    return out
+
+
+def tandem_draft_attn_shared(q, k_hat_shared, v_hat_shared, n_shared, k_hat_own, v_hat_own, n_own, k_cur, v_cur, n_cur,
+                             scale=None, out=None, ws=None, stream=None):
+    """q [B,samples,Hq,dh]; k_hat_shared,v_hat_shared [B,Hkv,T_max,dh], n_shared int32 [B]; k_hat_own,v_hat_own
+    [B*samples,Hkv,T_own,dh], n_own int32 [B*samples]; k_cur,v_cur [B*samples,Hkv,gamma_max,dh], n_cur int32 [B*samples]."""
+    import torch
+
+    B, ns, Hq, dh = q.shape
+    _, Hkv, T_max, _ = k_hat_shared.shape
+    T_own, gmax = k_hat_own.shape[2], k_cur.shape[2]
+    _need(q, (B, ns, Hq, dh), "q")
+    for t, nm in ((k_hat_shared, "k_hat_shared"), (v_hat_shared, "v_hat_shared")):
+        _need(t, (B, Hkv, T_max, dh), nm)
+    for t, nm in ((k_hat_own, "k_hat_own"), (v_hat_own, "v_hat_own")):
+        _need(t, (B * ns, Hkv, T_own, dh), nm)
+    for t, nm in ((k_cur, "k_cur"), (v_cur, "v_cur")):
+        _need(t, (B * ns, Hkv, gmax, dh), nm)
+    _need(n_shared, (B,), "n_shared")
+    for t, nm in ((n_own, "n_own"), (n_cur, "n_cur")):
+        _need(t, (B * ns,), nm)
+    for t, nm in ((n_shared, "n_shared"), (n_own, "n_own"), (n_cur, "n_cur")):
+        if t.dtype != torch.int32:
+            raise TypeError(f"{nm} must be int32")
+    for t in (k_hat_shared, v_hat_shared, k_hat_own, v_hat_own, k_cur, v_cur):
+        if t.dtype != q.dtype:
+            raise TypeError("q / K / V dtypes differ")
+    d = attn_desc(B, Hq, Hkv, dh, T_max, gmax, (1.0 / math.sqrt(dh)) if scale is None else scale, _dtype_code(q))
+    if out is None:
+        out = torch.empty_like(q)
+    if ws is None:
+        ws = _workspace(int(lib().tandem_draft_attn_shared_workspace(C.byref(d), ns, T_own)), q)
+    rc = lib().tandem_draft_attn_shared(C.byref(d), ns, T_own, _ptr(q), _ptr(k_hat_shared), _ptr(v_hat_shared),
+                                        _ptr(n_shared), _ptr(k_hat_own), _ptr(v_hat_own), _ptr(n_own), _ptr(k_cur),
+                                        _ptr(v_cur), _ptr(n_cur), _ptr(out), _ptr(ws), ws.numel(), _stream(stream))
+    _check(rc, "tandem_draft_attn_shared")
     return out
 
 

@@ -215,6 +215,84 @@ int tandem_block_attn_shared(const tandem_attn_desc* a, int32_t samples, int64_t
   return launch_attn_combine(x.part_ml, x.part_o, out, (int)rows, S, a->dh, a->dtype, st);
 }
 
+// splits of the two launches of the shared-prompt draft attention
+int plan_draft_shared(const tandem_attn_desc* a, int32_t samples, int64_t T_own, SharedPlan* pl) {
+  int rc = check_attn_desc(a);
+  if (rc != TANDEM_OK) return rc;
+  if (samples < 1 || samples > TANDEM_MAX_SHARED_ROWS || T_own < 1 || a->gamma_max < 1) return TANDEM_ERR_SHAPE;
+  if ((int64_t)a->B * samples > 65535 || (int64_t)a->Hkv * samples > 65535) return TANDEM_ERR_SHAPE;
+  const int G = a->Hq / a->Hkv;
+  pl->wide1 = pl->wide2 = 0;
+  pl->S1 = block_uses_mfma(a) ? attn_block_splits(a->B, a->Hkv, samples, G, a->T_max, &pl->wide1)
+                              : attn_rows_splits(a->B, a->Hkv, samples, G, a->T_max, 0, &pl->wide1);
+  pl->S2 = attn_rows_splits(a->B * samples, a->Hkv, 1, G, T_own, a->gamma_max, &pl->wide2);
+  return TANDEM_OK;
+}
+
+size_t tandem_draft_attn_shared_workspace(const tandem_attn_desc* a, int32_t samples, int64_t T_own) {
+  SharedPlan pl;
+  if (plan_draft_shared(a, samples, T_own, &pl) != TANDEM_OK) return 0;
+  return carved_bytes((size_t)a->B * samples * a->Hq, pl.S1 + pl.S2, a->dh);
+}
+
+int tandem_draft_attn_shared(const tandem_attn_desc* a, int32_t samples, int64_t T_own, const void* q,
+                             const void* k_hat_shared, const void* v_hat_shared, const int32_t* n_shared,
+                             const void* k_hat_own, const void* v_hat_own, const int32_t* n_own, const void* k_cur,
+                             const void* v_cur, const int32_t* n_cur, void* out, void* ws, size_t ws_bytes,
+                             void* hip_stream) {
+  SharedPlan pl;
+  int rc = plan_draft_shared(a, samples, T_own, &pl);
+  if (rc != TANDEM_OK) return rc;
+  if (!q || !k_hat_shared || !v_hat_shared || !n_shared || !k_hat_own || !v_hat_own || !n_own || !k_cur || !v_cur ||
+      !n_cur || !out || !ws)
+    return TANDEM_ERR_NULL;
+  const size_t rows = (size_t)a->B * samples * a->Hq;
+  const int S = pl.S1 + pl.S2;
+  if (ws_bytes < carved_bytes(rows, S, a->dh)) return TANDEM_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)hip_stream;
+  AttnArgs x{};
+  x.q = q;
+  x.Hq = a->Hq;
+  x.Hkv = a->Hkv;
+  x.dh = a->dh;
+  x.scale = a->scale;
+  x.dtype = a->dtype;
+  x.out = out;
+  x.causal = 0;
+  x.S_total = S;
+  carve(ws, rows, S, &x.part_ml, &x.part_o);
+  // the prompt's rows: per prompt, the queries of its samples form one block that sees all n_shared[b] keys
+  x.kA = k_hat_shared;
+  x.vA = v_hat_shared;
+  x.nA = n_shared;
+  x.B = a->B;
+  x.q_len = samples;
+  x.T_max = a->T_max;
+  x.gamma_max = 0;
+  x.S = pl.S1;
+  x.wide = pl.wide1;
+  x.s_off = 0;
+  rc = block_uses_mfma(a) ? launch_attn_block(x, st) : launch_attn_rows(x, st);
+  if (rc != TANDEM_OK) return rc;
+  // each sample's rows of completed blocks after the prompt and its rows of the block being drafted
+  x.kA = k_hat_own;
+  x.vA = v_hat_own;
+  x.nA = n_own;
+  x.kB = k_cur;
+  x.vB = v_cur;
+  x.nB = n_cur;
+  x.B = a->B * samples;
+  x.q_len = 1;
+  x.T_max = T_own;
+  x.gamma_max = a->gamma_max;
+  x.S = pl.S2;
+  x.wide = pl.wide2;
+  x.s_off = pl.S1;
+  rc = launch_attn_rows(x, st);
+  if (rc != TANDEM_OK) return rc;
+  return launch_attn_combine(x.part_ml, x.part_o, out, (int)rows, S, a->dh, a->dtype, st);
+}
+
 size_t tandem_block_prefix_attn_workspace(const tandem_attn_desc* a, int32_t q_len) {
   return tandem_block_attn_workspace(a, q_len);
 }

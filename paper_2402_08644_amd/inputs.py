@@ -126,6 +126,25 @@ def shared_attn_case(seed, B, samples, q_len, Hq, Hkv, dh, T_shared, T_own, n_sh
     }
 
 
+def shared_draft_case(seed, B, samples, Hq, Hkv, dh, T_shared, T_own, gmax, n_shared, n_own, n_cur, dtype="bf16", std=1.0):
+    """Inputs of one draft-attention call in which `samples` sequences continue each of B prompts."""
+    rng = np.random.default_rng(seed)
+    nseq = B * samples
+    return {
+        "q": normal(rng, (B, samples, Hq, dh), std, dtype),
+        "khs": normal(rng, (B, Hkv, T_shared, dh), std, dtype),
+        "vhs": normal(rng, (B, Hkv, T_shared, dh), std, dtype),
+        "kho": normal(rng, (nseq, Hkv, T_own, dh), std, dtype),
+        "vho": normal(rng, (nseq, Hkv, T_own, dh), std, dtype),
+        "kcur": normal(rng, (nseq, Hkv, gmax, dh), std, dtype),
+        "vcur": normal(rng, (nseq, Hkv, gmax, dh), std, dtype),
+        "n_shared": np.broadcast_to(np.asarray(n_shared, np.int32), (B,)).copy(),
+        "n_own": np.broadcast_to(np.asarray(n_own, np.int32), (nseq,)).copy(),
+        "n_cur": np.broadcast_to(np.asarray(n_cur, np.int32), (nseq,)).copy(),
+        "scale": 1.0 / math.sqrt(dh),
+    }
+
+
 def mixed_attn_case(seed, B, q_len, Hq, Hkv, dh, T_max, n_prefix, dtype="bf16", std=1.0):
     """Inputs of one all-positions small-model attention call: queries for q_len consecutive positions and the
     two caches (rows derived from the large model; the small model's own rows), Q/K/V ~ N(0, std)."""

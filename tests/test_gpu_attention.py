@@ -322,6 +322,54 @@ def test_block_attn_shared_parity_small(tb, B, ns, q_len, Hq, Hkv, dh, Ts, To, n
     print(f"shared small {B,ns,q_len,Hq,Hkv,dh,Ts,To,dtype}: max rel err {e[0]:.2e}")
 
 
+@pytest.mark.parametrize(
+    "B,ns,Hq,Hkv,dh,Ts,To,gmax,n_shared,n_own,n_cur,dtype",
+    [
+        (2, 4, 8, 8, 128, 700, 40, 4, [700, 37], [0, 36, 7, 40, 1, 2, 3, 30], [1, 4, 2, 3, 4, 1, 2, 3], "bf16"),  # small-model shape
+        (1, 8, 8, 2, 128, 1300, 64, 8, [1234], [5, 0, 64, 31, 2, 9, 50, 17], [8, 1, 2, 3, 4, 5, 6, 7], "bf16"),    # G=4: 32 rows
+        (3, 1, 4, 1, 128, 100, 300, 4, [100, 0, 64], [297, 0, 100], [1, 2, 4], "bf16"),                            # one sample
+        (2, 12, 4, 1, 128, 260, 20, 2, [0, 259], 7, 2, "bf16"),                                                    # 48 rows, an empty prompt
+        (2, 3, 4, 2, 64, 90, 12, 4, [90, 10], [10, 0, 3, 4, 5, 6], [1, 2, 3, 4, 1, 2], "bf16"),                    # dh=64 generic path
+        (2, 2, 2, 2, 64, 50, 16, 2, [17, 50], [0, 13, 7, 2], [2, 1, 2, 1], "f32"),
+    ],
+)
+def test_draft_attn_shared_parity_small(tb, B, ns, Hq, Hkv, dh, Ts, To, gmax, n_shared, n_own, n_cur, dtype):
+    torch, binding = tb
+    c = inputs.shared_draft_case(61, B, ns, Hq, Hkv, dh, Ts, To, gmax, n_shared, n_own, n_cur, dtype=dtype)
+    dev = lambda k: torch.from_numpy(c[k]).cuda() if k.startswith("n_") else c[k].to_torch()
+    out = binding.tandem_draft_attn_shared(dev("q"), dev("khs"), dev("vhs"), dev("n_shared"), dev("kho"), dev("vho"),
+                                           dev("n_own"), dev("kcur"), dev("vcur"), dev("n_cur"), scale=c["scale"])
+    torch.cuda.synchronize()
+    want = orc.draft_attn_shared(c["q"].f64, c["khs"].f64, c["vhs"].f64, c["n_shared"], c["kho"].f64, c["vho"].f64,
+                                 c["n_own"], c["kcur"].f64, c["vcur"].f64, c["n_cur"], c["scale"])
+    e = assert_rows_close(inputs.torch_to_f64(out).reshape(-1, Hq, dh), want.reshape(-1, Hq, dh), what="shared draft")
+    print(f"shared draft small {B,ns,Hq,Hkv,dh,Ts,To,dtype}: max rel err {e[0]:.2e}")
+
+
+def test_draft_attn_shared_error_codes(tb):
+    torch, binding = tb
+    import ctypes as C
+
+    L = binding.lib()
+    d = binding.attn_desc(2, 4, 2, 128, 64, 4, 0.1, binding.BF16)
+    t = torch.zeros(2 * 4 * 4 * 64 * 128, dtype=torch.bfloat16, device="cuda")
+    n = torch.zeros(8, dtype=torch.int32, device="cuda")
+    p, pn = C.c_void_p(t.data_ptr()), C.c_void_p(n.data_ptr())
+    ws = torch.zeros(1 << 22, dtype=torch.uint8, device="cuda")
+    pw = C.c_void_p(ws.data_ptr())
+    call = lambda ns, To, q=p, w=pw, wb=ws.numel(): L.tandem_draft_attn_shared(
+        C.byref(d), ns, To, q, p, p, pn, p, p, pn, p, p, pn, p, w, wb, None)
+    assert call(0, 16) == binding.ERR_SHAPE
+    assert call(4, 0) == binding.ERR_SHAPE
+    assert call(4, 16, q=None) == binding.ERR_NULL
+    assert call(4, 16, w=None) == binding.ERR_NULL
+    need = int(L.tandem_draft_attn_shared_workspace(C.byref(d), 4, 16))
+    assert need > 0
+    assert call(4, 16, wb=need - 1) == binding.ERR_WORKSPACE
+    assert call(4, 16, wb=need) == binding.OK
+    torch.cuda.synchronize()
+
+
 def test_block_attn_shared_equals_block_attn_on_copied_prompts(tb):
     """At the latency evaluation's shape (4 samples per prompt, long prompt, short continuations) the shared
     form agrees with tandem_block_attn on per-sample caches holding a copy of the prompt rows, and with the
