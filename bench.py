@@ -446,6 +446,57 @@ def run_prefill_workload(torch, binding, inputs, args):
     }
 
 
+def run_shared_step_workload(torch, binding, inputs, args):
+    """tandem_decode_step_shared at the C3 pair: 8 prompts x 4 samples = 32 sequences, prompt 7936 rows (once per prompt),
+    252 rows per sequence after it, gamma = 4."""
+    cfg = dict(C3)
+    P, ns, g = 8, 4, cfg["gamma"]
+    B, Tp, To = P * ns, 7936, 256
+    W = device_tandem_weights(inputs, cfg, 3)
+    model = binding.TandemModel(W, pack_weights=not args.plain_weights)
+    del W
+    k = [11]
+
+    def fill(*shape):
+        k[0] += 1
+        return inputs.device_normal(shape, k[0], 1.0)
+
+    pst = binding.TandemState(model, P, Tp, g, fill=fill)
+    pst.n.fill_(Tp)
+    state = binding.TandemState(model, B, To, g, fill=fill)
+    q = g + 1 if args.free_token else g
+    n0 = To - q
+    prompt = binding.TandemPrompt(pst, ns)
+    ws = torch.empty(binding.tandem_decode_step_shared_workspace(model, B, ns, g), dtype=torch.uint8, device="cuda")
+    out = {"tokens": torch.empty((B, q), dtype=torch.int32, device="cuda"),
+           "n_accepted": torch.empty((B,), dtype=torch.int32, device="cuda")}
+
+    def call(_i):
+        state.n.fill_(n0)
+        state.pending.fill_(1)
+        binding.tandem_decode_step(model, state, g, ws=ws, out=out, free_token=args.free_token, prompt=prompt)
+
+    torch.cuda.synchronize()
+    ms = _time_calls(torch, call, 1, args.steps, args.warmup, use_graph=not args.no_graph)
+    L, S = cfg["large"], cfg["small"]
+    weights = step_bytes(dict(cfg, B=0))  # B = 0: no KV rows, the weights of every model run
+    kv = lambda c, rows_p, rows_o: c["n_layers"] * c["Hkv"] * c["dh"] * 2 * 2 * (P * rows_p + B * rows_o)
+    total = weights + kv(L, Tp, To) + sum(kv(S, Tp, n0 + r + 1) for r in range(g))
+    gbs = total / (ms * 1e-3) / 1e9
+    return {
+        "metric": "Tandem decode steps/sec at gamma=4, 4 samples per prompt (prompt rows shared)",
+        "value": 1e3 / ms, "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "c3_step_shared: tandem_decode_step_shared bf16, 8 prompts x 4 samples (B=32), prompt 7936 rows "
+                               "once per prompt + 256 rows per sequence, gamma=4, C3 model pair"
+                               + (", free token" if args.free_token else ""),
+                   "step_algorithmic_GB": total / 1e9},
+        "roofline": {"bound": "hbm", "kernel": "whole step (weights of every model run + every visible cache row once)",
+                     "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS, "traffic": None},
+        "cpu_baseline": None,
+    }
+
+
 def run_score_workload(torch, binding, inputs, args):
     """One tandem_score call: the small model teacher-forced on 32 tokens of each of 32 sequences at context 4096 (C3
     pair; the large model's K_hat / V_hat rows are already in the state)."""
@@ -755,7 +806,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="c3_step", choices=sorted(WORKLOADS) + sorted(PROJECT_WORKLOADS) + ["c3_step", "c3_prefill", "c3_score"])
+    ap.add_argument("--workload", default="c3_step", choices=sorted(WORKLOADS) + sorted(PROJECT_WORKLOADS) + ["c3_step", "c3_prefill", "c3_score", "c3_step_shared"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--plain-weights", action="store_true",
@@ -797,6 +848,9 @@ def main():
     if args.workload == "c3_prefill":
         runner = run_prefill_workload
         args.steps = min(args.steps, 10)
+    if args.workload == "c3_step_shared":
+        runner = run_shared_step_workload
+        args.steps = min(args.steps, 20)
     if args.workload == "c3_score":
         runner = run_score_workload
         args.steps = min(args.steps, 20)

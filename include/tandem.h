@@ -286,6 +286,27 @@ int tandem_decode_step(const tandem_model *m, const tandem_state_desc *state, in
                        int32_t *out_tokens, int32_t *n_accepted, const tandem_step_aux *aux, void *ws, size_t ws_bytes,
                        void *hip_stream);
 
+/* ---- several samples per prompt (Sec. 3.1, num-samples; the latency evaluation's 4 samples) ----
+ * The step for state->B = prompts * samples sequences, sequence i = b * samples + s continuing prompt b.  The rows
+ * of the prompts live once per prompt in the caches of `prompt` (as a tandem_prefill on a state of `prompts`
+ * sequences leaves them: that state's KL / VL / Khat / Vhat and n) and are only read.  The caches of `state` hold
+ * each sequence's rows AFTER its prompt: state->n[i] counts those rows, state->T_max is their capacity.  Every
+ * attention call of the step runs through tandem_block_attn_shared / tandem_draft_attn_shared, so the prompt rows
+ * cross HBM once per prompt; everything else, and the result, is that of tandem_decode_step on per-sequence
+ * caches holding a copy of the prompt rows followed by the sequence's own (this model has no positional encoding). */
+typedef struct {
+  int32_t samples;
+  int64_t T_prompt;              /* rows per prompt cache */
+  void *const *KLp, *const *VLp; /* host arrays [L.n_layers] of device [prompts, L.Hkv, T_prompt, L.dh] */
+  void *const *Khp, *const *Vhp; /* host arrays [S.n_layers] of device [prompts, S.Hkv, T_prompt, S.dh] */
+  const int32_t *n_prompt;       /* device int32 [prompts] */
+} tandem_prompt_desc;
+
+size_t tandem_decode_step_shared_workspace(const tandem_model *m, int32_t B, int32_t samples, int32_t gamma);
+int tandem_decode_step_shared(const tandem_model *m, const tandem_state_desc *state, const tandem_prompt_desc *prompt,
+                              int32_t gamma, int32_t flags, int32_t *out_tokens, int32_t *n_accepted,
+                              const tandem_step_aux *aux, void *ws, size_t ws_bytes, void *hip_stream);
+
 /* ---- adaptive block length (Sec. 3.1 "Adaptive Block Length"; Sec. 4: threshold 0.8) ----
  * A 2-layer router MLP decides after every draft token whether M_S goes on drafting or M_L verifies now.  Its
  * input, in this order: the entropy (nats) of M_S's distribution over the vocabulary for the current token, the k

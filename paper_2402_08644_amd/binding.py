@@ -76,6 +76,12 @@ class StepAux(C.Structure):
     _fields_ = [(k, C.c_void_p) for k in ("draft", "verify", "y_small", "x_large", "logits_S", "logits_L")]
 
 
+class PromptDesc(C.Structure):
+    _fields_ = [("samples", C.c_int32), ("T_prompt", C.c_int64),
+                ("KLp", C.POINTER(C.c_void_p)), ("VLp", C.POINTER(C.c_void_p)),
+                ("Khp", C.POINTER(C.c_void_p)), ("Vhp", C.POINTER(C.c_void_p)), ("n_prompt", C.c_void_p)]
+
+
 class RouterDesc(C.Structure):
     _fields_ = [("k", C.c_int32), ("d_hidden", C.c_int32), ("dtype", C.c_int32), ("tau", C.c_float),
                 ("W1", C.c_void_p), ("b1", C.c_void_p), ("w2", C.c_void_p), ("b2", C.c_void_p)]
@@ -99,6 +105,7 @@ EXPORTS = (
     "tandem_prefill_workspace", "tandem_prefill",
     "tandem_router_eval", "tandem_decode_step_adaptive",
     "tandem_score_workspace", "tandem_score",
+    "tandem_decode_step_shared_workspace", "tandem_decode_step_shared",
 )
 
 _lib = None
@@ -117,6 +124,11 @@ def lib():
     L.tandem_status_string.argtypes = [C.c_int]
     L.tandem_project_workspace.restype = sz
     L.tandem_project_workspace.argtypes = [C.POINTER(FFDesc), i64]
+    L.tandem_decode_step_shared_workspace.restype = sz
+    L.tandem_decode_step_shared_workspace.argtypes = [vp, i32, i32, i32]
+    L.tandem_decode_step_shared.restype = C.c_int
+    L.tandem_decode_step_shared.argtypes = [vp, C.POINTER(StateDesc), C.POINTER(PromptDesc), i32, i32, vp, vp,
+                                            C.POINTER(StepAux), vp, sz, vp]
     L.tandem_score_workspace.restype = sz
     L.tandem_score_workspace.argtypes = [vp, i32, i32]
     L.tandem_score.restype = C.c_int
@@ -571,6 +583,21 @@ class TandemState:
                          arr("Vcur"), self.n.data_ptr(), self.pending.data_ptr())
 
 
+class TandemPrompt:
+    """The prompts of a step with several samples per prompt: the caches and lengths of a TandemState that
+    tandem_prefill filled for `prompts` sequences, read by every sample of a prompt."""
+
+    def __init__(self, prompt_state: TandemState, samples: int):
+        self.state, self.samples = prompt_state, samples
+        self._arrays = [(C.c_void_p * len(ts))(*[t.data_ptr() for t in ts])
+                        for ts in (prompt_state.KL, prompt_state.VL, prompt_state.Khat, prompt_state.Vhat)]
+        self.desc = PromptDesc(samples, prompt_state.T_max, *self._arrays, prompt_state.n.data_ptr())
+
+
+def tandem_decode_step_shared_workspace(model: TandemModel, B: int, samples: int, gamma: int) -> int:
+    return int(lib().tandem_decode_step_shared_workspace(model.handle, B, samples, gamma))
+
+
 def tandem_decode_step_workspace(model: TandemModel, B: int, gamma: int) -> int:
     return int(lib().tandem_decode_step_workspace(model.handle, B, gamma))
 
@@ -610,12 +637,13 @@ def tandem_router_eval(router: dict, logits, emb, out=None, stream=None):
 
 
 def tandem_decode_step(model: TandemModel, state: TandemState, gamma: int, forced=None, aux=False, ws=None, out=None,
-                       stream=None, free_token=False, router=None, tau=0.8):
+                       stream=None, free_token=False, router=None, tau=0.8, prompt=None):
     """Runs one step.  q = gamma, or gamma + 1 with free_token (M_L also verifies the last draft and always
     emits its own token after the accepted prefix).  Returns a dict with "tokens" [B,q] and "n_accepted" [B]
     (int32 device tensors) and, with aux=True, "draft" [B,gamma], "verify" [B,q], "y_small", "x_large",
     "logits_S", "logits_L".  With router (see router_desc) the block length adapts per sequence up to gamma:
-    the dict then also holds "n_drafted" [B] (int32) and "router_p" [B,gamma] (fp32)."""
+    the dict then also holds "n_drafted" [B] (int32) and "router_p" [B,gamma] (fp32).  With prompt (a TandemPrompt)
+    the state's sequences are samples of its prompts and the state's caches hold only their rows after the prompt."""
     import torch
 
     B = state.B
@@ -641,6 +669,17 @@ def tandem_decode_step(model: TandemModel, state: TandemState, gamma: int, force
         _need(forced, (B, gamma), "forced")
         if forced.dtype != torch.int32:
             raise TypeError("forced must be int32")
+    if prompt is not None:
+        if forced is not None or router is not None:
+            raise ValueError("the shared-prompt step takes neither forced tokens nor a router")
+        if ws is None:
+            ws = _workspace(tandem_decode_step_shared_workspace(model, B, prompt.samples, gamma), state.n)
+        rc = lib().tandem_decode_step_shared(model.handle, C.byref(state.desc), C.byref(prompt.desc), gamma,
+                                             STEP_FREE_TOKEN if free_token else 0, _ptr(out["tokens"]),
+                                             _ptr(out["n_accepted"]), C.byref(a) if a is not None else None, _ptr(ws),
+                                             ws.numel(), _stream(stream))
+        _check(rc, "tandem_decode_step_shared")
+        return out
     if ws is None:
         ws = _workspace(tandem_decode_step_workspace(model, B, gamma), state.n)
     if router is not None:

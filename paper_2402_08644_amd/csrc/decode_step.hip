@@ -194,7 +194,9 @@ struct StepPlan {
 };
 
 // score: the small model also runs on all B * gamma rows (teacher-forced pass), with the all-positions attention
-StepPlan make_plan(const tandem_model* m, int B, int gamma, int64_t T_max, int gamma_max, bool score = false) {
+// samples > 0: the step of several samples per prompt (attention through the shared-prompt entry points)
+StepPlan make_plan(const tandem_model* m, int B, int gamma, int64_t T_max, int gamma_max, bool score = false,
+                   int samples = 0, int64_t T_prompt = 0) {
   const tandem_decoder_desc &L = m->d.L, &S = m->d.S;
   const size_t es = elsize(m->d.dtype);
   const size_t M = (size_t)B * gamma;
@@ -243,6 +245,12 @@ StepPlan make_plan(const tandem_model* m, int B, int gamma, int64_t T_max, int g
     if (score) {
       tandem_attn_desc sd{B, S.Hq, S.Hkv, S.dh, T_max, 0, 1.f, m->d.dtype};
       p.attn_ws_bytes = maxz(p.attn_ws_bytes, tandem_mixed_attn_workspace(&sd, gamma));
+    }
+    if (samples > 0) {
+      tandem_attn_desc ld{B / samples, L.Hq, L.Hkv, L.dh, T_prompt, 0, 1.f, m->d.dtype};
+      tandem_attn_desc sd{B / samples, S.Hq, S.Hkv, S.dh, T_prompt, gamma_max, 1.f, m->d.dtype};
+      p.attn_ws_bytes = maxz(p.attn_ws_bytes, tandem_block_attn_shared_workspace(&ld, samples, T_max, gamma));
+      p.attn_ws_bytes = maxz(p.attn_ws_bytes, tandem_draft_attn_shared_workspace(&sd, samples, T_max));
     }
     p.attn_ws = take(p.attn_ws_bytes);
   }
@@ -296,6 +304,7 @@ struct Ctx {
   hipStream_t stream;
   int dtype;
   float eps;
+  const tandem_prompt_desc* pr = nullptr;  // several samples per prompt: the prompts' caches
   template <typename T = void> T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
   const void* pk(const void* W) const { return m->pk(W); }
 };
@@ -310,7 +319,18 @@ struct Ctx {
 // (block mode: those rows sit at positions nA[b] + row0 ..)
 int attn_call(const Ctx& c, const tandem_decoder_desc& D, const void* q, const void* kA, const void* vA, const int32_t* nA,
               const void* kB, const void* vB, const int32_t* nB, int causal, int q_len, void* out, int row0 = 0,
-              int q_rows = 0) {
+              int q_rows = 0, const void* kP = nullptr, const void* vP = nullptr) {
+  if (c.pr) {
+    // several samples per prompt: kP / vP hold the prompts' rows of this layer, kA / vA each sample's later rows
+    tandem_attn_desc d{c.st->B / c.pr->samples, D.Hq, D.Hkv, D.dh, c.pr->T_prompt, causal ? 0 : c.st->gamma_max,
+                       1.0f / sqrtf((float)D.dh), c.dtype};
+    void* aws = c.at<>(c.plan.attn_ws);
+    if (causal)
+      return tandem_block_attn_shared(&d, c.pr->samples, c.st->T_max, q, kP, vP, c.pr->n_prompt, kA, vA, nA, q_len, out, aws,
+                                      c.plan.attn_ws_bytes, c.stream);
+    return tandem_draft_attn_shared(&d, c.pr->samples, c.st->T_max, q, kP, vP, c.pr->n_prompt, kA, vA, nA, kB, vB, nB, out,
+                                    aws, c.plan.attn_ws_bytes, c.stream);
+  }
   AttnArgs a{};
   const size_t skip = (size_t)row0 * D.Hq * D.dh * elsize(c.dtype);
   q = (const char*)q + skip;
@@ -437,7 +457,8 @@ int large_block_pass(const Ctx& c, const int32_t* block_tokens, int nq, const ta
       // all of whose K/V rows are already in the cache
       for (int r0 = 0; r0 < nq; r0 += TANDEM_MAX_QLEN) {
         const int rows = nq - r0 < TANDEM_MAX_QLEN ? nq - r0 : TANDEM_MAX_QLEN;
-        TRY(attn_call(c, L, q, state->KL[j], state->VL[j], state->n, nullptr, nullptr, nullptr, 1, rows, att, r0, nq));
+        TRY(attn_call(c, L, q, state->KL[j], state->VL[j], state->n, nullptr, nullptr, nullptr, 1, rows, att, r0, nq,
+                      c.pr ? c.pr->KLp[j] : nullptr, c.pr ? c.pr->VLp[j] : nullptr));
       }
       return TANDEM_OK;
     };
@@ -598,7 +619,7 @@ size_t tandem_decode_step_workspace(const tandem_model* m, int32_t B, int32_t ga
 
 namespace {
 int decode_step_impl(const tandem_model* m, const tandem_state_desc* state, const tandem_router_desc* router,
-                     int32_t gamma, int32_t flags, const int32_t* forced, int32_t* out_tokens, int32_t* n_accepted,
+                     const tandem_prompt_desc* pr, int32_t gamma, int32_t flags, const int32_t* forced, int32_t* out_tokens, int32_t* n_accepted,
                      int32_t* n_drafted, float* router_p, const tandem_step_aux* aux, void* ws, size_t ws_bytes,
                      void* hip_stream) {
   if (!m || !state || !out_tokens || !n_accepted || !ws) return TANDEM_ERR_NULL;
@@ -616,12 +637,22 @@ int decode_step_impl(const tandem_model* m, const tandem_state_desc* state, cons
     if (!state->KL[j] || !state->VL[j]) return TANDEM_ERR_NULL;
   for (int j = 0; j < S.n_layers; ++j)
     if (!state->Khat[j] || !state->Vhat[j] || !state->Kcur[j] || !state->Vcur[j]) return TANDEM_ERR_NULL;
-  if (ws_bytes < tandem_decode_step_workspace(m, B, gamma)) return TANDEM_ERR_WORKSPACE;
+  if (pr) {
+    if (!pr->KLp || !pr->VLp || !pr->Khp || !pr->Vhp || !pr->n_prompt) return TANDEM_ERR_NULL;
+    if (pr->samples < 1 || B % pr->samples != 0 || pr->T_prompt < 1) return TANDEM_ERR_SHAPE;
+    for (int j = 0; j < L.n_layers; ++j)
+      if (!pr->KLp[j] || !pr->VLp[j]) return TANDEM_ERR_NULL;
+    for (int j = 0; j < S.n_layers; ++j)
+      if (!pr->Khp[j] || !pr->Vhp[j]) return TANDEM_ERR_NULL;
+  } else if (ws_bytes < tandem_decode_step_workspace(m, B, gamma)) {
+    return TANDEM_ERR_WORKSPACE;
+  }
 
   Ctx c;
   c.m = m;
   c.st = state;
-  c.plan = make_plan(m, B, nq, state->T_max, state->gamma_max);
+  c.pr = pr;
+  c.plan = make_plan(m, B, nq, state->T_max, state->gamma_max, false, pr ? pr->samples : 0, pr ? pr->T_prompt : 0);
   if (c.plan.total > ws_bytes) return TANDEM_ERR_WORKSPACE;
   c.ws = (char*)ws;
   c.stream = (hipStream_t)hip_stream;
@@ -655,7 +686,7 @@ int decode_step_impl(const tandem_model* m, const tandem_state_desc* state, cons
     for (int j = 0; j < S.n_layers; ++j) {
       auto attn_only = [&]() -> int {
         return attn_call(c, S, q, state->Khat[j], state->Vhat[j], state->n, state->Kcur[j], state->Vcur[j],
-                         ncur + (size_t)r * B, 0, 1, att);
+                         ncur + (size_t)r * B, 0, 1, att, 0, 0, c.pr ? c.pr->Khp[j] : nullptr, c.pr ? c.pr->Vhp[j] : nullptr);
       };
       if (c.plan.fused) {
         auto finish_qkv = [&](const float* part, int splits) -> int {
@@ -699,7 +730,23 @@ int decode_step_impl(const tandem_model* m, const tandem_state_desc* state, cons
 int tandem_decode_step(const tandem_model* m, const tandem_state_desc* state, int32_t gamma, int32_t flags,
                        const int32_t* forced, int32_t* out_tokens, int32_t* n_accepted, const tandem_step_aux* aux,
                        void* ws, size_t ws_bytes, void* hip_stream) {
-  return decode_step_impl(m, state, nullptr, gamma, flags, forced, out_tokens, n_accepted, nullptr, nullptr, aux, ws,
+  return decode_step_impl(m, state, nullptr, nullptr, gamma, flags, forced, out_tokens, n_accepted, nullptr, nullptr, aux, ws,
+                          ws_bytes, hip_stream);
+}
+
+size_t tandem_decode_step_shared_workspace(const tandem_model* m, int32_t B, int32_t samples, int32_t gamma) {
+  if (!m || B < 1 || samples < 1 || B % samples != 0 || gamma < 1 || gamma > TANDEM_MAX_QLEN) return 0;
+  const int64_t big = (int64_t)1 << 40;
+  size_t total = make_plan(m, B, gamma, big, gamma, false, samples, big).total;
+  if (gamma < TANDEM_MAX_QLEN) total = maxz(total, make_plan(m, B, gamma + 1, big, gamma, false, samples, big).total);
+  return total;
+}
+
+int tandem_decode_step_shared(const tandem_model* m, const tandem_state_desc* state, const tandem_prompt_desc* prompt,
+                              int32_t gamma, int32_t flags, int32_t* out_tokens, int32_t* n_accepted,
+                              const tandem_step_aux* aux, void* ws, size_t ws_bytes, void* hip_stream) {
+  if (!prompt) return TANDEM_ERR_NULL;
+  return decode_step_impl(m, state, nullptr, prompt, gamma, flags, nullptr, out_tokens, n_accepted, nullptr, nullptr, aux, ws,
                           ws_bytes, hip_stream);
 }
 
@@ -711,7 +758,7 @@ int tandem_decode_step_adaptive(const tandem_model* m, const tandem_state_desc* 
   int rc = check_router(router, m->d.S.d);
   if (rc != TANDEM_OK) return rc;
   if (router->dtype != m->d.dtype || m->d.S.vocab < router->k) return TANDEM_ERR_UNSUPPORTED;
-  return decode_step_impl(m, state, router, gamma_max, flags, nullptr, out_tokens, n_accepted, n_drafted, router_p, aux,
+  return decode_step_impl(m, state, router, nullptr, gamma_max, flags, nullptr, out_tokens, n_accepted, n_drafted, router_p, aux,
                           ws, ws_bytes, hip_stream);
 }
 

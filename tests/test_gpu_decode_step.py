@@ -510,3 +510,106 @@ def test_prefill_long_chunk_fp32_vs_oracle(tb):
                 g = getattr(gst, key)[j]
                 assert_rows_close(inputs.torch_to_f64(g[b, :, n[b]:n[b] + q]), ost[key][j][b, :, n[b]:n[b] + q], tol=2e-3,
                                   what=f"{key}[{j}] new rows")
+
+
+@pytest.mark.parametrize("free", [False, True])
+def test_decode_step_shared_prompt_vs_oracle_on_materialised_caches(tb, free):
+    """Several samples per prompt: the GPU step reads the prompt rows from per-prompt caches and keeps per-sequence
+    caches for the later rows only; the oracle runs the ordinary step on per-sequence caches that hold a copy of the
+    prompt rows followed by the sequence's own.  Same tokens (near-argmax), representations and new cache rows."""
+    torch, binding = tb
+    W = small_bf16_pair(110)
+    T = inputs.as_f64(W)
+    P, ns, gamma, Tp, To = 2, 3, 4, 64, 32
+    B = P * ns
+    n_prompt = [64, 17]
+    n_own = [0, 5, 11, 2, 0, 20]
+    pending = [int(v) for v in inputs.token_ids(111, (B,), 512)]
+    rng = np.random.default_rng(112)
+    model = binding.TandemModel(W)
+    pst = binding.TandemState(model, P, Tp, gamma)
+    gst = binding.TandemState(model, B, To, gamma)
+    ost = orc.empty_state(T, B, Tp + To)
+    for key, M in (("KL", T["L"]), ("VL", T["L"]), ("Khat", T["S"]), ("Vhat", T["S"])):
+        for j in range(len(M["layers"])):
+            hp = inputs.normal(rng, (P, M["Hkv"], Tp, M["dh"]), 1.0, "bf16")
+            ho = inputs.normal(rng, (B, M["Hkv"], To, M["dh"]), 1.0, "bf16")
+            getattr(pst, key)[j].copy_(hp.to_torch())
+            getattr(gst, key)[j].copy_(ho.to_torch())
+            for b in range(P):
+                for s_ in range(ns):
+                    i, m = b * ns + s_, n_prompt[b]
+                    ost[key][j][i, :, :m] = hp.f64[b, :, :m]
+                    ost[key][j][i, :, m:m + To] = ho.f64[i]
+    pst.n.copy_(torch.tensor(n_prompt, dtype=torch.int32))
+    gst.n.copy_(torch.tensor(n_own, dtype=torch.int32))
+    gst.pending.copy_(torch.tensor(pending, dtype=torch.int32))
+    n_full = [n_prompt[i // ns] + n_own[i] for i in range(B)]
+    ost["n"][:] = n_full
+    ost["pending"][:] = pending
+    prompt = binding.TandemPrompt(pst, ns)
+    got = binding.tandem_decode_step(model, gst, gamma, aux=True, free_token=free, prompt=prompt)
+    torch.cuda.synchronize()
+    want = orc.decode_step(T, ost, gamma, free_token=free)
+    q = gamma + (1 if free else 0)
+    tol = 2e-2 * math.ceil(math.sqrt(2 + 1))
+    # rows computed from identical inputs on both sides: the first draft run and the first verified row
+    assert_rows_close(inputs.torch_to_f64(got["y_small"][:, 0]), want["y_small"][:, 0], tol=tol, what="y_small, first run")
+    assert_rows_close(inputs.torch_to_f64(got["x_large"][:, 0]), want["x_large"][:, 0], tol=tol, what="x_large, first row")
+    assert tokens_ok(got["draft"][:, 0].cpu().numpy(), want["logits_S"][:, 0])
+    assert tokens_ok(got["verify"][:, 0].cpu().numpy(), want["logits_L"][:, 0])
+    same = (got["draft"].cpu().numpy() == want["draft"]).all(axis=1)  # sequences whose drafts agree token for token
+    assert same.sum() >= B // 2, same
+    for i in np.nonzero(same)[0]:
+        assert_rows_close(inputs.torch_to_f64(got["y_small"][i]), want["y_small"][i], tol=tol, what=f"y_small[{i}]")
+        assert_rows_close(inputs.torch_to_f64(got["x_large"][i]), want["x_large"][i], tol=tol, what=f"x_large[{i}]")
+        if (got["verify"][i].cpu().numpy() == want["verify"][i]).all():
+            assert int(got["n_accepted"][i]) == int(want["n_accepted"][i])
+            np.testing.assert_array_equal(got["tokens"][i].cpu().numpy(), want["tokens"][i])
+            assert int(gst.n[i]) == int(ost["n"][i]) - n_prompt[i // ns]
+        lo = n_own[i]
+        for key in ("KL", "VL", "Khat", "Vhat"):
+            for j in range(len(getattr(gst, key))):
+                g = inputs.torch_to_f64(getattr(gst, key)[j][i, :, lo:lo + q])
+                o = ost[key][j][i, :, n_full[i]:n_full[i] + q]
+                assert_rows_close(g, o, tol=tol, what=f"{key}[{j}][{i}] new rows")
+    # the prompt caches are only read
+    assert int(pst.n[0]) == n_prompt[0] and int(pst.n[1]) == n_prompt[1]
+
+
+def test_decode_step_shared_prompt_equals_plain_step_on_copies_gpu(tb):
+    """GPU against GPU: the shared-prompt step and the ordinary step on materialised copies emit the same tokens and
+    the same state (fp32 model: exact integers)."""
+    torch, binding = tb
+    W = inputs.tandem_weights(
+        7, vocab=96, large=dict(d=128, n_layers=2, Hq=4, Hkv=2, dh=64, d_ff=256),
+        small=dict(d=64, n_layers=1, Hq=1, Hkv=1, dh=64, d_ff=128), ell=(2,), d_hidden=96, dtype="f32", w_std=0.4)
+    model = binding.TandemModel(W)
+    P, ns, gamma, Tp, To = 2, 2, 3, 16, 24
+    B = P * ns
+    prompts = torch.tensor(inputs.token_ids(3, (P, 9), 96), dtype=torch.int32).cuda()
+    pst = binding.TandemState(model, P, Tp, gamma)
+    binding.tandem_prefill(model, pst, prompts[:, :8].contiguous())          # 8 prompt tokens ingested, the 9th pending
+    full = binding.TandemState(model, B, Tp + To, gamma)
+    own = binding.TandemState(model, B, To, gamma)
+    for key in ("KL", "VL", "Khat", "Vhat"):
+        for j, t in enumerate(getattr(pst, key)):
+            getattr(full, key)[j][:, :, :Tp] = t.repeat_interleave(ns, dim=0)
+    full.n.fill_(8)
+    pend = prompts[:, 8].repeat_interleave(ns)
+    # give the samples different continuations: one forced step with different tokens per sample
+    forced = torch.tensor(inputs.token_ids(4, (B, gamma), 96), dtype=torch.int32).cuda()
+    full.pending.copy_(pend)
+    binding.tandem_decode_step(model, full, gamma, forced=forced)
+    for key in ("KL", "VL", "Khat", "Vhat"):
+        for j, t in enumerate(getattr(own, key)):
+            t[:, :, :gamma] = getattr(full, key)[j][:, :, 8:8 + gamma]
+    own.n.fill_(gamma)
+    own.pending.copy_(full.pending)
+    prompt = binding.TandemPrompt(pst, ns)
+    for _ in range(4):
+        a = binding.tandem_decode_step(model, own, gamma, prompt=prompt, free_token=True)
+        f = binding.tandem_decode_step(model, full, gamma, free_token=True)
+        torch.cuda.synchronize()
+        assert torch.equal(a["tokens"], f["tokens"]) and torch.equal(a["n_accepted"], f["n_accepted"])
+        assert torch.equal(own.n + 8, full.n) and torch.equal(own.pending, full.pending)
