@@ -332,11 +332,13 @@ int tandem_router_eval(const tandem_router_desc *r, const void *logits, const vo
 /* tandem_decode_step with the adaptive block length: gamma_max is the largest block.  Sequence b stops drafting
  * after the first draft token whose router probability is below tau: g[b] tokens, 1 <= g[b] <= gamma_max.  The
  * batch still runs gamma_max draft runs and verifies q = gamma_max (+ 1) rows per sequence - a stopped sequence
- * keeps its place, its later rows are computed and ignored, and the cache rows they write lie beyond the new n[b]
- * and are overwritten by the following steps - but acceptance, emitted tokens, n[b] and pending[b] are those of
- * a step with gamma = g[b] (the free token, if asked for, is M_L's token after d_g[b]).
+ * keeps its place, its later rows are ignored, and the cache rows they write lie beyond the new n[b] and are
+ * overwritten by the following steps - but its draft attention is skipped in the later runs (no cache traffic, zero
+ * rows), and acceptance, emitted tokens, n[b] and pending[b] are those of a step with gamma = g[b] (the free token,
+ * if asked for, is M_L's token after d_g[b]).
  *   n_drafted  optional device int32 [B]: g[b]
- *   router_p   optional device fp32 [B, gamma_max]: the router's p after every draft run (also past g[b])
+ *   router_p   optional device fp32 [B, gamma_max]: the router's p after every draft run; entries past g[b], like the
+ *              aux outputs of those runs, are unspecified
  * No forced tokens.  Everything else as in tandem_decode_step, including the workspace size. */
 int tandem_decode_step_adaptive(const tandem_model *m, const tandem_state_desc *state,
                                 const tandem_router_desc *router, int32_t gamma_max, int32_t flags,

@@ -23,6 +23,7 @@ struct RowsParams {
   int S_total, s_off;  // partial slots per row and this launch's first slot
   long long row_skip;  // q / out hold (q_len * Hq + row_skip) rows per sequence
   int n_off;           // added to nA[b]
+  const int32_t* skip;  // optional [B]: a sequence with skip[b] != 0 is not processed, its output rows are zero
   int mixed_gamma;     // > 0: all-positions small-model attention with this block length (see below)
   long long T_max;
   float scale_log2e;
@@ -76,6 +77,24 @@ __global__ __launch_bounds__(64 * NW) void attn_rows_kernel(RowsParams p) {
   const T* vB = p.vB ? (const T*)p.vB + offB : nullptr;
 
   const long long row0 = ((long long)b * p.q_len + r) * p.Hq + (long long)kvh * G;  // first query row of the group
+  if (p.skip && p.skip[b] != 0) {
+    // (adaptive block length: the sequence has stopped drafting) nothing is read; zero rows, or neutral partials
+    for (int idx = threadIdx.x; idx < G * DH; idx += 64 * NW) {
+      const long long row = row0 + idx / DH;
+      const int d = idx % DH;
+      if (p.S_total == 1) {
+        ((T*)p.out)[(row + b * p.row_skip) * DH + d] = from_f32<T>(0.f);
+      } else {
+        const long long ps = row * p.S_total + p.s_off + s;
+        p.part_o[ps * DH + d] = 0.f;
+        if (d == 0) {
+          p.part_ml[ps * 2 + 0] = TANDEM_NEG_BIG;
+          p.part_ml[ps * 2 + 1] = 0.f;
+        }
+      }
+    }
+    return;
+  }
   float qv[G][EPL];
 #pragma unroll
   for (int g = 0; g < G; ++g) {
@@ -298,6 +317,7 @@ int launch_attn_rows(const AttnArgs& a, hipStream_t st) {
   p.s_off = a.S_total > 0 ? a.s_off : 0;
   p.row_skip = a.q_rows > a.q_len ? (long long)(a.q_rows - a.q_len) * a.Hq : 0;
   p.n_off = a.n_off;
+  p.skip = a.skip;
   p.mixed_gamma = a.mixed == 3 ? (a.gamma > 0 ? a.gamma : 1) : 0;
   p.T_max = a.T_max;
   p.scale_log2e = a.scale * 1.4426950408889634f;

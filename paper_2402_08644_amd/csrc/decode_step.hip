@@ -229,7 +229,8 @@ StepPlan make_plan(const tandem_model* m, int B, int gamma, int64_t T_max, int g
   p.ints = take(sizeof(int32_t) * (4 * M + B));  // + stop[B] of the adaptive block length
   // attention scratch: the larger of the draft and the block call
   {
-    const int Sd = attn_rows_splits(B, S.Hkv, 1, S.Hq / S.Hkv, T_max, gamma_max, nullptr);
+    int Sd = attn_rows_splits(B, S.Hkv, 1, S.Hq / S.Hkv, T_max, gamma_max, nullptr);
+    if (Sd < 4) Sd = 4;  // the adaptive step cuts the draft attention in at least four (see attn_call)
     size_t a = Sd > 1 ? align256((size_t)B * S.Hq * Sd * 2 * 4) + (size_t)B * S.Hq * Sd * S.dh * 4 : 0;
     const bool mfma = m->d.dtype == TANDEM_BF16 && L.dh == 128;
     // block calls cover at most TANDEM_MAX_QLEN rows per sequence (longer prompt chunks run in sub-blocks)
@@ -319,7 +320,7 @@ struct Ctx {
 // (block mode: those rows sit at positions nA[b] + row0 ..)
 int attn_call(const Ctx& c, const tandem_decoder_desc& D, const void* q, const void* kA, const void* vA, const int32_t* nA,
               const void* kB, const void* vB, const int32_t* nB, int causal, int q_len, void* out, int row0 = 0,
-              int q_rows = 0, const void* kP = nullptr, const void* vP = nullptr) {
+              int q_rows = 0, const void* kP = nullptr, const void* vP = nullptr, const int32_t* skip = nullptr) {
   if (c.pr) {
     // several samples per prompt: kP / vP hold the prompts' rows of this layer, kA / vA each sample's later rows
     tandem_attn_desc d{c.st->B / c.pr->samples, D.Hq, D.Hkv, D.dh, c.pr->T_prompt, causal ? 0 : c.st->gamma_max,
@@ -332,11 +333,12 @@ int attn_call(const Ctx& c, const tandem_decoder_desc& D, const void* q, const v
                                     aws, c.plan.attn_ws_bytes, c.stream);
   }
   AttnArgs a{};
-  const size_t skip = (size_t)row0 * D.Hq * D.dh * elsize(c.dtype);
-  q = (const char*)q + skip;
-  out = (char*)out + skip;
+  const size_t row0_bytes = (size_t)row0 * D.Hq * D.dh * elsize(c.dtype);
+  q = (const char*)q + row0_bytes;
+  out = (char*)out + row0_bytes;
   a.q_rows = q_rows;
   a.n_off = row0;
+  a.skip = skip;
   a.q = q;
   a.kA = kA;
   a.vA = vA;
@@ -358,6 +360,13 @@ int attn_call(const Ctx& c, const tandem_decoder_desc& D, const void* q, const v
   const bool mfma = causal && attn_block_supported(a);
   a.S = mfma ? attn_block_splits(a.B, a.Hkv, q_len, a.Hq / a.Hkv, a.T_max, &a.wide)
              : attn_rows_splits(a.B, a.Hkv, q_len, a.Hq / a.Hkv, a.T_max, causal ? 0 : c.st->gamma_max, &a.wide);
+  if (skip && !mfma && a.S * (a.wide ? 2 : 1) < 4) {
+    // Sequences may drop out of this call (adaptive block length): with one workgroup per sequence and KV head the
+    // remaining ones would stream no faster (a single compute unit pulls about 25 GB/s), so the context is cut in
+    // four and the time follows the number of sequences still drafting.
+    a.S = 4;
+    a.wide = 0;
+  }
   if (a.S > 1) {
     const size_t rows = (size_t)a.B * q_len * a.Hq;
     a.part_ml = c.at<float>(c.plan.attn_ws);
@@ -686,7 +695,8 @@ int decode_step_impl(const tandem_model* m, const tandem_state_desc* state, cons
     for (int j = 0; j < S.n_layers; ++j) {
       auto attn_only = [&]() -> int {
         return attn_call(c, S, q, state->Khat[j], state->Vhat[j], state->n, state->Kcur[j], state->Vcur[j],
-                         ncur + (size_t)r * B, 0, 1, att, 0, 0, c.pr ? c.pr->Khp[j] : nullptr, c.pr ? c.pr->Vhp[j] : nullptr);
+                         ncur + (size_t)r * B, 0, 1, att, 0, 0, c.pr ? c.pr->Khp[j] : nullptr, c.pr ? c.pr->Vhp[j] : nullptr,
+                         stop);  // a sequence the router has stopped costs no attention traffic in the later runs
       };
       if (c.plan.fused) {
         auto finish_qkv = [&](const float* part, int splits) -> int {
@@ -711,7 +721,8 @@ int decode_step_impl(const tandem_model* m, const tandem_state_desc* state, cons
       TRY(copy2d((char*)aux->logits_S + (size_t)r * S.vocab * es, (size_t)gamma * S.vocab * es, c.at<>(c.plan.logits),
                  S.vocab * es, S.vocab * es, B, c.stream));
     // adaptive block length (Sec. 3.1): the router sees this run's distribution; a sequence it stops keeps its
-    // place in the batch (the later runs compute rows that nobody reads) and is verified on its shorter block
+    // place in the batch (the later runs skip its attention and compute rows that nobody reads) and is verified on
+    // its shorter block
     if (router)
       TRY(launch_router(router, c.at<>(c.plan.logits), S.emb, B, S.vocab, S.d, r, stop, router_p ? router_p + r : nullptr,
                         gamma, c.stream));

@@ -41,6 +41,8 @@ struct AttnArgs {
   // A call may cover q_len of the q_rows rows that q and out hold per sequence (q / out then point at the first
   // covered row of sequence 0): q_rows = 0 means q_len.  n_off is added to every nA[b].
   int q_rows, n_off;
+  // attn_rows kernels only, optional [B]: sequences with skip[b] != 0 are not processed (zero output rows)
+  const int32_t* skip;
 };
 
 // number of context splits; *wide (optional) = 1 when the workgroups should have eight wavefronts (AttnArgs::wide)

@@ -108,7 +108,6 @@ def test_adaptive_step_tiny_config_fp32(tb, free):
     for b in range(B):
         g = int(want["n_drafted"][b])
         np.testing.assert_allclose(gp[b, :g], want["router_p"][b, :g], rtol=2e-3)
-        np.testing.assert_allclose(gp[b], probe["router_p"][b], rtol=2e-3)  # the batch keeps running past g
         for key, M in (("KL", T["L"]), ("Khat", T["S"]), ("VL", T["L"]), ("Vhat", T["S"])):
             for j in range(len(M["layers"])):
                 rows = int(ost["n"][b])
