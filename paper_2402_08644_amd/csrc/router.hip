@@ -32,8 +32,9 @@ __global__ __launch_bounds__(RT_THREADS) void router_kernel(const T* __restrict_
                                                             long long p_stride) {
   extern __shared__ float f[];  // features
   __shared__ float red[RT_WAVES], red2[RT_WAVES];
-  __shared__ int redi[RT_WAVES];
   __shared__ int ids[TANDEM_ROUTER_MAX_K];
+  __shared__ float cv[RT_WAVES * TANDEM_ROUTER_MAX_K];  // per-wavefront candidates of the top-k search
+  __shared__ int ci[RT_WAVES * TANDEM_ROUTER_MAX_K];
   __shared__ float bc[2];
   constexpr int NPT = 32;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -99,11 +100,24 @@ __global__ __launch_bounds__(RT_THREADS) void router_kernel(const T* __restrict_
   __syncthreads();
   const float Z = bc[1];
 
-  // k rounds of argmax over the tokens not yet taken (REG: bit c of `mine` marks this lane's c-th value as taken)
+  // The k largest logits in two levels: every wavefront finds the k largest of its own 64 x npt values (k rounds of a
+  // wavefront-wide argmax, no workgroup barrier; REG: bit c of `mine` marks this lane's c-th value as taken), then
+  // wavefront 0 finds the k largest of the 16 k candidates.  Equal logits go by the lower id at both levels.
+  constexpr int NONE = 0x7fffffff;
+  auto wave_argmax = [&](float& best, int& bi) {
+    for (int off = 32; off >= 1; off >>= 1) {
+      const float ov = __shfl_xor(best, off);
+      const int oi = __shfl_xor(bi, off);
+      if (oi != NONE && (bi == NONE || ov > best || (ov == best && oi < bi))) {
+        best = ov;
+        bi = oi;
+      }
+    }
+  };
   uint32_t mine = 0;
   for (int t = 0; t < k; ++t) {
     float best = -INFINITY;
-    int bi = 0x7fffffff;
+    int bi = NONE;
 #pragma unroll
     for (int c = 0; c < npt; ++c) {
       const int i = c * RT_THREADS + tid;
@@ -111,39 +125,49 @@ __global__ __launch_bounds__(RT_THREADS) void router_kernel(const T* __restrict_
       if (REG) {
         taken |= (mine >> c) & 1u;
       } else {
-        for (int u = 0; u < t; ++u) taken |= ids[u] == i;
+        for (int u = 0; u < t; ++u) taken |= ci[w * TANDEM_ROUTER_MAX_K + u] == i;
       }
       const float v = val(c);
-      if (!taken && (bi == 0x7fffffff || v > best)) {  // ids grow with c: a later equal value does not replace
+      if (!taken && (bi == NONE || v > best)) {  // ids grow with c: a later equal value does not replace
         best = v;
         bi = i;
       }
     }
-    for (int off = 32; off >= 1; off >>= 1) {
-      const float ov = __shfl_xor(best, off);
-      const int oi = __shfl_xor(bi, off);
-      if (oi != 0x7fffffff && (bi == 0x7fffffff || ov > best || (ov == best && oi < bi))) {
-        best = ov;
-        bi = oi;
-      }
-    }
+    wave_argmax(best, bi);
     if (lane == 0) {
-      red[w] = best;
-      redi[w] = bi;
+      cv[w * TANDEM_ROUTER_MAX_K + t] = best;
+      ci[w * TANDEM_ROUTER_MAX_K + t] = bi;
     }
-    __syncthreads();
-    if (tid == 0) {
-      for (int i = 1; i < RT_WAVES; ++i)
-        if (redi[i] != 0x7fffffff && (bi == 0x7fffffff || red[i] > best || (red[i] == best && redi[i] < bi))) {
-          best = red[i];
-          bi = redi[i];
-        }
-      ids[t] = bi;
-      f[((1 + t) & 7) * ((1 + k + k * d + 7) / 8 + 1) + ((1 + t) >> 3)] = expf(best - m) / Z;  // fi(1 + t)
-    }
-    __syncthreads();
-    if (REG && (ids[t] & (RT_THREADS - 1)) == tid) mine |= 1u << (ids[t] / RT_THREADS);
+    if (REG && bi != NONE && (bi & (RT_THREADS - 1)) == tid) mine |= 1u << (bi / RT_THREADS);
   }
+  __syncthreads();
+  if (w == 0) {
+    // candidate slots lane and lane + 64 of the 16 x MAX_K table (rounds t >= k of a wavefront were not filled)
+    float v0 = -INFINITY, v1 = -INFINITY;
+    int i0 = NONE, i1 = NONE;
+    if ((lane & (TANDEM_ROUTER_MAX_K - 1)) < k) {
+      v0 = cv[lane];
+      i0 = ci[lane];
+      v1 = cv[lane + 64];
+      i1 = ci[lane + 64];
+    }
+    for (int t = 0; t < k; ++t) {
+      float best = v0;
+      int bi = i0;
+      if (i1 != NONE && (bi == NONE || v1 > best || (v1 == best && i1 < bi))) {
+        best = v1;
+        bi = i1;
+      }
+      wave_argmax(best, bi);
+      if (lane == 0) {
+        ids[t] = bi;
+        f[((1 + t) & 7) * ((1 + k + k * d + 7) / 8 + 1) + ((1 + t) >> 3)] = expf(best - m) / Z;  // fi(1 + t)
+      }
+      if (i0 == bi) i0 = NONE;
+      if (i1 == bi) i1 = NONE;
+    }
+  }
+  __syncthreads();
 
   // Feature j lives at f[fi(j)], fi(j) = (j % 8) * FS + j / 8: lanes that take consecutive 16-byte pieces of a row
   // of W1 (8 or 4 consecutive features each) then read consecutive LDS words, whatever the row's alignment.
@@ -154,55 +178,58 @@ __global__ __launch_bounds__(RT_THREADS) void router_kernel(const T* __restrict_
     f[fi(1 + k + idx)] = to_f32<T>(emb[(long long)ids[idx / d] * d + idx % d]);
   __syncthreads();
 
-  // hidden layer: the units are dealt round-robin to the wavefronts, eight at a time per wavefront (eight
-  // independent rows of W1 in flight per lane); each row is read with 16-byte loads over its aligned middle part and element by
-  // element over the up to 15 bytes before and after it; each wavefront adds its share of the output sum
+  // hidden layer: unit i belongs to wavefront i % 16, eight units at a time per wavefront (eight independent rows of
+  // W1 in flight per lane).  Rows 16 apart start 32 F bytes apart, a multiple of 16: all rows of a wavefront have the
+  // same alignment, so they share the split into an aligned middle part read with 16-byte loads (each lane's 8 or 4
+  // features read from LDS once for all eight rows) and up to 15 bytes before and after it read element by element.
   constexpr int UN = 8, VEC = 16 / (int)sizeof(T);
+  int head = (int)(((16 - ((uintptr_t)(W1 + (long long)w * F) & 15)) & 15) / sizeof(T));
+  head = head < F ? head : F;
+  const int nvec = (F - head) / VEC;
+  const int tail = head + nvec * VEC + lane;  // this lane's element after the middle part (if < F)
   float zacc = 0.f;
   for (int i0 = w; i0 < hidden; i0 += RT_WAVES * UN) {
     float dot[UN];
     const T* wr[UN];
-    int head[UN], nvec[UN], nvmax = 0;
 #pragma unroll
     for (int u = 0; u < UN; ++u) {
       const int i = i0 + u * RT_WAVES;
       wr[u] = W1 + (long long)(i < hidden ? i : i0) * F;  // a unit past the end re-reads a valid row, not used
-      head[u] = (int)(((16 - ((uintptr_t)wr[u] & 15)) & 15) / sizeof(T));
-      head[u] = head[u] < F ? head[u] : F;
-      nvec[u] = (F - head[u]) / VEC;
-      nvmax = nvec[u] > nvmax ? nvec[u] : nvmax;
       dot[u] = 0.f;
     }
-    for (int v = lane; v < nvmax; v += 64) {
+    for (int v = lane; v < nvec; v += 64) {
+      const int j = head + v * VEC;
       uint4 raw[UN];
 #pragma unroll
-      for (int u = 0; u < UN; ++u) {
-        const int vv = v < nvec[u] ? v : 0;  // (rows differ by at most one piece: the odd one re-reads piece 0)
-        raw[u] = *reinterpret_cast<const uint4*>(wr[u] + head[u] + vv * VEC);
-      }
+      for (int u = 0; u < UN; ++u) raw[u] = *reinterpret_cast<const uint4*>(wr[u] + j);
+      float fv[VEC];
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) fv[e] = f[fi(j + e)];
 #pragma unroll
       for (int u = 0; u < UN; ++u) {
-        if (v >= nvec[u]) continue;
-        const int j = head[u] + v * VEC;
         const uint32_t rw[4] = {raw[u].x, raw[u].y, raw[u].z, raw[u].w};
         float acc = dot[u];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           if (sizeof(T) == 2) {
-            acc = fmaf(bf16lo_to_f32(rw[e]), f[fi(j + 2 * e)], acc);
-            acc = fmaf(bf16hi_to_f32(rw[e]), f[fi(j + 2 * e + 1)], acc);
+            acc = fmaf(bf16lo_to_f32(rw[e]), fv[(2 * e) % VEC], acc);
+            acc = fmaf(bf16hi_to_f32(rw[e]), fv[(2 * e + 1) % VEC], acc);
           } else {
-            acc = fmaf(__uint_as_float(rw[e]), f[fi(j + e)], acc);
+            acc = fmaf(__uint_as_float(rw[e]), fv[e % VEC], acc);
           }
         }
         dot[u] = acc;
       }
     }
+    if (lane < head) {
+      const float fl = f[fi(lane)];
 #pragma unroll
-    for (int u = 0; u < UN; ++u) {
-      if (lane < head[u]) dot[u] = fmaf(to_f32<T>(wr[u][lane]), f[fi(lane)], dot[u]);
-      const int tail = head[u] + nvec[u] * VEC + lane;
-      if (tail < F) dot[u] = fmaf(to_f32<T>(wr[u][tail]), f[fi(tail)], dot[u]);
+      for (int u = 0; u < UN; ++u) dot[u] = fmaf(to_f32<T>(wr[u][lane]), fl, dot[u]);
+    }
+    if (tail < F) {
+      const float ft = f[fi(tail)];
+#pragma unroll
+      for (int u = 0; u < UN; ++u) dot[u] = fmaf(to_f32<T>(wr[u][tail]), ft, dot[u]);
     }
 #pragma unroll
     for (int u = 0; u < UN; ++u) {
