@@ -38,6 +38,8 @@ def dev_router(R):
         (3, 777, 48, 1, 7, "f32"),         # odd sizes, a single top token, fewer units than wavefronts
         (4, 4096, 256, 8, 100, "bf16"),    # the largest k
         (32, 32768, 1024, 4, 256, "bf16"),  # C3's small model: one call of the decode step
+        (3, 40000, 32, 3, 8, "f32"),        # more than 32768 tokens: the logits row does not fit the registers
+        (3, 70001, 16, 8, 20, "bf16"),
     ],
 )
 def test_router_eval_parity(tb, rows, vocab, d, k, hidden, dtype):
@@ -53,7 +55,7 @@ def test_router_eval_parity(tb, rows, vocab, d, k, hidden, dtype):
     got = binding.tandem_router_eval(dev_router(R), logits.to_torch(), emb.to_torch())
     torch.cuda.synchronize()
     R64 = inputs.as_f64(R)
-    n_check = rows if vocab <= 4096 else 4   # the oracle's top-k scan is a Python loop
+    n_check = rows if vocab <= 4096 or rows <= 4 else 4   # the oracle's top-k scan is a Python loop
     want = np.array([orc.router_prob(R64, logits.f64[i], emb.f64) for i in range(n_check)])
     got = got.cpu().numpy().astype(np.float64)[:n_check]
     assert np.isfinite(got).all()
