@@ -177,25 +177,39 @@ def project_case(seed, M, d_L, d_hidden, d_S, dtype="bf16", x_std=1.0, w_std=0.0
 
 
 # ------------------------------------------------------------- model weights
-def decoder_weights(rng, vocab, d, n_layers, Hq, Hkv, dh, d_ff, dtype, w_std=0.02):
+def _gain(rng, shape, gain_std, dtype):
+    """RMSNorm gain: ones, or 1 + gain_std * N(0, 1) when gain_std > 0."""
+    if gain_std == 0.0:
+        return ones(shape, dtype)
+    return HostTensor(np.float32(1.0) + rng.standard_normal(shape, dtype=np.float32) * np.float32(gain_std), dtype)
+
+
+def _bias(rng, shape, bias_std, dtype):
+    return zeros(shape, dtype) if bias_std == 0.0 else normal(rng, shape, bias_std, dtype)
+
+
+def decoder_weights(rng, vocab, d, n_layers, Hq, Hkv, dh, d_ff, dtype, w_std=0.02, gain_std=0.0, bias_std=0.0):
+    """gain_std / bias_std = 0 give the benchmark configurations' gains 1 and biases 0 (no random numbers drawn for
+    them, so the weights of a seed do not depend on the option); > 0 gives gains 1 + gain_std N(0,1), biases
+    N(0, bias_std)."""
     def lay():
         return {
-            "g_attn": ones((d,), dtype),
+            "g_attn": _gain(rng, (d,), gain_std, dtype),
             "Wq": normal(rng, (Hq * dh, d), w_std, dtype),
             "Wk": normal(rng, (Hkv * dh, d), w_std, dtype),
             "Wv": normal(rng, (Hkv * dh, d), w_std, dtype),
             "Wo": normal(rng, (d, Hq * dh), w_std, dtype),
-            "g_mlp": ones((d,), dtype),
+            "g_mlp": _gain(rng, (d,), gain_std, dtype),
             "W1": normal(rng, (d_ff, d), w_std, dtype),
-            "b1": zeros((d_ff,), dtype),
+            "b1": _bias(rng, (d_ff,), bias_std, dtype),
             "W2": normal(rng, (d, d_ff), w_std, dtype),
-            "b2": zeros((d,), dtype),
+            "b2": _bias(rng, (d,), bias_std, dtype),
         }
 
     return {
         "emb": normal(rng, (vocab, d), w_std, dtype),
         "layers": [lay() for _ in range(n_layers)],
-        "g_final": ones((d,), dtype),
+        "g_final": _gain(rng, (d,), gain_std, dtype),
         "W_out": normal(rng, (vocab, d), w_std, dtype),
         "Hq": Hq,
         "Hkv": Hkv,
@@ -206,34 +220,38 @@ def decoder_weights(rng, vocab, d, n_layers, Hq, Hkv, dh, d_ff, dtype, w_std=0.0
     }
 
 
-def tandem_weights(seed, vocab, large, small, ell, d_hidden, dtype, act="gelu", w_std=0.02, eps=1e-6):
+def tandem_weights(seed, vocab, large, small, ell, d_hidden, dtype, act="gelu", w_std=0.02, eps=1e-6, gain_std=0.0,
+                   bias_std=0.0):
     """A random-init Tandem pair.  ``large``/``small`` are dicts with keys
     d, n_layers, Hq, Hkv, dh, d_ff.  ``ell[j]`` in [0, L_L] is the large layer whose
-    output small layer j reads.  d_hidden == 0 gives linear FF_Tandem maps."""
+    output small layer j reads.  d_hidden == 0 gives linear FF_Tandem maps.
+    gain_std / bias_std: see decoder_weights; they also apply to the FF_Tandem biases."""
     rng = np.random.default_rng(seed)
-    L = decoder_weights(rng, vocab, dtype=dtype, w_std=w_std, **large)
-    S = decoder_weights(rng, vocab, dtype=dtype, w_std=w_std, **small)
+    L = decoder_weights(rng, vocab, dtype=dtype, w_std=w_std, gain_std=gain_std, bias_std=bias_std, **large)
+    S = decoder_weights(rng, vocab, dtype=dtype, w_std=w_std, gain_std=gain_std, bias_std=bias_std, **small)
     ff = []
     for _ in range(small["n_layers"]):
         if d_hidden == 0:
-            ff.append({"W": normal(rng, (small["d"], large["d"]), w_std, dtype), "b": zeros((small["d"],), dtype)})
+            ff.append({"W": normal(rng, (small["d"], large["d"]), w_std, dtype),
+                       "b": _bias(rng, (small["d"],), bias_std, dtype)})
         else:
             ff.append(
                 {
                     "W1": normal(rng, (d_hidden, large["d"]), w_std, dtype),
-                    "b1": zeros((d_hidden,), dtype),
+                    "b1": _bias(rng, (d_hidden,), bias_std, dtype),
                     "W2": normal(rng, (small["d"], d_hidden), w_std, dtype),
-                    "b2": zeros((small["d"],), dtype),
+                    "b2": _bias(rng, (small["d"],), bias_std, dtype),
                     "act": act,
                 }
             )
     return {"L": L, "S": S, "ell": list(ell), "ff": ff, "eps": eps, "dtype": dtype}
 
 
-def tiny_tandem(seed=0, dtype="f32"):
+def tiny_tandem(seed=0, dtype="f32", gain_std=0.0, bias_std=0.0):
     """The tiny full-forward configuration: vocab 1000; large 4 layers d=256, 4 heads
     of 64, MLP 1024; small 2 layers d=128, 2 heads of 64, MLP 512, reading large
-    layers 2 and 4 through a 256->512->128 MLP; weights N(0, 0.02), biases 0, gains 1."""
+    layers 2 and 4 through a 256->512->128 MLP; weights N(0, 0.02), biases 0, gains 1
+    (gain_std / bias_std > 0: the same shapes with random gains and biases, for tests)."""
     return tandem_weights(
         seed,
         vocab=1000,
@@ -242,6 +260,8 @@ def tiny_tandem(seed=0, dtype="f32"):
         ell=(2, 4),
         d_hidden=512,
         dtype=dtype,
+        gain_std=gain_std,
+        bias_std=bias_std,
     )
 
 

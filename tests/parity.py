@@ -11,6 +11,10 @@ import numpy as np
 
 TOL = 2e-2
 
+# every comparison made through assert_rows_close in this process: (what, tol, worst max-norm error, worst l2 error);
+# tests/conftest.py writes the worst case per label to gpurun_out/parity_observed.json when the session ends
+OBSERVED = []
+
 
 def row_errors(got, want):
     got = np.asarray(got, np.float64).reshape(-1, got.shape[-1])
@@ -28,6 +32,7 @@ def assert_rows_close(got, want, tol=TOL, what=""):
     assert got.shape == want.shape, (got.shape, want.shape)
     assert np.isfinite(np.asarray(got, np.float64)).all(), f"{what}: non-finite values in the GPU result"
     e_inf, e_l2 = row_errors(got, want)
+    OBSERVED.append((what, float(tol), float(e_inf.max()), float(e_l2.max())))
     worst = int(np.argmax(e_inf))
     assert e_inf.max() <= tol, f"{what}: row {worst} max-norm relative error {e_inf.max():.3e} > {tol}"
     assert e_l2.max() <= tol, f"{what}: l2 relative error {e_l2.max():.3e} > {tol}"

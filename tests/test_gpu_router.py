@@ -85,7 +85,7 @@ def test_adaptive_step_tiny_config_fp32(tb, free):
     """Tiny configuration, fp32, gamma_max = 4, batch of 4 on random caches: block lengths, tokens, state and the
     cache rows below the new n are the oracle's."""
     torch, binding = tb
-    W = inputs.tiny_tandem(seed=0, dtype="f32")
+    W = inputs.tiny_tandem(seed=0, dtype="f32", gain_std=0.3, bias_std=0.02)  # random gains, non-zero biases
     T = inputs.as_f64(W)
     B, T_max, gmax = 4, 64, 4
     n, pending = [40, 7, 0, 21], [3, 500, 77, 999]

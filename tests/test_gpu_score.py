@@ -50,9 +50,9 @@ def run_score(tb, W, toks, gamma, chunks, T_max):
     return np.concatenate(lg, 1), np.concatenate(ys, 1), np.concatenate(gr, 1)
 
 
-@pytest.mark.parametrize("gamma,chunks", [(2, [32, 32, 32, 32]), (3, [7, 32, 1, 24])])
-def test_score_tiny_config_fp32_equals_teacher_forced_forward(tb, gamma, chunks):
-    W = inputs.tiny_tandem(seed=0, dtype="f32")
+@pytest.mark.parametrize("gamma,chunks,gains", [(2, [32, 32, 32, 32], False), (3, [7, 32, 1, 24], True)])
+def test_score_tiny_config_fp32_equals_teacher_forced_forward(tb, gamma, chunks, gains):
+    W = inputs.tiny_tandem(seed=0, dtype="f32", gain_std=0.3 if gains else 0.0, bias_std=0.02 if gains else 0.0)
     T = inputs.as_f64(W)
     S = sum(chunks)
     toks = inputs.token_ids(1, (1, S), 1000)

@@ -16,9 +16,11 @@ from paper_2402_08644_amd import inputs
 GOLD = os.path.join(os.path.dirname(__file__), "golden")
 
 
-def small_pair(seed=0, d_hidden=24, w_std=0.3, Hkv_L=2):
+def small_pair(seed=0, d_hidden=24, w_std=0.3, Hkv_L=2, gain_std=0.3, bias_std=0.2):
     """A very small Tandem pair with large weights spread (std 0.3) so that attention
-    weights are far from uniform and indexing mistakes change the output visibly."""
+    weights are far from uniform and indexing mistakes change the output visibly.  RMSNorm
+    gains 1 + 0.3 N(0,1) and biases N(0, 0.2) by default, so that a dropped or swapped gain
+    or bias changes every output (gain_std = bias_std = 0 is the benchmark configurations' form)."""
     W = inputs.tandem_weights(
         seed,
         vocab=40,
@@ -28,6 +30,8 @@ def small_pair(seed=0, d_hidden=24, w_std=0.3, Hkv_L=2):
         d_hidden=d_hidden,
         dtype="f32",
         w_std=w_std,
+        gain_std=gain_std,
+        bias_std=bias_std,
     )
     return inputs.as_f64(W)
 
@@ -148,17 +152,63 @@ def torch_tandem_forward(T, tokens, gamma):
         else:
             yh = F.linear(F.gelu(F.linear(src, t(ff["W1"]), t(ff["b1"]))), t(ff["W2"]), t(ff["b2"]))
         y = block(T["S"], lay, y, kv_src_extra=yh, mask=mask)
-    return y.numpy(), xs[-1].numpy()
+
+    def head(M, h):  # final RMSNorm, then the untied output head
+        return F.linear(F.rms_norm(h, (h.shape[-1],), t(M["g_final"]), eps=eps), t(M["W_out"])).numpy()
+
+    return y.numpy(), xs[-1].numpy(), head(T["S"], y), head(T["L"], xs[-1])
 
 
+@pytest.mark.parametrize("gains", [True, False])
 @pytest.mark.parametrize("gamma,d_hidden", [(1, 24), (2, 24), (3, 0), (5, 24)])
-def test_tandem_forward_vs_torch_mask_formulation(gamma, d_hidden):
-    T = small_pair(seed=gamma, d_hidden=d_hidden)
+def test_tandem_forward_vs_torch_mask_formulation(gamma, d_hidden, gains):
+    """Random RMSNorm gains and non-zero biases everywhere (gains) next to gains 1 / biases 0; representations
+    and both models' logits (final norm + untied head)."""
+    T = small_pair(seed=gamma, d_hidden=d_hidden) if gains else small_pair(seed=gamma, d_hidden=d_hidden, gain_std=0.0, bias_std=0.0)
     toks = inputs.token_ids(gamma, (13,), 40)
     got = orc.tandem_forward(T, toks, gamma)
-    want_y, want_x = torch_tandem_forward(T, toks, gamma)
+    want_y, want_x, want_lS, want_lL = torch_tandem_forward(T, toks, gamma)
     np.testing.assert_allclose(got["y"], want_y, rtol=1e-9, atol=1e-11)
     np.testing.assert_allclose(got["xs"][-1], want_x, rtol=1e-9, atol=1e-11)
+    np.testing.assert_allclose(got["logits_S"], want_lS, rtol=1e-9, atol=1e-11)
+    np.testing.assert_allclose(got["logits_L"], want_lL, rtol=1e-9, atol=1e-11)
+    if gains:  # the gains and biases matter: the gains-1 / bias-0 pair of the same seed gives other values
+        assert np.abs(np.asarray(T["S"]["g_final"]) - 1.0).max() > 0.1 and np.abs(T["S"]["layers"][0]["b2"]).max() > 0.05
+
+
+def test_logits_of_against_torch_rms_norm_and_linear():
+    """The output head alone: final RMSNorm with a random gain (a positive row scale would leave the argmax alone,
+    a per-feature gain does not), then the untied head; against torch's rms_norm + linear, and the effect of the
+    gain is visible in the greedy tokens."""
+    rng = np.random.default_rng(3)
+    d, V, rows = 24, 50, 9
+    M = {"g_final": 1.0 + 0.5 * rng.standard_normal(d), "W_out": rng.standard_normal((V, d))}
+    x = 3.0 * rng.standard_normal((rows, d))
+    eps = 1e-3
+    got = orc.logits_of(M, x, eps)
+    t = lambda a: torch.from_numpy(np.asarray(a, np.float64))
+    want = F.linear(F.rms_norm(t(x), (d,), t(M["g_final"]), eps=eps), t(M["W_out"])).numpy()
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-13)
+    # by hand for one row: x / sqrt(mean(x^2) + eps) * g, then W_out
+    r = x[4] / np.sqrt((x[4] ** 2).mean() + eps) * M["g_final"]
+    np.testing.assert_allclose(got[4], M["W_out"] @ r, rtol=1e-12, atol=1e-13)
+    # without the gain (or without the norm's gain applied per feature) some greedy tokens differ
+    plain = orc.logits_of({"g_final": np.ones(d), "W_out": M["W_out"]}, x, eps)
+    assert (plain.argmax(axis=1) != got.argmax(axis=1)).any()
+
+
+def test_argmax_lowest_ties_go_to_the_lowest_id():
+    assert orc.argmax_lowest(np.array([1.0, 3.0, 3.0, 2.0, 3.0])) == 1
+    assert orc.argmax_lowest(np.array([5.0, 5.0])) == 0
+    assert orc.argmax_lowest(np.array([-np.inf, -1.0, -1.0])) == 1
+    assert orc.argmax_lowest(np.zeros(7)) == 0
+    v = np.array([0.1, 0.7, 0.7 + 1e-17, 0.2])  # equal in fp64 after rounding: still the lower id
+    assert v[1] == v[2] and orc.argmax_lowest(v) == 1
+    rng = np.random.default_rng(0)
+    for _ in range(50):  # brute force: first index attaining the maximum
+        v = rng.integers(0, 4, size=rng.integers(1, 12)).astype(np.float64)
+        want = next(i for i in range(len(v)) if v[i] == max(v))
+        assert orc.argmax_lowest(v) == want
 
 
 def test_tiny_config_forward_vs_torch_mask_formulation():
@@ -166,8 +216,9 @@ def test_tiny_config_forward_vs_torch_mask_formulation():
     T = inputs.as_f64(inputs.tiny_tandem(seed=0, dtype="f32"))
     toks = inputs.token_ids(0, (128,), 1000)
     got = orc.tandem_forward(T, toks, 2)
-    want_y, _ = torch_tandem_forward(T, toks, 2)
+    want_y, _, want_lS, _ = torch_tandem_forward(T, toks, 2)
     np.testing.assert_allclose(got["y"], want_y, rtol=1e-9, atol=1e-11)
+    np.testing.assert_allclose(got["logits_S"], want_lS, rtol=1e-9, atol=1e-11)
 
 
 # ----------------------------------------------------------------- invariants
@@ -535,7 +586,7 @@ def test_adaptive_block_length_limits_and_per_sequence_equivalence(free):
                 np.testing.assert_array_equal(x, y)
     # a threshold inside the spread of this router's probabilities: mixed block lengths
     probe = orc.decode_step(T, mk(), gmax, free_token=free, router=R, tau=0.0)["router_p"]
-    tau = float(np.median(probe))
+    tau = float(np.median(probe[:, 0]))  # half of the sequences stop after their first token, the others go on
     sa = mk()
     a = orc.decode_step(T, sa, gmax, free_token=free, router=R, tau=tau)
     assert len(set(a["n_drafted"])) > 1, a["n_drafted"]
