@@ -8,9 +8,10 @@
  *
  * General conventions
  *   - Every pointer named "device" is GPU memory owned by the caller; the library never
- *     allocates or frees device memory and keeps no global state.  Descriptor structs and
- *     the pointer arrays inside them are host memory, read during the call only (the model
- *     handle copies what it needs).
+ *     allocates or frees device memory, never synchronises a stream or the device, and keeps
+ *     no mutable global state beyond one-time, thread-safe kernel attribute set-up.  Descriptor
+ *     structs and the pointer arrays inside them are host memory, read during the call only
+ *     (the model handle copies what it needs).
  *   - All entry points enqueue work on the given HIP stream (a hipStream_t passed as
  *     void*, NULL = default stream) and return without synchronising.
  *   - Return value: a tandem_status.  All argument checks happen on the host before any
@@ -54,7 +55,8 @@ typedef enum { TANDEM_ACT_NONE = 0, TANDEM_ACT_GELU = 1 /* exact erf form */, TA
 /* Shape of one attention layer's caches.
  *   caches:            [B, Hkv, T_max, dh]      (large K/V, or the large-derived K_hat/V_hat)
  *   own-block scratch: [B, Hkv, gamma_max, dh]  (K/V the small model computed for the current block)
- * Hq must be a multiple of Hkv (G = Hq/Hkv query heads share a KV head; G <= 8).
+ * Hq must be a multiple of Hkv; G = Hq/Hkv query heads share a KV head and must be 1, 2, 4 or 8
+ * (other group sizes return TANDEM_ERR_UNSUPPORTED).
  * dh is 64 or 128.  scale is the score multiplier, normally 1/sqrt(dh). */
 typedef struct {
   int32_t B, Hq, Hkv, dh;
@@ -211,15 +213,8 @@ typedef struct {
   const tandem_ff_desc *ff;  /* host [S.n_layers]; ff[j].d_L == L.d, ff[j].d_S == S.d          */
   float rms_eps;
   int32_t dtype;             /* tandem_dtype of every weight, cache and activation             */
-  int32_t flags;             /* TANDEM_MODEL_* bits                                            */
+  int32_t flags;             /* reserved, must be 0                                            */
 } tandem_model_desc;
-
-/* tandem_model_desc.flags: keep, in device memory owned by the model, a second copy of every bf16
- * weight matrix whose shape allows it (rows % 128 == 0, columns % 256 == 0) in the packed layout of
- * tandem_pack_weight: decode-time products then read each weight as one contiguous stream.  Costs
- * as much device memory again as those matrices (allocated by tandem_model_create with hipMalloc on
- * the current device, packed on the null stream, which is synchronised before returning). */
-#define TANDEM_MODEL_PACK_WEIGHTS 1
 
 /* Caller-owned decoding state (all device memory except the pointer arrays themselves).
  *   KL[j], VL[j]      [B, L.Hkv, T_max, dh]     M_L's K/V cache of large layer j
@@ -254,8 +249,21 @@ typedef struct {
 
 typedef struct tandem_model tandem_model; /* opaque host object: validated copy of a tandem_model_desc */
 
+/* tandem_model_create allocates host memory only (a validated copy of the descriptor); the weights stay the
+ * caller's and must outlive the handle. */
 int tandem_model_create(const tandem_model_desc *desc, tandem_model **out);
 void tandem_model_destroy(tandem_model *m);
+
+/* Packed copies of the model's weights, in memory the caller owns.  Every bf16 weight matrix of the model whose shape
+ * allows it (rows % 128 == 0, columns % 256 == 0) gets a second copy in the layout of tandem_pack_weight; the
+ * decode-time products of every later call on this handle then read each weight as one contiguous stream.
+ *   tandem_model_packed_bytes(m)  bytes the copies need (0: nothing to pack) - as much again as those matrices
+ *   tandem_model_pack(m, packed, packed_bytes, hip_stream)  packed: device, 256-byte aligned, at least that many
+ *     bytes, owned by the caller and kept alive and unmodified as long as the handle is used.  The packing kernels are
+ *     enqueued on hip_stream; calls that use the handle must be ordered after them (same stream, or an event).
+ * Not thread-safe against concurrent calls on the same handle.  Without it the row-major weights are used. */
+size_t tandem_model_packed_bytes(const tandem_model *m);
+int tandem_model_pack(tandem_model *m, void *packed, size_t packed_bytes, void *hip_stream);
 size_t tandem_decode_step_workspace(const tandem_model *m, int32_t B, int32_t gamma);
 
 /* tandem_decode_step flags.  TANDEM_STEP_FREE_TOKEN (Sec. 3.1, Fig. 2): M_L also processes the last

@@ -88,7 +88,6 @@ class RouterDesc(C.Structure):
 
 
 ROUTER_MAX_K = 8
-MODEL_PACK_WEIGHTS = 1
 STEP_FREE_TOKEN = 1
 PREFILL_EMIT = 1
 
@@ -101,7 +100,8 @@ EXPORTS = (
     "tandem_draft_attn_shared_workspace", "tandem_draft_attn_shared",
     "tandem_mixed_attn_workspace", "tandem_mixed_attn",
     "tandem_block_prefix_attn_workspace", "tandem_block_prefix_attn",
-    "tandem_model_create", "tandem_model_destroy", "tandem_decode_step_workspace", "tandem_decode_step",
+    "tandem_model_create", "tandem_model_destroy", "tandem_model_packed_bytes", "tandem_model_pack",
+    "tandem_decode_step_workspace", "tandem_decode_step",
     "tandem_prefill_workspace", "tandem_prefill",
     "tandem_router_eval", "tandem_decode_step_adaptive",
     "tandem_score_workspace", "tandem_score",
@@ -173,6 +173,10 @@ def lib():
     L.tandem_model_create.argtypes = [C.POINTER(ModelDesc), C.POINTER(vp)]
     L.tandem_model_destroy.restype = None
     L.tandem_model_destroy.argtypes = [vp]
+    L.tandem_model_packed_bytes.restype = sz
+    L.tandem_model_packed_bytes.argtypes = [vp]
+    L.tandem_model_pack.restype = C.c_int
+    L.tandem_model_pack.argtypes = [vp, vp, sz, vp]
     L.tandem_decode_step_workspace.restype = sz
     L.tandem_decode_step_workspace.argtypes = [vp, i32, i32]
     L.tandem_decode_step.restype = C.c_int
@@ -499,8 +503,9 @@ class TandemModel:
 
     `weights` has the layout produced by inputs.tandem_weights: {"L": decoder, "S": decoder,
     "ell": [...], "ff": [...], "eps": float} with per-layer Wq / Wk / Wv stored separately; they are
-    stacked here into the Wqkv operand the C ABI takes.  pack_weights: let the library keep packed copies of
-    the weight matrices (faster decode-time products, as much device memory again as those matrices)."""
+    stacked here into the Wqkv operand the C ABI takes.  pack_weights: also hold a buffer with the packed copies of
+    the weight matrices (tandem_model_pack: faster decode-time products, as much device memory again as those
+    matrices; packed on the current stream)."""
 
     def __init__(self, weights, pack_weights=True):
         import torch
@@ -540,10 +545,16 @@ class TandemModel:
             ffs[j] = ff_desc(held)
         ell = (C.c_int32 * len(self.ell))(*self.ell)
         self._keep += [ffs, ell]
-        desc = ModelDesc(L, S, ell, ffs, self.eps, self.dtype_code, MODEL_PACK_WEIGHTS if pack_weights else 0)
+        desc = ModelDesc(L, S, ell, ffs, self.eps, self.dtype_code, 0)
         handle = C.c_void_p()
         _check(lib().tandem_model_create(C.byref(desc), C.byref(handle)), "tandem_model_create")
         self.handle = handle
+        self.packed = None
+        if pack_weights:
+            need = int(lib().tandem_model_packed_bytes(handle))
+            if need > 0:
+                self.packed = torch.empty(need, dtype=torch.uint8, device=embL.device)
+                _check(lib().tandem_model_pack(handle, _ptr(self.packed), need, _stream(None)), "tandem_model_pack")
 
     def __del__(self):
         h = getattr(self, "handle", None)

@@ -1,7 +1,27 @@
 // C ABI entry points: argument validation on the host, then kernel launches.  Nothing is
 // enqueued when a check fails.
+#include <map>
+#include <mutex>
+#include <utility>
+
 #include "common.h"
 #include "kernels.h"
+
+int ensure_dynamic_lds(const void* kernel, size_t bytes) {
+  if (bytes <= 48 * 1024) return TANDEM_OK;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return TANDEM_ERR_HIP;
+  static std::mutex mu;
+  static std::map<std::pair<const void*, int>, size_t> done;  // (kernel, device) -> limit already set
+  std::lock_guard<std::mutex> lock(mu);
+  const auto key = std::make_pair(kernel, dev);
+  const auto it = done.find(key);
+  if (it != done.end() && it->second >= bytes) return TANDEM_OK;
+  if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess)
+    return TANDEM_ERR_HIP;
+  done[key] = bytes;
+  return TANDEM_OK;
+}
 
 namespace {
 

@@ -538,13 +538,7 @@ int launch_mrows(const BlockParams& p, int passes, int B, hipStream_t st) {
 template <int RT, int NW>
 int launch_rt(const BlockParams& p, int passes, int B, hipStream_t st) {
   const size_t lds_bytes = (size_t)(NW / 2) * RT * ST_REGS * 64 * sizeof(float);
-  static bool attr_set = false;
-  if (!attr_set && lds_bytes > 48 * 1024) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_block_kernel<RT, NW>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-    if (e != hipSuccess) return TANDEM_ERR_HIP;
-    attr_set = true;
-  }
+  if (const int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(&attn_block_kernel<RT, NW>), lds_bytes)) return rc;
   hipLaunchKernelGGL((attn_block_kernel<RT, NW>), dim3(p.S, p.Hkv * passes, B), dim3(64 * NW), lds_bytes, st, p);
   return hip_ok(hipGetLastError());
 }

@@ -97,3 +97,7 @@ template <int N> struct Unpack<bf16_t, N> {
 #define TANDEM_NEG_BIG (-1.0e30f)  // finite stand-in for "no key seen yet" (keeps exp2(m - m') NaN-free)
 
 static inline int hip_ok(hipError_t e) { return e == hipSuccess ? TANDEM_OK : TANDEM_ERR_HIP; }
+
+// Raises a kernel's dynamic-LDS limit to `bytes` (nothing to do up to 48 KB) once per kernel and device; safe to call
+// from several threads, cheap on every later call.  Returns a tandem_status.
+int ensure_dynamic_lds(const void* kernel, size_t bytes);

@@ -116,8 +116,7 @@ struct tandem_model {
   std::vector<tandem_layer_weights> L_layers, S_layers;
   std::vector<int32_t> ell;
   std::vector<tandem_ff_desc> ff;
-  void* packed_buf = nullptr;                              // one allocation holding every packed weight copy
-  std::unordered_map<const void*, const void*> packed;     // caller's weight pointer -> packed copy
+  std::unordered_map<const void*, const void*> packed;     // caller's weight pointer -> packed copy (caller's buffer)
   const void* pk(const void* W) const {
     auto it = packed.find(W);
     return it == packed.end() ? nullptr : it->second;
@@ -126,19 +125,19 @@ struct tandem_model {
 
 namespace {
 
-// Packed copies (the layout the stream GEMM kernel reads) of every weight matrix whose shape allows one, in
-// one device allocation owned by the model.
-int pack_model(tandem_model* m) {
-  struct Item {
-    const void* W;
-    int64_t N, K;
-  };
-  std::vector<Item> items;
+// The weight matrices of the model that have a packed form (the layout the stream GEMM kernel reads), each once.
+struct PackItem {
+  const void* W;
+  int64_t N, K;
+};
+std::vector<PackItem> pack_items(const tandem_model* m) {
+  std::vector<PackItem> items;
+  std::unordered_map<const void*, int> seen;
   const int dt = m->d.dtype;
   auto add = [&](const void* W, int64_t N, int64_t K) {
-    if (W && gemm_packable(N, K, dt) && reinterpret_cast<uintptr_t>(W) % 16 == 0 && !m->packed.count(W)) {
+    if (W && gemm_packable(N, K, dt) && reinterpret_cast<uintptr_t>(W) % 16 == 0 && !seen.count(W)) {
       items.push_back({W, N, K});
-      m->packed[W] = nullptr;
+      seen[W] = 1;
     }
   };
   auto add_decoder = [&](const tandem_decoder_desc& D) {
@@ -161,28 +160,7 @@ int pack_model(tandem_model* m) {
       add(f.W1, f.d_S, f.d_L);
     }
   }
-  if (items.empty()) return TANDEM_OK;
-  size_t total = 0;
-  for (const Item& it : items) total += align256((size_t)it.N * it.K * elsize(dt));
-  if (hipMalloc(&m->packed_buf, total) != hipSuccess) {
-    m->packed_buf = nullptr;
-    m->packed.clear();
-    return TANDEM_ERR_HIP;
-  }
-  size_t off = 0;
-  for (const Item& it : items) {
-    void* dst = (char*)m->packed_buf + off;
-    const int rc = launch_pack_weights(it.W, dst, it.N, it.K, nullptr);
-    if (rc != TANDEM_OK) return rc;
-    m->packed[it.W] = dst;
-    off += align256((size_t)it.N * it.K * elsize(dt));
-  }
-  if (hipStreamSynchronize(nullptr) != hipSuccess) return TANDEM_ERR_HIP;
-  for (tandem_ff_desc& f : m->ff) {
-    f.W1p = m->pk(f.W1);
-    f.W2p = f.d_hidden > 0 ? m->pk(f.W2) : nullptr;
-  }
-  return TANDEM_OK;
+  return items;
 }
 
 // Workspace layout of one step, a pure function of (model, B, gamma, T_max, gamma_max).
@@ -227,31 +205,47 @@ StepPlan make_plan(const tandem_model* m, int B, int gamma, int64_t T_max, int g
   p.keep = take(p.keep_stride * S.n_layers);
   // ints: ncur[gamma][B], block_tokens[B*gamma], draft[B*gamma], verify[B*gamma], stop[B]
   p.ints = take(sizeof(int32_t) * (4 * M + B));  // + stop[B] of the adaptive block length
-  // attention scratch: the larger of the draft and the block call
+  // Attention scratch: the larger of the draft and the block call, for ANY cache capacity.  The number of context
+  // splits a launch uses depends on the capacity (at most one split per 256 keys; an even count becomes half as many
+  // wide workgroups, an odd one does not), and not monotonically - so the table of partials is sized for the
+  // largest count any capacity can give: min(ceil(512 / groups), 64) slots per row.
   {
-    int Sd = attn_rows_splits(B, S.Hkv, 1, S.Hq / S.Hkv, T_max, gamma_max, nullptr);
+    auto smax = [](int64_t groups) -> int {
+      const int64_t w = (512 + groups - 1) / groups;
+      return (int)(w < 1 ? 1 : (w > 64 ? 64 : w));
+    };
+    auto carved = [](size_t rows, int S, int dh) -> size_t {
+      return S > 1 ? align256(rows * S * 2 * 4) + rows * S * dh * 4 : 0;
+    };
+    (void)T_max;
+    (void)T_prompt;
+    (void)gamma_max;
+    int Sd = smax((int64_t)B * S.Hkv);
     if (Sd < 4) Sd = 4;  // the adaptive step cuts the draft attention in at least four (see attn_call)
-    size_t a = Sd > 1 ? align256((size_t)B * S.Hq * Sd * 2 * 4) + (size_t)B * S.Hq * Sd * S.dh * 4 : 0;
+    size_t a = carved((size_t)B * S.Hq, Sd, S.dh);
     const bool mfma = m->d.dtype == TANDEM_BF16 && L.dh == 128;
     // block calls cover at most TANDEM_MAX_QLEN rows per sequence (longer prompt chunks run in sub-blocks)
     auto blk_ws = [&](int q) -> size_t {
-      const int Sb = mfma ? attn_block_splits(B, L.Hkv, q, L.Hq / L.Hkv, T_max, nullptr)
-                          : attn_rows_splits(B, L.Hkv, q, L.Hq / L.Hkv, T_max, 0, nullptr);
-      const size_t rows = (size_t)B * q * L.Hq;
-      return Sb > 1 ? align256(rows * Sb * 2 * 4) + rows * Sb * L.dh * 4 : 0;
+      return carved((size_t)B * q * L.Hq, smax(mfma ? (int64_t)B * L.Hkv : (int64_t)B * L.Hkv * q), L.dh);
     };
     size_t b = blk_ws(gamma < TANDEM_MAX_QLEN ? gamma : TANDEM_MAX_QLEN);
     if (gamma > TANDEM_MAX_QLEN && gamma % TANDEM_MAX_QLEN) b = maxz(b, blk_ws(gamma % TANDEM_MAX_QLEN));
     p.attn_ws_bytes = maxz(a, b);
     if (score) {
-      tandem_attn_desc sd{B, S.Hq, S.Hkv, S.dh, T_max, 0, 1.f, m->d.dtype};
-      p.attn_ws_bytes = maxz(p.attn_ws_bytes, tandem_mixed_attn_workspace(&sd, gamma));
+      // tandem_mixed_attn: the K_hat segment's splits plus one slot for the own-row segment (matrix-core kernels)
+      const bool smf = m->d.dtype == TANDEM_BF16 && S.dh == 128;
+      const int Ss = smf ? smax((int64_t)B * S.Hkv) + 1 : smax((int64_t)B * S.Hkv * gamma);
+      p.attn_ws_bytes = maxz(p.attn_ws_bytes, carved((size_t)B * gamma * S.Hq, Ss, S.dh));
     }
     if (samples > 0) {
-      tandem_attn_desc ld{B / samples, L.Hq, L.Hkv, L.dh, T_prompt, 0, 1.f, m->d.dtype};
-      tandem_attn_desc sd{B / samples, S.Hq, S.Hkv, S.dh, T_prompt, gamma_max, 1.f, m->d.dtype};
-      p.attn_ws_bytes = maxz(p.attn_ws_bytes, tandem_block_attn_shared_workspace(&ld, samples, T_max, gamma));
-      p.attn_ws_bytes = maxz(p.attn_ws_bytes, tandem_draft_attn_shared_workspace(&sd, samples, T_max));
+      // shared-prompt calls: the prompt segment (per prompt) and the own segment (per sequence) share one table
+      const int P = B / samples;
+      const bool smf = m->d.dtype == TANDEM_BF16 && S.dh == 128;
+      const int Sb = (mfma ? smax((int64_t)P * L.Hkv) : smax((int64_t)P * L.Hkv * samples * gamma)) +
+                     (mfma ? smax((int64_t)B * L.Hkv) : smax((int64_t)B * L.Hkv * gamma));
+      const int Sdr = (smf ? smax((int64_t)P * S.Hkv) : smax((int64_t)P * S.Hkv * samples)) + smax((int64_t)B * S.Hkv);
+      p.attn_ws_bytes = maxz(p.attn_ws_bytes, carved((size_t)B * gamma * L.Hq, Sb, L.dh));
+      p.attn_ws_bytes = maxz(p.attn_ws_bytes, carved((size_t)B * S.Hq, Sdr, S.dh));
     }
     p.attn_ws = take(p.attn_ws_bytes);
   }
@@ -561,6 +555,7 @@ int tandem_model_create(const tandem_model_desc* desc, tandem_model** out) {
   if (!desc || !out) return TANDEM_ERR_NULL;
   *out = nullptr;
   if (desc->dtype != TANDEM_F32 && desc->dtype != TANDEM_BF16) return TANDEM_ERR_UNSUPPORTED;
+  if (desc->flags != 0) return TANDEM_ERR_UNSUPPORTED;
   int rc = check_decoder(desc->L);
   if (rc != TANDEM_OK) return rc;
   rc = check_decoder(desc->S);
@@ -585,22 +580,44 @@ int tandem_model_create(const tandem_model_desc* desc, tandem_model** out) {
   m->d.S.layers = m->S_layers.data();
   m->d.ell = m->ell.data();
   m->d.ff = m->ff.data();
-  for (auto& f : m->ff) f.W1p = f.W2p = nullptr;  // the model packs for itself
-  if (desc->flags & TANDEM_MODEL_PACK_WEIGHTS) {
-    rc = pack_model(m);
-    if (rc != TANDEM_OK) {
-      tandem_model_destroy(m);
-      return rc;
-    }
-  }
+  for (auto& f : m->ff) f.W1p = f.W2p = nullptr;  // packed copies come from tandem_model_pack only
   *out = m;
   return TANDEM_OK;
 }
 
-void tandem_model_destroy(tandem_model* m) {
-  if (!m) return;
-  if (m->packed_buf) (void)hipFree(m->packed_buf);
-  delete m;
+void tandem_model_destroy(tandem_model* m) { delete m; }
+
+size_t tandem_model_packed_bytes(const tandem_model* m) {
+  if (!m) return 0;
+  size_t total = 0;
+  for (const PackItem& it : pack_items(m)) total += align256((size_t)it.N * it.K * elsize(m->d.dtype));
+  return total;
+}
+
+int tandem_model_pack(tandem_model* m, void* packed, size_t packed_bytes, void* hip_stream) {
+  if (!m) return TANDEM_ERR_NULL;
+  const std::vector<PackItem> items = pack_items(m);
+  if (items.empty()) return TANDEM_OK;
+  if (!packed) return TANDEM_ERR_NULL;
+  if (reinterpret_cast<uintptr_t>(packed) % 256 != 0) return TANDEM_ERR_SHAPE;
+  if (packed_bytes < tandem_model_packed_bytes(m)) return TANDEM_ERR_WORKSPACE;
+  size_t off = 0;
+  for (const PackItem& it : items) {
+    void* dst = (char*)packed + off;
+    const int rc = launch_pack_weights(it.W, dst, it.N, it.K, (hipStream_t)hip_stream);
+    if (rc != TANDEM_OK) {
+      m->packed.clear();
+      for (tandem_ff_desc& f : m->ff) f.W1p = f.W2p = nullptr;
+      return rc;
+    }
+    m->packed[it.W] = dst;
+    off += align256((size_t)it.N * it.K * elsize(m->d.dtype));
+  }
+  for (tandem_ff_desc& f : m->ff) {
+    f.W1p = m->pk(f.W1);
+    f.W2p = f.d_hidden > 0 ? m->pk(f.W2) : nullptr;
+  }
+  return TANDEM_OK;
 }
 
 size_t tandem_packed_weight_bytes(int64_t N, int64_t K, int32_t dtype) {
@@ -734,7 +751,7 @@ int decode_step_impl(const tandem_model* m, const tandem_state_desc* state, cons
 
   // ---- 4. accept ------------------------------------------------------------------------
   return launch_accept(draft, verify, forced, stop, out_tokens, n_accepted, n_drafted, state->n, state->pending, B, gamma,
-                       nq, c.stream);
+                       nq, state->T_max, c.stream);
 }
 }  // namespace
 
@@ -816,7 +833,7 @@ int tandem_prefill(const tandem_model* m, const tandem_state_desc* state, const 
     }
     TRY(head(c, L, B, state->pending, 1));
   }
-  return launch_advance(state->n, B, q_len, c.stream);
+  return launch_advance(state->n, B, q_len, state->T_max, c.stream);
 }
 
 size_t tandem_score_workspace(const tandem_model* m, int32_t B, int32_t q_len) {

@@ -920,13 +920,7 @@ int launch_skinny(const GemmParams& p, int mpasses, hipStream_t st) {
   const size_t xbytes = (size_t)NW * (32 * MT) * XP * sizeof(bf16_t);
   const size_t rbytes = (size_t)(NW / 2) * MT * 16 * 64 * sizeof(float);
   const size_t lds_bytes = xbytes > rbytes ? xbytes : rbytes;
-  static bool attr_set = false;
-  if (!attr_set && lds_bytes > 48 * 1024) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_skinny_kernel<MT, NW>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
-      return TANDEM_ERR_HIP;
-    attr_set = true;
-  }
+  if (const int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(&gemm_skinny_kernel<MT, NW>), lds_bytes)) return rc;
   hipLaunchKernelGGL((gemm_skinny_kernel<MT, NW>), dim3(p.N / 32, p.splitK, mpasses), dim3(NW * 64), lds_bytes, st, p);
   return hip_ok(hipGetLastError());
 }
@@ -934,13 +928,7 @@ int launch_skinny(const GemmParams& p, int mpasses, hipStream_t st) {
 template <int MT>
 int launch_stream(const GemmParams& p, int mpasses, hipStream_t st) {
   const size_t lds_bytes = (size_t)2 * (32 * MT) * XPS * sizeof(bf16_t);
-  static bool attr_set = false;
-  if (!attr_set && lds_bytes > 48 * 1024) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_stream_kernel<MT>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
-      return TANDEM_ERR_HIP;
-    attr_set = true;
-  }
+  if (const int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(&gemm_stream_kernel<MT>), lds_bytes)) return rc;
   GemmParams q = p;
   const int tiles = p.N / 128, S = p.splitK;
   q.xcd_map = (S >= 8 ? S % 8 == 0 : (8 % S == 0 && tiles % (8 / S) == 0)) ? 1 : 0;
@@ -953,26 +941,14 @@ int launch_tile(const GemmParams& p, int mpasses, hipStream_t st) {
   const size_t xbytes = (size_t)2 * 2 * (32 * MT) * XPT * sizeof(bf16_t);
   const size_t rbytes = (size_t)4 * MT * 16 * 64 * sizeof(float);
   const size_t lds_bytes = xbytes > rbytes ? xbytes : rbytes;
-  static bool attr_set = false;
-  if (!attr_set && lds_bytes > 48 * 1024) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_tile_kernel<MT>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
-      return TANDEM_ERR_HIP;
-    attr_set = true;
-  }
+  if (const int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(&gemm_tile_kernel<MT>), lds_bytes)) return rc;
   hipLaunchKernelGGL((gemm_tile_kernel<MT>), dim3(p.N / 128, p.splitK, mpasses), dim3(512), lds_bytes, st, p);
   return hip_ok(hipGetLastError());
 }
 
 int launch_big(const GemmParams& p, hipStream_t st) {
   const size_t lds_bytes = (size_t)2 * 2 * 256 * BK * sizeof(bf16_t);
-  static bool attr_set = false;
-  if (!attr_set) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_big_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)lds_bytes) != hipSuccess)
-      return TANDEM_ERR_HIP;
-    attr_set = true;
-  }
+  if (const int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(&gemm_big_kernel), lds_bytes)) return rc;
   const int tiles_m = (p.M + 255) / 256, tiles_n = p.N / 256;
   hipLaunchKernelGGL(gemm_big_kernel, dim3(tiles_m * tiles_n, p.splitK), dim3(256), lds_bytes, st, p, tiles_m, tiles_n);
   return hip_ok(hipGetLastError());

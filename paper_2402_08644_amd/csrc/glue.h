@@ -20,9 +20,9 @@ int launch_block_tokens(const int32_t* pending, const int32_t* follow, int32_t* 
 // stop (optional, [B]): sequence b drafted stop[b] tokens (0 = all gamma); n_drafted (optional) receives that number
 int launch_accept(const int32_t* draft, const int32_t* verify, const int32_t* forced, const int32_t* stop,
                   int32_t* out_tokens, int32_t* n_accepted, int32_t* n_drafted, int32_t* n, int32_t* pending, int B,
-                  int gamma, int q, hipStream_t st);
+                  int gamma, int q, int64_t cap, hipStream_t st);  // cap: n[b] never advances past the cache capacity
 // router of the adaptive block length (router.hip)
 int check_router(const tandem_router_desc* r, int d);
 int launch_router(const tandem_router_desc* r, const void* logits, const void* emb, int rows, int vocab, int d, int run,
                   int32_t* stop, float* p_out, int64_t p_stride, hipStream_t st);
-int launch_advance(int32_t* n, int B, int by, hipStream_t st);  // n[b] += by
+int launch_advance(int32_t* n, int B, int by, int64_t cap, hipStream_t st);  // n[b] = min(n[b] + by, cap)

@@ -247,7 +247,7 @@ __global__ __launch_bounds__(1024) void finish_scatter_kernel(const float* __res
   }
 }
 
-// block_tokens[b, 0] = pending[b]; block_tokens[b, r] = (forced ? forced : draft)[b, r-1];  ncur[r][b] = r + 1
+// ncur[r][b] = r + 1 (own-block rows visible to draft run r);  stop[b] = 0 (adaptive block length: nobody has stopped)
 __global__ void prepare_step_kernel(const int32_t* pending, int32_t* ncur, int32_t* stop, int B, int gamma) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < B * gamma) ncur[i] = i / B + 1;
@@ -270,7 +270,7 @@ __global__ void block_tokens_kernel(const int32_t* pending, const int32_t* follo
 // beyond them are ignored, and gb takes gamma's place in the rule above.
 __global__ void accept_kernel(const int32_t* draft, const int32_t* verify, const int32_t* forced, const int32_t* stop,
                               int32_t* out_tokens, int32_t* n_accepted, int32_t* n_drafted, int32_t* n,
-                              int32_t* pending, int B, int gamma, int q) {
+                              int32_t* pending, int B, int gamma, int q, long long cap) {
   const int b = blockIdx.x * blockDim.x + threadIdx.x;
   if (b >= B) return;
   const bool free_token = q > gamma;
@@ -282,7 +282,8 @@ __global__ void accept_kernel(const int32_t* draft, const int32_t* verify, const
     for (int r = 0; r < gamma; ++r) out_tokens[b * q + r] = forced[b * gamma + r];
     if (free_token) out_tokens[b * q + gamma] = verify[b * q + gamma];
     pending[b] = out_tokens[b * q + q - 1];
-    n[b] += q;
+    const long long nn = (long long)n[b] + q;
+    n[b] = (int32_t)(nn < 0 ? 0 : (nn > cap ? cap : nn));  // never past the caches' capacity
   } else {
     while (a < gb && draft[b * gamma + a] == verify[b * q + a]) ++a;
     const int emit = (a < gb || free_token) ? a + 1 : gb;
@@ -293,20 +294,23 @@ __global__ void accept_kernel(const int32_t* draft, const int32_t* verify, const
       out_tokens[b * q + r] = t;
     }
     pending[b] = out_tokens[b * q + emit - 1];
-    n[b] += emit;
+    const long long nn = (long long)n[b] + emit;
+    n[b] = (int32_t)(nn < 0 ? 0 : (nn > cap ? cap : nn));
   }
   n_accepted[b] = a;
 }
 
-__global__ void advance_kernel(int32_t* n, int B, int by) {
+__global__ void advance_kernel(int32_t* n, int B, int by, long long cap) {
   const int b = blockIdx.x * blockDim.x + threadIdx.x;
-  if (b < B) n[b] += by;
+  if (b >= B) return;
+  const long long nn = (long long)n[b] + by;
+  n[b] = (int32_t)(nn < 0 ? 0 : (nn > cap ? cap : nn));
 }
 
 }  // namespace
 
-int launch_advance(int32_t* n, int B, int by, hipStream_t st) {
-  hipLaunchKernelGGL(advance_kernel, dim3((B + 63) / 64), dim3(64), 0, st, n, B, by);
+int launch_advance(int32_t* n, int B, int by, int64_t cap, hipStream_t st) {
+  hipLaunchKernelGGL(advance_kernel, dim3((B + 63) / 64), dim3(64), 0, st, n, B, by, (long long)cap);
   return hip_ok(hipGetLastError());
 }
 
@@ -399,8 +403,8 @@ int launch_block_tokens(const int32_t* pending, const int32_t* follow, int32_t* 
 
 int launch_accept(const int32_t* draft, const int32_t* verify, const int32_t* forced, const int32_t* stop,
                   int32_t* out_tokens, int32_t* n_accepted, int32_t* n_drafted, int32_t* n, int32_t* pending, int B,
-                  int gamma, int q, hipStream_t st) {
+                  int gamma, int q, int64_t cap, hipStream_t st) {
   hipLaunchKernelGGL(accept_kernel, dim3((B + 63) / 64), dim3(64), 0, st, draft, verify, forced, stop, out_tokens,
-                     n_accepted, n_drafted, n, pending, B, gamma, q);
+                     n_accepted, n_drafted, n, pending, B, gamma, q, (long long)cap);
   return hip_ok(hipGetLastError());
 }

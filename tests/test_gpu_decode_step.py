@@ -1,8 +1,9 @@
 """GPU parity: tandem_decode_step through the C ABI against the fp64 oracle.
 
-Floating-point bar for whole-step outputs: bf16 steps accumulate one bf16 rounding of the
-residual stream per dense layer, so the per-row bound is the per-kernel 2e-2 times
-sqrt(number of decoder layers the row passed through), rounded up; fp32 steps use 2e-3.
+Floating-point bar for whole-step outputs (representations after all layers, new cache rows): the same 2e-2
+per row as for single kernels, although a bf16 step rounds the residual stream once per dense layer (observed
+worst case over this file: 1.5e-2, on K_hat / V_hat rows, which pass M_L's layers, FF_Tandem and a norm);
+fp32 steps use 2e-3.
 Tokens: the GPU's greedy token must lie in the oracle's near-argmax set
 {v : max_logit - logit_v <= 2e-2 * max|logit|} (several results are correct when logits tie
 within the arithmetic's resolution)."""
@@ -13,7 +14,7 @@ import pytest
 
 from oracle import tandem_oracle as orc
 from paper_2402_08644_amd import inputs
-from parity import assert_rows_close
+from parity import TOL, assert_rows_close
 
 pytestmark = pytest.mark.gpu
 
@@ -122,7 +123,7 @@ def test_decode_step_bf16_vs_oracle_on_random_caches(tb, gamma, B, n, gains):
     out = binding.tandem_decode_step(model, gst, gamma, forced=forced, aux=True)
     torch.cuda.synchronize()
     want = orc.decode_step(T, ost, gamma, forced=forced_np)
-    tol = 2e-2 * math.ceil(math.sqrt(2 + 1))
+    tol = TOL
     e1 = assert_rows_close(inputs.torch_to_f64(out["y_small"]), want["y_small"], tol=tol, what="y_small")
     e2 = assert_rows_close(inputs.torch_to_f64(out["x_large"]), want["x_large"], tol=tol, what="x_large")
     print(f"decode step gamma={gamma}: y_small err {e1[0]:.2e}, x_large err {e2[0]:.2e}")
@@ -162,7 +163,7 @@ def test_decode_step_bf16_many_rows_packed_and_plain_weights(tb, pack):
     out = binding.tandem_decode_step(model, gst, gamma, forced=torch.tensor(forced_np, dtype=torch.int32).cuda(), aux=True)
     torch.cuda.synchronize()
     want = orc.decode_step(T, ost, gamma, forced=forced_np)
-    tol = 2e-2 * math.ceil(math.sqrt(2 + 1))
+    tol = TOL
     assert_rows_close(inputs.torch_to_f64(out["y_small"]), want["y_small"], tol=tol, what="y_small")
     assert_rows_close(inputs.torch_to_f64(out["x_large"]), want["x_large"], tol=tol, what="x_large")
     assert tokens_ok(out["draft"].cpu().numpy(), want["logits_S"])
@@ -307,7 +308,7 @@ def test_decode_step_free_token_bf16_vs_oracle(tb, gamma, B, n):
     out = binding.tandem_decode_step(model, gst, gamma, forced=forced, aux=True, free_token=True)
     torch.cuda.synchronize()
     want = orc.decode_step(T, ost, gamma, forced=forced_np, free_token=True)
-    tol = 2e-2 * math.ceil(math.sqrt(2 + 1))
+    tol = TOL
     assert out["tokens"].shape == (B, q) and out["x_large"].shape[1] == q
     assert_rows_close(inputs.torch_to_f64(out["y_small"]), want["y_small"], tol=tol, what="y_small")
     assert_rows_close(inputs.torch_to_f64(out["x_large"]), want["x_large"], tol=tol, what="x_large")
@@ -373,7 +374,7 @@ def test_prefill_bf16_vs_oracle(tb, chunks, B):
     ost, host = oracle_state_from(T, B, T_max, 82, n, pending, "bf16")
     model = binding.TandemModel(W)
     gst = upload_state(tb, model, B, T_max, 4, host, n, pending)
-    tol = 2e-2 * math.ceil(math.sqrt(2 + 1))
+    tol = TOL
     for ci, q in enumerate(chunks):
         toks = inputs.token_ids(83 + ci, (B, q), 512)
         n0 = [int(v) for v in ost["n"]]
@@ -454,6 +455,31 @@ def test_decode_step_workspace_covers_both_modes(tb, B, gamma):
     binding.tandem_decode_step(model, gst, gamma, ws=ws, free_token=True)
     torch.cuda.synchronize()
     assert int(gst.n.min()) >= 2
+
+
+@pytest.mark.parametrize("B,T_max,free", [(8, 1800, True), (8, 1400, False), (4, 3000, True), (2, 5000, False)])
+def test_decode_step_workspace_is_enough_at_any_cache_capacity(tb, B, T_max, free):
+    """A buffer of exactly tandem_decode_step_workspace(m, B, gamma) bytes must do whatever the cache capacity: the
+    number of context splits (and so the table of partials) is not monotone in T_max - capacities like these give odd
+    split counts, which are not folded into wide workgroups.  Same for the adaptive step and for tandem_prefill."""
+    torch, binding = tb
+    W = small_bf16_pair(98)
+    model = binding.TandemModel(W)
+    gamma = 4
+    gst = binding.TandemState(model, B, T_max, gamma, fill=lambda *s: torch.randn(s, device="cuda").to(torch.bfloat16))
+    gst.n.fill_(T_max - 2 * (gamma + 1))
+    gst.pending.fill_(3)
+    ws = torch.empty(binding.tandem_decode_step_workspace(model, B, gamma), dtype=torch.uint8, device="cuda")
+    binding.tandem_decode_step(model, gst, gamma, ws=ws, free_token=free)
+    R = inputs.router_weights(5, 2, 256, 16, dtype="bf16", w_std=0.1, out_std=0.5)
+    router = {k: (v if k == "k" else v.to_torch()) for k, v in R.items()}
+    gst.n.fill_(T_max - 2 * (gamma + 1))
+    binding.tandem_decode_step(model, gst, gamma, ws=ws, free_token=free, router=router, tau=0.5)
+    gst.n.fill_(0)
+    wp = torch.empty(binding.tandem_prefill_workspace(model, B, 40), dtype=torch.uint8, device="cuda")
+    binding.tandem_prefill(model, gst, torch.zeros((B, 40), dtype=torch.int32, device="cuda"), ws=wp)
+    torch.cuda.synchronize()
+    assert int(gst.n.min()) == 40
 
 
 def test_decode_step_error_codes(tb):
@@ -599,7 +625,7 @@ def test_decode_step_shared_prompt_vs_oracle_on_materialised_caches(tb, free):
     got = binding.tandem_decode_step(model, gst, gamma, aux=True, free_token=free, prompt=prompt)
     torch.cuda.synchronize()
     q = gamma + (1 if free else 0)
-    tol = 2e-2 * math.ceil(math.sqrt(2 + 1))
+    tol = TOL
     draft, verify = got["draft"].cpu().numpy(), got["verify"].cpu().numpy()
     # Every sequence is compared.  Where a bf16 logit tie makes the GPU draft a different (equally valid) token than
     # the oracle would, the runs after it see other inputs: the oracle therefore follows the GPU's branch - it is

@@ -71,7 +71,7 @@ def test_score_bf16_batch_equals_teacher_forced_forward(tb):
     gamma, chunks = 4, [10, 17, 13]
     toks = inputs.token_ids(2, (2, 40), 512)
     lg, y, greedy = run_score(tb, W, toks, gamma, chunks, 64)
-    tol = 2e-2 * math.ceil(math.sqrt(2 + 2 + 1))  # rows pass the large layers, FF_Tandem and the small layers
+    tol = 2e-2  # rows pass the large layers, FF_Tandem and the small layers; observed 9e-3
     for b in range(2):
         ref = orc.tandem_forward(T, toks[b], gamma)
         assert_rows_close(y[b], ref["y"], tol=tol, what=f"y^(L_S) of sequence {b}")
