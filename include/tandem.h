@@ -188,6 +188,18 @@ int tandem_draft_attn(const tandem_attn_desc *a, const void *q, const void *k_ha
                       const int32_t *n_large, const void *k_cur, const void *v_cur, const int32_t *n_cur, void *out,
                       void *ws, size_t ws_bytes, void *hip_stream);
 
+/* tandem_draft_attn for callers that cannot allocate device memory or carry a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, kernels and results as
+ * tandem_draft_attn, but the split-K partials live in a device array that is part of the library image
+ * (TANDEM_STATIC_SCRATCH_BYTES per GPU, held from library load to process end); the call allocates nothing.
+ * Returns TANDEM_ERR_WORKSPACE when tandem_draft_attn_workspace(a) exceeds TANDEM_STATIC_SCRATCH_BYTES (nothing is
+ * enqueued): the limit covers every shape with up to two query heads per KV head, and grouped shapes with few splits.  All calls on one GPU share that array: calls that may overlap on one GPU (different streams, threads
+ * or processes' graphs replayed concurrently) race on it - order them.  Nothing in it needs clearing between calls. */
+#define TANDEM_STATIC_SCRATCH_BYTES (1u << 20)
+int tandem_draft_attn_static(const tandem_attn_desc *a, const void *q, const void *k_hat, const void *v_hat,
+                             const int32_t *n_large, const void *k_cur, const void *v_cur, const int32_t *n_cur, void *out,
+                             void *hip_stream);
+
 /* ------------------------------------------------------------------ whole decode step */
 
 /* One pre-norm decoder layer: h = x + Wo Atn(RMSNorm(x; g_attn)); x' = h + W2 gelu(W1 RMSNorm(h; g_mlp) + b1) + b2.

@@ -95,7 +95,7 @@ EXPORTS = (
     "tandem_status_string",
     "tandem_project_workspace", "tandem_block_attn_workspace", "tandem_draft_attn_workspace",
     "tandem_packed_weight_bytes", "tandem_pack_weight",
-    "tandem_project", "tandem_block_attn", "tandem_draft_attn",
+    "tandem_project", "tandem_block_attn", "tandem_draft_attn", "tandem_draft_attn_static",
     "tandem_block_attn_shared_workspace", "tandem_block_attn_shared",
     "tandem_draft_attn_shared_workspace", "tandem_draft_attn_shared",
     "tandem_mixed_attn_workspace", "tandem_mixed_attn",
@@ -169,6 +169,8 @@ def lib():
     L.tandem_block_attn.argtypes = [C.POINTER(AttnDesc), vp, vp, vp, vp, i32, vp, vp, sz, vp]
     L.tandem_draft_attn.restype = C.c_int
     L.tandem_draft_attn.argtypes = [C.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.tandem_draft_attn_static.restype = C.c_int
+    L.tandem_draft_attn_static.argtypes = [C.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, vp, vp, vp]
     L.tandem_model_create.restype = C.c_int
     L.tandem_model_create.argtypes = [C.POINTER(ModelDesc), C.POINTER(vp)]
     L.tandem_model_destroy.restype = None
@@ -247,6 +249,21 @@ def tandem_draft_attn_workspace(desc: AttnDesc) -> int:
 
 def tandem_block_attn_workspace(desc: AttnDesc, q_len: int) -> int:
     return int(lib().tandem_block_attn_workspace(C.byref(desc), q_len))
+
+
+STATIC_SCRATCH_BYTES = 1 << 20
+
+
+def tandem_draft_attn_static(q, k_hat, v_hat, n_large, k_cur, v_cur, n_cur, out, scale=None, stream=None):
+    """tandem_draft_attn without a workspace argument: the library's own static device scratch holds the split
+    partials.  `out` is required (the call allocates nothing, this wrapper included)."""
+    B, Hq, dh = q.shape
+    _, Hkv, T_max, _ = k_hat.shape
+    d = attn_desc(B, Hq, Hkv, dh, T_max, k_cur.shape[2], (1.0 / math.sqrt(dh)) if scale is None else scale, _dtype_code(q))
+    rc = lib().tandem_draft_attn_static(C.byref(d), _ptr(q), _ptr(k_hat), _ptr(v_hat), _ptr(n_large), _ptr(k_cur),
+                                        _ptr(v_cur), _ptr(n_cur), _ptr(out), _stream(stream))
+    _check(rc, "tandem_draft_attn_static")
+    return out
 
 
 def tandem_draft_attn(q, k_hat, v_hat, n_large, k_cur, v_cur, n_cur, scale=None, out=None, ws=None, stream=None):

@@ -23,9 +23,33 @@ int ensure_dynamic_lds(const void* kernel, size_t bytes) {
   return TANDEM_OK;
 }
 
+// Split-K partials of tandem_draft_attn_static: device memory that exists from the moment the library is loaded, so
+// that entry point never allocates.  One copy per GPU; in host code the name is only a handle for
+// hipGetSymbolAddress, the kernels get the address that call returns.  (No `used` attribute: with it the compiler
+// keeps the device-side symbol local, and the runtime, which finds the array by name, aborts.)
+static __device__ __align__(256) unsigned char scratch[TANDEM_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// Device address of `scratch` on the current device, looked up once per device.
+int static_scratch(void** out) {
+  constexpr int MAX_DEVICES = 64;
+  static std::mutex mu;
+  static void* ptr[MAX_DEVICES] = {};
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return TANDEM_ERR_HIP;
+  if (dev < 0 || dev >= MAX_DEVICES) return TANDEM_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return TANDEM_ERR_HIP;
+    ptr[dev] = p;
+  }
+  *out = ptr[dev];
+  return TANDEM_OK;
+}
 
 int check_attn_desc(const tandem_attn_desc* a) {
   if (!a) return TANDEM_ERR_NULL;
@@ -136,6 +160,19 @@ int tandem_draft_attn(const tandem_attn_desc* a, const void* q, const void* k_ha
   x.S = attn_rows_splits(a->B, a->Hkv, 1, a->Hq / a->Hkv, a->T_max, a->gamma_max, &x.wide);
   if (x.S > 1) carve(ws, (size_t)a->B * a->Hq, x.S, &x.part_ml, &x.part_o);
   return launch_attn_rows(x, (hipStream_t)hip_stream);
+}
+
+int tandem_draft_attn_static(const tandem_attn_desc* a, const void* q, const void* k_hat, const void* v_hat,
+                             const int32_t* n_large, const void* k_cur, const void* v_cur, const int32_t* n_cur, void* out,
+                             void* hip_stream) {
+  const int rc = check_attn_desc(a);
+  if (rc != TANDEM_OK) return rc;
+  if (tandem_draft_attn_workspace(a) > TANDEM_STATIC_SCRATCH_BYTES) return TANDEM_ERR_WORKSPACE;
+  void* ws = nullptr;
+  const int rs = static_scratch(&ws);
+  if (rs != TANDEM_OK) return rs;
+  // every partial slot the combine reads is written by this call's own launch first: nothing to clear
+  return tandem_draft_attn(a, q, k_hat, v_hat, n_large, k_cur, v_cur, n_cur, out, ws, TANDEM_STATIC_SCRATCH_BYTES, hip_stream);
 }
 
 int tandem_block_attn(const tandem_attn_desc* a, const void* q, const void* k_cache, const void* v_cache,
