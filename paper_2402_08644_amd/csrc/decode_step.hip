@@ -393,9 +393,10 @@ int decoder_layer(const Ctx& c, const tandem_decoder_desc& D, const tandem_layer
 // Fused form of one decoder layer (bf16): the QKV, O and second MLP products leave fp32 partials that row
 // kernels finish together with what follows them (cache scatter; residual + next RMSNorm), so a layer is
 // 10 launches instead of 13.  On entry c.xn holds RMSNorm(x; w.g_attn); on exit RMSNorm(x'; g_next).
+// x_keep (optional): receives a second copy of x' (the residual stream after this layer).
 template <typename ScatterFn, typename AttnFn>
 int decoder_layer_fused(const Ctx& c, const tandem_decoder_desc& D, const tandem_layer_weights& w, int rows,
-                        const void* g_next, ScatterFn finish_qkv, AttnFn attn) {
+                        const void* g_next, ScatterFn finish_qkv, AttnFn attn, void* x_keep = nullptr) {
   void *x = c.at<>(c.plan.x), *xn = c.at<>(c.plan.xn), *att = c.at<>(c.plan.att), *h = c.at<>(c.plan.h);
   float* gws = c.at<float>(c.plan.gemm_ws);
   const size_t gwb = c.plan.gemm_ws_bytes;
@@ -409,7 +410,7 @@ int decoder_layer_fused(const Ctx& c, const tandem_decoder_desc& D, const tandem
   TRY(gemm(xn, D.d, w.W1, c.pk(w.W1), w.b1, nullptr, 0, h, D.d_ff, rows, D.d_ff, D.d, TANDEM_ACT_GELU, c.dtype, gws, gwb, c.stream));
   TRY(gemm_deferred(h, D.d_ff, w.W2, c.pk(w.W2), rows, D.d, D.d_ff, c.dtype, gws, gwb, c.stream));
   TRY(launch_finish_norm(gws, gemm_splits(rows, D.d, D.d_ff, c.pk(w.W2) != nullptr), w.b2, x, x, g_next, xn, rows, D.d, c.eps, c.dtype,
-                         c.stream));
+                         c.stream, x_keep));
   return TANDEM_OK;
 }
 
@@ -437,23 +438,28 @@ int copy2d(void* dst, size_t dpitch, const void* src, size_t spitch, size_t widt
 // rows, tandem_block_attn per layer), then, per small layer, FF_Tandem on x^(ell[j]) of those rows and that
 // layer's RMSNorm and W_K / W_V, which append the K_hat / V_hat rows (Eq. (2) line 1).  verify (optional):
 // M_L's greedy token after every row.  Reads state->n, does not change it.
-int large_block_pass(const Ctx& c, const int32_t* block_tokens, int nq, const tandem_step_aux* aux, int32_t* verify) {
+// Tokens of the rows: tokens[B, nq], or - tokens == nullptr - pending[b] followed by the first nq - 1 of follow[b, :gamma].
+int large_block_pass(const Ctx& c, const int32_t* tokens, const int32_t* follow, int gamma, int nq,
+                     const tandem_step_aux* aux, int32_t* verify) {
   const tandem_model* m = c.m;
   const tandem_state_desc* state = c.st;
   const tandem_decoder_desc &L = m->d.L, &S = m->d.S;
   const int B = state->B, M = B * nq;
   const size_t es = elsize(c.dtype);
   void *x = c.at<>(c.plan.x), *qkv = c.at<>(c.plan.qkv), *q = c.at<>(c.plan.q), *att = c.at<>(c.plan.att);
-  TRY(launch_embed(L.emb, block_tokens, 1, x, M, L.d, L.vocab, c.dtype, c.stream));
-  auto keep = [&](int depth) -> int {  // x^(depth) for every small layer that reads it
+  TRY(launch_embed_norm(L.emb, tokens, 1, tokens ? nullptr : state->pending, follow, gamma, nq, 0, x,
+                        c.plan.fused ? L.layers[0].g_attn : nullptr, c.at<>(c.plan.xn), M, L.d, L.vocab, c.eps, nullptr,
+                        nullptr, 0, 0, c.dtype, c.stream));
+  // x^(depth) for every small layer that reads it; the first skip_first of them already have their copy
+  auto keep = [&](int depth, int skip_first) -> int {
+    int seen = 0;
     for (int j = 0; j < S.n_layers; ++j)
-      if (m->ell[j] == depth)
+      if (m->ell[j] == depth && seen++ >= skip_first)
         TRY(hip_ok(hipMemcpyAsync(c.ws + c.plan.keep + j * c.plan.keep_stride, x, (size_t)M * L.d * es,
                                   hipMemcpyDeviceToDevice, c.stream)));
     return TANDEM_OK;
   };
-  TRY(keep(0));
-  if (c.plan.fused) TRY(launch_rmsnorm(x, L.layers[0].g_attn, c.at<>(c.plan.xn), M, L.d, c.eps, c.dtype, c.stream));
+  TRY(keep(0, 0));
   for (int j = 0; j < L.n_layers; ++j) {
     auto attn_only = [&]() -> int {
       // more than TANDEM_MAX_QLEN rows per sequence (long prompt chunks): the attention runs on sub-blocks of rows,
@@ -471,7 +477,12 @@ int large_block_pass(const Ctx& c, const int32_t* block_tokens, int nq, const ta
                                      L.dh, state->T_max, L.Hq * L.dh, (L.Hq + 2 * L.Hkv) * L.dh, c.dtype, c.stream);
       };
       const void* g_next = j + 1 < L.n_layers ? L.layers[j + 1].g_attn : L.g_final;
-      TRY(decoder_layer_fused(c, L, L.layers[j], M, g_next, finish_qkv, attn_only));
+      // the first small layer that reads x^(j+1) gets its copy from the kernel that finishes this layer
+      void* x_keep = nullptr;
+      for (int t = S.n_layers - 1; t >= 0; --t)
+        if (m->ell[t] == j + 1) x_keep = c.ws + c.plan.keep + t * c.plan.keep_stride;
+      TRY(decoder_layer_fused(c, L, L.layers[j], M, g_next, finish_qkv, attn_only, x_keep));
+      TRY(keep(j + 1, 1));
     } else {
       auto attn = [&]() -> int {
         TRY(launch_scatter_qkv(qkv, q, state->KL[j], state->VL[j], state->n, 0, M, nq, L.Hq, L.Hkv, L.dh,
@@ -479,8 +490,8 @@ int large_block_pass(const Ctx& c, const int32_t* block_tokens, int nq, const ta
         return attn_only();
       };
       TRY(decoder_layer(c, L, L.layers[j], M, attn));
+      TRY(keep(j + 1, 0));
     }
-    TRY(keep(j + 1));
   }
   if (aux && aux->x_large)
     TRY(hip_ok(hipMemcpyAsync(aux->x_large, x, (size_t)M * L.d * es, hipMemcpyDeviceToDevice, c.stream)));
@@ -688,27 +699,19 @@ int decode_step_impl(const tandem_model* m, const tandem_state_desc* state, cons
   const int M = B * nq;  // rows of the verify pass and of everything derived from it
 
   int32_t* ncur = c.at<int32_t>(c.plan.ints);        // [gamma][B], ncur[r][b] = r + 1
-  int32_t* block_tokens = ncur + M;                  // [B, nq]
-  int32_t* draft = aux && aux->draft ? aux->draft : block_tokens + M;    // [B, gamma]
-  int32_t* verify = aux && aux->verify ? aux->verify : block_tokens + 2 * M;  // [B, nq]
+  int32_t* draft = aux && aux->draft ? aux->draft : ncur + 2 * (size_t)M;    // [B, gamma]
+  int32_t* verify = aux && aux->verify ? aux->verify : ncur + 3 * (size_t)M;  // [B, nq]
   int32_t* stop = router ? ncur + 4 * (size_t)M : nullptr;                    // [B], see accept_kernel
   void *x = c.at<>(c.plan.x), *qkv = c.at<>(c.plan.qkv), *q = c.at<>(c.plan.q), *att = c.at<>(c.plan.att);
 
-  TRY(launch_prepare_step(state->pending, ncur, stop, B, gamma, c.stream));
 
   // ---- 1. draft: gamma autoregressive runs of M_S --------------------------------------
   for (int r = 0; r < gamma; ++r) {
-    const int32_t* toks;
-    int64_t stride;
-    if (r == 0) {
-      toks = state->pending;
-      stride = 1;
-    } else {
-      toks = (forced ? forced : draft) + (r - 1);
-      stride = gamma;
-    }
-    TRY(launch_embed(S.emb, toks, stride, x, B, S.d, S.vocab, c.dtype, c.stream));
-    if (c.plan.fused) TRY(launch_rmsnorm(x, S.layers[0].g_attn, c.at<>(c.plan.xn), B, S.d, c.eps, c.dtype, c.stream));
+    // input of run r: the pending token, then the draft (or forced) token of the run before; the first run's kernel
+    // also sets up ncur (own-block rows visible to each run) and clears the router's stop marks
+    TRY(launch_embed_norm(S.emb, nullptr, 1, state->pending, forced ? forced : draft, gamma, 1, r, x,
+                          c.plan.fused ? S.layers[0].g_attn : nullptr, c.at<>(c.plan.xn), B, S.d, S.vocab, c.eps, ncur, stop,
+                          r == 0 ? B : 0, gamma, c.dtype, c.stream));
     for (int j = 0; j < S.n_layers; ++j) {
       auto attn_only = [&]() -> int {
         return attn_call(c, S, q, state->Khat[j], state->Vhat[j], state->n, state->Kcur[j], state->Vcur[j],
@@ -746,8 +749,7 @@ int decode_step_impl(const tandem_model* m, const tandem_state_desc* state, cons
   }
 
   // ---- 2. verify: M_L in block mode on the first nq of [pending, d_1 .. d_gamma]; 3. new K_hat / V_hat rows
-  TRY(launch_block_tokens(state->pending, forced ? forced : draft, block_tokens, B, gamma, nq, c.stream));
-  TRY(large_block_pass(c, block_tokens, nq, aux, verify));
+  TRY(large_block_pass(c, nullptr, forced ? forced : draft, gamma, nq, aux, verify));
 
   // ---- 4. accept ------------------------------------------------------------------------
   return launch_accept(draft, verify, forced, stop, out_tokens, n_accepted, n_drafted, state->n, state->pending, B, gamma,
@@ -820,7 +822,7 @@ int tandem_prefill(const tandem_model* m, const tandem_state_desc* state, const 
   const size_t es = elsize(c.dtype);
   tandem_step_aux aux{};
   aux.x_large = x_large;
-  TRY(large_block_pass(c, tokens, q_len, x_large ? &aux : nullptr, nullptr));
+  TRY(large_block_pass(c, tokens, nullptr, 0, q_len, x_large ? &aux : nullptr, nullptr));
   if (flags & TANDEM_PREFILL_EMIT) {
     // M_L's greedy token after the last row of every sequence: gather those rows of the residual stream to
     // the front of x (through a buffer that step 3 no longer needs) and run the head on B rows
@@ -867,8 +869,8 @@ int tandem_score(const tandem_model* m, const tandem_state_desc* state, void* co
   int32_t* tok_scratch = c.at<int32_t>(c.plan.ints);  // greedy tokens when the caller does not want them
   tandem_attn_desc ad{B, S.Hq, S.Hkv, S.dh, state->T_max, 0, 1.0f / sqrtf((float)S.dh), c.dtype};
 
-  TRY(launch_embed(S.emb, tokens, 1, x, M, S.d, S.vocab, c.dtype, c.stream));
-  if (c.plan.fused) TRY(launch_rmsnorm(x, S.layers[0].g_attn, c.at<>(c.plan.xn), M, S.d, c.eps, c.dtype, c.stream));
+  TRY(launch_embed_norm(S.emb, tokens, 1, nullptr, nullptr, 0, 1, 0, x, c.plan.fused ? S.layers[0].g_attn : nullptr,
+                        c.at<>(c.plan.xn), M, S.d, S.vocab, c.eps, nullptr, nullptr, 0, 0, c.dtype, c.stream));
   for (int j = 0; j < S.n_layers; ++j) {
     auto attn_only = [&]() -> int {
       return tandem_mixed_attn(&ad, q, state->Khat[j], state->Vhat[j], k_own[j], v_own[j], pos, q_len, gamma, att,

@@ -12,11 +12,6 @@ int launch_finish_scatter(const float* part, int splits, void* q, void* kc, void
                           int rows, int q_len, int Hq, int Hkv, int dh, int64_t cap, int q_cols, int row_cols, int dtype,
                           hipStream_t st);
 int launch_argmax(const void* logits, int rows, int vocab, int32_t* out, int64_t out_stride, int dtype, hipStream_t st);
-// stop (optional, [B]): cleared here; the router writes the draft run after which a sequence stops drafting
-int launch_prepare_step(const int32_t* pending, int32_t* ncur, int32_t* stop, int B, int gamma, hipStream_t st);
-// q: rows M_L verifies per sequence, gamma or gamma + 1 (free token)
-int launch_block_tokens(const int32_t* pending, const int32_t* follow, int32_t* block_tokens, int B, int gamma, int q,
-                        hipStream_t st);
 // stop (optional, [B]): sequence b drafted stop[b] tokens (0 = all gamma); n_drafted (optional) receives that number
 int launch_accept(const int32_t* draft, const int32_t* verify, const int32_t* forced, const int32_t* stop,
                   int32_t* out_tokens, int32_t* n_accepted, int32_t* n_drafted, int32_t* n, int32_t* pending, int B,

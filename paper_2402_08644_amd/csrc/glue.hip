@@ -20,15 +20,71 @@ __device__ __forceinline__ float4 load4(const bf16_t* p) {
   return make_float4(bf16lo_to_f32(u.x), bf16hi_to_f32(u.x), bf16lo_to_f32(u.y), bf16hi_to_f32(u.y));
 }
 
+// Token of row `row` of an embedding gather.  Plain form: tokens[row * stride].  Step form (pending != nullptr): row
+// = b * q + rr stands for block position r = rr + r0 of sequence b, whose token is pending[b] for r = 0 and
+// follow[b * gamma + r - 1] after that (the draft, or forced, tokens): no separate kernel has to lay the block's
+// tokens out first.
+struct TokenSrc {
+  const int32_t* tokens;
+  long long stride;
+  const int32_t *pending, *follow;
+  int gamma, q, r0;
+};
+__device__ __forceinline__ int token_of(const TokenSrc& t, int row) {
+  if (!t.pending) return t.tokens[(long long)row * t.stride];
+  const int b = row / t.q, r = row % t.q + t.r0;
+  return r == 0 ? t.pending[b] : t.follow[(long long)b * t.gamma + r - 1];
+}
+
+// x[row] = emb[token(row)]; and, when g is given, xn[row] = RMSNorm(x[row]; g) - the input of the first layer's
+// first product.  One workgroup per row.  init_B > 0 (first draft run of a step, one row per sequence): the
+// workgroup of sequence b also writes ncur[r][b] = r + 1 for r < init_gamma (own-block rows visible to draft run r)
+// and clears stop[b] (adaptive block length: nobody has stopped).
 template <typename T>
-__global__ void embed_kernel(const T* __restrict__ emb, const int32_t* __restrict__ tokens, long long tok_stride,
-                             T* __restrict__ x, int d, int vocab) {
+__global__ __launch_bounds__(256) void embed_norm_kernel(const T* __restrict__ emb, TokenSrc src, T* __restrict__ x,
+                                                         const T* __restrict__ g, T* __restrict__ xn, int d, int vocab,
+                                                         float eps, int32_t* ncur, int32_t* stop, int init_B,
+                                                         int init_gamma) {
+  __shared__ float red[4];
   const int row = blockIdx.x;
-  int t = tokens[(long long)row * tok_stride];
+  if (init_B > 0) {
+    if ((int)threadIdx.x < init_gamma) ncur[(long long)threadIdx.x * init_B + row] = threadIdx.x + 1;
+    if (stop && threadIdx.x == 0) stop[row] = 0;
+  }
+  int t = token_of(src, row);
   t = t < 0 ? 0 : (t >= vocab ? vocab - 1 : t);
-  const T* src = emb + (long long)t * d;
-  T* dst = x + (long long)row * d;
-  for (int i = threadIdx.x; i < d; i += blockDim.x) dst[i] = src[i];
+  const T* er = emb + (long long)t * d;
+  T* xr = x + (long long)row * d;
+  float ss = 0.f;
+  const bool vec = (d & 3) == 0;
+  if (vec) {
+    for (int i = threadIdx.x * 4; i < d; i += 1024) {
+      const float4 v = load4(er + i);
+      store4(xr + i, v);
+      ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+    }
+  } else {
+    for (int i = threadIdx.x; i < d; i += 256) {
+      const T e = er[i];
+      xr[i] = e;
+      const float v = to_f32<T>(e);
+      ss += v * v;
+    }
+  }
+  if (!g) return;
+  for (int off = 32; off >= 1; off >>= 1) ss += __shfl_xor(ss, off);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  const float inv = 1.0f / sqrtf((red[0] + red[1] + red[2] + red[3]) / (float)d + eps);
+  T* yr = xn + (long long)row * d;
+  if (vec) {
+    for (int i = threadIdx.x * 4; i < d; i += 1024) {
+      const float4 v = load4(er + i), gg = load4(g + i);
+      store4(yr + i, make_float4(v.x * inv * gg.x, v.y * inv * gg.y, v.z * inv * gg.z, v.w * inv * gg.w));
+    }
+  } else {
+    for (int i = threadIdx.x; i < d; i += 256) yr[i] = from_f32<T>(to_f32<T>(er[i]) * inv * to_f32<T>(g[i]));
+  }
 }
 
 template <typename T>
@@ -88,12 +144,14 @@ __global__ void scatter_qkv_kernel(const T* __restrict__ qkv, T* __restrict__ q,
   }
 }
 
-// greedy token per row; ties go to the lowest id
+// greedy token per row; ties go to the lowest id.  One workgroup of 1024 lanes per row; a lane has up to eight 8- or
+// 16-byte loads of the row in flight before it compares anything (the row is read once, and a row of 32768 logits
+// is only 64 KB: the kernel's time is the latency of its loads).
 template <typename T>
-__global__ __launch_bounds__(256) void argmax_kernel(const T* __restrict__ logits, int vocab, int32_t* __restrict__ out,
-                                                     long long out_stride) {
-  __shared__ float sv[4];
-  __shared__ int si[4];
+__global__ __launch_bounds__(1024) void argmax_kernel(const T* __restrict__ logits, int vocab, int32_t* __restrict__ out,
+                                                      long long out_stride) {
+  __shared__ float sv[16];
+  __shared__ int si[16];
   const long long row = blockIdx.x;
   const T* lr = logits + row * vocab;
   float best = -INFINITY;
@@ -105,15 +163,26 @@ __global__ __launch_bounds__(256) void argmax_kernel(const T* __restrict__ logit
     }
   };
   if ((vocab & 3) == 0) {
-    for (int i = threadIdx.x * 4; i < vocab; i += 1024) {
-      const float4 v = load4(lr + i);
-      consider(v.x, i);
-      consider(v.y, i + 1);
-      consider(v.z, i + 2);
-      consider(v.w, i + 3);
+    for (int base = threadIdx.x * 4; base < vocab; base += 8 * 4096) {
+      float4 v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int i = base + u * 4096;
+        v[u] = i < vocab ? load4(lr + i) : make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int i = base + u * 4096;
+        if (i < vocab) {
+          consider(v[u].x, i);
+          consider(v[u].y, i + 1);
+          consider(v[u].z, i + 2);
+          consider(v[u].w, i + 3);
+        }
+      }
     }
   } else {
-    for (int i = threadIdx.x; i < vocab; i += 256) consider(to_f32<T>(lr[i]), i);
+    for (int i = threadIdx.x; i < vocab; i += 1024) consider(to_f32<T>(lr[i]), i);
   }
   for (int off = 32; off >= 1; off >>= 1) {
     const float ov = __shfl_xor(best, off);
@@ -129,7 +198,7 @@ __global__ __launch_bounds__(256) void argmax_kernel(const T* __restrict__ logit
   }
   __syncthreads();
   if (threadIdx.x == 0) {
-    for (int w = 1; w < 4; ++w)
+    for (int w = 1; w < 16; ++w)
       if (sv[w] > best || (sv[w] == best && si[w] < bi)) {
         best = sv[w];
         bi = si[w];
@@ -139,7 +208,7 @@ __global__ __launch_bounds__(256) void argmax_kernel(const T* __restrict__ logit
 }
 
 // Finishes a deferred GEMM for one row per workgroup: v = sum_s part[s][row][:] (+ bias) (+ residual);
-// x_out = v (storage dtype); if g: xn_out = v / sqrt(mean(v^2) + eps) * g.  Partials are summed in split
+// x_out = v (storage dtype; also x_out2 when given); if g: xn_out = v / sqrt(mean(v^2) + eps) * g.  Partials are summed in split
 // order.  Up to 1024 threads per row, each owning NV groups of four consecutive columns held in registers,
 // so the row is read once.
 constexpr int FIN_NV = 4;  // column groups per thread: rows up to 1024 * 4 * FIN_NV = 16384 wide
@@ -147,8 +216,8 @@ constexpr int FIN_NV = 4;  // column groups per thread: rows up to 1024 * 4 * FI
 template <typename T>
 __global__ __launch_bounds__(1024) void finish_norm_kernel(const float* __restrict__ part, int splits, long long MN,
                                                            const T* __restrict__ bias, const T* residual, T* x_out,
-                                                           const T* __restrict__ g, T* __restrict__ xn_out, int d,
-                                                           float eps) {
+                                                           T* __restrict__ x_out2, const T* __restrict__ g,
+                                                           T* __restrict__ xn_out, int d, float eps) {
   __shared__ float red[16];
   const long long row = blockIdx.x;
   const float* pr = part + row * d;
@@ -198,6 +267,7 @@ __global__ __launch_bounds__(1024) void finish_norm_kernel(const float* __restri
     const int c = threadIdx.x * 4 + i * stride;
     if (c < d) {
       store4(x_out + row * d + c, v[i]);
+      if (x_out2) store4(x_out2 + row * d + c, v[i]);
       if (g) {
         const float4 gg = load4(g + c);
         store4(xn_out + row * d + c,
@@ -245,21 +315,6 @@ __global__ __launch_bounds__(1024) void finish_scatter_kernel(const float* __res
     }
     store4(dst, v);
   }
-}
-
-// ncur[r][b] = r + 1 (own-block rows visible to draft run r);  stop[b] = 0 (adaptive block length: nobody has stopped)
-__global__ void prepare_step_kernel(const int32_t* pending, int32_t* ncur, int32_t* stop, int B, int gamma) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < B * gamma) ncur[i] = i / B + 1;
-  if (stop && i < B) stop[i] = 0;
-}
-// block_tokens[b, r] (r < q): the tokens M_L processes, pending[b] then the first q - 1 of follow[b, :gamma]
-__global__ void block_tokens_kernel(const int32_t* pending, const int32_t* follow, int32_t* block_tokens, int B,
-                                    int gamma, int q) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= B * q) return;
-  const int b = i / q, r = i % q;
-  block_tokens[i] = r == 0 ? pending[b] : follow[b * gamma + r - 1];
 }
 
 // Sec. 3.1: first location where the draft differs from M_L's token; emit the agreed prefix and
@@ -314,14 +369,18 @@ int launch_advance(int32_t* n, int B, int by, int64_t cap, hipStream_t st) {
   return hip_ok(hipGetLastError());
 }
 
-int launch_embed(const void* emb, const int32_t* tokens, int64_t tok_stride, void* x, int rows, int d, int vocab,
-                 int dtype, hipStream_t st) {
+int launch_embed_norm(const void* emb, const int32_t* tokens, int64_t tok_stride, const int32_t* pending,
+                      const int32_t* follow, int gamma, int q, int r0, void* x, const void* g, void* xn, int rows, int d,
+                      int vocab, float eps, int32_t* ncur, int32_t* stop, int init_B, int init_gamma, int dtype,
+                      hipStream_t st) {
+  if (init_gamma > 256) return TANDEM_ERR_UNSUPPORTED;
+  TokenSrc src{tokens, (long long)tok_stride, pending, follow, gamma, q > 0 ? q : 1, r0};
   if (dtype == TANDEM_BF16)
-    hipLaunchKernelGGL(embed_kernel<bf16_t>, dim3(rows), dim3(256), 0, st, (const bf16_t*)emb, tokens,
-                       (long long)tok_stride, (bf16_t*)x, d, vocab);
+    hipLaunchKernelGGL(embed_norm_kernel<bf16_t>, dim3(rows), dim3(256), 0, st, (const bf16_t*)emb, src, (bf16_t*)x,
+                       (const bf16_t*)g, (bf16_t*)xn, d, vocab, eps, ncur, stop, init_B, init_gamma);
   else
-    hipLaunchKernelGGL(embed_kernel<float>, dim3(rows), dim3(256), 0, st, (const float*)emb, tokens,
-                       (long long)tok_stride, (float*)x, d, vocab);
+    hipLaunchKernelGGL(embed_norm_kernel<float>, dim3(rows), dim3(256), 0, st, (const float*)emb, src, (float*)x,
+                       (const float*)g, (float*)xn, d, vocab, eps, ncur, stop, init_B, init_gamma);
   return hip_ok(hipGetLastError());
 }
 
@@ -336,17 +395,17 @@ int launch_rmsnorm(const void* x, const void* g, void* y, int rows, int d, float
 }
 
 int launch_finish_norm(const float* part, int splits, const void* bias, const void* residual, void* x_out,
-                       const void* g, void* xn_out, int rows, int d, float eps, int dtype, hipStream_t st) {
+                       const void* g, void* xn_out, int rows, int d, float eps, int dtype, hipStream_t st, void* x_out2) {
   if (d % 4 != 0 || d > 1024 * 4 * FIN_NV) return TANDEM_ERR_UNSUPPORTED;
   const long long MN = (long long)rows * d;
   int threads = (d / 4 + 63) / 64 * 64;
   threads = threads > 1024 ? 1024 : threads;
   if (dtype == TANDEM_BF16)
     hipLaunchKernelGGL(finish_norm_kernel<bf16_t>, dim3(rows), dim3(threads), 0, st, part, splits, MN, (const bf16_t*)bias,
-                       (const bf16_t*)residual, (bf16_t*)x_out, (const bf16_t*)g, (bf16_t*)xn_out, d, eps);
+                       (const bf16_t*)residual, (bf16_t*)x_out, (bf16_t*)x_out2, (const bf16_t*)g, (bf16_t*)xn_out, d, eps);
   else
     hipLaunchKernelGGL(finish_norm_kernel<float>, dim3(rows), dim3(threads), 0, st, part, splits, MN, (const float*)bias,
-                       (const float*)residual, (float*)x_out, (const float*)g, (float*)xn_out, d, eps);
+                       (const float*)residual, (float*)x_out, (float*)x_out2, (const float*)g, (float*)xn_out, d, eps);
   return hip_ok(hipGetLastError());
 }
 
@@ -381,23 +440,11 @@ int launch_scatter_qkv(const void* qkv, void* q, void* kc, void* vc, const int32
 
 int launch_argmax(const void* logits, int rows, int vocab, int32_t* out, int64_t out_stride, int dtype, hipStream_t st) {
   if (dtype == TANDEM_BF16)
-    hipLaunchKernelGGL(argmax_kernel<bf16_t>, dim3(rows), dim3(256), 0, st, (const bf16_t*)logits, vocab, out,
+    hipLaunchKernelGGL(argmax_kernel<bf16_t>, dim3(rows), dim3(1024), 0, st, (const bf16_t*)logits, vocab, out,
                        (long long)out_stride);
   else
-    hipLaunchKernelGGL(argmax_kernel<float>, dim3(rows), dim3(256), 0, st, (const float*)logits, vocab, out,
+    hipLaunchKernelGGL(argmax_kernel<float>, dim3(rows), dim3(1024), 0, st, (const float*)logits, vocab, out,
                        (long long)out_stride);
-  return hip_ok(hipGetLastError());
-}
-
-int launch_prepare_step(const int32_t* pending, int32_t* ncur, int32_t* stop, int B, int gamma, hipStream_t st) {
-  hipLaunchKernelGGL(prepare_step_kernel, dim3((B * gamma + 255) / 256), dim3(256), 0, st, pending, ncur, stop, B, gamma);
-  return hip_ok(hipGetLastError());
-}
-
-int launch_block_tokens(const int32_t* pending, const int32_t* follow, int32_t* block_tokens, int B, int gamma, int q,
-                        hipStream_t st) {
-  hipLaunchKernelGGL(block_tokens_kernel, dim3((B * q + 255) / 256), dim3(256), 0, st, pending, follow, block_tokens,
-                     B, gamma, q);
   return hip_ok(hipGetLastError());
 }
 

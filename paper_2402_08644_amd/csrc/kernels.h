@@ -92,9 +92,17 @@ int launch_gemm(const GemmArgs& g, hipStream_t st);
 
 // ---------------------------------------------------------------- glue (glue.hip)
 int launch_rmsnorm(const void* x, const void* g, void* y, int rows, int d, float eps, int dtype, hipStream_t st);
-// finishes a deferred GEMM row by row: v = sum of partials (+ bias) (+ residual); x_out = v; and, when g is
-// given, xn_out = RMSNorm(v; g).  residual may alias x_out.
+// finishes a deferred GEMM row by row: v = sum of partials (+ bias) (+ residual); x_out = v (and x_out2 = v when
+// given: a second copy that outlives the next in-place update); and, when g is given, xn_out = RMSNorm(v; g).
+// residual may alias x_out.
 int launch_finish_norm(const float* part, int splits, const void* bias, const void* residual, void* x_out,
-                       const void* g, void* xn_out, int rows, int d, float eps, int dtype, hipStream_t st);
-int launch_embed(const void* emb, const int32_t* tokens, int64_t tok_stride, void* x, int rows, int d, int vocab,
-                 int dtype, hipStream_t st);
+                       const void* g, void* xn_out, int rows, int d, float eps, int dtype, hipStream_t st,
+                       void* x_out2 = nullptr);
+// x[row] = emb[token(row)] and, when g is given, xn[row] = RMSNorm(x[row]; g).  token(row): tokens[row * tok_stride],
+// or - pending given - the token at block position r = row % q + r0 of sequence b = row / q: pending[b] for r = 0,
+// follow[b * gamma + r - 1] otherwise.  init_B > 0 (rows == init_B): also ncur[r][b] = r + 1 for r < init_gamma and
+// stop[b] = 0 (stop optional) - the bookkeeping the first draft run of a step needs.
+int launch_embed_norm(const void* emb, const int32_t* tokens, int64_t tok_stride, const int32_t* pending,
+                      const int32_t* follow, int gamma, int q, int r0, void* x, const void* g, void* xn, int rows, int d,
+                      int vocab, float eps, int32_t* ncur, int32_t* stop, int init_B, int init_gamma, int dtype,
+                      hipStream_t st);
