@@ -702,13 +702,9 @@ def run_project_workload(torch, binding, inputs, args):
 
 
 def _traffic(name):
-    """HBM traffic per launch measured offline with rocprofv3 counters (see profiles/), or None."""
-    path = os.path.join(ROOT, "profiles", "traffic.json")
-    try:
-        with open(path) as f:
-            return json.load(f).get(name)
-    except Exception:
-        return None
+    """HBM traffic per launch measured offline with rocprofv3 counters (profiles/measured.json), or None."""
+    m = _measured(name)
+    return m.get("hbm_bytes_per_launch") if m else None
 
 
 def run_kernel_workload(torch, binding, inputs, args):
@@ -739,6 +735,53 @@ def run_kernel_workload(torch, binding, inputs, args):
                      "traffic": _traffic(args.workload)},
         "cpu_baseline": cpu,
     }
+
+
+def _quick_extra(torch, binding, inputs, args):
+    """Short timings of the other configurations' entry points, so that one default run shows every number the
+    target names: C1 / C2 / C4 attention (HBM-bound) and FF_Tandem at decode and prompt sizes."""
+    import gc
+
+    extra = {}
+    for name in ("c1_draft", "c2_block", "c4_draft", "c4_block"):
+        kind, kw, _n, _desc = WORKLOADS[name]
+        maker = {"draft": draft_workload, "block": block_workload}[kind]
+        call, n_copies, bytes_alg, _oracle = maker(torch, binding, inputs, **kw)
+        torch.cuda.synchronize()
+        ms = _time_calls(torch, call, n_copies, 60 if name.startswith("c4") else 200, 10, use_graph=not args.no_graph)
+        gbs = bytes_alg / (ms * 1e-3) / 1e9
+        extra[name] = {"us": ms * 1e3, "GBps": gbs, "frac_of_hbm_peak": gbs / HBM_PEAK_GBS}
+        del call, _oracle
+        gc.collect()
+        torch.cuda.empty_cache()
+    for name in ("c2_project", "c3_project", "project_m4096"):
+        sub = argparse.Namespace(**vars(args))
+        sub.workload, sub.no_cpu_baseline = name, True
+        sub.steps, sub.warmup = (20, 5) if name == "project_m4096" else (200, 20)
+        line = run_project_workload(torch, binding, inputs, sub)
+        extra[name] = {"us": line["ms_per_step"] * 1e3, "TFLOPs": line["value"], "roofline": {k: line["roofline"][k] for k in ("bound", "frac")}}
+        gc.collect()
+        torch.cuda.empty_cache()
+    return extra
+
+
+def _read_ceiling(torch, binding, tensors, use_graph):
+    """Rate of the library's plain read-only stream kernel over the given (large, distinct) device tensors."""
+    sink = torch.empty(binding.READ_STREAM_BLOCKS, dtype=torch.int32, device="cuda")
+    call = lambda i: binding.tandem_read_stream(tensors[i], sink)
+    ms = _time_calls(torch, call, len(tensors), 4 * len(tensors), 4, use_graph=use_graph)
+    nbytes = tensors[0].numel() * tensors[0].element_size()
+    return nbytes / (ms * 1e-3) / 1e9
+
+
+def _measured(name):
+    """Figures taken offline with rocprofv3 and kept under profiles/ (measured.json names the summary each comes from)."""
+    path = os.path.join(ROOT, "profiles", "measured.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get(name)
+    except Exception:
+        return None
 
 
 def run_step_workload(torch, binding, inputs, args):
@@ -772,14 +815,31 @@ def run_step_workload(torch, binding, inputs, args):
     gbs_blk = bytes_blk / (ms_blk * 1e-3) / 1e9
     gbs_drf = bytes_drf / (ms_drf * 1e-3) / 1e9
     total_bytes = step_bytes(cfg)
+    # the box's read ceiling: the plain read-only stream kernel over the same caches (537 MB each, one after the other)
+    ceiling = _read_ceiling(torch, binding, state.KL[:8], not args.no_graph)
+
+    def roof(kernel, gbs, ms_launch, key):
+        prof = _measured(key) or {}
+        r = {"bound": "hbm", "kernel": kernel, "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
+             "frac_is": "kernel launched alone in the step's launch configuration (live HIP events, this run)",
+             "ms_per_launch": ms_launch, "read_stream_ceiling_GBps": ceiling, "frac_of_read_ceiling": gbs / ceiling,
+             "traffic": prof.get("hbm_bytes_per_launch"), "traffic_source": prof.get("traffic_source")}
+        if prof.get("in_step_us"):
+            bytes_alg = bytes_blk if key == "c3_block" else bytes_drf
+            r["in_step"] = {"us": prof["in_step_us"], "frac": bytes_alg / (prof["in_step_us"] * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                            "source": prof.get("in_step_source")}
+        return r
 
     cpu = None
     if not args.no_cpu_baseline:
         est, parts = cpu_step_estimate(torch, inputs, cfg, state, model)
         cpu = {"value": 1.0 / est, "unit": "steps/s", "cores": _cpu_threads(), "kind": "oracle",
-               "sample": "fp64 numpy oracle pieces timed on one sequence of one layer (draft and block attention) and on a "
-                         "quarter of one layer's dense products, extrapolated by layer, run and batch counts: "
-                         + ", ".join(f"{k}={v:.3f}s" for k, v in parts.items())}
+               "sample": "fp64 numpy oracle pieces timed on the step's own caches (sequence 0 of layer 0 for the draft and the "
+                         "block attention: single-threaded loops over heads and rows around BLAS calls) and on a quarter of one "
+                         "layer's dense products (BLAS, `cores` threads), extrapolated by layer, run and batch counts: "
+                         + ", ".join(f"{k}={v:.3f}s" for k, v in parts.items())
+                         + "; no parity is taken on these slices (parity at this configuration: tests/test_gpu_full_size.py)"}
+    extra = None if args.no_extra else _quick_extra(torch, binding, inputs, args)
     return {
         "metric": "Tandem decode steps/sec at gamma=4 (draft/verify attention HBM GB/s in roofline)",
         "value": 1e3 / ms, "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
@@ -791,13 +851,10 @@ def run_step_workload(torch, binding, inputs, args):
                                   f"drafted in the last step: {sorted(out['n_drafted'].cpu().tolist())})" if args.adaptive else ""),
                    "step_algorithmic_GB": total_bytes / 1e9, "step_GBps": total_bytes / (ms * 1e-3) / 1e9,
                    "step_frac_of_hbm_peak": total_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
-        "roofline": {"bound": "hbm", "kernel": "attn_block_kernel (tandem_block_attn, one large layer of the step)",
-                     "achieved": gbs_blk, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs_blk / HBM_PEAK_GBS,
-                     "ms_per_launch": ms_blk, "traffic": _traffic("c3_block")},
-        "roofline_draft": {"bound": "hbm", "kernel": "attn_rows_kernel (tandem_draft_attn, one small layer of the step)",
-                           "achieved": gbs_drf, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs_drf / HBM_PEAK_GBS,
-                           "ms_per_launch": ms_drf, "traffic": _traffic("c3_draft")},
+        "roofline": roof("attn_block_kernel (tandem_block_attn, one large layer of the step)", gbs_blk, ms_blk, "c3_block"),
+        "roofline_draft": roof("attn_rows_kernel (tandem_draft_attn, one small layer of the step)", gbs_drf, ms_drf, "c3_draft"),
         "cpu_baseline": cpu,
+        "extra": extra,
     }
 
 
@@ -811,6 +868,8 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--plain-weights", action="store_true",
                     help="read weights in the caller's row-major layout only (no packed copies)")
+    ap.add_argument("--no-extra", action="store_true",
+                    help="c3_step: skip the short timings of the other configurations (C1, C2, C4, FF_Tandem)")
     ap.add_argument("--adaptive", action="store_true",
                     help="c3_step: run the step with the adaptive block length (tandem_decode_step_adaptive)")
     ap.add_argument("--free-token", action="store_true",

@@ -398,6 +398,14 @@ int tandem_score(const tandem_model *m, const tandem_state_desc *state, void *co
                  const int32_t *pos, const int32_t *tokens, int32_t q_len, int32_t gamma, int32_t *greedy, void *logits,
                  void *y_small, void *ws, size_t ws_bytes, void *hip_stream);
 
+/* Measurement helper, no part of the method: reads src[0 : bytes) (device, 16-byte aligned; a multiple of 16 bytes is
+ * read) once with plain coalesced 16-byte loads and writes TANDEM_READ_STREAM_BLOCKS 32-bit words of folded data to
+ * sink (device).  The rate this call reaches is the read ceiling of the box for kernels that stream HBM once, the
+ * yardstick bench.py reports next to the datasheet peak for the attention kernels (Sec. 3.1, footnote: attention is
+ * the part of decoding whose memory traffic does not amortise over the batch). */
+#define TANDEM_READ_STREAM_BLOCKS 2048
+int tandem_read_stream(const void *src, size_t bytes, void *sink, void *hip_stream);
+
 const char *tandem_status_string(int status);
 
 #pragma GCC visibility pop

@@ -92,7 +92,7 @@ STEP_FREE_TOKEN = 1
 PREFILL_EMIT = 1
 
 EXPORTS = (
-    "tandem_status_string",
+    "tandem_status_string", "tandem_read_stream",
     "tandem_project_workspace", "tandem_block_attn_workspace", "tandem_draft_attn_workspace",
     "tandem_packed_weight_bytes", "tandem_pack_weight",
     "tandem_project", "tandem_block_attn", "tandem_draft_attn", "tandem_draft_attn_static",
@@ -122,6 +122,8 @@ def lib():
     vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
     L.tandem_status_string.restype = C.c_char_p
     L.tandem_status_string.argtypes = [C.c_int]
+    L.tandem_read_stream.restype = C.c_int
+    L.tandem_read_stream.argtypes = [vp, sz, vp, vp]
     L.tandem_project_workspace.restype = sz
     L.tandem_project_workspace.argtypes = [C.POINTER(FFDesc), i64]
     L.tandem_decode_step_shared_workspace.restype = sz
@@ -237,6 +239,16 @@ def workspace(nbytes, device="cuda"):
     import torch
 
     return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+READ_STREAM_BLOCKS = 2048
+
+
+def tandem_read_stream(src, sink, stream=None):
+    """Plain read-only stream over the bytes of `src` (measurement helper); sink: int32 device tensor of
+    READ_STREAM_BLOCKS elements."""
+    _check(lib().tandem_read_stream(_ptr(src), src.numel() * src.element_size(), _ptr(sink), _stream(stream)),
+           "tandem_read_stream")
 
 
 def attn_desc(B, Hq, Hkv, dh, T_max, gamma_max, scale, dtype_code):

@@ -31,6 +31,35 @@ static __device__ __align__(256) unsigned char scratch[TANDEM_STATIC_SCRATCH_BYT
 
 namespace {
 
+// Plain read-only stream: every workgroup walks a contiguous piece of the buffer of its own with 16-byte loads (a
+// wavefront reads 1 KB of consecutive addresses per instruction, the workgroup 4 KB), eight loads in flight per lane;
+// the values are folded into one word per workgroup so that the loads cannot be dropped.  What this kernel reaches
+// is the box's ceiling for any kernel that reads HBM once.
+__global__ __launch_bounds__(256) void read_stream_kernel(const uint4* __restrict__ src, long long n16,
+                                                          uint32_t* __restrict__ sink) {
+  const long long per = (n16 + gridDim.x - 1) / gridDim.x;
+  const long long begin = (long long)blockIdx.x * per;
+  const long long end = begin + per < n16 ? begin + per : n16;
+  long long i = begin + threadIdx.x;
+  uint32_t acc = 0;
+  for (; i + 7 * 256 < end; i += 8 * 256) {
+    uint4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = src[i + u * 256];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+  }
+  for (; i < end; i += 256) {
+    const uint4 a = src[i];
+    acc ^= a.x ^ a.y ^ a.z ^ a.w;
+  }
+  for (int off = 32; off >= 1; off >>= 1) acc ^= __shfl_xor(acc, off);
+  __shared__ uint32_t red[4];
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) sink[blockIdx.x] = red[0] ^ red[1] ^ red[2] ^ red[3];
+}
+
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // Device address of `scratch` on the current device, looked up once per device.
@@ -113,6 +142,14 @@ const char* tandem_status_string(int status) {
     case TANDEM_ERR_HIP: return "HIP runtime error";
     default: return "unknown status";
   }
+}
+
+int tandem_read_stream(const void* src, size_t bytes, void* sink, void* hip_stream) {
+  if (!src || !sink) return TANDEM_ERR_NULL;
+  if (bytes < 16 || reinterpret_cast<uintptr_t>(src) % 16 != 0) return TANDEM_ERR_SHAPE;
+  hipLaunchKernelGGL(read_stream_kernel, dim3(TANDEM_READ_STREAM_BLOCKS), dim3(256), 0, (hipStream_t)hip_stream,
+                     (const uint4*)src, (long long)(bytes / 16), (uint32_t*)sink);
+  return hip_ok(hipGetLastError());
 }
 
 size_t tandem_draft_attn_workspace(const tandem_attn_desc* a) {
