@@ -550,7 +550,9 @@ bool attn_block_supported(const AttnArgs& a) { return a.dtype == TANDEM_BF16 && 
 // Context splits: a function of shapes only.  Measured on MI355X: about 512 workgroups in total (two
 // per CU) stream best; more splits only add partials and tail effects.  At least 8 tiles (256 keys) each.
 int attn_block_splits(int B, int Hkv, int q_len, int G, int64_t T_max, int* wide) {
-  const int64_t groups = (int64_t)B * Hkv;
+  // more than 32 query rows per KV head run as row passes of up to 128 rows, each a workgroup of its own
+  const int tiles = (G * q_len + 15) / 16;
+  const int64_t groups = (int64_t)B * Hkv * (tiles > 2 ? (tiles + 7) / 8 : 1);
   int64_t want = (512 + groups - 1) / groups;
   int64_t cap = T_max / 256;
   if (cap < 1) cap = 1;

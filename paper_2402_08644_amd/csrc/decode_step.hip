@@ -228,8 +228,10 @@ StepPlan make_plan(const tandem_model* m, int B, int gamma, int64_t T_max, int g
     auto blk_ws = [&](int q) -> size_t {
       return carved((size_t)B * q * L.Hq, smax(mfma ? (int64_t)B * L.Hkv : (int64_t)B * L.Hkv * q), L.dh);
     };
-    size_t b = blk_ws(gamma < TANDEM_MAX_QLEN ? gamma : TANDEM_MAX_QLEN);
-    if (gamma > TANDEM_MAX_QLEN && gamma % TANDEM_MAX_QLEN) b = maxz(b, blk_ws(gamma % TANDEM_MAX_QLEN));
+    // the matrix-core kernels take up to TANDEM_MAX_PREFILL rows per call (row passes inside one launch)
+    const int sub = mfma ? TANDEM_MAX_PREFILL : TANDEM_MAX_QLEN;
+    size_t b = blk_ws(gamma < sub ? gamma : sub);
+    if (gamma > sub && gamma % sub) b = maxz(b, blk_ws(gamma % sub));
     p.attn_ws_bytes = maxz(a, b);
     if (score) {
       // tandem_mixed_attn: the K_hat segment's splits plus one slot for the own-row segment (matrix-core kernels)
@@ -464,8 +466,9 @@ int large_block_pass(const Ctx& c, const int32_t* tokens, const int32_t* follow,
     auto attn_only = [&]() -> int {
       // more than TANDEM_MAX_QLEN rows per sequence (long prompt chunks): the attention runs on sub-blocks of rows,
       // all of whose K/V rows are already in the cache
-      for (int r0 = 0; r0 < nq; r0 += TANDEM_MAX_QLEN) {
-        const int rows = nq - r0 < TANDEM_MAX_QLEN ? nq - r0 : TANDEM_MAX_QLEN;
+      const int sub = c.dtype == TANDEM_BF16 && L.dh == 128 && !c.pr ? TANDEM_MAX_PREFILL : TANDEM_MAX_QLEN;
+      for (int r0 = 0; r0 < nq; r0 += sub) {
+        const int rows = nq - r0 < sub ? nq - r0 : sub;
         TRY(attn_call(c, L, q, state->KL[j], state->VL[j], state->n, nullptr, nullptr, nullptr, 1, rows, att, r0, nq,
                       c.pr ? c.pr->KLp[j] : nullptr, c.pr ? c.pr->VLp[j] : nullptr));
       }
