@@ -33,7 +33,9 @@ Parity pins (tests/test_oracle_*.py): brute-force python-loop softmax, hand
 cases, torch CPU scaled_dot_product_attention with an explicit mask, closed
 forms (zero FF_Tandem), block-by-block == causal forward, gamma=1 == causal
 decode, gamma -> inf == small model alone, incremental == teacher-forced,
-SPEED stream == greedy M_L stream, integer schedules of Fig. 2 / Fig. 4.
+SPEED stream == greedy M_L stream, integer schedules of Fig. 2 / Fig. 4; Deep Tandem (Sec. 5) against a
+mask-based torch formulation and its limits (zero FF_DeepTandem == plain M_S; block length beyond the sequence ==
+a constant sketch).
 Parity unpinned by the paper (it prints no tensor values): the block internals
 listed above (norm, activation, eps, head) and the MLP form of FF_Tandem; they
 are pinned only by the configuration text this build was given.
@@ -606,6 +608,86 @@ def block_prefix_attn(Q, Kc, Vc, n, gamma, scale):
                 out[b, r, h] = attention_one(Q[b, r, h], np.asarray(Kc, F64)[b, kv, :visible],
                                              np.asarray(Vc, F64)[b, kv, :visible], scale)
     return out
+
+
+# ----------------------------------------------------------------------------
+# Deep Tandem (Sec. 5, Eq. (3) and Eq. (4)): M_L predicts a sketch of the next block in parallel, M_S samples
+# autoregressively on top of it.  Written in the paper's 1-indexed notation: tokens x_1 .. x_S, block length gamma.
+#
+#   Eq. (3), for every row i >= 1 and k = ceil((i - gamma) / gamma):
+#     x_i^(0)   = Emb_L(x_{i - gamma})                                   (the formula's reading, see below)
+#     x~_i^(j+1) = Atn_L^(j+1)( x_i^(j) | x_{<= k gamma}^(j) ),   x_i^(j+1) = FF_L^(j+1)(x~_i^(j+1))
+#   Eq. (4), for every row i >= 2:
+#     y_i^(0)   = Emb_S(x_{i-1}) + FF_DeepTandem(x_i^(L_L))
+#     y~_i^(j+1) = Atn_S^(j+1)( y_i^(j) | y_{<= i}^(j) ),         y_i^(j+1) = FF_S^(j+1)(y~_i^(j+1))
+#   y_i^(L_S) is the model's prediction of token i.
+#
+# Readings (the paper is at odds with itself or silent; each is listed in the design notes):
+#   * the input of row i: the displayed formula gives Emb_L of token i - gamma, the sentence after it the
+#     (ceil((i - gamma) / gamma) gamma)-th token.  The formula is taken: with the sentence's reading all gamma rows
+#     of a block would get the same input and - there being no positional encoding here - the same sketch.
+#   * rows i <= gamma have no token i - gamma and see no key (k = 0): x_i^(0) = 0 and the attention output is 0
+#     (the layers' residual and MLP still act on them).
+#   * keys and values of a visible row are that row's own x^(j) under the layer's norm and W_K / W_V, as in Eq. (1).
+#   * M_S has no input for i = 1 (there is no x_0): its rows are i = 2 .. S + 1; row i reads M_L's row i.
+#   * blocks, norms, MLPs, heads as in the Tandem forward above.
+# T["ff_deep"]: FF_DeepTandem, d_L -> d_S, same forms as FF_Tandem.
+# ----------------------------------------------------------------------------
+def deep_tandem_forward(T, tokens, gamma):
+    """tokens: x_1 .. x_S.  Returns {"sketch": x^(L_L) of rows i = 1 .. S+1, "y": y^(L_S) of rows i = 2 .. S+1
+    (S rows; row i predicts token i), "logits": M_S's logits of those rows}."""
+    eps = T["eps"]
+    ML, MS = T["L"], T["S"]
+    x_tok = {i + 1: int(t) for i, t in enumerate(np.asarray(tokens))}  # 1-indexed tokens
+    S = len(x_tok)
+    rows = list(range(1, S + 2))  # rows of M_L
+    dL = np.asarray(ML["emb"]).shape[1]
+    x = {i: (np.asarray(ML["emb"], F64)[x_tok[i - gamma]] if i - gamma >= 1 else np.zeros(dL, F64)) for i in rows}
+    Hq, Hkv, dh = ML["Hq"], ML["Hkv"], ML["dh"]
+    G = Hq // Hkv
+    scale = 1.0 / math.sqrt(dh)
+    for lay in ML["layers"]:
+        hn = {i: rmsnorm(x[i], lay["g_attn"], eps) for i in rows}
+        q = {i: linear(hn[i], lay["Wq"]).reshape(Hq, dh) for i in rows}
+        kk = {i: linear(hn[i], lay["Wk"]).reshape(Hkv, dh) for i in rows}
+        vv = {i: linear(hn[i], lay["Wv"]).reshape(Hkv, dh) for i in rows}
+        nxt = {}
+        for i in rows:
+            k = -((-(i - gamma)) // gamma)  # ceil((i - gamma) / gamma)
+            vis = list(range(1, max(k, 0) * gamma + 1))  # rows x_1 .. x_{k gamma}
+            a = np.zeros((Hq, dh), F64)
+            if vis:
+                for h in range(Hq):
+                    K = np.stack([kk[p][h // G] for p in vis])
+                    V = np.stack([vv[p][h // G] for p in vis])
+                    a[h] = attention_one(q[i][h], K, V, scale)
+            xt = x[i] + linear(a.reshape(Hq * dh), lay["Wo"])
+            nxt[i] = xt + mlp(rmsnorm(xt, lay["g_mlp"], eps), lay)
+        x = nxt
+    sketch = np.stack([x[i] for i in rows])
+    srows = list(range(2, S + 2))  # rows of M_S
+    y = {i: np.asarray(MS["emb"], F64)[x_tok[i - 1]] + project(x[i], T["ff_deep"]) for i in srows}
+    Hq, Hkv, dh = MS["Hq"], MS["Hkv"], MS["dh"]
+    G = Hq // Hkv
+    scale = 1.0 / math.sqrt(dh)
+    for lay in MS["layers"]:
+        hn = {i: rmsnorm(y[i], lay["g_attn"], eps) for i in srows}
+        q = {i: linear(hn[i], lay["Wq"]).reshape(Hq, dh) for i in srows}
+        kk = {i: linear(hn[i], lay["Wk"]).reshape(Hkv, dh) for i in srows}
+        vv = {i: linear(hn[i], lay["Wv"]).reshape(Hkv, dh) for i in srows}
+        nxt = {}
+        for i in srows:
+            vis = [p for p in srows if p <= i]
+            a = np.zeros((Hq, dh), F64)
+            for h in range(Hq):
+                K = np.stack([kk[p][h // G] for p in vis])
+                V = np.stack([vv[p][h // G] for p in vis])
+                a[h] = attention_one(q[i][h], K, V, scale)
+            yt = y[i] + linear(a.reshape(Hq * dh), lay["Wo"])
+            nxt[i] = yt + mlp(rmsnorm(yt, lay["g_mlp"], eps), lay)
+        y = nxt
+    yo = np.stack([y[i] for i in srows])
+    return {"sketch": sketch, "y": yo, "logits": logits_of(MS, yo, eps)}
 
 
 # ----------------------------------------------------------------------------

@@ -221,7 +221,7 @@ def decoder_weights(rng, vocab, d, n_layers, Hq, Hkv, dh, d_ff, dtype, w_std=0.0
 
 
 def tandem_weights(seed, vocab, large, small, ell, d_hidden, dtype, act="gelu", w_std=0.02, eps=1e-6, gain_std=0.0,
-                   bias_std=0.0):
+                   bias_std=0.0, deep=False):
     """A random-init Tandem pair.  ``large``/``small`` are dicts with keys
     d, n_layers, Hq, Hkv, dh, d_ff.  ``ell[j]`` in [0, L_L] is the large layer whose
     output small layer j reads.  d_hidden == 0 gives linear FF_Tandem maps.
@@ -244,7 +244,19 @@ def tandem_weights(seed, vocab, large, small, ell, d_hidden, dtype, act="gelu", 
                     "act": act,
                 }
             )
-    return {"L": L, "S": S, "ell": list(ell), "ff": ff, "eps": eps, "dtype": dtype}
+    out = {"L": L, "S": S, "ell": list(ell), "ff": ff, "eps": eps, "dtype": dtype}
+    if deep:
+        # FF_DeepTandem (Sec. 5): one more map d_L -> d_S, drawn after everything else so that the other weights of a
+        # seed do not depend on the option
+        if d_hidden == 0:
+            out["ff_deep"] = {"W": normal(rng, (small["d"], large["d"]), w_std, dtype),
+                              "b": _bias(rng, (small["d"],), bias_std, dtype)}
+        else:
+            out["ff_deep"] = {"W1": normal(rng, (d_hidden, large["d"]), w_std, dtype),
+                              "b1": _bias(rng, (d_hidden,), bias_std, dtype),
+                              "W2": normal(rng, (small["d"], d_hidden), w_std, dtype),
+                              "b2": _bias(rng, (small["d"],), bias_std, dtype), "act": act}
+    return out
 
 
 def tiny_tandem(seed=0, dtype="f32", gain_std=0.0, bias_std=0.0):
