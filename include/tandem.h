@@ -398,6 +398,40 @@ int tandem_score(const tandem_model *m, const tandem_state_desc *state, void *co
                  const int32_t *pos, const int32_t *tokens, int32_t q_len, int32_t gamma, int32_t *greedy, void *logits,
                  void *y_small, void *ws, size_t ws_bytes, void *hip_stream);
 
+/* ---- Deep Tandem (Sec. 5, Eq. (3) and Eq. (4)), teacher-forced over known tokens ----
+ * M_L predicts a sketch of the next block in parallel; M_S, a plain causal decoder, adds each row's sketch to its input
+ * embedding.  In 0-indexed positions (the paper's row i is row i - 1 of M_L and position i - 2 of M_S):
+ *   M_L row r:   input Emb_L(token r - gamma) (a zero row when r < gamma); it attends, in every layer, the K/V rows of
+ *                M_L rows [0, floor(r / gamma) * gamma) - the blocks completed before its own (no visible row: zero
+ *                attention output); its final representation x^(L_L) is the sketch for M_S's position r - 1
+ *   M_S pos p:   y^(0) = Emb_S(token p) + FF_DeepTandem(sketch of M_L row p + 1); causal attention over its own rows
+ *                [0, p]; y^(L_S) predicts token p + 1
+ * (Where the displayed formula and the sentence after it disagree about M_L's input token, the formula is taken.)
+ * Caches are the caller's, indexed by row / position: KL, VL [L.n_layers] of [B, L.Hkv, T_max, dh] (M_L's rows) and
+ * KS, VS [S.n_layers] of [B, S.Hkv, T_max, dh] (M_S's rows), host arrays of device pointers.
+ *   tandem_deep_begin   computes M_L's row 0 (it has no token and sees nothing, but later rows attend it); once per
+ *                       sequence set, before the first tandem_deep_score
+ *   tandem_deep_score   one chunk: M_S positions pos[b] .. pos[b] + q_len - 1 and M_L rows pos[b] + 1 .. pos[b] + q_len;
+ *                       M_L rows up to pos[b] and M_S rows below pos[b] must be in the caches (earlier calls)
+ *     tokens  device int32 [B, n_tokens]: the known tokens of every sequence (positions >= n_tokens read the last one)
+ *     pos     device int32 [B], pos[b] + q_len < T_max;  1 <= q_len <= TANDEM_MAX_QLEN;  gamma >= 1
+ *     greedy  optional device int32 [B, q_len]; logits optional [B, q_len, vocab]; y_small optional [B, q_len, S.d];
+ *     sketch  optional [B, q_len, L.d]: x^(L_L) of M_L's rows of the chunk
+ *   ff_deep: FF_DeepTandem, d_L = L.d, d_S = S.d, model dtype.  ws: at least tandem_deep_score_workspace(...) bytes. */
+typedef struct {
+  int32_t B;
+  int64_t T_max;
+  void *const *KL, *const *VL; /* host arrays [L.n_layers] */
+  void *const *KS, *const *VS; /* host arrays [S.n_layers] */
+} tandem_deep_state_desc;
+size_t tandem_deep_score_workspace(const tandem_model *m, const tandem_ff_desc *ff_deep, int32_t B, int32_t q_len);
+int tandem_deep_begin(const tandem_model *m, const tandem_ff_desc *ff_deep, const tandem_deep_state_desc *st, void *ws,
+                      size_t ws_bytes, void *hip_stream);
+int tandem_deep_score(const tandem_model *m, const tandem_ff_desc *ff_deep, const tandem_deep_state_desc *st,
+                      const int32_t *tokens, int64_t n_tokens, const int32_t *pos, int32_t q_len, int32_t gamma,
+                      int32_t *greedy, void *logits, void *y_small, void *sketch, void *ws, size_t ws_bytes,
+                      void *hip_stream);
+
 /* Measurement helper, no part of the method: reads src[0 : bytes) (device, 16-byte aligned; a multiple of 16 bytes is
  * read) once with plain coalesced 16-byte loads and writes TANDEM_READ_STREAM_BLOCKS 32-bit words of folded data to
  * sink (device).  The rate this call reaches is the read ceiling of the box for kernels that stream HBM once, the

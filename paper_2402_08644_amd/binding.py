@@ -82,6 +82,12 @@ class PromptDesc(C.Structure):
                 ("Khp", C.POINTER(C.c_void_p)), ("Vhp", C.POINTER(C.c_void_p)), ("n_prompt", C.c_void_p)]
 
 
+class DeepStateDesc(C.Structure):
+    _fields_ = [("B", C.c_int32), ("T_max", C.c_int64),
+                ("KL", C.POINTER(C.c_void_p)), ("VL", C.POINTER(C.c_void_p)),
+                ("KS", C.POINTER(C.c_void_p)), ("VS", C.POINTER(C.c_void_p))]
+
+
 class RouterDesc(C.Structure):
     _fields_ = [("k", C.c_int32), ("d_hidden", C.c_int32), ("dtype", C.c_int32), ("tau", C.c_float),
                 ("W1", C.c_void_p), ("b1", C.c_void_p), ("w2", C.c_void_p), ("b2", C.c_void_p)]
@@ -105,6 +111,7 @@ EXPORTS = (
     "tandem_prefill_workspace", "tandem_prefill",
     "tandem_router_eval", "tandem_decode_step_adaptive",
     "tandem_score_workspace", "tandem_score",
+    "tandem_deep_score_workspace", "tandem_deep_begin", "tandem_deep_score",
     "tandem_decode_step_shared_workspace", "tandem_decode_step_shared",
 )
 
@@ -136,6 +143,13 @@ def lib():
     L.tandem_score.restype = C.c_int
     L.tandem_score.argtypes = [vp, C.POINTER(StateDesc), C.POINTER(vp), C.POINTER(vp), vp, vp, i32, i32, vp, vp, vp, vp,
                                sz, vp]
+    L.tandem_deep_score_workspace.restype = sz
+    L.tandem_deep_score_workspace.argtypes = [vp, C.POINTER(FFDesc), i32, i32]
+    L.tandem_deep_begin.restype = C.c_int
+    L.tandem_deep_begin.argtypes = [vp, C.POINTER(FFDesc), C.POINTER(DeepStateDesc), vp, sz, vp]
+    L.tandem_deep_score.restype = C.c_int
+    L.tandem_deep_score.argtypes = [vp, C.POINTER(FFDesc), C.POINTER(DeepStateDesc), vp, i64, vp, i32, i32, vp, vp, vp, vp,
+                                    vp, sz, vp]
     L.tandem_router_eval.restype = C.c_int
     L.tandem_router_eval.argtypes = [C.POINTER(RouterDesc), vp, vp, i32, i32, i32, vp, vp]
     L.tandem_decode_step_adaptive.restype = C.c_int
@@ -792,6 +806,58 @@ def tandem_score(model: TandemModel, state: TandemState, k_own, v_own, pos, toke
                             _ptr(out["greedy"]), _ptr(out.get("logits")), _ptr(out.get("y_small")), _ptr(ws), ws.numel(),
                             _stream(stream))
     _check(rc, "tandem_score")
+    return out
+
+
+class DeepState:
+    """Caller-owned caches of the Deep Tandem pass (Sec. 5): M_L's K/V rows and M_S's own K/V rows, by position."""
+
+    def __init__(self, model: TandemModel, B, T_max, device="cuda"):
+        import torch
+
+        self.B, self.T_max = B, T_max
+        L, S = model.L, model.S
+        mk = lambda D: [torch.zeros((B, D.Hkv, T_max, D.dh), dtype=model.dtype, device=device) for _ in range(D.n_layers)]
+        self.KL, self.VL, self.KS, self.VS = mk(L), mk(L), mk(S), mk(S)
+        self._arrays = [(C.c_void_p * len(ts))(*[t.data_ptr() for t in ts]) for ts in (self.KL, self.VL, self.KS, self.VS)]
+        self.desc = DeepStateDesc(B, T_max, *self._arrays)
+
+
+def tandem_deep_begin(model: TandemModel, ff_deep: dict, state: DeepState, ws=None, stream=None):
+    """M_L's row 0 of every sequence (before the first tandem_deep_score)."""
+    d = ff_desc(ff_deep)
+    if ws is None:
+        ws = _workspace(int(lib().tandem_deep_score_workspace(model.handle, C.byref(d), state.B, 1)), state.KL[0])
+    _check(lib().tandem_deep_begin(model.handle, C.byref(d), C.byref(state.desc), _ptr(ws), ws.numel(), _stream(stream)),
+           "tandem_deep_begin")
+
+
+def tandem_deep_score(model: TandemModel, ff_deep: dict, state: DeepState, tokens, pos, q_len, gamma, logits=False,
+                      y_small=False, sketch=False, ws=None, stream=None):
+    """One chunk of the teacher-forced Deep Tandem pass: tokens int32 [B, n_tokens] (all known tokens), pos int32 [B].
+    Returns {"greedy" [B,q_len], optionally "logits", "y_small", "sketch"}."""
+    import torch
+
+    B, n_tokens = tokens.shape
+    _need(tokens, (state.B, n_tokens), "tokens")
+    _need(pos, (state.B,), "pos")
+    if tokens.dtype != torch.int32 or pos.dtype != torch.int32:
+        raise TypeError("tokens and pos must be int32")
+    d = ff_desc(ff_deep)
+    dev = tokens.device
+    out = {"greedy": torch.empty((B, q_len), dtype=torch.int32, device=dev)}
+    if logits:
+        out["logits"] = torch.empty((B, q_len, model.S.vocab), dtype=model.dtype, device=dev)
+    if y_small:
+        out["y_small"] = torch.empty((B, q_len, model.S.d), dtype=model.dtype, device=dev)
+    if sketch:
+        out["sketch"] = torch.empty((B, q_len, model.L.d), dtype=model.dtype, device=dev)
+    if ws is None:
+        ws = _workspace(int(lib().tandem_deep_score_workspace(model.handle, C.byref(d), B, q_len)), tokens)
+    rc = lib().tandem_deep_score(model.handle, C.byref(d), C.byref(state.desc), _ptr(tokens), n_tokens, _ptr(pos), q_len,
+                                 int(gamma), _ptr(out["greedy"]), _ptr(out.get("logits")), _ptr(out.get("y_small")),
+                                 _ptr(out.get("sketch")), _ptr(ws), ws.numel(), _stream(stream))
+    _check(rc, "tandem_deep_score")
     return out
 
 

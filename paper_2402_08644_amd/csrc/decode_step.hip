@@ -80,10 +80,12 @@ int gemm_deferred(const void* X, int64_t ldx, const void* W, const void* Wp, int
 }
 
 // y_hat = FF_Tandem(x)   (Eq. (2), first line)
-int run_project(const tandem_ff_desc* ff, const void* x, void* y, int64_t M, void* ws, size_t ws_bytes, hipStream_t st) {
+// residual (optional, [M, d_S], may alias y): added to the result
+int run_project(const tandem_ff_desc* ff, const void* x, void* y, int64_t M, void* ws, size_t ws_bytes, hipStream_t st,
+                const void* residual = nullptr) {
   if (ff->d_hidden == 0)
-    return gemm(x, ff->d_L, ff->W1, ff->W1p, ff->b1, nullptr, 0, y, ff->d_S, (int)M, ff->d_S, ff->d_L, TANDEM_ACT_NONE, ff->dtype,
-                ws, ws_bytes, st);
+    return gemm(x, ff->d_L, ff->W1, ff->W1p, ff->b1, residual, ff->d_S, y, ff->d_S, (int)M, ff->d_S, ff->d_L, TANDEM_ACT_NONE,
+                ff->dtype, ws, ws_bytes, st);
   const size_t hidden = align256((size_t)M * ff->d_hidden * elsize(ff->dtype));
   void* hbuf = ws;
   void* gws = (char*)ws + hidden;
@@ -91,8 +93,8 @@ int run_project(const tandem_ff_desc* ff, const void* x, void* y, int64_t M, voi
   int rc = gemm(x, ff->d_L, ff->W1, ff->W1p, ff->b1, nullptr, 0, hbuf, ff->d_hidden, (int)M, ff->d_hidden, ff->d_L, ff->act,
                 ff->dtype, gws, gws_bytes, st);
   if (rc != TANDEM_OK) return rc;
-  return gemm(hbuf, ff->d_hidden, ff->W2, ff->W2p, ff->b2, nullptr, 0, y, ff->d_S, (int)M, ff->d_S, ff->d_hidden, TANDEM_ACT_NONE,
-              ff->dtype, gws, gws_bytes, st);
+  return gemm(hbuf, ff->d_hidden, ff->W2, ff->W2p, ff->b2, residual, ff->d_S, y, ff->d_S, (int)M, ff->d_S, ff->d_hidden,
+              TANDEM_ACT_NONE, ff->dtype, gws, gws_bytes, st);
 }
 
 int check_decoder(const tandem_decoder_desc& d) {
@@ -314,9 +316,12 @@ struct Ctx {
 
 // row0 / q_rows: the call covers rows row0 .. row0 + q_len - 1 of the q_rows rows that q and out hold per sequence
 // (block mode: those rows sit at positions nA[b] + row0 ..)
+// prefix_gamma > 0 (instead of causal): row r at position i = nA[b] + n_extra + row0 + r sees only the rows of the blocks
+// completed before its own, keys [0, floor(i / prefix_gamma) * prefix_gamma) (Deep Tandem, Eq. (3)).
 int attn_call(const Ctx& c, const tandem_decoder_desc& D, const void* q, const void* kA, const void* vA, const int32_t* nA,
               const void* kB, const void* vB, const int32_t* nB, int causal, int q_len, void* out, int row0 = 0,
-              int q_rows = 0, const void* kP = nullptr, const void* vP = nullptr, const int32_t* skip = nullptr) {
+              int q_rows = 0, const void* kP = nullptr, const void* vP = nullptr, const int32_t* skip = nullptr,
+              int prefix_gamma = 0, int n_extra = 0) {
   if (c.pr) {
     // several samples per prompt: kP / vP hold the prompts' rows of this layer, kA / vA each sample's later rows
     tandem_attn_desc d{c.st->B / c.pr->samples, D.Hq, D.Hkv, D.dh, c.pr->T_prompt, causal ? 0 : c.st->gamma_max,
@@ -333,7 +338,7 @@ int attn_call(const Ctx& c, const tandem_decoder_desc& D, const void* q, const v
   q = (const char*)q + row0_bytes;
   out = (char*)out + row0_bytes;
   a.q_rows = q_rows;
-  a.n_off = row0;
+  a.n_off = row0 + n_extra;
   a.skip = skip;
   a.q = q;
   a.kA = kA;
@@ -353,7 +358,11 @@ int attn_call(const Ctx& c, const tandem_decoder_desc& D, const void* q, const v
   a.scale = 1.0f / sqrtf((float)D.dh);
   a.dtype = c.dtype;
   a.out = out;
-  const bool mfma = causal && attn_block_supported(a);
+  const bool mfma = (causal || prefix_gamma > 0) && attn_block_supported(a);
+  if (prefix_gamma > 0) {
+    a.mixed = mfma ? 1 : 3;
+    a.gamma = prefix_gamma;
+  }
   a.S = mfma ? attn_block_splits(a.B, a.Hkv, q_len, a.Hq / a.Hkv, a.T_max, &a.wide)
              : attn_rows_splits(a.B, a.Hkv, q_len, a.Hq / a.Hkv, a.T_max, causal ? 0 : c.st->gamma_max, &a.wide);
   if (skip && !mfma && a.S * (a.wide ? 2 : 1) < 4) {
@@ -897,6 +906,150 @@ int tandem_score(const tandem_model* m, const tandem_state_desc* state, void* co
   }
   if (y_small) TRY(hip_ok(hipMemcpyAsync(y_small, x, (size_t)M * S.d * es, hipMemcpyDeviceToDevice, c.stream)));
   int32_t* tok = greedy ? greedy : tok_scratch;
+  TRY(c.plan.fused ? head_normed(c, S, M, tok, 1) : head(c, S, M, tok, 1));
+  if (logits)
+    TRY(hip_ok(hipMemcpyAsync(logits, c.at<>(c.plan.logits), (size_t)M * S.vocab * es, hipMemcpyDeviceToDevice, c.stream)));
+  return TANDEM_OK;
+}
+
+// ---------------------------------------------------------------- Deep Tandem (Sec. 5)
+namespace {
+
+struct DeepCtx {
+  Ctx c;
+  tandem_state_desc st;  // B and T_max for attn_call; the cache arrays are passed explicitly
+};
+
+int deep_setup(DeepCtx& dc, const tandem_model* m, const tandem_ff_desc* ff, const tandem_deep_state_desc* st, int q_len,
+               void* ws, size_t ws_bytes, void* hip_stream, size_t* ff_ws_off, size_t* ff_ws_bytes) {
+  if (!m || !ff || !st || !ws) return TANDEM_ERR_NULL;
+  if (!st->KL || !st->VL || !st->KS || !st->VS) return TANDEM_ERR_NULL;
+  const tandem_decoder_desc &L = m->d.L, &S = m->d.S;
+  int rc = check_ff(ff);
+  if (rc != TANDEM_OK) return rc;
+  if (ff->d_L != L.d || ff->d_S != S.d || ff->dtype != m->d.dtype) return TANDEM_ERR_SHAPE;
+  if (st->B < 1 || st->B > 65535 || st->T_max < 1) return TANDEM_ERR_SHAPE;
+  if (q_len < 1 || q_len > TANDEM_MAX_QLEN || q_len >= st->T_max) return TANDEM_ERR_SHAPE;
+  for (int j = 0; j < L.n_layers; ++j)
+    if (!st->KL[j] || !st->VL[j]) return TANDEM_ERR_NULL;
+  for (int j = 0; j < S.n_layers; ++j)
+    if (!st->KS[j] || !st->VS[j]) return TANDEM_ERR_NULL;
+  dc.st = tandem_state_desc{};
+  dc.st.B = st->B;
+  dc.st.T_max = st->T_max;
+  dc.st.gamma_max = 1;
+  Ctx& c = dc.c;
+  c.m = m;
+  c.st = &dc.st;
+  c.plan = make_plan(m, st->B, q_len, st->T_max, 1, true);
+  *ff_ws_off = c.plan.total;
+  *ff_ws_bytes = align256(project_ws(ff, (int64_t)st->B * q_len));
+  if (c.plan.total + *ff_ws_bytes > ws_bytes) return TANDEM_ERR_WORKSPACE;
+  c.ws = (char*)ws;
+  c.stream = (hipStream_t)hip_stream;
+  c.dtype = m->d.dtype;
+  c.eps = m->d.rms_eps;
+  return TANDEM_OK;
+}
+
+// M_L's rows r = (pos ? pos[b] : 0) + fixed + rr, rr < q_len, of Eq. (3): input = embedding of token r - gamma (zero
+// without one), every layer's K/V rows appended at row r, attention over the rows of the blocks completed before the
+// row's own.  Leaves x^(L_L) of the rows in the plan's x buffer.
+int deep_large_rows(const Ctx& c, const tandem_deep_state_desc* st, const int32_t* tokens, int64_t n_tokens,
+                    const int32_t* pos, int fixed, int q_len, int gamma) {
+  const tandem_decoder_desc& L = c.m->d.L;
+  const int M = st->B * q_len;
+  void *x = c.at<>(c.plan.x), *qkv = c.at<>(c.plan.qkv), *q = c.at<>(c.plan.q), *att = c.at<>(c.plan.att);
+  TRY(launch_embed_shifted(L.emb, tokens, n_tokens, pos, fixed, gamma, q_len, x, c.plan.fused ? L.layers[0].g_attn : nullptr,
+                           c.at<>(c.plan.xn), M, L.d, L.vocab, c.eps, c.dtype, c.stream));
+  for (int j = 0; j < L.n_layers; ++j) {
+    auto attn_only = [&]() -> int {
+      return attn_call(c, L, q, st->KL[j], st->VL[j], pos, nullptr, nullptr, nullptr, 0, q_len, att, 0, 0, nullptr, nullptr,
+                       nullptr, gamma, fixed);
+    };
+    if (c.plan.fused) {
+      auto finish_qkv = [&](const float* part, int splits) -> int {
+        return launch_finish_scatter(part, splits, q, st->KL[j], st->VL[j], pos, fixed, M, q_len, L.Hq, L.Hkv, L.dh,
+                                     st->T_max, L.Hq * L.dh, (L.Hq + 2 * L.Hkv) * L.dh, c.dtype, c.stream);
+      };
+      const void* g_next = j + 1 < L.n_layers ? L.layers[j + 1].g_attn : L.g_final;
+      TRY(decoder_layer_fused(c, L, L.layers[j], M, g_next, finish_qkv, attn_only));
+    } else {
+      auto attn = [&]() -> int {
+        TRY(launch_scatter_qkv(qkv, q, st->KL[j], st->VL[j], pos, fixed, M, q_len, L.Hq, L.Hkv, L.dh, st->T_max, 0,
+                               L.Hq * L.dh, (L.Hq + 2 * L.Hkv) * L.dh, c.dtype, c.stream));
+        return attn_only();
+      };
+      TRY(decoder_layer(c, L, L.layers[j], M, attn));
+    }
+  }
+  return TANDEM_OK;
+}
+
+}  // namespace
+
+size_t tandem_deep_score_workspace(const tandem_model* m, const tandem_ff_desc* ff_deep, int32_t B, int32_t q_len) {
+  if (!m || !ff_deep || check_ff(ff_deep) != TANDEM_OK || B < 1 || q_len < 1 || q_len > TANDEM_MAX_QLEN) return 0;
+  return make_plan(m, B, q_len, (int64_t)1 << 40, 1, true).total + align256(project_ws(ff_deep, (int64_t)B * q_len));
+}
+
+int tandem_deep_begin(const tandem_model* m, const tandem_ff_desc* ff_deep, const tandem_deep_state_desc* st, void* ws,
+                      size_t ws_bytes, void* hip_stream) {
+  DeepCtx dc;
+  size_t fo = 0, fb = 0;
+  TRY(deep_setup(dc, m, ff_deep, st, 1, ws, ws_bytes, hip_stream, &fo, &fb));
+  // row 0 of M_L: no input token, no visible key (any block length gives that; 1 is passed)
+  int32_t* zero = dc.c.at<int32_t>(dc.c.plan.ints);
+  TRY(launch_fill_i32(zero, 0, st->B, dc.c.stream));
+  return deep_large_rows(dc.c, st, nullptr, 0, zero, 0, 1, 1);
+}
+
+int tandem_deep_score(const tandem_model* m, const tandem_ff_desc* ff_deep, const tandem_deep_state_desc* st,
+                      const int32_t* tokens, int64_t n_tokens, const int32_t* pos, int32_t q_len, int32_t gamma,
+                      int32_t* greedy, void* logits, void* y_small, void* sketch, void* ws, size_t ws_bytes,
+                      void* hip_stream) {
+  if (!tokens || !pos) return TANDEM_ERR_NULL;
+  if (gamma < 1 || n_tokens < 1) return TANDEM_ERR_SHAPE;
+  DeepCtx dc;
+  size_t fo = 0, fb = 0;
+  TRY(deep_setup(dc, m, ff_deep, st, q_len, ws, ws_bytes, hip_stream, &fo, &fb));
+  const Ctx& c = dc.c;
+  const tandem_decoder_desc &L = m->d.L, &S = m->d.S;
+  const int B = st->B, M = B * q_len;
+  const size_t es = elsize(c.dtype);
+  // ---- Eq. (3): M_L's rows pos + 1 .. pos + q_len (row p + 1 is the sketch M_S's position p reads)
+  TRY(deep_large_rows(c, st, tokens, n_tokens, pos, 1, q_len, gamma));
+  void* keep = c.ws + c.plan.keep;  // x^(L_L) of the rows; the step's keep buffers are free here
+  TRY(hip_ok(hipMemcpyAsync(keep, c.at<>(c.plan.x), (size_t)M * L.d * es, hipMemcpyDeviceToDevice, c.stream)));
+  if (sketch) TRY(hip_ok(hipMemcpyAsync(sketch, keep, (size_t)M * L.d * es, hipMemcpyDeviceToDevice, c.stream)));
+  // ---- Eq. (4): y^(0) = Emb_S(token at p) + FF_DeepTandem(sketch), then M_S as a plain causal decoder on its own rows
+  void *x = c.at<>(c.plan.x), *qkv = c.at<>(c.plan.qkv), *q = c.at<>(c.plan.q), *att = c.at<>(c.plan.att);
+  TRY(launch_embed_shifted(S.emb, tokens, n_tokens, pos, 0, 0, q_len, x, nullptr, nullptr, M, S.d, S.vocab, c.eps, c.dtype,
+                           c.stream));
+  TRY(run_project(ff_deep, keep, x, M, c.ws + fo, fb, c.stream, x));
+  if (c.plan.fused) TRY(launch_rmsnorm(x, S.layers[0].g_attn, c.at<>(c.plan.xn), M, S.d, c.eps, c.dtype, c.stream));
+  for (int j = 0; j < S.n_layers; ++j) {
+    auto attn_only = [&]() -> int {
+      return attn_call(c, S, q, st->KS[j], st->VS[j], pos, nullptr, nullptr, nullptr, 1, q_len, att);
+    };
+    if (c.plan.fused) {
+      auto finish_qkv = [&](const float* part, int splits) -> int {
+        return launch_finish_scatter(part, splits, q, st->KS[j], st->VS[j], pos, 0, M, q_len, S.Hq, S.Hkv, S.dh, st->T_max,
+                                     S.Hq * S.dh, (S.Hq + 2 * S.Hkv) * S.dh, c.dtype, c.stream);
+      };
+      const void* g_next = j + 1 < S.n_layers ? S.layers[j + 1].g_attn : S.g_final;
+      TRY(decoder_layer_fused(c, S, S.layers[j], M, g_next, finish_qkv, attn_only));
+    } else {
+      auto attn = [&]() -> int {
+        TRY(launch_scatter_qkv(qkv, q, st->KS[j], st->VS[j], pos, 0, M, q_len, S.Hq, S.Hkv, S.dh, st->T_max, 0, S.Hq * S.dh,
+                               (S.Hq + 2 * S.Hkv) * S.dh, c.dtype, c.stream));
+        return attn_only();
+      };
+      TRY(decoder_layer(c, S, S.layers[j], M, attn));
+    }
+  }
+  if (y_small) TRY(hip_ok(hipMemcpyAsync(y_small, x, (size_t)M * S.d * es, hipMemcpyDeviceToDevice, c.stream)));
+  int32_t* tok = greedy ? greedy : c.at<int32_t>(c.plan.ints);
   TRY(c.plan.fused ? head_normed(c, S, M, tok, 1) : head(c, S, M, tok, 1));
   if (logits)
     TRY(hip_ok(hipMemcpyAsync(logits, c.at<>(c.plan.logits), (size_t)M * S.vocab * es, hipMemcpyDeviceToDevice, c.stream)));

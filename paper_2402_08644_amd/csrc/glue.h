@@ -21,3 +21,4 @@ int check_router(const tandem_router_desc* r, int d);
 int launch_router(const tandem_router_desc* r, const void* logits, const void* emb, int rows, int vocab, int d, int run,
                   int32_t* stop, float* p_out, int64_t p_stride, hipStream_t st);
 int launch_advance(int32_t* n, int B, int by, int64_t cap, hipStream_t st);  // n[b] = min(n[b] + by, cap)
+int launch_fill_i32(int32_t* p, int32_t v, int n, hipStream_t st);  // p[0:n) = v (a kernel: safe under graph capture)

@@ -24,13 +24,26 @@ __device__ __forceinline__ float4 load4(const bf16_t* p) {
 // = b * q + rr stands for block position r = rr + r0 of sequence b, whose token is pending[b] for r = 0 and
 // follow[b * gamma + r - 1] after that (the draft, or forced, tokens): no separate kernel has to lay the block's
 // tokens out first.
+// Shifted form (shift_pos or shift_mode): tokens is [B, n_tokens]; row = b * q + rr reads token index
+// (shift_pos ? shift_pos[b] : 0) + fixed + rr - shift of sequence b; a negative index means "no token" (-1 is
+// returned and the row is all zeros), an index past the end is clamped.
 struct TokenSrc {
   const int32_t* tokens;
   long long stride;
   const int32_t *pending, *follow;
   int gamma, q, r0;
+  const int32_t* shift_pos;
+  int shift_mode, fixed, shift;
+  long long n_tokens;
 };
 __device__ __forceinline__ int token_of(const TokenSrc& t, int row) {
+  if (t.shift_mode) {
+    const int b = row / t.q, rr = row % t.q;
+    long long idx = (long long)(t.shift_pos ? t.shift_pos[b] : 0) + t.fixed + rr - t.shift;
+    if (idx < 0) return -1;
+    idx = idx < t.n_tokens ? idx : t.n_tokens - 1;
+    return t.tokens[(long long)b * t.n_tokens + idx];
+  }
   if (!t.pending) return t.tokens[(long long)row * t.stride];
   const int b = row / t.q, r = row % t.q + t.r0;
   return r == 0 ? t.pending[b] : t.follow[(long long)b * t.gamma + r - 1];
@@ -52,6 +65,13 @@ __global__ __launch_bounds__(256) void embed_norm_kernel(const T* __restrict__ e
     if (stop && threadIdx.x == 0) stop[row] = 0;
   }
   int t = token_of(src, row);
+  if (src.shift_mode && t < 0) {  // a row without a token: zeros (its norm is zero as well)
+    for (int i = threadIdx.x; i < d; i += 256) {
+      x[(long long)row * d + i] = from_f32<T>(0.f);
+      if (g) xn[(long long)row * d + i] = from_f32<T>(0.f);
+    }
+    return;
+  }
   t = t < 0 ? 0 : (t >= vocab ? vocab - 1 : t);
   const T* er = emb + (long long)t * d;
   T* xr = x + (long long)row * d;
@@ -355,6 +375,11 @@ __global__ void accept_kernel(const int32_t* draft, const int32_t* verify, const
   n_accepted[b] = a;
 }
 
+__global__ void fill_i32_kernel(int32_t* p, int32_t v, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
 __global__ void advance_kernel(int32_t* n, int B, int by, long long cap) {
   const int b = blockIdx.x * blockDim.x + threadIdx.x;
   if (b >= B) return;
@@ -363,6 +388,11 @@ __global__ void advance_kernel(int32_t* n, int B, int by, long long cap) {
 }
 
 }  // namespace
+
+int launch_fill_i32(int32_t* p, int32_t v, int n, hipStream_t st) {
+  hipLaunchKernelGGL(fill_i32_kernel, dim3((n + 255) / 256), dim3(256), 0, st, p, v, n);
+  return hip_ok(hipGetLastError());
+}
 
 int launch_advance(int32_t* n, int B, int by, int64_t cap, hipStream_t st) {
   hipLaunchKernelGGL(advance_kernel, dim3((B + 63) / 64), dim3(64), 0, st, n, B, by, (long long)cap);
@@ -374,13 +404,26 @@ int launch_embed_norm(const void* emb, const int32_t* tokens, int64_t tok_stride
                       int vocab, float eps, int32_t* ncur, int32_t* stop, int init_B, int init_gamma, int dtype,
                       hipStream_t st) {
   if (init_gamma > 256) return TANDEM_ERR_UNSUPPORTED;
-  TokenSrc src{tokens, (long long)tok_stride, pending, follow, gamma, q > 0 ? q : 1, r0};
+  TokenSrc src{tokens, (long long)tok_stride, pending, follow, gamma, q > 0 ? q : 1, r0, nullptr, 0, 0, 0, 0};
   if (dtype == TANDEM_BF16)
     hipLaunchKernelGGL(embed_norm_kernel<bf16_t>, dim3(rows), dim3(256), 0, st, (const bf16_t*)emb, src, (bf16_t*)x,
                        (const bf16_t*)g, (bf16_t*)xn, d, vocab, eps, ncur, stop, init_B, init_gamma);
   else
     hipLaunchKernelGGL(embed_norm_kernel<float>, dim3(rows), dim3(256), 0, st, (const float*)emb, src, (float*)x,
                        (const float*)g, (float*)xn, d, vocab, eps, ncur, stop, init_B, init_gamma);
+  return hip_ok(hipGetLastError());
+}
+
+int launch_embed_shifted(const void* emb, const int32_t* tokens, int64_t n_tokens, const int32_t* pos, int fixed,
+                         int shift, int q, void* x, const void* g, void* xn, int rows, int d, int vocab, float eps,
+                         int dtype, hipStream_t st) {
+  TokenSrc src{tokens, 0, nullptr, nullptr, 0, q > 0 ? q : 1, 0, pos, 1, fixed, shift, (long long)n_tokens};
+  if (dtype == TANDEM_BF16)
+    hipLaunchKernelGGL(embed_norm_kernel<bf16_t>, dim3(rows), dim3(256), 0, st, (const bf16_t*)emb, src, (bf16_t*)x,
+                       (const bf16_t*)g, (bf16_t*)xn, d, vocab, eps, nullptr, nullptr, 0, 0);
+  else
+    hipLaunchKernelGGL(embed_norm_kernel<float>, dim3(rows), dim3(256), 0, st, (const float*)emb, src, (float*)x,
+                       (const float*)g, (float*)xn, d, vocab, eps, nullptr, nullptr, 0, 0);
   return hip_ok(hipGetLastError());
 }
 

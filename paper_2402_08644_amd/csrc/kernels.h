@@ -106,3 +106,9 @@ int launch_embed_norm(const void* emb, const int32_t* tokens, int64_t tok_stride
                       const int32_t* follow, int gamma, int q, int r0, void* x, const void* g, void* xn, int rows, int d,
                       int vocab, float eps, int32_t* ncur, int32_t* stop, int init_B, int init_gamma, int dtype,
                       hipStream_t st);
+// The same gather with shifted token indices: tokens is [B, n_tokens]; row b * q + rr reads token
+// (pos ? pos[b] : 0) + fixed + rr - shift of sequence b.  A negative index gives an all-zero row (x and xn), an
+// index past the end is clamped.  (Deep Tandem, Eq. (3): row i of M_L reads token i - gamma.)
+int launch_embed_shifted(const void* emb, const int32_t* tokens, int64_t n_tokens, const int32_t* pos, int fixed,
+                         int shift, int q, void* x, const void* g, void* xn, int rows, int d, int vocab, float eps,
+                         int dtype, hipStream_t st);
