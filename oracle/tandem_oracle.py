@@ -35,7 +35,8 @@ forms (zero FF_Tandem), block-by-block == causal forward, gamma=1 == causal
 decode, gamma -> inf == small model alone, incremental == teacher-forced,
 SPEED stream == greedy M_L stream, integer schedules of Fig. 2 / Fig. 4; Deep Tandem (Sec. 5) against a
 mask-based torch formulation and its limits (zero FF_DeepTandem == plain M_S; block length beyond the sequence ==
-a constant sketch).
+a constant sketch); its greedy decoding is the definition (forward re-evaluated per token), checked for prefix
+consistency of the forward it relies on.
 Parity unpinned by the paper (it prints no tensor values): the block internals
 listed above (norm, activation, eps, head) and the MLP form of FF_Tandem; they
 are pinned only by the configuration text this build was given.
@@ -688,6 +689,22 @@ def deep_tandem_forward(T, tokens, gamma):
         y = nxt
     yo = np.stack([y[i] for i in srows])
     return {"sketch": sketch, "y": yo, "logits": logits_of(MS, yo, eps)}
+
+
+def deep_tandem_generate(T, tokens, gamma, n_new):
+    """Greedy decoding with the Deep Tandem model (Sec. 5): the next token is the highest-logit token of the model's
+    prediction for the next row given all tokens so far (ties to the lowest id), n_new times.  Written as the
+    definition: the whole forward of Eq. (3)-(4) is evaluated again for every new token; nothing is cached.
+    (M_L's rows of a block read only tokens at least gamma positions back, which is what lets an implementation
+    compute the sketch of a whole block before M_S samples it - that structure is not used here.)
+    Returns {"tokens": prompt followed by the n_new new tokens, "logits": the n_new logit rows they came from}."""
+    toks = [int(t) for t in np.asarray(tokens)]
+    rows = []
+    for _ in range(n_new):
+        lg = deep_tandem_forward(T, np.asarray(toks), gamma)["logits"][-1]  # row S + 1: the prediction of token S + 1
+        rows.append(lg)
+        toks.append(argmax_lowest(lg))
+    return {"tokens": np.asarray(toks, np.int64), "logits": np.stack(rows)}
 
 
 # ----------------------------------------------------------------------------

@@ -482,6 +482,24 @@ def test_decode_step_workspace_is_enough_at_any_cache_capacity(tb, B, T_max, fre
     assert int(gst.n.min()) == 40
 
 
+def test_decode_step_workspace_sweep_over_batch_and_capacity(tb):
+    """The same contract over a grid of batch sizes and cache capacities (zero caches: only the host-side plan
+    check and a clean run matter here): no combination may be refused for lack of workspace."""
+    torch, binding = tb
+    W = small_bf16_pair(97, n_layers_L=1, n_layers_S=1)
+    model = binding.TandemModel(W)
+    gamma = 4
+    for B in (1, 3, 4, 8, 12):
+        ws = torch.empty(binding.tandem_decode_step_workspace(model, B, gamma), dtype=torch.uint8, device="cuda")
+        for T_max in (300, 520, 777, 1030, 1290, 1540, 1800, 2050, 2310, 2817, 3000, 3585, 4100, 5000, 6145):
+            gst = binding.TandemState(model, B, T_max, gamma)
+            gst.n.fill_(T_max - 2 * (gamma + 1))
+            for free in (False, True):
+                binding.tandem_decode_step(model, gst, gamma, ws=ws, free_token=free)  # raises on TANDEM_ERR_WORKSPACE
+            del gst
+    torch.cuda.synchronize()
+
+
 def test_decode_step_error_codes(tb):
     torch, binding = tb
     import ctypes as C

@@ -132,3 +132,62 @@ def test_sketch_of_a_block_depends_only_on_completed_blocks():
         np.testing.assert_array_equal(a["y"][: t - 1], b["y"][: t - 1])  # rows i = 2 .. t
         if t <= S:
             assert np.abs(a["y"][t - 1] - b["y"][t - 1]).max() > 1e-9  # row i = t + 1 reads token t
+
+
+def test_forward_is_prefix_consistent():
+    """Row i of the forward reads tokens below i only: appending tokens leaves the earlier rows' sketches,
+    and representations bit for bit the same (the logits to rounding) - what makes greedy decoding by re-evaluation well defined."""
+    T = deep_pair(seed=8)
+    toks = inputs.token_ids(8, (14,), 40)
+    full = orc.deep_tandem_forward(T, toks, 3)
+    for S in (1, 2, 5, 9):
+        part = orc.deep_tandem_forward(T, toks[:S], 3)
+        np.testing.assert_array_equal(part["sketch"], full["sketch"][: S + 1])
+        np.testing.assert_array_equal(part["y"], full["y"][:S])
+        # the head is one matrix product over all rows: its rounding depends on the number of rows
+        np.testing.assert_allclose(part["logits"], full["logits"][:S], rtol=1e-12, atol=1e-13)
+
+
+@pytest.mark.parametrize("gamma,S0", [(1, 3), (3, 1), (3, 6), (4, 5)])
+def test_greedy_generation_vs_block_schedule(gamma, S0):
+    """Greedy decoding by definition (forward re-evaluated for every token) against the schedule an implementation
+    would run: whenever gamma new tokens are due, M_L's next gamma rows are computed at once from the tokens known
+    so far (their sketches do not depend on the tokens about to be sampled), then M_S samples token by token on top
+    of them.  Here that schedule is emulated with the mask-based torch forward on a sequence padded with wrong
+    tokens where the future ones would be: the sketches of the gamma rows and each next-token distribution must not
+    see the padding."""
+    T = deep_pair(seed=20 + gamma)
+    prompt = inputs.token_ids(9, (S0,), 40)
+    n_new = 2 * gamma + 1
+    want = orc.deep_tandem_generate(T, prompt, gamma, n_new)
+    assert want["tokens"].shape == (S0 + n_new,)
+    np.testing.assert_array_equal(want["tokens"][:S0], prompt)
+    toks = [int(t) for t in prompt]
+    got_logits = []
+    while len(toks) < S0 + n_new:
+        S = len(toks)
+        # M_L rows S + 1 .. S + gamma (1-indexed) from the S known tokens, padded with garbage future tokens
+        padded = np.asarray(toks + [39 - (t % 7) for t in range(gamma)])
+        sk, _, _ = torch_deep_forward(T, padded, gamma)
+        sketch_rows = sk[S : S + gamma]  # rows S + 1 .. S + gamma
+        for t in range(gamma):
+            if len(toks) == S0 + n_new:
+                break
+            cur = np.asarray(toks + [0] * (gamma - t))  # the tokens sampled so far in this block are real
+            sk2, _, lg = torch_deep_forward(T, cur, gamma)
+            np.testing.assert_allclose(sk2[S + t], sketch_rows[t], rtol=1e-10, atol=1e-12)  # computed before sampling
+            row = lg[len(toks) - 1]  # M_S row that reads the last real token
+            got_logits.append(row)
+            toks.append(int(np.argmax(row)))
+    np.testing.assert_array_equal(np.asarray(toks), want["tokens"])
+    np.testing.assert_allclose(np.stack(got_logits), want["logits"], rtol=1e-8, atol=1e-10)
+
+
+def test_generated_tokens_are_the_argmax_of_the_teacher_forced_rows():
+    """Scoring the generated sequence reproduces it: token S0 + t is the highest logit of row S0 + t - 1."""
+    T = deep_pair(seed=31)
+    prompt = inputs.token_ids(10, (4,), 40)
+    out = orc.deep_tandem_generate(T, prompt, 2, 7)
+    lg = orc.deep_tandem_forward(T, out["tokens"][:-1], 2)["logits"]
+    np.testing.assert_array_equal(np.argmax(lg[3:], axis=1), out["tokens"][4:])
+    np.testing.assert_allclose(lg[3:], out["logits"], rtol=1e-12, atol=1e-14)
