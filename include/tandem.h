@@ -432,6 +432,26 @@ int tandem_deep_score(const tandem_model *m, const tandem_ff_desc *ff_deep, cons
                       int32_t *greedy, void *logits, void *y_small, void *sketch, void *ws, size_t ws_bytes,
                       void *hip_stream);
 
+/* One Deep Tandem decoding step (Sec. 5): greedy generation of the next gamma tokens of every sequence.
+ * M_L's rows of a block read only tokens at least gamma positions back (Eq. (3)), so the sketches of the next gamma
+ * rows are computed in ONE block pass of M_L before M_S samples any of them; M_S then runs gamma times, each run on
+ * the token the run before produced plus its row's sketch (Eq. (4)).  With len[b] tokens of sequence b known:
+ *   M_L rows len[b] .. len[b] + gamma - 1 (inputs: tokens len[b] - gamma .. len[b] - 1), then FF_DeepTandem of them;
+ *   run t = 0 .. gamma - 1: M_S position len[b] - 1 + t reads token len[b] - 1 + t and the sketch of M_L row
+ *   len[b] + t, attends its own rows [0, len[b] - 1 + t], and its highest logit (ties: lowest id) is token len[b] + t.
+ * Needs M_L rows [0, len[b]) and M_S positions [0, len[b] - 1) in the caches: tandem_deep_begin, then
+ * tandem_deep_score over the known tokens (pos = 0 .., the last chunk ending at position len[b] - 2) or earlier steps.
+ *   tokens  device int32 [B, n_tokens], read and written: the new tokens are appended at len[b] + t
+ *   len     device int32 [B], 1 <= len[b], len[b] + gamma <= min(n_tokens, T_max); advanced by gamma (never past that
+ *           minimum; a sequence that would pass it gets no defined tokens, nothing is written out of bounds)
+ *   out_tokens optional device int32 [B, gamma]; logits optional [B, gamma, vocab]; y_small optional [B, gamma, S.d];
+ *   sketch optional [B, gamma, L.d];  1 <= gamma <= TANDEM_MAX_QLEN
+ *   ws: at least tandem_deep_score_workspace(m, ff_deep, B, gamma) bytes.
+ * Scoring the sequence afterwards with tandem_deep_score reproduces the tokens (the same rows are computed). */
+int tandem_deep_step(const tandem_model *m, const tandem_ff_desc *ff_deep, const tandem_deep_state_desc *st,
+                     int32_t *tokens, int64_t n_tokens, int32_t *len, int32_t gamma, int32_t *out_tokens, void *logits,
+                     void *y_small, void *sketch, void *ws, size_t ws_bytes, void *hip_stream);
+
 /* Measurement helper, no part of the method: reads src[0 : bytes) (device, 16-byte aligned; a multiple of 16 bytes is
  * read) once with plain coalesced 16-byte loads and writes TANDEM_READ_STREAM_BLOCKS 32-bit words of folded data to
  * sink (device).  The rate this call reaches is the read ceiling of the box for kernels that stream HBM once, the

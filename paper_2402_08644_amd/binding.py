@@ -111,7 +111,7 @@ EXPORTS = (
     "tandem_prefill_workspace", "tandem_prefill",
     "tandem_router_eval", "tandem_decode_step_adaptive",
     "tandem_score_workspace", "tandem_score",
-    "tandem_deep_score_workspace", "tandem_deep_begin", "tandem_deep_score",
+    "tandem_deep_score_workspace", "tandem_deep_begin", "tandem_deep_score", "tandem_deep_step",
     "tandem_decode_step_shared_workspace", "tandem_decode_step_shared",
 )
 
@@ -147,6 +147,9 @@ def lib():
     L.tandem_deep_score_workspace.argtypes = [vp, C.POINTER(FFDesc), i32, i32]
     L.tandem_deep_begin.restype = C.c_int
     L.tandem_deep_begin.argtypes = [vp, C.POINTER(FFDesc), C.POINTER(DeepStateDesc), vp, sz, vp]
+    L.tandem_deep_step.restype = C.c_int
+    L.tandem_deep_step.argtypes = [vp, C.POINTER(FFDesc), C.POINTER(DeepStateDesc), vp, i64, vp, i32, vp, vp, vp, vp, vp, sz,
+                                   vp]
     L.tandem_deep_score.restype = C.c_int
     L.tandem_deep_score.argtypes = [vp, C.POINTER(FFDesc), C.POINTER(DeepStateDesc), vp, i64, vp, i32, i32, vp, vp, vp, vp,
                                     vp, sz, vp]
@@ -858,6 +861,35 @@ def tandem_deep_score(model: TandemModel, ff_deep: dict, state: DeepState, token
                                  int(gamma), _ptr(out["greedy"]), _ptr(out.get("logits")), _ptr(out.get("y_small")),
                                  _ptr(out.get("sketch")), _ptr(ws), ws.numel(), _stream(stream))
     _check(rc, "tandem_deep_score")
+    return out
+
+
+def tandem_deep_step(model: TandemModel, ff_deep: dict, state: DeepState, tokens, length, gamma, logits=False,
+                     y_small=False, sketch=False, ws=None, stream=None):
+    """One Deep Tandem decoding step: tokens int32 [B, n_tokens] (updated in place), length int32 [B] (advanced by gamma).
+    Returns {"tokens" [B, gamma], optionally "logits", "y_small", "sketch"}."""
+    import torch
+
+    B, n_tokens = tokens.shape
+    _need(tokens, (state.B, n_tokens), "tokens")
+    _need(length, (state.B,), "length")
+    if tokens.dtype != torch.int32 or length.dtype != torch.int32:
+        raise TypeError("tokens and length must be int32")
+    d = ff_desc(ff_deep)
+    dev = tokens.device
+    out = {"tokens": torch.empty((B, gamma), dtype=torch.int32, device=dev)}
+    if logits:
+        out["logits"] = torch.empty((B, gamma, model.S.vocab), dtype=model.dtype, device=dev)
+    if y_small:
+        out["y_small"] = torch.empty((B, gamma, model.S.d), dtype=model.dtype, device=dev)
+    if sketch:
+        out["sketch"] = torch.empty((B, gamma, model.L.d), dtype=model.dtype, device=dev)
+    if ws is None:
+        ws = _workspace(int(lib().tandem_deep_score_workspace(model.handle, C.byref(d), B, gamma)), tokens)
+    rc = lib().tandem_deep_step(model.handle, C.byref(d), C.byref(state.desc), _ptr(tokens), n_tokens, _ptr(length),
+                                int(gamma), _ptr(out["tokens"]), _ptr(out.get("logits")), _ptr(out.get("y_small")),
+                                _ptr(out.get("sketch")), _ptr(ws), ws.numel(), _stream(stream))
+    _check(rc, "tandem_deep_step")
     return out
 
 

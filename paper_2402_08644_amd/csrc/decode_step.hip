@@ -1056,4 +1056,61 @@ int tandem_deep_score(const tandem_model* m, const tandem_ff_desc* ff_deep, cons
   return TANDEM_OK;
 }
 
+int tandem_deep_step(const tandem_model* m, const tandem_ff_desc* ff_deep, const tandem_deep_state_desc* st,
+                     int32_t* tokens, int64_t n_tokens, int32_t* len, int32_t gamma, int32_t* out_tokens, void* logits,
+                     void* y_small, void* sketch, void* ws, size_t ws_bytes, void* hip_stream) {
+  if (!tokens || !len) return TANDEM_ERR_NULL;
+  if (gamma < 1 || n_tokens < 1) return TANDEM_ERR_SHAPE;
+  DeepCtx dc;
+  size_t fo = 0, fb = 0;
+  TRY(deep_setup(dc, m, ff_deep, st, gamma, ws, ws_bytes, hip_stream, &fo, &fb));
+  const Ctx& c = dc.c;
+  const tandem_decoder_desc &L = m->d.L, &S = m->d.S;
+  const int B = st->B, M = B * gamma;
+  const size_t es = elsize(c.dtype);
+  // ---- Eq. (3): the sketch of the next gamma rows in one block pass of M_L.  Row len + rr reads token len + rr - gamma,
+  // which is known, and the rows of the blocks completed before its own.
+  TRY(deep_large_rows(c, st, tokens, n_tokens, len, 0, gamma, gamma));
+  if (sketch) TRY(hip_ok(hipMemcpyAsync(sketch, c.at<>(c.plan.x), (size_t)M * L.d * es, hipMemcpyDeviceToDevice, c.stream)));
+  void* ffs = c.at<>(c.plan.yhat);  // FF_DeepTandem of the gamma sketches, [B, gamma, d_S]
+  TRY(run_project(ff_deep, c.at<>(c.plan.x), ffs, M, c.ws + fo, fb, c.stream));
+  // ---- Eq. (4): gamma runs of M_S, each on the token the run before produced
+  void *x = c.at<>(c.plan.x), *qkv = c.at<>(c.plan.qkv), *q = c.at<>(c.plan.q), *att = c.at<>(c.plan.att);
+  int32_t* out = out_tokens ? out_tokens : c.at<int32_t>(c.plan.ints);  // [B, gamma]
+  for (int t = 0; t < gamma; ++t) {
+    TRY(launch_deep_input(S.emb, tokens, n_tokens, len, t, out, gamma, ffs, x, c.plan.fused ? S.layers[0].g_attn : nullptr,
+                          c.at<>(c.plan.xn), B, S.d, S.vocab, c.eps, c.dtype, c.stream));
+    for (int j = 0; j < S.n_layers; ++j) {
+      // position len - 1 + t attends its own rows [0, len - 1 + t]: len + t rows of the position-indexed cache
+      auto attn_only = [&]() -> int {
+        return attn_call(c, S, q, st->KS[j], st->VS[j], len, nullptr, nullptr, nullptr, 0, 1, att, 0, 0, nullptr, nullptr,
+                         nullptr, 0, t);
+      };
+      if (c.plan.fused) {
+        auto finish_qkv = [&](const float* part, int splits) -> int {
+          return launch_finish_scatter(part, splits, q, st->KS[j], st->VS[j], len, t - 1, B, 1, S.Hq, S.Hkv, S.dh, st->T_max,
+                                       S.Hq * S.dh, (S.Hq + 2 * S.Hkv) * S.dh, c.dtype, c.stream);
+        };
+        const void* g_next = j + 1 < S.n_layers ? S.layers[j + 1].g_attn : S.g_final;
+        TRY(decoder_layer_fused(c, S, S.layers[j], B, g_next, finish_qkv, attn_only));
+      } else {
+        auto attn = [&]() -> int {
+          TRY(launch_scatter_qkv(qkv, q, st->KS[j], st->VS[j], len, t - 1, B, 1, S.Hq, S.Hkv, S.dh, st->T_max, 0, S.Hq * S.dh,
+                                 (S.Hq + 2 * S.Hkv) * S.dh, c.dtype, c.stream));
+          return attn_only();
+        };
+        TRY(decoder_layer(c, S, S.layers[j], B, attn));
+      }
+    }
+    if (y_small)
+      TRY(copy2d((char*)y_small + (size_t)t * S.d * es, (size_t)gamma * S.d * es, x, S.d * es, S.d * es, B, c.stream));
+    TRY(c.plan.fused ? head_normed(c, S, B, out + t, gamma) : head(c, S, B, out + t, gamma));
+    if (logits)
+      TRY(copy2d((char*)logits + (size_t)t * S.vocab * es, (size_t)gamma * S.vocab * es, c.at<>(c.plan.logits), S.vocab * es,
+                 S.vocab * es, B, c.stream));
+  }
+  const int64_t cap = n_tokens < st->T_max ? n_tokens : st->T_max;
+  return launch_deep_advance(tokens, n_tokens, len, out, B, gamma, cap, c.stream);
+}
+
 }  // extern "C"

@@ -22,3 +22,10 @@ int launch_router(const tandem_router_desc* r, const void* logits, const void* e
                   int32_t* stop, float* p_out, int64_t p_stride, hipStream_t st);
 int launch_advance(int32_t* n, int B, int by, int64_t cap, hipStream_t st);  // n[b] = min(n[b] + by, cap)
 int launch_fill_i32(int32_t* p, int32_t v, int n, hipStream_t st);  // p[0:n) = v (a kernel: safe under graph capture)
+// Deep Tandem decoding (Sec. 5): input of M_S's run t (token lookup, appending the run before's token, embedding +
+// add[b, t] and the first RMSNorm), and the end of a step (last token appended, len[b] = min(len[b] + gamma, cap))
+int launch_deep_input(const void* emb, int32_t* tokens, int64_t n_tokens, const int32_t* len, int t, const int32_t* prev,
+                      int gamma, const void* add, void* x, const void* g, void* xn, int B, int d, int vocab, float eps,
+                      int dtype, hipStream_t st);
+int launch_deep_advance(int32_t* tokens, int64_t n_tokens, int32_t* len, const int32_t* prev, int B, int gamma, int64_t cap,
+                        hipStream_t st);

@@ -375,6 +375,61 @@ __global__ void accept_kernel(const int32_t* draft, const int32_t* verify, const
   n_accepted[b] = a;
 }
 
+// Deep Tandem decoding (Sec. 5, Eq. (4)): the input of M_S's run t of a step, one workgroup per sequence b.
+// The run's token is tokens[b, len[b] - 1] for t = 0 (the last known token), else prev[b * gamma + t - 1], the greedy
+// token of the run before, which this kernel also appends to the sequence at tokens[b, len[b] + t - 1].
+// x[b] = emb[token] + add[(b * gamma + t)] (FF_DeepTandem of the row's sketch), and, when g is given,
+// xn[b] = RMSNorm(x[b]; g) from the unrounded sum.
+template <typename T>
+__global__ __launch_bounds__(256) void deep_input_kernel(const T* __restrict__ emb, int32_t* tokens, long long n_tokens,
+                                                         const int32_t* __restrict__ len, int t,
+                                                         const int32_t* __restrict__ prev, int gamma,
+                                                         const T* __restrict__ add, T* __restrict__ x,
+                                                         const T* __restrict__ g, T* __restrict__ xn, int d, int vocab,
+                                                         float eps) {
+  __shared__ float red[4];
+  const int b = blockIdx.x;
+  const long long at = (long long)len[b] + t - 1;  // position of the run's input token
+  int tok;
+  if (t == 0) {
+    const long long i = at < 0 ? 0 : (at < n_tokens ? at : n_tokens - 1);
+    tok = tokens[(long long)b * n_tokens + i];
+  } else {
+    tok = prev[(long long)b * gamma + t - 1];
+    if (threadIdx.x == 0 && at >= 0 && at < n_tokens) tokens[(long long)b * n_tokens + at] = tok;
+  }
+  tok = tok < 0 ? 0 : (tok >= vocab ? vocab - 1 : tok);
+  const T* er = emb + (long long)tok * d;
+  const T* ar = add + ((long long)b * gamma + t) * d;
+  T* xr = x + (long long)b * d;
+  float ss = 0.f;
+  for (int i = threadIdx.x; i < d; i += 256) {
+    const float v = to_f32<T>(er[i]) + to_f32<T>(ar[i]);
+    xr[i] = from_f32<T>(v);
+    ss += v * v;
+  }
+  if (!g) return;
+  for (int off = 32; off >= 1; off >>= 1) ss += __shfl_xor(ss, off);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  const float inv = 1.0f / sqrtf((red[0] + red[1] + red[2] + red[3]) / (float)d + eps);
+  T* yr = xn + (long long)b * d;
+  for (int i = threadIdx.x; i < d; i += 256)
+    yr[i] = from_f32<T>((to_f32<T>(er[i]) + to_f32<T>(ar[i])) * inv * to_f32<T>(g[i]));
+}
+
+// End of a Deep Tandem decoding step: the last run's token joins the sequence and len[b] advances by gamma, never
+// past cap.
+__global__ void deep_advance_kernel(int32_t* tokens, long long n_tokens, int32_t* len, const int32_t* prev, int B,
+                                    int gamma, long long cap) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B) return;
+  const long long at = (long long)len[b] + gamma - 1;
+  if (at >= 0 && at < n_tokens) tokens[(long long)b * n_tokens + at] = prev[(long long)b * gamma + gamma - 1];
+  const long long nn = (long long)len[b] + gamma;
+  len[b] = (int32_t)(nn < 0 ? 0 : (nn > cap ? cap : nn));
+}
+
 __global__ void fill_i32_kernel(int32_t* p, int32_t v, int n) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = v;
@@ -424,6 +479,27 @@ int launch_embed_shifted(const void* emb, const int32_t* tokens, int64_t n_token
   else
     hipLaunchKernelGGL(embed_norm_kernel<float>, dim3(rows), dim3(256), 0, st, (const float*)emb, src, (float*)x,
                        (const float*)g, (float*)xn, d, vocab, eps, nullptr, nullptr, 0, 0);
+  return hip_ok(hipGetLastError());
+}
+
+int launch_deep_input(const void* emb, int32_t* tokens, int64_t n_tokens, const int32_t* len, int t, const int32_t* prev,
+                      int gamma, const void* add, void* x, const void* g, void* xn, int B, int d, int vocab, float eps,
+                      int dtype, hipStream_t st) {
+  if (dtype == TANDEM_BF16)
+    hipLaunchKernelGGL(deep_input_kernel<bf16_t>, dim3(B), dim3(256), 0, st, (const bf16_t*)emb, tokens,
+                       (long long)n_tokens, len, t, prev, gamma, (const bf16_t*)add, (bf16_t*)x, (const bf16_t*)g,
+                       (bf16_t*)xn, d, vocab, eps);
+  else
+    hipLaunchKernelGGL(deep_input_kernel<float>, dim3(B), dim3(256), 0, st, (const float*)emb, tokens,
+                       (long long)n_tokens, len, t, prev, gamma, (const float*)add, (float*)x, (const float*)g, (float*)xn,
+                       d, vocab, eps);
+  return hip_ok(hipGetLastError());
+}
+
+int launch_deep_advance(int32_t* tokens, int64_t n_tokens, int32_t* len, const int32_t* prev, int B, int gamma, int64_t cap,
+                        hipStream_t st) {
+  hipLaunchKernelGGL(deep_advance_kernel, dim3((B + 63) / 64), dim3(64), 0, st, tokens, (long long)n_tokens, len, prev, B,
+                     gamma, (long long)cap);
   return hip_ok(hipGetLastError());
 }
 

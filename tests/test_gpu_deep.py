@@ -1,5 +1,5 @@
 """GPU parity: the Deep Tandem pass (Sec. 5, Eq. (3) and Eq. (4)) through the C ABI, chunk by chunk, against the
-oracle's whole-sequence forward."""
+oracle's whole-sequence forward, and its decoding steps against the oracle's greedy decoding."""
 import numpy as np
 import pytest
 
@@ -82,6 +82,125 @@ def test_deep_score_bf16_equals_oracle_forward(tb, gamma, chunks, d_hidden):
         assert_rows_close(y[b], ref["y"], tol=TOL, what="deep y bf16")
         assert_rows_close(lg[b], ref["logits"], tol=TOL, what="deep logits bf16")
         assert tokens_ok(gr[b], ref["logits"])
+
+
+def run_generate(tb, W, prompts, gamma, steps, T_max, score_chunk=None):
+    """Prompts of different lengths in one batch: deep_begin, the teacher-forced pass over positions 0 .. max(len) - 2
+    (rows past a shorter prompt's end are computed from filler tokens and overwritten by the steps), then `steps`
+    decoding steps.  Returns the token array, the lengths and the per-step outputs."""
+    torch, binding = tb
+    model = binding.TandemModel(W)
+    ffd = {k: (v.to_torch() if hasattr(v, "to_torch") else v) for k, v in W["ff_deep"].items()}
+    B = len(prompts)
+    vocab = int(W["S"]["emb"].shape[0])
+    st = binding.DeepState(model, B, T_max)
+    toks = np.asarray(inputs.token_ids(99, (B, T_max), vocab))  # filler beyond the prompts
+    for b, p in enumerate(prompts):
+        toks[b, : len(p)] = p
+    dev_toks = torch.tensor(toks, dtype=torch.int32).cuda()
+    length = torch.tensor([len(p) for p in prompts], dtype=torch.int32).cuda()
+    binding.tandem_deep_begin(model, ffd, st)
+    P = max(len(p) for p in prompts) - 1  # M_S positions 0 .. P - 1, M_L rows 1 .. P
+    p0 = 0
+    while p0 < P:
+        q = min(score_chunk or 32, P - p0)
+        pos = torch.full((B,), p0, dtype=torch.int32, device="cuda")
+        binding.tandem_deep_score(model, ffd, st, dev_toks, pos, q, gamma)
+        p0 += q
+    outs = []
+    for _ in range(steps):
+        o = binding.tandem_deep_step(model, ffd, st, dev_toks, length, gamma, logits=True, y_small=True, sketch=True)
+        outs.append({k: (v.cpu().numpy() if k == "tokens" else inputs.torch_to_f64(v)) for k, v in o.items()})
+    torch.cuda.synchronize()
+    return dev_toks.cpu().numpy(), length.cpu().numpy(), outs
+
+
+@pytest.mark.parametrize("gamma,lens,steps", [(3, (5, 8, 1), 3), (1, (4, 2), 5), (4, (4, 8), 2), (5, (2, 3), 2)])
+def test_deep_step_fp32_generates_the_oracle_tokens(tb, gamma, lens, steps):
+    """fp32, ragged prompt lengths (block-aligned and not, a one-token prompt): the steps' tokens are the oracle's
+    greedy decoding, token for token, and each step's logits, representations and sketches are the oracle's rows."""
+    W = inputs.tandem_weights(
+        3, vocab=200, large=dict(d=128, n_layers=3, Hq=4, Hkv=2, dh=64, d_ff=256),
+        small=dict(d=64, n_layers=2, Hq=2, Hkv=1, dh=64, d_ff=128), ell=(1, 3), d_hidden=96, dtype="f32", w_std=0.3,
+        gain_std=0.3, bias_std=0.1, deep=True)
+    T = inputs.as_f64(W)
+    prompts = [inputs.token_ids(40 + b, (n,), 200) for b, n in enumerate(lens)]
+    toks, length, outs = run_generate(tb, W, prompts, gamma, steps, 48, score_chunk=3)
+    n_new = steps * gamma
+    for b, p in enumerate(prompts):
+        S0 = len(p)
+        assert length[b] == S0 + n_new
+        ref = orc.deep_tandem_generate(T, p, gamma, n_new)
+        np.testing.assert_array_equal(toks[b, : S0 + n_new], ref["tokens"])
+        step_tokens = np.concatenate([o["tokens"][b] for o in outs])
+        np.testing.assert_array_equal(step_tokens, ref["tokens"][S0:])
+        fwd = orc.deep_tandem_forward(T, ref["tokens"][:-1], gamma)  # rows up to the one that predicts the last token
+        lg = np.concatenate([o["logits"][b] for o in outs])
+        y = np.concatenate([o["y_small"][b] for o in outs])
+        sk = np.concatenate([o["sketch"][b] for o in outs])
+        assert_rows_close(lg, ref["logits"], tol=2e-3, what="deep step logits fp32")
+        assert_rows_close(lg, fwd["logits"][S0 - 1 :], tol=2e-3, what="deep step logits fp32 (teacher-forced rows)")
+        assert_rows_close(y, fwd["y"][S0 - 1 :], tol=2e-3, what="deep step y fp32")
+        # the steps' sketch rows are M_L's rows S0 + 1 .. S0 + n_new (1-indexed): entries S0 .. of the oracle's list
+        assert_rows_close(sk, fwd["sketch"][S0 : S0 + n_new], tol=2e-3, what="deep step sketch fp32")
+
+
+@pytest.mark.parametrize("gamma,lens,d_hidden", [(4, (9, 12, 5), 256), (2, (7, 7), 0)])
+def test_deep_step_bf16_follows_the_oracle(tb, gamma, lens, d_hidden):
+    """bf16, heads of 128: three steps.  The oracle scores the sequence the GPU generated: every GPU token must be a
+    highest-logit token of the oracle's row within the arithmetic's resolution, and the rows must agree."""
+    W = inputs.tandem_weights(
+        5, vocab=512, large=dict(d=512, n_layers=2, Hq=8, Hkv=2, dh=128, d_ff=1024),
+        small=dict(d=256, n_layers=2, Hq=2, Hkv=2, dh=128, d_ff=512), ell=(1, 2), d_hidden=d_hidden, dtype="bf16",
+        w_std=0.05, gain_std=0.3, bias_std=0.05, deep=True)
+    T = inputs.as_f64(W)
+    prompts = [inputs.token_ids(60 + b, (n,), 512) for b, n in enumerate(lens)]
+    steps = 3
+    toks, length, outs = run_generate(tb, W, prompts, gamma, steps, 64)
+    from test_gpu_decode_step import tokens_ok
+
+    n_new = steps * gamma
+    for b, p in enumerate(prompts):
+        S0 = len(p)
+        assert length[b] == S0 + n_new
+        np.testing.assert_array_equal(toks[b, :S0], p)
+        seq = toks[b, : S0 + n_new]
+        step_tokens = np.concatenate([o["tokens"][b] for o in outs])
+        np.testing.assert_array_equal(step_tokens, seq[S0:])
+        fwd = orc.deep_tandem_forward(T, seq[:-1], gamma)
+        lg = np.concatenate([o["logits"][b] for o in outs])
+        y = np.concatenate([o["y_small"][b] for o in outs])
+        sk = np.concatenate([o["sketch"][b] for o in outs])
+        assert_rows_close(sk, fwd["sketch"][S0 : S0 + n_new], tol=TOL, what="deep step sketch bf16")
+        assert_rows_close(y, fwd["y"][S0 - 1 :], tol=TOL, what="deep step y bf16")
+        assert_rows_close(lg, fwd["logits"][S0 - 1 :], tol=TOL, what="deep step logits bf16")
+        assert tokens_ok(seq[S0:], fwd["logits"][S0 - 1 :])
+
+
+def test_deep_step_error_codes_and_capacity(tb):
+    torch, binding = tb
+    W = inputs.tandem_weights(
+        3, vocab=200, large=dict(d=128, n_layers=1, Hq=2, Hkv=2, dh=64, d_ff=256),
+        small=dict(d=64, n_layers=1, Hq=1, Hkv=1, dh=64, d_ff=128), ell=(1,), d_hidden=0, dtype="f32", deep=True)
+    model = binding.TandemModel(W)
+    ffd = {k: v.to_torch() for k, v in W["ff_deep"].items()}
+    st = binding.DeepState(model, 2, 16)
+    toks = torch.zeros((2, 16), dtype=torch.int32, device="cuda")
+    length = torch.tensor([3, 14], dtype=torch.int32, device="cuda")
+    for gamma in (0, 33):
+        with pytest.raises(binding.TandemError) as ei:
+            binding.tandem_deep_step(model, ffd, st, toks, length, gamma)
+        assert ei.value.status == binding.ERR_SHAPE
+    with pytest.raises(binding.TandemError) as ei:
+        binding.tandem_deep_step(model, ffd, st, toks, length, 4, ws=torch.empty(256, dtype=torch.uint8, device="cuda"))
+    assert ei.value.status == binding.ERR_WORKSPACE
+    # a sequence that would pass the capacity: nothing is written out of bounds and its length stops at the capacity
+    binding.tandem_deep_begin(model, ffd, st)
+    guard = toks.clone()
+    binding.tandem_deep_step(model, ffd, st, toks, length, 4)
+    torch.cuda.synchronize()
+    assert length.tolist() == [7, 16]
+    assert (toks[0, :3] == guard[0, :3]).all() and (toks[1, :14] == guard[1, :14]).all()
 
 
 def test_deep_score_error_codes(tb):
