@@ -544,6 +544,59 @@ def run_score_workload(torch, binding, inputs, args):
     }
 
 
+def run_deep_step_workload(torch, binding, inputs, args):
+    """One tandem_deep_step call (Sec. 5): 32 sequences at context 8192, gamma = 4, C3 model pair plus an FF_DeepTandem of
+    the configuration's FF_Tandem shape: M_L's block pass over the next 4 rows, then 4 runs of M_S."""
+    cfg = dict(C3)
+    B, g, ctx = cfg["B"], cfg["gamma"], cfg["ctx"]
+    W = device_tandem_weights(inputs, cfg, 3)
+    model = binding.TandemModel(W, pack_weights=not args.plain_weights)
+    del W
+    L, S = cfg["large"], cfg["small"]
+    ffd = {"W1": inputs.device_normal((cfg["d_hidden"], L["d"]), 901, 0.02),
+           "b1": torch.zeros(cfg["d_hidden"], dtype=torch.bfloat16, device="cuda"),
+           "W2": inputs.device_normal((S["d"], cfg["d_hidden"]), 902, 0.02),
+           "b2": torch.zeros(S["d"], dtype=torch.bfloat16, device="cuda"), "act": "gelu"}
+    if not args.plain_weights:
+        ffd["W1p"], ffd["W2p"] = binding.tandem_pack_weight(ffd["W1"]), binding.tandem_pack_weight(ffd["W2"])
+    st = binding.DeepState(model, B, ctx)
+    k = [17]
+    for caches in (st.KL, st.VL, st.KS, st.VS):
+        for j in range(len(caches)):
+            k[0] += 1
+            caches[j].copy_(inputs.device_normal(tuple(caches[j].shape), k[0], 1.0))
+    n0 = ctx - g
+    toks = torch.randint(0, cfg["vocab"], (B, ctx), dtype=torch.int32, device="cuda", generator=torch.Generator("cuda").manual_seed(9))
+    length = torch.empty((B,), dtype=torch.int32, device="cuda")
+    d = binding.ff_desc(ffd)
+    ws = torch.empty(int(binding.lib().tandem_deep_score_workspace(model.handle, d, B, g)), dtype=torch.uint8, device="cuda")
+
+    def call(_i):
+        length.fill_(n0)  # keep the context at ctx: the step itself advances the lengths
+        binding.tandem_deep_step(model, ffd, st, toks, length, g, ws=ws)
+
+    torch.cuda.synchronize()
+    ms = _time_calls(torch, call, 1, args.steps, args.warmup, use_graph=not args.no_graph)
+    per = lambda c: (c["Hq"] + 2 * c["Hkv"]) * c["dh"] * c["d"] + c["d"] * c["Hq"] * c["dh"] + 2 * c["d"] * c["d_ff"]
+    kv = lambda c, rows: c["n_layers"] * B * c["Hkv"] * rows * c["dh"] * 2 * 2
+    seen_L = (n0 // g) * g  # rows of the blocks completed before the new rows' block
+    total = (2 * L["n_layers"] * per(L) + kv(L, seen_L) + 2 * (cfg["d_hidden"] * L["d"] + S["d"] * cfg["d_hidden"])
+             + sum(2 * (S["n_layers"] * per(S) + cfg["vocab"] * S["d"]) + kv(S, n0 + t) for t in range(g)))
+    gbs = total / (ms * 1e-3) / 1e9
+    return {
+        "metric": "Deep Tandem decoding steps/sec at gamma=4 (tandem_deep_step)",
+        "value": 1e3 / ms, "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "c3_deep_step: tandem_deep_step bf16 B=32, context 8192, gamma=4, C3 model pair with an "
+                               "FF_DeepTandem MLP 4096-8192-1024 (M_L block pass with block-prefix attention, 4 runs of M_S "
+                               "with causal attention over its own rows)",
+                   "step_algorithmic_GB": total / 1e9},
+        "roofline": {"bound": "hbm", "kernel": "whole step (weights of every model run + every visible cache row once)",
+                     "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS, "traffic": None},
+        "cpu_baseline": None,
+    }
+
+
 def cpu_step_estimate(torch, inputs, cfg, state, model):
     """Oracle pieces of one step timed on sampled slices (one sequence / one layer each), extrapolated by
     the layer, run and batch counts.  The full fp64 step is ~2 TFLOP and is not run."""
@@ -863,7 +916,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="c3_step", choices=sorted(WORKLOADS) + sorted(PROJECT_WORKLOADS) + ["c3_step", "c3_prefill", "c3_score", "c3_step_shared"])
+    ap.add_argument("--workload", default="c3_step", choices=sorted(WORKLOADS) + sorted(PROJECT_WORKLOADS) + ["c3_step", "c3_prefill", "c3_score", "c3_step_shared", "c3_deep_step"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--plain-weights", action="store_true",
@@ -909,6 +962,9 @@ def main():
         args.steps = min(args.steps, 10)
     if args.workload == "c3_step_shared":
         runner = run_shared_step_workload
+        args.steps = min(args.steps, 20)
+    if args.workload == "c3_deep_step":
+        runner = run_deep_step_workload
         args.steps = min(args.steps, 20)
     if args.workload == "c3_score":
         runner = run_score_workload
