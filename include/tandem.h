@@ -354,8 +354,10 @@ int tandem_router_eval(const tandem_router_desc *r, const void *logits, const vo
  * batch still runs gamma_max draft runs and verifies q = gamma_max (+ 1) rows per sequence - a stopped sequence
  * keeps its place, its later rows are ignored, and the cache rows they write lie beyond the new n[b] and are
  * overwritten by the following steps - but its draft attention is skipped in the later runs (no cache traffic, zero
- * rows), and acceptance, emitted tokens, n[b] and pending[b] are those of a step with gamma = g[b] (the free token,
- * if asked for, is M_L's token after d_g[b]).
+ * rows), and once EVERY sequence has stopped the kernels of the remaining draft runs return at once (bf16 models: a
+ * device counter of sequences still drafting gates them; the launch sequence stays the same, so the step can still be
+ * captured in a HIP graph).  Acceptance, emitted tokens, n[b] and pending[b] are those of a step with gamma = g[b]
+ * (the free token, if asked for, is M_L's token after d_g[b]).
  *   n_drafted  optional device int32 [B]: g[b]
  *   router_p   optional device fp32 [B, gamma_max]: the router's p after every draft run; entries past g[b], like the
  *              aux outputs of those runs, are unspecified
@@ -372,7 +374,9 @@ int tandem_decode_step_adaptive(const tandem_model *m, const tandem_state_desc *
  * n[b] += q_len.  With TANDEM_PREFILL_EMIT, pending[b] becomes M_L's greedy token after the last row (the first
  * generated token); otherwise pending is left alone (the caller keeps the last prompt token pending).
  *   tokens   device int32 [B, q_len];  1 <= q_len <= TANDEM_MAX_PREFILL: longer prompts take several calls (the
- *            dense layers run on all B * q_len rows at once, the attention on sub-blocks of TANDEM_MAX_QLEN rows)
+ *            dense layers run on all B * q_len rows at once; the attention of a layer is one launch for bf16 models
+ *            with heads of 128, which takes the rows in passes of 128 per KV head, and runs on sub-blocks of
+ *            TANDEM_MAX_QLEN rows otherwise)
  *   x_large  optional device [B, q_len, L.d]: x^(L_L) of the rows
  *   requires n[b] + q_len <= T_max;  ws: at least tandem_prefill_workspace(m, B, q_len) bytes. */
 #define TANDEM_PREFILL_EMIT 1

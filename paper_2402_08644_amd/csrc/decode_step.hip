@@ -38,8 +38,10 @@ size_t project_ws(const tandem_ff_desc* ff, int64_t M) {
 }
 
 int gemm(const void* X, int64_t ldx, const void* W, const void* Wp, const void* bias, const void* residual, int64_t ldr, void* Y,
-         int64_t ldy, int M, int N, int K, int act, int dtype, void* ws, size_t ws_bytes, hipStream_t st) {
+         int64_t ldy, int M, int N, int K, int act, int dtype, void* ws, size_t ws_bytes, hipStream_t st,
+         const int32_t* gate = nullptr) {
   GemmArgs g;
+  g.gate = gate;
   g.X = X;
   g.ldx = ldx;
   g.W = W;
@@ -62,8 +64,9 @@ int gemm(const void* X, int64_t ldx, const void* W, const void* Wp, const void* 
 
 // X . W^T left as fp32 partial sums in ws (see GemmArgs::defer)
 int gemm_deferred(const void* X, int64_t ldx, const void* W, const void* Wp, int M, int N, int K, int dtype, void* ws, size_t ws_bytes,
-                  hipStream_t st) {
+                  hipStream_t st, const int32_t* gate = nullptr) {
   GemmArgs g{};
+  g.gate = gate;
   g.X = X;
   g.ldx = ldx;
   g.W = W;
@@ -206,7 +209,7 @@ StepPlan make_plan(const tandem_model* m, int B, int gamma, int64_t T_max, int g
   p.keep_stride = align256(M * L.d * es);
   p.keep = take(p.keep_stride * S.n_layers);
   // ints: ncur[gamma][B], block_tokens[B*gamma], draft[B*gamma], verify[B*gamma], stop[B]
-  p.ints = take(sizeof(int32_t) * (4 * M + B));  // + stop[B] of the adaptive block length
+  p.ints = take(sizeof(int32_t) * (4 * M + B + TANDEM_MAX_QLEN));  // + stop[B], active[gamma] of the adaptive block length
   // Attention scratch: the larger of the draft and the block call, for ANY cache capacity.  The number of context
   // splits a launch uses depends on the capacity (at most one split per 256 keys; an even count becomes half as many
   // wide workgroups, an odd one does not), and not monotonically - so the table of partials is sized for the
@@ -304,6 +307,8 @@ struct Ctx {
   int dtype;
   float eps;
   const tandem_prompt_desc* pr = nullptr;  // several samples per prompt: the prompts' caches
+  const int32_t* gate = nullptr;  // device flag of the current draft run (adaptive block length): 0 = every sequence
+                                  // has stopped drafting, the run's kernels return at once
   template <typename T = void> T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
   const void* pk(const void* W) const { return m->pk(W); }
 };
@@ -412,16 +417,17 @@ int decoder_layer_fused(const Ctx& c, const tandem_decoder_desc& D, const tandem
   float* gws = c.at<float>(c.plan.gemm_ws);
   const size_t gwb = c.plan.gemm_ws_bytes;
   const int nqkv = (D.Hq + 2 * D.Hkv) * D.dh, nq = D.Hq * D.dh;
-  TRY(gemm_deferred(xn, D.d, w.Wqkv, c.pk(w.Wqkv), rows, nqkv, D.d, c.dtype, gws, gwb, c.stream));
+  TRY(gemm_deferred(xn, D.d, w.Wqkv, c.pk(w.Wqkv), rows, nqkv, D.d, c.dtype, gws, gwb, c.stream, c.gate));
   TRY(finish_qkv(gws, gemm_splits(rows, nqkv, D.d, c.pk(w.Wqkv) != nullptr)));
   TRY(attn());
-  TRY(gemm_deferred(att, nq, w.Wo, c.pk(w.Wo), rows, D.d, nq, c.dtype, gws, gwb, c.stream));
+  TRY(gemm_deferred(att, nq, w.Wo, c.pk(w.Wo), rows, D.d, nq, c.dtype, gws, gwb, c.stream, c.gate));
   TRY(launch_finish_norm(gws, gemm_splits(rows, D.d, nq, c.pk(w.Wo) != nullptr), nullptr, x, x, w.g_mlp, xn, rows, D.d, c.eps, c.dtype,
-                         c.stream));
-  TRY(gemm(xn, D.d, w.W1, c.pk(w.W1), w.b1, nullptr, 0, h, D.d_ff, rows, D.d_ff, D.d, TANDEM_ACT_GELU, c.dtype, gws, gwb, c.stream));
-  TRY(gemm_deferred(h, D.d_ff, w.W2, c.pk(w.W2), rows, D.d, D.d_ff, c.dtype, gws, gwb, c.stream));
+                         c.stream, nullptr, c.gate));
+  TRY(gemm(xn, D.d, w.W1, c.pk(w.W1), w.b1, nullptr, 0, h, D.d_ff, rows, D.d_ff, D.d, TANDEM_ACT_GELU, c.dtype, gws, gwb, c.stream,
+           c.gate));
+  TRY(gemm_deferred(h, D.d_ff, w.W2, c.pk(w.W2), rows, D.d, D.d_ff, c.dtype, gws, gwb, c.stream, c.gate));
   TRY(launch_finish_norm(gws, gemm_splits(rows, D.d, D.d_ff, c.pk(w.W2) != nullptr), w.b2, x, x, g_next, xn, rows, D.d, c.eps, c.dtype,
-                         c.stream, x_keep));
+                         c.stream, x_keep, c.gate));
   return TANDEM_OK;
 }
 
@@ -429,8 +435,8 @@ int decoder_layer_fused(const Ctx& c, const tandem_decoder_desc& D, const tandem
 int head_normed(const Ctx& c, const tandem_decoder_desc& D, int rows, int32_t* tok_out, int64_t tok_stride) {
   void *xn = c.at<>(c.plan.xn), *lg = c.at<>(c.plan.logits);
   TRY(gemm(xn, D.d, D.W_out, c.pk(D.W_out), nullptr, nullptr, 0, lg, D.vocab, rows, D.vocab, D.d, TANDEM_ACT_NONE, c.dtype,
-           c.at<>(c.plan.gemm_ws), c.plan.gemm_ws_bytes, c.stream));
-  return launch_argmax(lg, rows, D.vocab, tok_out, tok_stride, c.dtype, c.stream);
+           c.at<>(c.plan.gemm_ws), c.plan.gemm_ws_bytes, c.stream, c.gate));
+  return launch_argmax(lg, rows, D.vocab, tok_out, tok_stride, c.dtype, c.stream, c.gate);
 }
 
 int head(const Ctx& c, const tandem_decoder_desc& D, int rows, int32_t* tok_out, int64_t tok_stride) {
@@ -714,6 +720,9 @@ int decode_step_impl(const tandem_model* m, const tandem_state_desc* state, cons
   int32_t* draft = aux && aux->draft ? aux->draft : ncur + 2 * (size_t)M;    // [B, gamma]
   int32_t* verify = aux && aux->verify ? aux->verify : ncur + 3 * (size_t)M;  // [B, nq]
   int32_t* stop = router ? ncur + 4 * (size_t)M : nullptr;                    // [B], see accept_kernel
+  // [gamma]: sequences still drafting after run r; run r + 1 is gated on it (bf16 path: when every sequence has
+  // stopped, the kernels of the remaining runs return at once)
+  int32_t* active = router && c.plan.fused ? stop + B : nullptr;
   void *x = c.at<>(c.plan.x), *qkv = c.at<>(c.plan.qkv), *q = c.at<>(c.plan.q), *att = c.at<>(c.plan.att);
 
 
@@ -721,9 +730,10 @@ int decode_step_impl(const tandem_model* m, const tandem_state_desc* state, cons
   for (int r = 0; r < gamma; ++r) {
     // input of run r: the pending token, then the draft (or forced) token of the run before; the first run's kernel
     // also sets up ncur (own-block rows visible to each run) and clears the router's stop marks
+    c.gate = active && r > 0 ? active + r - 1 : nullptr;
     TRY(launch_embed_norm(S.emb, nullptr, 1, state->pending, forced ? forced : draft, gamma, 1, r, x,
                           c.plan.fused ? S.layers[0].g_attn : nullptr, c.at<>(c.plan.xn), B, S.d, S.vocab, c.eps, ncur, stop,
-                          r == 0 ? B : 0, gamma, c.dtype, c.stream));
+                          r == 0 ? B : 0, gamma, c.dtype, c.stream, r == 0 ? active : nullptr, c.gate));
     for (int j = 0; j < S.n_layers; ++j) {
       auto attn_only = [&]() -> int {
         return attn_call(c, S, q, state->Khat[j], state->Vhat[j], state->n, state->Kcur[j], state->Vcur[j],
@@ -733,7 +743,8 @@ int decode_step_impl(const tandem_model* m, const tandem_state_desc* state, cons
       if (c.plan.fused) {
         auto finish_qkv = [&](const float* part, int splits) -> int {
           return launch_finish_scatter(part, splits, q, state->Kcur[j], state->Vcur[j], nullptr, r, B, 1, S.Hq, S.Hkv,
-                                       S.dh, state->gamma_max, S.Hq * S.dh, (S.Hq + 2 * S.Hkv) * S.dh, c.dtype, c.stream);
+                                       S.dh, state->gamma_max, S.Hq * S.dh, (S.Hq + 2 * S.Hkv) * S.dh, c.dtype, c.stream,
+                                       c.gate);
         };
         const void* g_next = j + 1 < S.n_layers ? S.layers[j + 1].g_attn : S.g_final;
         TRY(decoder_layer_fused(c, S, S.layers[j], B, g_next, finish_qkv, attn_only));
@@ -757,8 +768,9 @@ int decode_step_impl(const tandem_model* m, const tandem_state_desc* state, cons
     // its shorter block
     if (router)
       TRY(launch_router(router, c.at<>(c.plan.logits), S.emb, B, S.vocab, S.d, r, stop, router_p ? router_p + r : nullptr,
-                        gamma, c.stream));
+                        gamma, c.stream, active, c.gate));
   }
+  c.gate = nullptr;
 
   // ---- 2. verify: M_L in block mode on the first nq of [pending, d_1 .. d_gamma]; 3. new K_hat / V_hat rows
   TRY(large_block_pass(c, nullptr, forced ? forced : draft, gamma, nq, aux, verify));

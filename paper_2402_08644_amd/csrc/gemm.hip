@@ -38,6 +38,7 @@ struct GemmParams {
   long long ldx, ldr, ldy;
   int M, N, K, act, splitK, m_base, defer;
   int xcd_map;  // stream kernel: 1 = workgroup ids are mapped to (tile, split) so that a split stays on one XCD
+  const int32_t* gate;  // optional device flag: *gate == 0 means nobody needs this product, the kernels return at once
 };
 
 __device__ __forceinline__ float apply_act(float v, int act) {
@@ -132,6 +133,7 @@ constexpr int XP = 72;  // LDS row pitch in bf16 elements (64 + 8 padding)
 
 template <int MT, int NW>
 __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(GemmParams p) {
+  if (p.gate && *p.gate == 0) return;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int c32 = lane & 31, h = lane >> 5;
@@ -292,6 +294,7 @@ constexpr int XPT = KC + 8;  // LDS row pitch in bf16 elements
 
 template <int MT>
 __global__ __launch_bounds__(512) void gemm_tile_kernel(GemmParams p) {
+  if (p.gate && *p.gate == 0) return;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int ng = w & 3, kg = w >> 2;
@@ -466,6 +469,7 @@ constexpr int XPS = SK + 8;  // LDS row pitch in bf16 elements
 
 template <int MT>
 __global__ __launch_bounds__(512) void gemm_stream_kernel(GemmParams p) {
+  if (p.gate && *p.gate == 0) return;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int lane = threadIdx.x & 63;
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -714,6 +718,7 @@ typedef __attribute__((address_space(3))) void* lds_void_ptr;
 typedef const __attribute__((address_space(1))) void* global_void_ptr;
 
 __global__ __launch_bounds__(256, 1) void gemm_big_kernel(GemmParams p, int tiles_m, int tiles_n) {
+  if (p.gate && *p.gate == 0) return;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   bf16_t* As = reinterpret_cast<bf16_t*>(smem);  // [2][256][BK], pieces permuted inside a row
   bf16_t* Bs = As + 2 * 256 * BK;                // [2][256][BK]
@@ -888,6 +893,7 @@ __global__ __launch_bounds__(256, 1) void gemm_big_kernel(GemmParams p, int tile
 // sums the split partials in split order, then the epilogue
 template <typename T>
 __global__ void gemm_splitk_epilogue_kernel(GemmParams p) {
+  if (p.gate && *p.gate == 0) return;
   const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= (long long)p.M * p.N) return;
   const int m = (int)(idx / p.N), n = (int)(idx % p.N);
@@ -1065,6 +1071,7 @@ int launch_gemm(const GemmArgs& g, hipStream_t st) {
   p.m_base = 0;
   p.xcd_map = 0;
   p.defer = g.defer;
+  p.gate = g.gate;
   if (skinny_ok(g.M, g.N, g.K, g.dtype, g.ldx) && (reinterpret_cast<uintptr_t>(g.X) % 16 == 0) &&
       (reinterpret_cast<uintptr_t>(g.W) % 16 == 0) && (reinterpret_cast<uintptr_t>(g.Y) % 8 == 0) && g.ldy % 4 == 0) {
     const bool big = big_ok(g.M, g.N, g.K);

@@ -57,12 +57,14 @@ template <typename T>
 __global__ __launch_bounds__(256) void embed_norm_kernel(const T* __restrict__ emb, TokenSrc src, T* __restrict__ x,
                                                          const T* __restrict__ g, T* __restrict__ xn, int d, int vocab,
                                                          float eps, int32_t* ncur, int32_t* stop, int init_B,
-                                                         int init_gamma) {
+                                                         int init_gamma, int32_t* active, const int32_t* gate) {
   __shared__ float red[4];
   const int row = blockIdx.x;
+  if (gate && *gate == 0) return;  // the caller's flag says nobody needs this launch
   if (init_B > 0) {
     if ((int)threadIdx.x < init_gamma) ncur[(long long)threadIdx.x * init_B + row] = threadIdx.x + 1;
     if (stop && threadIdx.x == 0) stop[row] = 0;
+    if (active && row == 0 && (int)threadIdx.x < init_gamma) active[threadIdx.x] = 0;
   }
   int t = token_of(src, row);
   if (src.shift_mode && t < 0) {  // a row without a token: zeros (its norm is zero as well)
@@ -169,9 +171,10 @@ __global__ void scatter_qkv_kernel(const T* __restrict__ qkv, T* __restrict__ q,
 // is only 64 KB: the kernel's time is the latency of its loads).
 template <typename T>
 __global__ __launch_bounds__(1024) void argmax_kernel(const T* __restrict__ logits, int vocab, int32_t* __restrict__ out,
-                                                      long long out_stride) {
+                                                      long long out_stride, const int32_t* gate) {
   __shared__ float sv[16];
   __shared__ int si[16];
+  if (gate && *gate == 0) return;  // the caller's flag says nobody needs this launch
   const long long row = blockIdx.x;
   const T* lr = logits + row * vocab;
   float best = -INFINITY;
@@ -237,8 +240,9 @@ template <typename T>
 __global__ __launch_bounds__(1024) void finish_norm_kernel(const float* __restrict__ part, int splits, long long MN,
                                                            const T* __restrict__ bias, const T* residual, T* x_out,
                                                            T* __restrict__ x_out2, const T* __restrict__ g,
-                                                           T* __restrict__ xn_out, int d, float eps) {
+                                                           T* __restrict__ xn_out, int d, float eps, const int32_t* gate) {
   __shared__ float red[16];
+  if (gate && *gate == 0) return;  // the caller's flag says nobody needs this launch
   const long long row = blockIdx.x;
   const float* pr = part + row * d;
   const int stride = blockDim.x * 4;
@@ -304,7 +308,8 @@ __global__ __launch_bounds__(1024) void finish_scatter_kernel(const float* __res
                                                              T* __restrict__ q, T* __restrict__ kc, T* __restrict__ vc,
                                                              const int32_t* __restrict__ base, int fixed, int q_len,
                                                              int Hq, int Hkv, int dh, long long cap, int q_cols,
-                                                             int row_cols) {
+                                                             int row_cols, const int32_t* gate) {
+  if (gate && *gate == 0) return;  // the caller's flag says nobody needs this launch
   const int row = blockIdx.x;
   const int b = row / q_len, r = row % q_len;
   const float* pr = part + (long long)row * row_cols;
@@ -457,15 +462,15 @@ int launch_advance(int32_t* n, int B, int by, int64_t cap, hipStream_t st) {
 int launch_embed_norm(const void* emb, const int32_t* tokens, int64_t tok_stride, const int32_t* pending,
                       const int32_t* follow, int gamma, int q, int r0, void* x, const void* g, void* xn, int rows, int d,
                       int vocab, float eps, int32_t* ncur, int32_t* stop, int init_B, int init_gamma, int dtype,
-                      hipStream_t st) {
+                      hipStream_t st, int32_t* active, const int32_t* gate) {
   if (init_gamma > 256) return TANDEM_ERR_UNSUPPORTED;
   TokenSrc src{tokens, (long long)tok_stride, pending, follow, gamma, q > 0 ? q : 1, r0, nullptr, 0, 0, 0, 0};
   if (dtype == TANDEM_BF16)
     hipLaunchKernelGGL(embed_norm_kernel<bf16_t>, dim3(rows), dim3(256), 0, st, (const bf16_t*)emb, src, (bf16_t*)x,
-                       (const bf16_t*)g, (bf16_t*)xn, d, vocab, eps, ncur, stop, init_B, init_gamma);
+                       (const bf16_t*)g, (bf16_t*)xn, d, vocab, eps, ncur, stop, init_B, init_gamma, active, gate);
   else
     hipLaunchKernelGGL(embed_norm_kernel<float>, dim3(rows), dim3(256), 0, st, (const float*)emb, src, (float*)x,
-                       (const float*)g, (float*)xn, d, vocab, eps, ncur, stop, init_B, init_gamma);
+                       (const float*)g, (float*)xn, d, vocab, eps, ncur, stop, init_B, init_gamma, active, gate);
   return hip_ok(hipGetLastError());
 }
 
@@ -475,10 +480,10 @@ int launch_embed_shifted(const void* emb, const int32_t* tokens, int64_t n_token
   TokenSrc src{tokens, 0, nullptr, nullptr, 0, q > 0 ? q : 1, 0, pos, 1, fixed, shift, (long long)n_tokens};
   if (dtype == TANDEM_BF16)
     hipLaunchKernelGGL(embed_norm_kernel<bf16_t>, dim3(rows), dim3(256), 0, st, (const bf16_t*)emb, src, (bf16_t*)x,
-                       (const bf16_t*)g, (bf16_t*)xn, d, vocab, eps, nullptr, nullptr, 0, 0);
+                       (const bf16_t*)g, (bf16_t*)xn, d, vocab, eps, nullptr, nullptr, 0, 0, nullptr, nullptr);
   else
     hipLaunchKernelGGL(embed_norm_kernel<float>, dim3(rows), dim3(256), 0, st, (const float*)emb, src, (float*)x,
-                       (const float*)g, (float*)xn, d, vocab, eps, nullptr, nullptr, 0, 0);
+                       (const float*)g, (float*)xn, d, vocab, eps, nullptr, nullptr, 0, 0, nullptr, nullptr);
   return hip_ok(hipGetLastError());
 }
 
@@ -514,33 +519,34 @@ int launch_rmsnorm(const void* x, const void* g, void* y, int rows, int d, float
 }
 
 int launch_finish_norm(const float* part, int splits, const void* bias, const void* residual, void* x_out,
-                       const void* g, void* xn_out, int rows, int d, float eps, int dtype, hipStream_t st, void* x_out2) {
+                       const void* g, void* xn_out, int rows, int d, float eps, int dtype, hipStream_t st, void* x_out2,
+                       const int32_t* gate) {
   if (d % 4 != 0 || d > 1024 * 4 * FIN_NV) return TANDEM_ERR_UNSUPPORTED;
   const long long MN = (long long)rows * d;
   int threads = (d / 4 + 63) / 64 * 64;
   threads = threads > 1024 ? 1024 : threads;
   if (dtype == TANDEM_BF16)
     hipLaunchKernelGGL(finish_norm_kernel<bf16_t>, dim3(rows), dim3(threads), 0, st, part, splits, MN, (const bf16_t*)bias,
-                       (const bf16_t*)residual, (bf16_t*)x_out, (bf16_t*)x_out2, (const bf16_t*)g, (bf16_t*)xn_out, d, eps);
+                       (const bf16_t*)residual, (bf16_t*)x_out, (bf16_t*)x_out2, (const bf16_t*)g, (bf16_t*)xn_out, d, eps, gate);
   else
     hipLaunchKernelGGL(finish_norm_kernel<float>, dim3(rows), dim3(threads), 0, st, part, splits, MN, (const float*)bias,
-                       (const float*)residual, (float*)x_out, (float*)x_out2, (const float*)g, (float*)xn_out, d, eps);
+                       (const float*)residual, (float*)x_out, (float*)x_out2, (const float*)g, (float*)xn_out, d, eps, gate);
   return hip_ok(hipGetLastError());
 }
 
 int launch_finish_scatter(const float* part, int splits, void* q, void* kc, void* vc, const int32_t* base, int fixed,
                           int rows, int q_len, int Hq, int Hkv, int dh, int64_t cap, int q_cols, int row_cols, int dtype,
-                          hipStream_t st) {
+                          hipStream_t st, const int32_t* gate) {
   if (row_cols % 4 != 0 || q_cols % 4 != 0 || dh % 4 != 0) return TANDEM_ERR_UNSUPPORTED;
   const long long MN = (long long)rows * row_cols;
   int threads = (row_cols / 4 + 63) / 64 * 64;
   threads = threads > 1024 ? 1024 : threads;
   if (dtype == TANDEM_BF16)
     hipLaunchKernelGGL(finish_scatter_kernel<bf16_t>, dim3(rows), dim3(threads), 0, st, part, splits, MN, (bf16_t*)q,
-                       (bf16_t*)kc, (bf16_t*)vc, base, fixed, q_len, Hq, Hkv, dh, (long long)cap, q_cols, row_cols);
+                       (bf16_t*)kc, (bf16_t*)vc, base, fixed, q_len, Hq, Hkv, dh, (long long)cap, q_cols, row_cols, gate);
   else
     hipLaunchKernelGGL(finish_scatter_kernel<float>, dim3(rows), dim3(threads), 0, st, part, splits, MN, (float*)q,
-                       (float*)kc, (float*)vc, base, fixed, q_len, Hq, Hkv, dh, (long long)cap, q_cols, row_cols);
+                       (float*)kc, (float*)vc, base, fixed, q_len, Hq, Hkv, dh, (long long)cap, q_cols, row_cols, gate);
   return hip_ok(hipGetLastError());
 }
 
@@ -557,13 +563,14 @@ int launch_scatter_qkv(const void* qkv, void* q, void* kc, void* vc, const int32
   return hip_ok(hipGetLastError());
 }
 
-int launch_argmax(const void* logits, int rows, int vocab, int32_t* out, int64_t out_stride, int dtype, hipStream_t st) {
+int launch_argmax(const void* logits, int rows, int vocab, int32_t* out, int64_t out_stride, int dtype, hipStream_t st,
+                  const int32_t* gate) {
   if (dtype == TANDEM_BF16)
     hipLaunchKernelGGL(argmax_kernel<bf16_t>, dim3(rows), dim3(1024), 0, st, (const bf16_t*)logits, vocab, out,
-                       (long long)out_stride);
+                       (long long)out_stride, gate);
   else
     hipLaunchKernelGGL(argmax_kernel<float>, dim3(rows), dim3(1024), 0, st, (const float*)logits, vocab, out,
-                       (long long)out_stride);
+                       (long long)out_stride, gate);
   return hip_ok(hipGetLastError());
 }
 

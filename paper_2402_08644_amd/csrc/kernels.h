@@ -81,6 +81,8 @@ struct GemmArgs {
   size_t ws_bytes;
   int defer;  // 1: leave fp32 partial sums [splits, M, N] in ws and skip the epilogue (bf16 MFMA path only);
               //    a fused consumer kernel finishes the layer.  bias / act / residual / Y are then ignored.
+  const int32_t* gate = nullptr;  // optional device flag: when *gate == 0 the kernels return at once and write nothing
+                                  // (bf16 MFMA kernels and their split epilogue; the generic kernel ignores it)
 };
 size_t gemm_workspace(int M, int N, int K, int dtype);
 bool gemm_can_defer(int M, int N, int K, int dtype, int64_t ldx);  // deferred epilogue available for this shape
@@ -95,9 +97,10 @@ int launch_rmsnorm(const void* x, const void* g, void* y, int rows, int d, float
 // finishes a deferred GEMM row by row: v = sum of partials (+ bias) (+ residual); x_out = v (and x_out2 = v when
 // given: a second copy that outlives the next in-place update); and, when g is given, xn_out = RMSNorm(v; g).
 // residual may alias x_out.
+// gate (here and below, optional): a device flag; when *gate == 0 the kernel returns at once and writes nothing.
 int launch_finish_norm(const float* part, int splits, const void* bias, const void* residual, void* x_out,
                        const void* g, void* xn_out, int rows, int d, float eps, int dtype, hipStream_t st,
-                       void* x_out2 = nullptr);
+                       void* x_out2 = nullptr, const int32_t* gate = nullptr);
 // x[row] = emb[token(row)] and, when g is given, xn[row] = RMSNorm(x[row]; g).  token(row): tokens[row * tok_stride],
 // or - pending given - the token at block position r = row % q + r0 of sequence b = row / q: pending[b] for r = 0,
 // follow[b * gamma + r - 1] otherwise.  init_B > 0 (rows == init_B): also ncur[r][b] = r + 1 for r < init_gamma and
@@ -105,7 +108,7 @@ int launch_finish_norm(const float* part, int splits, const void* bias, const vo
 int launch_embed_norm(const void* emb, const int32_t* tokens, int64_t tok_stride, const int32_t* pending,
                       const int32_t* follow, int gamma, int q, int r0, void* x, const void* g, void* xn, int rows, int d,
                       int vocab, float eps, int32_t* ncur, int32_t* stop, int init_B, int init_gamma, int dtype,
-                      hipStream_t st);
+                      hipStream_t st, int32_t* active = nullptr, const int32_t* gate = nullptr);  // active: [init_gamma] counters cleared with stop
 // The same gather with shifted token indices: tokens is [B, n_tokens]; row b * q + rr reads token
 // (pos ? pos[b] : 0) + fixed + rr - shift of sequence b.  A negative index gives an all-zero row (x and xn), an
 // index past the end is clamped.  (Deep Tandem, Eq. (3): row i of M_L reads token i - gamma.)

@@ -29,7 +29,11 @@ __global__ __launch_bounds__(RT_THREADS) void router_kernel(const T* __restrict_
                                                             const T* __restrict__ w2, const T* __restrict__ b2, int vocab,
                                                             int d, int k, int hidden, float tau, int run,
                                                             int32_t* __restrict__ stop, float* __restrict__ p_out,
-                                                            long long p_stride) {
+                                                            long long p_stride, int32_t* __restrict__ active,
+                                                            const int32_t* __restrict__ gate) {
+  // gate: nobody drafts any more; a sequence that has stopped needs no further decision (its p is not written)
+  if (gate && *gate == 0) return;
+  if (stop && stop[blockIdx.x] != 0) return;
   extern __shared__ float f[];  // features
   __shared__ float red[RT_WAVES], red2[RT_WAVES];
   __shared__ int ids[TANDEM_ROUTER_MAX_K];
@@ -248,21 +252,23 @@ __global__ __launch_bounds__(RT_THREADS) void router_kernel(const T* __restrict_
     for (int i = 0; i < RT_WAVES; ++i) zs += red[i];
     const float p = 1.f / (1.f + expf(-zs));
     if (p_out) p_out[row * p_stride] = p;
-    if (stop && stop[row] == 0 && p < tau) stop[row] = run + 1;
+    if (stop && p < tau) stop[row] = run + 1;
+    else if (active) atomicAdd(active + run, 1);  // still drafting after this run
   }
 }
 
 template <typename T>
 void launch_router_t(const tandem_router_desc* r, const void* logits, const void* emb, int rows, int vocab, int d, int run,
-                     int32_t* stop, float* p_out, int64_t p_stride, size_t lds, hipStream_t st) {
+                     int32_t* stop, float* p_out, int64_t p_stride, size_t lds, hipStream_t st, int32_t* active,
+                     const int32_t* gate) {
   if (vocab <= 32 * RT_THREADS)
     hipLaunchKernelGGL((router_kernel<T, true>), dim3(rows), dim3(RT_THREADS), lds, st, (const T*)logits, (const T*)emb,
                        (const T*)r->W1, (const T*)r->b1, (const T*)r->w2, (const T*)r->b2, vocab, d, r->k, r->d_hidden,
-                       r->tau, run, stop, p_out, (long long)p_stride);
+                       r->tau, run, stop, p_out, (long long)p_stride, active, gate);
   else
     hipLaunchKernelGGL((router_kernel<T, false>), dim3(rows), dim3(RT_THREADS), lds, st, (const T*)logits, (const T*)emb,
                        (const T*)r->W1, (const T*)r->b1, (const T*)r->w2, (const T*)r->b2, vocab, d, r->k, r->d_hidden,
-                       r->tau, run, stop, p_out, (long long)p_stride);
+                       r->tau, run, stop, p_out, (long long)p_stride, active, gate);
 }
 
 }  // namespace
@@ -277,12 +283,12 @@ int check_router(const tandem_router_desc* r, int d) {
 }
 
 int launch_router(const tandem_router_desc* r, const void* logits, const void* emb, int rows, int vocab, int d, int run,
-                  int32_t* stop, float* p_out, int64_t p_stride, hipStream_t st) {
+                  int32_t* stop, float* p_out, int64_t p_stride, hipStream_t st, int32_t* active, const int32_t* gate) {
   const size_t lds = 8 * ((1 + (size_t)r->k * (d + 1) + 7) / 8 + 1) * sizeof(float);  // features, see fi() in the kernel
   if (r->dtype == TANDEM_BF16)
-    launch_router_t<bf16_t>(r, logits, emb, rows, vocab, d, run, stop, p_out, p_stride, lds, st);
+    launch_router_t<bf16_t>(r, logits, emb, rows, vocab, d, run, stop, p_out, p_stride, lds, st, active, gate);
   else
-    launch_router_t<float>(r, logits, emb, rows, vocab, d, run, stop, p_out, p_stride, lds, st);
+    launch_router_t<float>(r, logits, emb, rows, vocab, d, run, stop, p_out, p_stride, lds, st, active, gate);
   return hip_ok(hipGetLastError());
 }
 

@@ -544,6 +544,13 @@ def test_decode_step_graph_replays_equal_eager(tb, adaptive):
     ws = binding.workspace(binding.tandem_decode_step_workspace(model, B, gamma))
     out = binding.tandem_decode_step(model, gst, gamma, aux=True, ws=ws, free_token=True, router=router, tau=0.5)
     torch.cuda.synchronize()
+    # once more into zeroed outputs: with the router, entries of draft runs that nobody needed are left unwritten
+    gst.n.copy_(n_dev)
+    gst.pending.copy_(p_dev)
+    for v in out.values():
+        v.zero_()
+    binding.tandem_decode_step(model, gst, gamma, ws=ws, out=out, free_token=True, router=router, tau=0.5)
+    torch.cuda.synchronize()
     eager = {k: v.clone() for k, v in out.items()}
     eager_n, eager_p = gst.n.clone(), gst.pending.clone()
     eager_k = gst.Khat[1].clone()

@@ -144,6 +144,56 @@ def test_adaptive_step_thresholds_zero_and_above_one_equal_fixed_steps(tb):
             assert torch.equal(sa.n, sf.n) and torch.equal(sa.pending, sf.pending)
 
 
+def test_adaptive_step_skips_the_runs_after_every_sequence_has_stopped(tb):
+    """bf16: once no sequence drafts any more, the kernels of the remaining draft runs return at once - their greedy
+    tokens are never written - and the step's results are still the oracle's.  Two thresholds: every sequence stops
+    after the first token; and one chosen from the probabilities so that the last one stops after the second."""
+    torch, binding = tb
+    from test_gpu_decode_step import small_bf16_pair, tokens_ok
+
+    W = small_bf16_pair(71)
+    T = inputs.as_f64(W)
+    B, T_max, gmax = 4, 128, 4
+    n, pending = [40, 7, 0, 90], [3, 500, 77, 12]
+    Rh = inputs.router_weights(4, 2, 256, 16, dtype="bf16", w_std=0.1, out_std=0.2)
+    R, R64 = dev_router(Rh), inputs.as_f64(Rh)
+    probe_state, host = oracle_state_from(T, B, T_max, 6, n, pending, "bf16")
+    probe = orc.decode_step(T, probe_state, gmax, router=R64, tau=0.0)["router_p"]
+    # above every probability of run 0: all stop at once; above the largest of run 1 only: the last ones stop there
+    # (kept 0.01 away from every probability, so that bf16 logits cannot move a decision across it)
+    second = next(t for t in float(probe[:, 1].max()) + 0.011 + 0.003 * np.arange(200) if np.abs(probe - t).min() > 0.01)
+    assert second < 1.5
+    model = binding.TandemModel(W)
+    for tau in (1.5, second):
+        ost, _ = oracle_state_from(T, B, T_max, 6, n, pending, "bf16")
+        want = orc.decode_step(T, ost, gmax, router=R64, tau=tau)
+        last = int(max(want["n_drafted"]))
+        assert last < gmax
+        gst = upload_state(tb, model, B, T_max, gmax, host, n, pending)
+        dev = gst.n.device
+        out = dict(tokens=torch.empty((B, gmax), dtype=torch.int32, device=dev),
+                   n_accepted=torch.empty((B,), dtype=torch.int32, device=dev),
+                   draft=torch.full((B, gmax), -7, dtype=torch.int32, device=dev),
+                   verify=torch.empty((B, gmax), dtype=torch.int32, device=dev),
+                   y_small=torch.empty((B, gmax, model.S.d), dtype=model.dtype, device=dev),
+                   x_large=torch.empty((B, gmax, model.L.d), dtype=model.dtype, device=dev),
+                   logits_S=torch.empty((B, gmax, model.S.vocab), dtype=model.dtype, device=dev),
+                   logits_L=torch.empty((B, gmax, model.L.vocab), dtype=model.dtype, device=dev))
+        got = binding.tandem_decode_step(model, gst, gmax, router=R, tau=tau, out=out)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(got["n_drafted"].cpu().numpy(), want["n_drafted"])
+        draft = got["draft"].cpu().numpy()
+        assert (draft[:, :last] >= 0).all()      # the runs somebody needed ran
+        assert (draft[:, last:] == -7).all()     # the later ones wrote no token
+        # tokens: the oracle's, or within the arithmetic's resolution of its logits where the GPU's drafts agree
+        if np.array_equal(draft[:, :last], np.asarray(want["draft"])[:, :last]):
+            np.testing.assert_array_equal(got["n_accepted"].cpu().numpy(), want["n_accepted"])
+            np.testing.assert_array_equal(gst.n.cpu().numpy(), ost["n"])
+        for b in range(B):
+            g = int(want["n_drafted"][b])
+            assert tokens_ok(draft[b, :g], np.asarray(want["logits_S"])[b, :g])
+
+
 def test_router_error_codes(tb):
     torch, binding = tb
     import ctypes as C
