@@ -9,7 +9,8 @@
  * General conventions
  *   - Every pointer named "device" is GPU memory owned by the caller; the library never
  *     allocates or frees device memory, never synchronises a stream or the device, and keeps
- *     no mutable global state beyond one-time, thread-safe kernel attribute set-up.  Descriptor
+ *     no mutable global state beyond one-time, thread-safe kernel attribute set-up (and the scratch array of
+ *     tandem_draft_attn_static, which is part of the library image).  Descriptor
  *     structs and the pointer arrays inside them are host memory, read during the call only
  *     (the model handle copies what it needs).
  *   - All entry points enqueue work on the given HIP stream (a hipStream_t passed as
@@ -46,7 +47,7 @@ typedef enum {
 } tandem_status;
 
 typedef enum { TANDEM_F32 = 0, TANDEM_BF16 = 1 } tandem_dtype;
-typedef enum { TANDEM_ACT_NONE = 0, TANDEM_ACT_GELU = 1 /* exact erf form */, TANDEM_ACT_RELU = 2 } tandem_act;
+typedef enum { TANDEM_ACT_NONE = 0, TANDEM_ACT_GELU = 1 /* 0.5 x (1 + erf(x / sqrt 2)); the bf16 kernels evaluate erf to 1.5e-7 */, TANDEM_ACT_RELU = 2 } tandem_act;
 
 #define TANDEM_MAX_QLEN 32 /* most query rows per sequence in one block-mode pass */
 #define TANDEM_MAX_PREFILL 128 /* most prompt tokens per sequence in one tandem_prefill call */
