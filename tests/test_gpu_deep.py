@@ -177,6 +177,33 @@ def test_deep_step_bf16_follows_the_oracle(tb, gamma, lens, d_hidden):
         assert tokens_ok(seq[S0:], fwd["logits"][S0 - 1 :])
 
 
+def test_deep_step_bf16_many_sequences(tb):
+    """36 sequences: M_S's products take the 64-row weight-streaming kernels instead of the 32-row ones, M_L's block
+    pass two row passes; the oracle scores three of the sequences."""
+    W = inputs.tandem_weights(
+        8, vocab=512, large=dict(d=512, n_layers=2, Hq=8, Hkv=2, dh=128, d_ff=1024),
+        small=dict(d=256, n_layers=2, Hq=2, Hkv=2, dh=128, d_ff=512), ell=(1, 2), d_hidden=256, dtype="bf16",
+        w_std=0.05, gain_std=0.3, bias_std=0.05, deep=True)
+    T = inputs.as_f64(W)
+    gamma, steps, B = 4, 2, 36
+    lens = [5 + (3 * b) % 9 for b in range(B)]
+    prompts = [inputs.token_ids(200 + b, (n,), 512) for b, n in enumerate(lens)]
+    toks, length, outs = run_generate(tb, W, prompts, gamma, steps, 48)
+    from test_gpu_decode_step import tokens_ok
+
+    n_new = steps * gamma
+    for b in (0, 17, 35):
+        S0 = lens[b]
+        assert length[b] == S0 + n_new
+        seq = toks[b, : S0 + n_new]
+        fwd = orc.deep_tandem_forward(T, seq[:-1], gamma)
+        lg = np.concatenate([o["logits"][b] for o in outs])
+        sk = np.concatenate([o["sketch"][b] for o in outs])
+        assert_rows_close(sk, fwd["sketch"][S0 : S0 + n_new], tol=TOL, what="deep step sketch bf16 B=36")
+        assert_rows_close(lg, fwd["logits"][S0 - 1 :], tol=TOL, what="deep step logits bf16 B=36")
+        assert tokens_ok(seq[S0:], fwd["logits"][S0 - 1 :])
+
+
 def test_deep_step_error_codes_and_capacity(tb):
     torch, binding = tb
     W = inputs.tandem_weights(

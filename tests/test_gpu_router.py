@@ -194,6 +194,41 @@ def test_adaptive_step_skips_the_runs_after_every_sequence_has_stopped(tb):
             assert tokens_ok(draft[b, :g], np.asarray(want["logits_S"])[b, :g])
 
 
+def test_adaptive_step_gate_with_many_sequences(tb):
+    """40 sequences (M_S's products run the 64-row kernels): with a threshold above every probability all stop after
+    the first token, the later runs write nothing, and the step equals the gamma = 1 step bit for bit."""
+    torch, binding = tb
+    from test_gpu_decode_step import small_bf16_pair
+
+    W = small_bf16_pair(72)
+    B, T_max, gmax = 40, 64, 4
+    model = binding.TandemModel(W)
+    R = dev_router(inputs.router_weights(6, 2, 256, 16, dtype="bf16", w_std=0.1, out_std=0.2))
+    fill = lambda *s: torch.randn(s, device="cuda", generator=torch.Generator("cuda").manual_seed(5)).to(torch.bfloat16)
+    sa = binding.TandemState(model, B, T_max, gmax, fill=fill)
+    sf = binding.TandemState(model, B, T_max, gmax, fill=fill)
+    for st in (sa, sf):
+        st.n.copy_(torch.arange(B, dtype=torch.int32) % 50)
+        st.pending.copy_((torch.arange(B, dtype=torch.int32) * 7) % 512)
+    dev = sa.n.device
+    out = dict(tokens=torch.empty((B, gmax), dtype=torch.int32, device=dev),
+               n_accepted=torch.empty((B,), dtype=torch.int32, device=dev),
+               draft=torch.full((B, gmax), -7, dtype=torch.int32, device=dev),
+               verify=torch.empty((B, gmax), dtype=torch.int32, device=dev),
+               y_small=torch.empty((B, gmax, model.S.d), dtype=model.dtype, device=dev),
+               x_large=torch.empty((B, gmax, model.L.d), dtype=model.dtype, device=dev),
+               logits_S=torch.empty((B, gmax, model.S.vocab), dtype=model.dtype, device=dev),
+               logits_L=torch.empty((B, gmax, model.L.vocab), dtype=model.dtype, device=dev))
+    a = binding.tandem_decode_step(model, sa, gmax, router=R, tau=1.5, out=out)
+    f = binding.tandem_decode_step(model, sf, 1)
+    torch.cuda.synchronize()
+    assert a["n_drafted"].cpu().tolist() == [1] * B
+    assert bool((a["draft"][:, 0] >= 0).all()) and bool((a["draft"][:, 1:] == -7).all())
+    assert torch.equal(a["tokens"][:, :1], f["tokens"]) and bool((a["tokens"][:, 1:] == -1).all())
+    assert torch.equal(a["n_accepted"], f["n_accepted"])
+    assert torch.equal(sa.n, sf.n) and torch.equal(sa.pending, sf.pending)
+
+
 def test_router_error_codes(tb):
     torch, binding = tb
     import ctypes as C
