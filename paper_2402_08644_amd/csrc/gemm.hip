@@ -60,19 +60,23 @@ __device__ __forceinline__ float epilogue(float v, int m, int n, const GemmParam
 // (measured: 10 us per launch).  There the activation is a template argument, selected once per kernel by
 // ACT_SWITCH, and the erf of GELU is the branch-free rational-times-exponential form (Abramowitz & Stegun
 // 7.1.26, absolute error below 1.5e-7: three orders below bf16 resolution).
-__device__ __forceinline__ float erf_as(float x) {
-  const float ax = fabsf(x);
-  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, ax, 1.f));
-  float y = fmaf(1.061405429f, t, -1.453152027f);
-  y = fmaf(y, t, 1.421413741f);
-  y = fmaf(y, t, -0.284496736f);
-  y = fmaf(y, t, 0.254829592f);
-  y = 1.f - y * t * fast_exp2(-1.4426950408889634f * ax * ax);
-  return copysignf(y, x);
+// GELU with that erf formula, erf(x) = 1 - P(t) t exp(-x^2), t = 1 / (1 + p x) for x >= 0, arranged for epilogues that
+// finish hundreds of values per lane: with a = |v|, x = a / sqrt 2 and q = (P(t) t / 2) exp(-x^2) = erfc(x) / 2 it is
+// gelu(v) = v Phi(v) = max(v, 0) - a q for either sign of v: 19 instruction slots instead of 25 (the reciprocal and
+// the exponential count four each).
+__device__ __forceinline__ float gelu_as(float v) {
+  const float a = fabsf(v);
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f * 0.70710678118654752f, a, 1.f));
+  float y = fmaf(0.5f * 1.061405429f, t, 0.5f * -1.453152027f);
+  y = fmaf(y, t, 0.5f * 1.421413741f);
+  y = fmaf(y, t, 0.5f * -0.284496736f);
+  y = fmaf(y, t, 0.5f * 0.254829592f);
+  const float q = y * t * fast_exp2((-0.5f * 1.4426950408889634f) * (v * v));
+  return fmaf(-a, q, fmaxf(v, 0.f));
 }
 template <int ACT>
 __device__ __forceinline__ float act_fn(float v) {
-  if (ACT == TANDEM_ACT_GELU) return 0.5f * v * (1.f + erf_as(v * 0.70710678118654752f));
+  if (ACT == TANDEM_ACT_GELU) return gelu_as(v);
   if (ACT == TANDEM_ACT_RELU) return fmaxf(v, 0.f);
   return v;
 }
@@ -112,6 +116,26 @@ __device__ __forceinline__ void store_tile_bf16(const f32x16& acc, int mbase, in
     const uint32_t word = odd ? pack_bf16x2(got, v1) : pack_bf16x2(v0, got);
     const int row = odd ? m + 1 : m;
     if (row < p.M) *reinterpret_cast<uint32_t*>((bf16_t*)p.Y + (long long)row * p.ldy + (n & ~1)) = word;
+  }
+}
+
+// The same store for the big-tile kernel, whose epilogue finishes 256 values per lane: everything that does not depend
+// on the value is taken out of it.  yt: the wavefront's first output row at its first column (a wave-uniform byte
+// pointer); loff: this lane's byte offset inside that (row 4 h, plus 1 for odd lanes, column n & ~1); rowb: bytes per
+// row; mleft: rows of the wavefront's 128 that exist (FULL: all of them, no test per store); lrow = 4 h.  dm0 = first
+// row of the 32 x 32 tile inside the wavefront's 128, nofs = its first column.  No residual (products with one take
+// store_tile_bf16).
+template <int ACT, bool FULL>
+__device__ __forceinline__ void store_tile_big(const f32x16& acc, char* yt, uint32_t loff, uint32_t rowb, int dm0, int nofs,
+                                               bool odd, float bn, int mleft, int lrow) {
+#pragma unroll
+  for (int r = 0; r < 16; r += 2) {
+    const int dm = dm0 + 8 * (r >> 2) + (r & 3);  // rows dm (value r) and dm + 1 (value r + 1), plus 4 h in loff
+    const float v0 = act_fn<ACT>(acc[r] + bn), v1 = act_fn<ACT>(acc[r + 1] + bn);
+    const float got = dpp_f32<0xB1>(odd ? v0 : v1);  // from lane ^ 1
+    const uint32_t word = odd ? pack_bf16x2(got, v1) : pack_bf16x2(v0, got);
+    if (FULL || lrow + dm + (odd ? 1 : 0) < mleft)
+      *reinterpret_cast<uint32_t*>(yt + (size_t)dm * rowb + (size_t)nofs * 2 + loff) = word;
   }
 }
 
@@ -858,15 +882,6 @@ __global__ __launch_bounds__(256, 1) void gemm_big_kernel(GemmParams p, int tile
 #undef BG_OPS
 #undef BG_MFMA
 
-  // C layout: lane holds column j = lane%32 (feature n), rows i = 8*(r/4) + 4*(lane/32) + r%4 (row m)
-#define BG_OUT(i, j)                                                                              \
-  {                                                                                               \
-    const int n_ = n0 + wn * 128 + (j) * 32 + c32;                                                \
-    const float bn_ = p.bias ? bf16_to_f32(((const bf16_t*)p.bias)[n_]) : 0.f;                    \
-    store_tile_bf16<ACT>(acc[i][j], m0 + wm * 128 + (i) * 32, n_, h, bn_, p);                     \
-    __builtin_amdgcn_sched_barrier(0);                                                            \
-  }
-#define BG_OUT_ROW(i) BG_OUT(i, 0) BG_OUT(i, 1) BG_OUT(i, 2) BG_OUT(i, 3)
   if (p.splitK > 1 || p.defer) {
     // fp32 partial sums [split, M, N]: 32 lanes = 128 contiguous bytes of a row per store
     const int mrow = m0 + wm * 128 + 4 * h;
@@ -885,9 +900,48 @@ __global__ __launch_bounds__(256, 1) void gemm_big_kernel(GemmParams p, int tile
 #undef BG_PART
     return;
   }
-  ACT_SWITCH(p.act, { BG_OUT_ROW(0) BG_OUT_ROW(1) BG_OUT_ROW(2) BG_OUT_ROW(3) })
+  // C layout: lane holds column j = lane % 32 (feature n), rows i = 8 * (r / 4) + 4 * (lane / 32) + r % 4 (row m).
+  // Per lane 256 values: the wave-uniform and per-lane parts of the addresses, the biases and the row test are
+  // computed once (an epilogue that redid them per value took 12 us of a 120 us tile).
+  if (p.residual) {
+    // rare at this size (no caller of the library has one): the general store
+#define BG_OUT(i, j)                                                                              \
+  {                                                                                               \
+    const int n_ = n0 + wn * 128 + (j) * 32 + c32;                                                \
+    const float bn_ = p.bias ? bf16_to_f32(((const bf16_t*)p.bias)[n_]) : 0.f;                    \
+    store_tile_bf16<ACT>(acc[i][j], m0 + wm * 128 + (i) * 32, n_, h, bn_, p);                     \
+    __builtin_amdgcn_sched_barrier(0);                                                            \
+  }
+#define BG_OUT_ROW(i) BG_OUT(i, 0) BG_OUT(i, 1) BG_OUT(i, 2) BG_OUT(i, 3)
+    ACT_SWITCH(p.act, { BG_OUT_ROW(0) BG_OUT_ROW(1) BG_OUT_ROW(2) BG_OUT_ROW(3) })
 #undef BG_OUT_ROW
 #undef BG_OUT
+  } else {
+    const int mw = m0 + wm * 128, nw = n0 + wn * 128;
+    const bool odd = c32 & 1;
+    char* yt = reinterpret_cast<char*>((bf16_t*)p.Y + (long long)mw * p.ldy + nw);
+    const uint32_t rowb = (uint32_t)p.ldy * 2u;
+    const uint32_t loff = (uint32_t)(4 * h + (odd ? 1 : 0)) * rowb + (uint32_t)(c32 & ~1) * 2u;
+    const int mleft = p.M - mw, lrow = 4 * h;  // rows of this wavefront's 128 that exist; this lane's first row
+    float bn[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) bn[j] = p.bias ? bf16_to_f32(((const bf16_t*)p.bias)[nw + j * 32 + c32]) : 0.f;
+#define BG_OUT(i, j)                                                                                    \
+  store_tile_big<ACT, FULL>(acc[i][j], yt, loff, rowb, (i) * 32, (j) * 32, odd, bn[j], mleft, lrow);    \
+  __builtin_amdgcn_sched_barrier(0);
+#define BG_OUT_ROW(i) BG_OUT(i, 0) BG_OUT(i, 1) BG_OUT(i, 2) BG_OUT(i, 3)
+#define BG_OUT_ALL BG_OUT_ROW(0) BG_OUT_ROW(1) BG_OUT_ROW(2) BG_OUT_ROW(3)
+    if (mleft >= 128) {
+      constexpr bool FULL = true;
+      ACT_SWITCH(p.act, { BG_OUT_ALL })
+    } else if (mleft > 0) {
+      constexpr bool FULL = false;
+      ACT_SWITCH(p.act, { BG_OUT_ALL })
+    }
+#undef BG_OUT_ALL
+#undef BG_OUT_ROW
+#undef BG_OUT
+  }
 }
 
 // sums the split partials in split order, then the epilogue
