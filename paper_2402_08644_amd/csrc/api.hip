@@ -23,6 +23,21 @@ int ensure_dynamic_lds(const void* kernel, size_t bytes) {
   return TANDEM_OK;
 }
 
+int compute_units() {
+  constexpr int MAX_DEVICES = 64;
+  static std::mutex mu;
+  static int count[MAX_DEVICES] = {};
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return 0;
+  std::lock_guard<std::mutex> lock(mu);
+  if (count[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return 0;
+    count[dev] = n;
+  }
+  return count[dev];
+}
+
 // Split-K partials of tandem_draft_attn_static: device memory that exists from the moment the library is loaded, so
 // that entry point never allocates.  One copy per GPU; in host code the name is only a handle for
 // hipGetSymbolAddress, the kernels get the address that call returns.  (No `used` attribute: with it the compiler

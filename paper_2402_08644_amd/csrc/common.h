@@ -101,3 +101,5 @@ static inline int hip_ok(hipError_t e) { return e == hipSuccess ? TANDEM_OK : TA
 // Raises a kernel's dynamic-LDS limit to `bytes` (nothing to do up to 48 KB) once per kernel and device; safe to call
 // from several threads, cheap on every later call.  Returns a tandem_status.
 int ensure_dynamic_lds(const void* kernel, size_t bytes);
+// Compute units of the current device (looked up once per device; 0 when the runtime cannot tell).
+int compute_units();

@@ -751,35 +751,57 @@ __global__ __launch_bounds__(256, 1) void gemm_big_kernel(GemmParams p, int tile
   const int wm = w >> 1, wn = w & 1;
   const int c32 = lane & 31, h = lane >> 5;
 
-  // XCD-aware tile order
+  // XCD-aware tile order.  A workgroup takes the tiles blockIdx.x, blockIdx.x + gridDim.x, ... (the launcher starts
+  // one workgroup per compute unit when there are more tiles than that): ids go to the XCDs round-robin, so a
+  // workgroup's tiles stay on its XCD.
   const int total = tiles_m * tiles_n;
-  int id = blockIdx.x;
-  if ((total & 7) == 0) id = (id & 7) * (total >> 3) + (id >> 3);
-  int tn = id / tiles_m, tm = id % tiles_m;
-  if ((total & 7) == 0 && (tiles_m & 7) == 0 && (tiles_n & 3) == 0) {
-    // the 32 tiles an XCD works on at a time form an 8 x 4 block: 12 operand tiles feed 32 output tiles
-    const int block = id >> 5, within = id & 31, blocks_m = tiles_m >> 3;
-    tm = (block % blocks_m) * 8 + (within & 7);
-    tn = (block / blocks_m) * 4 + (within >> 3);
+#define BG_TILE(id_, m0_, n0_)                                                                          \
+  {                                                                                                     \
+    int id = (id_);                                                                                     \
+    if ((total & 7) == 0) id = (id & 7) * (total >> 3) + (id >> 3);                                     \
+    int tn = id / tiles_m, tm = id % tiles_m;                                                           \
+    if ((total & 7) == 0 && (tiles_m & 7) == 0 && (tiles_n & 3) == 0) {                                 \
+      /* the 32 tiles an XCD works on at a time form an 8 x 4 block: 12 operand tiles feed 32 output tiles */ \
+      const int block = id >> 5, within = id & 31, blocks_m = tiles_m >> 3;                             \
+      tm = (block % blocks_m) * 8 + (within & 7);                                                       \
+      tn = (block / blocks_m) * 4 + (within >> 3);                                                      \
+    }                                                                                                   \
+    m0_ = tm * 256;                                                                                     \
+    n0_ = tn * 256;                                                                                     \
   }
-  const int m0 = tm * 256, n0 = tn * 256;
+  int tile = blockIdx.x, m0, n0;
+  BG_TILE(tile, m0, n0)
   const int stages = (p.K / BK) / p.splitK;  // of this workgroup; even (launcher)
   const long long kbase = (long long)blockIdx.y * stages * BK;
 
   // Direct loads: instruction q of wavefront w fills rows 8 * (4 * q + w) .. + 8 of an operand tile (1 KB of
   // LDS); lane l lands on row l >> 3, position l & 7, so it fetches piece (l & 7) ^ ((row >> 1) & 7).
-  const int drow = lane >> 3;
-  const int dpiece = (lane & 7) ^ ((((w & 1) << 2) | (drow >> 1)) & 7);
   const bf16_t* ag[8];
   const bf16_t* bg[8];
-#pragma unroll
-  for (int q = 0; q < 8; ++q) {
-    const int row = 8 * (4 * q + w) + drow;
-    int m_ = m0 + row;
-    m_ = m_ < p.M ? m_ : p.M - 1;
-    ag[q] = (const bf16_t*)p.X + (long long)m_ * p.ldx + kbase + dpiece * 8;
-    bg[q] = (const bf16_t*)p.W + (long long)(n0 + row) * p.K + kbase + dpiece * 8;
+  // (the lane number is taken again from the hardware - through an opaque operand, so that the compiler neither
+  // reuses nor hoists it - and everything derived from it is recomputed where the addresses are set up: the main
+  // loop has no register to keep such values in, they would be spilled)
+#define BG_LANE(lane_)                                                                         \
+  int lane_;                                                                                   \
+  {                                                                                            \
+    unsigned ones_ = ~0u;                                                                      \
+    asm volatile("" : "+s"(ones_));                                                            \
+    lane_ = (int)__builtin_amdgcn_mbcnt_hi(ones_, __builtin_amdgcn_mbcnt_lo(ones_, 0u));       \
   }
+#define BG_PTRS(m0_, n0_)                                                                      \
+  {                                                                                            \
+    BG_LANE(lane_)                                                                             \
+    const int drow_ = lane_ >> 3;                                                              \
+    const int dpiece_ = (lane_ & 7) ^ ((((w & 1) << 2) | (drow_ >> 1)) & 7);                   \
+    _Pragma("unroll") for (int q = 0; q < 8; ++q) {                                            \
+      const int row = 8 * (4 * q + w) + drow_;                                                 \
+      int m_ = (m0_) + row;                                                                    \
+      m_ = m_ < p.M ? m_ : p.M - 1;                                                            \
+      ag[q] = (const bf16_t*)p.X + (long long)m_ * p.ldx + kbase + dpiece_ * 8;                \
+      bg[q] = (const bf16_t*)p.W + (long long)((n0_) + row) * p.K + kbase + dpiece_ * 8;       \
+    }                                                                                          \
+  }
+  BG_PTRS(m0, n0)
   // one direct load (1 KB): rows 8 * (4 * q + w) .. + 8 of the A (X) or B (W) tile of a stage
 #define BG_DMA_A(buf, k0, q)                                                                                \
   __builtin_amdgcn_global_load_lds((global_void_ptr)(ag[q] + (k0)),                                         \
@@ -791,12 +813,6 @@ __global__ __launch_bounds__(256, 1) void gemm_big_kernel(GemmParams p, int tile
   __builtin_amdgcn_sched_barrier(0);
 
   f32x16 acc[4][4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   // operand reads: row (wm | wn) * 128 + 32 * t + c32, piece 2 * ks + h, at position piece ^ ((c32 >> 1) & 7)
   const int fsw = (c32 >> 1) & 7;
@@ -862,6 +878,15 @@ __global__ __launch_bounds__(256, 1) void gemm_big_kernel(GemmParams p, int tile
     BG_DMA_A(0, 0, q)
     BG_DMA_B(0, 0, q)
   }
+  // Tile loop.  The first stage of a workgroup's next tile is requested before the epilogue of the current one, so
+  // its latency (and a workgroup launch) is off the path between two tiles.
+  for (;;) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 #pragma unroll
   for (int t = 0; t < 4; ++t) av1[t] = bv1[t] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};  // "last step of the stage before" of stage 0
   __syncthreads();
@@ -873,19 +898,28 @@ __global__ __launch_bounds__(256, 1) void gemm_big_kernel(GemmParams p, int tile
     BG_STAGE(1, k2)
   }
   BG_MFMA(av1, bv1)  // last step of the last stage
-#undef BG_DMA_A
-#undef BG_DMA_B
-#undef BG_MFMA2
-#undef BG_MFMA_DMA
-#undef BG_LDS_DONE
-#undef BG_STAGE
-#undef BG_OPS
-#undef BG_MFMA
+  // every wavefront is past the last stage's barrier: buffer 0 holds nothing anybody needs
+  const int m0c = m0, n0c = n0;  // the tile whose results are in the accumulators
+  const int next = tile + (int)gridDim.x;
+  const bool more = next < total;
+  if (more) {
+    tile = next;
+    BG_TILE(tile, m0, n0)
+    BG_PTRS(m0, n0)
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      BG_DMA_A(0, 0, q)
+      BG_DMA_B(0, 0, q)
+    }
+  }
 
+  // (lane coordinates taken afresh, see BG_LANE: everything the epilogue derives from them is computed per tile)
+  BG_LANE(lane_e)
+  const int c32e = lane_e & 31, he = lane_e >> 5;
   if (p.splitK > 1 || p.defer) {
     // fp32 partial sums [split, M, N]: 32 lanes = 128 contiguous bytes of a row per store
-    const int mrow = m0 + wm * 128 + 4 * h;
-    float* part = p.part + ((long long)blockIdx.y * p.M + mrow) * p.N + n0 + wn * 128 + c32;
+    const int mrow = m0c + wm * 128 + 4 * he;
+    float* part = p.part + ((long long)blockIdx.y * p.M + mrow) * p.N + n0c + wn * 128 + c32e;
 #define BG_PART(i, j)                                                                             \
   {                                                                                               \
     _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                              \
@@ -898,8 +932,7 @@ __global__ __launch_bounds__(256, 1) void gemm_big_kernel(GemmParams p, int tile
     BG_PART_ROW(0) BG_PART_ROW(1) BG_PART_ROW(2) BG_PART_ROW(3)
 #undef BG_PART_ROW
 #undef BG_PART
-    return;
-  }
+  } else
   // C layout: lane holds column j = lane % 32 (feature n), rows i = 8 * (r / 4) + 4 * (lane / 32) + r % 4 (row m).
   // Per lane 256 values: the wave-uniform and per-lane parts of the addresses, the biases and the row test are
   // computed once (an epilogue that redid them per value took 12 us of a 120 us tile).
@@ -907,9 +940,9 @@ __global__ __launch_bounds__(256, 1) void gemm_big_kernel(GemmParams p, int tile
     // rare at this size (no caller of the library has one): the general store
 #define BG_OUT(i, j)                                                                              \
   {                                                                                               \
-    const int n_ = n0 + wn * 128 + (j) * 32 + c32;                                                \
+    const int n_ = n0c + wn * 128 + (j) * 32 + c32e;                                               \
     const float bn_ = p.bias ? bf16_to_f32(((const bf16_t*)p.bias)[n_]) : 0.f;                    \
-    store_tile_bf16<ACT>(acc[i][j], m0 + wm * 128 + (i) * 32, n_, h, bn_, p);                     \
+    store_tile_bf16<ACT>(acc[i][j], m0c + wm * 128 + (i) * 32, n_, he, bn_, p);                    \
     __builtin_amdgcn_sched_barrier(0);                                                            \
   }
 #define BG_OUT_ROW(i) BG_OUT(i, 0) BG_OUT(i, 1) BG_OUT(i, 2) BG_OUT(i, 3)
@@ -917,15 +950,15 @@ __global__ __launch_bounds__(256, 1) void gemm_big_kernel(GemmParams p, int tile
 #undef BG_OUT_ROW
 #undef BG_OUT
   } else {
-    const int mw = m0 + wm * 128, nw = n0 + wn * 128;
-    const bool odd = c32 & 1;
+    const int mw = m0c + wm * 128, nw = n0c + wn * 128;
+    const bool odd = c32e & 1;
     char* yt = reinterpret_cast<char*>((bf16_t*)p.Y + (long long)mw * p.ldy + nw);
     const uint32_t rowb = (uint32_t)p.ldy * 2u;
-    const uint32_t loff = (uint32_t)(4 * h + (odd ? 1 : 0)) * rowb + (uint32_t)(c32 & ~1) * 2u;
-    const int mleft = p.M - mw, lrow = 4 * h;  // rows of this wavefront's 128 that exist; this lane's first row
+    const uint32_t loff = (uint32_t)(4 * he + (odd ? 1 : 0)) * rowb + (uint32_t)(c32e & ~1) * 2u;
+    const int mleft = p.M - mw, lrow = 4 * he;  // rows of this wavefront's 128 that exist; this lane's first row
     float bn[4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) bn[j] = p.bias ? bf16_to_f32(((const bf16_t*)p.bias)[nw + j * 32 + c32]) : 0.f;
+    for (int j = 0; j < 4; ++j) bn[j] = p.bias ? bf16_to_f32(((const bf16_t*)p.bias)[nw + j * 32 + c32e]) : 0.f;
 #define BG_OUT(i, j)                                                                                    \
   store_tile_big<ACT, FULL>(acc[i][j], yt, loff, rowb, (i) * 32, (j) * 32, odd, bn[j], mleft, lrow);    \
   __builtin_amdgcn_sched_barrier(0);
@@ -942,6 +975,22 @@ __global__ __launch_bounds__(256, 1) void gemm_big_kernel(GemmParams p, int tile
 #undef BG_OUT_ROW
 #undef BG_OUT
   }
+  if (!more) break;
+  // the load addresses of the new tile are computed again rather than kept in 32 registers through the epilogue
+  asm volatile("" : "+s"(m0), "+s"(n0));
+  BG_PTRS(m0, n0)
+  }  // tile loop
+#undef BG_DMA_A
+#undef BG_DMA_B
+#undef BG_MFMA2
+#undef BG_MFMA_DMA
+#undef BG_LDS_DONE
+#undef BG_STAGE
+#undef BG_OPS
+#undef BG_MFMA
+#undef BG_TILE
+#undef BG_PTRS
+#undef BG_LANE
 }
 
 // sums the split partials in split order, then the epilogue
@@ -1010,7 +1059,11 @@ int launch_big(const GemmParams& p, hipStream_t st) {
   const size_t lds_bytes = (size_t)2 * 2 * 256 * BK * sizeof(bf16_t);
   if (const int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(&gemm_big_kernel), lds_bytes)) return rc;
   const int tiles_m = (p.M + 255) / 256, tiles_n = p.N / 256;
-  hipLaunchKernelGGL(gemm_big_kernel, dim3(tiles_m * tiles_n, p.splitK), dim3(256), lds_bytes, st, p, tiles_m, tiles_n);
+  // one workgroup per compute unit, each taking every gridDim.x-th tile, when there are more tiles than units
+  int grid_x = tiles_m * tiles_n;
+  const int cus = compute_units();
+  if (cus > 0 && grid_x * p.splitK > cus && p.splitK == 1) grid_x = cus;
+  hipLaunchKernelGGL(gemm_big_kernel, dim3(grid_x, p.splitK), dim3(256), lds_bytes, st, p, tiles_m, tiles_n);
   return hip_ok(hipGetLastError());
 }
 // The big-tile kernel takes a product when its 256 x 256 tiles occupy at least half the CUs, or, from 1024
