@@ -692,14 +692,26 @@ __global__ __launch_bounds__(512) void gemm_stream_kernel(GemmParams p) {
   // each 32-row tile: a store instruction covers whole 128-byte (fp32) or 64-byte (bf16) row segments.
   const int n = n0 + c32;
   if (p.splitK > 1 || p.defer) {
-    float* dst = p.part + (long long)by * p.M * p.N + n;
+    // wave-uniform base + one per-lane byte offset; each store then adds a compile-time multiple of the row pitch
+    char* dst = reinterpret_cast<char*>(p.part + ((long long)by * p.M + m0) * p.N + n0);
+    const uint32_t rowb = (uint32_t)p.N * 4u;
+    const uint32_t loff = (uint32_t)(4 * h) * rowb + (uint32_t)c32 * 4u;
+    const int mleft = p.M - m0 - 4 * h;  // rows from this lane's first one to the end of the matrix
+    if (p.M - m0 >= 32 * MT) {
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+      for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int m = m0 + mt * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
-        if (m < p.M) dst[(long long)m * p.N] = acc[mt][r];
-      }
+        for (int r = 0; r < 16; ++r)
+          *reinterpret_cast<float*>(dst + (size_t)(mt * 32 + 8 * (r >> 2) + (r & 3)) * rowb + loff) = acc[mt][r];
+    } else {
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int dm = mt * 32 + 8 * (r >> 2) + (r & 3);
+          if (dm < mleft) *reinterpret_cast<float*>(dst + (size_t)dm * rowb + loff) = acc[mt][r];
+        }
+    }
     return;
   }
   const float bn = p.bias ? bf16_to_f32(((const bf16_t*)p.bias)[n]) : 0.f;
