@@ -208,7 +208,7 @@ StepPlan make_plan(const tandem_model* m, int B, int gamma, int64_t T_max, int g
   p.n_keep = S.n_layers;
   p.keep_stride = align256(M * L.d * es);
   p.keep = take(p.keep_stride * S.n_layers);
-  // ints: ncur[gamma][B], block_tokens[B*gamma], draft[B*gamma], verify[B*gamma], stop[B]
+  // ints: ncur[gamma][B] (2 M reserved), draft[B*gamma], verify[B*nq], stop[B], active[gamma]
   p.ints = take(sizeof(int32_t) * (4 * M + B + TANDEM_MAX_QLEN));  // + stop[B], active[gamma] of the adaptive block length
   // Attention scratch: the larger of the draft and the block call, for ANY cache capacity.  The number of context
   // splits a launch uses depends on the capacity (at most one split per 256 keys; an even count becomes half as many
@@ -451,7 +451,7 @@ int copy2d(void* dst, size_t dpitch, const void* src, size_t spitch, size_t widt
   return hip_ok(hipMemcpy2DAsync(dst, dpitch, src, spitch, width, height, hipMemcpyDeviceToDevice, st));
 }
 
-// M_L in block mode on block_tokens[B, nq] at positions n .. n+nq-1 (Eq. (1) on the new rows: appends its K/V
+// M_L in block mode on the block's tokens [B, nq] at positions n .. n+nq-1 (Eq. (1) on the new rows: appends its K/V
 // rows, tandem_block_attn per layer), then, per small layer, FF_Tandem on x^(ell[j]) of those rows and that
 // layer's RMSNorm and W_K / W_V, which append the K_hat / V_hat rows (Eq. (2) line 1).  verify (optional):
 // M_L's greedy token after every row.  Reads state->n, does not change it.
@@ -479,8 +479,8 @@ int large_block_pass(const Ctx& c, const int32_t* tokens, const int32_t* follow,
   TRY(keep(0, 0));
   for (int j = 0; j < L.n_layers; ++j) {
     auto attn_only = [&]() -> int {
-      // more than TANDEM_MAX_QLEN rows per sequence (long prompt chunks): the attention runs on sub-blocks of rows,
-      // all of whose K/V rows are already in the cache
+      // long prompt chunks: the matrix-core kernels take up to TANDEM_MAX_PREFILL rows per sequence in one launch (row
+      // passes inside it), the generic ones TANDEM_MAX_QLEN per launch; all K/V rows are already in the cache
       const int sub = c.dtype == TANDEM_BF16 && L.dh == 128 && !c.pr ? TANDEM_MAX_PREFILL : TANDEM_MAX_QLEN;
       for (int r0 = 0; r0 < nq; r0 += sub) {
         const int rows = nq - r0 < sub ? nq - r0 : sub;

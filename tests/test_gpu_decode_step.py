@@ -360,7 +360,7 @@ def test_free_token_stream_equals_greedy_large_decode_fp32(tb):
         assert got[:n_new] == want, (gamma, got, want)
 
 
-# (32,) x 9: 288 rows, big tiles; (70, 33): more than 32 rows per sequence - attention in sub-blocks of 32 + a tail
+# (32,) x 9: 288 rows, big tiles; (70, 33): more than 32 rows per sequence - row passes inside one attention launch
 @pytest.mark.parametrize("chunks,B", [((4, 1, 6), 3), ((32, 9), 2), ((16,), 5), ((32,), 9), ((70, 33), 2), ((128,), 1)])
 def test_prefill_bf16_vs_oracle(tb, chunks, B):
     """tandem_prefill chunk by chunk (ragged starting lengths): new cache rows, x^(L_L) and n against the oracle;
