@@ -114,13 +114,48 @@ __device__ __forceinline__ void write_row(const BlockParams& p, long long orow, 
   }
 }
 
+// The same for one block of 16 output elements (db): this lane's four values o of elements 16 db + 4 g4 + r4.  Used
+// by the merge of attn_block_kernel, where every wavefront finishes one such block of every row.
+__device__ __forceinline__ void write_piece(const BlockParams& p, long long orow, int b, int s, int g4, int db, float m,
+                                            float l, f32x4 o) {
+  if (p.merge_prev > 0) {
+    for (int t = 0; t < p.merge_prev; ++t) {
+      const long long ps = orow * p.S_total + t;
+      const float mo = p.part_ml[ps * 2], lo = p.part_ml[ps * 2 + 1];
+      const float mn = fmaxf(m, mo);
+      const float ca = fast_exp2(m - mn), cb = fast_exp2(mo - mn);
+      m = mn;
+      l = l * ca + lo * cb;
+      const float4 q = *reinterpret_cast<const float4*>(p.part_o + ps * 128 + 4 * g4 + 16 * db);
+      o[0] = o[0] * ca + q.x * cb;
+      o[1] = o[1] * ca + q.y * cb;
+      o[2] = o[2] * ca + q.z * cb;
+      o[3] = o[3] * ca + q.w * cb;
+    }
+  }
+  if (p.S_total == 1 || p.merge_prev > 0) {
+    const float inv = l > 0.f ? 1.f / l : 0.f;
+    uint2 u;
+    u.x = pack_bf16x2(o[0] * inv, o[1] * inv);
+    u.y = pack_bf16x2(o[2] * inv, o[3] * inv);
+    *reinterpret_cast<uint2*>(p.out + (orow + b * p.row_skip) * 128 + 4 * g4 + 16 * db) = u;
+  } else {
+    const long long ps = orow * p.S_total + p.s_off + s;
+    *reinterpret_cast<float4*>(p.part_o + ps * 128 + 4 * g4 + 16 * db) = make_float4(o[0], o[1], o[2], o[3]);
+    if (g4 == 0 && db == 0) {
+      p.part_ml[ps * 2 + 0] = m;
+      p.part_ml[ps * 2 + 1] = l;
+    }
+  }
+}
+
 constexpr int ST_REGS = 34;  // per-lane state of one row tile: m, l, 32 accumulators
 
 // NW wavefronts per workgroup (4 or 8): eight put the work of two context splits into one workgroup, whose
 // wavefronts merge through LDS, so that no partials leave the workgroup and no combine kernel follows.
 template <int RT, int NW>
 __global__ __launch_bounds__(64 * NW, (RT <= 2 && NW == 4 ? 2 : 1)) void attn_block_kernel(BlockParams p) {
-  extern __shared__ float lds[];  // [NW / 2][RT][ST_REGS][64]
+  extern __shared__ float lds[];  // [NW][RT][ST_REGS][64]
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int g4 = lane >> 4, c16 = lane & 15;
   const int s = blockIdx.x, b = blockIdx.z;
@@ -260,50 +295,43 @@ __global__ __launch_bounds__(64 * NW, (RT <= 2 && NW == 4 ? 2 : 1)) void attn_bl
     l[rt] += __shfl_xor(l[rt], 32);
   }
 
-  // tree merge of the wavefronts through LDS (lane-local: all waves use the same layout)
-  auto slot = [&](int buf, int rt, int reg) -> float& { return lds[((buf * RT + rt) * ST_REGS + reg) * 64 + lane]; };
-  auto put = [&](int buf) {
+  // Merge of the wavefronts through LDS (lane-local: all waves use the same layout), in one step: every wavefront
+  // parks its state, then wavefront w finishes the output elements 16 db .. 16 db + 15 of every row for db = w, w + NW,
+  // ...: it combines the NW states in wavefront order (a fixed order: results do not depend on timing) and writes
+  // its piece.  (A tree of pairwise merges took three to six barriers and left the writing to one wavefront.)
+  auto slot = [&](int wv, int rt, int reg) -> float& { return lds[((wv * RT + rt) * ST_REGS + reg) * 64 + lane]; };
 #pragma unroll
-    for (int rt = 0; rt < RT; ++rt) {
-      slot(buf, rt, 0) = m[rt];
-      slot(buf, rt, 1) = l[rt];
+  for (int rt = 0; rt < RT; ++rt) {
+    slot(w, rt, 0) = m[rt];
+    slot(w, rt, 1) = l[rt];
 #pragma unroll
-      for (int db = 0; db < 8; ++db)
+    for (int db = 0; db < 8; ++db)
 #pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) slot(buf, rt, 2 + db * 4 + r4) = acc[rt][db][r4];
-    }
-  };
-  auto take = [&](int buf) {
-#pragma unroll
-    for (int rt = 0; rt < RT; ++rt) {
-      const float mo = slot(buf, rt, 0), lo = slot(buf, rt, 1);
-      const float mn = fmaxf(m[rt], mo);
-      const float ca = fast_exp2(m[rt] - mn), cb = fast_exp2(mo - mn);
-      m[rt] = mn;
-      l[rt] = l[rt] * ca + lo * cb;
-#pragma unroll
-      for (int db = 0; db < 8; ++db)
-#pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) acc[rt][db][r4] = acc[rt][db][r4] * ca + slot(buf, rt, 2 + db * 4 + r4) * cb;
-    }
-  };
-  if (NW == 8) {
-    if (w >= 4) put(w - 4);
-    __syncthreads();
-    if (w < 4) take(w);
-    __syncthreads();
+      for (int r4 = 0; r4 < 4; ++r4) slot(w, rt, 2 + db * 4 + r4) = acc[rt][db][r4];
   }
-  if (w >= 2 && w < 4) put(w - 2);
   __syncthreads();
-  if (w < 2) take(w);
-  __syncthreads();
-  if (w == 1) put(0);
-  __syncthreads();
-  if (w == 0) {
-    take(0);
 #pragma unroll
-    for (int rt = 0; rt < RT; ++rt)
-      if (orow[rt] >= 0) write_row(p, orow[rt], b, s, g4, m[rt], l[rt], acc[rt]);
+  for (int rt = 0; rt < RT; ++rt) {
+    float mi[NW], mm = TANDEM_NEG_BIG;
+#pragma unroll
+    for (int i = 0; i < NW; ++i) {
+      mi[i] = slot(i, rt, 0);
+      mm = fmaxf(mm, mi[i]);
+    }
+    float ll = 0.f;
+#pragma unroll
+    for (int i = 0; i < NW; ++i) {
+      mi[i] = fast_exp2(mi[i] - mm);  // weight of state i
+      ll += slot(i, rt, 1) * mi[i];
+    }
+    for (int db = w; db < 8; db += NW) {
+      f32x4 o = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int i = 0; i < NW; ++i)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) o[r4] += slot(i, rt, 2 + db * 4 + r4) * mi[i];
+      if (orow[rt] >= 0) write_piece(p, orow[rt], b, s, g4, db, mm, ll, o);
+    }
   }
 }
 
@@ -537,7 +565,7 @@ int launch_mrows(const BlockParams& p, int passes, int B, hipStream_t st) {
 
 template <int RT, int NW>
 int launch_rt(const BlockParams& p, int passes, int B, hipStream_t st) {
-  const size_t lds_bytes = (size_t)(NW / 2) * RT * ST_REGS * 64 * sizeof(float);
+  const size_t lds_bytes = (size_t)NW * RT * ST_REGS * 64 * sizeof(float);
   if (const int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(&attn_block_kernel<RT, NW>), lds_bytes)) return rc;
   hipLaunchKernelGGL((attn_block_kernel<RT, NW>), dim3(p.S, p.Hkv * passes, B), dim3(64 * NW), lds_bytes, st, p);
   return hip_ok(hipGetLastError());
