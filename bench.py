@@ -120,11 +120,11 @@ def block_workload(torch, binding, inputs, B, q_len, Hq, Hkv, dh, n_prefix, seed
     R = _rotations(bytes_alg)
     sets = []
     for i in range(R):
-        sets.append(dict(
-            q=inputs.device_normal((B, q_len, Hq, dh), seed * 100 + 3 * i, 1.0),
-            k=inputs.device_normal((B, Hkv, T_max, dh), seed * 100 + 3 * i + 1, 1.0),
-            v=inputs.device_normal((B, Hkv, T_max, dh), seed * 100 + 3 * i + 2, 1.0),
-        ))
+        # K and V as a TandemState lays them out for the block attention (V out of phase with K, see the binding)
+        seeds = iter((seed * 100 + 3 * i + 1, seed * 100 + 3 * i + 2))
+        k, v = binding.kv_pair_out_of_phase(lambda *s: inputs.device_normal(s, next(seeds), 1.0), (B, Hkv, T_max, dh),
+                                            torch.bfloat16, "cuda")
+        sets.append(dict(q=inputs.device_normal((B, q_len, Hq, dh), seed * 100 + 3 * i, 1.0), k=k, v=v))
     n = torch.full((B,), n_prefix, dtype=torch.int32, device="cuda")
     out = torch.empty((B, q_len, Hq, dh), dtype=torch.bfloat16, device="cuda")
     d = binding.attn_desc(B, Hq, Hkv, dh, T_max, 0, 1.0 / math.sqrt(dh), binding.BF16)

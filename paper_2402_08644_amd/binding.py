@@ -609,6 +609,28 @@ class TandemModel:
             self.handle = None
 
 
+def kv_pair_out_of_phase(mk, shape, dtype, device):
+    """K and V caches [B, Hkv, T_max, dh] of one layer for the block-mode attention, placed so that V's rows start
+    1 MB out of phase with K's when a (sequence, head) region is a multiple of 2 MB.  A workgroup of the block
+    attention streams the K and the V region of one (sequence, head) side by side; with both on the same 2 MB phase
+    the launch measured 2.5 % slower (182.8 against 178.0 us at B=32, 8 KV heads, 8192 rows of 128) - the two streams
+    press on the same part of the memory system at every instant.  Other shapes get two ordinary tensors."""
+    import torch
+
+    B, H, T, dh = shape
+    es = torch.empty((), dtype=dtype).element_size()
+    region, nbytes = T * dh * es, B * H * T * dh * es
+    if region % (2 << 20) != 0 or not str(device).startswith("cuda"):
+        return mk(*shape), mk(*shape)
+    buf = torch.empty(2 * nbytes + (3 << 20), dtype=torch.uint8, device=device)
+    pad = (-buf.data_ptr()) % (2 << 20)
+    K = buf[pad: pad + nbytes].view(dtype).view(*shape)
+    V = buf[pad + nbytes + (1 << 20): pad + 2 * nbytes + (1 << 20)].view(dtype).view(*shape)
+    K.copy_(mk(*shape))
+    V.copy_(mk(*shape))
+    return K, V
+
+
 class TandemState:
     """Caller-owned caches and per-sequence state of tandem_decode_step, as torch tensors."""
 
@@ -618,8 +640,8 @@ class TandemState:
         self.B, self.T_max, self.gamma_max = B, T_max, gamma_max
         L, S = model.L, model.S
         mk = (lambda *s: torch.zeros(s, dtype=model.dtype, device=device)) if fill is None else fill
-        self.KL = [mk(B, L.Hkv, T_max, L.dh) for _ in range(L.n_layers)]
-        self.VL = [mk(B, L.Hkv, T_max, L.dh) for _ in range(L.n_layers)]
+        pairs = [kv_pair_out_of_phase(mk, (B, L.Hkv, T_max, L.dh), model.dtype, device) for _ in range(L.n_layers)]
+        self.KL, self.VL = [p[0] for p in pairs], [p[1] for p in pairs]
         self.Khat = [mk(B, S.Hkv, T_max, S.dh) for _ in range(S.n_layers)]
         self.Vhat = [mk(B, S.Hkv, T_max, S.dh) for _ in range(S.n_layers)]
         self.Kcur = [torch.zeros((B, S.Hkv, gamma_max, S.dh), dtype=model.dtype, device=device) for _ in range(S.n_layers)]

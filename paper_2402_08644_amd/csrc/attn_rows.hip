@@ -114,7 +114,16 @@ __global__ __launch_bounds__(64 * NW) void attn_rows_kernel(RowsParams p) {
     for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
   }
 
-  for (long long base = begin + (long long)w * (4 * U); base < end; base += 4 * NW * U) {
+  // Iteration i of a wavefront covers the 4 U rows from begin + (i NW + w) 4 U.  The workgroups of a launch all
+  // start at a multiple of the cache's per-head size and advance in step, so without further ado they would all
+  // press on the same memory channels at the same time: every workgroup starts its walk at a different iteration
+  // (a function of its position in the grid only) and wraps around.
+  const long long nit = (end - begin + 4 * NW * U - 1) / (4 * NW * U);
+  const long long rot = nit > 0 ? (long long)((blockIdx.z * 7 + blockIdx.y * 3 + blockIdx.x) * 5) % nit : 0;
+  for (long long it = 0; it < nit; ++it) {
+    long long ii = it + rot;
+    ii = ii >= nit ? ii - nit : ii;
+    const long long base = begin + (ii * NW + w) * (4 * U);
     Raw<RB> kr[U], vr[U];
     bool valid[U];
 #pragma unroll
