@@ -843,7 +843,9 @@ class DeepState:
         self.B, self.T_max = B, T_max
         L, S = model.L, model.S
         mk = lambda D: [torch.zeros((B, D.Hkv, T_max, D.dh), dtype=model.dtype, device=device) for _ in range(D.n_layers)]
-        self.KL, self.VL, self.KS, self.VS = mk(L), mk(L), mk(S), mk(S)
+        zeros = lambda *s: torch.zeros(s, dtype=model.dtype, device=device)
+        pairs = [kv_pair_out_of_phase(zeros, (B, L.Hkv, T_max, L.dh), model.dtype, device) for _ in range(L.n_layers)]
+        self.KL, self.VL, self.KS, self.VS = [p[0] for p in pairs], [p[1] for p in pairs], mk(S), mk(S)
         self._arrays = [(C.c_void_p * len(ts))(*[t.data_ptr() for t in ts]) for ts in (self.KL, self.VL, self.KS, self.VS)]
         self.desc = DeepStateDesc(B, T_max, *self._arrays)
 
