@@ -158,7 +158,7 @@ constexpr int ST_REGS = 34;  // per-lane state of one row tile: m, l, 32 accumul
 template <int RT, int NW>
 __global__ __launch_bounds__(64 * NW, (RT <= 2 && NW == 4 ? 2 : 1)) void attn_block_kernel(BlockParams p) {
   extern __shared__ float lds[];  // staging pieces [NW][16 KB] inside the loop, then the states [NW][RT][ST_REGS][64]
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int g4 = lane >> 4, c16 = lane & 15;
   const int s = blockIdx.x, b = blockIdx.z;
   const int kvh = blockIdx.y % p.Hkv, pass = blockIdx.y / p.Hkv;
@@ -233,36 +233,42 @@ __global__ __launch_bounds__(64 * NW, (RT <= 2 && NW == 4 ? 2 : 1)) void attn_bl
   // lines; loading the MFMA operand layout directly touches 64 of every 128 bytes per instruction, and with
   // the non-temporal hint that halves the rate), then operand reads in the layout of the two products.  Lane
   // (r4, slot) of load i brings piece slot ^ (row & 15) of tile row 4 i + r4: the operand reads of 16 rows at
-  // one piece index then fall into 16 different 16-byte bank groups.  The loads of the wavefront's next tile are
-  // issued as soon as the operands of this one are in registers and fly during the arithmetic.
-  unsigned char* const stg = reinterpret_cast<unsigned char*>(lds) + __builtin_amdgcn_readfirstlane(w) * 16384;
-  auto issue = [&](long long ti) __attribute__((always_inline)) {
+  // one piece index then fall into 16 different 16-byte bank groups.  The loads of the next tile's K (V) are
+  // issued as soon as this tile's K (V) operands are in registers and fly during the arithmetic.
+  unsigned char* const stg = reinterpret_cast<unsigned char*>(lds) + w * 16384;
+  // (addresses: a uniform tile base plus a 32-bit lane offset; rows past the end re-read the last valid row of the
+  // tile - there is one, a tile starts below `total` - and are masked below)
+  auto issue = [&](const bf16_t* base, unsigned char* dst, long long ti) __attribute__((always_inline)) {
     const long long key0 = ti << 5;
+    const unsigned char* tile = reinterpret_cast<const unsigned char*>(base + key0 * 128);
+    const long long left = total - 1 - key0;
+    const int last = left < 31 ? (int)left : 31;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int rl = 4 * i + g4;
-      long long row = key0 + rl;
-      row = row < total ? row : total - 1;  // rows past the end are re-reads of a valid row, masked below
-      const long long off = row * 128 + 8 * (c16 ^ (rl & 15));
-      __builtin_amdgcn_global_load_lds((global_void_ptr)(kbase + off), (lds_void_ptr)(stg + 1024 * i), 16, 0, 2);
-      __builtin_amdgcn_global_load_lds((global_void_ptr)(vbase + off), (lds_void_ptr)(stg + 8192 + 1024 * i), 16, 0, 2);
+      const uint32_t off = (uint32_t)(rl < last ? rl : last) * 256u + 16u * (uint32_t)(c16 ^ (rl & 15));
+      __builtin_amdgcn_global_load_lds((global_void_ptr)(tile + off), (lds_void_ptr)(dst + 1024 * i), 16, 0, 2);
     }
   };
-  if (tile_begin + w < tile_end) issue(tile_begin + w);
+  // Loads complete in issue order and the order is K(t), V(t), K(t + NW), V(t + NW), ...: with eight loads per half
+  // tile, "at most eight outstanding" means that the older half has arrived.
+  if (tile_begin + w < tile_end) {
+    issue(kbase, stg, tile_begin + w);
+    issue(vbase, stg + 8192, tile_begin + w);
+  }
   for (long long ti = tile_begin + w; ti < tile_end; ti += NW) {
     const long long key0 = ti << 5;
+    const bool more = ti + NW < tile_end;
     bf16x8 kreg[2][4], vreg[2][4];
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const int at = (16 * sub + c16) * 256 + 16 * ((4 * c + g4) ^ c16);
-        kreg[sub][c] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(stg + at));
-        vreg[sub][c] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(stg + 8192 + at));
-      }
+      for (int c = 0; c < 4; ++c)
+        kreg[sub][c] = __builtin_bit_cast(
+            bf16x8, *reinterpret_cast<const uint4*>(stg + (16 * sub + c16) * 256 + 16 * ((4 * c + g4) ^ c16)));
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    if (ti + NW < tile_end) issue(ti + NW);
+    if (more) issue(kbase, stg, ti + NW);
 
     bf16x8 pb[RT];
 #pragma unroll
@@ -299,6 +305,18 @@ __global__ __launch_bounds__(64 * NW, (RT <= 2 && NW == 4 ? 2 : 1)) void attn_bl
       pb[rt] = pack8(sc[0], sc[1]);
     }
 
+    if (more)
+      asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    else
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+      for (int c = 0; c < 4; ++c)
+        vreg[sub][c] = __builtin_bit_cast(
+            bf16x8, *reinterpret_cast<const uint4*>(stg + 8192 + (16 * sub + c16) * 256 + 16 * ((4 * c + g4) ^ c16)));
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    if (more) issue(vbase, stg + 8192, ti + NW);
 #pragma unroll
     for (int db = 0; db < 8; ++db) {
       const f32x4 z = {0.f, 0.f, 0.f, 0.f};

@@ -142,7 +142,8 @@ __device__ __forceinline__ void store_tile_big(const f32x16& acc, char* yt, uint
 __device__ __forceinline__ bf16x8 ldg8(const bf16_t* p) {
   return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(p));
 }
-// weights of a product that reads every weight once
+// weights of a product that reads every weight once and whose weights do not fit the last-level cache (the large
+// model's); the small model's weights are read again by every draft run of a step and stay plain loads
 __device__ __forceinline__ bf16x8 ldg8_stream(const bf16_t* p) { return __builtin_bit_cast(bf16x8, ld_stream16(p)); }
 
 // ---------------------------------------------------------------- skinny bf16 MFMA kernel
@@ -199,7 +200,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(GemmParams p) {
   auto gload = [&](bf16x8* a, int i) __attribute__((always_inline)) {
     const long long k0 = k_of(i);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) a[j] = ldg8_stream(wrow + k0 + 8 * j);
+    for (int j = 0; j < 4; ++j) a[j] = ldg8(wrow + k0 + 8 * j);
 #pragma unroll
     for (int q = 0; q < XL; ++q) {
       int m = m0 + xrow0 + 8 * q;
