@@ -47,16 +47,20 @@ struct BlockParams {
 __device__ __forceinline__ bf16x8 ld_bf16x8(const bf16_t* p) {
   return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(p));
 }
-// probabilities -> bf16 in the hot loop: the integer-arithmetic rounding measured 5 % faster for the whole
-// kernel than the hardware conversion instruction here (same results)
-__device__ __forceinline__ bf16x8 pack8(const f32x4& a, const f32x4& b) {
+// fp32 values that are bf16 values already (the transposed copies of V that come out of the selection products):
+// the upper halves of two words, one byte-permute instruction per pair
+__device__ __forceinline__ bf16x8 pack8_exact(const f32x4& a, const f32x4& b) {
+  auto hi2 = [](float lo, float hi) {
+    return __builtin_amdgcn_perm(__builtin_bit_cast(uint32_t, hi), __builtin_bit_cast(uint32_t, lo), 0x07060302u);
+  };
   uint4 u;
-  u.x = pack_bf16x2_alu(a[0], a[1]);
-  u.y = pack_bf16x2_alu(a[2], a[3]);
-  u.z = pack_bf16x2_alu(b[0], b[1]);
-  u.w = pack_bf16x2_alu(b[2], b[3]);
+  u.x = hi2(a[0], a[1]);
+  u.y = hi2(a[2], a[3]);
+  u.z = hi2(b[0], b[1]);
+  u.w = hi2(b[2], b[3]);
   return __builtin_bit_cast(bf16x8, u);
 }
+// rounding to bf16 with the conversion instruction (round to nearest even, NaN stays NaN)
 __device__ __forceinline__ bf16x8 pack8_hw(const f32x4& a, const f32x4& b) {
   uint4 u;
   u.x = pack_bf16x2(a[0], a[1]);
@@ -241,6 +245,7 @@ __global__ __launch_bounds__(64 * NW, (RT <= 2 && NW == 4 ? 2 : 1)) void attn_bl
   auto issue = [&](const bf16_t* base, unsigned char* dst, long long ti) __attribute__((always_inline)) {
     const long long key0 = ti << 5;
     const unsigned char* tile = reinterpret_cast<const unsigned char*>(base + key0 * 128);
+    asm volatile("" : "+s"(tile));  // one scalar base: the loads take it with a 32-bit lane offset
     const long long left = total - 1 - key0;
     const int last = left < 31 ? (int)left : 31;
 #pragma unroll
@@ -302,7 +307,7 @@ __global__ __launch_bounds__(64 * NW, (RT <= 2 && NW == 4 ? 2 : 1)) void attn_bl
       l[rt] = l[rt] * corr + ps;
 #pragma unroll
       for (int db = 0; db < 8; ++db) acc[rt][db] *= corr;
-      pb[rt] = pack8(sc[0], sc[1]);
+      pb[rt] = pack8_hw(sc[0], sc[1]);
     }
 
     if (more)
@@ -322,7 +327,7 @@ __global__ __launch_bounds__(64 * NW, (RT <= 2 && NW == 4 ? 2 : 1)) void attn_bl
       const f32x4 z = {0.f, 0.f, 0.f, 0.f};
       const f32x4 t0 = mfma16(vreg[0][db >> 1], sel[db & 1], z);
       const f32x4 t1 = mfma16(vreg[1][db >> 1], sel[db & 1], z);
-      const bf16x8 vt = pack8(t0, t1);
+      const bf16x8 vt = pack8_exact(t0, t1);
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) acc[rt][db] = mfma16(vt, pb[rt], acc[rt][db]);
     }
