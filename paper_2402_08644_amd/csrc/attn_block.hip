@@ -69,6 +69,17 @@ __device__ __forceinline__ bf16x8 pack8_hw(const f32x4& a, const f32x4& b) {
   u.w = pack_bf16x2(b[2], b[3]);
   return __builtin_bit_cast(bf16x8, u);
 }
+// maximum over the four lanes l, l ^ 16, l ^ 32, l ^ 48 with the row-swap instructions (no LDS traffic: the LDS
+// pipeline is busy with the incoming tiles, and a wait on it would also wait for them)
+__device__ __forceinline__ float max_over_rows(float x) {
+  typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+  const uint32_t u = __builtin_bit_cast(uint32_t, x);
+  const u32x2 a = __builtin_amdgcn_permlane16_swap(u, u, false, false);  // rows (0,1) and (2,3) exchanged
+  x = fmaxf(__builtin_bit_cast(float, a[0]), __builtin_bit_cast(float, a[1]));
+  const uint32_t v = __builtin_bit_cast(uint32_t, x);
+  const u32x2 b = __builtin_amdgcn_permlane32_swap(v, v, false, false);  // halves exchanged
+  return fmaxf(__builtin_bit_cast(float, b[0]), __builtin_bit_cast(float, b[1]));
+}
 __device__ __forceinline__ f32x4 mfma16(const bf16x8& a, const bf16x8& b, const f32x4& c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
@@ -273,7 +284,20 @@ __global__ __launch_bounds__(64 * NW, (RT <= 2 && NW == 4 ? 2 : 1)) void attn_bl
         kreg[sub][c] = __builtin_bit_cast(
             bf16x8, *reinterpret_cast<const uint4*>(stg + (16 * sub + c16) * 256 + 16 * ((4 * c + g4) ^ c16)));
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    f32x4 qk[RT][2];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub) {
+        f32x4 a = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) a = mfma16(kreg[sub][c], qreg[rt][c], a);
+        qk[rt][sub] = a;
+      }
+    // the K operands are consumed: the next tile's K may overwrite the staging piece
+    __builtin_amdgcn_sched_barrier(0);
     if (more) issue(kbase, stg, ti + NW);
+    __builtin_amdgcn_sched_barrier(0);
 
     bf16x8 pb[RT];
 #pragma unroll
@@ -281,9 +305,7 @@ __global__ __launch_bounds__(64 * NW, (RT <= 2 && NW == 4 ? 2 : 1)) void attn_bl
       f32x4 sc[2];
 #pragma unroll
       for (int sub = 0; sub < 2; ++sub) {
-        f32x4 a = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int c = 0; c < 4; ++c) a = mfma16(kreg[sub][c], qreg[rt][c], a);
+        f32x4 a = qk[rt][sub];
         const long long kidx = key0 + 16 * sub + 4 * g4;
 #pragma unroll
         for (int r4 = 0; r4 < 4; ++r4) a[r4] = (kidx + r4 <= lim[rt]) ? a[r4] * p.scale_log2e : -INFINITY;
@@ -291,8 +313,7 @@ __global__ __launch_bounds__(64 * NW, (RT <= 2 && NW == 4 ? 2 : 1)) void attn_bl
       }
       float mx = fmaxf(fmaxf(fmaxf(sc[0][0], sc[0][1]), fmaxf(sc[0][2], sc[0][3])),
                        fmaxf(fmaxf(sc[1][0], sc[1][1]), fmaxf(sc[1][2], sc[1][3])));
-      mx = fmaxf(mx, __shfl_xor(mx, 16));
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      mx = max_over_rows(mx);
       const float mn = fmaxf(m[rt], mx);
       const float corr = fast_exp2(m[rt] - mn);
       m[rt] = mn;
@@ -321,16 +342,22 @@ __global__ __launch_bounds__(64 * NW, (RT <= 2 && NW == 4 ? 2 : 1)) void attn_bl
         vreg[sub][c] = __builtin_bit_cast(
             bf16x8, *reinterpret_cast<const uint4*>(stg + 8192 + (16 * sub + c16) * 256 + 16 * ((4 * c + g4) ^ c16)));
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    if (more) issue(vbase, stg + 8192, ti + NW);
+    bf16x8 vt[8];
 #pragma unroll
     for (int db = 0; db < 8; ++db) {
       const f32x4 z = {0.f, 0.f, 0.f, 0.f};
       const f32x4 t0 = mfma16(vreg[0][db >> 1], sel[db & 1], z);
       const f32x4 t1 = mfma16(vreg[1][db >> 1], sel[db & 1], z);
-      const bf16x8 vt = pack8_exact(t0, t1);
-#pragma unroll
-      for (int rt = 0; rt < RT; ++rt) acc[rt][db] = mfma16(vt, pb[rt], acc[rt][db]);
+      vt[db] = pack8_exact(t0, t1);
     }
+    // likewise for V, once its transposed copies are in registers
+    __builtin_amdgcn_sched_barrier(0);
+    if (more) issue(vbase, stg + 8192, ti + NW);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int db = 0; db < 8; ++db)
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) acc[rt][db] = mfma16(vt[db], pb[rt], acc[rt][db]);
   }
 
   // row sums: lanes l, l^16, l^32, l^48 hold partial sums of the same query column
