@@ -142,9 +142,6 @@ __device__ __forceinline__ void store_tile_big(const f32x16& acc, char* yt, uint
 __device__ __forceinline__ bf16x8 ldg8(const bf16_t* p) {
   return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(p));
 }
-// weights of a product that reads every weight once and whose weights do not fit the last-level cache (the large
-// model's); the small model's weights are read again by every draft run of a step and stay plain loads
-__device__ __forceinline__ bf16x8 ldg8_stream(const bf16_t* p) { return __builtin_bit_cast(bf16x8, ld_stream16(p)); }
 
 // ---------------------------------------------------------------- skinny bf16 MFMA kernel
 // grid (N/32, splitK, ceil(M/(32*MT))); block NW*64.  Requires N % 32 == 0, K % 64 == 0.
@@ -630,7 +627,7 @@ __global__ __launch_bounds__(512) void gemm_stream_kernel(GemmParams p) {
   {                                                                                            \
     SG_STAGE(i, st_)                                                                           \
     __builtin_amdgcn_sched_barrier(0);                                                         \
-    _Pragma("unroll") for (int j = 0; j < 4; ++j) a[j] = ldg8_stream(wp + st_ * (32 * SK) + 512 * j); \
+    _Pragma("unroll") for (int j = 0; j < 4; ++j) a[j] = ldg8(wp + st_ * (32 * SK) + 512 * j); \
     __builtin_amdgcn_sched_barrier(0);                                                         \
   }
 #define SG_READ(b, buf, half)                                                                  \
