@@ -70,15 +70,18 @@ __device__ __forceinline__ bf16x8 pack8_hw(const f32x4& a, const f32x4& b) {
   return __builtin_bit_cast(bf16x8, u);
 }
 // maximum over the four lanes l, l ^ 16, l ^ 32, l ^ 48 with the row-swap instructions (no LDS traffic: the LDS
-// pipeline is busy with the incoming tiles, and a wait on it would also wait for them)
+// pipeline is busy with the incoming tiles).  v_permlane16_swap exchanges rows 1 and 3 of its first operand with
+// rows 0 and 2 of its second, v_permlane32_swap the upper half of the first with the lower half of the second:
+// started from two copies of x, the two operands hold x of both partners in every lane afterwards.  Written as
+// asm because the compiler's builtin hands back the first result twice; the s_nop covers the wait states the
+// instruction needs after a vector write of its operands.  All lanes must be active.
 __device__ __forceinline__ float max_over_rows(float x) {
-  typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-  const uint32_t u = __builtin_bit_cast(uint32_t, x);
-  const u32x2 a = __builtin_amdgcn_permlane16_swap(u, u, false, false);  // rows (0,1) and (2,3) exchanged
-  x = fmaxf(__builtin_bit_cast(float, a[0]), __builtin_bit_cast(float, a[1]));
-  const uint32_t v = __builtin_bit_cast(uint32_t, x);
-  const u32x2 b = __builtin_amdgcn_permlane32_swap(v, v, false, false);  // halves exchanged
-  return fmaxf(__builtin_bit_cast(float, b[0]), __builtin_bit_cast(float, b[1]));
+  float y = x;
+  asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1" : "+v"(x), "+v"(y));
+  x = fmaxf(x, y);
+  y = x;
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(x), "+v"(y));
+  return fmaxf(x, y);
 }
 __device__ __forceinline__ f32x4 mfma16(const bf16x8& a, const bf16x8& b, const f32x4& c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
@@ -591,8 +594,7 @@ __global__ __launch_bounds__(64 * NW) void attn_mrows_kernel(BlockParams p) {
     }
     float mx = fmaxf(fmaxf(fmaxf(sc[0][0], sc[0][1]), fmaxf(sc[0][2], sc[0][3])),
                      fmaxf(fmaxf(sc[1][0], sc[1][1]), fmaxf(sc[1][2], sc[1][3])));
-    mx = fmaxf(mx, __shfl_xor(mx, 16));
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    mx = max_over_rows(mx);
     mx *= absl;
     // The running maximum m is only raised when some row's scores pass it by more than 2^8 (weights stay
     // below 256, exact in the fp32 sums; the result does not depend on which m is subtracted), so the

@@ -257,6 +257,51 @@ def test_block_attn_causal_mask_exact(tb):
             assert np.count_nonzero(out[..., :77]) == 0 and np.count_nonzero(out[..., 78:]) == 0
 
 
+def _with_dominant_keys(case, kname, positions, dtype, c=48.5):
+    """Query component 0 = c in every row and key component 0 = c at the given positions: those keys score
+    c * c * scale (about 300 in base-2 units at d_h = 128) above keys whose scores are of order one, so a
+    running maximum that misses one of them overflows the exponentials."""
+    q = case["q"].f64.astype(np.float32).copy()
+    k = case[kname].f64.astype(np.float32).copy()
+    q[..., 0] = c
+    k[..., 0] = 0.0
+    for pos in positions:
+        k[:, :, pos, 0] = c
+    case["q"] = inputs.HostTensor(q, dtype)
+    case[kname] = inputs.HostTensor(k, dtype)
+    return case
+
+
+@pytest.mark.parametrize(
+    "B,q_len,Hq,Hkv,T_max,n",
+    [
+        (2, 4, 4, 1, 700, 690),     # one row tile per KV head: the key-split kernel, several tiles per wavefront
+        (2, 4, 8, 1, 700, 690),     # two row tiles
+        (1, 16, 8, 2, 600, 580),    # 64 rows per KV head: the row-split kernel
+    ],
+)
+@pytest.mark.parametrize("offset", [0, 5, 10, 15, 20, 25, 30])
+def test_block_attn_dominant_key_in_every_lane_group(tb, B, q_len, Hq, Hkv, T_max, n, offset):
+    """The running maximum of a query column is shared by four lanes that hold different keys of a tile (keys
+    4g .. 4g+3 and 16+4g .. 16+4g+3 in lane group g).  One key per tile position class that dominates all others
+    by far: a lane group whose maximum does not reach the others gives infinities instead of weights."""
+    case = inputs.block_attn_case(61 + offset, B, q_len, Hq, Hkv, 128, T_max, n, dtype="bf16")
+    positions = [32 * t + offset for t in (0, 3, 7, 12)]   # four dominant keys, all visible
+    case = _with_dominant_keys(case, "k", positions, "bf16")
+    got = run_block(tb, case)
+    want = oracle_block(case)
+    assert_rows_close(got, want, what=f"block, dominant keys at tile offset {offset}")
+    assert np.abs(got).max() < 10.0
+
+
+@pytest.mark.parametrize("offset", [0, 5, 10, 15, 20, 25, 30])
+def test_draft_attn_dominant_key(tb, offset):
+    case = inputs.draft_attn_case(71 + offset, 2, 4, 2, 128, 900, 4, [870, 333], [3, 1], dtype="bf16")
+    case = _with_dominant_keys(case, "khat", [32 * t + offset for t in (0, 2, 9)], "bf16")
+    got = run_draft(tb, case)
+    assert_rows_close(got, oracle_draft(case), what=f"draft, dominant keys at offset {offset}")
+
+
 def test_block_attn_is_deterministic_and_readonly(tb):
     torch, binding = tb
     case = inputs.block_attn_case(8, 3, 4, 8, 2, 128, 1000, [996, 500, 3], dtype="bf16")
