@@ -461,7 +461,7 @@ int tandem_deep_step(const tandem_model *m, const tandem_ff_desc *ff_deep, const
                      void *y_small, void *sketch, void *ws, size_t ws_bytes, void *hip_stream);
 
 /* Measurement helper, no part of the method: reads src[0 : bytes) (device, 16-byte aligned; a multiple of 16 bytes is
- * read) once with plain coalesced 16-byte loads and writes TANDEM_READ_STREAM_BLOCKS 32-bit words of folded data to
+ * read) once with coalesced non-temporal 16-byte loads and writes TANDEM_READ_STREAM_BLOCKS 32-bit words of folded data to
  * sink (device).  The rate this call reaches is the read ceiling of the box for kernels that stream HBM once, the
  * yardstick bench.py reports next to the datasheet peak for the attention kernels (Sec. 3.1, footnote: attention is
  * the part of decoding whose memory traffic does not amortise over the batch). */
