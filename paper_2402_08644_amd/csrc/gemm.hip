@@ -715,9 +715,29 @@ __global__ __launch_bounds__(512) void gemm_stream_kernel(GemmParams p) {
     return;
   }
   const float bn = p.bias ? bf16_to_f32(((const bf16_t*)p.bias)[n]) : 0.f;
-  ACT_SWITCH(p.act, {
-    _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) store_tile_bf16<ACT>(acc[mt], m0 + mt * 32, n, h, bn, p);
-  })
+  if (p.residual) {
+    ACT_SWITCH(p.act, {
+      _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) store_tile_bf16<ACT>(acc[mt], m0 + mt * 32, n, h, bn, p);
+    })
+    return;
+  }
+  // as in the big-tile kernel: a wave-uniform base, one byte offset per lane, no address arithmetic per value
+  const bool odd = c32 & 1;
+  char* yt = reinterpret_cast<char*>((bf16_t*)p.Y + (long long)m0 * p.ldy + n0);
+  const uint32_t rowb = (uint32_t)p.ldy * 2u;
+  const uint32_t loff = (uint32_t)(4 * h + (odd ? 1 : 0)) * rowb + (uint32_t)(c32 & ~1) * 2u;
+  const int mleft = p.M - m0;
+  if (mleft >= 32 * MT) {
+    ACT_SWITCH(p.act, {
+      _Pragma("unroll") for (int mt = 0; mt < MT; ++mt)
+          (store_tile_big<ACT, true>)(acc[mt], yt, loff, rowb, mt * 32, 0, odd, bn, mleft, 4 * h);
+    })
+  } else {
+    ACT_SWITCH(p.act, {
+      _Pragma("unroll") for (int mt = 0; mt < MT; ++mt)
+          (store_tile_big<ACT, false>)(acc[mt], yt, loff, rowb, mt * 32, 0, odd, bn, mleft, 4 * h);
+    })
+  }
 }
 
 // Re-lays W[N, K] (bf16, row-major) out in the 4 KB tiles the stream kernel reads: one thread per 16 bytes
