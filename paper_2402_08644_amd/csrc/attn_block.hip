@@ -5,8 +5,9 @@
 // and feeds R rows: R flop per KV byte - past the vector ALUs, a few percent of MFMA peak.
 //
 // Each wavefront works alone on 32-key tiles (no workgroup barrier in the main loop):
-//   * K and V rows are loaded straight from global memory in the MFMA A-operand layout
-//     (lane = key row l%16, 16 bytes at dh offset 32c + 8*(l/16));
+//   * a tile's K and V rows come through a 16 KB piece of LDS that belongs to the wavefront: direct
+//     global-to-LDS loads of whole rows (non-temporal), then 16-byte reads in the MFMA A-operand layout
+//     (lane = key row l%16, the 16 bytes at dh offset 32c + 8*(l/16));
 //   * S^T[key, q] = K Q^T with v_mfma_f32_16x16x32_bf16, Q^T held in registers;
 //   * online softmax per query column (one column per lane, 2 cross-lane max steps per tile);
 //   * the C-layout of two 16-key score tiles already IS the B-operand layout of P^T for a
@@ -14,7 +15,7 @@
 //     16+4g+j-4 (j>=4), so P never moves between lanes;
 //   * V is brought into the matching A-operand layout (keys along the contraction) by
 //     multiplying each 16x32 piece with a 0/1 selection matrix on the matrix cores - an
-//     exact transpose that needs no LDS and no barrier;
+//     exact transpose that needs no barrier;
 //   * O^T[d, q] += V^T P^T.
 // Wavefront states are merged through LDS at the end, context splits through the workspace.
 #include "common.h"
